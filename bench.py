@@ -1,0 +1,226 @@
+#!/usr/bin/env python3
+"""Benchmark of the BCR sparse product on one MI355X.
+
+A step is one pass of the hot path -- one grim_bcr_spmm launch -- over one batch of
+synthetic input of the headline workload: the VGG-style 3x3 convolution as an im2col
+BCR SpMM (M=256, K=2304, N=3136, fp16 in / fp32 accumulate, 16x32 blocks keeping
+8/16 rows and 8/32 columns).  Inputs are resident in HBM before the timed region; the
+steps rotate over enough (X, Y) buffer sets that no step finds its operands in the
+256 MB last-level cache.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--extra]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
+METRIC = "BCR SpMM/SpMV useful TFLOP/s, HBM GB/s, % of roofline vs oracle"
+
+
+def spmm_algorithmic_bytes(view, N: int, esz: int) -> int:
+    """Bytes one SpMM must move: X once, Y once, the compact weights and their indices."""
+    idx = 2 * (view["n_row_idx"] + view["n_col_idx"]) + 4 * 2 * (view["nb"] + 1) + 8 * (view["nb"] + 1) + 4 * view["nbr"]
+    return esz * view["K"] * N + 4 * view["M"] * N + esz * view["nnz"] + idx
+
+
+def spmv_algorithmic_bytes(view, batch: int, esz: int) -> int:
+    """Bytes one SpMV must move: compact weights, 8 bytes of bit masks per block, x and y."""
+    return esz * view["nnz"] + 8 * view["nb"] + 4 * view["nbr"] + esz * view["K"] * batch + 4 * view["M"] * batch
+
+
+def view_dict(A) -> dict:
+    v = A.view()
+    a = A.arrays()
+    return dict(M=v.M, K=v.K, nnz=v.nnz, nb=v.nb, nbr=v.nbr, n_row_idx=len(a["row_idx"]), n_col_idx=len(a["col_idx"]),
+                dev_bytes_mma=v.dev_bytes_mma)
+
+
+def time_launches(torch, fn, steps: int, warmup: int):
+    """Average seconds per launch by HIP events on the stream the kernels run on."""
+    for i in range(warmup):
+        fn(i)
+    torch.cuda.synchronize()
+    start = torch.cuda.Event(enable_timing=True)
+    stop = torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    start.record()
+    for i in range(steps):
+        fn(warmup + i)
+    stop.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    return start.elapsed_time(stop) * 1e-3 / steps, wall / steps
+
+
+def cpu_baseline(wl, reps: int = 3) -> dict:
+    """The oracle as it stands, timed on the host cores on the whole headline workload."""
+    import bcr_inputs as gen
+    from oracle import bcr_oracle as orc
+    W64 = gen.storage_to_f64(wl.W, wl.dtype)
+    X64 = gen.storage_to_f64(wl.X, wl.dtype)
+    Wm = orc.masked_dense(W64, wl.mask.BR, wl.mask.BC, wl.mask.row_ptr, wl.mask.row_idx, wl.mask.col_ptr, wl.mask.col_idx)
+    best = float("inf")
+    for _ in range(reps):
+        t0 = time.perf_counter()
+        orc.matmul(Wm, X64, want_scale=False, skip_zero=True)
+        best = min(best, time.perf_counter() - t0)
+    return {"value": wl.useful_flops() / best / 1e12, "unit": "TFLOP/s", "cores": orc.threads(), "kind": "oracle",
+            "sample": f"whole {wl.name} product (M={wl.M}, K={wl.K}, N={wl.N}), fp64 zero-skipping triple loop, "
+                      f"best of {reps}, {best * 1e3:.1f} ms"}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=400)
+    ap.add_argument("--warmup", type=int, default=40)
+    ap.add_argument("--sets", type=int, default=32, help="(X, Y) buffer sets the steps rotate over")
+    ap.add_argument("--tile-n", type=int, default=0)
+    ap.add_argument("--strips-per-wg", type=int, default=0)
+    ap.add_argument("--extra", action="store_true", help="also time the SpMV and large non-uniform workloads")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (the product shards over N with no exchange; "
+              "see DESIGN.md); --gpus must be 1", file=sys.stderr)
+        return 2
+
+    import torch
+    import bcr_inputs as gen
+    import paper_2108_11033_amd as g
+    from paper_2108_11033_amd import binding
+
+    g.load_library()                      # fails loudly if the HIP library is not built
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    stream = torch.cuda.current_stream()
+
+    def pack(wl):
+        m = wl.mask
+        return g.pack(wl.W, wl.dtype, m.BR, m.BC, m.row_ptr, m.row_idx, m.col_ptr, m.col_idx)
+
+    def dev_tensor(a, dtype):
+        if dtype == gen.BF16:
+            return torch.from_numpy(a.view(np.int16).copy()).to(dev).view(torch.bfloat16)
+        return torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+
+    # ---------------- headline: c2 ----------------
+    wl = gen.c2_vgg_conv()
+    A = pack(wl)
+    vd = view_dict(A)
+    X0 = dev_tensor(wl.X, wl.dtype)
+    sets = max(1, args.sets)
+    Xs = [X0] + [X0.clone() for _ in range(sets - 1)]
+    Ys = [torch.empty((wl.M, wl.N), dtype=torch.float32, device=dev) for _ in range(sets)]
+    tune = dict(tile_n=args.tile_n, strips_per_wg=args.strips_per_wg)
+
+    def step(i):
+        j = i % sets
+        g.spmm(A, Xs[j], wl.N, wl.N, Ys[j], wl.N, stream, **tune)
+
+    t_cold, wall_cold = time_launches(torch, step, args.steps, args.warmup)
+    t_warm, _ = time_launches(torch, lambda i: g.spmm(A, Xs[0], wl.N, wl.N, Ys[0], wl.N, stream, **tune),
+                              args.steps, args.warmup)
+    flops = wl.useful_flops()
+    abytes = spmm_algorithmic_bytes(vd, wl.N, 2)
+    value = flops / t_cold / 1e12
+    achieved = abytes / t_cold / 1e9
+    out = {
+        "metric": METRIC, "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": t_cold * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16", "data": "synthetic",
+        "config": {"workload": "c2: VGG-style 3x3 conv as im2col BCR SpMM, M=256 K=2304 N=3136, fp16 in / fp32 acc, "
+                               "16x32 blocks keep 8/16 rows x 8/32 cols (density 1/8)",
+                   "buffer_sets": sets, "useful_gflop_per_step": flops / 1e9, "algorithmic_mb_per_step": abytes / 1e6},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "kernel": "bcr_spmm_mma", "launch_us": t_cold * 1e6},
+        "warm_cache": {"ms_per_step": t_warm * 1e3, "useful_tflops": flops / t_warm / 1e12,
+                       "algorithmic_gbs": abytes / t_warm / 1e9,
+                       "note": "same X/Y every step: operands stay in the 256 MB last-level cache"},
+        "wall_ms_per_step": wall_cold * 1e3,
+    }
+
+    if args.extra:
+        extra = {}
+        # ---- c3: LSTM gate SpMV, batch 1 and 8: (A) same W, (B) rotating copies, (C) one batched launch
+        for batch in (1, 8):
+            w3 = gen.c3_lstm_gates(batch)
+            copies = 256
+            mats = [pack(w3) for _ in range(copies)]
+            v3 = view_dict(mats[0])
+            xs = dev_tensor(np.stack([w3.X] * copies), w3.dtype)
+            ys = torch.empty((copies, w3.M, batch), dtype=torch.float32, device=dev)
+            b3 = spmv_algorithmic_bytes(v3, batch, 2)
+            tA, _ = time_launches(torch, lambda i: g.spmv(mats[0], xs[0], batch, batch, ys[0], batch, stream), 1000, 50)
+            tB, _ = time_launches(torch, lambda i: g.spmv(mats[i % copies], xs[i % copies], batch, batch, ys[i % copies], batch, stream), 1000, 50)
+            G = binding.group(mats)
+            tC, _ = time_launches(torch, lambda i: g.spmv_batched(G, xs, w3.K * batch, batch, batch, ys, w3.M * batch, batch, stream), 20, 3)
+            tC /= copies
+            extra[f"c3_b{batch}"] = {
+                "algorithmic_mb": b3 / 1e6, "useful_mflop": w3.useful_flops() / 1e6,
+                "A_same_W_us": tA * 1e6, "A_gbs": b3 / tA / 1e9,
+                "B_rotating_us": tB * 1e6, "B_gbs": b3 / tB / 1e9, "B_frac_hbm": b3 / tB / 1e9 / HBM_PEAK_GBS,
+                "C_batched_us_per_product": tC * 1e6, "C_gbs": b3 / tC / 1e9, "C_frac_hbm": b3 / tC / 1e9 / HBM_PEAK_GBS,
+                "C_products_per_launch": copies,
+            }
+            del G, mats
+        # ---- c5: large non-uniform bf16 SpMM
+        w5 = gen.c5_nonuniform()
+        A5 = pack(w5)
+        v5 = view_dict(A5)
+        X5 = dev_tensor(w5.X, w5.dtype)
+        X5b = X5.clone()
+        Y5 = [torch.empty((w5.M, w5.N), dtype=torch.float32, device=dev) for _ in range(2)]
+        XX = [X5, X5b]
+        t5, _ = time_launches(torch, lambda i: g.spmm(A5, XX[i % 2], w5.N, w5.N, Y5[i % 2], w5.N, stream), 50, 5)
+        b5 = spmm_algorithmic_bytes(v5, w5.N, 2)
+        extra["c5"] = {"us": t5 * 1e6, "useful_tflops": w5.useful_flops() / t5 / 1e12, "algorithmic_mb": b5 / 1e6,
+                       "gbs": b5 / t5 / 1e9, "frac_hbm": b5 / t5 / 1e9 / HBM_PEAK_GBS, "nnz": v5["nnz"],
+                       "mma_layout_mb": v5["dev_bytes_mma"] / 1e6}
+        del X5, X5b, Y5, XX, A5
+        # ---- c4: the 13 VGG-16 conv layers
+        layers = []
+        tot_t = tot_b = tot_f = 0.0
+        for li in range(13):
+            w4 = gen.c4_vgg16_layer(li)
+            A4 = pack(w4)
+            v4 = view_dict(A4)
+            nset = 4
+            X4 = [dev_tensor(w4.X, w4.dtype)]
+            X4 += [X4[0].clone() for _ in range(nset - 1)]
+            Y4 = [torch.empty((w4.M, w4.N), dtype=torch.float32, device=dev) for _ in range(nset)]
+            t4, _ = time_launches(torch, lambda i: g.spmm(A4, X4[i % nset], w4.N, w4.N, Y4[i % nset], w4.N, stream), 100, 10)
+            b4 = spmm_algorithmic_bytes(v4, w4.N, 2)
+            layers.append({"layer": li + 1, "M": w4.M, "K": w4.K, "N": w4.N, "us": t4 * 1e6,
+                           "useful_tflops": w4.useful_flops() / t4 / 1e12, "gbs": b4 / t4 / 1e9})
+            tot_t += t4; tot_b += b4; tot_f += w4.useful_flops()
+            del X4, Y4, A4
+        extra["c4"] = {"layers": layers, "total_us": tot_t * 1e6, "useful_tflops": tot_f / tot_t / 1e12,
+                       "gbs": tot_b / tot_t / 1e9, "frac_hbm": tot_b / tot_t / 1e9 / HBM_PEAK_GBS}
+        out["extra"] = extra
+
+    if not args.no_cpu:
+        out["cpu_baseline"] = cpu_baseline(wl)
+    else:
+        out["cpu_baseline"] = None
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -1,0 +1,182 @@
+/*
+ * grim_bcr.h -- C ABI of the BCR (Block-based Column-Row) sparse product library
+ * for AMD MI355X (gfx950).
+ *
+ * The library computes  Y = W_bcr * X : the product of a BCR-pruned weight matrix
+ * with dense activations.  This is the inference hot path of GRIM (arXiv 2108.11033):
+ *   - Section 3.1 (unified view): CONV layers become weight matrix x im2col input
+ *     matrix (SpMM); FC / RNN gate layers become matrix x vector (SpMV).
+ *   - Section 3.2 (BCR sparsity): W (M x K) is cut into equal BR x BC blocks
+ *     (BR rows = outputs, BC columns = inputs); each block independently keeps a
+ *     set of whole rows and a set of whole columns; the survivors of a block form
+ *     a full (kept rows) x (kept columns) matrix.  Every other weight is zero.
+ *   - Section 4.2 (matrix reorder) and 4.3 (compact storage): rows with the same
+ *     amount of work are stored together and zero weights are not stored; the
+ *     column indices shared by the rows of a block are stored once.
+ *
+ * All functions return a grim_status and never throw or abort.  Unless stated
+ * otherwise, pointers named *_host are host memory and *_dev are device memory
+ * on the GPU that was current when the matrix was packed.  The library never
+ * takes ownership of caller memory.
+ */
+#ifndef GRIM_BCR_H
+#define GRIM_BCR_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct grim_bcr_matrix grim_bcr_matrix; /* opaque; owns its host and device copies */
+typedef struct grim_bcr_group grim_bcr_group;   /* opaque; a set of matrices for one batched launch */
+
+typedef enum {
+    GRIM_OK = 0,
+    GRIM_ERR_NULL = 1,        /* a required pointer is NULL */
+    GRIM_ERR_SHAPE = 2,       /* BR does not divide M, BC does not divide K, N < 1, leading
+                                 dimension too small, batch outside 1..8, size over a limit */
+    GRIM_ERR_INDEX = 3,       /* a ptr array is not monotone / does not start at 0, an index is
+                                 out of range, or a block's indices are not strictly ascending */
+    GRIM_ERR_DTYPE = 4,       /* unknown grim_dtype */
+    GRIM_ERR_ALLOC = 5,       /* host or device allocation failed */
+    GRIM_ERR_DEVICE = 6,      /* a HIP call failed, no GPU, or the matrix was packed host-only */
+    GRIM_ERR_UNSUPPORTED = 7  /* valid request that no kernel covers (e.g. BR > 64) */
+} grim_status;
+
+typedef enum { GRIM_F32 = 0, GRIM_F16 = 1, GRIM_BF16 = 2 } grim_dtype;
+
+/* Options of grim_bcr_pack.  Zero-initialise, then set what differs. */
+typedef struct grim_bcr_options {
+    int32_t no_reorder;  /* 0 (default): store row strips by decreasing work (Section 4.2);
+                            1: keep the natural strip order */
+    int32_t host_only;   /* 1: build only the host arrays (pack / unpack / arrays work without
+                            a GPU; spmm / spmv then return GRIM_ERR_DEVICE) */
+    int32_t chunk_rows;  /* rows of X staged per step by the matrix-core SpMM kernel;
+                            0 = choose.  Rounded to a whole number of column blocks. */
+    int32_t reserved[5];
+} grim_bcr_options;
+
+/* Borrowed, read-only view of the canonical compact arrays (host memory owned by
+ * the matrix, valid until grim_bcr_free).  "Stored order" of blocks: strips in
+ * strip_order, inside a strip column blocks ascending; t = position in that order.
+ *   strip_order[nbr]  strips by decreasing work w_s = sum_c kr*kc, ties by index
+ *   row_ptr[nb+1], row_idx[]  kept rows of stored block t, local, ascending
+ *   col_ptr[nb+1], col_idx[]  kept columns likewise
+ *   blk_ptr[nb+1]     offset of stored block t in weights (prefix sums of kr*kc)
+ *   weights[nnz]      each block row-major [kept row][kept col]; bit copies of W */
+typedef struct grim_bcr_view {
+    int64_t M, K;
+    int32_t BR, BC;
+    int32_t dtype;
+    int32_t reordered;
+    int64_t nbr, nbc, nb, nnz;
+    const int32_t *strip_order;
+    const int32_t *row_ptr;
+    const uint16_t *row_idx;
+    const int32_t *col_ptr;
+    const uint16_t *col_idx;
+    const int64_t *blk_ptr;
+    const void *weights;
+    /* bytes of the device-side layouts derived from the arrays above (0 if absent) */
+    int64_t dev_bytes_canonical; /* the arrays above, as uploaded */
+    int64_t dev_bytes_mma;       /* row-expanded matrix-core layout (fragments + gather lists) */
+    int64_t dev_bytes_gemv;      /* per-block row/column bit masks + offsets for the SpMV kernel */
+} grim_bcr_view;
+
+/*
+ * grim_bcr_pack -- compact a dense matrix under a BCR mask (Sections 3.2, 4.2, 4.3).
+ *   W_host   dense M x K matrix, row-major with leading dimension ldw (elements),
+ *            element type dt.  Values at pruned positions are ignored.
+ *   BR, BC   block size; BR must divide M and BC must divide K (the paper's block
+ *            sizes divide the layer's height and width, Section 5.1).  1 <= BR,BC <= 65535.
+ *   row_ptr  nb+1 prefix sums (nb = (M/BR)*(K/BC), blocks numbered b = s*(K/BC) + c);
+ *   row_idx  kept rows of block b = row_idx[row_ptr[b] .. row_ptr[b+1]), local to the
+ *            block (0..BR-1), strictly ascending.  col_ptr / col_idx likewise (0..BC-1).
+ *            A block may keep no rows or no columns (it then stores nothing).
+ *   opt      NULL = defaults.
+ *   out      receives the new matrix; release with grim_bcr_free.
+ * Packing is driven by the index sets only, never by inspecting values: kept weights
+ * are bit copies (zeros, negative zeros, NaNs included).  The inputs are copied; the
+ * caller may free them on return.  Unless opt->host_only, the device layouts are
+ * allocated and uploaded to the current GPU before returning (synchronous).
+ * Errors: NULL, SHAPE, INDEX, DTYPE, ALLOC, DEVICE.  On error *out is NULL.
+ */
+grim_status grim_bcr_pack(const void *W_host, grim_dtype dt, int64_t M, int64_t K, int64_t ldw,
+                          int32_t BR, int32_t BC,
+                          const int32_t *row_ptr, const uint16_t *row_idx,
+                          const int32_t *col_ptr, const uint16_t *col_idx,
+                          const grim_bcr_options *opt, grim_bcr_matrix **out);
+
+/* grim_bcr_unpack -- inverse of pack: writes the masked dense M x K matrix (leading
+ * dimension ldw >= K, element type of the matrix) to host memory; pruned positions
+ * become +0.  Bit-exact with respect to the packed input. */
+grim_status grim_bcr_unpack(const grim_bcr_matrix *A, void *W_host_out, int64_t ldw);
+
+/* grim_bcr_arrays -- fill *v with borrowed pointers to the canonical arrays. */
+grim_status grim_bcr_arrays(const grim_bcr_matrix *A, grim_bcr_view *v);
+
+/*
+ * grim_bcr_spmm -- Y = W_bcr * X on the GPU (Section 3.1: CONV as GEMM on the im2col
+ * matrix; Section 4.2-4.4: compact weights, input rows of a block loaded once and
+ * reused by all of its kept rows).
+ *   X_dev  K x N, row-major, leading dimension ldx >= N (elements), element type of A.
+ *   Y_dev  M x N fp32, row-major, leading dimension ldy >= N, in the ORIGINAL row order.
+ *          Overwritten (no accumulation into Y; rows kept by no block are written as 0).
+ *   hip_stream  a hipStream_t (NULL = the default stream).  The call only enqueues work:
+ *          it never synchronises and never allocates.
+ * Accumulation is in fp32 in a fixed order (no atomics): results are bit-reproducible
+ * from run to run.  N <= 8 is forwarded to the SpMV kernel when that path supports A.
+ * Errors: NULL, SHAPE (N < 1, ld too small), DEVICE, UNSUPPORTED.  Y is untouched on error.
+ */
+grim_status grim_bcr_spmm(const grim_bcr_matrix *A, const void *X_dev, int64_t N, int64_t ldx,
+                          float *Y_dev, int64_t ldy, void *hip_stream);
+
+/* grim_bcr_spmm_tuned -- grim_bcr_spmm with explicit launch parameters (the paper tunes
+ * tile sizes per kernel, Section 4.5; here a handful of choices replaces the search):
+ *   tile_n         columns of X per workgroup (32, 64 or 128; 0 = choose)
+ *   strips_per_wg  row strips per workgroup (multiple of 4 or 0 = choose)
+ *   kernel         0 = choose, 1 = force the portable FMA kernel, 2 = force the matrix-core kernel
+ * Invalid combinations return GRIM_ERR_UNSUPPORTED. */
+grim_status grim_bcr_spmm_tuned(const grim_bcr_matrix *A, const void *X_dev, int64_t N, int64_t ldx,
+                                float *Y_dev, int64_t ldy, int32_t tile_n, int32_t strips_per_wg,
+                                int32_t kernel, void *hip_stream);
+
+/*
+ * grim_bcr_spmv -- y = W_bcr * x for 1..8 right-hand sides (Section 3.1: FC and RNN
+ * gate matrices are matrix-vector products).  Same conventions as grim_bcr_spmm with
+ * N = batch: x_dev is K x batch (ldx >= batch), y_dev is M x batch fp32 (ldy >= batch).
+ * Reads the compact weights exactly once; the bytes moved are the stored weights plus
+ * 8 bytes of row/column bit masks per block.
+ * Errors: as grim_bcr_spmm; batch outside 1..8 is GRIM_ERR_SHAPE.
+ */
+grim_status grim_bcr_spmv(const grim_bcr_matrix *A, const void *x_dev, int32_t batch, int64_t ldx,
+                          float *y_dev, int64_t ldy, void *hip_stream);
+
+/*
+ * Batched SpMV: many independent (W_i, x_i) products in ONE launch.  A single
+ * gate-matrix product moves ~2 MB, far less than a kernel launch costs, so
+ * independent products are grouped to fill the GPU.
+ * grim_bcr_group_create copies the device descriptors of `count` packed matrices
+ * (same M, K, BR, BC, dtype; all packed on the current GPU) into one device table.
+ * The matrices must outlive the group.
+ * grim_bcr_spmv_batched computes y_i = W_i * x_i for i in [0, count): x_i starts at
+ * x_dev + i * x_stride elements (K x batch, ldx), y_i at y_dev + i * y_stride floats.
+ */
+grim_status grim_bcr_group_create(const grim_bcr_matrix *const *mats, int32_t count,
+                                  grim_bcr_group **out);
+grim_status grim_bcr_spmv_batched(const grim_bcr_group *G, const void *x_dev, int64_t x_stride,
+                                  int32_t batch, int64_t ldx, float *y_dev, int64_t y_stride,
+                                  int64_t ldy, void *hip_stream);
+void grim_bcr_group_free(grim_bcr_group *G);
+
+/* grim_bcr_free -- release a matrix and its device memory.  NULL is a no-op. */
+void grim_bcr_free(grim_bcr_matrix *A);
+
+/* grim_status_str -- static, human-readable name of a status code. */
+const char *grim_status_str(grim_status s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GRIM_BCR_H */

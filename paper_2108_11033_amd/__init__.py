@@ -1,0 +1,9 @@
+"""BCR (Block-based Column-Row) sparse SpMM / SpMV for AMD MI355X.
+
+Thin ctypes binding of libgrim_bcr.so (see include/grim_bcr.h).  All arithmetic
+runs in the library's HIP kernels; this package only marshals arguments.
+"""
+from .binding import (  # noqa: F401
+    BcrMatrix, BcrGroup, GrimError, lib_path, load_library, pack, spmm, spmv, spmv_batched,
+    F32, F16, BF16, STATUS_NAMES,
+)

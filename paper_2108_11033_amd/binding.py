@@ -1,0 +1,260 @@
+"""ctypes binding of the C ABI declared in include/grim_bcr.h.
+
+Argument marshalling only.  Host arrays are NumPy; device buffers are anything
+with a ``data_ptr()`` (torch tensors) or a raw integer address.  There is no
+CPU fallback: if libgrim_bcr.so is missing, importing a function that needs it
+raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+import numpy as np
+
+F32, F16, BF16 = 0, 1, 2
+_DT_CODE = {"f32": F32, "f16": F16, "bf16": BF16, F32: F32, F16: F16, BF16: BF16}
+_DT_NUMPY = {F32: np.float32, F16: np.float16, BF16: np.uint16}
+STATUS_NAMES = ["GRIM_OK", "GRIM_ERR_NULL", "GRIM_ERR_SHAPE", "GRIM_ERR_INDEX", "GRIM_ERR_DTYPE",
+                "GRIM_ERR_ALLOC", "GRIM_ERR_DEVICE", "GRIM_ERR_UNSUPPORTED"]
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_lib = None
+
+
+class GrimError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = int(status)
+        name = STATUS_NAMES[status] if 0 <= status < len(STATUS_NAMES) else str(status)
+        super().__init__(f"{where}: {name}")
+        self.name = name
+
+
+class Options(ctypes.Structure):
+    _fields_ = [("no_reorder", ctypes.c_int32), ("host_only", ctypes.c_int32),
+                ("chunk_rows", ctypes.c_int32), ("reserved", ctypes.c_int32 * 5)]
+
+
+class View(ctypes.Structure):
+    _fields_ = [("M", ctypes.c_int64), ("K", ctypes.c_int64), ("BR", ctypes.c_int32), ("BC", ctypes.c_int32),
+                ("dtype", ctypes.c_int32), ("reordered", ctypes.c_int32),
+                ("nbr", ctypes.c_int64), ("nbc", ctypes.c_int64), ("nb", ctypes.c_int64), ("nnz", ctypes.c_int64),
+                ("strip_order", ctypes.c_void_p), ("row_ptr", ctypes.c_void_p), ("row_idx", ctypes.c_void_p),
+                ("col_ptr", ctypes.c_void_p), ("col_idx", ctypes.c_void_p), ("blk_ptr", ctypes.c_void_p),
+                ("weights", ctypes.c_void_p),
+                ("dev_bytes_canonical", ctypes.c_int64), ("dev_bytes_mma", ctypes.c_int64),
+                ("dev_bytes_gemv", ctypes.c_int64)]
+
+
+EXPORTS = ["grim_bcr_pack", "grim_bcr_unpack", "grim_bcr_arrays", "grim_bcr_spmm", "grim_bcr_spmm_tuned",
+           "grim_bcr_spmv", "grim_bcr_group_create", "grim_bcr_spmv_batched", "grim_bcr_group_free",
+           "grim_bcr_free", "grim_status_str"]
+
+
+def lib_path() -> str:
+    return os.path.join(_HERE, "libgrim_bcr.so")
+
+
+def load_library():
+    """Load libgrim_bcr.so (built in-tree by paper_2108_11033_amd/build.py)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = lib_path()
+    if not os.path.exists(path):
+        raise ImportError(f"{path} is missing: run `python paper_2108_11033_amd/build.py` "
+                          "(there is no CPU fallback)")
+    # PyTorch ships its own HIP runtime (same SONAME as the system one).  Two HIP runtimes in
+    # one process cannot both own the GPU, so let torch's be loaded first; the library's
+    # dependency then binds to it.  Without torch the system runtime is used.
+    try:
+        import torch  # noqa: F401
+    except ImportError:
+        pass
+    lib = ctypes.CDLL(path)
+    i64, i32, p = ctypes.c_int64, ctypes.c_int32, ctypes.c_void_p
+    lib.grim_bcr_pack.argtypes = [p, i32, i64, i64, i64, i32, i32, p, p, p, p, p, ctypes.POINTER(p)]
+    lib.grim_bcr_unpack.argtypes = [p, p, i64]
+    lib.grim_bcr_arrays.argtypes = [p, ctypes.POINTER(View)]
+    lib.grim_bcr_spmm.argtypes = [p, p, i64, i64, p, i64, p]
+    lib.grim_bcr_spmm_tuned.argtypes = [p, p, i64, i64, p, i64, i32, i32, i32, p]
+    lib.grim_bcr_spmv.argtypes = [p, p, i32, i64, p, i64, p]
+    lib.grim_bcr_group_create.argtypes = [ctypes.POINTER(p), i32, ctypes.POINTER(p)]
+    lib.grim_bcr_spmv_batched.argtypes = [p, p, i64, i32, i64, p, i64, i64, p]
+    lib.grim_bcr_group_free.argtypes = [p]
+    lib.grim_bcr_free.argtypes = [p]
+    lib.grim_status_str.argtypes = [i32]
+    for name in EXPORTS:
+        getattr(lib, name).restype = i32
+    lib.grim_status_str.restype = ctypes.c_char_p
+    lib.grim_bcr_free.restype = None
+    lib.grim_bcr_group_free.restype = None
+    _lib = lib
+    return lib
+
+
+def _check(status: int, where: str):
+    if status != 0:
+        raise GrimError(status, where)
+
+
+def _addr(buf) -> Optional[int]:
+    if buf is None:
+        return None
+    if isinstance(buf, int):
+        return buf
+    if hasattr(buf, "data_ptr"):
+        return int(buf.data_ptr())
+    raise TypeError("device buffer must be an int address or expose data_ptr()")
+
+
+def _np_ptr(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        return None
+    if isinstance(stream, int):
+        return stream or None
+    return int(stream.cuda_stream) or None
+
+
+class BcrMatrix:
+    """Owner of a packed matrix handle (grim_bcr_matrix*)."""
+
+    def __init__(self, handle: int, lib):
+        self._h = ctypes.c_void_p(handle)
+        self._lib = lib
+
+    @property
+    def handle(self) -> ctypes.c_void_p:
+        if not self._h:
+            raise ValueError("matrix already freed")
+        return self._h
+
+    def view(self) -> View:
+        v = View()
+        _check(self._lib.grim_bcr_arrays(self.handle, ctypes.byref(v)), "grim_bcr_arrays")
+        return v
+
+    def arrays(self) -> dict:
+        """Copies of the canonical compact arrays as NumPy arrays."""
+        v = self.view()
+
+        def take(addr, count, dtype):
+            if count == 0 or not addr:
+                return np.zeros(0, dtype=dtype)
+            n = count * np.dtype(dtype).itemsize
+            return np.frombuffer(ctypes.string_at(addr, n), dtype=dtype).copy()
+
+        row_ptr = take(v.row_ptr, v.nb + 1, np.int32)
+        col_ptr = take(v.col_ptr, v.nb + 1, np.int32)
+        return {
+            "strip_order": take(v.strip_order, v.nbr, np.int32),
+            "row_ptr": row_ptr,
+            "row_idx": take(v.row_idx, int(row_ptr[-1]), np.uint16),
+            "col_ptr": col_ptr,
+            "col_idx": take(v.col_idx, int(col_ptr[-1]), np.uint16),
+            "blk_ptr": take(v.blk_ptr, v.nb + 1, np.int64),
+            "weights": take(v.weights, v.nnz, _DT_NUMPY[v.dtype]),
+        }
+
+    def unpack(self) -> np.ndarray:
+        v = self.view()
+        out = np.empty((v.M, v.K), dtype=_DT_NUMPY[v.dtype])
+        _check(self._lib.grim_bcr_unpack(self.handle, _np_ptr(out), v.K), "grim_bcr_unpack")
+        return out
+
+    def free(self):
+        if self._h:
+            self._lib.grim_bcr_free(self._h)
+            self._h = ctypes.c_void_p(None)
+
+    def __del__(self):
+        try:
+            self.free()
+        except Exception:
+            pass
+
+
+class BcrGroup:
+    def __init__(self, handle: int, lib, mats: Sequence[BcrMatrix]):
+        self._h = ctypes.c_void_p(handle)
+        self._lib = lib
+        self._mats = list(mats)     # keep the matrices alive
+
+    @property
+    def handle(self):
+        return self._h
+
+    @property
+    def count(self) -> int:
+        return len(self._mats)
+
+    def free(self):
+        if self._h:
+            self._lib.grim_bcr_group_free(self._h)
+            self._h = ctypes.c_void_p(None)
+
+    def __del__(self):
+        try:
+            self.free()
+        except Exception:
+            pass
+
+
+def pack(W: np.ndarray, dtype, BR: int, BC: int, row_ptr, row_idx, col_ptr, col_idx, *,
+         no_reorder: bool = False, host_only: bool = False, chunk_rows: int = 0) -> BcrMatrix:
+    """grim_bcr_pack.  ``W`` is a C-contiguous M x K NumPy array in the storage
+    type (uint16 bit patterns for bf16)."""
+    lib = load_library()
+    dt = _DT_CODE[dtype]
+    W = np.ascontiguousarray(W)
+    if W.dtype != _DT_NUMPY[dt]:
+        raise TypeError(f"W must be {_DT_NUMPY[dt]} for dtype {dtype}")
+    M, K = W.shape
+    row_ptr = np.ascontiguousarray(row_ptr, dtype=np.int32)
+    col_ptr = np.ascontiguousarray(col_ptr, dtype=np.int32)
+    row_idx = np.ascontiguousarray(row_idx, dtype=np.uint16)
+    col_idx = np.ascontiguousarray(col_idx, dtype=np.uint16)
+    opt = Options(int(no_reorder), int(host_only), int(chunk_rows))
+    out = ctypes.c_void_p()
+    st = lib.grim_bcr_pack(_np_ptr(W), dt, M, K, K, BR, BC,
+                           _np_ptr(row_ptr), _np_ptr(row_idx), _np_ptr(col_ptr), _np_ptr(col_idx),
+                           ctypes.byref(opt), ctypes.byref(out))
+    _check(st, "grim_bcr_pack")
+    return BcrMatrix(out.value, lib)
+
+
+def spmm(A: BcrMatrix, X, N: int, ldx: int, Y, ldy: int, stream=None, *,
+         tile_n: int = 0, strips_per_wg: int = 0, kernel: int = 0):
+    """grim_bcr_spmm / grim_bcr_spmm_tuned: enqueue Y = W_bcr * X."""
+    lib = A._lib
+    if tile_n or strips_per_wg or kernel:
+        st = lib.grim_bcr_spmm_tuned(A.handle, _addr(X), N, ldx, _addr(Y), ldy, tile_n, strips_per_wg,
+                                     kernel, _stream(stream))
+        _check(st, "grim_bcr_spmm_tuned")
+    else:
+        _check(lib.grim_bcr_spmm(A.handle, _addr(X), N, ldx, _addr(Y), ldy, _stream(stream)), "grim_bcr_spmm")
+
+
+def spmv(A: BcrMatrix, x, batch: int, ldx: int, y, ldy: int, stream=None):
+    """grim_bcr_spmv: enqueue y = W_bcr * x for 1..8 right-hand sides."""
+    _check(A._lib.grim_bcr_spmv(A.handle, _addr(x), batch, ldx, _addr(y), ldy, _stream(stream)), "grim_bcr_spmv")
+
+
+def group(mats: Sequence[BcrMatrix]) -> BcrGroup:
+    lib = load_library()
+    arr = (ctypes.c_void_p * len(mats))(*[m.handle for m in mats])
+    out = ctypes.c_void_p()
+    _check(lib.grim_bcr_group_create(arr, len(mats), ctypes.byref(out)), "grim_bcr_group_create")
+    return BcrGroup(out.value, lib, mats)
+
+
+def spmv_batched(G: BcrGroup, x, x_stride: int, batch: int, ldx: int, y, y_stride: int, ldy: int, stream=None):
+    """grim_bcr_spmv_batched: all products of the group in one launch."""
+    st = G._lib.grim_bcr_spmv_batched(G.handle, _addr(x), x_stride, batch, ldx, _addr(y), y_stride, ldy,
+                                      _stream(stream))
+    _check(st, "grim_bcr_spmv_batched")

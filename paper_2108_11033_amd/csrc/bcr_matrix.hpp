@@ -1,0 +1,117 @@
+// Internal definitions shared by the host packer and the kernel launchers.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+#include <vector>
+
+#include "grim_bcr.h"
+
+namespace grim {
+
+constexpr int kMmaMaxChunkRows = 128;   // rows of X staged in LDS per step by the matrix-core kernel
+constexpr int kGemvMaxXBytes = 65536;   // bytes of x (K * batch elements) the SpMV kernel keeps in LDS
+
+inline int dtype_size(int dt) { return dt == GRIM_F32 ? 4 : 2; }
+
+// Row-expanded layout for the matrix-core SpMM kernel (fp16 / bf16, BR = 16 or 32).
+// For every stored strip the kept columns of its blocks are concatenated into one
+// gather list of X rows, cut into chunks of `chunk_rows` consecutive rows of X and
+// padded per chunk to a multiple of `ks` (the k extent of one MFMA).  The weights
+// of a step are stored as the MFMA operand fragment itself (64 lanes x 8 values),
+// with pruned rows of a block as zeros, so that output rows sit at their strip
+// positions and no scatter is needed.
+struct MmaLayout {
+    bool present = false;
+    int32_t ks = 0;            // 32 for BR = 16 (16x16x32), 16 for BR = 32 (32x32x16)
+    int32_t chunk_blocks = 0;  // column blocks per chunk
+    int32_t chunk_rows = 0;    // chunk_blocks * BC
+    int32_t nchunks = 0;
+    int64_t nsteps = 0;
+    std::vector<int32_t> kstep_ptr;   // [nbr * (nchunks + 1)] first step of (strip t, chunk j)
+    std::vector<uint16_t> kidx;       // [nsteps * ks] row of the chunk's LDS tile; chunk_rows = zero row
+    std::vector<uint16_t> afrag;      // [nsteps * 512] operand fragments
+    int32_t *d_kstep_ptr = nullptr;
+    uint16_t *d_kidx = nullptr;
+    uint16_t *d_afrag = nullptr;
+    int64_t bytes = 0;
+};
+
+// Layout for the SpMV kernel (BR, BC <= 32): the compact weights themselves plus one
+// row bit mask and one column bit mask per stored block.
+struct GemvLayout {
+    bool present = false;
+    int32_t uniform_kr = -1, uniform_kc = -1;   // >= 0 when every block keeps the same counts
+    int32_t vec = 1;                            // widest aligned vector (elements) for weight rows
+    std::vector<uint32_t> masks;                // [nb * 2] (rowmask, colmask)
+    std::vector<uint32_t> woff;                 // [nb + 1] element offsets (32-bit copy of blk_ptr)
+    uint32_t *d_masks = nullptr;
+    uint32_t *d_woff = nullptr;
+    int64_t bytes = 0;
+};
+
+struct DeviceCanonical {
+    int32_t *strip_order = nullptr;
+    int32_t *row_ptr = nullptr;
+    uint16_t *row_idx = nullptr;
+    int32_t *col_ptr = nullptr;
+    uint16_t *col_idx = nullptr;
+    int64_t *blk_ptr = nullptr;
+    void *weights = nullptr;
+    uint64_t *rowmask64 = nullptr;   // per stored block, bit r set when local row r is kept (BR <= 64)
+    int64_t bytes = 0;
+};
+
+}  // namespace grim
+
+struct grim_bcr_matrix {
+    int64_t M = 0, K = 0;
+    int32_t BR = 0, BC = 0;
+    int32_t dtype = 0;
+    int32_t reordered = 0;
+    int64_t nbr = 0, nbc = 0, nb = 0, nnz = 0;
+    // canonical host arrays (stored order)
+    std::vector<int32_t> strip_order;
+    std::vector<int32_t> row_ptr, col_ptr;
+    std::vector<uint16_t> row_idx, col_idx;
+    std::vector<int64_t> blk_ptr;
+    std::vector<unsigned char> weights;
+    std::vector<uint64_t> rowmask64;
+    // device side
+    bool on_device = false;
+    int device = -1;
+    grim::DeviceCanonical dev;
+    grim::MmaLayout mma;
+    grim::GemvLayout gemv;
+};
+
+// Descriptor of one matrix as the SpMV kernel reads it (device table entry of a group).
+struct GemvDesc {
+    const void *weights;
+    const uint32_t *masks;
+    const uint32_t *woff;
+    const int32_t *strip_order;
+};
+
+struct grim_bcr_group {
+    int32_t count = 0;
+    int64_t M = 0, K = 0;
+    int32_t BR = 0, BC = 0, dtype = 0;
+    int64_t nbr = 0, nbc = 0;
+    int32_t uniform_kr = -1, uniform_kc = -1, vec = 1;
+    int device = -1;
+    GemvDesc *d_table = nullptr;
+};
+
+namespace grim {
+// kernel launchers (defined in the .hip files); all enqueue on `stream` and return a status
+grim_status launch_spmm_fma(const grim_bcr_matrix *A, const void *X, int64_t N, int64_t ldx, float *Y,
+                            int64_t ldy, hipStream_t stream);
+grim_status launch_spmm_mma(const grim_bcr_matrix *A, const void *X, int64_t N, int64_t ldx, float *Y,
+                            int64_t ldy, int32_t tile_n, int32_t strips_per_wg, hipStream_t stream);
+bool mma_supported(const grim_bcr_matrix *A);
+grim_status launch_spmv(const GemvDesc *table_dev_or_null, const GemvDesc &single, int32_t count,
+                        int64_t M, int64_t K, int32_t BR, int32_t BC, int32_t dtype, int32_t ukr,
+                        int32_t ukc, int32_t vec, const void *x, int64_t x_stride, int32_t batch,
+                        int64_t ldx, float *y, int64_t y_stride, int64_t ldy, hipStream_t stream);
+}  // namespace grim

@@ -1,0 +1,479 @@
+// Host side of the library: validation, compaction of the dense matrix into the
+// canonical block-compact arrays, the derived device layouts, upload, and the
+// extern "C" entry points.
+#include <algorithm>
+#include <cstring>
+#include <new>
+#include <numeric>
+
+#include "bcr_matrix.hpp"
+
+using namespace grim;
+
+namespace {
+
+struct Slab {
+    // one device allocation holding every array of a matrix, each 256-byte aligned
+    size_t total = 0;
+    size_t add(size_t bytes) {
+        size_t off = total;
+        total += (bytes + 255) & ~size_t(255);
+        return off;
+    }
+};
+
+grim_status validate_sets(int64_t nb, int32_t B, const int32_t *ptr, const uint16_t *idx) {
+    if (ptr[0] != 0) return GRIM_ERR_INDEX;
+    for (int64_t b = 0; b < nb; ++b) {
+        int64_t lo = ptr[b], hi = ptr[b + 1];
+        if (hi < lo || hi - lo > B) return GRIM_ERR_INDEX;
+        if (hi > lo && idx == nullptr) return GRIM_ERR_NULL;
+        for (int64_t t = lo; t < hi; ++t) {
+            if (idx[t] >= B) return GRIM_ERR_INDEX;
+            if (t > lo && idx[t] <= idx[t - 1]) return GRIM_ERR_INDEX;
+        }
+    }
+    return GRIM_OK;
+}
+
+// ---- derived layout: matrix-core SpMM ---------------------------------------------------
+void build_mma_layout(grim_bcr_matrix *A, int32_t chunk_rows_opt) {
+    MmaLayout &L = A->mma;
+    L.present = false;
+    if (A->dtype == GRIM_F32) return;
+    if (A->BR != 16 && A->BR != 32) return;
+    if (A->BC > kMmaMaxChunkRows) return;
+    int32_t want = chunk_rows_opt > 0 ? std::min<int32_t>(chunk_rows_opt, kMmaMaxChunkRows) : kMmaMaxChunkRows;
+    L.chunk_blocks = std::max<int32_t>(1, want / A->BC);
+    L.chunk_rows = L.chunk_blocks * A->BC;
+    L.nchunks = (int32_t)((A->nbc + L.chunk_blocks - 1) / L.chunk_blocks);
+    L.ks = A->BR == 16 ? 32 : 16;
+    const int32_t ks = L.ks, BR = A->BR, esz = 2;
+    const int lanes_per_kgroup = BR == 16 ? 16 : 32;   // lanes sharing one group of 8 k slots
+    L.kstep_ptr.assign((size_t)A->nbr * (L.nchunks + 1), 0);
+    L.kidx.clear();
+    L.afrag.clear();
+    struct Slot { int64_t t; int32_t j; };   // stored block, position of the kept column in it
+    std::vector<Slot> slots;
+    std::vector<int32_t> comp(BR);           // local row -> compact row or -1
+    int64_t step = 0;
+    const uint16_t *w = reinterpret_cast<const uint16_t *>(A->weights.data());
+    (void)esz;
+    for (int64_t st = 0; st < A->nbr; ++st) {
+        for (int32_t ch = 0; ch < L.nchunks; ++ch) {
+            L.kstep_ptr[st * (L.nchunks + 1) + ch] = (int32_t)step;
+            slots.clear();
+            std::vector<uint16_t> rows;
+            int64_t c0 = (int64_t)ch * L.chunk_blocks, c1 = std::min<int64_t>(A->nbc, c0 + L.chunk_blocks);
+            for (int64_t c = c0; c < c1; ++c) {
+                int64_t t = st * A->nbc + c;
+                if (A->row_ptr[t + 1] == A->row_ptr[t]) continue;   // no kept rows: nothing to multiply
+                for (int32_t q = A->col_ptr[t]; q < A->col_ptr[t + 1]; ++q) {
+                    slots.push_back({t, q - A->col_ptr[t]});
+                    rows.push_back((uint16_t)((c - c0) * A->BC + A->col_idx[q]));
+                }
+            }
+            size_t nsl = slots.size();
+            size_t padded = (nsl + ks - 1) / ks * ks;
+            for (size_t base = 0; base < padded; base += ks) {
+                size_t k0 = L.kidx.size(), a0 = L.afrag.size();
+                L.kidx.resize(k0 + ks);
+                L.afrag.resize(a0 + 512, 0);
+                for (int32_t e = 0; e < ks; ++e)
+                    L.kidx[k0 + e] = base + e < nsl ? rows[base + e] : (uint16_t)L.chunk_rows;
+                int64_t cur_t = -1;
+                for (int32_t e = 0; e < ks; ++e) {
+                    if (base + e >= nsl) break;
+                    const Slot &s = slots[base + e];
+                    if (s.t != cur_t) {
+                        cur_t = s.t;
+                        std::fill(comp.begin(), comp.end(), -1);
+                        for (int32_t q = A->row_ptr[s.t]; q < A->row_ptr[s.t + 1]; ++q)
+                            comp[A->row_idx[q]] = q - A->row_ptr[s.t];
+                    }
+                    int32_t kc = A->col_ptr[s.t + 1] - A->col_ptr[s.t];
+                    int32_t kgroup = e / 8, i = e % 8;
+                    for (int32_t m = 0; m < BR; ++m) {
+                        if (comp[m] < 0) continue;
+                        int32_t lane = kgroup * lanes_per_kgroup + m;
+                        L.afrag[a0 + (size_t)lane * 8 + i] = w[A->blk_ptr[s.t] + (int64_t)comp[m] * kc + s.j];
+                    }
+                }
+                ++step;
+            }
+        }
+        L.kstep_ptr[st * (L.nchunks + 1) + L.nchunks] = (int32_t)step;
+    }
+    L.nsteps = step;
+    L.present = true;
+}
+
+// ---- derived layout: SpMV --------------------------------------------------------------
+void build_gemv_layout(grim_bcr_matrix *A) {
+    GemvLayout &G = A->gemv;
+    G.present = false;
+    if (A->BR > 32 || A->BC > 32) return;
+    if (A->nnz >= (int64_t(1) << 31)) return;
+    G.masks.assign((size_t)A->nb * 2, 0);
+    G.woff.resize((size_t)A->nb + 1);
+    int32_t ukr = -2, ukc = -2;
+    int32_t vec = 8;
+    for (int64_t t = 0; t < A->nb; ++t) {
+        uint32_t rm = 0, cm = 0;
+        for (int32_t q = A->row_ptr[t]; q < A->row_ptr[t + 1]; ++q) rm |= 1u << A->row_idx[q];
+        for (int32_t q = A->col_ptr[t]; q < A->col_ptr[t + 1]; ++q) cm |= 1u << A->col_idx[q];
+        int32_t kr = A->row_ptr[t + 1] - A->row_ptr[t], kc = A->col_ptr[t + 1] - A->col_ptr[t];
+        if (kr == 0 || kc == 0) { rm = 0; cm = 0; kr = 0; kc = 0; }   // stores nothing
+        G.masks[2 * t] = rm;
+        G.masks[2 * t + 1] = cm;
+        G.woff[t] = (uint32_t)A->blk_ptr[t];
+        ukr = ukr == -2 ? kr : (ukr == kr ? ukr : -1);
+        ukc = ukc == -2 ? kc : (ukc == kc ? ukc : -1);
+        if (kr > 0) while (vec > 1 && kc % vec) vec >>= 1;
+    }
+    G.woff[A->nb] = (uint32_t)A->blk_ptr[A->nb];
+    G.uniform_kr = ukr < 0 ? -1 : ukr;
+    G.uniform_kc = ukc < 0 ? -1 : ukc;
+    if (G.uniform_kr < 0 || G.uniform_kc < 0) G.uniform_kr = G.uniform_kc = -1;
+    G.vec = std::min<int32_t>(vec, 16 / dtype_size(A->dtype));
+    G.present = true;
+}
+
+grim_status upload(grim_bcr_matrix *A) {
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || ndev < 1) { (void)hipGetLastError(); return GRIM_ERR_DEVICE; }
+    if (hipGetDevice(&A->device) != hipSuccess) return GRIM_ERR_DEVICE;
+    Slab s;
+    auto bytes = [](const auto &v) { return v.size() * sizeof(v[0]); };
+    size_t o_so = s.add(bytes(A->strip_order));
+    size_t o_rp = s.add(bytes(A->row_ptr));
+    size_t o_ri = s.add(bytes(A->row_idx));
+    size_t o_cp = s.add(bytes(A->col_ptr));
+    size_t o_ci = s.add(bytes(A->col_idx));
+    size_t o_bp = s.add(bytes(A->blk_ptr));
+    size_t o_w = s.add(A->weights.size() + 64);   // slack: vector loads may overrun a row's end
+    size_t o_rm = s.add(bytes(A->rowmask64));
+    size_t canon_end = s.total;
+    size_t o_kp = 0, o_ki = 0, o_af = 0, o_gm = 0, o_go = 0;
+    if (A->mma.present) {
+        o_kp = s.add(bytes(A->mma.kstep_ptr));
+        o_ki = s.add(bytes(A->mma.kidx) + 64);
+        o_af = s.add(bytes(A->mma.afrag) + 1024);
+    }
+    size_t mma_end = s.total;
+    if (A->gemv.present) {
+        o_gm = s.add(bytes(A->gemv.masks));
+        o_go = s.add(bytes(A->gemv.woff));
+    }
+    char *base = nullptr;
+    if (hipMalloc(reinterpret_cast<void **>(&base), s.total + 256) != hipSuccess) { (void)hipGetLastError(); return GRIM_ERR_ALLOC; }
+    if (hipMemset(base, 0, s.total + 256) != hipSuccess) { (void)hipFree(base); return GRIM_ERR_DEVICE; }
+    auto put = [&](size_t off, const void *src, size_t n) -> bool {
+        return n == 0 || hipMemcpy(base + off, src, n, hipMemcpyHostToDevice) == hipSuccess;
+    };
+    bool ok = put(o_so, A->strip_order.data(), bytes(A->strip_order)) && put(o_rp, A->row_ptr.data(), bytes(A->row_ptr)) &&
+              put(o_ri, A->row_idx.data(), bytes(A->row_idx)) && put(o_cp, A->col_ptr.data(), bytes(A->col_ptr)) &&
+              put(o_ci, A->col_idx.data(), bytes(A->col_idx)) && put(o_bp, A->blk_ptr.data(), bytes(A->blk_ptr)) &&
+              put(o_w, A->weights.data(), A->weights.size()) && put(o_rm, A->rowmask64.data(), bytes(A->rowmask64));
+    if (ok && A->mma.present)
+        ok = put(o_kp, A->mma.kstep_ptr.data(), bytes(A->mma.kstep_ptr)) && put(o_ki, A->mma.kidx.data(), bytes(A->mma.kidx)) &&
+             put(o_af, A->mma.afrag.data(), bytes(A->mma.afrag));
+    if (ok && A->gemv.present)
+        ok = put(o_gm, A->gemv.masks.data(), bytes(A->gemv.masks)) && put(o_go, A->gemv.woff.data(), bytes(A->gemv.woff));
+    if (!ok) { (void)hipGetLastError(); (void)hipFree(base); return GRIM_ERR_DEVICE; }
+    A->dev.strip_order = reinterpret_cast<int32_t *>(base + o_so);
+    A->dev.row_ptr = reinterpret_cast<int32_t *>(base + o_rp);
+    A->dev.row_idx = reinterpret_cast<uint16_t *>(base + o_ri);
+    A->dev.col_ptr = reinterpret_cast<int32_t *>(base + o_cp);
+    A->dev.col_idx = reinterpret_cast<uint16_t *>(base + o_ci);
+    A->dev.blk_ptr = reinterpret_cast<int64_t *>(base + o_bp);
+    A->dev.weights = base + o_w;
+    A->dev.rowmask64 = reinterpret_cast<uint64_t *>(base + o_rm);
+    A->dev.bytes = (int64_t)canon_end;
+    if (A->mma.present) {
+        A->mma.d_kstep_ptr = reinterpret_cast<int32_t *>(base + o_kp);
+        A->mma.d_kidx = reinterpret_cast<uint16_t *>(base + o_ki);
+        A->mma.d_afrag = reinterpret_cast<uint16_t *>(base + o_af);
+        A->mma.bytes = (int64_t)(mma_end - canon_end);
+    }
+    if (A->gemv.present) {
+        A->gemv.d_masks = reinterpret_cast<uint32_t *>(base + o_gm);
+        A->gemv.d_woff = reinterpret_cast<uint32_t *>(base + o_go);
+        A->gemv.bytes = (int64_t)(s.total - mma_end);
+    }
+    A->on_device = true;
+    return GRIM_OK;
+}
+
+grim_status check_call(const grim_bcr_matrix *A, const void *X, int64_t N, int64_t ldx, const float *Y, int64_t ldy) {
+    if (!A || !X || !Y) return GRIM_ERR_NULL;
+    if (N < 1 || ldx < N || ldy < N) return GRIM_ERR_SHAPE;
+    if (N > (int64_t(1) << 30) || ldx > (int64_t(1) << 40) || ldy > (int64_t(1) << 40)) return GRIM_ERR_SHAPE;
+    if (!A->on_device) return GRIM_ERR_DEVICE;
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev != A->device) return GRIM_ERR_DEVICE;
+    return GRIM_OK;
+}
+
+bool gemv_ok(const grim_bcr_matrix *A, int64_t N) {
+    return A->gemv.present && N >= 1 && N <= 8 && A->K * N * dtype_size(A->dtype) <= kGemvMaxXBytes;
+}
+
+GemvDesc desc_of(const grim_bcr_matrix *A) {
+    return GemvDesc{A->dev.weights, A->gemv.d_masks, A->gemv.d_woff, A->dev.strip_order};
+}
+
+}  // namespace
+
+extern "C" {
+
+grim_status grim_bcr_pack(const void *W_host, grim_dtype dt, int64_t M, int64_t K, int64_t ldw, int32_t BR, int32_t BC,
+                          const int32_t *row_ptr, const uint16_t *row_idx, const int32_t *col_ptr,
+                          const uint16_t *col_idx, const grim_bcr_options *opt, grim_bcr_matrix **out) {
+    if (out) *out = nullptr;
+    if (!out || !W_host || !row_ptr || !col_ptr) return GRIM_ERR_NULL;
+    if (dt != GRIM_F32 && dt != GRIM_F16 && dt != GRIM_BF16) return GRIM_ERR_DTYPE;
+    if (M < 1 || K < 1 || BR < 1 || BC < 1 || BR > 65535 || BC > 65535) return GRIM_ERR_SHAPE;
+    if (M % BR || K % BC || ldw < K) return GRIM_ERR_SHAPE;
+    if (M > (int64_t(1) << 31) - 1 || K > (int64_t(1) << 31) - 1) return GRIM_ERR_SHAPE;
+    const int64_t nbr = M / BR, nbc = K / BC;
+    if (nbr > (int64_t(1) << 30) / nbc) return GRIM_ERR_SHAPE;   // ptr arrays are 32-bit
+    const int64_t nb = nbr * nbc;
+    grim_status st = validate_sets(nb, BR, row_ptr, row_idx);
+    if (st != GRIM_OK) return st;
+    st = validate_sets(nb, BC, col_ptr, col_idx);
+    if (st != GRIM_OK) return st;
+
+    grim_bcr_matrix *A = nullptr;
+    try {
+        A = new grim_bcr_matrix();
+        A->M = M; A->K = K; A->BR = BR; A->BC = BC; A->dtype = dt;
+        A->nbr = nbr; A->nbc = nbc; A->nb = nb;
+        A->reordered = !(opt && opt->no_reorder);
+        // strip work = stored weights of the strip; heavier strips first, ties by index (Section 4.2)
+        std::vector<int64_t> work(nbr, 0);
+        for (int64_t s = 0; s < nbr; ++s)
+            for (int64_t c = 0; c < nbc; ++c) {
+                int64_t b = s * nbc + c;
+                work[s] += int64_t(row_ptr[b + 1] - row_ptr[b]) * int64_t(col_ptr[b + 1] - col_ptr[b]);
+            }
+        A->strip_order.resize(nbr);
+        std::iota(A->strip_order.begin(), A->strip_order.end(), 0);
+        if (A->reordered)
+            std::stable_sort(A->strip_order.begin(), A->strip_order.end(),
+                             [&](int32_t a, int32_t b) { return work[a] > work[b]; });
+        const int esz = dtype_size(dt);
+        A->row_ptr.assign(nb + 1, 0);
+        A->col_ptr.assign(nb + 1, 0);
+        A->blk_ptr.assign(nb + 1, 0);
+        A->rowmask64.assign(nb, 0);
+        int64_t t = 0;
+        for (int64_t p = 0; p < nbr; ++p) {
+            int64_t s = A->strip_order[p];
+            for (int64_t c = 0; c < nbc; ++c, ++t) {
+                int64_t b = s * nbc + c;
+                int32_t kr = row_ptr[b + 1] - row_ptr[b], kc = col_ptr[b + 1] - col_ptr[b];
+                A->row_ptr[t + 1] = A->row_ptr[t] + kr;
+                A->col_ptr[t + 1] = A->col_ptr[t] + kc;
+                A->blk_ptr[t + 1] = A->blk_ptr[t] + int64_t(kr) * kc;
+            }
+        }
+        A->nnz = A->blk_ptr[nb];
+        A->row_idx.resize(A->row_ptr[nb]);
+        A->col_idx.resize(A->col_ptr[nb]);
+        A->weights.resize((size_t)A->nnz * esz);
+        const unsigned char *W = static_cast<const unsigned char *>(W_host);
+        t = 0;
+        for (int64_t p = 0; p < nbr; ++p) {
+            int64_t s = A->strip_order[p];
+            for (int64_t c = 0; c < nbc; ++c, ++t) {
+                int64_t b = s * nbc + c;
+                int32_t kr = row_ptr[b + 1] - row_ptr[b], kc = col_ptr[b + 1] - col_ptr[b];
+                const uint16_t *R = kr ? row_idx + row_ptr[b] : nullptr;
+                const uint16_t *C = kc ? col_idx + col_ptr[b] : nullptr;
+                for (int32_t i = 0; i < kr; ++i) {
+                    A->row_idx[A->row_ptr[t] + i] = R[i];
+                    if (BR <= 64) A->rowmask64[t] |= uint64_t(1) << R[i];
+                }
+                for (int32_t j = 0; j < kc; ++j) A->col_idx[A->col_ptr[t] + j] = C[j];
+                unsigned char *dst = A->weights.data() + (size_t)A->blk_ptr[t] * esz;
+                for (int32_t i = 0; i < kr; ++i) {
+                    const unsigned char *src = W + ((s * BR + R[i]) * ldw + c * BC) * esz;
+                    for (int32_t j = 0; j < kc; ++j) std::memcpy(dst + ((size_t)i * kc + j) * esz, src + (size_t)C[j] * esz, esz);
+                }
+            }
+        }
+        if (!(opt && opt->host_only)) {
+            build_mma_layout(A, opt ? opt->chunk_rows : 0);
+            build_gemv_layout(A);
+        }
+    } catch (const std::bad_alloc &) {
+        delete A;
+        return GRIM_ERR_ALLOC;
+    }
+    if (!(opt && opt->host_only)) {
+        st = upload(A);
+        if (st != GRIM_OK) { delete A; return st; }
+    }
+    *out = A;
+    return GRIM_OK;
+}
+
+grim_status grim_bcr_unpack(const grim_bcr_matrix *A, void *W_host_out, int64_t ldw) {
+    if (!A || !W_host_out) return GRIM_ERR_NULL;
+    if (ldw < A->K) return GRIM_ERR_SHAPE;
+    const int esz = dtype_size(A->dtype);
+    unsigned char *W = static_cast<unsigned char *>(W_host_out);
+    for (int64_t i = 0; i < A->M; ++i) std::memset(W + i * ldw * esz, 0, (size_t)A->K * esz);
+    int64_t t = 0;
+    for (int64_t p = 0; p < A->nbr; ++p) {
+        int64_t s = A->strip_order[p];
+        for (int64_t c = 0; c < A->nbc; ++c, ++t) {
+            int32_t kr = A->row_ptr[t + 1] - A->row_ptr[t], kc = A->col_ptr[t + 1] - A->col_ptr[t];
+            const unsigned char *src = A->weights.data() + (size_t)A->blk_ptr[t] * esz;
+            for (int32_t i = 0; i < kr; ++i) {
+                int64_t r = s * A->BR + A->row_idx[A->row_ptr[t] + i];
+                for (int32_t j = 0; j < kc; ++j) {
+                    int64_t k = c * A->BC + A->col_idx[A->col_ptr[t] + j];
+                    std::memcpy(W + (r * ldw + k) * esz, src + ((size_t)i * kc + j) * esz, esz);
+                }
+            }
+        }
+    }
+    return GRIM_OK;
+}
+
+grim_status grim_bcr_arrays(const grim_bcr_matrix *A, grim_bcr_view *v) {
+    if (!A || !v) return GRIM_ERR_NULL;
+    v->M = A->M; v->K = A->K; v->BR = A->BR; v->BC = A->BC; v->dtype = A->dtype; v->reordered = A->reordered;
+    v->nbr = A->nbr; v->nbc = A->nbc; v->nb = A->nb; v->nnz = A->nnz;
+    v->strip_order = A->strip_order.data();
+    v->row_ptr = A->row_ptr.data();
+    v->row_idx = A->row_idx.data();
+    v->col_ptr = A->col_ptr.data();
+    v->col_idx = A->col_idx.data();
+    v->blk_ptr = A->blk_ptr.data();
+    v->weights = A->weights.data();
+    v->dev_bytes_canonical = A->on_device ? A->dev.bytes : 0;
+    v->dev_bytes_mma = A->on_device && A->mma.present ? A->mma.bytes : 0;
+    v->dev_bytes_gemv = A->on_device && A->gemv.present ? A->gemv.bytes : 0;
+    return GRIM_OK;
+}
+
+grim_status grim_bcr_spmm_tuned(const grim_bcr_matrix *A, const void *X_dev, int64_t N, int64_t ldx, float *Y_dev,
+                                int64_t ldy, int32_t tile_n, int32_t strips_per_wg, int32_t kernel, void *hip_stream) {
+    grim_status st = check_call(A, X_dev, N, ldx, Y_dev, ldy);
+    if (st != GRIM_OK) return st;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    if (kernel < 0 || kernel > 2 || tile_n < 0 || strips_per_wg < 0) return GRIM_ERR_UNSUPPORTED;
+    if (kernel == 0 && tile_n == 0 && strips_per_wg == 0 && gemv_ok(A, N)) {
+        GemvDesc d = desc_of(A);
+        return launch_spmv(nullptr, d, 1, A->M, A->K, A->BR, A->BC, A->dtype, A->gemv.uniform_kr, A->gemv.uniform_kc,
+                           A->gemv.vec, X_dev, 0, (int32_t)N, ldx, Y_dev, 0, ldy, stream);
+    }
+    bool mma = A->mma.present && kernel != 1;
+    if (kernel == 2 && !mma) return GRIM_ERR_UNSUPPORTED;
+    if (mma) return launch_spmm_mma(A, X_dev, N, ldx, Y_dev, ldy, tile_n, strips_per_wg, stream);
+    if (A->BR > 64) return GRIM_ERR_UNSUPPORTED;
+    return launch_spmm_fma(A, X_dev, N, ldx, Y_dev, ldy, stream);
+}
+
+grim_status grim_bcr_spmm(const grim_bcr_matrix *A, const void *X_dev, int64_t N, int64_t ldx, float *Y_dev, int64_t ldy,
+                          void *hip_stream) {
+    return grim_bcr_spmm_tuned(A, X_dev, N, ldx, Y_dev, ldy, 0, 0, 0, hip_stream);
+}
+
+grim_status grim_bcr_spmv(const grim_bcr_matrix *A, const void *x_dev, int32_t batch, int64_t ldx, float *y_dev,
+                          int64_t ldy, void *hip_stream) {
+    if (!A || !x_dev || !y_dev) return GRIM_ERR_NULL;
+    if (batch < 1 || batch > 8) return GRIM_ERR_SHAPE;
+    grim_status st = check_call(A, x_dev, batch, ldx, y_dev, ldy);
+    if (st != GRIM_OK) return st;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    if (gemv_ok(A, batch)) {
+        GemvDesc d = desc_of(A);
+        return launch_spmv(nullptr, d, 1, A->M, A->K, A->BR, A->BC, A->dtype, A->gemv.uniform_kr, A->gemv.uniform_kc,
+                           A->gemv.vec, x_dev, 0, batch, ldx, y_dev, 0, ldy, stream);
+    }
+    if (A->BR > 64) return GRIM_ERR_UNSUPPORTED;
+    return launch_spmm_fma(A, x_dev, batch, ldx, y_dev, ldy, stream);
+}
+
+grim_status grim_bcr_group_create(const grim_bcr_matrix *const *mats, int32_t count, grim_bcr_group **out) {
+    if (out) *out = nullptr;
+    if (!mats || !out) return GRIM_ERR_NULL;
+    if (count < 1 || count > (1 << 20)) return GRIM_ERR_SHAPE;
+    for (int32_t i = 0; i < count; ++i)
+        if (!mats[i]) return GRIM_ERR_NULL;
+    const grim_bcr_matrix *A0 = mats[0];
+    int dev = -1;
+    if (!A0->on_device || hipGetDevice(&dev) != hipSuccess || dev != A0->device) return GRIM_ERR_DEVICE;
+    if (!A0->gemv.present) return GRIM_ERR_UNSUPPORTED;
+    grim_bcr_group *G = nullptr;
+    std::vector<GemvDesc> table;
+    try {
+        G = new grim_bcr_group();
+        table.resize(count);
+    } catch (const std::bad_alloc &) {
+        delete G;
+        return GRIM_ERR_ALLOC;
+    }
+    G->count = count; G->M = A0->M; G->K = A0->K; G->BR = A0->BR; G->BC = A0->BC; G->dtype = A0->dtype;
+    G->nbr = A0->nbr; G->nbc = A0->nbc; G->device = dev;
+    G->uniform_kr = A0->gemv.uniform_kr; G->uniform_kc = A0->gemv.uniform_kc; G->vec = A0->gemv.vec;
+    for (int32_t i = 0; i < count; ++i) {
+        const grim_bcr_matrix *A = mats[i];
+        if (A->M != G->M || A->K != G->K || A->BR != G->BR || A->BC != G->BC || A->dtype != G->dtype) { delete G; return GRIM_ERR_SHAPE; }
+        if (!A->on_device || A->device != dev) { delete G; return GRIM_ERR_DEVICE; }
+        if (!A->gemv.present) { delete G; return GRIM_ERR_UNSUPPORTED; }
+        if (A->gemv.uniform_kr != G->uniform_kr || A->gemv.uniform_kc != G->uniform_kc) G->uniform_kr = G->uniform_kc = -1;
+        G->vec = std::min(G->vec, A->gemv.vec);
+        table[i] = desc_of(A);
+    }
+    if (hipMalloc(reinterpret_cast<void **>(&G->d_table), sizeof(GemvDesc) * count) != hipSuccess) { (void)hipGetLastError(); delete G; return GRIM_ERR_ALLOC; }
+    if (hipMemcpy(G->d_table, table.data(), sizeof(GemvDesc) * count, hipMemcpyHostToDevice) != hipSuccess) {
+        (void)hipGetLastError(); (void)hipFree(G->d_table); delete G; return GRIM_ERR_DEVICE;
+    }
+    *out = G;
+    return GRIM_OK;
+}
+
+grim_status grim_bcr_spmv_batched(const grim_bcr_group *G, const void *x_dev, int64_t x_stride, int32_t batch, int64_t ldx,
+                                  float *y_dev, int64_t y_stride, int64_t ldy, void *hip_stream) {
+    if (!G || !x_dev || !y_dev) return GRIM_ERR_NULL;
+    if (batch < 1 || batch > 8 || ldx < batch || ldy < batch || x_stride < 0 || y_stride < 0) return GRIM_ERR_SHAPE;
+    if (G->K * batch * dtype_size(G->dtype) > kGemvMaxXBytes) return GRIM_ERR_UNSUPPORTED;
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev != G->device) return GRIM_ERR_DEVICE;
+    GemvDesc none{nullptr, nullptr, nullptr, nullptr};
+    return launch_spmv(G->d_table, none, G->count, G->M, G->K, G->BR, G->BC, G->dtype, G->uniform_kr, G->uniform_kc, G->vec,
+                       x_dev, x_stride, batch, ldx, y_dev, y_stride, ldy, static_cast<hipStream_t>(hip_stream));
+}
+
+void grim_bcr_group_free(grim_bcr_group *G) {
+    if (!G) return;
+    if (G->d_table) (void)hipFree(G->d_table);
+    delete G;
+}
+
+void grim_bcr_free(grim_bcr_matrix *A) {
+    if (!A) return;
+    if (A->on_device && A->dev.strip_order) (void)hipFree(A->dev.strip_order);   // base of the slab
+    delete A;
+}
+
+const char *grim_status_str(grim_status s) {
+    switch (s) {
+        case GRIM_OK: return "GRIM_OK";
+        case GRIM_ERR_NULL: return "GRIM_ERR_NULL: required pointer is NULL";
+        case GRIM_ERR_SHAPE: return "GRIM_ERR_SHAPE: invalid shape, block size, leading dimension or batch";
+        case GRIM_ERR_INDEX: return "GRIM_ERR_INDEX: malformed kept-row / kept-column index sets";
+        case GRIM_ERR_DTYPE: return "GRIM_ERR_DTYPE: unknown element type";
+        case GRIM_ERR_ALLOC: return "GRIM_ERR_ALLOC: allocation failed";
+        case GRIM_ERR_DEVICE: return "GRIM_ERR_DEVICE: HIP failure, no GPU, wrong current device, or host-only matrix";
+        case GRIM_ERR_UNSUPPORTED: return "GRIM_ERR_UNSUPPORTED: no kernel covers this request";
+    }
+    return "unknown grim_status";
+}
+
+}  // extern "C"

@@ -1,0 +1,312 @@
+"""GPU parity: the HIP path, called through the C ABI, against the fp64 CPU oracle on the
+same seeded inputs.  Structures must match bit for bit; values within 1e-5 (fp32) or
+2e-3 (fp16 / bf16 inputs, fp32 accumulation), measured against the sum of |terms| and
+against max|Y|."""
+import numpy as np
+import pytest
+
+import bcr_inputs as gen
+from oracle import pack_ref
+from helpers import (assert_close, oracle_product, pack_workload, run_spmm, run_spmv, to_device, torch_dev)
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def g():
+    import paper_2108_11033_amd as lib
+    lib.load_library()
+    return lib
+
+
+def _check_structure(A, wl):
+    ref = pack_ref.pack(wl.W, wl.mask)
+    got = A.arrays()
+    for k in ref:
+        assert got[k].tobytes() == ref[k].tobytes(), k
+    assert A.unpack().tobytes() == pack_ref.unpack(ref, wl.M, wl.K, wl.mask.BR, wl.mask.BC, wl.W.dtype).tobytes()
+
+
+def _spmm_case(g, wl, what, structure=True, **tune):
+    A = pack_workload(g, wl.W, wl.dtype, wl.mask)
+    if structure:
+        _check_structure(A, wl)
+    Y = run_spmm(g, A, wl.X, wl.dtype, wl.M, wl.N, **tune)
+    Yref, S = oracle_product(wl.W, wl.X, wl.dtype, wl.mask)
+    return assert_close(Y, Yref, S, wl.dtype, what)
+
+
+# ------------------------------------------------------------------ the named configurations
+def test_c1_fp32_single_spmm(g):
+    _spmm_case(g, gen.c1_single_fp32(), "c1")
+
+
+@pytest.mark.parametrize("N", [200, 3136])
+def test_c2_vgg_conv_fp16(g, N):
+    _spmm_case(g, gen.c2_vgg_conv(N), f"c2 N={N}")
+
+
+@pytest.mark.parametrize("batch", [1, 8])
+def test_c3_lstm_gates_spmv(g, batch):
+    wl = gen.c3_lstm_gates(batch)
+    A = pack_workload(g, wl.W, wl.dtype, wl.mask)
+    _check_structure(A, wl)
+    y = run_spmv(g, A, wl.X, wl.dtype, wl.M, batch)
+    yref, S = oracle_product(wl.W, wl.X, wl.dtype, wl.mask)
+    assert_close(y, yref, S, wl.dtype, f"c3 batch={batch}")
+    # spmm with N <= 8 reaches the same kernel and the same bits
+    y2 = run_spmm(g, A, wl.X, wl.dtype, wl.M, batch)
+    assert y2.tobytes() == y.tobytes()
+
+
+@pytest.mark.parametrize("layer", range(13))
+def test_c4_vgg16_layers_fp16(g, layer):
+    # the large-N layers are cut to a few tiles plus a ragged tail; N = 784 and 196 run whole
+    N0 = gen.VGG16_LAYERS[layer][2]
+    N = N0 if N0 <= 784 else 328
+    _spmm_case(g, gen.c4_vgg16_layer(layer, N), f"c4 L{layer + 1} N={N}", structure=layer < 3)
+
+
+def test_c5_nonuniform_bf16_small_n(g):
+    _spmm_case(g, gen.c5_nonuniform(N=300), "c5 N=300")
+
+
+def test_c5_full_size_sampled(g):
+    # full configuration in the launch shape the benchmark times; the oracle computes a
+    # sample of rows (all strips touched) x a sample of columns (first, last and ragged tiles)
+    wl = gen.c5_nonuniform()
+    A = pack_workload(g, wl.W, wl.dtype, wl.mask)
+    Y = run_spmm(g, A, wl.X, wl.dtype, wl.M, wl.N)
+    rng = np.random.default_rng(55)
+    rows = np.sort(rng.choice(wl.M, 48, replace=False))
+    cols = np.unique(np.concatenate([np.arange(0, 70), np.arange(wl.N - 70, wl.N),
+                                     rng.choice(wl.N, 200, replace=False)]))
+    Yref, S = oracle_product(wl.W, wl.X, wl.dtype, wl.mask, rows=rows, cols=cols)
+    assert_close(Y[np.ix_(rows, cols)], Yref, S, wl.dtype, "c5 full sampled")
+    assert np.isfinite(Y).all()
+
+
+# ------------------------------------------------------------------ launch shapes and kernels
+@pytest.mark.parametrize("dtype,BR", [(gen.F16, 16), (gen.BF16, 16), (gen.F16, 32), (gen.BF16, 32)])
+@pytest.mark.parametrize("tile_n,strips", [(32, 4), (32, 16), (64, 4), (64, 8), (64, 16), (128, 4), (128, 8)])
+def test_mma_kernel_all_tilings(g, dtype, BR, tile_n, strips):
+    M, K, N = 6 * BR, 416, 333                     # 6 strips (ragged group), 13 column blocks, ragged N
+    mask = gen.random_mask(M, K, BR, 32, (0, 4, 8, 16), (0, 4, 8, 12, 32), seed=70 + BR)
+    W = gen.normal_weights(M, K, dtype, seed=71)
+    X = gen.normal_activations(K, N, dtype, seed=72, relu=True)
+    A = pack_workload(g, W, dtype, mask)
+    Y = run_spmm(g, A, X, dtype, M, N, tile_n=tile_n, strips_per_wg=strips, kernel=2)
+    Yref, S = oracle_product(W, X, dtype, mask)
+    assert_close(Y, Yref, S, dtype, f"mma {dtype} BR={BR} tn={tile_n} g={strips}")
+
+
+@pytest.mark.parametrize("dtype", [gen.F32, gen.F16, gen.BF16])
+@pytest.mark.parametrize("BR,BC", [(1, 1), (4, 16), (8, 8), (16, 16), (32, 32), (64, 48), (16, 27)])
+def test_fma_kernel_block_shapes(g, dtype, BR, BC):
+    M, K, N = BR * 3, BC * 5, 130
+    mask = gen.random_mask(M, K, BR, BC, tuple(sorted({0, 1, max(1, BR // 2), BR})),
+                           tuple(sorted({0, 1, max(1, BC // 4), BC})), seed=80 + BR)
+    W = gen.normal_weights(M, K, dtype, seed=81)
+    X = gen.normal_activations(K, N, dtype, seed=82)
+    A = pack_workload(g, W, dtype, mask)
+    Y = run_spmm(g, A, X, dtype, M, N, kernel=1)
+    Yref, S = oracle_product(W, X, dtype, mask)
+    assert_close(Y, Yref, S, dtype, f"fma {dtype} {BR}x{BC}")
+
+
+def test_unaligned_leading_dimensions_and_tails(g):
+    for dtype, BR in ((gen.F16, 16), (gen.BF16, 32)):
+        M, K = 4 * BR, 256
+        mask = gen.random_mask(M, K, BR, 32, (4, 8), (8, 12), seed=90)
+        W = gen.normal_weights(M, K, dtype, seed=91)
+        for N, ldx, ldy in ((196, 196, 196), (67, 71, 69), (1, 1, 1), (9, 12, 9), (64, 64, 66), (130, 136, 132)):
+            X = gen.normal_activations(K, N, dtype, seed=92)
+            A = pack_workload(g, W, dtype, mask)
+            Y = run_spmm(g, A, X, dtype, M, N, ldx=ldx, ldy=ldy, kernel=2)
+            Yref, S = oracle_product(W, X, dtype, mask)
+            assert_close(Y, Yref, S, dtype, f"{dtype} N={N} ldx={ldx} ldy={ldy}")
+
+
+# ------------------------------------------------------------------ degenerate cases
+@pytest.mark.parametrize("dtype", [gen.F32, gen.F16])
+def test_degenerate_masks(g, dtype):
+    M, K, N, BR, BC = 64, 128, 70, 16, 32
+    W = gen.normal_weights(M, K, dtype, seed=100)
+    X = gen.normal_activations(K, N, dtype, seed=101)
+    cases = {
+        "nothing kept": gen.random_mask(M, K, BR, BC, 0, 0, seed=1),
+        "rows but no columns": gen.random_mask(M, K, BR, BC, 4, 0, seed=2),
+        "columns but no rows": gen.random_mask(M, K, BR, BC, 0, 8, seed=3),
+        "everything kept": gen.full_mask(M, K, BR, BC),
+        "one row one column": gen.random_mask(M, K, BR, BC, 1, 1, seed=4),
+        "whole-matrix block": gen.random_mask(M, K, M, K, 9, 40, seed=5),
+    }
+    for name, mask in cases.items():
+        A = pack_workload(g, W, dtype, mask)
+        Y = run_spmm(g, A, X, dtype, M, N)
+        Yref, S = oracle_product(W, X, dtype, mask)
+        assert_close(Y, Yref, S, dtype, name)
+        for batch in (1, 3):
+            if mask.BR <= 64:
+                y = run_spmv(g, A, X[:, :batch].copy(), dtype, M, batch)
+                assert_close(y, Yref[:, :batch], S[:, :batch], dtype, name + " spmv")
+
+
+def test_integer_data_is_bit_exact_and_reproducible(g):
+    # small integers: every partial sum is exact in fp32, so GPU == oracle bit for bit
+    for dtype, BR, kern in ((gen.F32, 16, 0), (gen.F16, 16, 2), (gen.BF16, 32, 2), (gen.F16, 32, 1)):
+        M, K, N = 4 * BR, 320, 150
+        mask = gen.random_mask(M, K, BR, 32, (2, 4, 8), (4, 8, 16), seed=110)
+        W = gen.small_int_values((M, K), dtype, seed=111)
+        X = gen.small_int_values((K, N), dtype, seed=112)
+        A = pack_workload(g, W, dtype, mask)
+        Y1 = run_spmm(g, A, X, dtype, M, N, kernel=kern)
+        Y2 = run_spmm(g, A, X, dtype, M, N, kernel=kern)
+        Yref, _ = oracle_product(W, X, dtype, mask)
+        assert np.array_equal(Y1.astype(np.float64), Yref)
+        assert Y1.tobytes() == Y2.tobytes()
+        y = run_spmv(g, A, X[:, :5].copy(), dtype, M, 5)
+        assert np.array_equal(y.astype(np.float64), Yref[:, :5])
+
+
+def test_run_to_run_bit_reproducible_random_data(g):
+    wl = gen.c2_vgg_conv(N=640)
+    A = pack_workload(g, wl.W, wl.dtype, wl.mask)
+    Ys = [run_spmm(g, A, wl.X, wl.dtype, wl.M, wl.N) for _ in range(3)]
+    assert Ys[0].tobytes() == Ys[1].tobytes() == Ys[2].tobytes()
+    wl = gen.c3_lstm_gates(8)
+    A = pack_workload(g, wl.W, wl.dtype, wl.mask)
+    ys = [run_spmv(g, A, wl.X, wl.dtype, wl.M, 8) for _ in range(3)]
+    assert ys[0].tobytes() == ys[1].tobytes() == ys[2].tobytes()
+
+
+def test_fp16_subnormal_weights_are_not_flushed(g):
+    # N(0, 0.02) puts ~0.24% of the weights below the smallest normal fp16; here all of them
+    M, K, N, BR, BC = 32, 128, 64, 16, 32
+    rng = np.random.default_rng(120)
+    W = (rng.integers(1, 1000, size=(M, K)) * 2.0 ** -24 * rng.choice([-1, 1], size=(M, K))).astype(np.float16)
+    X = (rng.integers(1, 64, size=(K, N)) * 16.0).astype(np.float16)
+    mask = gen.random_mask(M, K, BR, BC, 8, 8, seed=121)
+    A = pack_workload(g, W, gen.F16, mask)
+    for kern in (1, 2):
+        Y = run_spmm(g, A, X, gen.F16, M, N, kernel=kern)
+        Yref, S = oracle_product(W, X, gen.F16, mask)
+        assert np.abs(Yref).max() > 0
+        assert_close(Y, Yref, S, gen.F16, f"subnormal kernel={kern}")
+    y = run_spmv(g, A, X[:, :2].copy(), gen.F16, M, 2)
+    assert_close(y, Yref[:, :2], S[:, :2], gen.F16, "subnormal spmv")
+
+
+def test_no_reorder_option_gives_same_product(g):
+    wl = gen.c5_nonuniform(N=96)
+    A0 = pack_workload(g, wl.W, wl.dtype, wl.mask, no_reorder=True)
+    A1 = pack_workload(g, wl.W, wl.dtype, wl.mask)
+    assert A0.arrays()["strip_order"].tolist() == list(range(wl.M // 32))
+    ref = pack_ref.pack(wl.W, wl.mask, reorder=False)
+    assert all(A0.arrays()[k].tobytes() == ref[k].tobytes() for k in ref)
+    Y0 = run_spmm(g, A0, wl.X, wl.dtype, wl.M, wl.N)
+    Y1 = run_spmm(g, A1, wl.X, wl.dtype, wl.M, wl.N)
+    assert Y0.tobytes() == Y1.tobytes()          # per-row arithmetic does not depend on strip order
+
+
+# ------------------------------------------------------------------ SpMV
+@pytest.mark.parametrize("dtype", [gen.F32, gen.F16, gen.BF16])
+@pytest.mark.parametrize("batch", [1, 2, 3, 4, 5, 6, 7, 8])
+def test_spmv_nonuniform_all_batches(g, dtype, batch):
+    M, K, BR, BC = 160, 1120, 32, 32                  # 35 column blocks: a full pass of 32 and a ragged one
+    mask = gen.random_mask(M, K, BR, BC, (0, 1, 8, 13, 32), (0, 3, 12, 16, 32), seed=130)
+    W = gen.normal_weights(M, K, dtype, seed=131)
+    x = gen.normal_activations(K, batch, dtype, seed=132)
+    A = pack_workload(g, W, dtype, mask)
+    yref, S = oracle_product(W, x, dtype, mask)
+    y = run_spmv(g, A, x, dtype, M, batch)
+    assert_close(y, yref, S, dtype, f"spmv {dtype} b={batch}")
+    y2 = run_spmv(g, A, x, dtype, M, batch, ldx=batch + 3, ldy=batch + 1)
+    assert y2.tobytes() == y.tobytes()
+
+
+@pytest.mark.parametrize("BR,BC", [(8, 16), (16, 8), (32, 24), (4, 32)])
+def test_spmv_small_blocks(g, BR, BC):
+    dtype = gen.F16
+    M, K = BR * 10, BC * 20
+    mask = gen.random_mask(M, K, BR, BC, (1, BR // 2, BR), (1, BC // 2, BC), seed=140)
+    W = gen.normal_weights(M, K, dtype, seed=141)
+    x = gen.normal_activations(K, 4, dtype, seed=142)
+    A = pack_workload(g, W, dtype, mask)
+    yref, S = oracle_product(W, x, dtype, mask)
+    assert_close(run_spmv(g, A, x, dtype, M, 4), yref, S, dtype, f"spmv {BR}x{BC}")
+
+
+def test_spmv_falls_back_when_blocks_exceed_masks(g):
+    dtype = gen.F16
+    M, K = 128, 256
+    mask = gen.random_mask(M, K, 64, 64, (8, 16), (8, 32), seed=150)
+    W = gen.normal_weights(M, K, dtype, seed=151)
+    x = gen.normal_activations(K, 2, dtype, seed=152)
+    A = pack_workload(g, W, dtype, mask)
+    yref, S = oracle_product(W, x, dtype, mask)
+    assert_close(run_spmv(g, A, x, dtype, M, 2), yref, S, dtype, "spmv 64x64 blocks")
+
+
+@pytest.mark.parametrize("batch", [1, 8])
+def test_spmv_batched_matches_single_calls(g, batch):
+    torch, dev = torch_dev()
+    dtype = gen.F16
+    M, K, BR, BC, count = 256, 512, 32, 32, 5
+    mats, xs, refs = [], [], []
+    for i in range(count):
+        mask = gen.random_mask(M, K, BR, BC, 8, 12, seed=160 + i)
+        W = gen.normal_weights(M, K, dtype, seed=170 + i)
+        x = gen.normal_activations(K, batch, dtype, seed=180 + i)
+        mats.append(pack_workload(g, W, dtype, mask))
+        xs.append(x)
+        refs.append(oracle_product(W, x, dtype, mask))
+    from paper_2108_11033_amd import binding
+    G = binding.group(mats)
+    xd = to_device(np.stack(xs), dtype)                       # [count, K, batch]
+    yd = torch.full((count, M, batch), float("nan"), dtype=torch.float32, device=dev)
+    g.spmv_batched(G, xd, K * batch, batch, batch, yd, M * batch, batch, torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    y = yd.cpu().numpy()
+    for i in range(count):
+        assert_close(y[i], refs[i][0], refs[i][1], dtype, f"batched {i}")
+        yi = run_spmv(g, mats[i], xs[i], dtype, M, batch)
+        assert yi.tobytes() == y[i].tobytes()
+
+
+# ------------------------------------------------------------------ errors leave Y untouched
+def test_device_call_errors(g):
+    torch, dev = torch_dev()
+    wl = gen.c2_vgg_conv(N=64)
+    A = pack_workload(g, wl.W, wl.dtype, wl.mask)
+    Xd = to_device(wl.X, wl.dtype)
+    Yd = torch.full((wl.M, 64), 7.0, dtype=torch.float32, device=dev)
+    from paper_2108_11033_amd import GrimError
+    for kwargs, name in (
+        (dict(N=0, ldx=64, ldy=64), "GRIM_ERR_SHAPE"),
+        (dict(N=64, ldx=63, ldy=64), "GRIM_ERR_SHAPE"),
+        (dict(N=64, ldx=64, ldy=10), "GRIM_ERR_SHAPE"),
+    ):
+        with pytest.raises(GrimError) as e:
+            g.spmm(A, Xd, kwargs["N"], kwargs["ldx"], Yd, kwargs["ldy"])
+        assert e.value.name == name
+    with pytest.raises(GrimError) as e:
+        g.spmm(A, None, 64, 64, Yd, 64)
+    assert e.value.name == "GRIM_ERR_NULL"
+    with pytest.raises(GrimError) as e:
+        g.spmv(A, Xd, 9, 64, Yd, 64)
+    assert e.value.name == "GRIM_ERR_SHAPE"
+    with pytest.raises(GrimError) as e:
+        g.spmm(A, Xd, 64, 64, Yd, 64, tile_n=48)
+    assert e.value.name == "GRIM_ERR_UNSUPPORTED"
+    H = pack_workload(g, wl.W, wl.dtype, wl.mask, host_only=True)
+    with pytest.raises(GrimError) as e:
+        g.spmm(H, Xd, 64, 64, Yd, 64)
+    assert e.value.name == "GRIM_ERR_DEVICE"
+    big = gen.random_mask(256, 256, 128, 32, 8, 8, seed=1)
+    B = pack_workload(g, gen.normal_weights(256, 256, gen.F16, 1), gen.F16, big)
+    with pytest.raises(GrimError) as e:
+        g.spmm(B, Xd, 64, 64, Yd, 64)
+    assert e.value.name == "GRIM_ERR_UNSUPPORTED"
+    torch.cuda.synchronize()
+    assert (Yd == 7.0).all()
