@@ -135,9 +135,10 @@ grim_status grim_bcr_spmm(const grim_bcr_matrix *A, const void *X_dev, int64_t N
 /* grim_bcr_spmm_tuned -- grim_bcr_spmm with explicit launch parameters (the paper tunes
  * tile sizes per kernel, Section 4.5; here a handful of choices replaces the search):
  *   tile_n         columns of X per workgroup (32, 64 or 128; 0 = choose)
- *   strips_per_wg  row strips per workgroup (multiple of 4 or 0 = choose)
+ *   strips_per_wg  row strips per workgroup (4, 8 or 16; 0 = choose)
  *   kernel         0 = choose, 1 = force the portable FMA kernel, 2 = force the matrix-core kernel
- * Invalid combinations return GRIM_ERR_UNSUPPORTED. */
+ * Combinations that are not compiled, or whose staging buffers do not fit the 160 KB of LDS
+ * for this matrix, return GRIM_ERR_UNSUPPORTED. */
 grim_status grim_bcr_spmm_tuned(const grim_bcr_matrix *A, const void *X_dev, int64_t N, int64_t ldx,
                                 float *Y_dev, int64_t ldy, int32_t tile_n, int32_t strips_per_wg,
                                 int32_t kernel, void *hip_stream);

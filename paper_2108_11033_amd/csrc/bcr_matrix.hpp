@@ -9,18 +9,23 @@
 
 namespace grim {
 
-constexpr int kMmaMaxChunkRows = 128;   // rows of X staged in LDS per step by the matrix-core kernel
+constexpr int kMmaMaxChunkRows = 256;   // rows of X staged in LDS per step by the matrix-core kernel
 constexpr int kGemvMaxXBytes = 65536;   // bytes of x (K * batch elements) the SpMV kernel keeps in LDS
 
 inline int dtype_size(int dt) { return dt == GRIM_F32 ? 4 : 2; }
 
 // Row-expanded layout for the matrix-core SpMM kernel (fp16 / bf16, BR = 16 or 32).
-// For every stored strip the kept columns of its blocks are concatenated into one
-// gather list of X rows, cut into chunks of `chunk_rows` consecutive rows of X and
-// padded per chunk to a multiple of `ks` (the k extent of one MFMA).  The weights
-// of a step are stored as the MFMA operand fragment itself (64 lanes x 8 values),
-// with pruned rows of a block as zeros, so that output rows sit at their strip
-// positions and no scatter is needed.
+// K is cut into chunks of `chunk_rows` consecutive rows of X.  For every (chunk, stored
+// strip) the kept columns of the strip's blocks inside the chunk are concatenated into a
+// gather list of staged X rows, padded to a multiple of `ks` (the k extent of one MFMA);
+// every `ks` entries form a step.  A step is stored as a record of
+//   afrag: the MFMA weight operand itself (64 lanes x 8 values), pruned rows of a block
+//          as zeros, so output rows sit at their strip positions and no scatter is needed;
+//   lidx:  per lane, the two staged rows it names in the two LDS transpose reads of the
+//          step (low / high 16 bits); the row `chunk_rows` is an all-zero row (padding).
+// A record is 1280 contiguous bytes.  Records are stored chunk-major, strips in stored order
+// inside a chunk, so the records a workgroup (a group of consecutive stored strips) needs for
+// one chunk are one contiguous byte range.
 struct MmaLayout {
     bool present = false;
     int32_t ks = 0;            // 32 for BR = 16 (16x16x32), 16 for BR = 32 (32x32x16)
@@ -28,12 +33,11 @@ struct MmaLayout {
     int32_t chunk_rows = 0;    // chunk_blocks * BC
     int32_t nchunks = 0;
     int64_t nsteps = 0;
-    std::vector<int32_t> kstep_ptr;   // [nbr * (nchunks + 1)] first step of (strip t, chunk j)
-    std::vector<uint16_t> kidx;       // [nsteps * ks] row of the chunk's LDS tile; chunk_rows = zero row
-    std::vector<uint16_t> afrag;      // [nsteps * 512] operand fragments
-    int32_t *d_kstep_ptr = nullptr;
-    uint16_t *d_kidx = nullptr;
-    uint16_t *d_afrag = nullptr;
+    int32_t amax[4] = {0, 0, 0, 0};   // most steps any (group, chunk) holds, for groups of 4, 8, 16, 32 strips
+    std::vector<int32_t> cptr;        // [nchunks * (nbr + 1)] first step of (chunk, stored strip); last = end of chunk
+    std::vector<uint16_t> recs;       // [nsteps * 640]: per step afrag (512 values) then lidx (64 x 32 bit)
+    int32_t *d_cptr = nullptr;
+    uint16_t *d_recs = nullptr;
     int64_t bytes = 0;
 };
 

@@ -37,34 +37,29 @@ grim_status validate_sets(int64_t nb, int32_t B, const int32_t *ptr, const uint1
 }
 
 // ---- derived layout: matrix-core SpMM ---------------------------------------------------
-void build_mma_layout(grim_bcr_matrix *A, int32_t chunk_rows_opt) {
+
+bool build_mma_layout_for(grim_bcr_matrix *A, int32_t chunk_blocks) {
     MmaLayout &L = A->mma;
-    L.present = false;
-    if (A->dtype == GRIM_F32) return;
-    if (A->BR != 16 && A->BR != 32) return;
-    if (A->BC > kMmaMaxChunkRows) return;
-    int32_t want = chunk_rows_opt > 0 ? std::min<int32_t>(chunk_rows_opt, kMmaMaxChunkRows) : kMmaMaxChunkRows;
-    L.chunk_blocks = std::max<int32_t>(1, want / A->BC);
+    L.chunk_blocks = chunk_blocks;
     L.chunk_rows = L.chunk_blocks * A->BC;
     L.nchunks = (int32_t)((A->nbc + L.chunk_blocks - 1) / L.chunk_blocks);
     L.ks = A->BR == 16 ? 32 : 16;
-    const int32_t ks = L.ks, BR = A->BR, esz = 2;
+    const int32_t ks = L.ks, BR = A->BR;
     const int lanes_per_kgroup = BR == 16 ? 16 : 32;   // lanes sharing one group of 8 k slots
-    L.kstep_ptr.assign((size_t)A->nbr * (L.nchunks + 1), 0);
-    L.kidx.clear();
-    L.afrag.clear();
+    L.cptr.assign((size_t)L.nchunks * (A->nbr + 1), 0);
+    L.recs.clear();
     struct Slot { int64_t t; int32_t j; };   // stored block, position of the kept column in it
     std::vector<Slot> slots;
+    std::vector<uint16_t> rows;
     std::vector<int32_t> comp(BR);           // local row -> compact row or -1
     int64_t step = 0;
     const uint16_t *w = reinterpret_cast<const uint16_t *>(A->weights.data());
-    (void)esz;
-    for (int64_t st = 0; st < A->nbr; ++st) {
-        for (int32_t ch = 0; ch < L.nchunks; ++ch) {
-            L.kstep_ptr[st * (L.nchunks + 1) + ch] = (int32_t)step;
+    for (int32_t ch = 0; ch < L.nchunks; ++ch) {
+        const int64_t c0 = (int64_t)ch * L.chunk_blocks, c1 = std::min<int64_t>(A->nbc, c0 + L.chunk_blocks);
+        for (int64_t st = 0; st < A->nbr; ++st) {
+            L.cptr[(size_t)ch * (A->nbr + 1) + st] = (int32_t)step;
             slots.clear();
-            std::vector<uint16_t> rows;
-            int64_t c0 = (int64_t)ch * L.chunk_blocks, c1 = std::min<int64_t>(A->nbc, c0 + L.chunk_blocks);
+            rows.clear();
             for (int64_t c = c0; c < c1; ++c) {
                 int64_t t = st * A->nbc + c;
                 if (A->row_ptr[t + 1] == A->row_ptr[t]) continue;   // no kept rows: nothing to multiply
@@ -73,38 +68,77 @@ void build_mma_layout(grim_bcr_matrix *A, int32_t chunk_rows_opt) {
                     rows.push_back((uint16_t)((c - c0) * A->BC + A->col_idx[q]));
                 }
             }
-            size_t nsl = slots.size();
-            size_t padded = (nsl + ks - 1) / ks * ks;
+            const size_t nsl = slots.size();
+            const size_t padded = (nsl + ks - 1) / ks * ks;
             for (size_t base = 0; base < padded; base += ks) {
-                size_t k0 = L.kidx.size(), a0 = L.afrag.size();
-                L.kidx.resize(k0 + ks);
-                L.afrag.resize(a0 + 512, 0);
-                for (int32_t e = 0; e < ks; ++e)
-                    L.kidx[k0 + e] = base + e < nsl ? rows[base + e] : (uint16_t)L.chunk_rows;
+                const size_t a0 = L.recs.size(), l0 = a0 + 512;
+                L.recs.resize(a0 + 640, 0);
+                auto row_of = [&](int32_t e) -> uint32_t { return base + e < nsl ? rows[base + e] : (uint32_t)L.chunk_rows; };
+                for (int32_t lane = 0; lane < 64; ++lane) {
+                    // the lane names row slot (8 * kgroup + (lane % 16) / 4) in the first transpose
+                    // read of the step and that slot + 4 in the second
+                    const int32_t kgroup = BR == 16 ? lane / 16 : lane / 32;
+                    const int32_t e0 = 8 * kgroup + (lane % 16) / 4;
+                    L.recs[l0 + 2 * lane] = (uint16_t)row_of(e0);
+                    L.recs[l0 + 2 * lane + 1] = (uint16_t)row_of(e0 + 4);
+                }
                 int64_t cur_t = -1;
                 for (int32_t e = 0; e < ks; ++e) {
                     if (base + e >= nsl) break;
-                    const Slot &s = slots[base + e];
-                    if (s.t != cur_t) {
-                        cur_t = s.t;
+                    const Slot &sl = slots[base + e];
+                    if (sl.t != cur_t) {
+                        cur_t = sl.t;
                         std::fill(comp.begin(), comp.end(), -1);
-                        for (int32_t q = A->row_ptr[s.t]; q < A->row_ptr[s.t + 1]; ++q)
-                            comp[A->row_idx[q]] = q - A->row_ptr[s.t];
+                        for (int32_t q = A->row_ptr[sl.t]; q < A->row_ptr[sl.t + 1]; ++q)
+                            comp[A->row_idx[q]] = q - A->row_ptr[sl.t];
                     }
-                    int32_t kc = A->col_ptr[s.t + 1] - A->col_ptr[s.t];
-                    int32_t kgroup = e / 8, i = e % 8;
+                    const int32_t kc = A->col_ptr[sl.t + 1] - A->col_ptr[sl.t];
+                    const int32_t kgroup = e / 8, i = e % 8;
                     for (int32_t m = 0; m < BR; ++m) {
                         if (comp[m] < 0) continue;
-                        int32_t lane = kgroup * lanes_per_kgroup + m;
-                        L.afrag[a0 + (size_t)lane * 8 + i] = w[A->blk_ptr[s.t] + (int64_t)comp[m] * kc + s.j];
+                        const int32_t lane = kgroup * lanes_per_kgroup + m;
+                        L.recs[a0 + (size_t)lane * 8 + i] = w[A->blk_ptr[sl.t] + (int64_t)comp[m] * kc + sl.j];
                     }
                 }
                 ++step;
             }
         }
-        L.kstep_ptr[st * (L.nchunks + 1) + L.nchunks] = (int32_t)step;
+        L.cptr[(size_t)ch * (A->nbr + 1) + A->nbr] = (int32_t)step;
     }
     L.nsteps = step;
+    for (int gi = 0; gi < 4; ++gi) {
+        const int64_t Gs = 4 << gi;
+        int32_t amax = 0;
+        for (int32_t ch = 0; ch < L.nchunks; ++ch) {
+            const int32_t *cp = &L.cptr[(size_t)ch * (A->nbr + 1)];
+            for (int64_t t0 = 0; t0 < A->nbr; t0 += Gs)
+                amax = std::max(amax, cp[std::min<int64_t>(A->nbr, t0 + Gs)] - cp[t0]);
+        }
+        L.amax[gi] = amax;
+    }
+    // fits the default launch (64 columns per workgroup, groups of 4 strips)?  The producers move
+    // at most 32 KB of X rows and 32 KB of records per chunk.
+    return L.chunk_rows <= 256 && (int64_t)L.amax[0] * 1280 <= 32 * 1024;
+}
+
+void build_mma_layout(grim_bcr_matrix *A, int32_t chunk_rows_opt) {
+    MmaLayout &L = A->mma;
+    L.present = false;
+    if (A->dtype == GRIM_F32) return;
+    if (A->BR != 16 && A->BR != 32) return;
+    if (A->BC > kMmaMaxChunkRows) return;
+    const int32_t want = chunk_rows_opt > 0 ? std::min<int32_t>(chunk_rows_opt, kMmaMaxChunkRows) : kMmaMaxChunkRows;
+    // largest chunk whose weight records still leave room in LDS; denser matrices get smaller chunks
+    int32_t blocks = std::max<int32_t>(1, want / A->BC);
+    bool fits = build_mma_layout_for(A, blocks);
+    while (!fits && blocks > 1) {
+        blocks = (blocks + 1) / 2;
+        fits = build_mma_layout_for(A, blocks);
+    }
+    if (!fits) {   // even one column block per chunk overflows LDS: leave this matrix to the FMA kernel
+        L.cptr.clear(); L.recs.clear();
+        return;
+    }
     L.present = true;
 }
 
@@ -154,11 +188,10 @@ grim_status upload(grim_bcr_matrix *A) {
     size_t o_w = s.add(A->weights.size() + 64);   // slack: vector loads may overrun a row's end
     size_t o_rm = s.add(bytes(A->rowmask64));
     size_t canon_end = s.total;
-    size_t o_kp = 0, o_ki = 0, o_af = 0, o_gm = 0, o_go = 0;
+    size_t o_kp = 0, o_af = 0, o_gm = 0, o_go = 0;
     if (A->mma.present) {
-        o_kp = s.add(bytes(A->mma.kstep_ptr));
-        o_ki = s.add(bytes(A->mma.kidx) + 64);
-        o_af = s.add(bytes(A->mma.afrag) + 1024);
+        o_kp = s.add(bytes(A->mma.cptr));
+        o_af = s.add(bytes(A->mma.recs) + 2048);   // slack: records are fetched in 1 KB slots
     }
     size_t mma_end = s.total;
     if (A->gemv.present) {
@@ -176,8 +209,7 @@ grim_status upload(grim_bcr_matrix *A) {
               put(o_ci, A->col_idx.data(), bytes(A->col_idx)) && put(o_bp, A->blk_ptr.data(), bytes(A->blk_ptr)) &&
               put(o_w, A->weights.data(), A->weights.size()) && put(o_rm, A->rowmask64.data(), bytes(A->rowmask64));
     if (ok && A->mma.present)
-        ok = put(o_kp, A->mma.kstep_ptr.data(), bytes(A->mma.kstep_ptr)) && put(o_ki, A->mma.kidx.data(), bytes(A->mma.kidx)) &&
-             put(o_af, A->mma.afrag.data(), bytes(A->mma.afrag));
+        ok = put(o_kp, A->mma.cptr.data(), bytes(A->mma.cptr)) && put(o_af, A->mma.recs.data(), bytes(A->mma.recs));
     if (ok && A->gemv.present)
         ok = put(o_gm, A->gemv.masks.data(), bytes(A->gemv.masks)) && put(o_go, A->gemv.woff.data(), bytes(A->gemv.woff));
     if (!ok) { (void)hipGetLastError(); (void)hipFree(base); return GRIM_ERR_DEVICE; }
@@ -191,9 +223,8 @@ grim_status upload(grim_bcr_matrix *A) {
     A->dev.rowmask64 = reinterpret_cast<uint64_t *>(base + o_rm);
     A->dev.bytes = (int64_t)canon_end;
     if (A->mma.present) {
-        A->mma.d_kstep_ptr = reinterpret_cast<int32_t *>(base + o_kp);
-        A->mma.d_kidx = reinterpret_cast<uint16_t *>(base + o_ki);
-        A->mma.d_afrag = reinterpret_cast<uint16_t *>(base + o_af);
+        A->mma.d_cptr = reinterpret_cast<int32_t *>(base + o_kp);
+        A->mma.d_recs = reinterpret_cast<uint16_t *>(base + o_af);
         A->mma.bytes = (int64_t)(mma_end - canon_end);
     }
     if (A->gemv.present) {

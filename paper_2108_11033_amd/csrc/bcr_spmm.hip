@@ -7,13 +7,16 @@
 //    here a consequence of treating the block as a small dense matrix).
 //  * bcr_spmm_mma  -- matrix-core kernel for fp16 / bf16 with BR = 16 or 32.
 //    A workgroup owns a tile of TN columns of X and a group of row strips.  Chunks of
-//    consecutive X rows are staged in LDS once per workgroup (tiling, Section 4.4);
-//    each wave gathers the rows its strip keeps with LDS transpose reads straight into
-//    MFMA operand layout and multiplies them with pre-built weight fragments.  Strips
-//    are visited in stored (work-sorted, Section 4.2) order so the waves of a
-//    workgroup carry near-equal work.  Accumulation is fp32, order fixed, no atomics.
+//    consecutive X rows are staged in LDS once per workgroup (tiling, Section 4.4) by a
+//    dedicated producer wave using direct global->LDS loads, one chunk ahead of the
+//    consumer waves.  Each consumer wave gathers the rows its strips keep with LDS
+//    transpose reads straight into MFMA operand layout and multiplies them with
+//    pre-built weight fragments.  Strips are dealt to waves in stored (work-sorted,
+//    Section 4.2) order so the waves of a workgroup carry near-equal work.
+//    Accumulation is fp32, order fixed, no atomics.
 #include <hip/hip_runtime.h>
 
+#include <cstdlib>
 #include <type_traits>
 
 #include "bcr_matrix.hpp"
@@ -124,18 +127,27 @@ grim_status launch_spmm_fma(const grim_bcr_matrix *A, const void *X, int64_t N, 
 // matrix-core kernel
 // ------------------------------------------------------------------------------------------
 struct MmaParams {
-    const uint16_t *afrag;
-    const uint16_t *kidx;
-    const int32_t *kstep_ptr;
+    const uint16_t *recs;
+    const int32_t *cptr;
     const int32_t *strip_order;
     const unsigned short *X;
     float *Y;
     int64_t N, ldx, ldy;
     int32_t K, nbr, nchunks, chunk_rows;
     int32_t ntiles, ngroups;
-    int32_t xvec;   // widest aligned vector (elements: 8, 4, 2 or 1) for rows of X
+    int32_t amax;   // record slots per LDS stage
+    int32_t xvec;   // widest aligned vector (elements: 8, 4 or 1) for rows of X
     int32_t yvec;   // 4 when rows of Y allow aligned float4 stores, else 1
+#ifdef GRIM_DBG
+    long long *dbg;
+#endif
 };
+
+#ifdef GRIM_DBG
+#define GRIM_STAMP(slot, j) do { if (p.dbg && blockIdx.x == 8 && lane == 0) p.dbg[((j) + 1) * 16 + (slot)] = (long long)__builtin_amdgcn_s_memtime(); } while (0)
+#else
+#define GRIM_STAMP(slot, j) do { } while (0)
+#endif
 
 template <bool BF16>
 __device__ __forceinline__ f32x4 mfma16(i16x8 a, i16x8 b, f32x4 c) {
@@ -159,24 +171,52 @@ __device__ __forceinline__ i16x4 lds_tr_read(const char *lds_addr) {
     return __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) i16x4 *)(lds_addr));
 }
 
+// Staged rows have no padding; the 16-byte chunks of a row are XOR-swizzled by the row
+// number so that the four rows one transpose read touches fall into different bank groups
+// whenever their numbers differ mod 4.
+template <int CPR>   // 16-byte chunks per staged row
+__device__ __forceinline__ int swizzle(int row) {
+    return CPR >= 8 ? ((row & 3) << 1) : (((row >> 1) & 1) << 1);
+}
+
+constexpr int kRecBytes = 1280;   // one step: weight fragment (1 KB) + per-lane gather rows (256 B)
+
+// LDS bytes of one stage: staged X rows + zero row, then room for amax records rounded up to
+// whole 1 KB slots
+__host__ __device__ inline int mma_stage_bytes(int chunk_rows, int pitch, int amax) {
+    return (chunk_rows + 1) * pitch + ((amax * kRecBytes + 1023) / 1024 + 1) * 1024;
+}
+
+// Workgroup = NW consumer waves + NP producer waves; LDS holds two stages, each
+//   [chunk_rows staged rows of X | one zero row | the chunk's step records].
+// Everything a chunk needs -- the X rows of the tile and the records of the group's strips, one
+// contiguous byte range -- is cut into 1 KB slots (one 16-byte load per lane).  The producers
+// form two teams that alternate chunks; the NM members of a team share a chunk's slots.  A team
+// issues the loads of chunk c + 2 into registers while the consumers multiply chunk c, and
+// writes them to the free stage one chunk later, so two chunks are in flight per workgroup and
+// global load latency spans two chunk periods.  One barrier per chunk, no atomics.
+//
 // BR = 16: operands of v_mfma_f32_16x16x32: lane l holds row/col l % 16, k slots 8 * (l / 16) + 0..7.
 //          The product is taken as (X^T tile) x (W^T fragment) so that a lane ends up with 4
 //          consecutive columns n of one output row (16-byte stores).
 // BR = 32: v_mfma_f32_32x32x16: lane l holds row/col l % 32, k slots 8 * (l / 32) + 0..7; weights
 //          are the first operand, so a lane holds one column n and 16 rows.
-template <bool BF16, int BR, int NT, int SPW>
-__global__ void __launch_bounds__(256) bcr_spmm_mma(MmaParams p) {
+template <bool BF16, int BR, int NT, int SPW, int NW, int NP, int SX, int SR>
+__global__ void __launch_bounds__((NW + NP) * 64) bcr_spmm_mma(MmaParams p) {
     constexpr int NSUB = BR == 16 ? 16 : 32;
     constexpr int TN = NT * NSUB;
-    constexpr int KS = BR == 16 ? 32 : 16;
-    constexpr int ROWB = TN * 2 + 32;            // LDS row pitch in bytes
-    constexpr int SLOTS = TN / 8;                // 16-byte slots per staged row
-    constexpr int PF = kMmaMaxChunkRows * SLOTS / 256;
-    constexpr int G = 4 * SPW;                   // strips per workgroup
+    constexpr int PITCH = TN * 2;                // LDS row pitch in bytes (no padding)
+    constexpr int CPR = PITCH / 16;              // 16-byte chunks per staged row
+    constexpr int RPS = 1024 / PITCH;            // staged rows per slot
+    constexpr int G = NW * SPW;                  // strips per workgroup
+    constexpr int NM = NP / 2;                   // members of a producer team
     using Acc = typename std::conditional<BR == 16, f32x4, f32x16>::type;
 
     extern __shared__ __attribute__((aligned(16))) char lds[];
-    const int stage_bytes = (p.chunk_rows + 1) * ROWB;
+    const int xbytes = (p.chunk_rows + 1) * PITCH;            // X rows + zero row
+    const int stage_bytes = mma_stage_bytes(p.chunk_rows, PITCH, p.amax);
+    // after the two stages: first record of (chunk, strip of this group), [nchunks][G + 1]
+    const int *tab = reinterpret_cast<const int *>(lds + 2 * stage_bytes);
 
     // workgroup -> (tile, strip group); all groups of a tile run on the same XCD
     // (workgroups are dealt to the 8 XCDs round-robin by linear id)
@@ -187,14 +227,130 @@ __global__ void __launch_bounds__(256) bcr_spmm_mma(MmaParams p) {
     if (tile >= p.ntiles) return;
     const int64_t n0 = (int64_t)tile * TN;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int t0 = group * G;                                  // first stored strip of the group
+    const int t1 = t0 + G < p.nbr ? t0 + G : p.nbr;
 
-    // zero rows (gather target of padded k slots) of both stages
-    if (tid < 2 * (ROWB / 4)) {
-        int st = tid / (ROWB / 4), w = tid % (ROWB / 4);
-        *reinterpret_cast<unsigned int *>(lds + st * stage_bytes + p.chunk_rows * ROWB + w * 4) = 0u;
+    // zero rows (gather target of padded k slots), one per stage
+    if (tid < 2 * (PITCH / 4)) {
+        const int st = tid / (PITCH / 4), w = tid % (PITCH / 4);
+        *reinterpret_cast<unsigned int *>(lds + st * stage_bytes + p.chunk_rows * PITCH + w * 4) = 0u;
     }
 
+    if (wave >= NW) {
+        // ---- producers ----
+        const int q = wave - NW, team = q & 1, mem = q >> 1;
+        // this lane's place in an X slot: row (within the slot's RPS rows) and 16-byte chunk
+        const int lrow = lane / CPR;
+        const int c = (lane % CPR) ^ swizzle<CPR>(lrow);      // slots are RPS rows apart: same swizzle
+        const int64_t n = n0 + c * 8;
+        // Interior tiles of 16-byte-aligned X take the pipelined path: plain 16-byte loads, no
+        // test or merge after a load, so all loads of a chunk are in flight together.
+        const bool fast = p.xvec == 8 && n0 + TN <= p.N;
+        u32x4 RX[SX], RR[SR];
+
+        struct Shape { int xs, nrs, rows; int64_t k0, rbyte; };
+        // chunks 0 and 1 are shaped from global memory (the table is not filled yet), later
+        // chunks from the LDS table
+        auto shape_of = [&](int chunk, bool from_table) {
+            Shape h;
+            int r0, nrec;
+            if (from_table) {
+                r0 = tab[chunk * (G + 1)];
+                nrec = tab[chunk * (G + 1) + G] - r0;
+            } else {
+                const int32_t *cp = p.cptr + (int64_t)chunk * (p.nbr + 1);
+                r0 = cp[t0];
+                nrec = cp[t1] - r0;
+            }
+            h.rbyte = (int64_t)r0 * kRecBytes;
+            h.nrs = (nrec * kRecBytes + 1023) >> 10;
+            h.k0 = (int64_t)chunk * p.chunk_rows;
+            h.rows = (int)((p.K - h.k0) < p.chunk_rows ? (p.K - h.k0) : p.chunk_rows);
+            h.xs = (h.rows + RPS - 1) / RPS;
+            return h;
+        };
+        auto load_chunk = [&](int chunk, bool from_table) {
+            const Shape h = shape_of(chunk, from_table);
+            const char *rsrc = reinterpret_cast<const char *>(p.recs) + h.rbyte + lane * 16;
+#pragma unroll
+            for (int i = 0; i < SR; ++i) {
+                const int sl = mem + i * NM;
+                if (sl < h.nrs) RR[i] = *reinterpret_cast<const u32x4 *>(rsrc + (int64_t)sl * 1024);
+            }
+            if (fast) {
+                // rows past the end of the chunk are clamped to its last row (never stored / read)
+                const unsigned short *xsrc = p.X + h.k0 * p.ldx + n;
+#pragma unroll
+                for (int i = 0; i < SX; ++i) {
+                    int row = (mem + i * NM) * RPS + lrow;
+                    row = row < h.rows ? row : h.rows - 1;
+                    RX[i] = *reinterpret_cast<const u32x4 *>(xsrc + (int64_t)row * p.ldx);
+                }
+            }
+        };
+        auto store_chunk = [&](int chunk, bool from_table) {
+            const Shape h = shape_of(chunk, from_table);
+            char *sbase = lds + (chunk & 1) * stage_bytes;
+#pragma unroll
+            for (int i = 0; i < SR; ++i) {
+                const int sl = mem + i * NM;
+                if (sl < h.nrs) *reinterpret_cast<u32x4 *>(sbase + xbytes + sl * 1024 + lane * 16) = RR[i];
+            }
+            if (fast) {
+#pragma unroll
+                for (int i = 0; i < SX; ++i) {
+                    const int sl = mem + i * NM;
+                    if (sl * RPS + lrow < h.rows) *reinterpret_cast<u32x4 *>(sbase + sl * 1024 + lane * 16) = RX[i];
+                }
+            } else {
+                // edge tile (row tail) or rows of X not 16-byte aligned: guarded loads, element-wise
+                // where needed, staged synchronously
+                for (int sl = mem; sl < h.xs; sl += NM) {
+                    const int row = sl * RPS + lrow;
+                    if (row < h.rows && n < p.N) {
+                        const unsigned short *g = p.X + (h.k0 + row) * p.ldx + n;
+                        u32x4 v;
+                        if (p.xvec == 8 && n + 8 <= p.N) {
+                            v = *reinterpret_cast<const u32x4 *>(g);
+                        } else if (p.xvec >= 4 && n + 8 <= p.N) {
+                            const uint2 a = *reinterpret_cast<const uint2 *>(g);
+                            const uint2 b = *reinterpret_cast<const uint2 *>(g + 4);
+                            v = u32x4{a.x, a.y, b.x, b.y};
+                        } else {
+                            unsigned int w[4] = {0u, 0u, 0u, 0u};
+                            for (int e = 0; e < 8; ++e)
+                                if (n + e < p.N) w[e >> 1] |= (unsigned int)g[e] << ((e & 1) * 16);
+                            v = u32x4{w[0], w[1], w[2], w[3]};
+                        }
+                        *reinterpret_cast<u32x4 *>(sbase + sl * 1024 + lane * 16) = v;
+                    }
+                }
+            }
+        };
+
+        if (q < 3) GRIM_STAMP(q * 4 + 0, -1);
+        if (team < p.nchunks) load_chunk(team, false);        // team 0: chunk 0, team 1: chunk 1
+        if (q < 3) GRIM_STAMP(q * 4 + 1, -1);
+        if (team == 0) store_chunk(0, false);
+        if (q < 3) GRIM_STAMP(q * 4 + 2, -1);
+        __syncthreads();
+        for (int j = 0; j < p.nchunks; ++j) {
+            if (q < 3) GRIM_STAMP(q * 4 + 0, j);
+            if ((j & 1) == team) {
+                if (j + 2 < p.nchunks) load_chunk(j + 2, true);   // registers were emptied one chunk ago
+            } else {
+                if (j + 1 < p.nchunks) store_chunk(j + 1, true);  // stage (j + 1) % 2 was read last in chunk j - 1
+            }
+            if (q < 3) GRIM_STAMP(q * 4 + 2, j);
+            __syncthreads();
+            if (q < 3) GRIM_STAMP(q * 4 + 3, j);
+        }
+        return;
+    }
+
+    // ---- consumers ----
     Acc acc[SPW][NT];
 #pragma unroll
     for (int s = 0; s < SPW; ++s)
@@ -203,88 +359,83 @@ __global__ void __launch_bounds__(256) bcr_spmm_mma(MmaParams p) {
 #pragma unroll
             for (int e = 0; e < (BR == 16 ? 4 : 16); ++e) acc[s][q][e] = 0.f;
 
-    // ---- staging of X: global -> registers -> LDS ----
-    u32x4 pre[PF];
-    auto fetch = [&](int chunk) {
-        const int64_t k0 = (int64_t)chunk * p.chunk_rows;
-        const int rows = (int)((p.K - k0) < p.chunk_rows ? (p.K - k0) : p.chunk_rows);
-#pragma unroll
-        for (int i = 0; i < PF; ++i) {
-            const int sl = tid + i * 256;
-            const int r = sl / SLOTS, cs = sl % SLOTS;
-            u32x4 v = {0u, 0u, 0u, 0u};
-            if (r < rows) {
-                const int64_t n = n0 + cs * 8;
-                const unsigned short *src = p.X + (k0 + r) * p.ldx + n;
-                if (p.xvec == 8 && n + 8 <= p.N) {
-                    v = *reinterpret_cast<const u32x4 *>(src);
-                } else if (p.xvec >= 4 && n + 8 <= p.N) {
-                    const uint2 a = *reinterpret_cast<const uint2 *>(src);
-                    const uint2 b = *reinterpret_cast<const uint2 *>(src + 4);
-                    v = u32x4{a.x, a.y, b.x, b.y};
-                } else {
-                    unsigned int w[4] = {0u, 0u, 0u, 0u};
-#pragma unroll
-                    for (int e = 0; e < 8; ++e)
-                        if (n + e < p.N) w[e >> 1] |= (unsigned int)src[e] << ((e & 1) * 16);
-                    v = u32x4{w[0], w[1], w[2], w[3]};
-                }
-            }
-            pre[i] = v;
-        }
-    };
-    auto stash = [&](int stage) {
-        char *dst = lds + stage * stage_bytes;
-#pragma unroll
-        for (int i = 0; i < PF; ++i) {
-            const int sl = tid + i * 256;
-            const int r = sl / SLOTS, cs = sl % SLOTS;
-            if (r < p.chunk_rows) *reinterpret_cast<u32x4 *>(dst + r * ROWB + cs * 16) = pre[i];
-        }
-    };
-
-    // per-lane constants of the gather
+    // per-lane constants of the gather: byte column inside a sub-tile
     const int i16 = lane & 15;
-    const int kslot = (BR == 16 ? 8 * (lane >> 4) : 8 * (lane >> 5)) + (i16 >> 2);
-    const int ncol = (BR == 16 ? 0 : 16 * ((lane >> 4) & 1)) + 4 * (i16 & 3);
+    const int ncolb = ((BR == 16 ? 0 : 16 * ((lane >> 4) & 1)) + 4 * (i16 & 3)) * 2;
+    const int cl = ncolb >> 4, within = ncolb & 15;
 
-    fetch(0);
-    stash(0);
-    __syncthreads();
+    int tstrip[SPW];
+#pragma unroll
+    for (int s = 0; s < SPW; ++s) tstrip[s] = t0 + s * NW + wave;   // stored strips of this wave
 
-    for (int ch = 0; ch < p.nchunks; ++ch) {
-        if (ch + 1 < p.nchunks) fetch(ch + 1);
-        const char *stage = lds + (ch & 1) * stage_bytes + ncol * 2;
+    // fill the table while the producers fetch the first chunk (strips past the last one get
+    // the chunk's end, i.e. an empty range)
+    {
+        int *wtab = reinterpret_cast<int *>(lds + 2 * stage_bytes);
+        for (int e = tid; e < p.nchunks * (G + 1); e += NW * 64) {
+            const int ch = e / (G + 1), i = e % (G + 1);
+            const int t = t0 + i < p.nbr ? t0 + i : p.nbr;
+            wtab[e] = p.cptr[(int64_t)ch * (p.nbr + 1) + t];
+        }
+    }
+    // record ranges of this wave's strips inside the stage, for chunk `ch`
+    auto ranges = [&](int ch, int (&a0)[SPW], int (&a1)[SPW]) {
+        const int *row = tab + ch * (G + 1);
+        const int base = row[0];
 #pragma unroll
         for (int s = 0; s < SPW; ++s) {
-            const int t = group * G + s * 4 + wave;       // stored strip of this wave
-            if (t >= p.nbr) continue;
-            const int32_t *kp = p.kstep_ptr + (int64_t)t * (p.nchunks + 1) + ch;
-            const int ks0 = kp[0], ks1 = kp[1];
-            for (int ks = ks0; ks < ks1; ++ks) {
-                const i16x8 w = *reinterpret_cast<const i16x8 *>(p.afrag + (int64_t)ks * 512 + lane * 8);
-                const int r0 = p.kidx[(int64_t)ks * KS + kslot];
-                const int r1 = p.kidx[(int64_t)ks * KS + kslot + 4];
-                const char *a0 = stage + r0 * ROWB;
-                const char *a1 = stage + r1 * ROWB;
+            a0[s] = row[s * NW + wave] - base;
+            a1[s] = row[s * NW + wave + 1] - base;
+        }
+    };
+    struct Step { i16x8 w; unsigned int rr; };
+    auto load_step = [&](const char *frs, int r) {
+        Step f;
+        const char *rec = frs + r * kRecBytes;
+        f.w = *reinterpret_cast<const i16x8 *>(rec + lane * 16);
+        f.rr = *reinterpret_cast<const unsigned int *>(rec + 1024 + lane * 4);
+        return f;
+    };
+
+    int a0[SPW], a1[SPW];
+    __syncthreads();
+    for (int ch = 0; ch < p.nchunks; ++ch) {
+        const char *stage = lds + (ch & 1) * stage_bytes;
+        const char *frs = stage + xbytes;
+        if (wave == 0) GRIM_STAMP(12, ch);
+        ranges(ch, a0, a1);
+#pragma unroll
+        for (int s = 0; s < SPW; ++s) {
+            if (a0[s] >= a1[s]) continue;
+            Step cur = load_step(frs, a0[s]);
+            for (int r = a0[s]; r < a1[s]; ++r) {
+                const Step nxt = load_step(frs, r + 1 < a1[s] ? r + 1 : r);
+                const int r0 = cur.rr & 0xffff, r1 = cur.rr >> 16;
+                const int sw0 = swizzle<CPR>(r0), sw1 = swizzle<CPR>(r1);
+                const char *x0 = stage + r0 * PITCH + within;
+                const char *x1 = stage + r1 * PITCH + within;
 #pragma unroll
                 for (int q = 0; q < NT; ++q) {
-                    const i16x4 lo = lds_tr_read(a0 + q * NSUB * 2);
-                    const i16x4 hi = lds_tr_read(a1 + q * NSUB * 2);
+                    const int cq = q * (NSUB / 8) + cl;
+                    const i16x4 lo = lds_tr_read(x0 + ((cq ^ sw0) << 4));
+                    const i16x4 hi = lds_tr_read(x1 + ((cq ^ sw1) << 4));
                     const i16x8 x = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-                    if constexpr (BR == 16) acc[s][q] = mfma16<BF16>(x, w, acc[s][q]);
-                    else acc[s][q] = mfma32<BF16>(w, x, acc[s][q]);
+                    if constexpr (BR == 16) acc[s][q] = mfma16<BF16>(x, cur.w, acc[s][q]);
+                    else acc[s][q] = mfma32<BF16>(cur.w, x, acc[s][q]);
                 }
+                cur = nxt;
             }
         }
-        if (ch + 1 < p.nchunks) stash((ch + 1) & 1);
+        if (wave == 0) GRIM_STAMP(13, ch);
         __syncthreads();
+        if (wave == 0) GRIM_STAMP(14, ch);
     }
+    if (wave == 0) GRIM_STAMP(15, p.nchunks);
 
     // ---- write the strip tiles of Y (original row order) ----
 #pragma unroll
     for (int s = 0; s < SPW; ++s) {
-        const int t = group * G + s * 4 + wave;
+        const int t = tstrip[s];
         if (t >= p.nbr) continue;
         const int64_t row0 = (int64_t)p.strip_order[t] * BR;
 #pragma unroll
@@ -317,43 +468,69 @@ __global__ void __launch_bounds__(256) bcr_spmm_mma(MmaParams p) {
 
 bool mma_supported(const grim_bcr_matrix *A) { return A->mma.present; }
 
-template <bool BF16, int BR, int NT, int SPW>
+static int amax_of(const grim_bcr_matrix *A, int g) { return A->mma.amax[g <= 4 ? 0 : g <= 8 ? 1 : g <= 16 ? 2 : 3]; }
+
+// Compiled launch shapes: 4 consumer waves, 8 producer waves (two teams of 4); per producer
+// SX slots of X and SR slots of records in registers.
+struct MmaShape { int tn, strips, sx, sr; };
+static bool mma_shape(int BR, int tn, int strips, MmaShape *out) {
+    const int sx = tn == 32 ? 4 : tn == 64 ? 8 : tn == 128 ? 16 : 0;      // 256 staged rows
+    const int sr = strips == 4 ? 8 : strips == 8 ? 12 : strips == 16 ? 16 : 0;
+    if (!sx || !sr) return false;
+    if (BR == 32 && (strips / 4) * (tn / 32) > 4) return false;            // accumulator registers
+    *out = MmaShape{tn, strips, sx, sr};
+    return true;
+}
+static bool mma_shape_fits(const grim_bcr_matrix *A, int tn, int strips) {
+    MmaShape sh;
+    if (!mma_shape(A->BR, tn, strips, &sh)) return false;
+    const int rps = 1024 / (tn * 2), amax = amax_of(A, strips);
+    if ((A->mma.chunk_rows + rps - 1) / rps > 4 * sh.sx) return false;
+    if ((amax * kRecBytes + 1023) / 1024 > 4 * sh.sr) return false;
+    return 2 * (int64_t)mma_stage_bytes(A->mma.chunk_rows, tn * 2, amax) + (int64_t)A->mma.nchunks * (strips + 1) * 4 <= 160 * 1024;
+}
+
+template <bool BF16, int BR, int NT, int SPW, int SX, int SR>
 static grim_status launch_mma_inst(const MmaParams &p, hipStream_t stream) {
     constexpr int TN = NT * (BR == 16 ? 16 : 32);
-    constexpr int ROWB = TN * 2 + 32;
-    const size_t lds = 2 * (size_t)(p.chunk_rows + 1) * ROWB;
+    const size_t lds = 2 * (size_t)mma_stage_bytes(p.chunk_rows, TN * 2, p.amax) + (size_t)p.nchunks * (4 * SPW + 1) * 4;
     const int64_t tiles8 = ((int64_t)p.ntiles + 7) / 8 * 8;
     const int64_t nwg = tiles8 * p.ngroups;
     if (nwg > 0x7fffffff) return GRIM_ERR_SHAPE;
-    auto kern = bcr_spmm_mma<BF16, BR, NT, SPW>;
-    if (lds > 64 * 1024) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
+    auto kern = bcr_spmm_mma<BF16, BR, NT, SPW, 4, 8, SX, SR>;
+    static bool attr_done = false;    // raising a kernel's LDS limit is needed once per process
+    if (lds > 64 * 1024 && !attr_done) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess) {
             (void)hipGetLastError();
             return GRIM_ERR_DEVICE;
         }
+        attr_done = true;
     }
-    hipLaunchKernelGGL(kern, dim3((unsigned)nwg), dim3(256), lds, stream, p);
+    hipLaunchKernelGGL(kern, dim3((unsigned)nwg), dim3(12 * 64), lds, stream, p);
     return hipGetLastError() == hipSuccess ? GRIM_OK : GRIM_ERR_DEVICE;
 }
 
 template <bool BF16, int BR>
-static grim_status launch_mma_br(MmaParams &p, int tile_n, int spw, hipStream_t stream) {
+static grim_status launch_mma_br(MmaParams &p, const grim_bcr_matrix *A, int tile_n, int strips, hipStream_t stream) {
     constexpr int NSUB = BR == 16 ? 16 : 32;
-    const int nt = tile_n / NSUB;
+    const int nt = tile_n / NSUB, spw = strips / 4;
     p.ntiles = (int32_t)((p.N + tile_n - 1) / tile_n);
-    p.ngroups = (p.nbr + 4 * spw - 1) / (4 * spw);
-#define GRIM_CASE(NT_, SPW_) \
-    if (nt == NT_ && spw == SPW_) return launch_mma_inst<BF16, BR, NT_, SPW_>(p, stream);
+    p.ngroups = (p.nbr + strips - 1) / strips;
+    p.amax = amax_of(A, strips);
+#define GRIM_CASE(TN_, G_, SX_, SR_) \
+    if (tile_n == TN_ && strips == G_) return launch_mma_inst<BF16, BR, TN_ / NSUB, G_ / 4, SX_, SR_>(p, stream);
+#ifdef GRIM_FEW_SHAPES   /* development builds: one shape */
+    GRIM_CASE(64, 4, 8, 8)
+#else
+    GRIM_CASE(32, 4, 4, 8) GRIM_CASE(32, 8, 4, 12) GRIM_CASE(32, 16, 4, 16)
+    GRIM_CASE(64, 4, 8, 8) GRIM_CASE(64, 8, 8, 12)
+    GRIM_CASE(128, 4, 16, 8)
     if constexpr (BR == 16) {
-        GRIM_CASE(2, 1) GRIM_CASE(2, 2) GRIM_CASE(2, 4)
-        GRIM_CASE(4, 1) GRIM_CASE(4, 2) GRIM_CASE(4, 4)
-        GRIM_CASE(8, 1) GRIM_CASE(8, 2)
-    } else {
-        GRIM_CASE(1, 1) GRIM_CASE(1, 2) GRIM_CASE(1, 4)
-        GRIM_CASE(2, 1) GRIM_CASE(2, 2) GRIM_CASE(2, 4)
-        GRIM_CASE(4, 1) GRIM_CASE(4, 2)
+        GRIM_CASE(64, 16, 8, 16) GRIM_CASE(128, 8, 16, 12) GRIM_CASE(128, 16, 16, 16)
     }
+#endif
 #undef GRIM_CASE
+    (void)nt; (void)spw;
     return GRIM_ERR_UNSUPPORTED;
 }
 
@@ -362,22 +539,24 @@ grim_status launch_spmm_mma(const grim_bcr_matrix *A, const void *X, int64_t N, 
     if (!A->mma.present) return GRIM_ERR_UNSUPPORTED;
     if (tile_n != 0 && tile_n != 32 && tile_n != 64 && tile_n != 128) return GRIM_ERR_UNSUPPORTED;
     if (strips_per_wg != 0 && strips_per_wg != 4 && strips_per_wg != 8 && strips_per_wg != 16) return GRIM_ERR_UNSUPPORTED;
-    const int tn = tile_n ? tile_n : (N <= 32 ? 32 : 64);
-    int spw;
-    if (strips_per_wg) {
-        spw = strips_per_wg / 4;
-    } else {
+    int tn = tile_n ? tile_n : (N <= 32 ? 32 : 64);
+    int strips = strips_per_wg;
+    if (!strips) {
         // Every strip group of a tile re-reads the tile's rows of X (through L2), so take the
-        // largest group that still leaves about one workgroup per compute unit.
+        // largest compiled group that fits and still leaves about one workgroup per compute unit.
         const int64_t tiles = (N + tn - 1) / tn;
-        spw = A->nbr > 8 ? 4 : A->nbr > 4 ? 2 : 1;
-        while (spw > 1 && tiles * ((A->nbr + 4 * spw - 1) / (4 * spw)) < 256) spw >>= 1;
+        strips = 4;
+        for (int g = 16; g > 4; g >>= 1) {
+            if (A->nbr <= g / 2 || !mma_shape_fits(A, tn, g)) continue;
+            if (tiles * ((A->nbr + g - 1) / g) < 256) continue;
+            strips = g;
+            break;
+        }
     }
-    if (tn == 128 && spw > 2) spw = 2;   // accumulator registers
+    if (!mma_shape_fits(A, tn, strips)) return GRIM_ERR_UNSUPPORTED;
     MmaParams p;
-    p.afrag = A->mma.d_afrag;
-    p.kidx = A->mma.d_kidx;
-    p.kstep_ptr = A->mma.d_kstep_ptr;
+    p.recs = A->mma.d_recs;
+    p.cptr = A->mma.d_cptr;
     p.strip_order = A->dev.strip_order;
     p.X = static_cast<const unsigned short *>(X);
     p.Y = Y;
@@ -386,9 +565,12 @@ grim_status launch_spmm_mma(const grim_bcr_matrix *A, const void *X, int64_t N, 
     const uintptr_t xa = reinterpret_cast<uintptr_t>(X), ya = reinterpret_cast<uintptr_t>(Y);
     p.xvec = (xa % 16 == 0 && ldx % 8 == 0) ? 8 : (xa % 8 == 0 && ldx % 4 == 0) ? 4 : 1;
     p.yvec = (ya % 16 == 0 && ldy % 4 == 0) ? 4 : 1;
+#ifdef GRIM_DBG
+    p.dbg = reinterpret_cast<long long *>(getenv("GRIM_DBG_PTR") ? strtoull(getenv("GRIM_DBG_PTR"), nullptr, 0) : 0ull);
+#endif
     const bool bf = A->dtype == GRIM_BF16;
-    if (A->BR == 16) return bf ? launch_mma_br<true, 16>(p, tn, spw, stream) : launch_mma_br<false, 16>(p, tn, spw, stream);
-    return bf ? launch_mma_br<true, 32>(p, tn, spw, stream) : launch_mma_br<false, 32>(p, tn, spw, stream);
+    if (A->BR == 16) return bf ? launch_mma_br<true, 16>(p, A, tn, strips, stream) : launch_mma_br<false, 16>(p, A, tn, strips, stream);
+    return bf ? launch_mma_br<true, 32>(p, A, tn, strips, stream) : launch_mma_br<false, 32>(p, A, tn, strips, stream);
 }
 
 }  // namespace grim

@@ -95,8 +95,12 @@ def test_mma_kernel_all_tilings(g, dtype, BR, tile_n, strips):
     W = gen.normal_weights(M, K, dtype, seed=71)
     X = gen.normal_activations(K, N, dtype, seed=72, relu=True)
     A = pack_workload(g, W, dtype, mask)
-    Y = run_spmm(g, A, X, dtype, M, N, tile_n=tile_n, strips_per_wg=strips, kernel=2)
     Yref, S = oracle_product(W, X, dtype, mask)
+    try:
+        Y = run_spmm(g, A, X, dtype, M, N, tile_n=tile_n, strips_per_wg=strips, kernel=2)
+    except g.GrimError as e:                # a shape that is not compiled, or whose staging does not fit LDS
+        assert e.name == "GRIM_ERR_UNSUPPORTED"
+        pytest.skip(f"launch shape tn={tile_n} strips={strips} refused for this matrix")
     assert_close(Y, Yref, S, dtype, f"mma {dtype} BR={BR} tn={tile_n} g={strips}")
 
 
