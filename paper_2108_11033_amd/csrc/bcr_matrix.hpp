@@ -47,6 +47,7 @@ struct GemvLayout {
     bool present = false;
     int32_t uniform_kr = -1, uniform_kc = -1;   // >= 0 when every block keeps the same counts
     int32_t vec = 1;                            // widest aligned vector (elements) for weight rows
+    int32_t krmax = 0, kcmax = 0;               // most rows / columns any block keeps
     std::vector<uint32_t> masks;                // [nb * 2] (rowmask, colmask)
     std::vector<uint32_t> woff;                 // [nb + 1] element offsets (32-bit copy of blk_ptr)
     uint32_t *d_masks = nullptr;
@@ -102,7 +103,7 @@ struct grim_bcr_group {
     int64_t M = 0, K = 0;
     int32_t BR = 0, BC = 0, dtype = 0;
     int64_t nbr = 0, nbc = 0;
-    int32_t uniform_kr = -1, uniform_kc = -1, vec = 1;
+    int32_t uniform_kr = -1, uniform_kc = -1, vec = 1, krmax = 0, kcmax = 0;
     int device = -1;
     GemvDesc *d_table = nullptr;
 };
@@ -116,6 +117,6 @@ grim_status launch_spmm_mma(const grim_bcr_matrix *A, const void *X, int64_t N, 
 bool mma_supported(const grim_bcr_matrix *A);
 grim_status launch_spmv(const GemvDesc *table_dev_or_null, const GemvDesc &single, int32_t count,
                         int64_t M, int64_t K, int32_t BR, int32_t BC, int32_t dtype, int32_t ukr,
-                        int32_t ukc, int32_t vec, const void *x, int64_t x_stride, int32_t batch,
+                        int32_t ukc, int32_t vec, int32_t krmax, int32_t kcmax, const void *x, int64_t x_stride, int32_t batch,
                         int64_t ldx, float *y, int64_t y_stride, int64_t ldy, hipStream_t stream);
 }  // namespace grim

@@ -146,6 +146,7 @@ void build_mma_layout(grim_bcr_matrix *A, int32_t chunk_rows_opt) {
 void build_gemv_layout(grim_bcr_matrix *A) {
     GemvLayout &G = A->gemv;
     G.present = false;
+    G.krmax = G.kcmax = 0;
     if (A->BR > 32 || A->BC > 32) return;
     if (A->nnz >= (int64_t(1) << 31)) return;
     G.masks.assign((size_t)A->nb * 2, 0);
@@ -164,6 +165,8 @@ void build_gemv_layout(grim_bcr_matrix *A) {
         ukr = ukr == -2 ? kr : (ukr == kr ? ukr : -1);
         ukc = ukc == -2 ? kc : (ukc == kc ? ukc : -1);
         if (kr > 0) while (vec > 1 && kc % vec) vec >>= 1;
+        G.krmax = std::max(G.krmax, kr);
+        G.kcmax = std::max(G.kcmax, kc);
     }
     G.woff[A->nb] = (uint32_t)A->blk_ptr[A->nb];
     G.uniform_kr = ukr < 0 ? -1 : ukr;
@@ -400,7 +403,7 @@ grim_status grim_bcr_spmm_tuned(const grim_bcr_matrix *A, const void *X_dev, int
     if (kernel == 0 && tile_n == 0 && strips_per_wg == 0 && gemv_ok(A, N)) {
         GemvDesc d = desc_of(A);
         return launch_spmv(nullptr, d, 1, A->M, A->K, A->BR, A->BC, A->dtype, A->gemv.uniform_kr, A->gemv.uniform_kc,
-                           A->gemv.vec, X_dev, 0, (int32_t)N, ldx, Y_dev, 0, ldy, stream);
+                           A->gemv.vec, A->gemv.krmax, A->gemv.kcmax, X_dev, 0, (int32_t)N, ldx, Y_dev, 0, ldy, stream);
     }
     bool mma = A->mma.present && kernel != 1;
     if (kernel == 2 && !mma) return GRIM_ERR_UNSUPPORTED;
@@ -424,7 +427,7 @@ grim_status grim_bcr_spmv(const grim_bcr_matrix *A, const void *x_dev, int32_t b
     if (gemv_ok(A, batch)) {
         GemvDesc d = desc_of(A);
         return launch_spmv(nullptr, d, 1, A->M, A->K, A->BR, A->BC, A->dtype, A->gemv.uniform_kr, A->gemv.uniform_kc,
-                           A->gemv.vec, x_dev, 0, batch, ldx, y_dev, 0, ldy, stream);
+                           A->gemv.vec, A->gemv.krmax, A->gemv.kcmax, x_dev, 0, batch, ldx, y_dev, 0, ldy, stream);
     }
     if (A->BR > 64) return GRIM_ERR_UNSUPPORTED;
     return launch_spmm_fma(A, x_dev, batch, ldx, y_dev, ldy, stream);
@@ -452,6 +455,7 @@ grim_status grim_bcr_group_create(const grim_bcr_matrix *const *mats, int32_t co
     G->count = count; G->M = A0->M; G->K = A0->K; G->BR = A0->BR; G->BC = A0->BC; G->dtype = A0->dtype;
     G->nbr = A0->nbr; G->nbc = A0->nbc; G->device = dev;
     G->uniform_kr = A0->gemv.uniform_kr; G->uniform_kc = A0->gemv.uniform_kc; G->vec = A0->gemv.vec;
+    G->krmax = A0->gemv.krmax; G->kcmax = A0->gemv.kcmax;
     for (int32_t i = 0; i < count; ++i) {
         const grim_bcr_matrix *A = mats[i];
         if (A->M != G->M || A->K != G->K || A->BR != G->BR || A->BC != G->BC || A->dtype != G->dtype) { delete G; return GRIM_ERR_SHAPE; }
@@ -459,6 +463,8 @@ grim_status grim_bcr_group_create(const grim_bcr_matrix *const *mats, int32_t co
         if (!A->gemv.present) { delete G; return GRIM_ERR_UNSUPPORTED; }
         if (A->gemv.uniform_kr != G->uniform_kr || A->gemv.uniform_kc != G->uniform_kc) G->uniform_kr = G->uniform_kc = -1;
         G->vec = std::min(G->vec, A->gemv.vec);
+        G->krmax = std::max(G->krmax, A->gemv.krmax);
+        G->kcmax = std::max(G->kcmax, A->gemv.kcmax);
         table[i] = desc_of(A);
     }
     if (hipMalloc(reinterpret_cast<void **>(&G->d_table), sizeof(GemvDesc) * count) != hipSuccess) { (void)hipGetLastError(); delete G; return GRIM_ERR_ALLOC; }
@@ -477,7 +483,7 @@ grim_status grim_bcr_spmv_batched(const grim_bcr_group *G, const void *x_dev, in
     int dev = -1;
     if (hipGetDevice(&dev) != hipSuccess || dev != G->device) return GRIM_ERR_DEVICE;
     GemvDesc none{nullptr, nullptr, nullptr, nullptr};
-    return launch_spmv(G->d_table, none, G->count, G->M, G->K, G->BR, G->BC, G->dtype, G->uniform_kr, G->uniform_kc, G->vec,
+    return launch_spmv(G->d_table, none, G->count, G->M, G->K, G->BR, G->BC, G->dtype, G->uniform_kr, G->uniform_kc, G->vec, G->krmax, G->kcmax,
                        x_dev, x_stride, batch, ldx, y_dev, y_stride, ldy, static_cast<hipStream_t>(hip_stream));
 }
 

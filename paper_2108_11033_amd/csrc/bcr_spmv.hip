@@ -1,15 +1,22 @@
 // SpMV / skinny SpMM kernel: y = W_bcr * x for 1..8 right-hand sides (Section 3.1: FC and
 // RNN gate layers are matrix-vector products).
 //
-// The compact weights ARE the memory traffic here, so they are read exactly once, in
-// their compact kept-rows x kept-columns form (Section 4.3), with 8 bytes of row / column
-// bit masks per block as the only index data.  One workgroup owns one row strip.  Eight
-// lanes share a block: lane i takes compact rows i, i + 8, ... and walks the row's kept
-// columns, taking x from an LDS copy (every gathered x value is shared by all kept rows of
-// the block -- the load-redundancy elimination of Section 4.4).  Per-block partial sums go
-// to private LDS slots; one thread per (strip row, right-hand side) then adds the partials
-// of the blocks that keep its row in ascending column-block order: fixed order, no atomics.
+// The compact weights ARE the memory traffic here, so they are read exactly once, in their
+// compact kept-rows x kept-columns form (Section 4.3), with 8 bytes of row / column bit masks
+// per block as the only index data.  One workgroup owns one row strip:
+//   1. the strip's weights -- one contiguous byte range -- its block masks and x are fetched with
+//      coalesced 16-byte loads, all issued before any is used, and parked in LDS;
+//   2. a group of LPB lanes takes a block, lane i its compact row i: a dot product over the
+//      block's kept columns with x gathered from LDS (every gathered x value is shared by all kept
+//      rows of the block -- the load-redundancy elimination of Section 4.4); partial sums go to
+//      private LDS slots;
+//   3. one thread per (strip row, right-hand side, block range) adds the partials of the blocks
+//      that keep its row in ascending block order, then the block ranges are added in ascending
+//      order: a fixed summation tree, no atomics, bit-reproducible.
+// Strips too large for LDS are processed in segments of column blocks.
 #include <hip/hip_runtime.h>
+
+#include <cstdlib>
 
 #include "bcr_matrix.hpp"
 
@@ -19,12 +26,26 @@ struct GemvParams {
     const GemvDesc *table;   // device table (batched launch) or nullptr
     GemvDesc single;
     int32_t BR, BC, nbc, K;
+    int32_t nbr_total;       // row strips of the matrix
     int32_t ukr, ukc;        // uniform kept counts or -1
+    int32_t lpb_shift;       // log2(lanes per block), 2..5
+    int32_t seg_blocks;      // column blocks per LDS segment (<= kSegMax)
+    int32_t wbytes;          // LDS bytes reserved for a segment's weights
+    int32_t krmax, kcmax;    // most rows / columns any block keeps
     const void *x;
     float *y;
     int64_t x_stride, y_stride, ldx, ldy;
     int32_t xvec16;          // x is contiguous and 16-byte aligned: copy with 16-byte loads
+#ifdef GRIM_DBG
+    long long *dbg;
+#endif
 };
+
+#ifdef GRIM_DBG
+#define GEMV_STAMP(k) do { if (p.dbg && blockIdx.x == 1 && blockIdx.y == gridDim.y / 2 && (threadIdx.x & 63) == 0) p.dbg[(threadIdx.x >> 6) * 16 + (k)] = (long long)__builtin_amdgcn_s_memtime(); } while (0)
+#else
+#define GEMV_STAMP(k) do { } while (0)
+#endif
 
 template <int DT> struct GElem;
 template <> struct GElem<GRIM_F32> { using type = float; };
@@ -38,92 +59,429 @@ template <> __device__ __forceinline__ float g2f<GRIM_BF16>(unsigned short v) {
     return __builtin_bit_cast(float, (unsigned int)v << 16);
 }
 
-constexpr int kSlots = 32;      // blocks in flight per workgroup pass (8 lanes each)
-constexpr int kRowsMax = 32;    // BR <= 32
+constexpr int kSegMax = 64;          // column blocks per segment at most
+constexpr int kWLoads = 8;           // 16-byte weight loads per thread per segment (256 threads: 32 KB)
+constexpr int kGemvWBytes = kWLoads * 256 * 16;
+
+typedef unsigned int gu32x4 __attribute__((ext_vector_type(4)));
+
+// position of the j-th (0-based) set bit of m; j < popcount(m)
+__device__ __forceinline__ int nth_set_bit(unsigned int m, int j) {
+    int pos = 0;
+    int c = __builtin_popcount(m & 0xffffu);
+    if (j >= c) { j -= c; m >>= 16; pos = 16; }
+    c = __builtin_popcount(m & 0xffu);
+    if (j >= c) { j -= c; m >>= 8; pos += 8; }
+    c = __builtin_popcount(m & 0xfu);
+    if (j >= c) { j -= c; m >>= 4; pos += 4; }
+    c = __builtin_popcount(m & 0x3u);
+    if (j >= c) { j -= c; m >>= 2; pos += 2; }
+    if (j >= (int)(m & 1u)) pos += 1;
+    return pos;
+}
+
+__host__ __device__ inline int gemv_xg_stride(int kcmax, int B) { return ((kcmax + 7) & ~7) * B; }
 
 template <int DT, int B, int VEC>
-__global__ void __launch_bounds__(256) bcr_spmv(GemvParams p) {
+__global__ void __launch_bounds__(256, (B == 1 ? 6 : 1)) bcr_spmv(GemvParams p) {
     using T = typename GElem<DT>::type;
     struct __attribute__((aligned(sizeof(T) * VEC))) WVec { T v[VEC]; };
+    struct __attribute__((aligned(sizeof(T) * VEC))) XVec { T v[VEC * B]; };
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    float *part = reinterpret_cast<float *>(smem);                        // [kSlots][kRowsMax][B]
-    unsigned int *msk = reinterpret_cast<unsigned int *>(part + kSlots * kRowsMax * B);   // [kSlots]
-    T *xs = reinterpret_cast<T *>(msk + kSlots);                          // [K][B]
+    // LDS: [weights segment + 16][row masks][column masks][block offsets][gathered x per block]
+    //      [partials + one zero slot][block-range sums][x]
+    char *wl = smem;
+    unsigned int *rmask = reinterpret_cast<unsigned int *>(smem + p.wbytes + 16);
+    unsigned int *cmask = rmask + kSegMax;
+    unsigned int *wof = cmask + kSegMax;
+    const int xgs = gemv_xg_stride(p.kcmax, B);
+    T *xg = reinterpret_cast<T *>(wof + kSegMax + 4);                      // [seg_blocks][xgs]
+    float *part = reinterpret_cast<float *>(reinterpret_cast<char *>(xg) + ((p.seg_blocks * xgs * (int)sizeof(T) + 15) & ~15));
+    const int zero_slot = p.seg_blocks * p.krmax * B;                      // part[zero_slot] == 0
+    float *red = part + ((zero_slot + 4) & ~3);                            // [nseg][BR * B]
+    const int rb = p.BR * B;                                               // outputs of the strip
+    const int nseg = 256 / rb;                                             // BR <= 32 and B <= 8: rb <= 256
+    T *xs = reinterpret_cast<T *>(red + ((nseg * rb + 3) & ~3));
 
     const int tid = threadIdx.x;
     const int64_t t = blockIdx.x;            // stored strip
     const int64_t mi = blockIdx.y;           // matrix of the group
     const GemvDesc d = p.table ? p.table[mi] : p.single;
-    const T *W = static_cast<const T *>(d.weights);
+    const char *W = static_cast<const char *>(d.weights);
     const T *x = static_cast<const T *>(p.x) + mi * p.x_stride;
     float *y = p.y + mi * p.y_stride;
+    const int lpb = 1 << p.lpb_shift;
 
-    // x -> LDS, layout [k][b]
-    const int nx = p.K * B;
-    if (p.xvec16) {
-        constexpr int PER = 16 / sizeof(T);
-        const uint4 *src = reinterpret_cast<const uint4 *>(x);
-        uint4 *dst = reinterpret_cast<uint4 *>(xs);
-        for (int e = tid; e < nx / PER; e += 256) dst[e] = src[e];
-    } else {
-        for (int e = tid; e < nx; e += 256) xs[e] = x[(int64_t)(e / B) * p.ldx + (e % B)];
-    }
-    __syncthreads();
-
-    const int bs = tid >> 3, i0 = tid & 7;
-    const int r_out = tid / B, b_out = tid % B;      // reducer role: tid < BR * B
+    // reducer role: thread -> (block range sg, output o = r * B + b)
+    const int sg = tid / rb, o = tid % rb;
+    const int r_out = o / B, b_out = o % B;
+    const bool reducer = sg < nseg;
     float yacc = 0.f;
+    if (tid == 0) part[zero_slot] = 0.f;
+    GEMV_STAMP(0);
 
-    for (int cbase = 0; cbase < p.nbc; cbase += kSlots) {
-        const int c = cbase + bs;
-        unsigned int rm = 0, cm = 0;
-        if (c < p.nbc) {
-            const int64_t blk = t * p.nbc + c;
-            rm = d.masks[2 * blk];
-            cm = d.masks[2 * blk + 1];
-            const int kr = __builtin_popcount(rm), kc = __builtin_popcount(cm);
-            const unsigned int woff = p.ukr >= 0 ? (unsigned int)blk * (unsigned int)(p.ukr * p.ukc) : d.woff[blk];
-            const int xbase = c * p.BC;
-            for (int i = i0; i < kr; i += 8) {
-                const T *wr = W + woff + i * kc;
+    for (int c0 = 0; c0 < p.nbc; c0 += p.seg_blocks) {
+        const int nb = p.nbc - c0 < p.seg_blocks ? p.nbc - c0 : p.seg_blocks;
+        const int64_t blk0 = t * p.nbc + c0;
+        // ---- 1. fetch: block masks / offsets, the segment's weights, and (first segment) x;
+        //         every load is issued before any is used ----
+        unsigned int m0 = 0, m1 = 0, wo = 0;
+        if (tid < nb) {
+            const uint2 mm = *reinterpret_cast<const uint2 *>(d.masks + 2 * (blk0 + tid));
+            m0 = mm.x;
+            m1 = mm.y;
+        }
+        unsigned int wstart, wend;           // element range of the segment's weights
+        if (p.ukr >= 0) {
+            wstart = (unsigned int)blk0 * (unsigned int)(p.ukr * p.ukc);
+            wend = wstart + (unsigned int)nb * (unsigned int)(p.ukr * p.ukc);
+            if (tid <= nb) wo = wstart + (unsigned int)tid * (unsigned int)(p.ukr * p.ukc);
+        } else {
+            wstart = d.woff[blk0];
+            wend = d.woff[blk0 + nb];
+            if (tid <= nb) wo = d.woff[blk0 + tid];
+        }
+        const unsigned int bstart = wstart * (unsigned int)sizeof(T), bend = wend * (unsigned int)sizeof(T);
+        const unsigned int a0 = bstart & ~15u;               // 16-byte aligned fetch window
+        const int nvec = (int)((bend - a0 + 15u) >> 4);      // <= kWLoads * 256 by construction
+        // round 0 of the weights and of x share one latency; later rounds (large segments, wide x)
+        // are rare and run one after the other
+        const bool xfast = c0 == 0 && p.xvec16;
+        const int nxv = xfast ? p.K * B / (16 / (int)sizeof(T)) : 0;
+        const gu32x4 *xsrc = reinterpret_cast<const gu32x4 *>(x);
+        gu32x4 wreg[4], xreg[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            if (i * 256 < nvec) {                            // same for the whole workgroup
+                int v = tid + i * 256;
+                v = v < nvec ? v : nvec - 1;                 // clamp: the duplicates are never stored
+                wreg[i] = *reinterpret_cast<const gu32x4 *>(W + a0 + (size_t)v * 16);
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            if (i * 256 < nxv) {
+                int v = tid + i * 256;
+                v = v < nxv ? v : nxv - 1;
+                xreg[i] = xsrc[v];
+            }
+        }
+        GEMV_STAMP(1);
+        if (c0 > 0) __syncthreads();                          // previous segment fully consumed
+        if (tid < nb) { rmask[tid] = m0; cmask[tid] = m1; }
+        if (tid <= nb) wof[tid] = wo - wstart;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int v = tid + i * 256;
+            if (v < nvec) *reinterpret_cast<gu32x4 *>(wl + (size_t)v * 16) = wreg[i];
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int v = tid + i * 256;
+            if (v < nxv) reinterpret_cast<gu32x4 *>(xs)[v] = xreg[i];
+        }
+        for (int v = tid + 1024; v < nvec; v += 256)
+            *reinterpret_cast<gu32x4 *>(wl + (size_t)v * 16) = *reinterpret_cast<const gu32x4 *>(W + a0 + (size_t)v * 16);
+        for (int v = tid + 1024; v < nxv; v += 256) reinterpret_cast<gu32x4 *>(xs)[v] = xsrc[v];
+        if (c0 == 0 && !p.xvec16) {
+            // x with a leading dimension or unaligned: element by element, layout [k][b]
+            for (int e = tid; e < p.K * B; e += 256) xs[e] = x[(int64_t)(e / B) * p.ldx + (e % B)];
+        }
+        GEMV_STAMP(2);
+        __syncthreads();
+        GEMV_STAMP(3);
+        // ---- 2. lane group -> block.  The group first gathers the block's kept columns of x
+        //         (lane li takes kept columns li, li + lpb, ...); group and block live in one
+        //         wave, whose LDS operations complete in order, so no workgroup barrier is needed
+        //         before the rows read the gathered values.  Then lane -> compact row: dot product.
+        const T *wbase = reinterpret_cast<const T *>(wl + (bstart - a0));
+        const int slots = 256 >> p.lpb_shift;
+        const int li = tid & (lpb - 1);
+        for (int s = tid >> p.lpb_shift; s < nb; s += slots) {
+            const unsigned int cm = cmask[s];
+            const int kr = __builtin_popcount(rmask[s]), kc = __builtin_popcount(cm);
+            T *xgb = xg + s * xgs;
+            {
+                // kept column j of the block = position of the j-th set bit of its column mask
+                const T *xb = xs + (c0 + s) * p.BC * B;
+                for (int j = li; j < kc; j += lpb) {
+                    const int col = nth_set_bit(cm, j);
+#pragma unroll
+                    for (int b = 0; b < B; ++b) xgb[j * B + b] = xb[col * B + b];
+                }
+            }
+            __builtin_amdgcn_wave_barrier();
+            for (int i = li; i < kr; i += lpb) {
+                const T *wr = wbase + wof[s] + i * kc;
                 float acc[B];
 #pragma unroll
                 for (int b = 0; b < B; ++b) acc[b] = 0.f;
-                unsigned int m = cm;
+#pragma unroll 4
                 for (int j = 0; j < kc; j += VEC) {
                     const WVec wv = *reinterpret_cast<const WVec *>(wr + j);
+                    const XVec xv = *reinterpret_cast<const XVec *>(xgb + j * B);
 #pragma unroll
                     for (int v = 0; v < VEC; ++v) {
-                        const int col = __builtin_ctz(m);
-                        m &= m - 1;
                         const float w = g2f<DT>(wv.v[v]);
-                        const T *xp = xs + (xbase + col) * B;
 #pragma unroll
-                        for (int b = 0; b < B; ++b) acc[b] = __builtin_fmaf(w, g2f<DT>(xp[b]), acc[b]);
+                        for (int b = 0; b < B; ++b) acc[b] = __builtin_fmaf(w, g2f<DT>(xv.v[v * B + b]), acc[b]);
                     }
                 }
 #pragma unroll
-                for (int b = 0; b < B; ++b) part[(bs * kRowsMax + i) * B + b] = acc[b];
+                for (int b = 0; b < B; ++b) part[(s * p.krmax + i) * B + b] = acc[b];
             }
         }
-        if (i0 == 0) msk[bs] = rm;
+        GEMV_STAMP(4);
         __syncthreads();
-        if (tid < p.BR * B) {
-#pragma unroll 8
-            for (int s = 0; s < kSlots; ++s) {
-                const unsigned int m = msk[s];
-                if ((m >> r_out) & 1u) {
-                    const int i = __builtin_popcount(m & ((1u << r_out) - 1u));
-                    yacc += part[(s * kRowsMax + i) * B + b_out];
+        GEMV_STAMP(5);
+        // ---- 3. per output: add the partials of the blocks that keep its row, ascending ----
+        if (reducer) {
+            const int per = (nb + nseg - 1) / nseg;
+            const int s0 = sg * per, s1 = s0 + per < nb ? s0 + per : nb;
+            const unsigned int below = (1u << r_out) - 1u;
+            for (int sb = s0; sb < s1; sb += 8) {
+                float v[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {                 // eight independent LDS reads in flight
+                    const int s = sb + u < s1 ? sb + u : s1 - 1;
+                    const unsigned int m = rmask[s];
+                    const int i = __builtin_popcount(m & below);
+                    const bool hit = sb + u < s1 && ((m >> r_out) & 1u);
+                    v[u] = part[hit ? (s * p.krmax + i) * B + b_out : zero_slot];
                 }
+#pragma unroll
+                for (int u = 0; u < 8; ++u) yacc += v[u];     // adding 0 for a miss changes nothing
             }
         }
-        __syncthreads();
     }
-    if (tid < p.BR * B) {
+    GEMV_STAMP(6);
+    // block ranges are combined in ascending order by the first range's threads
+    if (nseg > 1) {
+        if (reducer) red[sg * rb + o] = yacc;
+        __syncthreads();
+        if (tid < rb) {
+            float sum = red[o];
+            for (int g = 1; g < nseg; ++g) sum += red[g * rb + o];
+            yacc = sum;
+        }
+    }
+    if (tid < rb) {
         const int64_t row = (int64_t)d.strip_order[t] * p.BR + r_out;
         y[row * p.ldy + b_out] = yacc;
     }
+    GEMV_STAMP(7);
+}
+
+// ------------------------------------------------------------------------------------------
+// One right-hand side: one WAVE per strip, one LANE per block.
+//
+// With a single x the work per weight is one FMA, so the cost that matters is every instruction
+// that is not an FMA.  Here each lane owns a whole block of the strip (64 blocks per pass):
+//   - its two bit masks stay in registers (no index traffic through LDS);
+//   - it walks the set bits of its column mask once, parking the gathered x values in a private
+//     LDS row that all of its kept rows then reuse (Section 4.4);
+//   - it computes its kept rows one after the other from the strip's weights, which the wave
+//     fetched as one contiguous range with 16-byte loads and parked in LDS;
+//   - it scatters each row's sum to a [strip row][block] table (zero where a block does not keep
+//     the row); lane pairs then add each strip row's 64 entries in ascending block order.
+// A workgroup is four such waves (four consecutive strips) sharing one LDS copy of x.
+// ------------------------------------------------------------------------------------------
+constexpr int kWaveWLoads = 16;                    // 16 KB of weights per wave per pass
+constexpr int kPartStride = 66;                    // floats per strip row of the partial table
+
+template <int DT, int VEC, int KRMAX>
+__global__ void __launch_bounds__(256) bcr_spmv_wave(GemvParams p) {
+    using T = typename GElem<DT>::type;
+    struct __attribute__((aligned(sizeof(T) * VEC))) WVec { T v[VEC]; };
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int xgs = gemv_xg_stride(p.kcmax, 1);
+    const int xbytes = (p.K * (int)sizeof(T) + 15) & ~15;
+    const int region = p.wbytes + 64 * xgs * (int)sizeof(T);      // per wave: weights / partial table, gathered x
+    T *xs = reinterpret_cast<T *>(smem);
+    char *wl = smem + xbytes + wave * region;
+    float *part = reinterpret_cast<float *>(wl);                  // reuses the weights' space
+    T *xg = reinterpret_cast<T *>(wl + p.wbytes) + lane * xgs;    // this lane's gathered x
+
+    const int64_t t = (int64_t)blockIdx.x * 4 + wave;             // stored strip of this wave
+    const int64_t mi = blockIdx.y;
+    const GemvDesc d = p.table ? p.table[mi] : p.single;
+    const char *W = static_cast<const char *>(d.weights);
+    const T *x = static_cast<const T *>(p.x) + mi * p.x_stride;
+    float *y = p.y + mi * p.y_stride;
+
+    GEMV_STAMP(0);
+    // x -> LDS, once per workgroup
+    if (p.xvec16) {
+        const int nxv = p.K * (int)sizeof(T) / 16;
+        const gu32x4 *xsrc = reinterpret_cast<const gu32x4 *>(x);
+        gu32x4 xreg[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            if (i * 256 < nxv) {
+                int v = tid + i * 256;
+                v = v < nxv ? v : nxv - 1;
+                xreg[i] = xsrc[v];
+            }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int v = tid + i * 256;
+            if (v < nxv) reinterpret_cast<gu32x4 *>(xs)[v] = xreg[i];
+        }
+        for (int v = tid + 1024; v < nxv; v += 256) reinterpret_cast<gu32x4 *>(xs)[v] = xsrc[v];
+    } else {
+        for (int e = tid; e < p.K; e += 256) xs[e] = x[(int64_t)e * p.ldx];
+    }
+    __syncthreads();
+    GEMV_STAMP(1);
+    if (t >= p.nbr_total) return;
+
+    const int r_out = lane & 31, half = lane >> 5;
+    float yacc = 0.f;
+    for (int c0 = 0; c0 < p.nbc; c0 += p.seg_blocks) {
+        const int nb = p.nbc - c0 < p.seg_blocks ? p.nbc - c0 : p.seg_blocks;
+        const int64_t blk0 = t * p.nbc + c0;
+        const bool valid = lane < nb;
+        unsigned int rm = 0, cm = 0, wo = 0;
+        if (valid) {
+            const uint2 mm = *reinterpret_cast<const uint2 *>(d.masks + 2 * (blk0 + lane));
+            rm = mm.x;
+            cm = mm.y;
+        }
+        unsigned int wstart, wend;
+        if (p.ukr >= 0) {
+            const unsigned int u = (unsigned int)(p.ukr * p.ukc);
+            wstart = (unsigned int)blk0 * u;
+            wend = wstart + (unsigned int)nb * u;
+            wo = (unsigned int)lane * u;
+        } else {
+            wstart = d.woff[blk0];
+            wend = d.woff[blk0 + nb];
+            if (valid) wo = d.woff[blk0 + lane] - wstart;
+        }
+        const unsigned int bstart = wstart * (unsigned int)sizeof(T), bend = wend * (unsigned int)sizeof(T);
+        const unsigned int a0 = bstart & ~15u;
+        const int nvec = (int)((bend - a0 + 15u) >> 4);          // <= kWaveWLoads * 64 by construction
+        gu32x4 wreg[kWaveWLoads];
+#pragma unroll
+        for (int i = 0; i < kWaveWLoads; ++i) {
+            if (i * 64 < nvec) {
+                int v = lane + i * 64;
+                v = v < nvec ? v : nvec - 1;
+                wreg[i] = *reinterpret_cast<const gu32x4 *>(W + a0 + (size_t)v * 16);
+            }
+        }
+        GEMV_STAMP(2);
+#pragma unroll
+        for (int i = 0; i < kWaveWLoads; ++i) {
+            if (i * 64 < nvec) {
+                const int v = lane + i * 64;
+                if (v < nvec) *reinterpret_cast<gu32x4 *>(wl + (size_t)v * 16) = wreg[i];
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
+        GEMV_STAMP(3);
+        // gather this block's kept columns of x
+        const int kr = __builtin_popcount(rm), kc = __builtin_popcount(cm);
+        {
+            const T *xb = xs + (c0 + lane) * p.BC;
+            unsigned int m = cm;
+            for (int j = 0; m; ++j) {
+                const int col = __builtin_ctz(m);
+                m &= m - 1;
+                xg[j] = xb[col];
+            }
+        }
+        GEMV_STAMP(4);
+        // kept rows, one after the other
+        const T *wblk = reinterpret_cast<const T *>(wl + (bstart - a0)) + wo;
+        float acc[KRMAX];
+#pragma unroll
+        for (int i = 0; i < KRMAX; ++i) {
+            float a = 0.f;
+            if (i < kr) {
+                const T *wr = wblk + i * kc;
+#pragma unroll 4
+                for (int j = 0; j < kc; j += VEC) {
+                    const WVec wv = *reinterpret_cast<const WVec *>(wr + j);
+                    const WVec xv = *reinterpret_cast<const WVec *>(xg + j);
+#pragma unroll
+                    for (int v = 0; v < VEC; ++v) a = __builtin_fmaf(g2f<DT>(wv.v[v]), g2f<DT>(xv.v[v]), a);
+                }
+            }
+            acc[i] = a;
+        }
+        __builtin_amdgcn_wave_barrier();                          // every lane is done with the weights
+        GEMV_STAMP(5);
+        // partial table [strip row][block], zero where a block does not keep the row
+        for (int z = lane; z < (p.BR * kPartStride + 3) / 4; z += 64)
+            reinterpret_cast<gu32x4 *>(part)[z] = gu32x4{0u, 0u, 0u, 0u};
+        __builtin_amdgcn_wave_barrier();
+        {
+            unsigned int m = rm;
+#pragma unroll
+            for (int i = 0; i < KRMAX; ++i) {
+                if (i < kr) {
+                    const int r = __builtin_ctz(m);
+                    m &= m - 1;
+                    part[r * kPartStride + lane] = acc[i];
+                }
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
+        GEMV_STAMP(6);
+        // lanes (row, half): 32 blocks each, ascending; then first half + second half
+        float hs = 0.f;
+        if (r_out < p.BR) {
+            const float2 *src = reinterpret_cast<const float2 *>(part + r_out * kPartStride + half * 32);
+#pragma unroll
+            for (int q = 0; q < 16; ++q) {
+                const float2 v = src[q];
+                hs += v.x;
+                hs += v.y;
+            }
+        }
+        const float other = __shfl_xor(hs, 32);
+        yacc += half == 0 ? hs + other : other + hs;
+        __builtin_amdgcn_wave_barrier();                          // table consumed before the next pass refills LDS
+        GEMV_STAMP(7);
+    }
+    if (half == 0 && r_out < p.BR) {
+        const int64_t row = (int64_t)d.strip_order[t] * p.BR + r_out;
+        y[row * p.ldy] = yacc;
+    }
+    GEMV_STAMP(8);
+}
+
+template <int DT, int VEC>
+static grim_status launch_wave_kr(const GemvParams &p, int krmax, dim3 grid, size_t lds, hipStream_t stream) {
+#define GRIM_WAVE(KR)                                                                                         \
+    {                                                                                                         \
+        auto kern = bcr_spmv_wave<DT, VEC, KR>;                                                               \
+        static bool attr_done = false;                                                                        \
+        if (lds > 64 * 1024 && !attr_done) {                                                                  \
+            if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess) { \
+                (void)hipGetLastError();                                                                      \
+                return GRIM_ERR_DEVICE;                                                                       \
+            }                                                                                                 \
+            attr_done = true;                                                                                 \
+        }                                                                                                     \
+        hipLaunchKernelGGL(kern, grid, dim3(256), lds, stream, p);                                            \
+        return hipGetLastError() == hipSuccess ? GRIM_OK : GRIM_ERR_DEVICE;                                   \
+    }
+    if (krmax <= 8) GRIM_WAVE(8)
+    if (krmax <= 16) GRIM_WAVE(16)
+    GRIM_WAVE(32)
+#undef GRIM_WAVE
+}
+
+template <int DT>
+static grim_status launch_wave(const GemvParams &p, int vec, int krmax, dim3 grid, size_t lds, hipStream_t stream) {
+    if (vec >= 8 && sizeof(typename GElem<DT>::type) == 2) return launch_wave_kr<DT, 8>(p, krmax, grid, lds, stream);
+    if (vec >= 4) return launch_wave_kr<DT, 4>(p, krmax, grid, lds, stream);
+    if (vec >= 2) return launch_wave_kr<DT, 2>(p, krmax, grid, lds, stream);
+    return launch_wave_kr<DT, 1>(p, krmax, grid, lds, stream);
 }
 
 template <int DT, int B>
@@ -131,10 +489,13 @@ static grim_status launch_vec(const GemvParams &p, int vec, dim3 grid, size_t ld
 #define GRIM_GEMV(V)                                                                                          \
     {                                                                                                         \
         auto kern = bcr_spmv<DT, B, V>;                                                                       \
-        if (lds > 64 * 1024 &&                                                                                \
-            hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) { \
-            (void)hipGetLastError();                                                                          \
-            return GRIM_ERR_DEVICE;                                                                           \
+        static bool attr_done = false;                                                                        \
+        if (lds > 64 * 1024 && !attr_done) {                                                                  \
+            if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess) { \
+                (void)hipGetLastError();                                                                      \
+                return GRIM_ERR_DEVICE;                                                                       \
+            }                                                                                                 \
+            attr_done = true;                                                                                 \
         }                                                                                                     \
         hipLaunchKernelGGL(kern, grid, dim3(256), lds, stream, p);                                            \
         return hipGetLastError() == hipSuccess ? GRIM_OK : GRIM_ERR_DEVICE;                                   \
@@ -162,22 +523,69 @@ static grim_status launch_batch(const GemvParams &p, int batch, int vec, dim3 gr
 }
 
 grim_status launch_spmv(const GemvDesc *table, const GemvDesc &single, int32_t count, int64_t M, int64_t K, int32_t BR,
-                        int32_t BC, int32_t dtype, int32_t ukr, int32_t ukc, int32_t vec, const void *x, int64_t x_stride,
-                        int32_t batch, int64_t ldx, float *y, int64_t y_stride, int64_t ldy, hipStream_t stream) {
-    if (BR > kRowsMax || BC > 32 || batch < 1 || batch > 8) return GRIM_ERR_UNSUPPORTED;
+                        int32_t BC, int32_t dtype, int32_t ukr, int32_t ukc, int32_t vec, int32_t krmax, int32_t kcmax,
+                        const void *x, int64_t x_stride, int32_t batch, int64_t ldx, float *y, int64_t y_stride, int64_t ldy,
+                        hipStream_t stream) {
+    if (BR > 32 || BC > 32 || batch < 1 || batch > 8) return GRIM_ERR_UNSUPPORTED;
     const int esz = dtype_size(dtype);
     const int64_t nbr = M / BR;
     if (nbr > 0x7fffffff || count > 65535) return GRIM_ERR_SHAPE;
+    if (krmax < 1) krmax = 1;
+    if (kcmax < 1) kcmax = 1;
     GemvParams p;
     p.table = table;
     p.single = single;
     p.BR = BR; p.BC = BC; p.nbc = (int32_t)(K / BC); p.K = (int32_t)K;
+    p.nbr_total = (int32_t)nbr;
     p.ukr = ukr; p.ukc = ukc;
+    p.krmax = krmax;
+    p.kcmax = kcmax;
+    int lpb = 4;
+    while (lpb < krmax && lpb < 32) lpb <<= 1;
+    if (krmax <= 8 && krmax > 4) lpb = 8;
+    p.lpb_shift = lpb == 4 ? 2 : lpb == 8 ? 3 : lpb == 16 ? 4 : 5;
+    // a segment's weights (plus the 16-byte alignment window) must fit the per-thread fetch budget
+    const int64_t blk_bytes = (int64_t)krmax * kcmax * esz;
+    int64_t seg = (kGemvWBytes - 32) / blk_bytes;
+    if (seg < 1) return GRIM_ERR_UNSUPPORTED;
+    if (seg > kSegMax) seg = kSegMax;
+    p.seg_blocks = (int32_t)seg;
+    p.wbytes = (int32_t)((seg * blk_bytes + 32 + 15) & ~int64_t(15));
     p.x = x; p.y = y; p.x_stride = x_stride; p.y_stride = y_stride; p.ldx = ldx; p.ldy = ldy;
     const bool contiguous = ldx == batch && reinterpret_cast<uintptr_t>(x) % 16 == 0 &&
                             (K * batch * esz) % 16 == 0 && (count == 1 || (x_stride * esz) % 16 == 0);
     p.xvec16 = contiguous ? 1 : 0;
-    const size_t lds = (size_t)kSlots * kRowsMax * batch * 4 + kSlots * 4 + (((size_t)K * batch * esz + 15) & ~size_t(15));
+#ifdef GRIM_DBG
+    p.dbg = reinterpret_cast<long long *>(getenv("GRIM_DBG_PTR") ? strtoull(getenv("GRIM_DBG_PTR"), nullptr, 0) : 0ull);
+#endif
+    if (batch == 1 && (int64_t)K * esz <= 32 * 1024) {
+        // one wave per strip, one lane per block
+        int64_t wseg = (kWaveWLoads * 1024 - 32) / blk_bytes;
+        if (wseg > 64) wseg = 64;
+        if (wseg >= 1) {
+            GemvParams q = p;
+            q.seg_blocks = (int32_t)wseg;
+            int64_t wb = (wseg * blk_bytes + 32 + 15) & ~int64_t(15);
+            const int64_t table = ((int64_t)BR * kPartStride * 4 + 15) & ~int64_t(15);
+            if (wb < table) wb = table;
+            q.wbytes = (int32_t)wb;
+            const size_t wlds = (((size_t)K * esz + 15) & ~size_t(15)) + 4 * ((size_t)wb + 64 * (size_t)gemv_xg_stride(kcmax, 1) * esz);
+            if (wlds <= 160 * 1024) {
+                dim3 wgrid((unsigned)((nbr + 3) / 4), (unsigned)count);
+                switch (dtype) {
+                    case GRIM_F32: return launch_wave<GRIM_F32>(q, vec, krmax, wgrid, wlds, stream);
+                    case GRIM_F16: return launch_wave<GRIM_F16>(q, vec, krmax, wgrid, wlds, stream);
+                    case GRIM_BF16: return launch_wave<GRIM_BF16>(q, vec, krmax, wgrid, wlds, stream);
+                }
+            }
+        }
+    }
+    const int rb = BR * batch;
+    const int nseg = 256 / rb;
+    const size_t lds = (size_t)p.wbytes + 16 + 2 * kSegMax * 4 + (kSegMax + 4) * 4 +
+                       (((size_t)seg * gemv_xg_stride(kcmax, batch) * esz + 15) & ~size_t(15)) +
+                       (size_t)((seg * krmax * batch + 4) & ~3) * 4 + (size_t)((nseg * rb + 3) & ~3) * 4 +
+                       (((size_t)K * batch * esz + 15) & ~size_t(15));
     if (lds > 160 * 1024) return GRIM_ERR_UNSUPPORTED;
     dim3 grid((unsigned)nbr, (unsigned)count);
     switch (dtype) {
