@@ -25,6 +25,9 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
+# HBM bytes per c2 launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a device copy of known
+# size (profiles/bcr_spmm_mma_c2.md): 8569.5 KiB x 2.0 fetched + 3136.0 KiB x 1.0 written
+C2_TRAFFIC_BYTES = (8569.5 * 2.0 + 3136.0) * 1024
 METRIC = "BCR SpMM/SpMV useful TFLOP/s, HBM GB/s, % of roofline vs oracle"
 
 
@@ -90,6 +93,8 @@ def main() -> int:
     ap.add_argument("--strips-per-wg", type=int, default=0)
     ap.add_argument("--extra", action="store_true", help="also time the SpMV and large non-uniform workloads")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--calibrate", action="store_true",
+                    help="also run a plain 256 MiB device copy (reference for scaling rocprofv3 byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the product shards over N with no exchange; "
@@ -147,13 +152,22 @@ def main() -> int:
                                "16x32 blocks keep 8/16 rows x 8/32 cols (density 1/8)",
                    "buffer_sets": sets, "useful_gflop_per_step": flops / 1e9, "algorithmic_mb_per_step": abytes / 1e6},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": C2_TRAFFIC_BYTES,
                      "kernel": "bcr_spmm_mma", "launch_us": t_cold * 1e6},
         "warm_cache": {"ms_per_step": t_warm * 1e3, "useful_tflops": flops / t_warm / 1e12,
                        "algorithmic_gbs": abytes / t_warm / 1e9,
                        "note": "same X/Y every step: operands stay in the 256 MB last-level cache"},
         "wall_ms_per_step": wall_cold * 1e3,
     }
+
+    if args.calibrate:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        out["calibration_copy_bytes"] = 256 << 20
+        del src, dst
 
     if args.extra:
         extra = {}
