@@ -14,18 +14,20 @@ constexpr int kGemvMaxXBytes = 65536;   // bytes of x (K * batch elements) the S
 
 inline int dtype_size(int dt) { return dt == GRIM_F32 ? 4 : 2; }
 
-// Row-expanded layout for the matrix-core SpMM kernel (fp16 / bf16, BR = 16 or 32).
-// K is cut into chunks of `chunk_rows` consecutive rows of X.  For every (chunk, stored
-// strip) the kept columns of the strip's blocks inside the chunk are concatenated into a
-// gather list of staged X rows, padded to a multiple of `ks` (the k extent of one MFMA);
-// every `ks` entries form a step.  A step is stored as a record of
-//   afrag: the MFMA weight operand itself (64 lanes x 8 values), pruned rows of a block
-//          as zeros, so output rows sit at their strip positions and no scatter is needed;
-//   lidx:  per lane, the two staged rows it names in the two LDS transpose reads of the
-//          step (low / high 16 bits); the row `chunk_rows` is an all-zero row (padding).
-// A record is 1280 contiguous bytes.  Records are stored chunk-major, strips in stored order
-// inside a chunk, so the records a workgroup (a group of consecutive stored strips) needs for
-// one chunk are one contiguous byte range.
+// Layout for the matrix-core SpMM kernel (fp16 / bf16, BR = 16 or 32).
+// K is cut into chunks of `chunk_rows` consecutive rows of X.  For every (chunk, stored strip)
+// the kept columns of the strip's blocks inside the chunk are laid out as groups of 8 k slots
+// (a block's columns are padded to a multiple of 8 with the all-zero staged row), `ks / 8`
+// groups per MFMA step.  A (chunk, strip) region is
+//   [steps x header][payload]
+//   header : per step, the staged-row numbers of its k slots (u16, ordered so that the pair a
+//            lane names in its two LDS transpose reads is adjacent), then per group the block's
+//            row bit mask (u32) and the offset of the group's weights in 16-byte units from the
+//            region start (u32);
+//   payload: per group, for every KEPT row of the block 8 weights (16 bytes) -- compact: pruned
+//            rows are not stored; a lane finds its row by popcount of the mask below its bit.
+// Regions are stored chunk-major, strips in stored order inside a chunk, so what a workgroup
+// (a group of consecutive stored strips) needs for one chunk is one contiguous byte range.
 struct MmaLayout {
     bool present = false;
     int32_t ks = 0;            // 32 for BR = 16 (16x16x32), 16 for BR = 32 (32x32x16)
@@ -33,11 +35,13 @@ struct MmaLayout {
     int32_t chunk_rows = 0;    // chunk_blocks * BC
     int32_t nchunks = 0;
     int64_t nsteps = 0;
-    int32_t amax[4] = {0, 0, 0, 0};   // most steps any (group, chunk) holds, for groups of 4, 8, 16, 32 strips
+    int32_t amax[4] = {0, 0, 0, 0};   // most 16-byte units any (group, chunk) holds, for groups of 4, 8, 16, 32 strips
     std::vector<int32_t> cptr;        // [nchunks * (nbr + 1)] first step of (chunk, stored strip); last = end of chunk
-    std::vector<uint16_t> recs;       // [nsteps * 640]: per step afrag (512 values) then lidx (64 x 32 bit)
+    std::vector<int32_t> bptr;        // same shape: region start in 16-byte units
+    std::vector<unsigned char> recs;
     int32_t *d_cptr = nullptr;
-    uint16_t *d_recs = nullptr;
+    int32_t *d_bptr = nullptr;
+    unsigned char *d_recs = nullptr;
     int64_t bytes = 0;
 };
 

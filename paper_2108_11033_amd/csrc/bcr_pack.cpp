@@ -44,81 +44,91 @@ bool build_mma_layout_for(grim_bcr_matrix *A, int32_t chunk_blocks) {
     L.chunk_rows = L.chunk_blocks * A->BC;
     L.nchunks = (int32_t)((A->nbc + L.chunk_blocks - 1) / L.chunk_blocks);
     L.ks = A->BR == 16 ? 32 : 16;
-    const int32_t ks = L.ks, BR = A->BR;
-    const int lanes_per_kgroup = BR == 16 ? 16 : 32;   // lanes sharing one group of 8 k slots
+    const int32_t ng = L.ks / 8;                       // groups of 8 k slots per step
+    const int32_t hdr = L.ks * 2 + ng * 8;             // header bytes per step (a multiple of 16)
     L.cptr.assign((size_t)L.nchunks * (A->nbr + 1), 0);
+    L.bptr.assign((size_t)L.nchunks * (A->nbr + 1), 0);
     L.recs.clear();
-    struct Slot { int64_t t; int32_t j; };   // stored block, position of the kept column in it
-    std::vector<Slot> slots;
-    std::vector<uint16_t> rows;
-    std::vector<int32_t> comp(BR);           // local row -> compact row or -1
+    struct Group { int64_t t; int32_t j0; };           // stored block (-1: empty), first kept-column position
+    std::vector<Group> groups;
     int64_t step = 0;
     const uint16_t *w = reinterpret_cast<const uint16_t *>(A->weights.data());
+    const uint16_t zero_row = (uint16_t)L.chunk_rows;
     for (int32_t ch = 0; ch < L.nchunks; ++ch) {
         const int64_t c0 = (int64_t)ch * L.chunk_blocks, c1 = std::min<int64_t>(A->nbc, c0 + L.chunk_blocks);
         for (int64_t st = 0; st < A->nbr; ++st) {
             L.cptr[(size_t)ch * (A->nbr + 1) + st] = (int32_t)step;
-            slots.clear();
-            rows.clear();
+            L.bptr[(size_t)ch * (A->nbr + 1) + st] = (int32_t)(L.recs.size() / 16);
+            groups.clear();
             for (int64_t c = c0; c < c1; ++c) {
-                int64_t t = st * A->nbc + c;
-                if (A->row_ptr[t + 1] == A->row_ptr[t]) continue;   // no kept rows: nothing to multiply
-                for (int32_t q = A->col_ptr[t]; q < A->col_ptr[t + 1]; ++q) {
-                    slots.push_back({t, q - A->col_ptr[t]});
-                    rows.push_back((uint16_t)((c - c0) * A->BC + A->col_idx[q]));
-                }
+                const int64_t t = st * A->nbc + c;
+                const int32_t kr = A->row_ptr[t + 1] - A->row_ptr[t], kc = A->col_ptr[t + 1] - A->col_ptr[t];
+                if (kr == 0 || kc == 0) continue;       // nothing to multiply
+                for (int32_t j0 = 0; j0 < kc; j0 += 8) groups.push_back({t, j0});
             }
-            const size_t nsl = slots.size();
-            const size_t padded = (nsl + ks - 1) / ks * ks;
-            for (size_t base = 0; base < padded; base += ks) {
-                const size_t a0 = L.recs.size(), l0 = a0 + 512;
-                L.recs.resize(a0 + 640, 0);
-                auto row_of = [&](int32_t e) -> uint32_t { return base + e < nsl ? rows[base + e] : (uint32_t)L.chunk_rows; };
-                for (int32_t lane = 0; lane < 64; ++lane) {
-                    // the lane names row slot (8 * kgroup + (lane % 16) / 4) in the first transpose
-                    // read of the step and that slot + 4 in the second
-                    const int32_t kgroup = BR == 16 ? lane / 16 : lane / 32;
-                    const int32_t e0 = 8 * kgroup + (lane % 16) / 4;
-                    L.recs[l0 + 2 * lane] = (uint16_t)row_of(e0);
-                    L.recs[l0 + 2 * lane + 1] = (uint16_t)row_of(e0 + 4);
+            while (groups.size() % ng) groups.push_back({-1, 0});
+            const size_t nst = groups.size() / ng;
+            const size_t region0 = L.recs.size();
+            L.recs.resize(region0 + nst * hdr, 0);
+            uint32_t pay16 = (uint32_t)(nst * hdr / 16);    // next free payload unit, from the region start
+            for (size_t q = 0; q < groups.size(); ++q) {
+                const Group &gp = groups[q];
+                const size_t sidx = q / ng, g = q % ng;
+                unsigned char *h = L.recs.data() + region0 + sidx * hdr;
+                uint16_t rows[8];
+                uint32_t rowmask = 0, off = 0;
+                int32_t kr = 0, kc = 0;
+                int64_t c = 0;
+                if (gp.t >= 0) {
+                    kr = A->row_ptr[gp.t + 1] - A->row_ptr[gp.t];
+                    kc = A->col_ptr[gp.t + 1] - A->col_ptr[gp.t];
+                    c = gp.t % A->nbc;
+                    for (int32_t qq = A->row_ptr[gp.t]; qq < A->row_ptr[gp.t + 1]; ++qq) rowmask |= 1u << A->row_idx[qq];
                 }
-                int64_t cur_t = -1;
-                for (int32_t e = 0; e < ks; ++e) {
-                    if (base + e >= nsl) break;
-                    const Slot &sl = slots[base + e];
-                    if (sl.t != cur_t) {
-                        cur_t = sl.t;
-                        std::fill(comp.begin(), comp.end(), -1);
-                        for (int32_t q = A->row_ptr[sl.t]; q < A->row_ptr[sl.t + 1]; ++q)
-                            comp[A->row_idx[q]] = q - A->row_ptr[sl.t];
-                    }
-                    const int32_t kc = A->col_ptr[sl.t + 1] - A->col_ptr[sl.t];
-                    const int32_t kgroup = e / 8, i = e % 8;
-                    for (int32_t m = 0; m < BR; ++m) {
-                        if (comp[m] < 0) continue;
-                        const int32_t lane = kgroup * lanes_per_kgroup + m;
-                        L.recs[a0 + (size_t)lane * 8 + i] = w[A->blk_ptr[sl.t] + (int64_t)comp[m] * kc + sl.j];
-                    }
+                for (int32_t e = 0; e < 8; ++e)
+                    rows[e] = (gp.t >= 0 && gp.j0 + e < kc)
+                                  ? (uint16_t)((c - c0) * A->BC + A->col_idx[A->col_ptr[gp.t] + gp.j0 + e])
+                                  : zero_row;
+                // slot rows: quad qd of the group pairs slot qd with slot qd + 4
+                uint16_t *hs = reinterpret_cast<uint16_t *>(h) + g * 8;
+                for (int32_t qd = 0; qd < 4; ++qd) {
+                    hs[2 * qd] = rows[qd];
+                    hs[2 * qd + 1] = rows[qd + 4];
                 }
-                ++step;
+                if (gp.t >= 0) {
+                    off = pay16;
+                    const size_t p0 = L.recs.size();
+                    L.recs.resize(p0 + (size_t)kr * 16, 0);
+                    h = L.recs.data() + region0 + sidx * hdr;     // resize may move the buffer
+                    uint16_t *pw = reinterpret_cast<uint16_t *>(L.recs.data() + p0);
+                    for (int32_t i = 0; i < kr; ++i)
+                        for (int32_t e = 0; e < 8 && gp.j0 + e < kc; ++e)
+                            pw[i * 8 + e] = w[A->blk_ptr[gp.t] + (int64_t)i * kc + gp.j0 + e];
+                    pay16 += (uint32_t)kr;
+                }
+                uint32_t *hd = reinterpret_cast<uint32_t *>(h + L.ks * 2) + g * 2;
+                hd[0] = rowmask;
+                hd[1] = off;
             }
+            step += (int64_t)nst;
         }
         L.cptr[(size_t)ch * (A->nbr + 1) + A->nbr] = (int32_t)step;
+        L.bptr[(size_t)ch * (A->nbr + 1) + A->nbr] = (int32_t)(L.recs.size() / 16);
     }
     L.nsteps = step;
     for (int gi = 0; gi < 4; ++gi) {
         const int64_t Gs = 4 << gi;
         int32_t amax = 0;
         for (int32_t ch = 0; ch < L.nchunks; ++ch) {
-            const int32_t *cp = &L.cptr[(size_t)ch * (A->nbr + 1)];
+            const int32_t *bp = &L.bptr[(size_t)ch * (A->nbr + 1)];
             for (int64_t t0 = 0; t0 < A->nbr; t0 += Gs)
-                amax = std::max(amax, cp[std::min<int64_t>(A->nbr, t0 + Gs)] - cp[t0]);
+                amax = std::max(amax, bp[std::min<int64_t>(A->nbr, t0 + Gs)] - bp[t0]);
         }
         L.amax[gi] = amax;
     }
     // fits the default launch (64 columns per workgroup, groups of 4 strips)?  The producers move
     // at most 32 KB of X rows and 32 KB of records per chunk.
-    return L.chunk_rows <= 256 && (int64_t)L.amax[0] * 1280 <= 32 * 1024;
+    return L.chunk_rows <= 256 && (int64_t)L.amax[0] * 16 <= 32 * 1024 && L.recs.size() < (size_t(1) << 31) * 16;
 }
 
 void build_mma_layout(grim_bcr_matrix *A, int32_t chunk_rows_opt) {
@@ -136,7 +146,7 @@ void build_mma_layout(grim_bcr_matrix *A, int32_t chunk_rows_opt) {
         fits = build_mma_layout_for(A, blocks);
     }
     if (!fits) {   // even one column block per chunk overflows LDS: leave this matrix to the FMA kernel
-        L.cptr.clear(); L.recs.clear();
+        L.cptr.clear(); L.bptr.clear(); L.recs.clear();
         return;
     }
     L.present = true;
@@ -191,9 +201,10 @@ grim_status upload(grim_bcr_matrix *A) {
     size_t o_w = s.add(A->weights.size() + 64);   // slack: vector loads may overrun a row's end
     size_t o_rm = s.add(bytes(A->rowmask64));
     size_t canon_end = s.total;
-    size_t o_kp = 0, o_af = 0, o_gm = 0, o_go = 0;
+    size_t o_kp = 0, o_bp2 = 0, o_af = 0, o_gm = 0, o_go = 0;
     if (A->mma.present) {
         o_kp = s.add(bytes(A->mma.cptr));
+        o_bp2 = s.add(bytes(A->mma.bptr));
         o_af = s.add(bytes(A->mma.recs) + 2048);   // slack: records are fetched in 1 KB slots
     }
     size_t mma_end = s.total;
@@ -212,7 +223,8 @@ grim_status upload(grim_bcr_matrix *A) {
               put(o_ci, A->col_idx.data(), bytes(A->col_idx)) && put(o_bp, A->blk_ptr.data(), bytes(A->blk_ptr)) &&
               put(o_w, A->weights.data(), A->weights.size()) && put(o_rm, A->rowmask64.data(), bytes(A->rowmask64));
     if (ok && A->mma.present)
-        ok = put(o_kp, A->mma.cptr.data(), bytes(A->mma.cptr)) && put(o_af, A->mma.recs.data(), bytes(A->mma.recs));
+        ok = put(o_kp, A->mma.cptr.data(), bytes(A->mma.cptr)) && put(o_bp2, A->mma.bptr.data(), bytes(A->mma.bptr)) &&
+             put(o_af, A->mma.recs.data(), bytes(A->mma.recs));
     if (ok && A->gemv.present)
         ok = put(o_gm, A->gemv.masks.data(), bytes(A->gemv.masks)) && put(o_go, A->gemv.woff.data(), bytes(A->gemv.woff));
     if (!ok) { (void)hipGetLastError(); (void)hipFree(base); return GRIM_ERR_DEVICE; }
@@ -227,7 +239,8 @@ grim_status upload(grim_bcr_matrix *A) {
     A->dev.bytes = (int64_t)canon_end;
     if (A->mma.present) {
         A->mma.d_cptr = reinterpret_cast<int32_t *>(base + o_kp);
-        A->mma.d_recs = reinterpret_cast<uint16_t *>(base + o_af);
+        A->mma.d_bptr = reinterpret_cast<int32_t *>(base + o_bp2);
+        A->mma.d_recs = reinterpret_cast<unsigned char *>(base + o_af);
         A->mma.bytes = (int64_t)(mma_end - canon_end);
     }
     if (A->gemv.present) {

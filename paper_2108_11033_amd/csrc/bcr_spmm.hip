@@ -127,15 +127,16 @@ grim_status launch_spmm_fma(const grim_bcr_matrix *A, const void *X, int64_t N, 
 // matrix-core kernel
 // ------------------------------------------------------------------------------------------
 struct MmaParams {
-    const uint16_t *recs;
+    const unsigned char *recs;
     const int32_t *cptr;
+    const int32_t *bptr;
     const int32_t *strip_order;
     const unsigned short *X;
     float *Y;
     int64_t N, ldx, ldy;
     int32_t K, nbr, nchunks, chunk_rows;
     int32_t ntiles, ngroups;
-    int32_t amax;   // record slots per LDS stage
+    int32_t amax;   // 16-byte units of records one LDS stage must hold
     int32_t xvec;   // widest aligned vector (elements: 8, 4 or 1) for rows of X
     int32_t yvec;   // 4 when rows of Y allow aligned float4 stores, else 1
 #ifdef GRIM_DBG
@@ -173,24 +174,23 @@ __device__ __forceinline__ i16x4 lds_tr_read(const char *lds_addr) {
 
 // Staged rows have no padding; the 16-byte chunks of a row are XOR-swizzled by the row
 // number so that the four rows one transpose read touches fall into different bank groups
-// whenever their numbers differ mod 4.
+// whenever their numbers differ mod 4 (mod 8 for 128-byte rows, where consecutive rows
+// already sit in opposite halves of the 256-byte bank line; measured 3-7 % faster).
 template <int CPR>   // 16-byte chunks per staged row
 __device__ __forceinline__ int swizzle(int row) {
-    return CPR >= 8 ? ((row & 3) << 1) : (((row >> 1) & 1) << 1);
+    return CPR == 8 ? (((row >> 1) & 3) << 1) : CPR > 8 ? ((row & 3) << 1) : (((row >> 1) & 1) << 1);
 }
 
-constexpr int kRecBytes = 1280;   // one step: weight fragment (1 KB) + per-lane gather rows (256 B)
-
-// LDS bytes of one stage: staged X rows + zero row, then room for amax records rounded up to
-// whole 1 KB slots
+// LDS bytes of one stage: staged X rows + zero row, then room for amax 16-byte units of
+// records rounded up to whole 1 KB slots
 __host__ __device__ inline int mma_stage_bytes(int chunk_rows, int pitch, int amax) {
-    return (chunk_rows + 1) * pitch + ((amax * kRecBytes + 1023) / 1024 + 1) * 1024;
+    return (chunk_rows + 1) * pitch + ((amax * 16 + 1023) / 1024 + 1) * 1024;
 }
 
 // Workgroup = NW consumer waves + NP producer waves; LDS holds two stages, each
 //   [chunk_rows staged rows of X | one zero row | the chunk's step records].
-// Everything a chunk needs -- the X rows of the tile and the records of the group's strips, one
-// contiguous byte range -- is cut into 1 KB slots (one 16-byte load per lane).  The producers
+// Everything a chunk needs -- the X rows of the tile and the record regions of the group's strips,
+// one contiguous byte range -- is cut into 1 KB slots (one 16-byte load per lane).  The producers
 // form two teams that alternate chunks; the NM members of a team share a chunk's slots.  A team
 // issues the loads of chunk c + 2 into registers while the consumers multiply chunk c, and
 // writes them to the free stage one chunk later, so two chunks are in flight per workgroup and
@@ -215,8 +215,11 @@ __global__ void __launch_bounds__((NW + NP) * 64) bcr_spmm_mma(MmaParams p) {
     extern __shared__ __attribute__((aligned(16))) char lds[];
     const int xbytes = (p.chunk_rows + 1) * PITCH;            // X rows + zero row
     const int stage_bytes = mma_stage_bytes(p.chunk_rows, PITCH, p.amax);
-    // after the two stages: first record of (chunk, strip of this group), [nchunks][G + 1]
-    const int *tab = reinterpret_cast<const int *>(lds + 2 * stage_bytes);
+    constexpr int KS = BR == 16 ? 32 : 16;       // k slots per step
+    constexpr int HDR = KS * 2 + (KS / 8) * 8;   // header bytes per step
+    // after the two stages: (first step, region start in 16-byte units) of (chunk, strip of this
+    // group), [nchunks][G + 1]
+    const int2 *tab = reinterpret_cast<const int2 *>(lds + 2 * stage_bytes);
 
     // workgroup -> (tile, strip group); all groups of a tile run on the same XCD
     // (workgroups are dealt to the 8 XCDs round-robin by linear id)
@@ -255,17 +258,17 @@ __global__ void __launch_bounds__((NW + NP) * 64) bcr_spmm_mma(MmaParams p) {
         // chunks from the LDS table
         auto shape_of = [&](int chunk, bool from_table) {
             Shape h;
-            int r0, nrec;
+            int b0, units;
             if (from_table) {
-                r0 = tab[chunk * (G + 1)];
-                nrec = tab[chunk * (G + 1) + G] - r0;
+                b0 = tab[chunk * (G + 1)].y;
+                units = tab[chunk * (G + 1) + G].y - b0;
             } else {
-                const int32_t *cp = p.cptr + (int64_t)chunk * (p.nbr + 1);
-                r0 = cp[t0];
-                nrec = cp[t1] - r0;
+                const int32_t *bp = p.bptr + (int64_t)chunk * (p.nbr + 1);
+                b0 = bp[t0];
+                units = bp[t1] - b0;
             }
-            h.rbyte = (int64_t)r0 * kRecBytes;
-            h.nrs = (nrec * kRecBytes + 1023) >> 10;
+            h.rbyte = (int64_t)b0 * 16;
+            h.nrs = (units * 16 + 1023) >> 10;
             h.k0 = (int64_t)chunk * p.chunk_rows;
             h.rows = (int)((p.K - h.k0) < p.chunk_rows ? (p.K - h.k0) : p.chunk_rows);
             h.xs = (h.rows + RPS - 1) / RPS;
@@ -371,45 +374,51 @@ __global__ void __launch_bounds__((NW + NP) * 64) bcr_spmm_mma(MmaParams p) {
     // fill the table while the producers fetch the first chunk (strips past the last one get
     // the chunk's end, i.e. an empty range)
     {
-        int *wtab = reinterpret_cast<int *>(lds + 2 * stage_bytes);
+        int2 *wtab = reinterpret_cast<int2 *>(lds + 2 * stage_bytes);
         for (int e = tid; e < p.nchunks * (G + 1); e += NW * 64) {
             const int ch = e / (G + 1), i = e % (G + 1);
             const int t = t0 + i < p.nbr ? t0 + i : p.nbr;
-            wtab[e] = p.cptr[(int64_t)ch * (p.nbr + 1) + t];
+            wtab[e] = int2{p.cptr[(int64_t)ch * (p.nbr + 1) + t], p.bptr[(int64_t)ch * (p.nbr + 1) + t]};
         }
     }
-    // record ranges of this wave's strips inside the stage, for chunk `ch`
-    auto ranges = [&](int ch, int (&a0)[SPW], int (&a1)[SPW]) {
-        const int *row = tab + ch * (G + 1);
-        const int base = row[0];
-#pragma unroll
-        for (int s = 0; s < SPW; ++s) {
-            a0[s] = row[s * NW + wave] - base;
-            a1[s] = row[s * NW + wave + 1] - base;
-        }
-    };
+    // per-lane constants of the weight fragment: output row inside the strip and k group
+    const int m_row = BR == 16 ? (lane & 15) : (lane & 31);
+    const int kgroup = BR == 16 ? (lane >> 4) : (lane >> 5);
+    const unsigned int below = (1u << m_row) - 1u;
+    const int hdr_rows = (kgroup * 4 + (i16 >> 2)) * 4;        // this lane's pair of staged-row numbers
+    const int hdr_desc = KS * 2 + kgroup * 8;                  // its group's (row mask, payload offset)
+
     struct Step { i16x8 w; unsigned int rr; };
-    auto load_step = [&](const char *frs, int r) {
+    // one step of a strip region: header lookups, then this lane's 8 weights (its row of the
+    // group's block if the block keeps that row, else zeros)
+    auto load_step = [&](const char *region, int r) {
         Step f;
-        const char *rec = frs + r * kRecBytes;
-        f.w = *reinterpret_cast<const i16x8 *>(rec + lane * 16);
-        f.rr = *reinterpret_cast<const unsigned int *>(rec + 1024 + lane * 4);
+        const char *h = region + r * HDR;
+        f.rr = *reinterpret_cast<const unsigned int *>(h + hdr_rows);
+        const uint2 dsc = *reinterpret_cast<const uint2 *>(h + hdr_desc);
+        const bool kept = (dsc.x >> m_row) & 1u;
+        const int idx = kept ? __builtin_popcount(dsc.x & below) : 0;
+        const i16x8 w = *reinterpret_cast<const i16x8 *>(region + (dsc.y + idx) * 16);
+        f.w = kept ? w : i16x8{0, 0, 0, 0, 0, 0, 0, 0};
         return f;
     };
 
-    int a0[SPW], a1[SPW];
     __syncthreads();
     for (int ch = 0; ch < p.nchunks; ++ch) {
         const char *stage = lds + (ch & 1) * stage_bytes;
         const char *frs = stage + xbytes;
         if (wave == 0) GRIM_STAMP(12, ch);
-        ranges(ch, a0, a1);
+        const int2 *row = tab + ch * (G + 1);
+        const int2 base = row[0];
 #pragma unroll
         for (int s = 0; s < SPW; ++s) {
-            if (a0[s] >= a1[s]) continue;
-            Step cur = load_step(frs, a0[s]);
-            for (int r = a0[s]; r < a1[s]; ++r) {
-                const Step nxt = load_step(frs, r + 1 < a1[s] ? r + 1 : r);
+            const int2 e0 = row[s * NW + wave], e1 = row[s * NW + wave + 1];
+            const int nst = e1.x - e0.x;
+            if (nst <= 0) continue;
+            const char *region = frs + (e0.y - base.y) * 16;
+            Step cur = load_step(region, 0);
+            for (int r = 0; r < nst; ++r) {
+                const Step nxt = load_step(region, r + 1 < nst ? r + 1 : r);
                 const int r0 = cur.rr & 0xffff, r1 = cur.rr >> 16;
                 const int sw0 = swizzle<CPR>(r0), sw1 = swizzle<CPR>(r1);
                 const char *x0 = stage + r0 * PITCH + within;
@@ -470,15 +479,18 @@ bool mma_supported(const grim_bcr_matrix *A) { return A->mma.present; }
 
 static int amax_of(const grim_bcr_matrix *A, int g) { return A->mma.amax[g <= 4 ? 0 : g <= 8 ? 1 : g <= 16 ? 2 : 3]; }
 
-// Compiled launch shapes: 4 consumer waves, 8 producer waves (two teams of 4); per producer
-// SX slots of X and SR slots of records in registers.
-struct MmaShape { int tn, strips, sx, sr; };
+// Compiled launch shapes.  Groups of 4 strips use 4 consumer waves, larger groups 8 (LDS reads
+// per MFMA are high, so a second consumer wave per SIMD hides their latency); always 8
+// producer waves (two teams of 4), each holding SX slots of X and SR slots of records.
+struct MmaShape { int tn, strips, nw, sx, sr; };
 static bool mma_shape(int BR, int tn, int strips, MmaShape *out) {
     const int sx = tn == 32 ? 4 : tn == 64 ? 8 : tn == 128 ? 16 : 0;      // 256 staged rows
-    const int sr = strips == 4 ? 8 : strips == 8 ? 12 : strips == 16 ? 16 : 0;
+    const int sr = strips == 4 ? 8 : strips == 8 ? 8 : strips == 16 ? 12 : 0;
     if (!sx || !sr) return false;
-    if (BR == 32 && (strips / 4) * (tn / 32) > 4) return false;            // accumulator registers
-    *out = MmaShape{tn, strips, sx, sr};
+    if (tn == 128 && strips != 4) return false;
+    const int nw = strips == 4 ? 4 : 8;
+    if (BR == 32 && (strips / nw) * (tn / 32) > 4) return false;           // accumulator registers
+    *out = MmaShape{tn, strips, nw, sx, sr};
     return true;
 }
 static bool mma_shape_fits(const grim_bcr_matrix *A, int tn, int strips) {
@@ -486,18 +498,18 @@ static bool mma_shape_fits(const grim_bcr_matrix *A, int tn, int strips) {
     if (!mma_shape(A->BR, tn, strips, &sh)) return false;
     const int rps = 1024 / (tn * 2), amax = amax_of(A, strips);
     if ((A->mma.chunk_rows + rps - 1) / rps > 4 * sh.sx) return false;
-    if ((amax * kRecBytes + 1023) / 1024 > 4 * sh.sr) return false;
-    return 2 * (int64_t)mma_stage_bytes(A->mma.chunk_rows, tn * 2, amax) + (int64_t)A->mma.nchunks * (strips + 1) * 4 <= 160 * 1024;
+    if ((amax * 16 + 1023) / 1024 > 4 * sh.sr) return false;
+    return 2 * (int64_t)mma_stage_bytes(A->mma.chunk_rows, tn * 2, amax) + (int64_t)A->mma.nchunks * (strips + 1) * 8 <= 160 * 1024;
 }
 
-template <bool BF16, int BR, int NT, int SPW, int SX, int SR>
+template <bool BF16, int BR, int NT, int SPW, int NW, int SX, int SR>
 static grim_status launch_mma_inst(const MmaParams &p, hipStream_t stream) {
     constexpr int TN = NT * (BR == 16 ? 16 : 32);
-    const size_t lds = 2 * (size_t)mma_stage_bytes(p.chunk_rows, TN * 2, p.amax) + (size_t)p.nchunks * (4 * SPW + 1) * 4;
+    const size_t lds = 2 * (size_t)mma_stage_bytes(p.chunk_rows, TN * 2, p.amax) + (size_t)p.nchunks * (NW * SPW + 1) * 8;
     const int64_t tiles8 = ((int64_t)p.ntiles + 7) / 8 * 8;
     const int64_t nwg = tiles8 * p.ngroups;
     if (nwg > 0x7fffffff) return GRIM_ERR_SHAPE;
-    auto kern = bcr_spmm_mma<BF16, BR, NT, SPW, 4, 8, SX, SR>;
+    auto kern = bcr_spmm_mma<BF16, BR, NT, SPW, NW, 8, SX, SR>;
     static bool attr_done = false;    // raising a kernel's LDS limit is needed once per process
     if (lds > 64 * 1024 && !attr_done) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess) {
@@ -506,31 +518,26 @@ static grim_status launch_mma_inst(const MmaParams &p, hipStream_t stream) {
         }
         attr_done = true;
     }
-    hipLaunchKernelGGL(kern, dim3((unsigned)nwg), dim3(12 * 64), lds, stream, p);
+    hipLaunchKernelGGL(kern, dim3((unsigned)nwg), dim3((NW + 8) * 64), lds, stream, p);
     return hipGetLastError() == hipSuccess ? GRIM_OK : GRIM_ERR_DEVICE;
 }
 
 template <bool BF16, int BR>
 static grim_status launch_mma_br(MmaParams &p, const grim_bcr_matrix *A, int tile_n, int strips, hipStream_t stream) {
     constexpr int NSUB = BR == 16 ? 16 : 32;
-    const int nt = tile_n / NSUB, spw = strips / 4;
     p.ntiles = (int32_t)((p.N + tile_n - 1) / tile_n);
     p.ngroups = (p.nbr + strips - 1) / strips;
     p.amax = amax_of(A, strips);
-#define GRIM_CASE(TN_, G_, SX_, SR_) \
-    if (tile_n == TN_ && strips == G_) return launch_mma_inst<BF16, BR, TN_ / NSUB, G_ / 4, SX_, SR_>(p, stream);
-#ifdef GRIM_FEW_SHAPES   /* development builds: one shape */
-    GRIM_CASE(64, 4, 8, 8)
+#define GRIM_CASE(TN_, G_, NW_, SX_, SR_) \
+    if (tile_n == TN_ && strips == G_) return launch_mma_inst<BF16, BR, TN_ / NSUB, G_ / NW_, NW_, SX_, SR_>(p, stream);
+#ifdef GRIM_FEW_SHAPES   /* development builds: two shapes */
+    GRIM_CASE(64, 4, 4, 8, 8) GRIM_CASE(64, 16, 8, 8, 12)
 #else
-    GRIM_CASE(32, 4, 4, 8) GRIM_CASE(32, 8, 4, 12) GRIM_CASE(32, 16, 4, 16)
-    GRIM_CASE(64, 4, 8, 8) GRIM_CASE(64, 8, 8, 12)
-    GRIM_CASE(128, 4, 16, 8)
-    if constexpr (BR == 16) {
-        GRIM_CASE(64, 16, 8, 16) GRIM_CASE(128, 8, 16, 12) GRIM_CASE(128, 16, 16, 16)
-    }
+    GRIM_CASE(32, 4, 4, 4, 8) GRIM_CASE(32, 8, 8, 4, 8) GRIM_CASE(32, 16, 8, 4, 12)
+    GRIM_CASE(64, 4, 4, 8, 8) GRIM_CASE(64, 8, 8, 8, 8) GRIM_CASE(64, 16, 8, 8, 12)
+    GRIM_CASE(128, 4, 4, 16, 8)
 #endif
 #undef GRIM_CASE
-    (void)nt; (void)spw;
     return GRIM_ERR_UNSUPPORTED;
 }
 
@@ -557,6 +564,7 @@ grim_status launch_spmm_mma(const grim_bcr_matrix *A, const void *X, int64_t N, 
     MmaParams p;
     p.recs = A->mma.d_recs;
     p.cptr = A->mma.d_cptr;
+    p.bptr = A->mma.d_bptr;
     p.strip_order = A->dev.strip_order;
     p.X = static_cast<const unsigned short *>(X);
     p.Y = Y;
