@@ -248,9 +248,17 @@ __global__ void __launch_bounds__((NW + NP) * 64) bcr_spmm_mma(MmaParams p) {
         const int lrow = lane / CPR;
         const int c = (lane % CPR) ^ swizzle<CPR>(lrow);      // slots are RPS rows apart: same swizzle
         const int64_t n = n0 + c * 8;
-        // Interior tiles of 16-byte-aligned X take the pipelined path: plain 16-byte loads, no
-        // test or merge after a load, so all loads of a chunk are in flight together.
-        const bool fast = p.xvec == 8 && n0 + TN <= p.N;
+        // Lanes whose 8 columns lie inside the row take the pipelined path when the rows of X are
+        // at least 8-byte aligned: plain 16-byte (or two 8-byte) loads into registers, no test or
+        // merge after a load, so all loads of a chunk are in flight together.  Lanes straddling the
+        // end of the row (N not a multiple of 8) or unaligned rows are staged element-wise when the
+        // chunk is written; lanes past the end of the row stage nothing (their columns are never
+        // stored).
+        const bool full = p.xvec >= 4 && n + 8 <= p.N;
+        const bool part = !full && n < p.N;
+        const bool wide = p.xvec == 8;
+        // interior tile of 16-byte-aligned X: every lane is full, no per-lane control flow at all
+        const bool all_wide = wide && n0 + TN <= p.N;
         u32x4 RX[SX], RR[SR];
 
         struct Shape { int xs, nrs, rows; int64_t k0, rbyte; };
@@ -282,14 +290,34 @@ __global__ void __launch_bounds__((NW + NP) * 64) bcr_spmm_mma(MmaParams p) {
                 const int sl = mem + i * NM;
                 if (sl < h.nrs) RR[i] = *reinterpret_cast<const u32x4 *>(rsrc + (int64_t)sl * 1024);
             }
-            if (fast) {
-                // rows past the end of the chunk are clamped to its last row (never stored / read)
+            if (all_wide) {
                 const unsigned short *xsrc = p.X + h.k0 * p.ldx + n;
 #pragma unroll
                 for (int i = 0; i < SX; ++i) {
                     int row = (mem + i * NM) * RPS + lrow;
                     row = row < h.rows ? row : h.rows - 1;
                     RX[i] = *reinterpret_cast<const u32x4 *>(xsrc + (int64_t)row * p.ldx);
+                }
+            } else if (full) {
+                // rows past the end of the chunk are clamped to its last row (never stored / read)
+                const unsigned short *xsrc = p.X + h.k0 * p.ldx + n;
+                if (wide) {
+#pragma unroll
+                    for (int i = 0; i < SX; ++i) {
+                        int row = (mem + i * NM) * RPS + lrow;
+                        row = row < h.rows ? row : h.rows - 1;
+                        RX[i] = *reinterpret_cast<const u32x4 *>(xsrc + (int64_t)row * p.ldx);
+                    }
+                } else {
+#pragma unroll
+                    for (int i = 0; i < SX; ++i) {
+                        int row = (mem + i * NM) * RPS + lrow;
+                        row = row < h.rows ? row : h.rows - 1;
+                        const unsigned short *g = xsrc + (int64_t)row * p.ldx;
+                        const uint2 a = *reinterpret_cast<const uint2 *>(g);
+                        const uint2 b = *reinterpret_cast<const uint2 *>(g + 4);
+                        RX[i].x = a.x; RX[i].y = a.y; RX[i].z = b.x; RX[i].w = b.y;
+                    }
                 }
             }
         };
@@ -301,33 +329,28 @@ __global__ void __launch_bounds__((NW + NP) * 64) bcr_spmm_mma(MmaParams p) {
                 const int sl = mem + i * NM;
                 if (sl < h.nrs) *reinterpret_cast<u32x4 *>(sbase + xbytes + sl * 1024 + lane * 16) = RR[i];
             }
-            if (fast) {
+            if (all_wide) {
 #pragma unroll
                 for (int i = 0; i < SX; ++i) {
                     const int sl = mem + i * NM;
                     if (sl * RPS + lrow < h.rows) *reinterpret_cast<u32x4 *>(sbase + sl * 1024 + lane * 16) = RX[i];
                 }
-            } else {
-                // edge tile (row tail) or rows of X not 16-byte aligned: guarded loads, element-wise
-                // where needed, staged synchronously
+            } else if (full) {
+#pragma unroll
+                for (int i = 0; i < SX; ++i) {
+                    const int sl = mem + i * NM;
+                    if (sl * RPS + lrow < h.rows) *reinterpret_cast<u32x4 *>(sbase + sl * 1024 + lane * 16) = RX[i];
+                }
+            }
+            if (!all_wide && part) {
                 for (int sl = mem; sl < h.xs; sl += NM) {
                     const int row = sl * RPS + lrow;
-                    if (row < h.rows && n < p.N) {
+                    if (row < h.rows) {
                         const unsigned short *g = p.X + (h.k0 + row) * p.ldx + n;
-                        u32x4 v;
-                        if (p.xvec == 8 && n + 8 <= p.N) {
-                            v = *reinterpret_cast<const u32x4 *>(g);
-                        } else if (p.xvec >= 4 && n + 8 <= p.N) {
-                            const uint2 a = *reinterpret_cast<const uint2 *>(g);
-                            const uint2 b = *reinterpret_cast<const uint2 *>(g + 4);
-                            v = u32x4{a.x, a.y, b.x, b.y};
-                        } else {
-                            unsigned int w[4] = {0u, 0u, 0u, 0u};
-                            for (int e = 0; e < 8; ++e)
-                                if (n + e < p.N) w[e >> 1] |= (unsigned int)g[e] << ((e & 1) * 16);
-                            v = u32x4{w[0], w[1], w[2], w[3]};
-                        }
-                        *reinterpret_cast<u32x4 *>(sbase + sl * 1024 + lane * 16) = v;
+                        unsigned int w[4] = {0u, 0u, 0u, 0u};
+                        for (int e = 0; e < 8; ++e)
+                            if (n + e < p.N) w[e >> 1] |= (unsigned int)g[e] << ((e & 1) * 16);
+                        *reinterpret_cast<u32x4 *>(sbase + sl * 1024 + lane * 16) = u32x4{w[0], w[1], w[2], w[3]};
                     }
                 }
             }
@@ -546,19 +569,31 @@ grim_status launch_spmm_mma(const grim_bcr_matrix *A, const void *X, int64_t N, 
     if (!A->mma.present) return GRIM_ERR_UNSUPPORTED;
     if (tile_n != 0 && tile_n != 32 && tile_n != 64 && tile_n != 128) return GRIM_ERR_UNSUPPORTED;
     if (strips_per_wg != 0 && strips_per_wg != 4 && strips_per_wg != 8 && strips_per_wg != 16) return GRIM_ERR_UNSUPPORTED;
-    int tn = tile_n ? tile_n : (N <= 32 ? 32 : 64);
-    int strips = strips_per_wg;
-    if (!strips) {
-        // Every strip group of a tile re-reads the tile's rows of X (through L2), so take the
-        // largest compiled group that fits and still leaves about one workgroup per compute unit.
-        const int64_t tiles = (N + tn - 1) / tn;
-        strips = 4;
-        for (int g = 16; g > 4; g >>= 1) {
-            if (A->nbr <= g / 2 || !mma_shape_fits(A, tn, g)) continue;
-            if (tiles * ((A->nbr + g - 1) / g) < 256) continue;
-            strips = g;
-            break;
+    int tn = tile_n, strips = strips_per_wg;
+    if (!tn || !strips) {
+        // Pick the launch shape by bytes through one compute unit: a workgroup streams its tile's
+        // rows of X (64-byte row pieces of a 32-column tile cost about 1.8x per byte), the records
+        // of its strips, and pays a fixed start-up; workgroups beyond 256 run in rounds.
+        const double rec_total = (double)A->mma.recs.size();
+        double best = 0;
+        int best_tn = 0, best_g = 0;
+        for (int t : {64, 32}) {
+            if (tile_n && t != tile_n) continue;
+            for (int g : {16, 8, 4}) {
+                if (strips_per_wg && g != strips_per_wg) continue;
+                if (g > 4 && A->nbr <= g / 2) continue;
+                if (!mma_shape_fits(A, t, g)) continue;
+                const int64_t nwg = ((N + t - 1) / t) * ((A->nbr + g - 1) / g);
+                const double rounds = (double)((nwg + 255) / 256);
+                const double bytes = (double)A->K * t * 2 * (t == 32 ? 1.8 : 1.0) +
+                                     rec_total * (double)(g < A->nbr ? g : A->nbr) / (double)A->nbr + 100e3;
+                const double cost = rounds * bytes;
+                if (!best_tn || cost < best) { best = cost; best_tn = t; best_g = g; }
+            }
         }
+        if (!best_tn) return GRIM_ERR_UNSUPPORTED;
+        tn = best_tn;
+        strips = best_g;
     }
     if (!mma_shape_fits(A, tn, strips)) return GRIM_ERR_UNSUPPORTED;
     MmaParams p;
