@@ -127,8 +127,8 @@ bool build_mma_layout_for(grim_bcr_matrix *A, int32_t chunk_blocks) {
         L.amax[gi] = amax;
     }
     // fits the default launch (64 columns per workgroup, groups of 4 strips)?  The producers move
-    // at most 32 KB of X rows and 32 KB of records per chunk.
-    return L.chunk_rows <= 256 && (int64_t)L.amax[0] * 16 <= 32 * 1024 && L.recs.size() < (size_t(1) << 31) * 16;
+    // at most 32 KB of X rows and 16 KB of records per chunk.
+    return L.chunk_rows <= 256 && (int64_t)L.amax[0] * 16 <= 16 * 1024 && L.recs.size() < (size_t(1) << 31) * 16;
 }
 
 void build_mma_layout(grim_bcr_matrix *A, int32_t chunk_rows_opt) {

@@ -228,7 +228,12 @@ __global__ void __launch_bounds__((NW + NP) * 64) bcr_spmm_mma(MmaParams p) {
     const int tile = (slot / p.ngroups) * 8 + xcd;
     const int group = slot % p.ngroups;
     if (tile >= p.ntiles) return;
-    const int64_t n0 = (int64_t)tile * TN;
+    // A ragged last tile is shifted left to end exactly at N when that keeps its rows 8-byte
+    // aligned: it then overlaps its neighbour and both write the same bits to the shared columns
+    // (a column's sum does not depend on the tile that computes it), and no lane has to stage a
+    // partial 16-byte piece element by element.
+    int64_t n0 = (int64_t)tile * TN;
+    if (n0 + TN > p.N && p.N >= TN && ((p.N - TN) & 3) == 0) n0 = p.N - TN;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -256,7 +261,7 @@ __global__ void __launch_bounds__((NW + NP) * 64) bcr_spmm_mma(MmaParams p) {
         // stored).
         const bool full = p.xvec >= 4 && n + 8 <= p.N;
         const bool part = !full && n < p.N;
-        const bool wide = p.xvec == 8;
+        const bool wide = p.xvec == 8 && (n0 & 7) == 0;
         // interior tile of 16-byte-aligned X: every lane is full, no per-lane control flow at all
         const bool all_wide = wide && n0 + TN <= p.N;
         u32x4 RX[SX], RR[SR];
@@ -508,7 +513,7 @@ static int amax_of(const grim_bcr_matrix *A, int g) { return A->mma.amax[g <= 4 
 struct MmaShape { int tn, strips, nw, sx, sr; };
 static bool mma_shape(int BR, int tn, int strips, MmaShape *out) {
     const int sx = tn == 32 ? 4 : tn == 64 ? 8 : tn == 128 ? 16 : 0;      // 256 staged rows
-    const int sr = strips == 4 ? 8 : strips == 8 ? 8 : strips == 16 ? 12 : 0;
+    const int sr = strips == 4 ? 4 : strips == 8 ? 8 : strips == 16 ? 12 : 0;
     if (!sx || !sr) return false;
     if (tn == 128 && strips != 4) return false;
     const int nw = strips == 4 ? 4 : 8;
@@ -554,11 +559,11 @@ static grim_status launch_mma_br(MmaParams &p, const grim_bcr_matrix *A, int til
 #define GRIM_CASE(TN_, G_, NW_, SX_, SR_) \
     if (tile_n == TN_ && strips == G_) return launch_mma_inst<BF16, BR, TN_ / NSUB, G_ / NW_, NW_, SX_, SR_>(p, stream);
 #ifdef GRIM_FEW_SHAPES   /* development builds: two shapes */
-    GRIM_CASE(64, 4, 4, 8, 8) GRIM_CASE(64, 16, 8, 8, 12)
+    GRIM_CASE(64, 4, 4, 8, 4) GRIM_CASE(64, 16, 8, 8, 12)
 #else
-    GRIM_CASE(32, 4, 4, 4, 8) GRIM_CASE(32, 8, 8, 4, 8) GRIM_CASE(32, 16, 8, 4, 12)
-    GRIM_CASE(64, 4, 4, 8, 8) GRIM_CASE(64, 8, 8, 8, 8) GRIM_CASE(64, 16, 8, 8, 12)
-    GRIM_CASE(128, 4, 4, 16, 8)
+    GRIM_CASE(32, 4, 4, 4, 4) GRIM_CASE(32, 8, 8, 4, 8) GRIM_CASE(32, 16, 8, 4, 12)
+    GRIM_CASE(64, 4, 4, 8, 4) GRIM_CASE(64, 8, 8, 8, 8) GRIM_CASE(64, 16, 8, 8, 12)
+    GRIM_CASE(128, 4, 4, 16, 4)
 #endif
 #undef GRIM_CASE
     return GRIM_ERR_UNSUPPORTED;
