@@ -36,6 +36,7 @@ struct GemvParams {
     float *y;
     int64_t x_stride, y_stride, ldx, ldy;
     int32_t xvec16;          // x is contiguous and 16-byte aligned: copy with 16-byte loads
+    int32_t sps;             // wave kernel: consecutive strips per wave
 #ifdef GRIM_DBG
     long long *dbg;
 #endif
@@ -64,6 +65,26 @@ constexpr int kWLoads = 8;           // 16-byte weight loads per thread per segm
 constexpr int kGemvWBytes = kWLoads * 256 * 16;
 
 typedef unsigned int gu32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int gu32x2 __attribute__((ext_vector_type(2)));
+
+// Pointers read out of a descriptor in memory carry no address space, and loads through them
+// would be generic ("flat") loads, which also tick the counter that LDS traffic is waited on.
+// Everything the descriptors point to is device global memory, so the kernels say so.
+#define GRIM_GLOBAL __attribute__((address_space(1)))
+struct GemvGlobal {
+    const GRIM_GLOBAL char *weights;
+    const GRIM_GLOBAL unsigned int *masks;
+    const GRIM_GLOBAL unsigned int *woff;
+    const GRIM_GLOBAL int *strip_order;
+};
+__device__ __forceinline__ GemvGlobal to_global(const GemvDesc &d) {
+    GemvGlobal g;
+    g.weights = (const GRIM_GLOBAL char *)d.weights;
+    g.masks = (const GRIM_GLOBAL unsigned int *)d.masks;
+    g.woff = (const GRIM_GLOBAL unsigned int *)d.woff;
+    g.strip_order = (const GRIM_GLOBAL int *)d.strip_order;
+    return g;
+}
 
 // position of the j-th (0-based) set bit of m; j < popcount(m)
 __device__ __forceinline__ int nth_set_bit(unsigned int m, int j) {
@@ -81,6 +102,23 @@ __device__ __forceinline__ int nth_set_bit(unsigned int m, int j) {
 }
 
 __host__ __device__ inline int gemv_xg_stride(int kcmax, int B) { return ((kcmax + 7) & ~7) * B; }
+
+// Wave kernel: elements between the private gathered-x rows of neighbouring lanes.  An odd
+// multiple of 8 bytes, so that the 64 lanes' 8-byte reads spread over all LDS banks.
+__host__ __device__ inline int wave_xg_stride(int kcmax, int esz) {
+    int units = (kcmax * esz + 7) / 8;      // 8-byte units per row
+    if (!(units & 1)) ++units;
+    return units * 8 / esz;
+}
+
+// The staged weights of a strip are one linear byte range; lane l works on block l, so at any
+// moment the lanes read addresses one block size apart -- for most block sizes that is a
+// handful of LDS banks.  XOR-ing the 16-byte vector index with higher bits of itself scatters
+// them over the banks; writer and readers apply the same permutation.
+__device__ __forceinline__ unsigned int wave_swz(unsigned int byte_addr) {
+    const unsigned int v = byte_addr >> 4;
+    return ((v ^ ((v >> 3) & 7u)) << 4) | (byte_addr & 15u);
+}
 
 template <int DT, int B, int VEC>
 __global__ void __launch_bounds__(256, (B == 1 ? 6 : 1)) bcr_spmv(GemvParams p) {
@@ -106,10 +144,10 @@ __global__ void __launch_bounds__(256, (B == 1 ? 6 : 1)) bcr_spmv(GemvParams p) 
     const int tid = threadIdx.x;
     const int64_t t = blockIdx.x;            // stored strip
     const int64_t mi = blockIdx.y;           // matrix of the group
-    const GemvDesc d = p.table ? p.table[mi] : p.single;
-    const char *W = static_cast<const char *>(d.weights);
-    const T *x = static_cast<const T *>(p.x) + mi * p.x_stride;
-    float *y = p.y + mi * p.y_stride;
+    const GemvGlobal d = to_global(p.table ? p.table[mi] : p.single);
+    const GRIM_GLOBAL char *W = d.weights;
+    const GRIM_GLOBAL T *x = (const GRIM_GLOBAL T *)p.x + mi * p.x_stride;
+    GRIM_GLOBAL float *y = (GRIM_GLOBAL float *)p.y + mi * p.y_stride;
     const int lpb = 1 << p.lpb_shift;
 
     // reducer role: thread -> (block range sg, output o = r * B + b)
@@ -127,7 +165,7 @@ __global__ void __launch_bounds__(256, (B == 1 ? 6 : 1)) bcr_spmv(GemvParams p) 
         //         every load is issued before any is used ----
         unsigned int m0 = 0, m1 = 0, wo = 0;
         if (tid < nb) {
-            const uint2 mm = *reinterpret_cast<const uint2 *>(d.masks + 2 * (blk0 + tid));
+            const gu32x2 mm = *reinterpret_cast<const GRIM_GLOBAL gu32x2 *>(d.masks + 2 * (blk0 + tid));
             m0 = mm.x;
             m1 = mm.y;
         }
@@ -148,14 +186,14 @@ __global__ void __launch_bounds__(256, (B == 1 ? 6 : 1)) bcr_spmv(GemvParams p) 
         // are rare and run one after the other
         const bool xfast = c0 == 0 && p.xvec16;
         const int nxv = xfast ? p.K * B / (16 / (int)sizeof(T)) : 0;
-        const gu32x4 *xsrc = reinterpret_cast<const gu32x4 *>(x);
+        const GRIM_GLOBAL gu32x4 *xsrc = reinterpret_cast<const GRIM_GLOBAL gu32x4 *>(x);
         gu32x4 wreg[4], xreg[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             if (i * 256 < nvec) {                            // same for the whole workgroup
                 int v = tid + i * 256;
                 v = v < nvec ? v : nvec - 1;                 // clamp: the duplicates are never stored
-                wreg[i] = *reinterpret_cast<const gu32x4 *>(W + a0 + (size_t)v * 16);
+                wreg[i] = *reinterpret_cast<const GRIM_GLOBAL gu32x4 *>(W + a0 + (size_t)v * 16);
             }
         }
 #pragma unroll
@@ -181,7 +219,7 @@ __global__ void __launch_bounds__(256, (B == 1 ? 6 : 1)) bcr_spmv(GemvParams p) 
             if (v < nxv) reinterpret_cast<gu32x4 *>(xs)[v] = xreg[i];
         }
         for (int v = tid + 1024; v < nvec; v += 256)
-            *reinterpret_cast<gu32x4 *>(wl + (size_t)v * 16) = *reinterpret_cast<const gu32x4 *>(W + a0 + (size_t)v * 16);
+            *reinterpret_cast<gu32x4 *>(wl + (size_t)v * 16) = *reinterpret_cast<const GRIM_GLOBAL gu32x4 *>(W + a0 + (size_t)v * 16);
         for (int v = tid + 1024; v < nxv; v += 256) reinterpret_cast<gu32x4 *>(xs)[v] = xsrc[v];
         if (c0 == 0 && !p.xvec16) {
             // x with a leading dimension or unaligned: element by element, layout [k][b]
@@ -289,14 +327,14 @@ __global__ void __launch_bounds__(256, (B == 1 ? 6 : 1)) bcr_spmv(GemvParams p) 
 constexpr int kWaveWLoads = 16;                    // 16 KB of weights per wave per pass
 constexpr int kPartStride = 66;                    // floats per strip row of the partial table
 
-template <int DT, int VEC, int KRMAX>
+template <int DT, int VEC, int KRMAX, int KCMAX>
 __global__ void __launch_bounds__(256) bcr_spmv_wave(GemvParams p) {
     using T = typename GElem<DT>::type;
     struct __attribute__((aligned(sizeof(T) * VEC))) WVec { T v[VEC]; };
     extern __shared__ __attribute__((aligned(16))) char smem[];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int xgs = gemv_xg_stride(p.kcmax, 1);
+    const int xgs = wave_xg_stride(KCMAX, (int)sizeof(T));
     const int xbytes = (p.K * (int)sizeof(T) + 15) & ~15;
     const int region = p.wbytes + 64 * xgs * (int)sizeof(T);      // per wave: weights / partial table, gathered x
     T *xs = reinterpret_cast<T *>(smem);
@@ -304,18 +342,17 @@ __global__ void __launch_bounds__(256) bcr_spmv_wave(GemvParams p) {
     float *part = reinterpret_cast<float *>(wl);                  // reuses the weights' space
     T *xg = reinterpret_cast<T *>(wl + p.wbytes) + lane * xgs;    // this lane's gathered x
 
-    const int64_t t = (int64_t)blockIdx.x * 4 + wave;             // stored strip of this wave
     const int64_t mi = blockIdx.y;
-    const GemvDesc d = p.table ? p.table[mi] : p.single;
-    const char *W = static_cast<const char *>(d.weights);
-    const T *x = static_cast<const T *>(p.x) + mi * p.x_stride;
-    float *y = p.y + mi * p.y_stride;
+    const GemvGlobal d = to_global(p.table ? p.table[mi] : p.single);
+    const GRIM_GLOBAL char *W = d.weights;
+    const GRIM_GLOBAL T *x = (const GRIM_GLOBAL T *)p.x + mi * p.x_stride;
+    GRIM_GLOBAL float *y = (GRIM_GLOBAL float *)p.y + mi * p.y_stride;
 
     GEMV_STAMP(0);
     // x -> LDS, once per workgroup
     if (p.xvec16) {
         const int nxv = p.K * (int)sizeof(T) / 16;
-        const gu32x4 *xsrc = reinterpret_cast<const gu32x4 *>(x);
+        const GRIM_GLOBAL gu32x4 *xsrc = reinterpret_cast<const GRIM_GLOBAL gu32x4 *>(x);
         gu32x4 xreg[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i)
@@ -335,21 +372,32 @@ __global__ void __launch_bounds__(256) bcr_spmv_wave(GemvParams p) {
     }
     __syncthreads();
     GEMV_STAMP(1);
-    if (t >= p.nbr_total) return;
+    // This wave's strips: sps consecutive stored strips, each cut into segments of at most
+    // seg_blocks column blocks.  The (strip, segment) items are processed in order; the loads of
+    // item i+1 are issued before the arithmetic of item i, so that they are in flight behind it.
+    const int nsegs = (p.nbc + p.seg_blocks - 1) / p.seg_blocks;
+    const int64_t t0 = ((int64_t)blockIdx.x * 4 + wave) * p.sps;
+    if (t0 >= p.nbr_total) return;
+    const int nstrips = p.nbr_total - t0 < p.sps ? (int)(p.nbr_total - t0) : p.sps;
+    const int nitems = nstrips * nsegs;
 
-    const int r_out = lane & 31, half = lane >> 5;
-    float yacc = 0.f;
-    for (int c0 = 0; c0 < p.nbc; c0 += p.seg_blocks) {
-        const int nb = p.nbc - c0 < p.seg_blocks ? p.nbc - c0 : p.seg_blocks;
-        const int64_t blk0 = t * p.nbc + c0;
+    struct Item {
+        unsigned int rm, cm;     // this lane's block: kept rows / kept columns
+        unsigned int wblk;       // byte address of the block in the staged range
+        int nvec;                // 16-byte vectors of the staged range
+        int c0;                  // first column block of the segment
+        int srow;                // original strip index (read when the strip's last segment is fetched)
+    };
+    gu32x4 wreg[kWaveWLoads];
+    auto fetch = [&](int it, Item &I) {
+        const int sn = it / nsegs;
+        const int sg = it - sn * nsegs;
+        const int64_t t = t0 + sn;
+        I.c0 = sg * p.seg_blocks;
+        const int nb = p.nbc - I.c0 < p.seg_blocks ? p.nbc - I.c0 : p.seg_blocks;
+        const int64_t blk0 = t * p.nbc + I.c0;
         const bool valid = lane < nb;
-        unsigned int rm = 0, cm = 0, wo = 0;
-        if (valid) {
-            const uint2 mm = *reinterpret_cast<const uint2 *>(d.masks + 2 * (blk0 + lane));
-            rm = mm.x;
-            cm = mm.y;
-        }
-        unsigned int wstart, wend;
+        unsigned int wstart, wend, wo = 0;
         if (p.ukr >= 0) {
             const unsigned int u = (unsigned int)(p.ukr * p.ukc);
             wstart = (unsigned int)blk0 * u;
@@ -362,30 +410,55 @@ __global__ void __launch_bounds__(256) bcr_spmv_wave(GemvParams p) {
         }
         const unsigned int bstart = wstart * (unsigned int)sizeof(T), bend = wend * (unsigned int)sizeof(T);
         const unsigned int a0 = bstart & ~15u;
-        const int nvec = (int)((bend - a0 + 15u) >> 4);          // <= kWaveWLoads * 64 by construction
-        gu32x4 wreg[kWaveWLoads];
+        I.nvec = (int)((bend - a0 + 15u) >> 4);                 // <= kWaveWLoads * 64 by construction
+        I.wblk = (bstart - a0) + wo * (unsigned int)sizeof(T);
 #pragma unroll
         for (int i = 0; i < kWaveWLoads; ++i) {
-            if (i * 64 < nvec) {
+            if (i * 64 < I.nvec) {
                 int v = lane + i * 64;
-                v = v < nvec ? v : nvec - 1;
-                wreg[i] = *reinterpret_cast<const gu32x4 *>(W + a0 + (size_t)v * 16);
+                v = v < I.nvec ? v : I.nvec - 1;
+                wreg[i] = *reinterpret_cast<const GRIM_GLOBAL gu32x4 *>(W + a0 + (size_t)v * 16);
             }
         }
-        GEMV_STAMP(2);
+        I.rm = 0;
+        I.cm = 0;
+        if (valid) {
+            const gu32x2 mm = *reinterpret_cast<const GRIM_GLOBAL gu32x2 *>(d.masks + 2 * (blk0 + lane));
+            I.rm = mm.x;
+            I.cm = mm.y;
+        }
+        I.srow = sg == nsegs - 1 ? d.strip_order[t] : 0;
+    };
+
+    const int r_out = lane & 31, half = lane >> 5;
+    float yacc = 0.f;
+    Item cur, nxt;
+    fetch(0, cur);
+    GEMV_STAMP(2);
+    for (int it = 0; it < nitems; ++it) {
+        const unsigned int rm = cur.rm, cm = cur.cm;
 #pragma unroll
         for (int i = 0; i < kWaveWLoads; ++i) {
-            if (i * 64 < nvec) {
+            if (i * 64 < cur.nvec) {
                 const int v = lane + i * 64;
-                if (v < nvec) *reinterpret_cast<gu32x4 *>(wl + (size_t)v * 16) = wreg[i];
+                if (v < cur.nvec) *reinterpret_cast<gu32x4 *>(wl + wave_swz((unsigned int)v * 16u)) = wreg[i];
             }
         }
         __builtin_amdgcn_wave_barrier();
         GEMV_STAMP(3);
-        // gather this block's kept columns of x
+        nxt = cur;
+        if (it + 1 < nitems) fetch(it + 1, nxt);
+        // gather this block's kept columns of x into the lane's private row, zero beyond them
         const int kr = __builtin_popcount(rm), kc = __builtin_popcount(cm);
         {
-            const T *xb = xs + (c0 + lane) * p.BC;
+#pragma unroll
+            for (int g = 0; g < KCMAX / VEC; ++g) {
+                WVec z;
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) z.v[v] = T(0);
+                *reinterpret_cast<WVec *>(xg + g * VEC) = z;
+            }
+            const T *xb = xs + (cur.c0 + lane) * p.BC;
             unsigned int m = cm;
             for (int j = 0; m; ++j) {
                 const int col = __builtin_ctz(m);
@@ -394,20 +467,30 @@ __global__ void __launch_bounds__(256) bcr_spmv_wave(GemvParams p) {
             }
         }
         GEMV_STAMP(4);
-        // kept rows, one after the other
-        const T *wblk = reinterpret_cast<const T *>(wl + (bstart - a0)) + wo;
+        // Kept rows, one after the other, fully unrolled and free of control flow so that the LDS
+        // reads of many rows are in flight together: rows past this block's count re-read row 0
+        // and are not stored; weights past this block's column count may be anything in the
+        // staged range and are replaced by zeros before they are used.
+        const unsigned int wblk = cur.wblk;
+        WVec xv[KCMAX / VEC];
+#pragma unroll
+        for (int g = 0; g < KCMAX / VEC; ++g) xv[g] = *reinterpret_cast<const WVec *>(xg + g * VEC);
         float acc[KRMAX];
 #pragma unroll
         for (int i = 0; i < KRMAX; ++i) {
-            float a = 0.f;
-            if (i < kr) {
-                const T *wr = wblk + i * kc;
-#pragma unroll 4
-                for (int j = 0; j < kc; j += VEC) {
-                    const WVec wv = *reinterpret_cast<const WVec *>(wr + j);
-                    const WVec xv = *reinterpret_cast<const WVec *>(xg + j);
+            const unsigned int wr = wblk + (unsigned int)((i < kr ? i : 0) * kc) * (unsigned int)sizeof(T);
+            WVec wv[KCMAX / VEC];
 #pragma unroll
-                    for (int v = 0; v < VEC; ++v) a = __builtin_fmaf(g2f<DT>(wv.v[v]), g2f<DT>(xv.v[v]), a);
+            for (int g = 0; g < KCMAX / VEC; ++g)
+                wv[g] = *reinterpret_cast<const WVec *>(wl + wave_swz(wr + (unsigned int)(g * VEC) * (unsigned int)sizeof(T)));
+            float a = 0.f;
+#pragma unroll
+            for (int g = 0; g < KCMAX / VEC; ++g) {
+                const bool on = g * VEC < kc;                     // kc is a multiple of VEC
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) {
+                    const float w = on ? g2f<DT>(wv[g].v[v]) : 0.f;
+                    a = __builtin_fmaf(w, g2f<DT>(xv[g].v[v]), a);
                 }
             }
             acc[i] = a;
@@ -444,44 +527,328 @@ __global__ void __launch_bounds__(256) bcr_spmv_wave(GemvParams p) {
         }
         const float other = __shfl_xor(hs, 32);
         yacc += half == 0 ? hs + other : other + hs;
-        __builtin_amdgcn_wave_barrier();                          // table consumed before the next pass refills LDS
+        __builtin_amdgcn_wave_barrier();                          // table consumed before the next item refills LDS
         GEMV_STAMP(7);
-    }
-    if (half == 0 && r_out < p.BR) {
-        const int64_t row = (int64_t)d.strip_order[t] * p.BR + r_out;
-        y[row * p.ldy] = yacc;
+        if (cur.c0 + p.seg_blocks >= p.nbc) {                     // last segment of a strip
+            if (half == 0 && r_out < p.BR) y[((int64_t)cur.srow * p.BR + r_out) * p.ldy] = yacc;
+            yacc = 0.f;
+        }
+        cur = nxt;
     }
     GEMV_STAMP(8);
 }
 
-template <int DT, int VEC>
-static grim_status launch_wave_kr(const GemvParams &p, int krmax, dim3 grid, size_t lds, hipStream_t stream) {
-#define GRIM_WAVE(KR)                                                                                         \
-    {                                                                                                         \
-        auto kern = bcr_spmv_wave<DT, VEC, KR>;                                                               \
-        static bool attr_done = false;                                                                        \
-        if (lds > 64 * 1024 && !attr_done) {                                                                  \
-            if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess) { \
-                (void)hipGetLastError();                                                                      \
-                return GRIM_ERR_DEVICE;                                                                       \
-            }                                                                                                 \
-            attr_done = true;                                                                                 \
-        }                                                                                                     \
-        hipLaunchKernelGGL(kern, grid, dim3(256), lds, stream, p);                                            \
-        return hipGetLastError() == hipSuccess ? GRIM_OK : GRIM_ERR_DEVICE;                                   \
+template <int DT, int VEC, int KR, int KC>
+static grim_status launch_wave_inst(const GemvParams &p, dim3 grid, size_t lds, hipStream_t stream) {
+    auto kern = bcr_spmv_wave<DT, VEC, KR, KC>;
+    static bool attr_done = false;
+    if (lds > 64 * 1024 && !attr_done) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess) {
+            (void)hipGetLastError();
+            return GRIM_ERR_DEVICE;
+        }
+        attr_done = true;
     }
-    if (krmax <= 8) GRIM_WAVE(8)
-    if (krmax <= 16) GRIM_WAVE(16)
-    GRIM_WAVE(32)
-#undef GRIM_WAVE
+    hipLaunchKernelGGL(kern, grid, dim3(256), lds, stream, p);
+    return hipGetLastError() == hipSuccess ? GRIM_OK : GRIM_ERR_DEVICE;
+}
+
+template <int DT, int VEC>
+static grim_status launch_wave_vec(const GemvParams &p, int krmax, int kcmax, dim3 grid, size_t lds, hipStream_t stream) {
+    if (krmax <= 8) {
+        if (kcmax <= 16) return launch_wave_inst<DT, VEC, 8, 16>(p, grid, lds, stream);
+        return launch_wave_inst<DT, VEC, 8, 32>(p, grid, lds, stream);
+    }
+    if (kcmax <= 16) return launch_wave_inst<DT, VEC, 32, 16>(p, grid, lds, stream);
+    return launch_wave_inst<DT, VEC, 32, 32>(p, grid, lds, stream);
 }
 
 template <int DT>
-static grim_status launch_wave(const GemvParams &p, int vec, int krmax, dim3 grid, size_t lds, hipStream_t stream) {
-    if (vec >= 8 && sizeof(typename GElem<DT>::type) == 2) return launch_wave_kr<DT, 8>(p, krmax, grid, lds, stream);
-    if (vec >= 4) return launch_wave_kr<DT, 4>(p, krmax, grid, lds, stream);
-    if (vec >= 2) return launch_wave_kr<DT, 2>(p, krmax, grid, lds, stream);
-    return launch_wave_kr<DT, 1>(p, krmax, grid, lds, stream);
+static grim_status launch_wave(const GemvParams &p, int vec, int krmax, int kcmax, dim3 grid, size_t lds, hipStream_t stream) {
+    if (vec >= 4) return launch_wave_vec<DT, 4>(p, krmax, kcmax, grid, lds, stream);
+    return launch_wave_vec<DT, 1>(p, krmax, kcmax, grid, lds, stream);
+}
+
+// ------------------------------------------------------------------------------------------
+// One right-hand side, every block keeping exactly KR rows and KC columns (a layer pruned at one
+// rate): the wave-per-strip scheme with every size known at compile time.
+//   - a block is NV 16-byte vectors; the strip's vectors are parked in LDS with one vector of
+//     padding per block when NV is even, so that the lanes' block bases are an odd number of
+//     vectors apart and 16-byte reads at a fixed offset from them hit all banks evenly;
+//   - a lane reads its whole block and its KC activations into registers; two-byte types
+//     multiply pairs with the packed dot-product instruction (fp32 sum, subnormals kept);
+//   - row sums go through the same [strip row][block] table as in the general kernel.
+// ------------------------------------------------------------------------------------------
+typedef _Float16 gh2 __attribute__((ext_vector_type(2)));
+typedef __bf16 gb2 __attribute__((ext_vector_type(2)));
+
+template <int DT, int KR, int KC>
+__global__ void __launch_bounds__(256) bcr_spmv_wave_exact(GemvParams p) {
+    using T = typename GElem<DT>::type;
+    constexpr int ESZ = (int)sizeof(T);
+    constexpr int NV = KR * KC * ESZ / 16;       // 16-byte vectors per block
+    constexpr int PV = NV | 1;                   // LDS stride of a block, in vectors
+    static_assert(KR * KC * ESZ % 16 == 0 && (ESZ == 4 || KC % 2 == 0) && KC <= 32 && KR <= 32, "block shape");
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int xbytes = (p.K * ESZ + 15) & ~15;
+    T *xs = reinterpret_cast<T *>(smem);
+    char *wl = smem + xbytes + wave * p.wbytes;
+    float *part = reinterpret_cast<float *>(wl);                  // reuses the weights' space
+
+    const int64_t mi = blockIdx.y;
+    const GemvGlobal d = to_global(p.table ? p.table[mi] : p.single);
+    const GRIM_GLOBAL char *W = d.weights;
+    const GRIM_GLOBAL T *x = (const GRIM_GLOBAL T *)p.x + mi * p.x_stride;
+    GRIM_GLOBAL float *y = (GRIM_GLOBAL float *)p.y + mi * p.y_stride;
+
+    GEMV_STAMP(0);
+    if (p.xvec16) {
+        const int nxv = p.K * ESZ / 16;
+        const GRIM_GLOBAL gu32x4 *xsrc = reinterpret_cast<const GRIM_GLOBAL gu32x4 *>(x);
+        gu32x4 xreg[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            if (i * 256 < nxv) {
+                int v = tid + i * 256;
+                v = v < nxv ? v : nxv - 1;
+                xreg[i] = xsrc[v];
+            }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int v = tid + i * 256;
+            if (v < nxv) reinterpret_cast<gu32x4 *>(xs)[v] = xreg[i];
+        }
+        for (int v = tid + 1024; v < nxv; v += 256) reinterpret_cast<gu32x4 *>(xs)[v] = xsrc[v];
+    } else {
+        for (int e = tid; e < p.K; e += 256) xs[e] = x[(int64_t)e * p.ldx];
+    }
+    __syncthreads();
+    GEMV_STAMP(1);
+
+    const int nsegs = (p.nbc + p.seg_blocks - 1) / p.seg_blocks;
+    const int64_t t0 = ((int64_t)blockIdx.x * 4 + wave) * p.sps;
+    if (t0 >= p.nbr_total) return;
+    const int nstrips = p.nbr_total - t0 < p.sps ? (int)(p.nbr_total - t0) : p.sps;
+    const int nitems = nstrips * nsegs;
+
+    struct Item {
+        unsigned int rm, cm;
+        int nvec, c0, srow;
+    };
+    gu32x4 wreg[NV];
+    auto fetch = [&](int it, Item &I) {
+        const int sn = it / nsegs;
+        const int sg = it - sn * nsegs;
+        const int64_t t = t0 + sn;
+        I.c0 = sg * p.seg_blocks;
+        const int nb = p.nbc - I.c0 < p.seg_blocks ? p.nbc - I.c0 : p.seg_blocks;
+        const int64_t blk0 = t * p.nbc + I.c0;
+        I.nvec = nb * NV;
+        const GRIM_GLOBAL char *src = W + (size_t)blk0 * (NV * 16);
+        if (nb == 64) {
+#pragma unroll
+            for (int i = 0; i < NV; ++i)
+                wreg[i] = *reinterpret_cast<const GRIM_GLOBAL gu32x4 *>(src + (unsigned int)(lane * 16 + i * 1024));
+        } else {
+#pragma unroll
+            for (int i = 0; i < NV; ++i) {
+                int v = lane + i * 64;
+                v = v < I.nvec ? v : I.nvec - 1;
+                wreg[i] = *reinterpret_cast<const GRIM_GLOBAL gu32x4 *>(src + (unsigned int)(v * 16));
+            }
+        }
+        I.rm = 0;
+        I.cm = KC == 32 ? 0xffffffffu : (1u << (KC & 31)) - 1u;   // idle lanes: any KC columns, no rows
+        if (lane < nb) {
+            const gu32x2 mm = *reinterpret_cast<const GRIM_GLOBAL gu32x2 *>(d.masks + 2 * (blk0 + lane));
+            I.rm = mm.x;
+            I.cm = mm.y;
+        }
+        I.srow = sg == nsegs - 1 ? d.strip_order[t] : 0;
+    };
+
+    float yacc = 0.f;
+    Item cur, nxt;
+    fetch(0, cur);
+    GEMV_STAMP(2);
+    for (int it = 0; it < nitems; ++it) {
+        const unsigned int rm = cur.rm, cm = cur.cm;
+        if (cur.nvec == 64 * NV) {
+#pragma unroll
+            for (int i = 0; i < NV; ++i) {
+                const int v = lane + i * 64;
+                const int slot = PV == NV ? v : v + v / NV;
+                *reinterpret_cast<gu32x4 *>(wl + slot * 16) = wreg[i];
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < NV; ++i) {
+                const int v = lane + i * 64;
+                const int slot = PV == NV ? v : v + v / NV;
+                if (v < cur.nvec) *reinterpret_cast<gu32x4 *>(wl + slot * 16) = wreg[i];
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
+        GEMV_STAMP(3);
+        nxt = cur;
+        if (it + 1 < nitems) fetch(it + 1, nxt);
+
+        // this block's KC activations
+        T xe[KC];
+        {
+            int xblk = cur.c0 + lane;
+            xblk = xblk < p.nbc ? xblk : p.nbc - 1;
+            const T *xb = xs + xblk * p.BC;
+            unsigned int m = cm;
+#pragma unroll
+            for (int j = 0; j < KC; ++j) {
+                const int col = __builtin_ctz(m);                 // KC bits are set
+                m &= m - 1;
+                xe[j] = xb[col];
+            }
+        }
+        gu32x4 w[NV];
+        {
+            const gu32x4 *wb = reinterpret_cast<const gu32x4 *>(wl) + lane * PV;
+#pragma unroll
+            for (int j = 0; j < NV; ++j) w[j] = wb[j];
+        }
+        GEMV_STAMP(4);
+        float acc[KR];
+        if constexpr (DT == GRIM_F32) {
+#pragma unroll
+            for (int i = 0; i < KR; ++i) {
+                float a = 0.f;
+#pragma unroll
+                for (int j = 0; j < KC; ++j) {
+                    const int q = i * KC + j;
+                    a = __builtin_fmaf(__builtin_bit_cast(float, w[q >> 2][q & 3]), xe[j], a);
+                }
+                acc[i] = a;
+            }
+        } else {
+            unsigned int xp[KC / 2];
+#pragma unroll
+            for (int h = 0; h < KC / 2; ++h) {
+                unsigned short lo, hi;
+                __builtin_memcpy(&lo, &xe[2 * h], 2);
+                __builtin_memcpy(&hi, &xe[2 * h + 1], 2);
+                xp[h] = (unsigned int)lo | ((unsigned int)hi << 16);
+            }
+#pragma unroll
+            for (int i = 0; i < KR; ++i) {
+                float a = 0.f;
+#pragma unroll
+                for (int h = 0; h < KC / 2; ++h) {
+                    const int q = i * (KC / 2) + h;
+                    const unsigned int wd = w[q >> 2][q & 3];
+                    if constexpr (DT == GRIM_F16)
+                        a = __builtin_amdgcn_fdot2(__builtin_bit_cast(gh2, wd), __builtin_bit_cast(gh2, xp[h]), a, false);
+                    else
+                        a = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(gb2, wd), __builtin_bit_cast(gb2, xp[h]), a, false);
+                }
+                acc[i] = a;
+            }
+        }
+        __builtin_amdgcn_wave_barrier();                          // every lane holds its block in registers
+        GEMV_STAMP(5);
+        for (int z = lane; z < (p.BR * kPartStride + 3) / 4; z += 64)
+            reinterpret_cast<gu32x4 *>(part)[z] = gu32x4{0u, 0u, 0u, 0u};
+        __builtin_amdgcn_wave_barrier();
+        if (rm) {
+            unsigned int m = rm;
+#pragma unroll
+            for (int i = 0; i < KR; ++i) {
+                const int r = __builtin_ctz(m);                   // KR bits are set
+                m &= m - 1;
+                part[r * kPartStride + lane] = acc[i];
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
+        GEMV_STAMP(6);
+        // Row sums in a fixed order.  Up to 16 strip rows: lanes (row, quarter) add 16 blocks
+        // each, then quarters pair up; more rows: lanes (row, half) add 32 blocks each.
+        float rs;
+        bool writer;
+        int r_out;
+        if (p.BR <= 16) {
+            r_out = lane & 15;
+            const int qd = lane >> 4;
+            float s = 0.f;
+            if (r_out < p.BR) {
+                const float2 *src = reinterpret_cast<const float2 *>(part + r_out * kPartStride + qd * 16);
+#pragma unroll
+                for (int q = 0; q < 8; ++q) {
+                    const float2 v = src[q];
+                    s += v.x;
+                    s += v.y;
+                }
+            }
+            const float s2 = s + __shfl_xor(s, 16);
+            rs = s2 + __shfl_xor(s2, 32);
+            writer = qd == 0;
+        } else {
+            r_out = lane & 31;
+            const int half = lane >> 5;
+            float s = 0.f;
+            if (r_out < p.BR) {
+                const float2 *src = reinterpret_cast<const float2 *>(part + r_out * kPartStride + half * 32);
+#pragma unroll
+                for (int q = 0; q < 16; ++q) {
+                    const float2 v = src[q];
+                    s += v.x;
+                    s += v.y;
+                }
+            }
+            rs = s + __shfl_xor(s, 32);
+            writer = half == 0;
+        }
+        yacc += rs;
+        __builtin_amdgcn_wave_barrier();                          // table consumed before the next item refills LDS
+        GEMV_STAMP(7);
+        if (cur.c0 + p.seg_blocks >= p.nbc) {                     // last segment of a strip
+            if (writer && r_out < p.BR) y[((int64_t)cur.srow * p.BR + r_out) * p.ldy] = yacc;
+            yacc = 0.f;
+        }
+        cur = nxt;
+    }
+    GEMV_STAMP(8);
+}
+
+template <int DT, int KR, int KC>
+static grim_status launch_exact_inst(const GemvParams &p, dim3 grid, size_t lds, hipStream_t stream) {
+    auto kern = bcr_spmv_wave_exact<DT, KR, KC>;
+    static bool attr_done = false;
+    if (lds > 64 * 1024 && !attr_done) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess) {
+            (void)hipGetLastError();
+            return GRIM_ERR_DEVICE;
+        }
+        attr_done = true;
+    }
+    hipLaunchKernelGGL(kern, grid, dim3(256), lds, stream, p);
+    return hipGetLastError() == hipSuccess ? GRIM_OK : GRIM_ERR_DEVICE;
+}
+
+// Compiled (kept rows, kept columns) pairs; a block must be a whole number of 16-byte vectors
+// and at most 24 of them (the block lives in registers).
+template <int DT>
+static grim_status launch_exact(const GemvParams &p, int kr, int kc, dim3 grid, size_t lds, hipStream_t stream) {
+    constexpr int ESZ = (int)sizeof(typename GElem<DT>::type);
+#define GRIM_EXACT(R, C)                                                                   \
+    if constexpr ((R) * (C) * ESZ % 16 == 0 && (R) * (C) * ESZ <= 384)                     \
+        if (kr == (R) && kc == (C)) return launch_exact_inst<DT, R, C>(p, grid, lds, stream);
+#ifdef GRIM_FEW_SHAPES   /* development builds */
+    GRIM_EXACT(8, 12)
+#else
+    GRIM_EXACT(4, 4) GRIM_EXACT(4, 8) GRIM_EXACT(4, 12) GRIM_EXACT(4, 16)
+    GRIM_EXACT(8, 4) GRIM_EXACT(8, 8) GRIM_EXACT(8, 12) GRIM_EXACT(8, 16)
+    GRIM_EXACT(16, 4) GRIM_EXACT(16, 8) GRIM_EXACT(16, 12)
+#endif
+#undef GRIM_EXACT
+    return GRIM_ERR_UNSUPPORTED;
 }
 
 template <int DT, int B>
@@ -522,6 +889,17 @@ static grim_status launch_batch(const GemvParams &p, int batch, int vec, dim3 gr
     return GRIM_ERR_SHAPE;
 }
 
+// Strips a wave of the wave-per-strip kernels walks: 1 when the launch is small, up to 4 while
+// at least 2048 workgroups remain.
+static int wave_strips_per_wave(int64_t count, int64_t nbr) {
+    int sps = 1;
+    while (sps < 4 && count * ((nbr + 4 * sps * 2 - 1) / (4 * sps * 2)) >= 2048) sps *= 2;
+#ifdef GRIM_DBG
+    if (const char *e = getenv("GRIM_SPS")) sps = atoi(e);
+#endif
+    return sps;
+}
+
 grim_status launch_spmv(const GemvDesc *table, const GemvDesc &single, int32_t count, int64_t M, int64_t K, int32_t BR,
                         int32_t BC, int32_t dtype, int32_t ukr, int32_t ukc, int32_t vec, int32_t krmax, int32_t kcmax,
                         const void *x, int64_t x_stride, int32_t batch, int64_t ldx, float *y, int64_t y_stride, int64_t ldy,
@@ -537,6 +915,7 @@ grim_status launch_spmv(const GemvDesc *table, const GemvDesc &single, int32_t c
     p.single = single;
     p.BR = BR; p.BC = BC; p.nbc = (int32_t)(K / BC); p.K = (int32_t)K;
     p.nbr_total = (int32_t)nbr;
+    p.sps = 1;
     p.ukr = ukr; p.ukc = ukc;
     p.krmax = krmax;
     p.kcmax = kcmax;
@@ -560,6 +939,27 @@ grim_status launch_spmv(const GemvDesc *table, const GemvDesc &single, int32_t c
 #endif
     if (batch == 1 && (int64_t)K * esz <= 32 * 1024) {
         // one wave per strip, one lane per block
+        if (ukr > 0 && ukc > 0 && (ukr * ukc * esz) % 16 == 0 && ukr * ukc * esz <= 384) {
+            const int nv = ukr * ukc * esz / 16;
+            GemvParams q = p;
+            q.seg_blocks = 64;
+            int64_t wb = (int64_t)64 * (nv | 1) * 16;
+            const int64_t table = ((int64_t)BR * kPartStride * 4 + 15) & ~int64_t(15);
+            if (wb < table) wb = table;
+            q.wbytes = (int32_t)wb;
+            const size_t wlds = (((size_t)K * esz + 15) & ~size_t(15)) + 4 * (size_t)wb;
+            q.sps = wave_strips_per_wave(count, nbr);
+            dim3 wgrid((unsigned)((nbr + 4 * q.sps - 1) / (4 * q.sps)), (unsigned)count);
+            grim_status st = GRIM_ERR_UNSUPPORTED;
+            if (wlds <= 160 * 1024) {
+                switch (dtype) {
+                    case GRIM_F32: st = launch_exact<GRIM_F32>(q, ukr, ukc, wgrid, wlds, stream); break;
+                    case GRIM_F16: st = launch_exact<GRIM_F16>(q, ukr, ukc, wgrid, wlds, stream); break;
+                    case GRIM_BF16: st = launch_exact<GRIM_BF16>(q, ukr, ukc, wgrid, wlds, stream); break;
+                }
+            }
+            if (st != GRIM_ERR_UNSUPPORTED) return st;
+        }
         int64_t wseg = (kWaveWLoads * 1024 - 32) / blk_bytes;
         if (wseg > 64) wseg = 64;
         if (wseg >= 1) {
@@ -569,13 +969,18 @@ grim_status launch_spmv(const GemvDesc *table, const GemvDesc &single, int32_t c
             const int64_t table = ((int64_t)BR * kPartStride * 4 + 15) & ~int64_t(15);
             if (wb < table) wb = table;
             q.wbytes = (int32_t)wb;
-            const size_t wlds = (((size_t)K * esz + 15) & ~size_t(15)) + 4 * ((size_t)wb + 64 * (size_t)gemv_xg_stride(kcmax, 1) * esz);
+            const size_t wlds = (((size_t)K * esz + 15) & ~size_t(15)) + 4 * ((size_t)wb + 64 * (size_t)wave_xg_stride(kcmax <= 16 ? 16 : 32, esz) * esz) + 256;
             if (wlds <= 160 * 1024) {
-                dim3 wgrid((unsigned)((nbr + 3) / 4), (unsigned)count);
+                // A lone product wants every strip on a wave of its own (latency); many products
+                // at once fill the GPU anyway, and a wave then walks several strips so that the
+                // next strip's weights stream in behind the current strip's arithmetic.
+                const int sps = wave_strips_per_wave(count, nbr);
+                q.sps = sps;
+                dim3 wgrid((unsigned)((nbr + 4 * sps - 1) / (4 * sps)), (unsigned)count);
                 switch (dtype) {
-                    case GRIM_F32: return launch_wave<GRIM_F32>(q, vec, krmax, wgrid, wlds, stream);
-                    case GRIM_F16: return launch_wave<GRIM_F16>(q, vec, krmax, wgrid, wlds, stream);
-                    case GRIM_BF16: return launch_wave<GRIM_BF16>(q, vec, krmax, wgrid, wlds, stream);
+                    case GRIM_F32: return launch_wave<GRIM_F32>(q, vec, krmax, kcmax, wgrid, wlds, stream);
+                    case GRIM_F16: return launch_wave<GRIM_F16>(q, vec, krmax, kcmax, wgrid, wlds, stream);
+                    case GRIM_BF16: return launch_wave<GRIM_BF16>(q, vec, krmax, kcmax, wgrid, wlds, stream);
                 }
             }
         }
