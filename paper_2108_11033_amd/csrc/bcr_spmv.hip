@@ -572,13 +572,26 @@ static grim_status launch_wave(const GemvParams &p, int vec, int krmax, int kcma
 // ------------------------------------------------------------------------------------------
 // One right-hand side, every block keeping exactly KR rows and KC columns (a layer pruned at one
 // rate): the wave-per-strip scheme with every size known at compile time.
-//   - a block is NV 16-byte vectors; the strip's vectors are parked in LDS with one vector of
-//     padding per block when NV is even, so that the lanes' block bases are an odd number of
-//     vectors apart and 16-byte reads at a fixed offset from them hit all banks evenly;
+//   - a block is NV 16-byte vectors; the strip's vectors are parked in LDS with a little
+//     padding so that 16-byte reads at a fixed offset from the lanes' block bases hit all
+//     banks evenly;
 //   - a lane reads its whole block and its KC activations into registers; two-byte types
 //     multiply pairs with the packed dot-product instruction (fp32 sum, subnormals kept);
 //   - row sums go through the same [strip row][block] table as in the general kernel.
 // ------------------------------------------------------------------------------------------
+// Lanes read their blocks with 16-byte loads at a common offset from bases NV vectors apart;
+// 16 such vectors span the LDS banks.  When NV shares a factor g with 16 the bases of 16
+// neighbouring lanes fall on only 16/g distinct bank groups, so one vector of padding goes
+// after every 16/g blocks, which shifts each run of 16/g lanes onto its own group.
+__host__ __device__ constexpr int exact_pad_period(int nv) {
+    int g = 1;
+    while (g < 16 && nv % (g * 2) == 0) g *= 2;
+    return g == 1 ? 0 : 16 / g;
+}
+__host__ __device__ constexpr int exact_region_vectors(int nv) {
+    return 64 * nv + (exact_pad_period(nv) ? 64 / exact_pad_period(nv) : 0);
+}
+
 typedef _Float16 gh2 __attribute__((ext_vector_type(2)));
 typedef __bf16 gb2 __attribute__((ext_vector_type(2)));
 
@@ -587,7 +600,7 @@ __global__ void __launch_bounds__(256) bcr_spmv_wave_exact(GemvParams p) {
     using T = typename GElem<DT>::type;
     constexpr int ESZ = (int)sizeof(T);
     constexpr int NV = KR * KC * ESZ / 16;       // 16-byte vectors per block
-    constexpr int PV = NV | 1;                   // LDS stride of a block, in vectors
+    constexpr int PB = exact_pad_period(NV);     // one vector of padding after every PB blocks (0: none)
     static_assert(KR * KC * ESZ % 16 == 0 && (ESZ == 4 || KC % 2 == 0) && KC <= 32 && KR <= 32, "block shape");
     extern __shared__ __attribute__((aligned(16))) char smem[];
     const int tid = threadIdx.x, lane = tid & 63;
@@ -603,35 +616,11 @@ __global__ void __launch_bounds__(256) bcr_spmv_wave_exact(GemvParams p) {
     const GRIM_GLOBAL T *x = (const GRIM_GLOBAL T *)p.x + mi * p.x_stride;
     GRIM_GLOBAL float *y = (GRIM_GLOBAL float *)p.y + mi * p.y_stride;
 
-    GEMV_STAMP(0);
-    if (p.xvec16) {
-        const int nxv = p.K * ESZ / 16;
-        const GRIM_GLOBAL gu32x4 *xsrc = reinterpret_cast<const GRIM_GLOBAL gu32x4 *>(x);
-        gu32x4 xreg[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-            if (i * 256 < nxv) {
-                int v = tid + i * 256;
-                v = v < nxv ? v : nxv - 1;
-                xreg[i] = xsrc[v];
-            }
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int v = tid + i * 256;
-            if (v < nxv) reinterpret_cast<gu32x4 *>(xs)[v] = xreg[i];
-        }
-        for (int v = tid + 1024; v < nxv; v += 256) reinterpret_cast<gu32x4 *>(xs)[v] = xsrc[v];
-    } else {
-        for (int e = tid; e < p.K; e += 256) xs[e] = x[(int64_t)e * p.ldx];
-    }
-    __syncthreads();
-    GEMV_STAMP(1);
 
     const int nsegs = (p.nbc + p.seg_blocks - 1) / p.seg_blocks;
     const int64_t t0 = ((int64_t)blockIdx.x * 4 + wave) * p.sps;
-    if (t0 >= p.nbr_total) return;
-    const int nstrips = p.nbr_total - t0 < p.sps ? (int)(p.nbr_total - t0) : p.sps;
-    const int nitems = nstrips * nsegs;
+    const int nstrips = p.nbr_total - t0 < p.sps ? (int)(p.nbr_total - t0) : p.sps;   // <= 0: nothing to do
+    const int nitems = nstrips > 0 ? nstrips * nsegs : 0;
 
     struct Item {
         unsigned int rm, cm;
@@ -669,29 +658,79 @@ __global__ void __launch_bounds__(256) bcr_spmv_wave_exact(GemvParams p) {
         I.srow = sg == nsegs - 1 ? d.strip_order[t] : 0;
     };
 
-    float yacc = 0.f;
+    // output lanes: (strip row, lane group); 4 groups of 16 lanes up to 16 strip rows, else 2 of 32
+    const int ngrp = p.BR <= 16 ? 4 : 2;
+    const int r_out = p.BR <= 16 ? lane & 15 : lane & 31;
+    const int grp = p.BR <= 16 ? lane >> 4 : lane >> 5;
+    // Finished strips wait in registers -- lane group g keeps the strips numbered g, g + ngrp, ...
+    // since the last store -- and go out kKeep * ngrp strips at a time, or when the wave is done:
+    // few, large stores, whole cache lines when the strips are neighbours in the original order
+    // as well (as equal-work strips are), and for launches of one round of workgroups all at the
+    // end, where they no longer cut into the stream of weight reads.
+    constexpr int kKeep = 4;
+    float yacc = 0.f, ykeep[kKeep];
+    int rowkeep[kKeep], npend = 0;                                // npend: strips kept, not yet stored
+    auto store_kept = [&]() {
+#pragma unroll
+        for (int k = 0; k < kKeep; ++k) {
+            if (grp + k * ngrp < npend && r_out < p.BR) y[((int64_t)rowkeep[k] * p.BR + r_out) * p.ldy] = ykeep[k];
+        }
+        npend = 0;
+    };
+    // x -> LDS, once per workgroup.  Its loads go out first and the first item's right behind
+    // them, so that the weights are already on their way while x is parked.
     Item cur, nxt;
-    fetch(0, cur);
-    GEMV_STAMP(2);
+    GEMV_STAMP(0);
+    if (p.xvec16) {
+        const int nxv = p.K * ESZ / 16;
+        const GRIM_GLOBAL gu32x4 *xsrc = reinterpret_cast<const GRIM_GLOBAL gu32x4 *>(x);
+        gu32x4 xreg[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            if (i * 256 < nxv) {
+                int v = tid + i * 256;
+                v = v < nxv ? v : nxv - 1;
+                xreg[i] = xsrc[v];
+            }
+        if (nitems) fetch(0, cur);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int v = tid + i * 256;
+            if (v < nxv) reinterpret_cast<gu32x4 *>(xs)[v] = xreg[i];
+        }
+        for (int v = tid + 1024; v < nxv; v += 256) reinterpret_cast<gu32x4 *>(xs)[v] = xsrc[v];
+    } else {
+        if (nitems) fetch(0, cur);
+        for (int e = tid; e < p.K; e += 256) xs[e] = x[(int64_t)e * p.ldx];
+    }
+    __syncthreads();
+    GEMV_STAMP(1);
+    if (!nitems) return;
     for (int it = 0; it < nitems; ++it) {
+        GEMV_STAMP(9);
         const unsigned int rm = cur.rm, cm = cur.cm;
         if (cur.nvec == 64 * NV) {
 #pragma unroll
             for (int i = 0; i < NV; ++i) {
                 const int v = lane + i * 64;
-                const int slot = PV == NV ? v : v + v / NV;
+                const int slot = PB ? v + v / (NV * PB) : v;
                 *reinterpret_cast<gu32x4 *>(wl + slot * 16) = wreg[i];
             }
         } else {
 #pragma unroll
             for (int i = 0; i < NV; ++i) {
                 const int v = lane + i * 64;
-                const int slot = PV == NV ? v : v + v / NV;
+                const int slot = PB ? v + v / (NV * PB) : v;
                 if (v < cur.nvec) *reinterpret_cast<gu32x4 *>(wl + slot * 16) = wreg[i];
             }
         }
         __builtin_amdgcn_wave_barrier();
         GEMV_STAMP(3);
+        // Stores and loads complete in no fixed order relative to each other, so waiting for a
+        // load means waiting for every store issued before that wait as well.  The kept sums are
+        // therefore stored here, right after the wait for this item's weights and a whole item
+        // ahead of the next such wait.
+        if (npend == kKeep * ngrp) store_kept();
         nxt = cur;
         if (it + 1 < nitems) fetch(it + 1, nxt);
 
@@ -711,7 +750,7 @@ __global__ void __launch_bounds__(256) bcr_spmv_wave_exact(GemvParams p) {
         }
         gu32x4 w[NV];
         {
-            const gu32x4 *wb = reinterpret_cast<const gu32x4 *>(wl) + lane * PV;
+            const gu32x4 *wb = reinterpret_cast<const gu32x4 *>(wl) + lane * NV + (PB ? lane / PB : 0);
 #pragma unroll
             for (int j = 0; j < NV; ++j) w[j] = wb[j];
         }
@@ -769,16 +808,13 @@ __global__ void __launch_bounds__(256) bcr_spmv_wave_exact(GemvParams p) {
         __builtin_amdgcn_wave_barrier();
         GEMV_STAMP(6);
         // Row sums in a fixed order.  Up to 16 strip rows: lanes (row, quarter) add 16 blocks
-        // each, then quarters pair up; more rows: lanes (row, half) add 32 blocks each.
+        // each, then quarters pair up; more rows: lanes (row, half) add 32 blocks each.  Every
+        // lane group ends up with the full sum.
         float rs;
-        bool writer;
-        int r_out;
         if (p.BR <= 16) {
-            r_out = lane & 15;
-            const int qd = lane >> 4;
             float s = 0.f;
             if (r_out < p.BR) {
-                const float2 *src = reinterpret_cast<const float2 *>(part + r_out * kPartStride + qd * 16);
+                const float2 *src = reinterpret_cast<const float2 *>(part + r_out * kPartStride + grp * 16);
 #pragma unroll
                 for (int q = 0; q < 8; ++q) {
                     const float2 v = src[q];
@@ -788,13 +824,10 @@ __global__ void __launch_bounds__(256) bcr_spmv_wave_exact(GemvParams p) {
             }
             const float s2 = s + __shfl_xor(s, 16);
             rs = s2 + __shfl_xor(s2, 32);
-            writer = qd == 0;
         } else {
-            r_out = lane & 31;
-            const int half = lane >> 5;
             float s = 0.f;
             if (r_out < p.BR) {
-                const float2 *src = reinterpret_cast<const float2 *>(part + r_out * kPartStride + half * 32);
+                const float2 *src = reinterpret_cast<const float2 *>(part + r_out * kPartStride + grp * 32);
 #pragma unroll
                 for (int q = 0; q < 16; ++q) {
                     const float2 v = src[q];
@@ -803,17 +836,23 @@ __global__ void __launch_bounds__(256) bcr_spmv_wave_exact(GemvParams p) {
                 }
             }
             rs = s + __shfl_xor(s, 32);
-            writer = half == 0;
         }
-        yacc += rs;
+        yacc += rs;                                               // the same value in every lane group
         __builtin_amdgcn_wave_barrier();                          // table consumed before the next item refills LDS
         GEMV_STAMP(7);
         if (cur.c0 + p.seg_blocks >= p.nbc) {                     // last segment of a strip
-            if (writer && r_out < p.BR) y[((int64_t)cur.srow * p.BR + r_out) * p.ldy] = yacc;
+#pragma unroll
+            for (int k = 0; k < kKeep; ++k)
+                if (npend == grp + k * ngrp) {
+                    ykeep[k] = yacc;
+                    rowkeep[k] = cur.srow;
+                }
             yacc = 0.f;
+            ++npend;
         }
         cur = nxt;
     }
+    store_kept();
     GEMV_STAMP(8);
 }
 
@@ -889,11 +928,11 @@ static grim_status launch_batch(const GemvParams &p, int batch, int vec, dim3 gr
     return GRIM_ERR_SHAPE;
 }
 
-// Strips a wave of the wave-per-strip kernels walks: 1 when the launch is small, up to 4 while
-// at least 2048 workgroups remain.
-static int wave_strips_per_wave(int64_t count, int64_t nbr) {
+// Strips a wave of the wave-per-strip kernels walks: 1 when the launch is small, up to max_sps
+// while at least 512 workgroups (two per compute unit) remain.
+static int wave_strips_per_wave(int64_t count, int64_t nbr, int max_sps) {
     int sps = 1;
-    while (sps < 4 && count * ((nbr + 4 * sps * 2 - 1) / (4 * sps * 2)) >= 2048) sps *= 2;
+    while (sps < max_sps && count * ((nbr + 4 * sps * 2 - 1) / (4 * sps * 2)) >= 512) sps *= 2;
 #ifdef GRIM_DBG
     if (const char *e = getenv("GRIM_SPS")) sps = atoi(e);
 #endif
@@ -943,12 +982,12 @@ grim_status launch_spmv(const GemvDesc *table, const GemvDesc &single, int32_t c
             const int nv = ukr * ukc * esz / 16;
             GemvParams q = p;
             q.seg_blocks = 64;
-            int64_t wb = (int64_t)64 * (nv | 1) * 16;
+            int64_t wb = (int64_t)exact_region_vectors(nv) * 16;
             const int64_t table = ((int64_t)BR * kPartStride * 4 + 15) & ~int64_t(15);
             if (wb < table) wb = table;
             q.wbytes = (int32_t)wb;
             const size_t wlds = (((size_t)K * esz + 15) & ~size_t(15)) + 4 * (size_t)wb;
-            q.sps = wave_strips_per_wave(count, nbr);
+            q.sps = wave_strips_per_wave(count, nbr, 8);
             dim3 wgrid((unsigned)((nbr + 4 * q.sps - 1) / (4 * q.sps)), (unsigned)count);
             grim_status st = GRIM_ERR_UNSUPPORTED;
             if (wlds <= 160 * 1024) {
@@ -974,7 +1013,7 @@ grim_status launch_spmv(const GemvDesc *table, const GemvDesc &single, int32_t c
                 // A lone product wants every strip on a wave of its own (latency); many products
                 // at once fill the GPU anyway, and a wave then walks several strips so that the
                 // next strip's weights stream in behind the current strip's arithmetic.
-                const int sps = wave_strips_per_wave(count, nbr);
+                const int sps = wave_strips_per_wave(count, nbr, 4);
                 q.sps = sps;
                 dim3 wgrid((unsigned)((nbr + 4 * sps - 1) / (4 * sps)), (unsigned)count);
                 switch (dtype) {
