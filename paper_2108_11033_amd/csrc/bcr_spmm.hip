@@ -416,54 +416,92 @@ __global__ void __launch_bounds__((NW + NP) * 64) bcr_spmm_mma(MmaParams p) {
     const int hdr_rows = (kgroup * 4 + (i16 >> 2)) * 4;        // this lane's pair of staged-row numbers
     const int hdr_desc = KS * 2 + kgroup * 8;                  // its group's (row mask, payload offset)
 
-    struct Step { i16x8 w; unsigned int rr; };
-    // one step of a strip region: header lookups, then this lane's 8 weights (its row of the
-    // group's block if the block keeps that row, else zeros)
-    auto load_step = [&](const char *region, int r) {
-        Step f;
+    // A step's header holds the staged-row numbers of its k slots and, per group of 8 slots, the
+    // block's row mask and the place of its weights; the weights of a lane (its row of the
+    // group's block if the block keeps that row, else zeros) can only be read once the header
+    // is there.  Steps are therefore taken two at a time, with the headers of the next pair
+    // requested before the current pair is multiplied: per pair one LDS round trip for the
+    // weights and X values of both steps instead of two dependent ones per step.
+    struct Hdr { unsigned int rr; uint2 dsc; };
+    auto load_hdr = [&](const char *region, int r) {
+        Hdr f;
         const char *h = region + r * HDR;
         f.rr = *reinterpret_cast<const unsigned int *>(h + hdr_rows);
-        const uint2 dsc = *reinterpret_cast<const uint2 *>(h + hdr_desc);
-        const bool kept = (dsc.x >> m_row) & 1u;
-        const int idx = kept ? __builtin_popcount(dsc.x & below) : 0;
-        const i16x8 w = *reinterpret_cast<const i16x8 *>(region + (dsc.y + idx) * 16);
-        f.w = kept ? w : i16x8{0, 0, 0, 0, 0, 0, 0, 0};
+        f.dsc = *reinterpret_cast<const uint2 *>(h + hdr_desc);
         return f;
+    };
+    auto load_w = [&](const char *region, const Hdr &f) {
+        const bool kept = (f.dsc.x >> m_row) & 1u;
+        const int idx = kept ? __builtin_popcount(f.dsc.x & below) : 0;
+        const i16x8 w = *reinterpret_cast<const i16x8 *>(region + (f.dsc.y + idx) * 16);
+        return kept ? w : i16x8{0, 0, 0, 0, 0, 0, 0, 0};
+    };
+    auto load_x = [&](const char *stage, const Hdr &f, i16x8 (&x)[NT]) {
+        const int r0 = f.rr & 0xffff, r1 = f.rr >> 16;
+        const int sw0 = swizzle<CPR>(r0), sw1 = swizzle<CPR>(r1);
+        const char *x0 = stage + r0 * PITCH + within;
+        const char *x1 = stage + r1 * PITCH + within;
+#pragma unroll
+        for (int q = 0; q < NT; ++q) {
+            const int cq = q * (NSUB / 8) + cl;
+            const i16x4 lo = lds_tr_read(x0 + ((cq ^ sw0) << 4));
+            const i16x4 hi = lds_tr_read(x1 + ((cq ^ sw1) << 4));
+            x[q] = i16x8{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+        }
     };
 
     __syncthreads();
-    for (int ch = 0; ch < p.nchunks; ++ch) {
-        const char *stage = lds + (ch & 1) * stage_bytes;
-        const char *frs = stage + xbytes;
-        if (wave == 0) GRIM_STAMP(12, ch);
+    // (number of steps, region offset) of this wave's strips in a chunk, read one chunk ahead so
+    // that the look-up is off the critical path after the barrier
+    struct Entry { int nst, off; };
+    auto entries_of = [&](int ch, Entry (&en)[SPW]) {
         const int2 *row = tab + ch * (G + 1);
         const int2 base = row[0];
 #pragma unroll
         for (int s = 0; s < SPW; ++s) {
             const int2 e0 = row[s * NW + wave], e1 = row[s * NW + wave + 1];
-            const int nst = e1.x - e0.x;
+            en[s].nst = e1.x - e0.x;
+            en[s].off = (e0.y - base.y) * 16;
+        }
+    };
+    Entry en[SPW], en_next[SPW];
+    entries_of(0, en);
+    for (int ch = 0; ch < p.nchunks; ++ch) {
+        const char *stage = lds + (ch & 1) * stage_bytes;
+        const char *frs = stage + xbytes;
+        if (wave == 0) GRIM_STAMP(12, ch);
+        entries_of(ch + 1 < p.nchunks ? ch + 1 : ch, en_next);
+#pragma unroll
+        for (int s = 0; s < SPW; ++s) {
+            const int nst = en[s].nst;
             if (nst <= 0) continue;
-            const char *region = frs + (e0.y - base.y) * 16;
-            Step cur = load_step(region, 0);
-            for (int r = 0; r < nst; ++r) {
-                const Step nxt = load_step(region, r + 1 < nst ? r + 1 : r);
-                const int r0 = cur.rr & 0xffff, r1 = cur.rr >> 16;
-                const int sw0 = swizzle<CPR>(r0), sw1 = swizzle<CPR>(r1);
-                const char *x0 = stage + r0 * PITCH + within;
-                const char *x1 = stage + r1 * PITCH + within;
+            const char *region = frs + en[s].off;
+            Hdr ha = load_hdr(region, 0), hb = load_hdr(region, nst > 1 ? 1 : 0);
+            for (int r = 0; r < nst; r += 2) {
+                const i16x8 wa = load_w(region, ha), wb = load_w(region, hb);
+                i16x8 xa[NT], xb[NT];
+                load_x(stage, ha, xa);
+                load_x(stage, hb, xb);
+                const int ra = r + 2 < nst ? r + 2 : nst - 1, rb = r + 3 < nst ? r + 3 : nst - 1;
+                ha = load_hdr(region, ra);
+                hb = load_hdr(region, rb);
 #pragma unroll
                 for (int q = 0; q < NT; ++q) {
-                    const int cq = q * (NSUB / 8) + cl;
-                    const i16x4 lo = lds_tr_read(x0 + ((cq ^ sw0) << 4));
-                    const i16x4 hi = lds_tr_read(x1 + ((cq ^ sw1) << 4));
-                    const i16x8 x = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-                    if constexpr (BR == 16) acc[s][q] = mfma16<BF16>(x, cur.w, acc[s][q]);
-                    else acc[s][q] = mfma32<BF16>(cur.w, x, acc[s][q]);
+                    if constexpr (BR == 16) acc[s][q] = mfma16<BF16>(xa[q], wa, acc[s][q]);
+                    else acc[s][q] = mfma32<BF16>(wa, xa[q], acc[s][q]);
                 }
-                cur = nxt;
+                if (r + 1 < nst) {
+#pragma unroll
+                    for (int q = 0; q < NT; ++q) {
+                        if constexpr (BR == 16) acc[s][q] = mfma16<BF16>(xb[q], wb, acc[s][q]);
+                        else acc[s][q] = mfma32<BF16>(wb, xb[q], acc[s][q]);
+                    }
+                }
             }
         }
         if (wave == 0) GRIM_STAMP(13, ch);
+#pragma unroll
+        for (int s = 0; s < SPW; ++s) en[s] = en_next[s];
         __syncthreads();
         if (wave == 0) GRIM_STAMP(14, ch);
     }
