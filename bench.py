@@ -26,8 +26,8 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
 # HBM bytes per c2 launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a device copy of known
-# size (profiles/bcr_spmm_mma_c2.md): 8569.5 KiB x 2.0 fetched + 3136.0 KiB x 1.0 written
-C2_TRAFFIC_BYTES = (8569.5 * 2.0 + 3136.0) * 1024
+# size (profiles/bcr_spmm_mma_c2.md): 7835.5 KiB x 2.0 fetched + 3136.0 KiB x 1.0 written
+C2_TRAFFIC_BYTES = (7835.5 * 2.0 + 3136.0) * 1024
 METRIC = "BCR SpMM/SpMV useful TFLOP/s, HBM GB/s, % of roofline vs oracle"
 
 

@@ -80,7 +80,7 @@ typedef struct grim_bcr_view {
     const void *weights;
     /* bytes of the device-side layouts derived from the arrays above (0 if absent) */
     int64_t dev_bytes_canonical; /* the arrays above, as uploaded */
-    int64_t dev_bytes_mma;       /* row-expanded matrix-core layout (fragments + gather lists) */
+    int64_t dev_bytes_mma;       /* matrix-core layout: per-step gather lists, row masks and kept-row weights */
     int64_t dev_bytes_gemv;      /* per-block row/column bit masks + offsets for the SpMV kernel */
 } grim_bcr_view;
 

@@ -7,12 +7,13 @@
 //    here a consequence of treating the block as a small dense matrix).
 //  * bcr_spmm_mma  -- matrix-core kernel for fp16 / bf16 with BR = 16 or 32.
 //    A workgroup owns a tile of TN columns of X and a group of row strips.  Chunks of
-//    consecutive X rows are staged in LDS once per workgroup (tiling, Section 4.4) by a
-//    dedicated producer wave using direct global->LDS loads, one chunk ahead of the
+//    consecutive X rows are staged in LDS once per workgroup (tiling, Section 4.4) by
+//    dedicated producer waves (global -> registers -> LDS), two chunks ahead of the
 //    consumer waves.  Each consumer wave gathers the rows its strips keep with LDS
-//    transpose reads straight into MFMA operand layout and multiplies them with
-//    pre-built weight fragments.  Strips are dealt to waves in stored (work-sorted,
-//    Section 4.2) order so the waves of a workgroup carry near-equal work.
+//    transpose reads straight into MFMA operand layout and multiplies them with the
+//    kept rows of the blocks' weights (lanes of rows a block does not keep multiply
+//    zeros).  Strips are dealt to waves in stored (work-sorted, Section 4.2) order so
+//    the waves of a workgroup carry near-equal work.
 //    Accumulation is fp32, order fixed, no atomics.
 #include <hip/hip_runtime.h>
 

@@ -3,7 +3,10 @@
 //
 // The compact weights ARE the memory traffic here, so they are read exactly once, in their
 // compact kept-rows x kept-columns form (Section 4.3), with 8 bytes of row / column bit masks
-// per block as the only index data.  One workgroup owns one row strip:
+// per block as the only index data.  Three kernels: one right-hand side goes to the
+// wave-per-strip kernels further down (bcr_spmv_wave_exact when every block keeps the same
+// counts, else bcr_spmv_wave); 2..8 right-hand sides to bcr_spmv, where one workgroup owns one
+// row strip:
 //   1. the strip's weights -- one contiguous byte range -- its block masks and x are fetched with
 //      coalesced 16-byte loads, all issued before any is used, and parked in LDS;
 //   2. a group of LPB lanes takes a block, lane i its compact row i: a dot product over the
