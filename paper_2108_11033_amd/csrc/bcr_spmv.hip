@@ -766,7 +766,8 @@ __global__ void __launch_bounds__(256) bcr_spmv_wave_exact(GemvParams p) {
 #pragma unroll
                 for (int j = 0; j < KC; ++j) {
                     const int q = i * KC + j;
-                    a = __builtin_fmaf(__builtin_bit_cast(float, w[q >> 2][q & 3]), xe[j], a);
+                    const unsigned int wd = w[q >> 2][q & 3];       // a copy: bit_cast of the element itself reads element 0
+                    a = __builtin_fmaf(__builtin_bit_cast(float, wd), xe[j], a);
                 }
                 acc[i] = a;
             }

@@ -252,6 +252,55 @@ def test_spmv_falls_back_when_blocks_exceed_masks(g):
     assert_close(run_spmv(g, A, x, dtype, M, 2), yref, S, dtype, "spmv 64x64 blocks")
 
 
+# Every (kept rows, kept columns) pair the uniform one-right-hand-side kernel is compiled for, in each
+# element type, with: 16- and 32-row blocks (4 and 2 output lane groups), a strip of more than 64 column
+# blocks (two passes of lanes, the second ragged), a strip count that is not a multiple of the 4 strips
+# of a workgroup, unit and non-unit strides of x and y.
+UNIFORM_PAIRS = [(4, 4), (4, 8), (4, 12), (4, 16), (8, 4), (8, 8), (8, 12), (8, 16), (16, 4), (16, 8), (16, 12)]
+
+
+@pytest.mark.parametrize("dtype", [gen.F16, gen.BF16, gen.F32])
+@pytest.mark.parametrize("kr,kc", UNIFORM_PAIRS)
+def test_spmv_uniform_pairs(g, dtype, kr, kc):
+    for BR, nbr, nbc in ((16, 7, 70), (32, 5, 9)):
+        BC = 32
+        M, K = BR * nbr, BC * nbc
+        mask = gen.random_mask(M, K, BR, BC, kr, kc, seed=200 + kr * 17 + kc)
+        W = gen.normal_weights(M, K, dtype, seed=201 + kr)
+        x = gen.normal_activations(K, 1, dtype, seed=202 + kc)
+        A = pack_workload(g, W, dtype, mask)
+        yref, S = oracle_product(W, x, dtype, mask)
+        y = run_spmv(g, A, x, dtype, M, 1)
+        assert_close(y, yref, S, dtype, f"uniform spmv {dtype} {BR}x{BC} keep {kr}x{kc}")
+        y2 = run_spmv(g, A, x, dtype, M, 1, ldx=3, ldy=2)
+        assert y2.tobytes() == y.tobytes()
+        A.free()
+
+
+@pytest.mark.parametrize("dtype", [gen.F16, gen.F32])
+def test_spmv_uniform_many_products_per_launch(g, dtype):
+    """Enough products in one launch that every wave walks several strips (next strip's loads in flight,
+    finished strips stored in groups), with a strip count that leaves the last waves short."""
+    torch, dev = torch_dev()
+    M, K, BR, BC, count = 16 * 37, 32 * 20, 16, 32, 256
+    mask = gen.random_mask(M, K, BR, BC, 8, 12, seed=210)
+    W = gen.normal_weights(M, K, dtype, seed=211)
+    A = pack_workload(g, W, dtype, mask)
+    xs = [gen.normal_activations(K, 1, dtype, seed=212 + i) for i in range(3)]
+    refs = [oracle_product(W, x, dtype, mask) for x in xs]
+    from paper_2108_11033_amd import binding
+    G = binding.group([A] * count)
+    xd = to_device(np.stack([xs[i % 3] for i in range(count)]), dtype)
+    yd = torch.full((count, M, 1), float("nan"), dtype=torch.float32, device=dev)
+    g.spmv_batched(G, xd, K, 1, 1, yd, M, 1, torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    y = yd.cpu().numpy()
+    for i in range(count):
+        assert_close(y[i], refs[i % 3][0], refs[i % 3][1], dtype, f"product {i} of {count}")
+    for i in range(3):
+        assert y[i].tobytes() == run_spmv(g, A, xs[i], dtype, M, 1).tobytes()
+
+
 @pytest.mark.parametrize("batch", [1, 8])
 def test_spmv_batched_matches_single_calls(g, batch):
     torch, dev = torch_dev()
