@@ -40,6 +40,7 @@ struct GemvParams {
     int64_t x_stride, y_stride, ldx, ldy;
     int32_t xvec16;          // x is contiguous and 16-byte aligned: copy with 16-byte loads
     int32_t sps;             // wave kernel: consecutive strips per wave
+    int32_t batch;           // right-hand sides (kernels that take it at run time)
 #ifdef GRIM_DBG
     long long *dbg;
 #endif
@@ -894,6 +895,262 @@ static grim_status launch_exact(const GemvParams &p, int kr, int kc, dim3 grid, 
     return GRIM_ERR_UNSUPPORTED;
 }
 
+// ------------------------------------------------------------------------------------------
+// 2..8 right-hand sides, every block keeping exactly KR rows and KC columns, strips of at most 64
+// column blocks: the uniform wave-per-strip scheme with a loop over the right-hand sides around
+// everything after the weights.  A strip's weights are fetched and parked once; for each column
+// of x the lane gathers its KC activations, multiplies, and the row sums go through the
+// [strip row][block] table.  Results collect in a per-wave LDS tile [right-hand side][strip row]
+// and leave with the next strip's first store slot (see the one-column kernel for why a store
+// is not issued just before a wait for loads), coalesced when y is contiguous.
+// x sits in LDS as [k][right-hand side], shared by the workgroup's waves.
+// ------------------------------------------------------------------------------------------
+template <int DT, int KR, int KC>
+__global__ void __launch_bounds__(512) bcr_spmv_wave_exact_b(GemvParams p) {
+    using T = typename GElem<DT>::type;
+    constexpr int ESZ = (int)sizeof(T);
+    constexpr int NV = KR * KC * ESZ / 16;       // 16-byte vectors per block
+    constexpr int PB = exact_pad_period(NV);     // one vector of padding after every PB blocks (0: none)
+    static_assert(KR * KC * ESZ % 16 == 0 && (ESZ == 4 || KC % 2 == 0) && KC <= 32 && KR <= 32, "block shape");
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    const int tid = threadIdx.x, lane = tid & 63, nthreads = blockDim.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int B = p.batch;
+    const int xbytes = (p.K * B * ESZ + 15) & ~15;
+    T *xs = reinterpret_cast<T *>(smem);
+    char *wl = smem + xbytes + wave * p.wbytes;
+    float *part = reinterpret_cast<float *>(wl);                  // reuses the weights' space
+    float *ybuf = reinterpret_cast<float *>(wl + p.wbytes - 8 * 32 * 4);   // [8][32], behind weights and table
+
+    const int64_t mi = blockIdx.y;
+    const GemvGlobal d = to_global(p.table ? p.table[mi] : p.single);
+    const GRIM_GLOBAL char *W = d.weights;
+    const GRIM_GLOBAL T *x = (const GRIM_GLOBAL T *)p.x + mi * p.x_stride;
+    GRIM_GLOBAL float *y = (GRIM_GLOBAL float *)p.y + mi * p.y_stride;
+
+    const int64_t t0 = ((int64_t)blockIdx.x * (nthreads >> 6) + wave) * p.sps;
+    const int nstrips = p.nbr_total - t0 < p.sps ? (int)(p.nbr_total - t0) : p.sps;   // <= 0: nothing to do
+    const int nitems = nstrips > 0 ? nstrips : 0;
+    const int nb = p.nbc;                                         // <= 64: one lane per block of the strip
+    const int nvec = nb * NV;
+
+    struct Item { unsigned int rm, cm; int srow; };
+    gu32x4 wreg[NV];
+    auto fetch = [&](int it, Item &I) {
+        const int64_t t = t0 + it;
+        const int64_t blk0 = t * p.nbc;
+        const GRIM_GLOBAL char *src = W + (size_t)blk0 * (NV * 16);
+#pragma unroll
+        for (int i = 0; i < NV; ++i) {
+            int v = lane + i * 64;
+            v = v < nvec ? v : nvec - 1;
+            wreg[i] = *reinterpret_cast<const GRIM_GLOBAL gu32x4 *>(src + (unsigned int)(v * 16));
+        }
+        I.rm = 0;
+        I.cm = KC == 32 ? 0xffffffffu : (1u << (KC & 31)) - 1u;   // idle lanes: any KC columns, no rows
+        if (lane < nb) {
+            const gu32x2 mm = *reinterpret_cast<const GRIM_GLOBAL gu32x2 *>(d.masks + 2 * (blk0 + lane));
+            I.rm = mm.x;
+            I.cm = mm.y;
+        }
+        I.srow = d.strip_order[t];
+    };
+
+    // output lanes: (strip row, lane group); 4 groups of 16 lanes up to 16 strip rows, else 2 of 32
+    const int r_out = p.BR <= 16 ? lane & 15 : lane & 31;
+    const int grp = p.BR <= 16 ? lane >> 4 : lane >> 5;
+    int pend_row = -1;                                            // strip whose sums wait in ybuf
+    auto flush = [&]() {
+        if (pend_row >= 0) {
+            for (int e = lane; e < p.BR * B; e += 64) {
+                const int r = e / B, b = e - r * B;
+                y[((int64_t)pend_row * p.BR + r) * p.ldy + b] = ybuf[b * 32 + r];
+            }
+        }
+        pend_row = -1;
+    };
+
+    Item cur, nxt;
+    if (p.xvec16) {
+        const int nxv = p.K * B * ESZ / 16;
+        const GRIM_GLOBAL gu32x4 *xsrc = reinterpret_cast<const GRIM_GLOBAL gu32x4 *>(x);
+        gu32x4 xreg[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            int v = tid + i * nthreads;
+            v = v < nxv ? v : nxv - 1;
+            xreg[i] = xsrc[v];
+        }
+        if (nitems) fetch(0, cur);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int v = tid + i * nthreads;
+            if (v < nxv) reinterpret_cast<gu32x4 *>(xs)[v] = xreg[i];
+        }
+        for (int v = tid + 4 * nthreads; v < nxv; v += nthreads) reinterpret_cast<gu32x4 *>(xs)[v] = xsrc[v];
+    } else {
+        if (nitems) fetch(0, cur);
+        for (int e = tid; e < p.K * B; e += nthreads) {
+            const int k = e / B;
+            xs[e] = x[(int64_t)k * p.ldx + (e - k * B)];
+        }
+    }
+    __syncthreads();
+    if (!nitems) return;
+    for (int it = 0; it < nitems; ++it) {
+        const unsigned int rm = cur.rm, cm = cur.cm;
+#pragma unroll
+        for (int i = 0; i < NV; ++i) {
+            const int v = lane + i * 64;
+            const int slot = PB ? v + v / (NV * PB) : v;
+            if (v < nvec) *reinterpret_cast<gu32x4 *>(wl + slot * 16) = wreg[i];
+        }
+        __builtin_amdgcn_wave_barrier();
+        flush();                                                  // the previous strip's sums
+        nxt = cur;
+        if (it + 1 < nitems) fetch(it + 1, nxt);
+
+        // where this block's KC activations start in x (element index of right-hand side 0)
+        int xo[KC];
+        {
+            int xblk = lane < p.nbc ? lane : p.nbc - 1;
+            unsigned int m = cm;
+#pragma unroll
+            for (int j = 0; j < KC; ++j) {
+                const int col = __builtin_ctz(m);                 // KC bits are set
+                m &= m - 1;
+                xo[j] = (xblk * p.BC + col) * B;
+            }
+        }
+        gu32x4 w[NV];
+        {
+            const gu32x4 *wb = reinterpret_cast<const gu32x4 *>(wl) + lane * NV + (PB ? lane / PB : 0);
+#pragma unroll
+            for (int j = 0; j < NV; ++j) w[j] = wb[j];
+        }
+        for (int b = 0; b < B; ++b) {
+            T xe[KC];
+#pragma unroll
+            for (int j = 0; j < KC; ++j) xe[j] = xs[xo[j] + b];
+            float acc[KR];
+            if constexpr (DT == GRIM_F32) {
+#pragma unroll
+                for (int i = 0; i < KR; ++i) {
+                    float a = 0.f;
+#pragma unroll
+                    for (int j = 0; j < KC; ++j) {
+                        const int q = i * KC + j;
+                        const unsigned int wd = w[q >> 2][q & 3];
+                        a = __builtin_fmaf(__builtin_bit_cast(float, wd), xe[j], a);
+                    }
+                    acc[i] = a;
+                }
+            } else {
+                unsigned int xp[KC / 2];
+#pragma unroll
+                for (int h = 0; h < KC / 2; ++h) {
+                    unsigned short lo, hi;
+                    __builtin_memcpy(&lo, &xe[2 * h], 2);
+                    __builtin_memcpy(&hi, &xe[2 * h + 1], 2);
+                    xp[h] = (unsigned int)lo | ((unsigned int)hi << 16);
+                }
+#pragma unroll
+                for (int i = 0; i < KR; ++i) {
+                    float a = 0.f;
+#pragma unroll
+                    for (int h = 0; h < KC / 2; ++h) {
+                        const int q = i * (KC / 2) + h;
+                        const unsigned int wd = w[q >> 2][q & 3];
+                        if constexpr (DT == GRIM_F16)
+                            a = __builtin_amdgcn_fdot2(__builtin_bit_cast(gh2, wd), __builtin_bit_cast(gh2, xp[h]), a, false);
+                        else
+                            a = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(gb2, wd), __builtin_bit_cast(gb2, xp[h]), a, false);
+                    }
+                    acc[i] = a;
+                }
+            }
+            __builtin_amdgcn_wave_barrier();                      // every lane holds its block in registers
+            for (int z = lane; z < (p.BR * kPartStride + 3) / 4; z += 64)
+                reinterpret_cast<gu32x4 *>(part)[z] = gu32x4{0u, 0u, 0u, 0u};
+            __builtin_amdgcn_wave_barrier();
+            if (rm) {
+                unsigned int m = rm;
+#pragma unroll
+                for (int i = 0; i < KR; ++i) {
+                    const int r = __builtin_ctz(m);               // KR bits are set
+                    m &= m - 1;
+                    part[r * kPartStride + lane] = acc[i];
+                }
+            }
+            __builtin_amdgcn_wave_barrier();
+            float rs;
+            if (p.BR <= 16) {
+                float s = 0.f;
+                if (r_out < p.BR) {
+                    const float2 *src = reinterpret_cast<const float2 *>(part + r_out * kPartStride + grp * 16);
+#pragma unroll
+                    for (int q = 0; q < 8; ++q) {
+                        const float2 v = src[q];
+                        s += v.x;
+                        s += v.y;
+                    }
+                }
+                const float s2 = s + __shfl_xor(s, 16);
+                rs = s2 + __shfl_xor(s2, 32);
+            } else {
+                float s = 0.f;
+                if (r_out < p.BR) {
+                    const float2 *src = reinterpret_cast<const float2 *>(part + r_out * kPartStride + grp * 32);
+#pragma unroll
+                    for (int q = 0; q < 16; ++q) {
+                        const float2 v = src[q];
+                        s += v.x;
+                        s += v.y;
+                    }
+                }
+                rs = s + __shfl_xor(s, 32);
+            }
+            if (grp == 0 && r_out < p.BR) ybuf[b * 32 + r_out] = rs;
+            __builtin_amdgcn_wave_barrier();                      // table consumed before it is zeroed again
+        }
+        pend_row = cur.srow;
+        cur = nxt;
+    }
+    flush();
+}
+
+template <int DT, int KR, int KC>
+static grim_status launch_exact_b_inst(const GemvParams &p, dim3 grid, int threads, size_t lds, hipStream_t stream) {
+    auto kern = bcr_spmv_wave_exact_b<DT, KR, KC>;
+    static bool attr_done = false;
+    if (lds > 64 * 1024 && !attr_done) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess) {
+            (void)hipGetLastError();
+            return GRIM_ERR_DEVICE;
+        }
+        attr_done = true;
+    }
+    hipLaunchKernelGGL(kern, grid, dim3(threads), lds, stream, p);
+    return hipGetLastError() == hipSuccess ? GRIM_OK : GRIM_ERR_DEVICE;
+}
+
+template <int DT>
+static grim_status launch_exact_b(const GemvParams &p, int kr, int kc, dim3 grid, int threads, size_t lds, hipStream_t stream) {
+    constexpr int ESZ = (int)sizeof(typename GElem<DT>::type);
+#define GRIM_EXACT(R, C)                                                                   \
+    if constexpr ((R) * (C) * ESZ % 16 == 0 && (R) * (C) * ESZ <= 384)                     \
+        if (kr == (R) && kc == (C)) return launch_exact_b_inst<DT, R, C>(p, grid, threads, lds, stream);
+#ifdef GRIM_FEW_SHAPES   /* development builds */
+    GRIM_EXACT(8, 12)
+#else
+    GRIM_EXACT(4, 4) GRIM_EXACT(4, 8) GRIM_EXACT(4, 12) GRIM_EXACT(4, 16)
+    GRIM_EXACT(8, 4) GRIM_EXACT(8, 8) GRIM_EXACT(8, 12) GRIM_EXACT(8, 16)
+    GRIM_EXACT(16, 4) GRIM_EXACT(16, 8) GRIM_EXACT(16, 12)
+#endif
+#undef GRIM_EXACT
+    return GRIM_ERR_UNSUPPORTED;
+}
+
 template <int DT, int B>
 static grim_status launch_vec(const GemvParams &p, int vec, dim3 grid, size_t lds, hipStream_t stream) {
 #define GRIM_GEMV(V)                                                                                          \
@@ -959,6 +1216,7 @@ grim_status launch_spmv(const GemvDesc *table, const GemvDesc &single, int32_t c
     p.BR = BR; p.BC = BC; p.nbc = (int32_t)(K / BC); p.K = (int32_t)K;
     p.nbr_total = (int32_t)nbr;
     p.sps = 1;
+    p.batch = batch;
     p.ukr = ukr; p.ukc = ukc;
     p.krmax = krmax;
     p.kcmax = kcmax;
@@ -1027,6 +1285,29 @@ grim_status launch_spmv(const GemvDesc *table, const GemvDesc &single, int32_t c
                 }
             }
         }
+    }
+    if (batch > 1 && dtype != GRIM_F32 && ukr > 0 && ukc > 0 && (ukr * ukc * esz) % 16 == 0 && ukr * ukc * esz <= 384 &&
+        K / BC <= 64 && (int64_t)K * batch * esz <= 64 * 1024 && (int64_t)count * nbr >= 1024) {
+        // uniform blocks, several right-hand sides, a launch of at least 128 workgroups: wave per
+        // strip, 8 waves share x in LDS (smaller launches are quicker with a workgroup per strip)
+        const int nv = ukr * ukc * esz / 16, nw = 8;
+        GemvParams q = p;
+        q.seg_blocks = 64;
+        int64_t wb = (int64_t)exact_region_vectors(nv) * 16;
+        const int64_t table = ((int64_t)BR * kPartStride * 4 + 15) & ~int64_t(15);
+        if (wb < table) wb = table;
+        wb += 8 * 32 * 4;                                       // the wave's result tile
+        q.wbytes = (int32_t)wb;
+        const size_t wlds = (((size_t)K * batch * esz + 15) & ~size_t(15)) + nw * (size_t)wb;
+        int sps = 1;
+        while (sps < 4 && (int64_t)count * ((nbr + nw * sps * 2 - 1) / (nw * sps * 2)) >= 512) sps *= 2;
+        q.sps = sps;
+        dim3 wgrid((unsigned)((nbr + nw * sps - 1) / (nw * sps)), (unsigned)count);
+        grim_status st = GRIM_ERR_UNSUPPORTED;
+        if (wlds <= 160 * 1024)
+            st = dtype == GRIM_F16 ? launch_exact_b<GRIM_F16>(q, ukr, ukc, wgrid, nw * 64, wlds, stream)
+                                   : launch_exact_b<GRIM_BF16>(q, ukr, ukc, wgrid, nw * 64, wlds, stream);
+        if (st != GRIM_ERR_UNSUPPORTED) return st;
     }
     const int rb = BR * batch;
     const int nseg = 256 / rb;

@@ -277,6 +277,53 @@ def test_spmv_uniform_pairs(g, dtype, kr, kc):
         A.free()
 
 
+@pytest.mark.parametrize("dtype", [gen.F16, gen.BF16])
+@pytest.mark.parametrize("batch", [2, 5, 8])
+@pytest.mark.parametrize("kr,kc", UNIFORM_PAIRS)
+def test_spmv_uniform_pairs_several_rhs(g, dtype, batch, kr, kc):
+    """2..8 right-hand sides on uniformly pruned matrices: launches of at least 1024 strips of at most 64
+    column blocks take the wave-per-strip kernel with a loop over the right-hand sides (smaller ones the
+    workgroup-per-strip kernel, covered by the single calls below); contiguous and strided x / y."""
+    torch, dev = torch_dev()
+    from paper_2108_11033_amd import binding
+    for BR, nbr, nbc, count in ((16, 11, 64, 96), (32, 5, 9, 208)):
+        BC = 32
+        M, K = BR * nbr, BC * nbc
+        mask = gen.random_mask(M, K, BR, BC, kr, kc, seed=220 + kr * 17 + kc)
+        W = gen.normal_weights(M, K, dtype, seed=221 + kr)
+        A = pack_workload(g, W, dtype, mask)
+        xs = [gen.normal_activations(K, batch, dtype, seed=222 + kc + i) for i in range(2)]
+        refs = [oracle_product(W, x, dtype, mask) for x in xs]
+        G = binding.group([A] * count)
+        stream = torch.cuda.current_stream()
+        xd = to_device(np.stack([xs[i % 2] for i in range(count)]), dtype)               # [count, K, batch]
+        yd = torch.full((count, M, batch), float("nan"), dtype=torch.float32, device=dev)
+        g.spmv_batched(G, xd, K * batch, batch, batch, yd, M * batch, batch, stream)
+        torch.cuda.synchronize()
+        y = yd.cpu().numpy()
+        for i in (0, 1, count // 2, count - 2, count - 1):
+            assert_close(y[i], refs[i % 2][0], refs[i % 2][1], dtype,
+                         f"uniform {dtype} {BR}x{BC} keep {kr}x{kc} b={batch} product {i}")
+        assert all(y[i].tobytes() == y[i % 2].tobytes() for i in range(count))
+        # strided x and y
+        ldx, ldy = batch + 3, batch + 1
+        xp = np.zeros((count, K, ldx), dtype=xs[0].dtype)
+        for i in range(count):
+            xp[i, :, :batch] = xs[i % 2]
+        xd2 = to_device(xp, dtype)
+        yd2 = torch.full((count, M, ldy), float("nan"), dtype=torch.float32, device=dev)
+        g.spmv_batched(G, xd2, K * ldx, batch, ldx, yd2, M * ldy, ldy, stream)
+        torch.cuda.synchronize()
+        y2 = yd2.cpu().numpy()
+        assert np.isnan(y2[:, :, batch:]).all()
+        assert y2[:, :, :batch].tobytes() == y.tobytes()
+        # one product at a time gives the same values to within the tolerance
+        y1 = run_spmv(g, A, xs[0], dtype, M, batch)
+        assert_close(y1, refs[0][0], refs[0][1], dtype, "single call")
+        G.free()
+        A.free()
+
+
 @pytest.mark.parametrize("dtype", [gen.F16, gen.F32])
 def test_spmv_uniform_many_products_per_launch(g, dtype):
     """Enough products in one launch that every wave walks several strips (next strip's loads in flight,
