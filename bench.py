@@ -25,9 +25,13 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
-# HBM bytes per c2 launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a device copy of known
-# size (profiles/bcr_spmm_mma_c2.md): 7835.5 KiB x 2.0 fetched + 3136.0 KiB x 1.0 written
-C2_TRAFFIC_BYTES = (7835.5 * 2.0 + 3136.0) * 1024
+# HBM bytes per c2 launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (KiB per dispatch), each scaled by
+# what the same counter reads for a device copy of known size (x 2.0 fetched, x 1.0 written); per kernel family, from
+# profiles/bcr_spmm_gather_c2.md and profiles/bcr_spmm_mma_c2.md
+C2_TRAFFIC_BYTES = {
+    "bcr_spmm_gather": (7765.9 * 2.0 + 3136.0) * 1024,
+    "bcr_spmm_mma": (7834.0 * 2.0 + 3136.0) * 1024,
+}
 METRIC = "BCR SpMM/SpMV useful TFLOP/s, HBM GB/s, % of roofline vs oracle"
 
 
@@ -91,6 +95,7 @@ def main() -> int:
     ap.add_argument("--sets", type=int, default=32, help="(X, Y) buffer sets the steps rotate over")
     ap.add_argument("--tile-n", type=int, default=0)
     ap.add_argument("--strips-per-wg", type=int, default=0)
+    ap.add_argument("--kernel", type=int, default=0, help="0 choose, 2 staged matrix-core kernel, 3 row-gathering one")
     ap.add_argument("--extra", action="store_true", help="also time the SpMV and large non-uniform workloads")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--calibrate", action="store_true",
@@ -131,7 +136,8 @@ def main() -> int:
     sets = max(1, args.sets)
     Xs = [X0] + [X0.clone() for _ in range(sets - 1)]
     Ys = [torch.empty((wl.M, wl.N), dtype=torch.float32, device=dev) for _ in range(sets)]
-    tune = dict(tile_n=args.tile_n, strips_per_wg=args.strips_per_wg)
+    tune = dict(tile_n=args.tile_n, strips_per_wg=args.strips_per_wg, kernel=args.kernel)
+    kernel_name = g.spmm_kernel_name(A, Xs[0], wl.N, wl.N, **tune)
 
     def step(i):
         j = i % sets
@@ -152,8 +158,8 @@ def main() -> int:
                                "16x32 blocks keep 8/16 rows x 8/32 cols (density 1/8)",
                    "buffer_sets": sets, "useful_gflop_per_step": flops / 1e9, "algorithmic_mb_per_step": abytes / 1e6},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": C2_TRAFFIC_BYTES,
-                     "kernel": "bcr_spmm_mma", "launch_us": t_cold * 1e6},
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": C2_TRAFFIC_BYTES.get(kernel_name),
+                     "kernel": kernel_name, "launch_us": t_cold * 1e6},
         "warm_cache": {"ms_per_step": t_warm * 1e3, "useful_tflops": flops / t_warm / 1e12,
                        "algorithmic_gbs": abytes / t_warm / 1e9,
                        "note": "same X/Y every step: operands stay in the 256 MB last-level cache"},

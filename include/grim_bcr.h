@@ -136,12 +136,21 @@ grim_status grim_bcr_spmm(const grim_bcr_matrix *A, const void *X_dev, int64_t N
  * tile sizes per kernel, Section 4.5; here a handful of choices replaces the search):
  *   tile_n         columns of X per workgroup (32, 64 or 128; 0 = choose)
  *   strips_per_wg  row strips per workgroup (4, 8 or 16; 0 = choose)
- *   kernel         0 = choose, 1 = force the portable FMA kernel, 2 = force the matrix-core kernel
- * Combinations that are not compiled, or whose staging buffers do not fit the 160 KB of LDS
- * for this matrix, return GRIM_ERR_UNSUPPORTED. */
+ *   kernel         0 = choose, 1 = force the portable FMA kernel, 2 = force the staged matrix-core
+ *                  kernel (tile_n / strips_per_wg apply to it), 3 = force the row-gathering
+ *                  matrix-core kernel (fp16 / bf16, BR = 16, N >= 64, N and ldx multiples of 4,
+ *                  X 8-byte aligned; tile_n and strips_per_wg must be 0)
+ * Combinations that are not compiled, that the matrix or the operands do not qualify for, or whose
+ * staging buffers do not fit the 160 KB of LDS for this matrix, return GRIM_ERR_UNSUPPORTED. */
 grim_status grim_bcr_spmm_tuned(const grim_bcr_matrix *A, const void *X_dev, int64_t N, int64_t ldx,
                                 float *Y_dev, int64_t ldy, int32_t tile_n, int32_t strips_per_wg,
                                 int32_t kernel, void *hip_stream);
+
+/* grim_bcr_spmm_kernel_name -- which kernel family the grim_bcr_spmm_tuned call with these arguments
+ * would launch: "bcr_spmm_gather", "bcr_spmm_mma" (staged), "bcr_spmm_fma", "bcr_spmv" (N <= 8), or
+ * "none" when the call would fail.  A static string; launches nothing.  For profiling and reports. */
+const char *grim_bcr_spmm_kernel_name(const grim_bcr_matrix *A, const void *X_dev, int64_t N, int64_t ldx,
+                                      int32_t tile_n, int32_t strips_per_wg, int32_t kernel);
 
 /*
  * grim_bcr_spmv -- y = W_bcr * x for 1..8 right-hand sides (Section 3.1: FC and RNN

@@ -49,7 +49,7 @@ class View(ctypes.Structure):
 
 EXPORTS = ["grim_bcr_pack", "grim_bcr_unpack", "grim_bcr_arrays", "grim_bcr_spmm", "grim_bcr_spmm_tuned",
            "grim_bcr_spmv", "grim_bcr_group_create", "grim_bcr_spmv_batched", "grim_bcr_group_free",
-           "grim_bcr_free", "grim_status_str"]
+           "grim_bcr_free", "grim_status_str", "grim_bcr_spmm_kernel_name"]
 
 
 def lib_path() -> str:
@@ -85,9 +85,11 @@ def load_library():
     lib.grim_bcr_group_free.argtypes = [p]
     lib.grim_bcr_free.argtypes = [p]
     lib.grim_status_str.argtypes = [i32]
+    lib.grim_bcr_spmm_kernel_name.argtypes = [p, p, i64, i64, i32, i32, i32]
     for name in EXPORTS:
         getattr(lib, name).restype = i32
     lib.grim_status_str.restype = ctypes.c_char_p
+    lib.grim_bcr_spmm_kernel_name.restype = ctypes.c_char_p
     lib.grim_bcr_free.restype = None
     lib.grim_bcr_group_free.restype = None
     _lib = lib
@@ -238,6 +240,11 @@ def spmm(A: BcrMatrix, X, N: int, ldx: int, Y, ldy: int, stream=None, *,
         _check(st, "grim_bcr_spmm_tuned")
     else:
         _check(lib.grim_bcr_spmm(A.handle, _addr(X), N, ldx, _addr(Y), ldy, _stream(stream)), "grim_bcr_spmm")
+
+
+def spmm_kernel_name(A: BcrMatrix, X, N: int, ldx: int, *, tile_n: int = 0, strips_per_wg: int = 0, kernel: int = 0) -> str:
+    """grim_bcr_spmm_kernel_name: the kernel family the same spmm call would launch."""
+    return A._lib.grim_bcr_spmm_kernel_name(A.handle, _addr(X), N, ldx, tile_n, strips_per_wg, kernel).decode()
 
 
 def spmv(A: BcrMatrix, x, batch: int, ldx: int, y, ldy: int, stream=None):

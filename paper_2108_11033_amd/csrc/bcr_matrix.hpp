@@ -45,6 +45,32 @@ struct MmaLayout {
     int64_t bytes = 0;
 };
 
+// Layout for the row-gathering matrix-core SpMM kernel (fp16 / bf16, BR = 16).
+// The kept columns of a stored strip's blocks, in column-block order, are cut into groups of 8 k
+// slots (a block's columns padded to a multiple of 8) and groups into steps of 32 k slots -- one
+// v_mfma_f32_16x16x32 per 16 columns of X.  Nothing depends on how K is cut: a wave takes any
+// contiguous range of a strip's steps.
+//   rows   : per step 32 x u32, the row of X behind k slot g * 8 + j at position j * 4 + g
+//            (0xffffffff = padding: the slot multiplies zeros), so that the lane that fetches slots
+//            j, j + 8, j + 16, j + 24 reads its four row numbers with one 16-byte load;
+//   desc   : per step and group the block's row bit mask (u32) and the place of the group's
+//            weights in `payload`, in 16-byte units (u32);
+//   payload: per group, for every KEPT row of the block 8 weights (16 bytes).
+struct GatherLayout {
+    bool present = false;
+    int64_t nsteps = 0;
+    int64_t xrows = 0;                    // k slots that name a row of X (not padding), over all strips
+    std::vector<int32_t> sptr;            // [nbr + 1] first step of each stored strip
+    std::vector<uint32_t> rows;           // [nsteps * 32]
+    std::vector<uint32_t> desc;           // [nsteps * 8]
+    std::vector<unsigned char> payload;
+    int32_t *d_sptr = nullptr;
+    uint32_t *d_rows = nullptr;
+    uint32_t *d_desc = nullptr;
+    unsigned char *d_payload = nullptr;
+    int64_t bytes = 0;
+};
+
 // Layout for the SpMV kernel (BR, BC <= 32): the compact weights themselves plus one
 // row bit mask and one column bit mask per stored block.
 struct GemvLayout {
@@ -91,6 +117,7 @@ struct grim_bcr_matrix {
     int device = -1;
     grim::DeviceCanonical dev;
     grim::MmaLayout mma;
+    grim::GatherLayout gather;
     grim::GemvLayout gemv;
 };
 
@@ -119,6 +146,13 @@ grim_status launch_spmm_fma(const grim_bcr_matrix *A, const void *X, int64_t N, 
 grim_status launch_spmm_mma(const grim_bcr_matrix *A, const void *X, int64_t N, int64_t ldx, float *Y,
                             int64_t ldy, int32_t tile_n, int32_t strips_per_wg, hipStream_t stream);
 bool mma_supported(const grim_bcr_matrix *A);
+// row-gathering matrix-core kernel; GRIM_ERR_UNSUPPORTED when the matrix or the operands do not qualify
+grim_status launch_spmm_gather(const grim_bcr_matrix *A, const void *X, int64_t N, int64_t ldx, float *Y,
+                               int64_t ldy, hipStream_t stream);
+bool gather_applies(const grim_bcr_matrix *A, const void *X, int64_t N, int64_t ldx);
+// cost estimates (bytes through one compute unit) used to choose between the two matrix-core kernels
+double gather_cost(const grim_bcr_matrix *A, int64_t N);
+double mma_best_shape(const grim_bcr_matrix *A, int64_t N, int32_t tile_n, int32_t strips_per_wg, int *tn_out, int *g_out);
 grim_status launch_spmv(const GemvDesc *table_dev_or_null, const GemvDesc &single, int32_t count,
                         int64_t M, int64_t K, int32_t BR, int32_t BC, int32_t dtype, int32_t ukr,
                         int32_t ukc, int32_t vec, int32_t krmax, int32_t kcmax, const void *x, int64_t x_stride, int32_t batch,

@@ -152,6 +152,58 @@ void build_mma_layout(grim_bcr_matrix *A, int32_t chunk_rows_opt) {
     L.present = true;
 }
 
+// ---- derived layout: row-gathering SpMM ----------------------------------------------------
+void build_gather_layout(grim_bcr_matrix *A) {
+    GatherLayout &L = A->gather;
+    L = GatherLayout();
+    if (A->dtype == GRIM_F32 || A->BR != 16 || A->K > 0x7fffffff) return;
+    const uint16_t *w = reinterpret_cast<const uint16_t *>(A->weights.data());
+    L.sptr.assign((size_t)A->nbr + 1, 0);
+    struct Group { int64_t t; int32_t j0; };
+    std::vector<Group> groups;
+    for (int64_t st = 0; st < A->nbr; ++st) {
+        L.sptr[(size_t)st] = (int32_t)L.nsteps;
+        groups.clear();
+        for (int64_t c = 0; c < A->nbc; ++c) {
+            const int64_t t = st * A->nbc + c;
+            const int32_t kr = A->row_ptr[t + 1] - A->row_ptr[t], kc = A->col_ptr[t + 1] - A->col_ptr[t];
+            if (kr == 0 || kc == 0) continue;
+            for (int32_t j0 = 0; j0 < kc; j0 += 8) groups.push_back({t, j0});
+        }
+        while (groups.size() % 4) groups.push_back({-1, 0});
+        const size_t nst = groups.size() / 4;
+        if ((uint64_t)L.nsteps + nst > 0x7fffffffu) { L = GatherLayout(); return; }
+        const size_t step0 = (size_t)L.nsteps;
+        L.rows.resize((step0 + nst) * 32, 0xffffffffu);
+        L.desc.resize((step0 + nst) * 8, 0u);
+        for (size_t q = 0; q < groups.size(); ++q) {
+            const Group &gp = groups[q];
+            const size_t step = step0 + q / 4, g = q % 4;
+            if (gp.t < 0) continue;                       // padding group: rows stay 0xffffffff, mask 0
+            const int32_t kr = A->row_ptr[gp.t + 1] - A->row_ptr[gp.t], kc = A->col_ptr[gp.t + 1] - A->col_ptr[gp.t];
+            const int64_t c = gp.t % A->nbc;
+            uint32_t rowmask = 0;
+            for (int32_t qq = A->row_ptr[gp.t]; qq < A->row_ptr[gp.t + 1]; ++qq) rowmask |= 1u << A->row_idx[qq];
+            for (int32_t j = 0; j < 8 && gp.j0 + j < kc; ++j) {
+                L.rows[step * 32 + (size_t)j * 4 + g] = (uint32_t)(c * A->BC + A->col_idx[A->col_ptr[gp.t] + gp.j0 + j]);
+                ++L.xrows;
+            }
+            const size_t p0 = L.payload.size();
+            if (p0 / 16 + (size_t)kr > 0xffffffffu) { L = GatherLayout(); return; }
+            L.payload.resize(p0 + (size_t)kr * 16, 0);
+            uint16_t *pw = reinterpret_cast<uint16_t *>(L.payload.data() + p0);
+            for (int32_t i = 0; i < kr; ++i)
+                for (int32_t e = 0; e < 8 && gp.j0 + e < kc; ++e)
+                    pw[i * 8 + e] = w[A->blk_ptr[gp.t] + (int64_t)i * kc + gp.j0 + e];
+            L.desc[step * 8 + g * 2] = rowmask;
+            L.desc[step * 8 + g * 2 + 1] = (uint32_t)(p0 / 16);
+        }
+        L.nsteps += (int64_t)nst;
+    }
+    L.sptr[(size_t)A->nbr] = (int32_t)L.nsteps;
+    L.present = true;
+}
+
 // ---- derived layout: SpMV --------------------------------------------------------------
 void build_gemv_layout(grim_bcr_matrix *A) {
     GemvLayout &G = A->gemv;
@@ -207,6 +259,13 @@ grim_status upload(grim_bcr_matrix *A) {
         o_bp2 = s.add(bytes(A->mma.bptr));
         o_af = s.add(bytes(A->mma.recs) + 2048);   // slack: records are fetched in 1 KB slots
     }
+    size_t o_gs = 0, o_gr = 0, o_gd = 0, o_gp = 0;
+    if (A->gather.present) {
+        o_gs = s.add(bytes(A->gather.sptr));
+        o_gr = s.add(bytes(A->gather.rows) + 16);
+        o_gd = s.add(bytes(A->gather.desc) + 16);
+        o_gp = s.add(bytes(A->gather.payload) + 16);
+    }
     size_t mma_end = s.total;
     if (A->gemv.present) {
         o_gm = s.add(bytes(A->gemv.masks));
@@ -225,6 +284,9 @@ grim_status upload(grim_bcr_matrix *A) {
     if (ok && A->mma.present)
         ok = put(o_kp, A->mma.cptr.data(), bytes(A->mma.cptr)) && put(o_bp2, A->mma.bptr.data(), bytes(A->mma.bptr)) &&
              put(o_af, A->mma.recs.data(), bytes(A->mma.recs));
+    if (ok && A->gather.present)
+        ok = put(o_gs, A->gather.sptr.data(), bytes(A->gather.sptr)) && put(o_gr, A->gather.rows.data(), bytes(A->gather.rows)) &&
+             put(o_gd, A->gather.desc.data(), bytes(A->gather.desc)) && put(o_gp, A->gather.payload.data(), bytes(A->gather.payload));
     if (ok && A->gemv.present)
         ok = put(o_gm, A->gemv.masks.data(), bytes(A->gemv.masks)) && put(o_go, A->gemv.woff.data(), bytes(A->gemv.woff));
     if (!ok) { (void)hipGetLastError(); (void)hipFree(base); return GRIM_ERR_DEVICE; }
@@ -242,6 +304,13 @@ grim_status upload(grim_bcr_matrix *A) {
         A->mma.d_bptr = reinterpret_cast<int32_t *>(base + o_bp2);
         A->mma.d_recs = reinterpret_cast<unsigned char *>(base + o_af);
         A->mma.bytes = (int64_t)(mma_end - canon_end);
+    }
+    if (A->gather.present) {
+        A->gather.d_sptr = reinterpret_cast<int32_t *>(base + o_gs);
+        A->gather.d_rows = reinterpret_cast<uint32_t *>(base + o_gr);
+        A->gather.d_desc = reinterpret_cast<uint32_t *>(base + o_gd);
+        A->gather.d_payload = reinterpret_cast<unsigned char *>(base + o_gp);
+        A->gather.bytes = (int64_t)(o_gp + bytes(A->gather.payload) + 16 - o_gs);
     }
     if (A->gemv.present) {
         A->gemv.d_masks = reinterpret_cast<uint32_t *>(base + o_gm);
@@ -352,6 +421,7 @@ grim_status grim_bcr_pack(const void *W_host, grim_dtype dt, int64_t M, int64_t 
         }
         if (!(opt && opt->host_only)) {
             build_mma_layout(A, opt ? opt->chunk_rows : 0);
+            build_gather_layout(A);
             build_gemv_layout(A);
         }
     } catch (const std::bad_alloc &) {
@@ -407,22 +477,56 @@ grim_status grim_bcr_arrays(const grim_bcr_matrix *A, grim_bcr_view *v) {
     return GRIM_OK;
 }
 
+// which kernel family a grim_bcr_spmm_tuned call runs
+enum SpmmRoute { ROUTE_NONE, ROUTE_SPMV, ROUTE_FMA, ROUTE_MMA, ROUTE_GATHER };
+static SpmmRoute spmm_route(const grim_bcr_matrix *A, const void *X_dev, int64_t N, int64_t ldx, int32_t tile_n,
+                            int32_t strips_per_wg, int32_t kernel) {
+    if (kernel < 0 || kernel > 3 || tile_n < 0 || strips_per_wg < 0) return ROUTE_NONE;
+    const bool free_choice = kernel == 0 && tile_n == 0 && strips_per_wg == 0;
+    if (kernel == 3) return !tile_n && !strips_per_wg && gather_applies(A, X_dev, N, ldx) ? ROUTE_GATHER : ROUTE_NONE;
+    if (free_choice && gemv_ok(A, N)) return ROUTE_SPMV;
+    const bool mma = A->mma.present && kernel != 1;
+    if (kernel == 2 && !mma) return ROUTE_NONE;
+    if (free_choice && gather_applies(A, X_dev, N, ldx)) {
+        // both matrix-core kernels apply: take the one that moves fewer bytes through a compute unit
+        int tn = 0, g = 0;
+        const double staged = mma ? mma_best_shape(A, N, 0, 0, &tn, &g) : -1.0;
+        if (staged < 0 || gather_cost(A, N) < staged) return ROUTE_GATHER;
+    }
+    if (mma) return ROUTE_MMA;
+    return A->BR > 64 ? ROUTE_NONE : ROUTE_FMA;
+}
+
 grim_status grim_bcr_spmm_tuned(const grim_bcr_matrix *A, const void *X_dev, int64_t N, int64_t ldx, float *Y_dev,
                                 int64_t ldy, int32_t tile_n, int32_t strips_per_wg, int32_t kernel, void *hip_stream) {
     grim_status st = check_call(A, X_dev, N, ldx, Y_dev, ldy);
     if (st != GRIM_OK) return st;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    if (kernel < 0 || kernel > 2 || tile_n < 0 || strips_per_wg < 0) return GRIM_ERR_UNSUPPORTED;
-    if (kernel == 0 && tile_n == 0 && strips_per_wg == 0 && gemv_ok(A, N)) {
-        GemvDesc d = desc_of(A);
-        return launch_spmv(nullptr, d, 1, A->M, A->K, A->BR, A->BC, A->dtype, A->gemv.uniform_kr, A->gemv.uniform_kc,
-                           A->gemv.vec, A->gemv.krmax, A->gemv.kcmax, X_dev, 0, (int32_t)N, ldx, Y_dev, 0, ldy, stream);
+    switch (spmm_route(A, X_dev, N, ldx, tile_n, strips_per_wg, kernel)) {
+        case ROUTE_SPMV: {
+            GemvDesc d = desc_of(A);
+            return launch_spmv(nullptr, d, 1, A->M, A->K, A->BR, A->BC, A->dtype, A->gemv.uniform_kr, A->gemv.uniform_kc,
+                               A->gemv.vec, A->gemv.krmax, A->gemv.kcmax, X_dev, 0, (int32_t)N, ldx, Y_dev, 0, ldy, stream);
+        }
+        case ROUTE_GATHER: return launch_spmm_gather(A, X_dev, N, ldx, Y_dev, ldy, stream);
+        case ROUTE_MMA: return launch_spmm_mma(A, X_dev, N, ldx, Y_dev, ldy, tile_n, strips_per_wg, stream);
+        case ROUTE_FMA: return launch_spmm_fma(A, X_dev, N, ldx, Y_dev, ldy, stream);
+        case ROUTE_NONE: break;
     }
-    bool mma = A->mma.present && kernel != 1;
-    if (kernel == 2 && !mma) return GRIM_ERR_UNSUPPORTED;
-    if (mma) return launch_spmm_mma(A, X_dev, N, ldx, Y_dev, ldy, tile_n, strips_per_wg, stream);
-    if (A->BR > 64) return GRIM_ERR_UNSUPPORTED;
-    return launch_spmm_fma(A, X_dev, N, ldx, Y_dev, ldy, stream);
+    return GRIM_ERR_UNSUPPORTED;
+}
+
+const char *grim_bcr_spmm_kernel_name(const grim_bcr_matrix *A, const void *X_dev, int64_t N, int64_t ldx, int32_t tile_n,
+                                      int32_t strips_per_wg, int32_t kernel) {
+    if (!A || !X_dev || N < 1 || ldx < N || !A->on_device) return "none";
+    switch (spmm_route(A, X_dev, N, ldx, tile_n, strips_per_wg, kernel)) {
+        case ROUTE_SPMV: return "bcr_spmv";
+        case ROUTE_GATHER: return "bcr_spmm_gather";
+        case ROUTE_MMA: return "bcr_spmm_mma";
+        case ROUTE_FMA: return "bcr_spmm_fma";
+        case ROUTE_NONE: break;
+    }
+    return "none";
 }
 
 grim_status grim_bcr_spmm(const grim_bcr_matrix *A, const void *X_dev, int64_t N, int64_t ldx, float *Y_dev, int64_t ldy,

@@ -542,6 +542,204 @@ __global__ void __launch_bounds__((NW + NP) * 64) bcr_spmm_mma(MmaParams p) {
     }
 }
 
+// ------------------------------------------------------------------------------------------
+// row-gathering matrix-core kernel (fp16 / bf16, BR = 16, X rows 16-byte aligned)
+//
+// Workgroup = (tile of 64 columns of X, one stored strip); its 4 waves split the strip's steps
+// (i.e. K) between them and add their partial tiles in a fixed order at the end -- the only
+// barrier.  A wave works on its own: it reads the row numbers and block descriptors of a batch
+// of steps, then fetches exactly the rows of X those steps multiply (8 lanes per 128-byte row
+// piece) and the kept rows of the blocks' weights straight into registers, parks the X rows of
+// one step in a private 4 KB LDS buffer in k-slot order, and reads them back with transpose
+// reads as MFMA operands.  No producer/consumer hand-over: latency is covered by the four
+// workgroups a compute unit holds and by the batch of loads a wave has in flight.
+// Unlike the staged kernel a row of X is fetched once per strip that keeps it (not once per
+// group of strips), but only kept rows are fetched, and every compute unit has work even when
+// the tiles are few.
+// ------------------------------------------------------------------------------------------
+struct GatherParams {
+    const int32_t *sptr;
+    const uint32_t *rows;
+    const uint32_t *desc;
+    const unsigned char *payload;
+    const int32_t *strip_order;
+    const unsigned short *X;
+    float *Y;
+    int64_t N, ldx, ldy;
+    int32_t nbr, ntiles;
+    int32_t yvec;
+};
+
+template <bool BF16, bool WIDE>   // WIDE: rows of X are 16-byte aligned (else 8-byte: two loads per piece)
+__global__ void __launch_bounds__(256, 4) bcr_spmm_gather(GatherParams p) {
+    constexpr int NT = 4, TN = 64, PITCH = 128, CPR = 8;
+    constexpr int SB = 4;                        // steps a wave has in flight
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+    // workgroup -> (tile, stored strip); all strips of a tile run on the same XCD
+    const int id = blockIdx.x;
+    const int xcd = id & 7, slot = id >> 3;
+    const int tile = (slot / p.nbr) * 8 + xcd;
+    const int t = slot % p.nbr;
+    if (tile >= p.ntiles) return;
+    int64_t n0 = (int64_t)tile * TN;
+    if (n0 + TN > p.N) n0 = p.N - TN;            // ragged last tile: overlap the neighbour (N >= 64, N % 4 == 0)
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int g0 = p.sptr[t], nst = p.sptr[t + 1] - g0;
+    const int s_beg = g0 + (int)((int64_t)nst * wave / 4), s_end = g0 + (int)((int64_t)nst * (wave + 1) / 4);
+    char *buf = lds + wave * 8192;               // two step buffers of 32 rows x 128 bytes
+
+    // fetch side: lane = (row slot rs, 16-byte piece c); its i-th load is k slot i * 8 + rs
+    const int rs = lane >> 3, c = lane & 7;
+    const unsigned short *xcol = p.X + n0 + c * 8;
+    int wr_off[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int lrow = i * 8 + rs;
+        wr_off[i] = lrow * PITCH + ((c ^ swizzle<CPR>(lrow)) << 4);
+    }
+    // multiply side: lane = (output row m_row, k group); the two transpose reads of a sub-tile
+    // name k slots kgroup * 8 + qd and + 4
+    const int i16 = lane & 15, kgroup = lane >> 4, qd = i16 >> 2, m_row = i16;
+    const unsigned int below = (1u << m_row) - 1u;
+    const int ncolb = (4 * (i16 & 3)) * 2, cl = ncolb >> 4, within = ncolb & 15;
+    const int r0 = kgroup * 8 + qd, r1 = r0 + 4;
+    const int sw0 = swizzle<CPR>(r0), sw1 = swizzle<CPR>(r1);
+    const int x0 = r0 * PITCH + within, x1 = r1 * PITCH + within;
+
+    f32x4 acc[NT];
+#pragma unroll
+    for (int q = 0; q < NT; ++q) acc[q] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    const u32x4 *rows4 = reinterpret_cast<const u32x4 *>(p.rows);
+    const uint2 *desc2 = reinterpret_cast<const uint2 *>(p.desc);
+    const i16x8 *pay = reinterpret_cast<const i16x8 *>(p.payload);
+    for (int s = s_beg; s < s_end; s += SB) {
+        const int nb = s_end - s < SB ? s_end - s : SB;
+        u32x4 hdr[SB];
+        uint2 dsc[SB];
+#pragma unroll
+        for (int u = 0; u < SB; ++u) {
+            const int st = s + (u < nb ? u : nb - 1);
+            hdr[u] = rows4[(int64_t)st * 8 + rs];
+            dsc[u] = desc2[(int64_t)st * 4 + kgroup];
+        }
+        u32x4 RX[SB][4];
+        i16x8 PW[SB];
+#pragma unroll
+        for (int u = 0; u < SB; ++u) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const unsigned int row = hdr[u][i] == 0xffffffffu ? 0u : hdr[u][i];
+                const unsigned short *src = xcol + (int64_t)row * p.ldx;
+                if constexpr (WIDE) {
+                    RX[u][i] = *reinterpret_cast<const u32x4 *>(src);
+                } else {
+                    const uint2 a = *reinterpret_cast<const uint2 *>(src);
+                    const uint2 b = *reinterpret_cast<const uint2 *>(src + 4);
+                    RX[u][i] = u32x4{a.x, a.y, b.x, b.y};
+                }
+            }
+            const bool kept = (dsc[u].x >> m_row) & 1u;
+            const unsigned int idx = dsc[u].y + (kept ? __builtin_popcount(dsc[u].x & below) : 0);
+            const i16x8 wv = pay[idx];           // a block's first kept row if this lane's is not kept (zeroed below)
+            PW[u] = kept ? wv : i16x8{0, 0, 0, 0, 0, 0, 0, 0};
+        }
+#pragma unroll
+        for (int u = 0; u < SB; ++u) {
+            if (u < nb) {
+                char *b = buf + (u & 1) * 4096;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const u32x4 v = hdr[u][i] == 0xffffffffu ? u32x4{0u, 0u, 0u, 0u} : RX[u][i];
+                    *reinterpret_cast<u32x4 *>(b + wr_off[i]) = v;
+                }
+                __builtin_amdgcn_wave_barrier();
+#pragma unroll
+                for (int q = 0; q < NT; ++q) {
+                    const int cq = q * 2 + cl;
+                    const i16x4 lo = lds_tr_read(b + x0 + ((cq ^ sw0) << 4));
+                    const i16x4 hi = lds_tr_read(b + x1 + ((cq ^ sw1) << 4));
+                    const i16x8 x = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+                    acc[q] = mfma16<BF16>(x, PW[u], acc[q]);
+                }
+                __builtin_amdgcn_wave_barrier();
+            }
+        }
+    }
+
+    // add the four waves' partial tiles in wave order; wave q finishes sub-tile q.  A wave parks
+    // its partial tile in its own (now idle) step buffers.
+    f32x4 *red = reinterpret_cast<f32x4 *>(lds);
+#pragma unroll
+    for (int q = 0; q < NT; ++q) red[wave * 512 + q * 64 + lane] = acc[q];
+    __syncthreads();
+    const int q = wave;
+    f32x4 sum = red[q * 64 + lane];
+#pragma unroll
+    for (int w = 1; w < 4; ++w) {
+        const f32x4 v = red[w * 512 + q * 64 + lane];
+        sum[0] += v[0]; sum[1] += v[1]; sum[2] += v[2]; sum[3] += v[3];
+    }
+    // D[n][m]: lane holds m = lane % 16, n = 4 * (lane / 16) + 0..3
+    const int64_t row = (int64_t)p.strip_order[t] * 16 + (lane & 15);
+    const int64_t n = n0 + q * 16 + 4 * (lane >> 4);
+    float *dst = p.Y + row * p.ldy + n;
+    if (p.yvec == 4) {
+        *reinterpret_cast<f32x4 *>(dst) = sum;
+    } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) dst[e] = sum[e];
+    }
+}
+
+bool gather_applies(const grim_bcr_matrix *A, const void *X, int64_t N, int64_t ldx) {
+    return A->gather.present && N >= 64 && N % 4 == 0 && ldx % 4 == 0 && reinterpret_cast<uintptr_t>(X) % 8 == 0;
+}
+
+// Bytes through one compute unit, the quantity both matrix-core kernels are bound by at these
+// sizes: a workgroup fetches the rows of X its strip keeps (128 bytes each) and the strip's
+// records, pays a start-up, and 256 compute units share the workgroups.
+double gather_cost(const grim_bcr_matrix *A, int64_t N) {
+    const GatherLayout &L = A->gather;
+    const double nbr = (double)A->nbr;
+    const double per_wg = (double)L.xrows / nbr * 128.0 +
+                          ((double)L.nsteps * 160.0 + (double)L.payload.size()) / nbr + 30e3;
+    const double nwg = (double)((N + 63) / 64) * nbr;
+    return (nwg > 256.0 ? nwg / 256.0 : 1.0) * per_wg;
+}
+
+grim_status launch_spmm_gather(const grim_bcr_matrix *A, const void *X, int64_t N, int64_t ldx, float *Y, int64_t ldy,
+                               hipStream_t stream) {
+    if (!gather_applies(A, X, N, ldx)) return GRIM_ERR_UNSUPPORTED;
+    GatherParams p;
+    p.sptr = A->gather.d_sptr;
+    p.rows = A->gather.d_rows;
+    p.desc = A->gather.d_desc;
+    p.payload = A->gather.d_payload;
+    p.strip_order = A->dev.strip_order;
+    p.X = static_cast<const unsigned short *>(X);
+    p.Y = Y;
+    p.N = N; p.ldx = ldx; p.ldy = ldy;
+    p.nbr = (int32_t)A->nbr;
+    p.ntiles = (int32_t)((N + 63) / 64);
+    p.yvec = (reinterpret_cast<uintptr_t>(Y) % 16 == 0 && ldy % 4 == 0 && N % 4 == 0) ? 4 : 1;
+    const int64_t nwg = ((int64_t)p.ntiles + 7) / 8 * 8 * p.nbr;
+    if (nwg > 0x7fffffff) return GRIM_ERR_SHAPE;
+    const size_t lds = 4 * 8192;
+    const bool wide = N % 8 == 0 && ldx % 8 == 0 && reinterpret_cast<uintptr_t>(X) % 16 == 0;
+    const dim3 grid((unsigned)nwg), block(256);
+    if (A->dtype == GRIM_BF16) {
+        if (wide) hipLaunchKernelGGL((bcr_spmm_gather<true, true>), grid, block, lds, stream, p);
+        else hipLaunchKernelGGL((bcr_spmm_gather<true, false>), grid, block, lds, stream, p);
+    } else {
+        if (wide) hipLaunchKernelGGL((bcr_spmm_gather<false, true>), grid, block, lds, stream, p);
+        else hipLaunchKernelGGL((bcr_spmm_gather<false, false>), grid, block, lds, stream, p);
+    }
+    return hipGetLastError() == hipSuccess ? GRIM_OK : GRIM_ERR_DEVICE;
+}
+
 bool mma_supported(const grim_bcr_matrix *A) { return A->mma.present; }
 
 static int amax_of(const grim_bcr_matrix *A, int g) { return A->mma.amax[g <= 4 ? 0 : g <= 8 ? 1 : g <= 16 ? 2 : 3]; }
@@ -608,6 +806,31 @@ static grim_status launch_mma_br(MmaParams &p, const grim_bcr_matrix *A, int til
     return GRIM_ERR_UNSUPPORTED;
 }
 
+// Pick the launch shape by bytes through one compute unit: a workgroup streams its tile's rows of
+// X (64-byte row pieces of a 32-column tile cost about 1.8x per byte), the records of its strips,
+// and pays a fixed start-up; workgroups beyond 256 run in rounds.  Returns the cost (< 0: no
+// compiled shape fits); tile_n / strips_per_wg != 0 pin that knob.
+double mma_best_shape(const grim_bcr_matrix *A, int64_t N, int32_t tile_n, int32_t strips_per_wg, int *tn_out, int *g_out) {
+    if (!A->mma.present) return -1.0;
+    const double rec_total = (double)A->mma.recs.size();
+    double best = -1.0;
+    for (int t : {64, 32}) {
+        if (tile_n && t != tile_n) continue;
+        for (int g : {16, 8, 4}) {
+            if (strips_per_wg && g != strips_per_wg) continue;
+            if (g > 4 && A->nbr <= g / 2) continue;
+            if (!mma_shape_fits(A, t, g)) continue;
+            const int64_t nwg = ((N + t - 1) / t) * ((A->nbr + g - 1) / g);
+            const double rounds = (double)((nwg + 255) / 256);
+            const double bytes = (double)A->K * t * 2 * (t == 32 ? 1.8 : 1.0) +
+                                 rec_total * (double)(g < A->nbr ? g : A->nbr) / (double)A->nbr + 100e3;
+            const double cost = rounds * bytes;
+            if (best < 0 || cost < best) { best = cost; *tn_out = t; *g_out = g; }
+        }
+    }
+    return best;
+}
+
 grim_status launch_spmm_mma(const grim_bcr_matrix *A, const void *X, int64_t N, int64_t ldx, float *Y, int64_t ldy,
                             int32_t tile_n, int32_t strips_per_wg, hipStream_t stream) {
     if (!A->mma.present) return GRIM_ERR_UNSUPPORTED;
@@ -615,29 +838,7 @@ grim_status launch_spmm_mma(const grim_bcr_matrix *A, const void *X, int64_t N, 
     if (strips_per_wg != 0 && strips_per_wg != 4 && strips_per_wg != 8 && strips_per_wg != 16) return GRIM_ERR_UNSUPPORTED;
     int tn = tile_n, strips = strips_per_wg;
     if (!tn || !strips) {
-        // Pick the launch shape by bytes through one compute unit: a workgroup streams its tile's
-        // rows of X (64-byte row pieces of a 32-column tile cost about 1.8x per byte), the records
-        // of its strips, and pays a fixed start-up; workgroups beyond 256 run in rounds.
-        const double rec_total = (double)A->mma.recs.size();
-        double best = 0;
-        int best_tn = 0, best_g = 0;
-        for (int t : {64, 32}) {
-            if (tile_n && t != tile_n) continue;
-            for (int g : {16, 8, 4}) {
-                if (strips_per_wg && g != strips_per_wg) continue;
-                if (g > 4 && A->nbr <= g / 2) continue;
-                if (!mma_shape_fits(A, t, g)) continue;
-                const int64_t nwg = ((N + t - 1) / t) * ((A->nbr + g - 1) / g);
-                const double rounds = (double)((nwg + 255) / 256);
-                const double bytes = (double)A->K * t * 2 * (t == 32 ? 1.8 : 1.0) +
-                                     rec_total * (double)(g < A->nbr ? g : A->nbr) / (double)A->nbr + 100e3;
-                const double cost = rounds * bytes;
-                if (!best_tn || cost < best) { best = cost; best_tn = t; best_g = g; }
-            }
-        }
-        if (!best_tn) return GRIM_ERR_UNSUPPORTED;
-        tn = best_tn;
-        strips = best_g;
+        if (mma_best_shape(A, N, tile_n, strips_per_wg, &tn, &strips) < 0) return GRIM_ERR_UNSUPPORTED;
     }
     if (!mma_shape_fits(A, tn, strips)) return GRIM_ERR_UNSUPPORTED;
     MmaParams p;

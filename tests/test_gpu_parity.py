@@ -252,6 +252,57 @@ def test_spmv_falls_back_when_blocks_exceed_masks(g):
     assert_close(run_spmv(g, A, x, dtype, M, 2), yref, S, dtype, "spmv 64x64 blocks")
 
 
+# ------------------------------------------------------------------ row-gathering matrix-core kernel
+@pytest.mark.parametrize("dtype", [gen.F16, gen.BF16])
+@pytest.mark.parametrize("N,ldx_pad,ldy_pad", [(64, 0, 0), (200, 0, 0), (196, 0, 0), (328, 8, 4), (132, 4, 3)])
+def test_gather_kernel_shapes(g, dtype, N, ldx_pad, ldy_pad):
+    """kernel = 3 forced: tiles that overlap at the ragged end, rows of X aligned to 16 and to 8 bytes,
+    padded leading dimensions (Y with a stride that rules out 16-byte stores), non-uniform blocks with
+    empty ones, strips with fewer steps than waves, an all-empty strip."""
+    M, K, BR, BC = 16 * 9, 32 * 23, 16, 32
+    mask = gen.random_mask(M, K, BR, BC, (0, 1, 5, 8, 16), (0, 3, 8, 17, 32), seed=300)
+    # strip 2 keeps nothing at all, strip 4 a single block
+    keep_r, keep_c = [], []
+    nbc = K // BC
+    for b in range((M // BR) * nbc):
+        r = mask.row_idx[mask.row_ptr[b]:mask.row_ptr[b + 1]]
+        c = mask.col_idx[mask.col_ptr[b]:mask.col_ptr[b + 1]]
+        s_, c_ = divmod(b, nbc)
+        if s_ == 2 or (s_ == 4 and c_ != 7):
+            r, c = r[:0], c[:0]
+        keep_r.append(r); keep_c.append(c)
+    mask = gen.mask_from_sets(M, K, BR, BC, keep_r, keep_c)
+    W = gen.normal_weights(M, K, dtype, seed=301)
+    X = gen.normal_activations(K, N, dtype, seed=302)
+    A = pack_workload(g, W, dtype, mask)
+    Yref, S = oracle_product(W, X, dtype, mask)
+    Y = run_spmm(g, A, X, dtype, M, N, ldx=N + ldx_pad, ldy=N + ldy_pad, kernel=3)
+    assert_close(Y, Yref, S, dtype, f"gather {dtype} N={N}")
+    Y2 = run_spmm(g, A, X, dtype, M, N, ldx=N + ldx_pad, ldy=N + ldy_pad, kernel=3)
+    assert Y2.tobytes() == Y.tobytes()
+
+
+def test_gather_kernel_c2_and_refusals(g):
+    wl = gen.c2_vgg_conv(3136)
+    A = pack_workload(g, wl.W, wl.dtype, wl.mask)
+    Yref, S = oracle_product(wl.W, wl.X, wl.dtype, wl.mask)
+    Y = run_spmm(g, A, wl.X, wl.dtype, wl.M, wl.N, kernel=3)
+    assert_close(Y, Yref, S, wl.dtype, "gather c2")
+    from paper_2108_11033_amd.binding import GrimError
+    for N in (8, 63, 66, 201):                                   # too narrow / rows not 8-byte aligned
+        X = gen.normal_activations(wl.K, N, wl.dtype, seed=303)
+        with pytest.raises(GrimError) as e:
+            run_spmm(g, A, X, wl.dtype, wl.M, N, kernel=3)
+        assert e.value.status == 7
+    with pytest.raises(GrimError):                                # tile knobs belong to the staged kernel
+        run_spmm(g, A, wl.X, wl.dtype, wl.M, wl.N, kernel=3, tile_n=64)
+    wl5 = gen.c5_nonuniform(64)                                   # 32-row blocks: staged kernel only
+    A5 = pack_workload(g, wl5.W, wl5.dtype, wl5.mask)
+    with pytest.raises(GrimError) as e:
+        run_spmm(g, A5, wl5.X, wl5.dtype, wl5.M, wl5.N, kernel=3)
+    assert e.value.status == 7
+
+
 # Every (kept rows, kept columns) pair the uniform one-right-hand-side kernel is compiled for, in each
 # element type, with: 16- and 32-row blocks (4 and 2 output lane groups), a strip of more than 64 column
 # blocks (two passes of lanes, the second ragged), a strip count that is not a multiple of the 4 strips
