@@ -212,7 +212,21 @@ def main() -> int:
         extra["c5"] = {"us": t5 * 1e6, "useful_tflops": w5.useful_flops() / t5 / 1e12, "algorithmic_mb": b5 / 1e6,
                        "gbs": b5 / t5 / 1e9, "frac_hbm": b5 / t5 / 1e9 / HBM_PEAK_GBS, "nnz": v5["nnz"],
                        "mma_layout_mb": v5["dev_bytes_mma"] / 1e6}
+        extra["c5"]["kernel"] = g.spmm_kernel_name(A5, X5, w5.N, w5.N)
         del X5, X5b, Y5, XX, A5
+        # ---- c2's layer at a large N (224 x 224 positions): the same weights, 16x the columns
+        wb = gen.c2_vgg_conv(50176)
+        Ab = pack(wb)
+        vb = view_dict(Ab)
+        Xb = [dev_tensor(wb.X, wb.dtype)]
+        Xb.append(Xb[0].clone())
+        Yb = [torch.empty((wb.M, wb.N), dtype=torch.float32, device=dev) for _ in range(2)]
+        tb, _ = time_launches(torch, lambda i: g.spmm(Ab, Xb[i % 2], wb.N, wb.N, Yb[i % 2], wb.N, stream), 30, 3)
+        bb = spmm_algorithmic_bytes(vb, wb.N, 2)
+        extra["c2_N50176"] = {"us": tb * 1e6, "useful_tflops": wb.useful_flops() / tb / 1e12, "algorithmic_mb": bb / 1e6,
+                              "gbs": bb / tb / 1e9, "frac_hbm": bb / tb / 1e9 / HBM_PEAK_GBS,
+                              "kernel": g.spmm_kernel_name(Ab, Xb[0], wb.N, wb.N)}
+        del Xb, Yb, Ab
         # ---- c4: the 13 VGG-16 conv layers
         layers = []
         tot_t = tot_b = tot_f = 0.0
@@ -227,7 +241,8 @@ def main() -> int:
             t4, _ = time_launches(torch, lambda i: g.spmm(A4, X4[i % nset], w4.N, w4.N, Y4[i % nset], w4.N, stream), 100, 10)
             b4 = spmm_algorithmic_bytes(v4, w4.N, 2)
             layers.append({"layer": li + 1, "M": w4.M, "K": w4.K, "N": w4.N, "us": t4 * 1e6,
-                           "useful_tflops": w4.useful_flops() / t4 / 1e12, "gbs": b4 / t4 / 1e9})
+                           "useful_tflops": w4.useful_flops() / t4 / 1e12, "gbs": b4 / t4 / 1e9,
+                           "kernel": g.spmm_kernel_name(A4, X4[0], w4.N, w4.N)})
             tot_t += t4; tot_b += b4; tot_f += w4.useful_flops()
             del X4, Y4, A4
         extra["c4"] = {"layers": layers, "total_us": tot_t * 1e6, "useful_tflops": tot_f / tot_t / 1e12,

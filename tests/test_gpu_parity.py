@@ -303,6 +303,28 @@ def test_gather_kernel_c2_and_refusals(g):
     assert e.value.status == 7
 
 
+def test_kernel_choice_follows_the_cost_model(g):
+    """grim_bcr_spmm_kernel_name reports the route; few tiles per strip group -> row-gathering kernel, very
+    many tiles of a many-strip matrix -> staged kernel; fp32 -> FMA kernel; N <= 8 -> SpMV."""
+    torch, dev = torch_dev()
+    wl = gen.c2_vgg_conv(200)
+    A = pack_workload(g, wl.W, wl.dtype, wl.mask)
+    X = to_device(wl.X, wl.dtype)
+    assert g.spmm_kernel_name(A, X, 200, 200) == "bcr_spmm_gather"
+    assert g.spmm_kernel_name(A, X, 200, 200, kernel=2) == "bcr_spmm_mma"
+    assert g.spmm_kernel_name(A, X, 200, 200, tile_n=64) == "bcr_spmm_mma"
+    assert g.spmm_kernel_name(A, X, 8, 200) == "bcr_spmv"
+    assert g.spmm_kernel_name(A, X, 199, 200) == "bcr_spmm_mma"       # rows not 8-byte aligned
+    assert g.spmm_kernel_name(A, X, 200, 200, kernel=1) == "bcr_spmm_fma"
+    assert g.spmm_kernel_name(A, X, 200, 100) == "none"               # ldx < N
+    big = torch.empty(16, dtype=torch.float16, device=dev)            # only the address is looked at
+    assert g.spmm_kernel_name(A, big, 50176, 50176) == "bcr_spmm_mma"
+    w1 = gen.c1_single_fp32()
+    A1 = pack_workload(g, w1.W, w1.dtype, w1.mask)
+    assert g.spmm_kernel_name(A1, to_device(w1.X, w1.dtype), w1.N, w1.N) == "bcr_spmm_fma"
+    assert g.spmm_kernel_name(A1, to_device(w1.X, w1.dtype), w1.N, w1.N, kernel=3) == "none"
+
+
 # Every (kept rows, kept columns) pair the uniform one-right-hand-side kernel is compiled for, in each
 # element type, with: 16- and 32-row blocks (4 and 2 output lane groups), a strip of more than 64 column
 # blocks (two passes of lanes, the second ragged), a strip count that is not a multiple of the 4 strips
