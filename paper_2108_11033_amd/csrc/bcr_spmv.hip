@@ -3,10 +3,10 @@
 //
 // The compact weights ARE the memory traffic here, so they are read exactly once, in their
 // compact kept-rows x kept-columns form (Section 4.3), with 8 bytes of row / column bit masks
-// per block as the only index data.  Three kernels: one right-hand side goes to the
-// wave-per-strip kernels further down (bcr_spmv_wave_exact when every block keeps the same
-// counts, else bcr_spmv_wave); 2..8 right-hand sides to bcr_spmv, where one workgroup owns one
-// row strip:
+// per block as the only index data.  Matrices whose blocks all keep the same counts go to the
+// wave-per-strip kernels further down (bcr_spmv_wave_exact for one right-hand side,
+// bcr_spmv_wave_exact_b for several in a large launch); everything else to bcr_spmv, where one
+// workgroup owns one row strip:
 //   1. the strip's weights -- one contiguous byte range -- its block masks and x are fetched with
 //      coalesced 16-byte loads, all issued before any is used, and parked in LDS;
 //   2. a group of LPB lanes takes a block, lane i its compact row i: a dot product over the
@@ -106,23 +106,6 @@ __device__ __forceinline__ int nth_set_bit(unsigned int m, int j) {
 }
 
 __host__ __device__ inline int gemv_xg_stride(int kcmax, int B) { return ((kcmax + 7) & ~7) * B; }
-
-// Wave kernel: elements between the private gathered-x rows of neighbouring lanes.  An odd
-// multiple of 8 bytes, so that the 64 lanes' 8-byte reads spread over all LDS banks.
-__host__ __device__ inline int wave_xg_stride(int kcmax, int esz) {
-    int units = (kcmax * esz + 7) / 8;      // 8-byte units per row
-    if (!(units & 1)) ++units;
-    return units * 8 / esz;
-}
-
-// The staged weights of a strip are one linear byte range; lane l works on block l, so at any
-// moment the lanes read addresses one block size apart -- for most block sizes that is a
-// handful of LDS banks.  XOR-ing the 16-byte vector index with higher bits of itself scatters
-// them over the banks; writer and readers apply the same permutation.
-__device__ __forceinline__ unsigned int wave_swz(unsigned int byte_addr) {
-    const unsigned int v = byte_addr >> 4;
-    return ((v ^ ((v >> 3) & 7u)) << 4) | (byte_addr & 15u);
-}
 
 template <int DT, int B, int VEC>
 __global__ void __launch_bounds__(256, (B == 1 ? 6 : 1)) bcr_spmv(GemvParams p) {
@@ -314,264 +297,7 @@ __global__ void __launch_bounds__(256, (B == 1 ? 6 : 1)) bcr_spmv(GemvParams p) 
     GEMV_STAMP(7);
 }
 
-// ------------------------------------------------------------------------------------------
-// One right-hand side: one WAVE per strip, one LANE per block.
-//
-// With a single x the work per weight is one FMA, so the cost that matters is every instruction
-// that is not an FMA.  Here each lane owns a whole block of the strip (64 blocks per pass):
-//   - its two bit masks stay in registers (no index traffic through LDS);
-//   - it walks the set bits of its column mask once, parking the gathered x values in a private
-//     LDS row that all of its kept rows then reuse (Section 4.4);
-//   - it computes its kept rows one after the other from the strip's weights, which the wave
-//     fetched as one contiguous range with 16-byte loads and parked in LDS;
-//   - it scatters each row's sum to a [strip row][block] table (zero where a block does not keep
-//     the row); lane pairs then add each strip row's 64 entries in ascending block order.
-// A workgroup is four such waves (four consecutive strips) sharing one LDS copy of x.
-// ------------------------------------------------------------------------------------------
-constexpr int kWaveWLoads = 16;                    // 16 KB of weights per wave per pass
-constexpr int kPartStride = 66;                    // floats per strip row of the partial table
-
-template <int DT, int VEC, int KRMAX, int KCMAX>
-__global__ void __launch_bounds__(256) bcr_spmv_wave(GemvParams p) {
-    using T = typename GElem<DT>::type;
-    struct __attribute__((aligned(sizeof(T) * VEC))) WVec { T v[VEC]; };
-    extern __shared__ __attribute__((aligned(16))) char smem[];
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int xgs = wave_xg_stride(KCMAX, (int)sizeof(T));
-    const int xbytes = (p.K * (int)sizeof(T) + 15) & ~15;
-    const int region = p.wbytes + 64 * xgs * (int)sizeof(T);      // per wave: weights / partial table, gathered x
-    T *xs = reinterpret_cast<T *>(smem);
-    char *wl = smem + xbytes + wave * region;
-    float *part = reinterpret_cast<float *>(wl);                  // reuses the weights' space
-    T *xg = reinterpret_cast<T *>(wl + p.wbytes) + lane * xgs;    // this lane's gathered x
-
-    const int64_t mi = blockIdx.y;
-    const GemvGlobal d = to_global(p.table ? p.table[mi] : p.single);
-    const GRIM_GLOBAL char *W = d.weights;
-    const GRIM_GLOBAL T *x = (const GRIM_GLOBAL T *)p.x + mi * p.x_stride;
-    GRIM_GLOBAL float *y = (GRIM_GLOBAL float *)p.y + mi * p.y_stride;
-
-    GEMV_STAMP(0);
-    // x -> LDS, once per workgroup
-    if (p.xvec16) {
-        const int nxv = p.K * (int)sizeof(T) / 16;
-        const GRIM_GLOBAL gu32x4 *xsrc = reinterpret_cast<const GRIM_GLOBAL gu32x4 *>(x);
-        gu32x4 xreg[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-            if (i * 256 < nxv) {
-                int v = tid + i * 256;
-                v = v < nxv ? v : nxv - 1;
-                xreg[i] = xsrc[v];
-            }
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int v = tid + i * 256;
-            if (v < nxv) reinterpret_cast<gu32x4 *>(xs)[v] = xreg[i];
-        }
-        for (int v = tid + 1024; v < nxv; v += 256) reinterpret_cast<gu32x4 *>(xs)[v] = xsrc[v];
-    } else {
-        for (int e = tid; e < p.K; e += 256) xs[e] = x[(int64_t)e * p.ldx];
-    }
-    __syncthreads();
-    GEMV_STAMP(1);
-    // This wave's strips: sps consecutive stored strips, each cut into segments of at most
-    // seg_blocks column blocks.  The (strip, segment) items are processed in order; the loads of
-    // item i+1 are issued before the arithmetic of item i, so that they are in flight behind it.
-    const int nsegs = (p.nbc + p.seg_blocks - 1) / p.seg_blocks;
-    const int64_t t0 = ((int64_t)blockIdx.x * 4 + wave) * p.sps;
-    if (t0 >= p.nbr_total) return;
-    const int nstrips = p.nbr_total - t0 < p.sps ? (int)(p.nbr_total - t0) : p.sps;
-    const int nitems = nstrips * nsegs;
-
-    struct Item {
-        unsigned int rm, cm;     // this lane's block: kept rows / kept columns
-        unsigned int wblk;       // byte address of the block in the staged range
-        int nvec;                // 16-byte vectors of the staged range
-        int c0;                  // first column block of the segment
-        int srow;                // original strip index (read when the strip's last segment is fetched)
-    };
-    gu32x4 wreg[kWaveWLoads];
-    auto fetch = [&](int it, Item &I) {
-        const int sn = it / nsegs;
-        const int sg = it - sn * nsegs;
-        const int64_t t = t0 + sn;
-        I.c0 = sg * p.seg_blocks;
-        const int nb = p.nbc - I.c0 < p.seg_blocks ? p.nbc - I.c0 : p.seg_blocks;
-        const int64_t blk0 = t * p.nbc + I.c0;
-        const bool valid = lane < nb;
-        unsigned int wstart, wend, wo = 0;
-        if (p.ukr >= 0) {
-            const unsigned int u = (unsigned int)(p.ukr * p.ukc);
-            wstart = (unsigned int)blk0 * u;
-            wend = wstart + (unsigned int)nb * u;
-            wo = (unsigned int)lane * u;
-        } else {
-            wstart = d.woff[blk0];
-            wend = d.woff[blk0 + nb];
-            if (valid) wo = d.woff[blk0 + lane] - wstart;
-        }
-        const unsigned int bstart = wstart * (unsigned int)sizeof(T), bend = wend * (unsigned int)sizeof(T);
-        const unsigned int a0 = bstart & ~15u;
-        I.nvec = (int)((bend - a0 + 15u) >> 4);                 // <= kWaveWLoads * 64 by construction
-        I.wblk = (bstart - a0) + wo * (unsigned int)sizeof(T);
-#pragma unroll
-        for (int i = 0; i < kWaveWLoads; ++i) {
-            if (i * 64 < I.nvec) {
-                int v = lane + i * 64;
-                v = v < I.nvec ? v : I.nvec - 1;
-                wreg[i] = *reinterpret_cast<const GRIM_GLOBAL gu32x4 *>(W + a0 + (size_t)v * 16);
-            }
-        }
-        I.rm = 0;
-        I.cm = 0;
-        if (valid) {
-            const gu32x2 mm = *reinterpret_cast<const GRIM_GLOBAL gu32x2 *>(d.masks + 2 * (blk0 + lane));
-            I.rm = mm.x;
-            I.cm = mm.y;
-        }
-        I.srow = sg == nsegs - 1 ? d.strip_order[t] : 0;
-    };
-
-    const int r_out = lane & 31, half = lane >> 5;
-    float yacc = 0.f;
-    Item cur, nxt;
-    fetch(0, cur);
-    GEMV_STAMP(2);
-    for (int it = 0; it < nitems; ++it) {
-        const unsigned int rm = cur.rm, cm = cur.cm;
-#pragma unroll
-        for (int i = 0; i < kWaveWLoads; ++i) {
-            if (i * 64 < cur.nvec) {
-                const int v = lane + i * 64;
-                if (v < cur.nvec) *reinterpret_cast<gu32x4 *>(wl + wave_swz((unsigned int)v * 16u)) = wreg[i];
-            }
-        }
-        __builtin_amdgcn_wave_barrier();
-        GEMV_STAMP(3);
-        nxt = cur;
-        if (it + 1 < nitems) fetch(it + 1, nxt);
-        // gather this block's kept columns of x into the lane's private row, zero beyond them
-        const int kr = __builtin_popcount(rm), kc = __builtin_popcount(cm);
-        {
-#pragma unroll
-            for (int g = 0; g < KCMAX / VEC; ++g) {
-                WVec z;
-#pragma unroll
-                for (int v = 0; v < VEC; ++v) z.v[v] = T(0);
-                *reinterpret_cast<WVec *>(xg + g * VEC) = z;
-            }
-            const T *xb = xs + (cur.c0 + lane) * p.BC;
-            unsigned int m = cm;
-            for (int j = 0; m; ++j) {
-                const int col = __builtin_ctz(m);
-                m &= m - 1;
-                xg[j] = xb[col];
-            }
-        }
-        GEMV_STAMP(4);
-        // Kept rows, one after the other, fully unrolled and free of control flow so that the LDS
-        // reads of many rows are in flight together: rows past this block's count re-read row 0
-        // and are not stored; weights past this block's column count may be anything in the
-        // staged range and are replaced by zeros before they are used.
-        const unsigned int wblk = cur.wblk;
-        WVec xv[KCMAX / VEC];
-#pragma unroll
-        for (int g = 0; g < KCMAX / VEC; ++g) xv[g] = *reinterpret_cast<const WVec *>(xg + g * VEC);
-        float acc[KRMAX];
-#pragma unroll
-        for (int i = 0; i < KRMAX; ++i) {
-            const unsigned int wr = wblk + (unsigned int)((i < kr ? i : 0) * kc) * (unsigned int)sizeof(T);
-            WVec wv[KCMAX / VEC];
-#pragma unroll
-            for (int g = 0; g < KCMAX / VEC; ++g)
-                wv[g] = *reinterpret_cast<const WVec *>(wl + wave_swz(wr + (unsigned int)(g * VEC) * (unsigned int)sizeof(T)));
-            float a = 0.f;
-#pragma unroll
-            for (int g = 0; g < KCMAX / VEC; ++g) {
-                const bool on = g * VEC < kc;                     // kc is a multiple of VEC
-#pragma unroll
-                for (int v = 0; v < VEC; ++v) {
-                    const float w = on ? g2f<DT>(wv[g].v[v]) : 0.f;
-                    a = __builtin_fmaf(w, g2f<DT>(xv[g].v[v]), a);
-                }
-            }
-            acc[i] = a;
-        }
-        __builtin_amdgcn_wave_barrier();                          // every lane is done with the weights
-        GEMV_STAMP(5);
-        // partial table [strip row][block], zero where a block does not keep the row
-        for (int z = lane; z < (p.BR * kPartStride + 3) / 4; z += 64)
-            reinterpret_cast<gu32x4 *>(part)[z] = gu32x4{0u, 0u, 0u, 0u};
-        __builtin_amdgcn_wave_barrier();
-        {
-            unsigned int m = rm;
-#pragma unroll
-            for (int i = 0; i < KRMAX; ++i) {
-                if (i < kr) {
-                    const int r = __builtin_ctz(m);
-                    m &= m - 1;
-                    part[r * kPartStride + lane] = acc[i];
-                }
-            }
-        }
-        __builtin_amdgcn_wave_barrier();
-        GEMV_STAMP(6);
-        // lanes (row, half): 32 blocks each, ascending; then first half + second half
-        float hs = 0.f;
-        if (r_out < p.BR) {
-            const float2 *src = reinterpret_cast<const float2 *>(part + r_out * kPartStride + half * 32);
-#pragma unroll
-            for (int q = 0; q < 16; ++q) {
-                const float2 v = src[q];
-                hs += v.x;
-                hs += v.y;
-            }
-        }
-        const float other = __shfl_xor(hs, 32);
-        yacc += half == 0 ? hs + other : other + hs;
-        __builtin_amdgcn_wave_barrier();                          // table consumed before the next item refills LDS
-        GEMV_STAMP(7);
-        if (cur.c0 + p.seg_blocks >= p.nbc) {                     // last segment of a strip
-            if (half == 0 && r_out < p.BR) y[((int64_t)cur.srow * p.BR + r_out) * p.ldy] = yacc;
-            yacc = 0.f;
-        }
-        cur = nxt;
-    }
-    GEMV_STAMP(8);
-}
-
-template <int DT, int VEC, int KR, int KC>
-static grim_status launch_wave_inst(const GemvParams &p, dim3 grid, size_t lds, hipStream_t stream) {
-    auto kern = bcr_spmv_wave<DT, VEC, KR, KC>;
-    static bool attr_done = false;
-    if (lds > 64 * 1024 && !attr_done) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess) {
-            (void)hipGetLastError();
-            return GRIM_ERR_DEVICE;
-        }
-        attr_done = true;
-    }
-    hipLaunchKernelGGL(kern, grid, dim3(256), lds, stream, p);
-    return hipGetLastError() == hipSuccess ? GRIM_OK : GRIM_ERR_DEVICE;
-}
-
-template <int DT, int VEC>
-static grim_status launch_wave_vec(const GemvParams &p, int krmax, int kcmax, dim3 grid, size_t lds, hipStream_t stream) {
-    if (krmax <= 8) {
-        if (kcmax <= 16) return launch_wave_inst<DT, VEC, 8, 16>(p, grid, lds, stream);
-        return launch_wave_inst<DT, VEC, 8, 32>(p, grid, lds, stream);
-    }
-    if (kcmax <= 16) return launch_wave_inst<DT, VEC, 32, 16>(p, grid, lds, stream);
-    return launch_wave_inst<DT, VEC, 32, 32>(p, grid, lds, stream);
-}
-
-template <int DT>
-static grim_status launch_wave(const GemvParams &p, int vec, int krmax, int kcmax, dim3 grid, size_t lds, hipStream_t stream) {
-    if (vec >= 4) return launch_wave_vec<DT, 4>(p, krmax, kcmax, grid, lds, stream);
-    return launch_wave_vec<DT, 1>(p, krmax, kcmax, grid, lds, stream);
-}
+constexpr int kPartStride = 66;                    // floats per strip row of the partial table (wave-per-strip kernels)
 
 // ------------------------------------------------------------------------------------------
 // One right-hand side, every block keeping exactly KR rows and KC columns (a layer pruned at one
@@ -581,7 +307,8 @@ static grim_status launch_wave(const GemvParams &p, int vec, int krmax, int kcma
 //     banks evenly;
 //   - a lane reads its whole block and its KC activations into registers; two-byte types
 //     multiply pairs with the packed dot-product instruction (fp32 sum, subnormals kept);
-//   - row sums go through the same [strip row][block] table as in the general kernel.
+//   - each lane scatters its rows' sums to a [strip row][block] table in LDS (zero where a block
+//     does not keep the row); lanes (strip row, group) then add each row's 64 entries in a fixed order.
 // ------------------------------------------------------------------------------------------
 // Lanes read their blocks with 16-byte loads at a common offset from bases NV vectors apart;
 // 16 such vectors span the LDS banks.  When NV shares a factor g with 16 the bases of 16
@@ -1239,7 +966,7 @@ grim_status launch_spmv(const GemvDesc *table, const GemvDesc &single, int32_t c
     p.dbg = reinterpret_cast<long long *>(getenv("GRIM_DBG_PTR") ? strtoull(getenv("GRIM_DBG_PTR"), nullptr, 0) : 0ull);
 #endif
     if (batch == 1 && (int64_t)K * esz <= 32 * 1024) {
-        // one wave per strip, one lane per block
+        // uniformly pruned matrix: one wave per strip, one lane per block
         if (ukr > 0 && ukc > 0 && (ukr * ukc * esz) % 16 == 0 && ukr * ukc * esz <= 384) {
             const int nv = ukr * ukc * esz / 16;
             GemvParams q = p;
@@ -1260,30 +987,6 @@ grim_status launch_spmv(const GemvDesc *table, const GemvDesc &single, int32_t c
                 }
             }
             if (st != GRIM_ERR_UNSUPPORTED) return st;
-        }
-        int64_t wseg = (kWaveWLoads * 1024 - 32) / blk_bytes;
-        if (wseg > 64) wseg = 64;
-        if (wseg >= 1) {
-            GemvParams q = p;
-            q.seg_blocks = (int32_t)wseg;
-            int64_t wb = (wseg * blk_bytes + 32 + 15) & ~int64_t(15);
-            const int64_t table = ((int64_t)BR * kPartStride * 4 + 15) & ~int64_t(15);
-            if (wb < table) wb = table;
-            q.wbytes = (int32_t)wb;
-            const size_t wlds = (((size_t)K * esz + 15) & ~size_t(15)) + 4 * ((size_t)wb + 64 * (size_t)wave_xg_stride(kcmax <= 16 ? 16 : 32, esz) * esz) + 256;
-            if (wlds <= 160 * 1024) {
-                // A lone product wants every strip on a wave of its own (latency); many products
-                // at once fill the GPU anyway, and a wave then walks several strips so that the
-                // next strip's weights stream in behind the current strip's arithmetic.
-                const int sps = wave_strips_per_wave(count, nbr, 4);
-                q.sps = sps;
-                dim3 wgrid((unsigned)((nbr + 4 * sps - 1) / (4 * sps)), (unsigned)count);
-                switch (dtype) {
-                    case GRIM_F32: return launch_wave<GRIM_F32>(q, vec, krmax, kcmax, wgrid, wlds, stream);
-                    case GRIM_F16: return launch_wave<GRIM_F16>(q, vec, krmax, kcmax, wgrid, wlds, stream);
-                    case GRIM_BF16: return launch_wave<GRIM_BF16>(q, vec, krmax, kcmax, wgrid, wlds, stream);
-                }
-            }
         }
     }
     if (batch > 1 && dtype != GRIM_F32 && ukr > 0 && ukc > 0 && (ukr * ukc * esz) % 16 == 0 && ukr * ukc * esz <= 384 &&
