@@ -180,6 +180,36 @@ grim_status grim_bcr_spmv_batched(const grim_bcr_group *G, const void *x_dev, in
                                   int64_t ldy, void *hip_stream);
 void grim_bcr_group_free(grim_bcr_group *G);
 
+/*
+ * BCRC export (Section 4.3, "Compact Model Storage"): the paper's six-array, row-level form of the
+ * same pruned matrix.  Rows of the whole matrix are reordered so that rows with the same set of
+ * kept (global) columns are adjacent -- groups in order of the first original row that shows the
+ * pattern, rows inside a group in ascending original order -- and the column indices of a group are
+ * stored once:
+ *   reorder[M]            original row id of reordered row p            (the paper's `reorder`)
+ *   row_offset[M+1]       start of reordered row p in weights           (`row offset`)
+ *   occurrence[G+1]       first reordered row of each group             (`occurrence`)
+ *   column_stride[G+1]    start of each group's list in compact_column  (`column stride`)
+ *   compact_column[...]   global column indices of each group, ascending (`compact column`)
+ *   weights[nnz]          reordered rows, each its kept weights in column order (`weights`)
+ * Rows that keep nothing form one group with an empty column list.  Host-only (works on matrices
+ * packed with host_only); the arrays are owned by the grim_bcrc object.
+ */
+typedef struct grim_bcrc grim_bcrc;
+typedef struct grim_bcrc_view {
+    int64_t M, K, ngroups, nnz, ncols;   /* ncols = length of compact_column */
+    int32_t dtype;
+    const int32_t *reorder;
+    const int64_t *row_offset;
+    const int32_t *occurrence;
+    const int64_t *column_stride;
+    const int32_t *compact_column;
+    const void *weights;
+} grim_bcrc_view;
+grim_status grim_bcr_export_bcrc(const grim_bcr_matrix *A, grim_bcrc **out);   /* NULL, ALLOC */
+grim_status grim_bcrc_arrays(const grim_bcrc *B, grim_bcrc_view *v);
+void grim_bcrc_free(grim_bcrc *B);
+
 /* grim_bcr_free -- release a matrix and its device memory.  NULL is a no-op. */
 void grim_bcr_free(grim_bcr_matrix *A);
 

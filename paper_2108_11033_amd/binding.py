@@ -47,9 +47,17 @@ class View(ctypes.Structure):
                 ("dev_bytes_gemv", ctypes.c_int64)]
 
 
+class BcrcView(ctypes.Structure):
+    _fields_ = [("M", ctypes.c_int64), ("K", ctypes.c_int64), ("ngroups", ctypes.c_int64), ("nnz", ctypes.c_int64),
+                ("ncols", ctypes.c_int64), ("dtype", ctypes.c_int32),
+                ("reorder", ctypes.c_void_p), ("row_offset", ctypes.c_void_p), ("occurrence", ctypes.c_void_p),
+                ("column_stride", ctypes.c_void_p), ("compact_column", ctypes.c_void_p), ("weights", ctypes.c_void_p)]
+
+
 EXPORTS = ["grim_bcr_pack", "grim_bcr_unpack", "grim_bcr_arrays", "grim_bcr_spmm", "grim_bcr_spmm_tuned",
            "grim_bcr_spmv", "grim_bcr_group_create", "grim_bcr_spmv_batched", "grim_bcr_group_free",
-           "grim_bcr_free", "grim_status_str", "grim_bcr_spmm_kernel_name"]
+           "grim_bcr_free", "grim_status_str", "grim_bcr_spmm_kernel_name",
+           "grim_bcr_export_bcrc", "grim_bcrc_arrays", "grim_bcrc_free"]
 
 
 def lib_path() -> str:
@@ -85,12 +93,16 @@ def load_library():
     lib.grim_bcr_group_free.argtypes = [p]
     lib.grim_bcr_free.argtypes = [p]
     lib.grim_status_str.argtypes = [i32]
+    lib.grim_bcr_export_bcrc.argtypes = [p, ctypes.POINTER(p)]
+    lib.grim_bcrc_arrays.argtypes = [p, ctypes.POINTER(BcrcView)]
+    lib.grim_bcrc_free.argtypes = [p]
     lib.grim_bcr_spmm_kernel_name.argtypes = [p, p, i64, i64, i32, i32, i32]
     for name in EXPORTS:
         getattr(lib, name).restype = i32
     lib.grim_status_str.restype = ctypes.c_char_p
     lib.grim_bcr_spmm_kernel_name.restype = ctypes.c_char_p
     lib.grim_bcr_free.restype = None
+    lib.grim_bcrc_free.restype = None
     lib.grim_bcr_group_free.restype = None
     _lib = lib
     return lib
@@ -240,6 +252,30 @@ def spmm(A: BcrMatrix, X, N: int, ldx: int, Y, ldy: int, stream=None, *,
         _check(st, "grim_bcr_spmm_tuned")
     else:
         _check(lib.grim_bcr_spmm(A.handle, _addr(X), N, ldx, _addr(Y), ldy, _stream(stream)), "grim_bcr_spmm")
+
+
+def export_bcrc(A: BcrMatrix) -> dict:
+    """grim_bcr_export_bcrc: copies of the paper's six BCRC arrays (plus sizes) as NumPy arrays."""
+    lib = A._lib
+    h = ctypes.c_void_p()
+    _check(lib.grim_bcr_export_bcrc(A.handle, ctypes.byref(h)), "grim_bcr_export_bcrc")
+    try:
+        v = BcrcView()
+        _check(lib.grim_bcrc_arrays(h, ctypes.byref(v)), "grim_bcrc_arrays")
+
+        def arr(ptr, n, dt):
+            if n == 0:
+                return np.zeros(0, dtype=dt)
+            return np.ctypeslib.as_array(ctypes.cast(ptr, ctypes.POINTER(ctypes.c_uint8)), shape=(n * np.dtype(dt).itemsize,)).view(dt).copy()
+        wdt = np.float32 if v.dtype == F32 else np.uint16
+        return {"M": v.M, "K": v.K, "ngroups": v.ngroups, "nnz": v.nnz,
+                "reorder": arr(v.reorder, v.M, np.int32), "row_offset": arr(v.row_offset, v.M + 1, np.int64),
+                "occurrence": arr(v.occurrence, v.ngroups + 1, np.int32),
+                "column_stride": arr(v.column_stride, v.ngroups + 1, np.int64),
+                "compact_column": arr(v.compact_column, v.ncols, np.int32),
+                "weights": arr(v.weights, v.nnz, wdt)}
+    finally:
+        lib.grim_bcrc_free(h)
 
 
 def spmm_kernel_name(A: BcrMatrix, X, N: int, ldx: int, *, tile_n: int = 0, strips_per_wg: int = 0, kernel: int = 0) -> str:

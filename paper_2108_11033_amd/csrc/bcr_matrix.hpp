@@ -121,6 +121,18 @@ struct grim_bcr_matrix {
     grim::GemvLayout gemv;
 };
 
+// The paper's six BCRC arrays (Section 4.3), host side.
+struct grim_bcrc {
+    int64_t M = 0, K = 0;
+    int32_t dtype = 0;
+    std::vector<int32_t> reorder;
+    std::vector<int64_t> row_offset;
+    std::vector<int32_t> occurrence;
+    std::vector<int64_t> column_stride;
+    std::vector<int32_t> compact_column;
+    std::vector<unsigned char> weights;
+};
+
 // Descriptor of one matrix as the SpMV kernel reads it (device table entry of a group).
 struct GemvDesc {
     const void *weights;

@@ -3,6 +3,7 @@
 // extern "C" entry points.
 #include <algorithm>
 #include <cstring>
+#include <map>
 #include <new>
 #include <numeric>
 
@@ -459,6 +460,89 @@ grim_status grim_bcr_unpack(const grim_bcr_matrix *A, void *W_host_out, int64_t 
     }
     return GRIM_OK;
 }
+
+grim_status grim_bcr_export_bcrc(const grim_bcr_matrix *A, grim_bcrc **out) {
+    if (out) *out = nullptr;
+    if (!A || !out) return GRIM_ERR_NULL;
+    if (A->M > 0x7fffffff || A->K > 0x7fffffff) return GRIM_ERR_SHAPE;
+    grim_bcrc *B = nullptr;
+    try {
+        B = new grim_bcrc();
+        B->M = A->M; B->K = A->K; B->dtype = A->dtype;
+        const int esz = dtype_size(A->dtype);
+        // stored position of every strip
+        std::vector<int64_t> pos((size_t)A->nbr);
+        for (int64_t p = 0; p < A->nbr; ++p) pos[(size_t)A->strip_order[p]] = p;
+        // per original row: its kept global columns, and where each block's run of weights starts
+        struct Run { int64_t w0; int32_t kc; };
+        std::vector<std::vector<int32_t>> pattern((size_t)A->M);
+        std::vector<std::vector<Run>> runs((size_t)A->M);
+        for (int64_t s = 0; s < A->nbr; ++s) {
+            for (int64_t c = 0; c < A->nbc; ++c) {
+                const int64_t t = pos[(size_t)s] * A->nbc + c;
+                const int32_t kr = A->row_ptr[t + 1] - A->row_ptr[t], kc = A->col_ptr[t + 1] - A->col_ptr[t];
+                if (!kr || !kc) continue;
+                for (int32_t i = 0; i < kr; ++i) {
+                    const int64_t r = s * A->BR + A->row_idx[A->row_ptr[t] + i];
+                    for (int32_t j = 0; j < kc; ++j)
+                        pattern[(size_t)r].push_back((int32_t)(c * A->BC + A->col_idx[A->col_ptr[t] + j]));
+                    runs[(size_t)r].push_back({A->blk_ptr[t] + (int64_t)i * kc, kc});
+                }
+            }
+        }
+        // groups in order of first appearance
+        std::map<std::vector<int32_t>, int32_t> ids;
+        std::vector<std::vector<int32_t>> members;
+        for (int64_t r = 0; r < A->M; ++r) {
+            auto it = ids.find(pattern[(size_t)r]);
+            if (it == ids.end()) {
+                it = ids.emplace(pattern[(size_t)r], (int32_t)members.size()).first;
+                members.emplace_back();
+            }
+            members[(size_t)it->second].push_back((int32_t)r);
+        }
+        B->occurrence.push_back(0);
+        B->column_stride.push_back(0);
+        B->row_offset.push_back(0);
+        B->weights.reserve(A->weights.size());
+        for (const auto &grp : members) {
+            const std::vector<int32_t> &cols = pattern[(size_t)grp[0]];
+            B->compact_column.insert(B->compact_column.end(), cols.begin(), cols.end());
+            B->column_stride.push_back((int64_t)B->compact_column.size());
+            for (int32_t r : grp) {
+                B->reorder.push_back(r);
+                for (const Run &run : runs[(size_t)r]) {
+                    const unsigned char *src = A->weights.data() + (size_t)run.w0 * esz;
+                    B->weights.insert(B->weights.end(), src, src + (size_t)run.kc * esz);
+                }
+                B->row_offset.push_back((int64_t)(B->weights.size() / esz));
+            }
+            B->occurrence.push_back((int32_t)B->reorder.size());
+        }
+    } catch (const std::bad_alloc &) {
+        delete B;
+        return GRIM_ERR_ALLOC;
+    }
+    *out = B;
+    return GRIM_OK;
+}
+
+grim_status grim_bcrc_arrays(const grim_bcrc *B, grim_bcrc_view *v) {
+    if (!B || !v) return GRIM_ERR_NULL;
+    v->M = B->M; v->K = B->K; v->dtype = B->dtype;
+    v->ngroups = (int64_t)B->occurrence.size() - 1;
+    v->nnz = B->row_offset.back();
+    v->ncols = (int64_t)B->compact_column.size();
+    v->reorder = B->reorder.data();
+    v->row_offset = B->row_offset.data();
+    v->occurrence = B->occurrence.data();
+    v->column_stride = B->column_stride.data();
+    v->compact_column = B->compact_column.data();
+    v->weights = B->weights.data();
+    return GRIM_OK;
+}
+
+void grim_bcrc_free(grim_bcrc *B) { delete B; }
 
 grim_status grim_bcr_arrays(const grim_bcr_matrix *A, grim_bcr_view *v) {
     if (!A || !v) return GRIM_ERR_NULL;
