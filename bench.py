@@ -98,6 +98,9 @@ def main() -> int:
     ap.add_argument("--kernel", type=int, default=0, help="0 choose, 2 staged matrix-core kernel, 3 row-gathering one")
     ap.add_argument("--extra", action="store_true", help="also time the SpMV and large non-uniform workloads")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--sweep", action="store_true",
+                    help="also run the block-size search of the paper on a 1024x1024 layer at 10x pruning, and the "
+                         "strip-reorder ablation on the non-uniform workload")
     ap.add_argument("--calibrate", action="store_true",
                     help="also run a plain 256 MiB device copy (reference for scaling rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -248,6 +251,32 @@ def main() -> int:
         extra["c4"] = {"layers": layers, "total_us": tot_t * 1e6, "useful_tflops": tot_f / tot_t / 1e12,
                        "gbs": tot_b / tot_t / 1e9, "frac_hbm": tot_b / tot_t / 1e9 / HBM_PEAK_GBS}
         out["extra"] = extra
+
+    if args.sweep:
+        from paper_2108_11033_amd import tune
+        sweep = {}
+        sizes = [(4, 4), (8, 8), (16, 16), (16, 32), (32, 32), (16, 64), (32, 64), (64, 64), (16, 128), (32, 128)]
+        # matrix-vector layer (the paper's RNN case), 256 independent products per launch; and the same layer as a GEMM
+        for name, n, products in (("spmv_256_products", 1, 256), ("spmm_N3136", 3136, 1)):
+            cand = [s for s in sizes if n > 8 or (s[0] <= 32 and s[1] <= 32)]
+            best, trace = tune.find_block_size(1024, 1024, n, 10.0, cand, dtype="f16", threshold=1.1,
+                                               products=products, steps=30, warmup=3)
+            # the search stops early; time the remaining sizes too so that the whole curve is on record
+            seen = {s for s, _ in trace}
+            rest = []
+            for sz in cand:
+                if sz not in seen:
+                    W_, X_, m_ = tune.synthesize(1024, 1024, n, sz[0], sz[1], 10.0, "f16")
+                    rest.append((sz, tune.time_layer(W_, X_, m_, "f16", products=products, steps=30, warmup=3)))
+            sweep[name] = {"chosen": list(best) if best else None,
+                           "searched_us": [[list(sz), t * 1e6] for sz, t in trace],
+                           "not_searched_us": [[list(sz), t * 1e6] for sz, t in rest]}
+        # strip reorder on / off on c5 (work per strip varies there)
+        w5 = gen.c5_nonuniform()
+        t_on = tune.time_layer(w5.W, w5.X, w5.mask, w5.dtype, steps=30, warmup=3)
+        t_off = tune.time_layer(w5.W, w5.X, w5.mask, w5.dtype, steps=30, warmup=3, no_reorder=True)
+        sweep["c5_reorder"] = {"reordered_us": t_on * 1e6, "natural_order_us": t_off * 1e6, "ratio": t_off / t_on}
+        out["sweep"] = sweep
 
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(wl)
