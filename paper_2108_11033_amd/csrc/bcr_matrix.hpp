@@ -45,11 +45,15 @@ struct MmaLayout {
     int64_t bytes = 0;
 };
 
-// Layout for the row-gathering matrix-core SpMM kernel (fp16 / bf16, BR = 16).
-// The kept columns of a stored strip's blocks, in column-block order, are cut into groups of 8 k
-// slots (a block's columns padded to a multiple of 8) and groups into steps of 32 k slots -- one
-// v_mfma_f32_16x16x32 per 16 columns of X.  Nothing depends on how K is cut: a wave takes any
-// contiguous range of a strip's steps.
+// Layout for the row-gathering matrix-core SpMM kernel (fp16 / bf16; block heights that divide 16
+// or are multiples of 16).  The rows of the matrix in stored order (stored strip p, local row r ->
+// p * BR + r) are cut into runs of 16, the MFMA tile height: a run is one strip for BR = 16, a
+// quarter of a strip for BR = 64, four strips for BR = 4.  The kept columns of the blocks that
+// reach into a run, in column-block order, are cut into groups of 8 k slots (a block's columns
+// padded to a multiple of 8; a group belongs to one block and carries that block's kept rows
+// inside the run as a 16-bit mask) and groups into steps of 32 k slots -- one v_mfma_f32_16x16x32
+// per 16 columns of X.  Nothing depends on how K is cut: a wave takes any contiguous range of a
+// run's steps.
 //   rows   : per step 32 x u32, the row of X behind k slot g * 8 + j at position j * 4 + g
 //            (0xffffffff = padding: the slot multiplies zeros), so that the lane that fetches slots
 //            j, j + 8, j + 16, j + 24 reads its four row numbers with one 16-byte load;
@@ -60,11 +64,14 @@ struct GatherLayout {
     bool present = false;
     int64_t nsteps = 0;
     int64_t xrows = 0;                    // k slots that name a row of X (not padding), over all strips
-    std::vector<int32_t> sptr;            // [nbr + 1] first step of each stored strip
+    int64_t nstrips = 0;                  // 16-row runs: ceil(M / 16)
+    std::vector<int32_t> sptr;            // [nstrips + 1] first step of each run
+    std::vector<int32_t> out_row;         // [nstrips * 16] original row of every stored row (-1 past M)
     std::vector<uint32_t> rows;           // [nsteps * 32]
     std::vector<uint32_t> desc;           // [nsteps * 8]
     std::vector<unsigned char> payload;
     int32_t *d_sptr = nullptr;
+    int32_t *d_out_row = nullptr;
     uint32_t *d_rows = nullptr;
     uint32_t *d_desc = nullptr;
     unsigned char *d_payload = nullptr;

@@ -157,21 +157,45 @@ void build_mma_layout(grim_bcr_matrix *A, int32_t chunk_rows_opt) {
 void build_gather_layout(grim_bcr_matrix *A) {
     GatherLayout &L = A->gather;
     L = GatherLayout();
-    if (A->dtype == GRIM_F32 || A->BR != 16 || A->K > 0x7fffffff) return;
+    // Block heights that divide 16 or are multiples of 16 map onto 16-row MFMA tiles: stored rows
+    // (stored strip p, local row r) are numbered p * BR + r and cut into runs of 16.
+    if (A->dtype == GRIM_F32 || A->K > 0x7fffffff || A->M > 0x7fffffff) return;
+    if (!(16 % A->BR == 0 || A->BR % 16 == 0)) return;
     const uint16_t *w = reinterpret_cast<const uint16_t *>(A->weights.data());
-    L.sptr.assign((size_t)A->nbr + 1, 0);
-    struct Group { int64_t t; int32_t j0; };
+    const int64_t nss = (A->M + 15) / 16;                 // 16-row strips of the stored order
+    L.nstrips = nss;
+    L.sptr.assign((size_t)nss + 1, 0);
+    L.out_row.assign((size_t)nss * 16, -1);
+    for (int64_t p = 0; p < A->nbr; ++p)
+        for (int32_t r = 0; r < A->BR; ++r)
+            L.out_row[(size_t)(p * A->BR + r)] = (int32_t)((int64_t)A->strip_order[p] * A->BR + r);
+    struct Group { int64_t t; int32_t j0; uint32_t rowmask; int32_t rlo, rhi; };   // rows [rlo, rhi) of the block's kept list
     std::vector<Group> groups;
-    for (int64_t st = 0; st < A->nbr; ++st) {
-        L.sptr[(size_t)st] = (int32_t)L.nsteps;
+    for (int64_t u = 0; u < nss; ++u) {
+        L.sptr[(size_t)u] = (int32_t)L.nsteps;
         groups.clear();
+        const int64_t row0 = u * 16, row1 = std::min<int64_t>(A->M, row0 + 16);
+        const int64_t p0 = row0 / A->BR, p1 = (row1 - 1) / A->BR;           // stored strips that overlap this run
         for (int64_t c = 0; c < A->nbc; ++c) {
-            const int64_t t = st * A->nbc + c;
-            const int32_t kr = A->row_ptr[t + 1] - A->row_ptr[t], kc = A->col_ptr[t + 1] - A->col_ptr[t];
-            if (kr == 0 || kc == 0) continue;
-            for (int32_t j0 = 0; j0 < kc; j0 += 8) groups.push_back({t, j0});
+            for (int64_t p = p0; p <= p1; ++p) {
+                const int64_t t = p * A->nbc + c;
+                const int32_t kr = A->row_ptr[t + 1] - A->row_ptr[t], kc = A->col_ptr[t + 1] - A->col_ptr[t];
+                if (kr == 0 || kc == 0) continue;
+                // the block's kept rows that fall into this run, as bits of the run's 16 rows
+                uint32_t rowmask = 0;
+                int32_t rlo = -1, rhi = -1;
+                for (int32_t i = 0; i < kr; ++i) {
+                    const int64_t sr = p * A->BR + A->row_idx[A->row_ptr[t] + i];
+                    if (sr < row0 || sr >= row1) continue;
+                    rowmask |= 1u << (sr - row0);
+                    if (rlo < 0) rlo = i;
+                    rhi = i + 1;
+                }
+                if (!rowmask) continue;
+                for (int32_t j0 = 0; j0 < kc; j0 += 8) groups.push_back({t, j0, rowmask, rlo, rhi});
+            }
         }
-        while (groups.size() % 4) groups.push_back({-1, 0});
+        while (groups.size() % 4) groups.push_back({-1, 0, 0u, 0, 0});
         const size_t nst = groups.size() / 4;
         if ((uint64_t)L.nsteps + nst > 0x7fffffffu) { L = GatherLayout(); return; }
         const size_t step0 = (size_t)L.nsteps;
@@ -181,27 +205,26 @@ void build_gather_layout(grim_bcr_matrix *A) {
             const Group &gp = groups[q];
             const size_t step = step0 + q / 4, g = q % 4;
             if (gp.t < 0) continue;                       // padding group: rows stay 0xffffffff, mask 0
-            const int32_t kr = A->row_ptr[gp.t + 1] - A->row_ptr[gp.t], kc = A->col_ptr[gp.t + 1] - A->col_ptr[gp.t];
+            const int32_t kc = A->col_ptr[gp.t + 1] - A->col_ptr[gp.t];
             const int64_t c = gp.t % A->nbc;
-            uint32_t rowmask = 0;
-            for (int32_t qq = A->row_ptr[gp.t]; qq < A->row_ptr[gp.t + 1]; ++qq) rowmask |= 1u << A->row_idx[qq];
             for (int32_t j = 0; j < 8 && gp.j0 + j < kc; ++j) {
                 L.rows[step * 32 + (size_t)j * 4 + g] = (uint32_t)(c * A->BC + A->col_idx[A->col_ptr[gp.t] + gp.j0 + j]);
                 ++L.xrows;
             }
-            const size_t p0 = L.payload.size();
-            if (p0 / 16 + (size_t)kr > 0xffffffffu) { L = GatherLayout(); return; }
-            L.payload.resize(p0 + (size_t)kr * 16, 0);
-            uint16_t *pw = reinterpret_cast<uint16_t *>(L.payload.data() + p0);
-            for (int32_t i = 0; i < kr; ++i)
+            const int32_t nrows = gp.rhi - gp.rlo;        // kept rows are ascending, so the run's share is contiguous
+            const size_t pl0 = L.payload.size();
+            if (pl0 / 16 + (size_t)nrows > 0xffffffffu) { L = GatherLayout(); return; }
+            L.payload.resize(pl0 + (size_t)nrows * 16, 0);
+            uint16_t *pw = reinterpret_cast<uint16_t *>(L.payload.data() + pl0);
+            for (int32_t i = 0; i < nrows; ++i)
                 for (int32_t e = 0; e < 8 && gp.j0 + e < kc; ++e)
-                    pw[i * 8 + e] = w[A->blk_ptr[gp.t] + (int64_t)i * kc + gp.j0 + e];
-            L.desc[step * 8 + g * 2] = rowmask;
-            L.desc[step * 8 + g * 2 + 1] = (uint32_t)(p0 / 16);
+                    pw[i * 8 + e] = w[A->blk_ptr[gp.t] + (int64_t)(gp.rlo + i) * kc + gp.j0 + e];
+            L.desc[step * 8 + g * 2] = gp.rowmask;
+            L.desc[step * 8 + g * 2 + 1] = (uint32_t)(pl0 / 16);
         }
         L.nsteps += (int64_t)nst;
     }
-    L.sptr[(size_t)A->nbr] = (int32_t)L.nsteps;
+    L.sptr[(size_t)nss] = (int32_t)L.nsteps;
     L.present = true;
 }
 
@@ -260,9 +283,10 @@ grim_status upload(grim_bcr_matrix *A) {
         o_bp2 = s.add(bytes(A->mma.bptr));
         o_af = s.add(bytes(A->mma.recs) + 2048);   // slack: records are fetched in 1 KB slots
     }
-    size_t o_gs = 0, o_gr = 0, o_gd = 0, o_gp = 0;
+    size_t o_gs = 0, o_gq = 0, o_gr = 0, o_gd = 0, o_gp = 0;
     if (A->gather.present) {
         o_gs = s.add(bytes(A->gather.sptr));
+        o_gq = s.add(bytes(A->gather.out_row));
         o_gr = s.add(bytes(A->gather.rows) + 16);
         o_gd = s.add(bytes(A->gather.desc) + 16);
         o_gp = s.add(bytes(A->gather.payload) + 16);
@@ -286,7 +310,7 @@ grim_status upload(grim_bcr_matrix *A) {
         ok = put(o_kp, A->mma.cptr.data(), bytes(A->mma.cptr)) && put(o_bp2, A->mma.bptr.data(), bytes(A->mma.bptr)) &&
              put(o_af, A->mma.recs.data(), bytes(A->mma.recs));
     if (ok && A->gather.present)
-        ok = put(o_gs, A->gather.sptr.data(), bytes(A->gather.sptr)) && put(o_gr, A->gather.rows.data(), bytes(A->gather.rows)) &&
+        ok = put(o_gs, A->gather.sptr.data(), bytes(A->gather.sptr)) && put(o_gq, A->gather.out_row.data(), bytes(A->gather.out_row)) && put(o_gr, A->gather.rows.data(), bytes(A->gather.rows)) &&
              put(o_gd, A->gather.desc.data(), bytes(A->gather.desc)) && put(o_gp, A->gather.payload.data(), bytes(A->gather.payload));
     if (ok && A->gemv.present)
         ok = put(o_gm, A->gemv.masks.data(), bytes(A->gemv.masks)) && put(o_go, A->gemv.woff.data(), bytes(A->gemv.woff));
@@ -308,6 +332,7 @@ grim_status upload(grim_bcr_matrix *A) {
     }
     if (A->gather.present) {
         A->gather.d_sptr = reinterpret_cast<int32_t *>(base + o_gs);
+        A->gather.d_out_row = reinterpret_cast<int32_t *>(base + o_gq);
         A->gather.d_rows = reinterpret_cast<uint32_t *>(base + o_gr);
         A->gather.d_desc = reinterpret_cast<uint32_t *>(base + o_gd);
         A->gather.d_payload = reinterpret_cast<unsigned char *>(base + o_gp);

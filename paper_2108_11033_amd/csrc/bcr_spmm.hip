@@ -543,9 +543,10 @@ __global__ void __launch_bounds__((NW + NP) * 64) bcr_spmm_mma(MmaParams p) {
 }
 
 // ------------------------------------------------------------------------------------------
-// row-gathering matrix-core kernel (fp16 / bf16, BR = 16, X rows 16-byte aligned)
+// row-gathering matrix-core kernel (fp16 / bf16; block heights that divide 16 or are multiples of
+// 16: the rows of the matrix in stored order are cut into runs of 16, "strips" below)
 //
-// Workgroup = (tile of 64 columns of X, one stored strip); its 4 waves split the strip's steps
+// Workgroup = (tile of 64 columns of X, one 16-row strip); its 4 waves split the strip's steps
 // (i.e. K) between them and add their partial tiles in a fixed order at the end -- the only
 // barrier.  A wave works on its own: it reads the row numbers and block descriptors of a batch
 // of steps, then fetches exactly the rows of X those steps multiply (8 lanes per 128-byte row
@@ -559,14 +560,14 @@ __global__ void __launch_bounds__((NW + NP) * 64) bcr_spmm_mma(MmaParams p) {
 // ------------------------------------------------------------------------------------------
 struct GatherParams {
     const int32_t *sptr;
+    const int32_t *out_row;   // original row of stored row t * 16 + m, -1 past the matrix
     const uint32_t *rows;
     const uint32_t *desc;
     const unsigned char *payload;
-    const int32_t *strip_order;
     const unsigned short *X;
     float *Y;
     int64_t N, ldx, ldy;
-    int32_t nbr, ntiles;
+    int32_t nbr, ntiles;      // nbr: 16-row runs of the stored row order
     int32_t yvec;
 };
 
@@ -683,14 +684,16 @@ __global__ void __launch_bounds__(256, 4) bcr_spmm_gather(GatherParams p) {
         sum[0] += v[0]; sum[1] += v[1]; sum[2] += v[2]; sum[3] += v[3];
     }
     // D[n][m]: lane holds m = lane % 16, n = 4 * (lane / 16) + 0..3
-    const int64_t row = (int64_t)p.strip_order[t] * 16 + (lane & 15);
+    const int64_t row = p.out_row[(int64_t)t * 16 + (lane & 15)];
     const int64_t n = n0 + q * 16 + 4 * (lane >> 4);
-    float *dst = p.Y + row * p.ldy + n;
-    if (p.yvec == 4) {
-        *reinterpret_cast<f32x4 *>(dst) = sum;
-    } else {
+    if (row >= 0) {
+        float *dst = p.Y + row * p.ldy + n;
+        if (p.yvec == 4) {
+            *reinterpret_cast<f32x4 *>(dst) = sum;
+        } else {
 #pragma unroll
-        for (int e = 0; e < 4; ++e) dst[e] = sum[e];
+            for (int e = 0; e < 4; ++e) dst[e] = sum[e];
+        }
     }
 }
 
@@ -703,7 +706,7 @@ bool gather_applies(const grim_bcr_matrix *A, const void *X, int64_t N, int64_t 
 // records, pays a start-up, and 256 compute units share the workgroups.
 double gather_cost(const grim_bcr_matrix *A, int64_t N) {
     const GatherLayout &L = A->gather;
-    const double nbr = (double)A->nbr;
+    const double nbr = (double)L.nstrips;
     const double per_wg = (double)L.xrows / nbr * 128.0 +
                           ((double)L.nsteps * 160.0 + (double)L.payload.size()) / nbr + 30e3;
     const double nwg = (double)((N + 63) / 64) * nbr;
@@ -718,11 +721,11 @@ grim_status launch_spmm_gather(const grim_bcr_matrix *A, const void *X, int64_t 
     p.rows = A->gather.d_rows;
     p.desc = A->gather.d_desc;
     p.payload = A->gather.d_payload;
-    p.strip_order = A->dev.strip_order;
+    p.out_row = A->gather.d_out_row;
     p.X = static_cast<const unsigned short *>(X);
     p.Y = Y;
     p.N = N; p.ldx = ldx; p.ldy = ldy;
-    p.nbr = (int32_t)A->nbr;
+    p.nbr = (int32_t)A->gather.nstrips;
     p.ntiles = (int32_t)((N + 63) / 64);
     p.yvec = (reinterpret_cast<uintptr_t>(Y) % 16 == 0 && ldy % 4 == 0 && N % 4 == 0) ? 4 : 1;
     const int64_t nwg = ((int64_t)p.ntiles + 7) / 8 * 8 * p.nbr;

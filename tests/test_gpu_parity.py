@@ -296,11 +296,40 @@ def test_gather_kernel_c2_and_refusals(g):
         assert e.value.status == 7
     with pytest.raises(GrimError):                                # tile knobs belong to the staged kernel
         run_spmm(g, A, wl.X, wl.dtype, wl.M, wl.N, kernel=3, tile_n=64)
-    wl5 = gen.c5_nonuniform(64)                                   # 32-row blocks: staged kernel only
-    A5 = pack_workload(g, wl5.W, wl5.dtype, wl5.mask)
+    w1 = gen.c1_single_fp32()                                     # fp32: no matrix-core kernel
+    A1 = pack_workload(g, w1.W, w1.dtype, w1.mask)
     with pytest.raises(GrimError) as e:
-        run_spmm(g, A5, wl5.X, wl5.dtype, wl5.M, wl5.N, kernel=3)
+        run_spmm(g, A1, w1.X, w1.dtype, w1.M, w1.N, kernel=3)
     assert e.value.status == 7
+    M, K = 96, 128                                                # 24-row blocks neither divide 16 nor are a multiple
+    m24 = gen.random_mask(M, K, 24, 32, 12, 8, seed=304)
+    A24 = pack_workload(g, gen.normal_weights(M, K, gen.F16, seed=305), gen.F16, m24)
+    with pytest.raises(GrimError) as e:
+        run_spmm(g, A24, gen.normal_activations(K, 64, gen.F16, seed=306), gen.F16, M, 64, kernel=3)
+    assert e.value.status == 7
+
+
+@pytest.mark.parametrize("dtype", [gen.F16, gen.BF16])
+@pytest.mark.parametrize("BR,BC", [(4, 16), (1, 32), (2, 8), (8, 24), (32, 32), (48, 16), (64, 64)])
+def test_gather_kernel_block_heights(g, dtype, BR, BC):
+    """Block heights that divide 16 (several strips share a 16-row tile; 4 x 16 is the block size of the
+    paper's CNN evaluation) or are multiples of 16 (a strip spans several tiles), mixed kept counts with
+    empty blocks, a row count that is not a multiple of 16 where the block height allows it; forced and
+    chosen by the library."""
+    M = 192 if BR in (48, 64) else 72 if 72 % BR == 0 else 96
+    K, N = BC * 13, 136
+    mask = gen.random_mask(M, K, BR, BC, tuple(sorted({0, 1, (BR + 1) // 2, BR})), tuple(sorted({0, 1, BC // 3 + 1, BC})), seed=310 + BR)
+    W = gen.normal_weights(M, K, dtype, seed=311)
+    X = gen.normal_activations(K, N, dtype, seed=312)
+    A = pack_workload(g, W, dtype, mask)
+    Yref, S = oracle_product(W, X, dtype, mask)
+    Y = run_spmm(g, A, X, dtype, M, N, kernel=3)
+    assert_close(Y, Yref, S, dtype, f"gather {dtype} {BR}x{BC}")
+    Xd = to_device(X, dtype)
+    if BR not in (16, 32):
+        assert g.spmm_kernel_name(A, Xd, N, N) == "bcr_spmm_gather"      # the only matrix-core route
+    Y0 = run_spmm(g, A, X, dtype, M, N)
+    assert_close(Y0, Yref, S, dtype, f"auto {dtype} {BR}x{BC}")
 
 
 def test_kernel_choice_follows_the_cost_model(g):
@@ -476,8 +505,8 @@ def test_device_call_errors(g):
     with pytest.raises(GrimError) as e:
         g.spmm(H, Xd, 64, 64, Yd, 64)
     assert e.value.name == "GRIM_ERR_DEVICE"
-    big = gen.random_mask(256, 256, 128, 32, 8, 8, seed=1)
-    B = pack_workload(g, gen.normal_weights(256, 256, gen.F16, 1), gen.F16, big)
+    big = gen.random_mask(144, 256, 72, 32, 8, 8, seed=1)        # 72-row blocks: too tall for the FMA kernel, no 16-row tiling
+    B = pack_workload(g, gen.normal_weights(144, 256, gen.F16, 1), gen.F16, big)
     with pytest.raises(GrimError) as e:
         g.spmm(B, Xd, 64, 64, Yd, 64)
     assert e.value.name == "GRIM_ERR_UNSUPPORTED"
