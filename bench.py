@@ -201,6 +201,17 @@ def main() -> int:
                 "C_batched_us_per_product": tC * 1e6, "C_gbs": b3 / tC / 1e9, "C_frac_hbm": b3 / tC / 1e9 / HBM_PEAK_GBS,
                 "C_products_per_launch": copies,
             }
+            # the same matrix as an LSTM layer (hidden = input = 1024): one step = gate product + cell
+            Hh = w3.M // 4
+            xh = [dev_tensor(w3.X, w3.dtype).clone() for _ in range(2)]
+            gates = torch.empty((w3.M, batch), dtype=torch.float32, device=dev)
+            cst = torch.zeros((Hh, batch), dtype=torch.float32, device=dev)
+
+            def lstm(i):
+                g.lstm_step(mats[0], xh[i % 2], batch, batch, gates, batch, None, cst, batch, xh[(i + 1) % 2][w3.K - Hh:],
+                            batch, None, 0, stream)
+            tL, _ = time_launches(torch, lstm, 1000, 50)
+            extra[f"c3_b{batch}"]["lstm_step_us"] = tL * 1e6
             del G, mats
         # ---- c5: large non-uniform bf16 SpMM
         w5 = gen.c5_nonuniform()

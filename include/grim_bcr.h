@@ -182,6 +182,30 @@ grim_status grim_bcr_spmv_batched(const grim_bcr_group *G, const void *x_dev, in
 void grim_bcr_group_free(grim_bcr_group *G);
 
 /*
+ * LSTM cell around the gate product (Section 3.1: an RNN layer's gate matrices are one matrix-vector
+ * product per time step).  With the gate matrix [W_ih | W_hh] of 4H rows packed as one BCR matrix
+ * and the step's input vector [x; h], grim_bcr_spmv delivers the gate pre-activations, rows [0, H)
+ * input gate, [H, 2H) forget gate, [2H, 3H) cell candidate, [3H, 4H) output gate (the order is this
+ * library's convention; the paper does not fix one).  grim_lstm_cell is the elementwise rest:
+ *     i, f, o = sigmoid(gate + bias), g = tanh(gate + bias), c <- f * c + i * g, h = o * tanh(c)
+ *   gates_dev   4H x batch fp32, leading dimension ldg >= batch
+ *   bias_dev    4H fp32 or NULL
+ *   c_dev       H x batch fp32 (ldc), read and overwritten
+ *   h_dev       H x batch of element type dt (ldh), written; typically the h part of the next step's
+ *               input vector.  May be NULL.
+ *   h32_dev     optional fp32 copy of h (ldh32); NULL to skip
+ * grim_bcr_lstm_step = grim_bcr_spmv(A, xh_dev, ...) into gates_dev, then grim_lstm_cell; A must have
+ * 4H rows.  Both only enqueue work on hip_stream.  Errors: NULL, SHAPE (batch outside 1..8 for the
+ * step, H < 1, leading dimension too small, A->M != 4H), DTYPE, DEVICE, UNSUPPORTED.
+ */
+grim_status grim_lstm_cell(const float *gates_dev, int64_t ldg, const float *bias_dev, float *c_dev, int64_t ldc,
+                           void *h_dev, grim_dtype dt, int64_t ldh, float *h32_dev, int64_t ldh32,
+                           int64_t H, int32_t batch, void *hip_stream);
+grim_status grim_bcr_lstm_step(const grim_bcr_matrix *A, const void *xh_dev, int32_t batch, int64_t ldx,
+                               float *gates_dev, int64_t ldg, const float *bias_dev, float *c_dev, int64_t ldc,
+                               void *h_dev, int64_t ldh, float *h32_dev, int64_t ldh32, void *hip_stream);
+
+/*
  * BCRC export (Section 4.3, "Compact Model Storage"): the paper's six-array, row-level form of the
  * same pruned matrix.  Rows of the whole matrix are reordered so that rows with the same set of
  * kept (global) columns are adjacent -- groups in order of the first original row that shows the

@@ -57,7 +57,7 @@ class BcrcView(ctypes.Structure):
 EXPORTS = ["grim_bcr_pack", "grim_bcr_unpack", "grim_bcr_arrays", "grim_bcr_spmm", "grim_bcr_spmm_tuned",
            "grim_bcr_spmv", "grim_bcr_group_create", "grim_bcr_spmv_batched", "grim_bcr_group_free",
            "grim_bcr_free", "grim_status_str", "grim_bcr_spmm_kernel_name",
-           "grim_bcr_export_bcrc", "grim_bcrc_arrays", "grim_bcrc_free"]
+           "grim_bcr_export_bcrc", "grim_bcrc_arrays", "grim_bcrc_free", "grim_lstm_cell", "grim_bcr_lstm_step"]
 
 
 def lib_path() -> str:
@@ -96,6 +96,8 @@ def load_library():
     lib.grim_bcr_export_bcrc.argtypes = [p, ctypes.POINTER(p)]
     lib.grim_bcrc_arrays.argtypes = [p, ctypes.POINTER(BcrcView)]
     lib.grim_bcrc_free.argtypes = [p]
+    lib.grim_lstm_cell.argtypes = [p, i64, p, p, i64, p, i32, i64, p, i64, i64, i32, p]
+    lib.grim_bcr_lstm_step.argtypes = [p, p, i32, i64, p, i64, p, p, i64, p, i64, p, i64, p]
     lib.grim_bcr_spmm_kernel_name.argtypes = [p, p, i64, i64, i32, i32, i32]
     for name in EXPORTS:
         getattr(lib, name).restype = i32
@@ -252,6 +254,20 @@ def spmm(A: BcrMatrix, X, N: int, ldx: int, Y, ldy: int, stream=None, *,
         _check(st, "grim_bcr_spmm_tuned")
     else:
         _check(lib.grim_bcr_spmm(A.handle, _addr(X), N, ldx, _addr(Y), ldy, _stream(stream)), "grim_bcr_spmm")
+
+
+def lstm_cell(gates, ldg: int, bias, c, ldc: int, h, dtype, ldh: int, h32, ldh32: int, H: int, batch: int, stream=None):
+    """grim_lstm_cell: enqueue the elementwise part of an LSTM step (c updated in place, h written)."""
+    lib = load_library()
+    _check(lib.grim_lstm_cell(_addr(gates), ldg, _addr(bias), _addr(c), ldc, _addr(h), _DT_CODE[dtype], ldh,
+                              _addr(h32), ldh32, H, batch, _stream(stream)), "grim_lstm_cell")
+
+
+def lstm_step(A: BcrMatrix, xh, batch: int, ldx: int, gates, ldg: int, bias, c, ldc: int, h, ldh: int,
+              h32=None, ldh32: int = 0, stream=None):
+    """grim_bcr_lstm_step: gate product of [W_ih | W_hh] with [x; h], then the cell."""
+    _check(A._lib.grim_bcr_lstm_step(A.handle, _addr(xh), batch, ldx, _addr(gates), ldg, _addr(bias), _addr(c), ldc,
+                                     _addr(h), ldh, _addr(h32), ldh32, _stream(stream)), "grim_bcr_lstm_step")
 
 
 def export_bcrc(A: BcrMatrix) -> dict:

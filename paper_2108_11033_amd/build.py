@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libgrim_bcr.so")
-SOURCES = ["bcr_pack.cpp", "bcr_spmm.hip", "bcr_spmv.hip"]
+SOURCES = ["bcr_pack.cpp", "bcr_spmm.hip", "bcr_spmv.hip", "lstm_cell.hip"]
 
 
 def build(verbose: bool = False) -> str:

@@ -176,4 +176,7 @@ grim_status launch_spmv(const GemvDesc *table_dev_or_null, const GemvDesc &singl
                         int64_t M, int64_t K, int32_t BR, int32_t BC, int32_t dtype, int32_t ukr,
                         int32_t ukc, int32_t vec, int32_t krmax, int32_t kcmax, const void *x, int64_t x_stride, int32_t batch,
                         int64_t ldx, float *y, int64_t y_stride, int64_t ldy, hipStream_t stream);
+grim_status launch_lstm_cell(const float *gates, int64_t ldg, const float *bias, float *c, int64_t ldc, void *h,
+                             int32_t dtype, int64_t ldh, float *h32, int64_t ldh32, int64_t H, int32_t batch,
+                             hipStream_t stream);
 }  // namespace grim

@@ -659,6 +659,31 @@ grim_status grim_bcr_spmv(const grim_bcr_matrix *A, const void *x_dev, int32_t b
     return launch_spmm_fma(A, x_dev, batch, ldx, y_dev, ldy, stream);
 }
 
+grim_status grim_lstm_cell(const float *gates_dev, int64_t ldg, const float *bias_dev, float *c_dev, int64_t ldc,
+                           void *h_dev, grim_dtype dt, int64_t ldh, float *h32_dev, int64_t ldh32, int64_t H,
+                           int32_t batch, void *hip_stream) {
+    if (!gates_dev || !c_dev) return GRIM_ERR_NULL;
+    if (H < 1 || batch < 1 || ldg < batch || ldc < batch || (h_dev && ldh < batch) || (h32_dev && ldh32 < batch))
+        return GRIM_ERR_SHAPE;
+    if (H > (int64_t(1) << 40) / batch) return GRIM_ERR_SHAPE;
+    if (dt != GRIM_F32 && dt != GRIM_F16 && dt != GRIM_BF16) return GRIM_ERR_DTYPE;
+    return launch_lstm_cell(gates_dev, ldg, bias_dev, c_dev, ldc, h_dev, dt, ldh, h32_dev, ldh32, H, batch,
+                            static_cast<hipStream_t>(hip_stream));
+}
+
+grim_status grim_bcr_lstm_step(const grim_bcr_matrix *A, const void *xh_dev, int32_t batch, int64_t ldx,
+                               float *gates_dev, int64_t ldg, const float *bias_dev, float *c_dev, int64_t ldc,
+                               void *h_dev, int64_t ldh, float *h32_dev, int64_t ldh32, void *hip_stream) {
+    if (!A || !xh_dev || !gates_dev || !c_dev) return GRIM_ERR_NULL;
+    if (A->M % 4 != 0) return GRIM_ERR_SHAPE;
+    const int64_t H = A->M / 4;
+    if (batch < 1 || batch > 8 || ldc < batch || (h_dev && ldh < batch) || (h32_dev && ldh32 < batch)) return GRIM_ERR_SHAPE;
+    grim_status st = grim_bcr_spmv(A, xh_dev, batch, ldx, gates_dev, ldg, hip_stream);
+    if (st != GRIM_OK) return st;
+    return grim_lstm_cell(gates_dev, ldg, bias_dev, c_dev, ldc, h_dev, (grim_dtype)A->dtype, ldh, h32_dev, ldh32, H, batch,
+                          hip_stream);
+}
+
 grim_status grim_bcr_group_create(const grim_bcr_matrix *const *mats, int32_t count, grim_bcr_group **out) {
     if (out) *out = nullptr;
     if (!mats || !out) return GRIM_ERR_NULL;

@@ -1,0 +1,69 @@
+// LSTM cell around the gate product (Section 3.1: the gate matrices of an RNN layer are one
+// matrix-vector product per time step; Section 5 evaluates RNNs end to end).
+//
+// The BCR product y = [W_ih | W_hh] * [x; h] delivers the four gate pre-activations stacked as
+// rows [0, H) input gate, [H, 2H) forget gate, [2H, 3H) cell candidate, [3H, 4H) output gate.
+// This kernel is the elementwise rest of the step:
+//     i = sigmoid(y_i + b_i)   f = sigmoid(y_f + b_f)   g = tanh(y_g + b_g)   o = sigmoid(y_o + b_o)
+//     c' = f * c + i * g        h' = o * tanh(c')
+// c stays fp32 and is updated in place; h' is written in the matrix's element type straight into
+// the lower part of the next step's input vector [x; h], and optionally as fp32 as well.
+#include <hip/hip_runtime.h>
+
+#include "bcr_matrix.hpp"
+
+namespace grim {
+
+struct LstmParams {
+    const float *gates;
+    const float *bias;
+    float *c;
+    void *h;
+    float *h32;
+    int64_t ldg, ldc, ldh, ldh32, H;
+    int32_t batch, dtype;
+};
+
+__device__ __forceinline__ float sigmoidf_(float v) { return 1.0f / (1.0f + expf(-v)); }
+
+__device__ __forceinline__ unsigned short f32_to_bf16_rne(float f) {
+    unsigned int u = __builtin_bit_cast(unsigned int, f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (unsigned short)((u >> 16) | 0x40u);   // NaN stays NaN
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (unsigned short)(u >> 16);
+}
+
+__global__ void __launch_bounds__(256) lstm_cell_kernel(LstmParams p) {
+    const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (e >= p.H * p.batch) return;
+    const int64_t r = e / p.batch;
+    const int b = (int)(e - r * p.batch);
+    const float bi = p.bias ? p.bias[r] : 0.f, bf = p.bias ? p.bias[p.H + r] : 0.f;
+    const float bg = p.bias ? p.bias[2 * p.H + r] : 0.f, bo = p.bias ? p.bias[3 * p.H + r] : 0.f;
+    const float gi = sigmoidf_(p.gates[r * p.ldg + b] + bi);
+    const float gf = sigmoidf_(p.gates[(p.H + r) * p.ldg + b] + bf);
+    const float gg = tanhf(p.gates[(2 * p.H + r) * p.ldg + b] + bg);
+    const float go = sigmoidf_(p.gates[(3 * p.H + r) * p.ldg + b] + bo);
+    const float c = gf * p.c[r * p.ldc + b] + gi * gg;
+    const float h = go * tanhf(c);
+    p.c[r * p.ldc + b] = c;
+    if (p.h32) p.h32[r * p.ldh32 + b] = h;
+    if (p.h) {
+        if (p.dtype == GRIM_F32) static_cast<float *>(p.h)[r * p.ldh + b] = h;
+        else if (p.dtype == GRIM_F16) static_cast<_Float16 *>(p.h)[r * p.ldh + b] = (_Float16)h;
+        else static_cast<unsigned short *>(p.h)[r * p.ldh + b] = f32_to_bf16_rne(h);
+    }
+}
+
+grim_status launch_lstm_cell(const float *gates, int64_t ldg, const float *bias, float *c, int64_t ldc, void *h,
+                             int32_t dtype, int64_t ldh, float *h32, int64_t ldh32, int64_t H, int32_t batch,
+                             hipStream_t stream) {
+    LstmParams p{gates, bias, c, h, h32, ldg, ldc, ldh, ldh32, H, batch, dtype};
+    const int64_t n = H * batch;
+    const int64_t nwg = (n + 255) / 256;
+    if (nwg > 0x7fffffff) return GRIM_ERR_SHAPE;
+    hipLaunchKernelGGL(lstm_cell_kernel, dim3((unsigned)nwg), dim3(256), 0, stream, p);
+    return hipGetLastError() == hipSuccess ? GRIM_OK : GRIM_ERR_DEVICE;
+}
+
+}  // namespace grim
