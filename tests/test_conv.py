@@ -1,0 +1,139 @@
+"""Convolution with the im2col matrix never materialised (Section 3.1 / 4.5): pins of the fp64 reference (CPU)
+and parity of grim_bcr_conv2d against it (GPU)."""
+import numpy as np
+import pytest
+
+import bcr_inputs as gen
+from oracle import bcr_oracle as orc
+from oracle import conv_ref
+
+
+def _masked(W, dtype, mask):
+    return orc.masked_dense(gen.storage_to_f64(W, dtype), mask.BR, mask.BC, mask.row_ptr, mask.row_idx, mask.col_ptr, mask.col_idx)
+
+
+# ------------------------------------------------------------------ pins of the reference (no GPU)
+@pytest.mark.parametrize("kh,kw", [(3, 3), (1, 1), (3, 1), (1, 3)])
+def test_reference_equals_im2col_product_and_library_conv(kh, kw):
+    import torch
+    Cin, H, W, M = 6, 7, 9, 8
+    rng = np.random.default_rng(31)
+    Wm = rng.standard_normal((M, Cin * kh * kw))
+    Wm[rng.random(Wm.shape) < 0.6] = 0.0
+    F = rng.standard_normal((Cin, H, W))
+    Y = conv_ref.conv_same(Wm, F, kh, kw)
+    # the GEMM view of Section 3.1: filter matrix times the im2col matrix
+    assert np.allclose(Y.reshape(M, -1), Wm @ conv_ref.im2col(F, kh, kw), rtol=0, atol=1e-12)
+    # the library routine, double precision, zero padding kh // 2, kw // 2
+    Yt = torch.nn.functional.conv2d(torch.from_numpy(F)[None], torch.from_numpy(Wm.reshape(M, Cin, kh, kw)),
+                                    padding=(kh // 2, kw // 2))[0].numpy()
+    assert np.allclose(Y, Yt, rtol=0, atol=1e-12)
+
+
+def test_reference_special_cases():
+    Cin, H, W, M = 3, 5, 8, 4
+    rng = np.random.default_rng(32)
+    F = rng.standard_normal((Cin, H, W))
+    # a 1 x 1 kernel is a plain matrix product over channels
+    W1 = rng.standard_normal((M, Cin))
+    assert np.allclose(conv_ref.conv_same(W1, F, 1, 1).reshape(M, -1), W1 @ F.reshape(Cin, -1), atol=1e-13)
+    # a single centre tap of a 3 x 3 kernel copies the channel; the corner tap shifts it by one row and one column
+    Wc = np.zeros((1, Cin * 9)); Wc[0, 1 * 9 + 4] = 1.0
+    assert np.array_equal(conv_ref.conv_same(Wc, F, 3, 3)[0], F[1])
+    Wk = np.zeros((1, Cin * 9)); Wk[0, 2 * 9 + 0] = 1.0          # (r, q) = (0, 0): Y[h, w] = F[h - 1, w - 1]
+    Yk = conv_ref.conv_same(Wk, F, 3, 3)[0]
+    assert np.array_equal(Yk[1:, 1:], F[2, :-1, :-1]) and not Yk[0].any() and not Yk[:, 0].any()
+    # integer data: exact, and the scale bounds the result
+    Wi = rng.integers(-3, 4, (M, Cin * 9)).astype(np.float64)
+    Fi = rng.integers(-3, 4, (Cin, H, W)).astype(np.float64)
+    Yi = conv_ref.conv_same(Wi, Fi, 3, 3)
+    assert np.array_equal(Yi, np.round(Yi)) and (np.abs(Yi) <= conv_ref.abs_scale(Wi, Fi, 3, 3)).all()
+
+
+# ------------------------------------------------------------------ GPU
+def _run(g, A, F, dtype, M, Cin, H, W, kh, kw, ldy=None):
+    import torch
+    from helpers import to_device
+    dev = torch.device("cuda:0")
+    N = H * W
+    ldy = N if ldy is None else ldy
+    Fd = to_device(np.ascontiguousarray(F.reshape(Cin, N)), dtype)
+    Yd = torch.full((M, ldy), float("nan"), dtype=torch.float32, device=dev)
+    g.conv2d(A, Fd, Cin, H, W, kh, kw, Yd, ldy, torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    Y = Yd.cpu().numpy()
+    if ldy > N:
+        assert np.isnan(Y[:, N:]).all()
+    return Y[:, :N].reshape(M, H, W)
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("dtype", [gen.F16, gen.BF16])
+@pytest.mark.parametrize("Cin,H,W,kh,kw,BR,BC", [
+    (32, 14, 14, 3, 3, 16, 32),      # 14 x 14: image rows of 28 bytes, every alignment of the window occurs
+    (16, 12, 20, 3, 3, 4, 16),       # the paper's 4 x 16 blocks
+    (64, 8, 8, 1, 1, 16, 32),        # 1 x 1: a plain product, one tile exactly
+    (24, 9, 16, 3, 1, 16, 24),
+    (8, 10, 13, 1, 3, 32, 8),        # odd width (130 positions)
+])
+def test_conv_parity(dtype, Cin, H, W, kh, kw, BR, BC):
+    import paper_2108_11033_amd as g
+    from helpers import pack_workload, TOL
+    M, K = 96, Cin * kh * kw
+    mask = gen.random_mask(M, K, BR, BC, tuple(sorted({0, 1, BR // 2, BR})), tuple(sorted({1, BC // 4 + 1, BC})), seed=700 + Cin)
+    Wt = gen.normal_weights(M, K, dtype, seed=701)
+    F = gen.normal_activations(Cin, H * W, dtype, seed=702, relu=True).reshape(Cin, H, W)
+    A = pack_workload(g, Wt, dtype, mask)
+    Wm, F64 = _masked(Wt, dtype, mask), gen.storage_to_f64(F, dtype)
+    Yref, S = conv_ref.conv_same(Wm, F64, kh, kw), conv_ref.abs_scale(Wm, F64, kh, kw)
+    Y = _run(g, A, F, dtype, M, Cin, H, W, kh, kw)
+    assert np.isfinite(Y).all()
+    assert (Y[S == 0] == 0).all()
+    pos = S > 0
+    assert (np.abs(Y - Yref)[pos] / S[pos]).max() <= TOL[dtype]
+    assert np.abs(Y - Yref).max() <= TOL[dtype] * np.abs(Yref).max()
+    Y2 = _run(g, A, F, dtype, M, Cin, H, W, kh, kw, ldy=H * W + 5)
+    assert Y2.tobytes() == Y.tobytes()
+
+
+@pytest.mark.gpu
+def test_conv_integer_data_is_exact_and_equals_the_im2col_product():
+    """Small integers: every sum is exact, so the fused path, the library's own product on the materialised
+    im2col matrix and the reference must agree bit for bit."""
+    import torch
+    import paper_2108_11033_amd as g
+    from helpers import pack_workload, run_spmm
+    dtype, Cin, H, W, M = gen.F16, 32, 16, 24, 64
+    K = Cin * 9
+    mask = gen.random_mask(M, K, 16, 32, (0, 4, 8), (0, 8, 16), seed=710)
+    Wt = gen.small_int_values((M, K), dtype, seed=711)
+    F = gen.small_int_values((Cin, H, W), dtype, seed=712)
+    A = pack_workload(g, Wt, dtype, mask)
+    Yref = conv_ref.conv_same(_masked(Wt, dtype, mask), gen.storage_to_f64(F, dtype), 3, 3)
+    Y = _run(g, A, F, dtype, M, Cin, H, W, 3, 3)
+    assert np.array_equal(Y.astype(np.float64), Yref)
+    X = conv_ref.im2col(F, 3, 3)
+    Yx = run_spmm(g, A, X, dtype, M, H * W)
+    assert Yx.tobytes() == np.ascontiguousarray(Y.reshape(M, -1)).tobytes()
+
+
+@pytest.mark.gpu
+def test_conv_refusals():
+    import torch
+    import paper_2108_11033_amd as g
+    from helpers import pack_workload, to_device
+    from paper_2108_11033_amd import GrimError
+    dev = torch.device("cuda:0")
+    wl = gen.c2_vgg_conv(64)
+    A = pack_workload(g, wl.W, wl.dtype, wl.mask)                 # K = 2304 = 256 * 9
+    F = torch.zeros((256, 64), dtype=torch.float16, device=dev)
+    Y = torch.full((256, 64), 5.0, dtype=torch.float32, device=dev)
+    for args, name in (((255, 8, 8, 3, 3), "GRIM_ERR_SHAPE"),      # Cin * kh * kw != K
+                       ((256, 8, 8, 2, 2), "GRIM_ERR_SHAPE"),      # even kernel
+                       ((256, 4, 8, 3, 3), "GRIM_ERR_UNSUPPORTED"),  # fewer than 64 positions
+                       ((256, 16, 4, 3, 3), "GRIM_ERR_UNSUPPORTED")):  # image rows shorter than 8
+        with pytest.raises(GrimError) as e:
+            g.conv2d(A, F, *args, Y, 64)
+        assert e.value.name == name, args
+    torch.cuda.synchronize()
+    assert (Y == 5.0).all()
