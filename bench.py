@@ -97,6 +97,8 @@ def main() -> int:
     ap.add_argument("--strips-per-wg", type=int, default=0)
     ap.add_argument("--kernel", type=int, default=0, help="0 choose, 2 staged matrix-core kernel, 3 row-gathering one")
     ap.add_argument("--extra", action="store_true", help="also time the SpMV and large non-uniform workloads")
+    ap.add_argument("--conv", action="store_true",
+                    help="also time c2's layer as a convolution on the feature map (no im2col matrix)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--sweep", action="store_true",
                     help="also run the block-size search of the paper on a 1024x1024 layer at 10x pruning, and the "
@@ -262,6 +264,20 @@ def main() -> int:
         extra["c4"] = {"layers": layers, "total_us": tot_t * 1e6, "useful_tflops": tot_f / tot_t / 1e12,
                        "gbs": tot_b / tot_t / 1e9, "frac_hbm": tot_b / tot_t / 1e9 / HBM_PEAK_GBS}
         out["extra"] = extra
+
+    if args.conv:
+        # c2's layer fed with the feature map it stands for: 256 channels of 56 x 56, 3 x 3 kernel, same padding
+        Cin, Hc, Wc = 256, 56, 56
+        F0 = dev_tensor(gen.normal_activations(Cin, Hc * Wc, wl.dtype, seed=77, relu=True), wl.dtype)
+        Fs = [F0] + [F0.clone() for _ in range(sets - 1)]
+        tc, _ = time_launches(torch, lambda i: g.conv2d(A, Fs[i % sets], Cin, Hc, Wc, 3, 3, Ys[i % sets], wl.N, stream),
+                              args.steps, args.warmup)
+        cbytes = abytes - wl.K * wl.N * 2 + Cin * Hc * Wc * 2
+        out["conv"] = {"workload": "c2's weights on a 256 x 56 x 56 fp16 feature map, 3x3, zero padding 1",
+                       "us": tc * 1e6, "useful_tflops": flops / tc / 1e12, "algorithmic_mb": cbytes / 1e6,
+                       "gbs": cbytes / tc / 1e9, "product_on_materialised_im2col_us": t_cold * 1e6,
+                       "im2col_matrix_mb": wl.K * wl.N * 2 / 1e6}
+        del Fs
 
     if args.sweep:
         from paper_2108_11033_amd import tune

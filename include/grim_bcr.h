@@ -182,6 +182,25 @@ grim_status grim_bcr_spmv_batched(const grim_bcr_group *G, const void *x_dev, in
 void grim_bcr_group_free(grim_bcr_group *G);
 
 /*
+ * grim_bcr_conv2d -- a CONV layer without its im2col matrix (Section 3.1: CONV = filter matrix x im2col
+ * matrix; Section 4.5: rows of that matrix whose weights are all pruned are skipped).  Stride 1, zero
+ * padding kh/2 and kw/2 ("same"), kh and kw odd, batch 1:
+ *     Y[m][h * W + w] = sum over (cin, r, q) of W_bcr[m][cin * kh * kw + r * kw + q] *
+ *                       F[cin][h + r - kh/2][w + q - kw/2]            (F = 0 outside the image)
+ * i.e. column k of the packed matrix is (cin, r, q) in that order (the order of the usual
+ * weight.reshape(Cout, Cin * kh * kw)); A must have K = Cin * kh * kw columns.
+ *   F_dev  Cin x H x W contiguous, element type of A (any element alignment)
+ *   Y_dev  M x (H * W) fp32, leading dimension ldy >= H * W, overwritten
+ * The result equals grim_bcr_spmm on the materialised im2col matrix (bit for bit when every sum is
+ * exact); only the feature map is read -- kh * kw times fewer bytes -- and only the rows a strip keeps.
+ * Runs on the row-gathering matrix-core kernel: fp16 / bf16, block height a divisor or a multiple of
+ * 16, 64 <= H * W < 2^24, W >= 8, kh * kw <= 16, Cin * H * W <= 2^30; otherwise GRIM_ERR_UNSUPPORTED.
+ * Errors: NULL, SHAPE (even kernel, K != Cin * kh * kw, ldy < H * W, sizes < 1), DEVICE, UNSUPPORTED.
+ */
+grim_status grim_bcr_conv2d(const grim_bcr_matrix *A, const void *F_dev, int32_t Cin, int32_t H, int32_t W,
+                            int32_t kh, int32_t kw, float *Y_dev, int64_t ldy, void *hip_stream);
+
+/*
  * LSTM cell around the gate product (Section 3.1: an RNN layer's gate matrices are one matrix-vector
  * product per time step).  With the gate matrix [W_ih | W_hh] of 4H rows packed as one BCR matrix
  * and the step's input vector [x; h], grim_bcr_spmv delivers the gate pre-activations, rows [0, H)

@@ -659,6 +659,17 @@ grim_status grim_bcr_spmv(const grim_bcr_matrix *A, const void *x_dev, int32_t b
     return launch_spmm_fma(A, x_dev, batch, ldx, y_dev, ldy, stream);
 }
 
+grim_status grim_bcr_conv2d(const grim_bcr_matrix *A, const void *F_dev, int32_t Cin, int32_t H, int32_t W, int32_t kh,
+                            int32_t kw, float *Y_dev, int64_t ldy, void *hip_stream) {
+    if (!A || !F_dev || !Y_dev) return GRIM_ERR_NULL;
+    if (Cin < 1 || H < 1 || W < 1 || kh < 1 || kw < 1 || kh % 2 == 0 || kw % 2 == 0) return GRIM_ERR_SHAPE;
+    if ((int64_t)Cin * kh * kw != A->K || ldy < (int64_t)H * W) return GRIM_ERR_SHAPE;
+    if (!A->on_device) return GRIM_ERR_DEVICE;
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev != A->device) { (void)hipGetLastError(); return GRIM_ERR_DEVICE; }
+    return launch_conv_gather(A, F_dev, Cin, H, W, kh, kw, Y_dev, ldy, static_cast<hipStream_t>(hip_stream));
+}
+
 grim_status grim_lstm_cell(const float *gates_dev, int64_t ldg, const float *bias_dev, float *c_dev, int64_t ldc,
                            void *h_dev, grim_dtype dt, int64_t ldh, float *h32_dev, int64_t ldh32, int64_t H,
                            int32_t batch, void *hip_stream) {

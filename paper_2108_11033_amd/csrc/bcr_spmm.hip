@@ -743,6 +743,260 @@ grim_status launch_spmm_gather(const grim_bcr_matrix *A, const void *X, int64_t 
     return hipGetLastError() == hipSuccess ? GRIM_OK : GRIM_ERR_DEVICE;
 }
 
+// ------------------------------------------------------------------------------------------
+// convolution with the im2col matrix never formed (Section 3.1: CONV = filter matrix x im2col
+// matrix; Section 4.5: rows of that matrix whose weights are all pruned are skipped)
+//
+// Same scheme and layout as the row-gathering kernel; only the fetch differs.  Row k of the
+// im2col matrix is (input channel cin, kernel row r, kernel column q) with k = cin * kh * kw +
+// r * kw + q, and its entry at output position n = h * W + w is F[cin][h + r - kh/2][w + q - kw/2]
+// (zero outside the image).  For 8 consecutive positions these are 8 consecutive elements of the
+// feature map starting at cin * H * W + n + (r - kh/2) * W + (q - kw/2) -- at any 2-byte alignment
+// -- with some of them invalid at the image border.  A lane loads its window with one 16-byte
+// load at that address, and when the step is multiplied zeroes the invalid elements with a
+// 16-byte mask that depends on (kernel tap, piece of the tile) only and is read from a table the
+// workgroup builds in LDS when it starts.  A window that would reach outside the feature map
+// (the first and last few positions of the first and last channel) is put together from single
+// guarded element loads instead.  Only rows kept by the strip are ever touched, and the feature
+// map is read instead of a matrix kh * kw times its size.
+// ------------------------------------------------------------------------------------------
+struct ConvParams {
+    const int32_t *sptr;
+    const int32_t *out_row;
+    const uint32_t *rows;
+    const uint32_t *desc;
+    const unsigned char *payload;
+    const unsigned short *F;     // [Cin][H][W]
+    float *Y;                    // [M][ldy], position n = h * W + w
+    int64_t ldy;
+    int32_t N, H, W, kh, kw;     // N = H * W
+    int32_t KK, kk_magic;        // kh * kw and ceil(2^31 / KK): k / KK = umulhi(2 k, magic) for k < 2^27, KK <= 16
+    int32_t kw_magic;            // ceil(256 / kw): tap / kw = tap * magic >> 8 for tap < 16
+    int32_t total;               // elements of the feature map
+    int32_t nbr, ntiles;
+    int32_t yvec;
+};
+
+struct __attribute__((packed, aligned(2))) ConvWindow {
+    unsigned int d[4];
+};
+
+constexpr int kConvMaxTaps = 16;
+constexpr int kConvLdsBytes = 4 * 8192 + (kConvMaxTaps + 1) * 8 * 16;
+
+template <bool BF16>
+__global__ void __launch_bounds__(256, 4) bcr_conv_gather(ConvParams p) {
+    constexpr int NT = 4, TN = 64, PITCH = 128, CPR = 8;
+    constexpr int SB = 3;                        // steps a wave has in flight
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+    const int id = blockIdx.x;
+    const int xcd = id & 7, slot = id >> 3;
+    const int tile = (slot / p.nbr) * 8 + xcd;
+    const int t = slot % p.nbr;
+    if (tile >= p.ntiles) return;
+    int n0 = tile * TN;
+    if (n0 + TN > p.N) n0 = p.N - TN;            // ragged last tile: overlap the neighbour (N >= 64)
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int g0 = p.sptr[t], nst = p.sptr[t + 1] - g0;
+    const int s_beg = g0 + (int)((int64_t)nst * wave / 4), s_end = g0 + (int)((int64_t)nst * (wave + 1) / 4);
+    char *buf = lds + wave * 8192;
+    // per (tap, piece of the tile) the 16-byte validity mask of the piece's 8 positions; entry KK
+    // is all zero (padding slots).
+    u32x4 *vtab = reinterpret_cast<u32x4 *>(lds + 4 * 8192);
+    const int ph = p.kh >> 1, pw = p.kw >> 1;
+    if (tid < (p.KK + 1) * 8) {
+        const int tap = tid >> 3, cc = tid & 7;
+        const int r = tap / p.kw, q = tap - r * p.kw;
+        const int dr = r - ph, dq = q - pw;
+        const int nb = n0 + cc * 8;
+        const int h0 = nb / p.W, w0 = nb - h0 * p.W;
+        unsigned int m[4] = {0u, 0u, 0u, 0u};
+        if (tap < p.KK) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                int h = h0, w = w0 + j;
+                if (w >= p.W) { w -= p.W; ++h; }     // W >= 8: a window wraps once at most
+                const bool ok = h + dr >= 0 && h + dr < p.H && w + dq >= 0 && w + dq < p.W;
+                m[j >> 1] |= ok ? (j & 1 ? 0xffff0000u : 0x0000ffffu) : 0u;
+            }
+        }
+        vtab[tid] = u32x4{m[0], m[1], m[2], m[3]};
+    }
+    __syncthreads();
+
+    // fetch side: lane = (row slot rs, piece c): positions nbase .. nbase + 7 of the tile
+    const int rs = lane >> 3, c = lane & 7;
+    const int nbase = n0 + c * 8;
+    const int wr_off0 = rs * PITCH + ((c ^ swizzle<CPR>(rs)) << 4);     // the swizzle does not depend on i (row i * 8 + rs)
+    // multiply side (as in the row-gathering kernel)
+    const int i16 = lane & 15, kgroup = lane >> 4, qd = i16 >> 2, m_row = i16;
+    const unsigned int below = (1u << m_row) - 1u;
+    const int ncolb = (4 * (i16 & 3)) * 2, cl = ncolb >> 4, within = ncolb & 15;
+    const int r0 = kgroup * 8 + qd, r1 = r0 + 4;
+    const int sw0 = swizzle<CPR>(r0), sw1 = swizzle<CPR>(r1);
+    const int x0 = r0 * PITCH + within, x1 = r1 * PITCH + within;
+
+    f32x4 acc[NT];
+#pragma unroll
+    for (int q = 0; q < NT; ++q) acc[q] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    const u32x4 *rows4 = reinterpret_cast<const u32x4 *>(p.rows);
+    const uint2 *desc2 = reinterpret_cast<const uint2 *>(p.desc);
+    const i16x8 *pay = reinterpret_cast<const i16x8 *>(p.payload);
+    const char *Fb = reinterpret_cast<const char *>(p.F);
+    const int HW = p.N, wstep = p.W - p.kw, nshift = nbase - (ph * p.W + pw), emax = p.total - 8;
+    for (int s = s_beg; s < s_end; s += SB) {
+        const int nb = s_end - s < SB ? s_end - s : SB;
+        u32x4 hdr[SB];
+        uint2 dsc[SB];
+#pragma unroll
+        for (int u = 0; u < SB; ++u) {
+            const int st = s + (u < nb ? u : nb - 1);
+            hdr[u] = rows4[(int64_t)st * 8 + rs];
+            dsc[u] = desc2[(int64_t)st * 4 + kgroup];
+        }
+        u32x4 RX[SB][4];
+        unsigned int vsel[SB];                   // per step, 8 bits per window: which validity mask goes with it (the tap; KK: padding)
+        i16x8 PW[SB];
+        // element index of the window of k slot `k` for this lane, and the tap it belongs to
+        // (24-bit multiplies: Cin, H * W, W and the tap numbers are all below 2^24)
+        auto window = [&](unsigned int k, int &tap) {
+            const unsigned int cin = __umulhi(k << 1, (unsigned int)p.kk_magic);
+            tap = (int)(k - __umul24(cin, (unsigned int)p.KK));
+            const unsigned int r = __umul24((unsigned int)tap, (unsigned int)p.kw_magic) >> 8;   // tap / kw
+            // r * W + (tap - r * kw), less the centre tap's offset
+            return (int)(__umul24(cin, (unsigned int)HW) + __umul24(r, (unsigned int)wstep)) + tap + nshift;
+        };
+        bool edge_any = false;
+#pragma unroll
+        for (int u = 0; u < SB; ++u) {
+            vsel[u] = 0u;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const bool is_pad = hdr[u][i] == 0xffffffffu;
+                int tap;
+                const int e0 = window(is_pad ? 0u : hdr[u][i], tap);
+                vsel[u] |= (unsigned int)(is_pad ? p.KK : tap) << (8 * i);
+                const bool edge = e0 < 0 || e0 > emax;
+                edge_any |= edge;
+                ConvWindow wv;
+                __builtin_memcpy(&wv, Fb + (unsigned int)(edge ? 0 : e0 * 2), 16);   // byte offset below 2^31
+                RX[u][i] = u32x4{wv.d[0], wv.d[1], wv.d[2], wv.d[3]};
+            }
+        }
+        if (__builtin_amdgcn_ballot_w64(edge_any)) {
+            // Rare: only where the tile touches the first or last positions of the feature map.
+            // The row numbers are fetched again, so that the common path need not keep them.
+#pragma unroll
+            for (int u = 0; u < SB; ++u) {
+                const int st = s + (u < nb ? u : nb - 1);
+                const u32x4 h2 = rows4[(int64_t)st * 8 + rs];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    int tap;
+                    const int e0 = window(h2[i] == 0xffffffffu ? 0u : h2[i], tap);
+                    if (e0 < 0 || e0 > emax) {
+                        unsigned int d[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+                        for (int j = 0; j < 8; ++j) {
+                            const int e = e0 + j;
+                            const unsigned int v = e >= 0 && e < p.total ? p.F[e] : 0u;
+                            d[j >> 1] |= v << ((j & 1) * 16);
+                        }
+                        RX[u][i] = u32x4{d[0], d[1], d[2], d[3]};
+                    }
+                }
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < SB; ++u) {
+            const bool kept = (dsc[u].x >> m_row) & 1u;
+            const unsigned int idx = dsc[u].y + (kept ? __builtin_popcount(dsc[u].x & below) : 0);
+            const i16x8 wv = pay[idx];
+            PW[u] = kept ? wv : i16x8{0, 0, 0, 0, 0, 0, 0, 0};
+        }
+#pragma unroll
+        for (int u = 0; u < SB; ++u) {
+            if (u < nb) {
+                char *b = buf + (u & 1) * 4096;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const u32x4 vm = vtab[((vsel[u] >> (8 * i)) & 0xffu) * 8 + c];
+                    const u32x4 v = {RX[u][i][0] & vm[0], RX[u][i][1] & vm[1], RX[u][i][2] & vm[2], RX[u][i][3] & vm[3]};
+                    *reinterpret_cast<u32x4 *>(b + wr_off0 + i * 8 * PITCH) = v;
+                }
+                __builtin_amdgcn_wave_barrier();
+#pragma unroll
+                for (int q = 0; q < NT; ++q) {
+                    const int cq = q * 2 + cl;
+                    const i16x4 lo = lds_tr_read(b + x0 + ((cq ^ sw0) << 4));
+                    const i16x4 hi = lds_tr_read(b + x1 + ((cq ^ sw1) << 4));
+                    const i16x8 x = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+                    acc[q] = mfma16<BF16>(x, PW[u], acc[q]);
+                }
+                __builtin_amdgcn_wave_barrier();
+            }
+        }
+    }
+
+    // the waves' partial tiles go through their step buffers; the tables behind them stay intact
+    f32x4 *red = reinterpret_cast<f32x4 *>(lds);
+#pragma unroll
+    for (int q = 0; q < NT; ++q) red[wave * 512 + q * 64 + lane] = acc[q];
+    __syncthreads();
+    const int q = wave;
+    f32x4 sum = red[q * 64 + lane];
+#pragma unroll
+    for (int w = 1; w < 4; ++w) {
+        const f32x4 v = red[w * 512 + q * 64 + lane];
+        sum[0] += v[0]; sum[1] += v[1]; sum[2] += v[2]; sum[3] += v[3];
+    }
+    const int64_t row = p.out_row[(int64_t)t * 16 + (lane & 15)];
+    const int64_t n = n0 + q * 16 + 4 * (lane >> 4);
+    if (row >= 0) {
+        float *dst = p.Y + row * p.ldy + n;
+        if (p.yvec == 4 && (n & 3) == 0) {
+            *reinterpret_cast<f32x4 *>(dst) = sum;
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) dst[e] = sum[e];
+        }
+    }
+}
+
+grim_status launch_conv_gather(const grim_bcr_matrix *A, const void *F, int32_t Cin, int32_t H, int32_t W, int32_t kh,
+                               int32_t kw, float *Y, int64_t ldy, hipStream_t stream) {
+    const int64_t N = (int64_t)H * W, total = (int64_t)Cin * N;
+    if (!A->gather.present || N < 64 || W < 8 || kh * kw > kConvMaxTaps || total > (int64_t(1) << 30) ||
+        A->K > (int64_t(1) << 27) || Cin >= (1 << 24) || N >= (1 << 24) || reinterpret_cast<uintptr_t>(F) % 2 != 0)
+        return GRIM_ERR_UNSUPPORTED;
+    ConvParams p;
+    p.sptr = A->gather.d_sptr;
+    p.out_row = A->gather.d_out_row;
+    p.rows = A->gather.d_rows;
+    p.desc = A->gather.d_desc;
+    p.payload = A->gather.d_payload;
+    p.F = static_cast<const unsigned short *>(F);
+    p.Y = Y;
+    p.ldy = ldy;
+    p.N = (int32_t)N; p.H = H; p.W = W; p.kh = kh; p.kw = kw;
+    p.KK = kh * kw;
+    p.kk_magic = (int32_t)(uint32_t)(((uint64_t(1) << 31) + p.KK - 1) / p.KK);
+    p.kw_magic = (256 + kw - 1) / kw;
+    p.total = (int32_t)total;
+    p.nbr = (int32_t)A->gather.nstrips;
+    p.ntiles = (int32_t)((N + 63) / 64);
+    p.yvec = (reinterpret_cast<uintptr_t>(Y) % 16 == 0 && ldy % 4 == 0 && N % 4 == 0) ? 4 : 1;
+    const int64_t nwg = ((int64_t)p.ntiles + 7) / 8 * 8 * p.nbr;
+    if (nwg > 0x7fffffff) return GRIM_ERR_SHAPE;
+    const size_t lds = kConvLdsBytes;
+    if (A->dtype == GRIM_BF16) hipLaunchKernelGGL(bcr_conv_gather<true>, dim3((unsigned)nwg), dim3(256), lds, stream, p);
+    else hipLaunchKernelGGL(bcr_conv_gather<false>, dim3((unsigned)nwg), dim3(256), lds, stream, p);
+    return hipGetLastError() == hipSuccess ? GRIM_OK : GRIM_ERR_DEVICE;
+}
+
 bool mma_supported(const grim_bcr_matrix *A) { return A->mma.present; }
 
 static int amax_of(const grim_bcr_matrix *A, int g) { return A->mma.amax[g <= 4 ? 0 : g <= 8 ? 1 : g <= 16 ? 2 : 3]; }

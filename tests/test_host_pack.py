@@ -25,7 +25,7 @@ def _pack(W, dtype, mask, **kw):
 def test_library_exports_every_declared_symbol():
     header = open(os.path.join(ROOT, "include", "grim_bcr.h")).read()
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
-    declared = set(re.findall(r"\b(grim_[a-z_]+)\s*\(", header))
+    declared = set(re.findall(r"\b(grim_[a-z0-9_]+)\s*\(", header))
     assert declared == set(binding.EXPORTS)
     lib = ctypes.CDLL(g.lib_path())
     for name in declared:
