@@ -225,6 +225,9 @@ void build_gather_layout(grim_bcr_matrix *A) {
         L.nsteps += (int64_t)nst;
     }
     L.sptr[(size_t)nss] = (int32_t)L.nsteps;
+    L.usteps = nss > 0 ? L.sptr[1] - L.sptr[0] : 0;
+    for (int64_t u = 0; u < nss && L.usteps > 0; ++u)
+        if (L.sptr[(size_t)u + 1] - L.sptr[(size_t)u] != L.usteps) L.usteps = 0;
     L.present = true;
 }
 

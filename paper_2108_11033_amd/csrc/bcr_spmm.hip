@@ -568,8 +568,18 @@ struct GatherParams {
     float *Y;
     int64_t N, ldx, ldy;
     int32_t nbr, ntiles;      // nbr: 16-row runs of the stored row order
+    int32_t usteps;           // > 0: steps of every run (sptr is not read)
     int32_t yvec;
+#ifdef GRIM_DBG
+    long long *dbg;
+#endif
 };
+
+#ifdef GRIM_DBG
+#define GATHER_STAMP(slot) do { if (p.dbg && (threadIdx.x & 63) == 0) p.dbg[((int64_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * 8 + (slot)] = (long long)__builtin_amdgcn_s_memtime(); } while (0)
+#else
+#define GATHER_STAMP(slot) do { } while (0)
+#endif
 
 template <bool BF16, bool WIDE>   // WIDE: rows of X are 16-byte aligned (else 8-byte: two loads per piece)
 __global__ void __launch_bounds__(256, 4) bcr_spmm_gather(GatherParams p) {
@@ -582,12 +592,14 @@ __global__ void __launch_bounds__(256, 4) bcr_spmm_gather(GatherParams p) {
     const int tile = (slot / p.nbr) * 8 + xcd;
     const int t = slot % p.nbr;
     if (tile >= p.ntiles) return;
+    GATHER_STAMP(0);
     int64_t n0 = (int64_t)tile * TN;
     if (n0 + TN > p.N) n0 = p.N - TN;            // ragged last tile: overlap the neighbour (N >= 64, N % 4 == 0)
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int g0 = p.sptr[t], nst = p.sptr[t + 1] - g0;
+    // one dependent memory round trip less at the start when every run has the same number of steps
+    const int g0 = p.usteps ? t * p.usteps : p.sptr[t], nst = p.usteps ? p.usteps : p.sptr[t + 1] - g0;
     const int s_beg = g0 + (int)((int64_t)nst * wave / 4), s_end = g0 + (int)((int64_t)nst * (wave + 1) / 4);
     char *buf = lds + wave * 8192;               // two step buffers of 32 rows x 128 bytes
 
@@ -612,19 +624,36 @@ __global__ void __launch_bounds__(256, 4) bcr_spmm_gather(GatherParams p) {
     f32x4 acc[NT];
 #pragma unroll
     for (int q = 0; q < NT; ++q) acc[q] = f32x4{0.f, 0.f, 0.f, 0.f};
+    const int orow = p.out_row[(int64_t)t * 16 + (lane & 15)];   // asked for now, needed at the very end
 
     const u32x4 *rows4 = reinterpret_cast<const u32x4 *>(p.rows);
     const uint2 *desc2 = reinterpret_cast<const uint2 *>(p.desc);
     const i16x8 *pay = reinterpret_cast<const i16x8 *>(p.payload);
+    // Row numbers and descriptor of the first step of the next batch are asked for together with
+    // the current batch's, so that a wave whose steps do not fit one batch (18 steps over 4 waves:
+    // 4 + 1) starts the rows of X of the next batch without another dependent round trip.
+    u32x4 nhdr = {0u, 0u, 0u, 0u};
+    uint2 ndsc = {0u, 0u};
+    if (s_beg < s_end) {
+        nhdr = rows4[(int64_t)s_beg * 8 + rs];
+        ndsc = desc2[(int64_t)s_beg * 4 + kgroup];
+    }
     for (int s = s_beg; s < s_end; s += SB) {
         const int nb = s_end - s < SB ? s_end - s : SB;
         u32x4 hdr[SB];
         uint2 dsc[SB];
+        hdr[0] = nhdr;
+        dsc[0] = ndsc;
 #pragma unroll
-        for (int u = 0; u < SB; ++u) {
+        for (int u = 1; u < SB; ++u) {
             const int st = s + (u < nb ? u : nb - 1);
             hdr[u] = rows4[(int64_t)st * 8 + rs];
             dsc[u] = desc2[(int64_t)st * 4 + kgroup];
+        }
+        {
+            const int st = s + SB < s_end ? s + SB : s_end - 1;
+            nhdr = rows4[(int64_t)st * 8 + rs];
+            ndsc = desc2[(int64_t)st * 4 + kgroup];
         }
         u32x4 RX[SB][4];
         i16x8 PW[SB];
@@ -647,6 +676,9 @@ __global__ void __launch_bounds__(256, 4) bcr_spmm_gather(GatherParams p) {
             const i16x8 wv = pay[idx];           // a block's first kept row if this lane's is not kept (zeroed below)
             PW[u] = kept ? wv : i16x8{0, 0, 0, 0, 0, 0, 0, 0};
         }
+#ifdef GRIM_DBG
+        if (s == s_beg) { GATHER_STAMP(1); if (RX[0][0][0] == 0x12345678u && PW[SB - 1][0] == 77) GATHER_STAMP(7); GATHER_STAMP(2); }
+#endif
 #pragma unroll
         for (int u = 0; u < SB; ++u) {
             if (u < nb) {
@@ -672,10 +704,12 @@ __global__ void __launch_bounds__(256, 4) bcr_spmm_gather(GatherParams p) {
 
     // add the four waves' partial tiles in wave order; wave q finishes sub-tile q.  A wave parks
     // its partial tile in its own (now idle) step buffers.
+    GATHER_STAMP(4);
     f32x4 *red = reinterpret_cast<f32x4 *>(lds);
 #pragma unroll
     for (int q = 0; q < NT; ++q) red[wave * 512 + q * 64 + lane] = acc[q];
     __syncthreads();
+    GATHER_STAMP(5);
     const int q = wave;
     f32x4 sum = red[q * 64 + lane];
 #pragma unroll
@@ -684,7 +718,7 @@ __global__ void __launch_bounds__(256, 4) bcr_spmm_gather(GatherParams p) {
         sum[0] += v[0]; sum[1] += v[1]; sum[2] += v[2]; sum[3] += v[3];
     }
     // D[n][m]: lane holds m = lane % 16, n = 4 * (lane / 16) + 0..3
-    const int64_t row = p.out_row[(int64_t)t * 16 + (lane & 15)];
+    const int64_t row = orow;
     const int64_t n = n0 + q * 16 + 4 * (lane >> 4);
     if (row >= 0) {
         float *dst = p.Y + row * p.ldy + n;
@@ -695,6 +729,7 @@ __global__ void __launch_bounds__(256, 4) bcr_spmm_gather(GatherParams p) {
             for (int e = 0; e < 4; ++e) dst[e] = sum[e];
         }
     }
+    GATHER_STAMP(6);
 }
 
 bool gather_applies(const grim_bcr_matrix *A, const void *X, int64_t N, int64_t ldx) {
@@ -726,10 +761,14 @@ grim_status launch_spmm_gather(const grim_bcr_matrix *A, const void *X, int64_t 
     p.Y = Y;
     p.N = N; p.ldx = ldx; p.ldy = ldy;
     p.nbr = (int32_t)A->gather.nstrips;
+    p.usteps = A->gather.usteps;
     p.ntiles = (int32_t)((N + 63) / 64);
     p.yvec = (reinterpret_cast<uintptr_t>(Y) % 16 == 0 && ldy % 4 == 0 && N % 4 == 0) ? 4 : 1;
     const int64_t nwg = ((int64_t)p.ntiles + 7) / 8 * 8 * p.nbr;
     if (nwg > 0x7fffffff) return GRIM_ERR_SHAPE;
+#ifdef GRIM_DBG
+    p.dbg = reinterpret_cast<long long *>(getenv("GRIM_DBG_PTR") ? strtoull(getenv("GRIM_DBG_PTR"), nullptr, 0) : 0ull);
+#endif
     const size_t lds = 4 * 8192;
     const bool wide = N % 8 == 0 && ldx % 8 == 0 && reinterpret_cast<uintptr_t>(X) % 16 == 0;
     const dim3 grid((unsigned)nwg), block(256);
@@ -774,6 +813,7 @@ struct ConvParams {
     int32_t kw_magic;            // ceil(256 / kw): tap / kw = tap * magic >> 8 for tap < 16
     int32_t total;               // elements of the feature map
     int32_t nbr, ntiles;
+    int32_t usteps;              // > 0: steps of every run (sptr is not read)
     int32_t yvec;
 };
 
@@ -799,7 +839,8 @@ __global__ void __launch_bounds__(256, 4) bcr_conv_gather(ConvParams p) {
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int g0 = p.sptr[t], nst = p.sptr[t + 1] - g0;
+    // one dependent memory round trip less at the start when every run has the same number of steps
+    const int g0 = p.usteps ? t * p.usteps : p.sptr[t], nst = p.usteps ? p.usteps : p.sptr[t + 1] - g0;
     const int s_beg = g0 + (int)((int64_t)nst * wave / 4), s_end = g0 + (int)((int64_t)nst * (wave + 1) / 4);
     char *buf = lds + wave * 8192;
     // per (tap, piece of the tile) the 16-byte validity mask of the piece's 8 positions; entry KK
@@ -987,6 +1028,7 @@ grim_status launch_conv_gather(const grim_bcr_matrix *A, const void *F, int32_t 
     p.kw_magic = (256 + kw - 1) / kw;
     p.total = (int32_t)total;
     p.nbr = (int32_t)A->gather.nstrips;
+    p.usteps = A->gather.usteps;
     p.ntiles = (int32_t)((N + 63) / 64);
     p.yvec = (reinterpret_cast<uintptr_t>(Y) % 16 == 0 && ldy % 4 == 0 && N % 4 == 0) ? 4 : 1;
     const int64_t nwg = ((int64_t)p.ntiles + 7) / 8 * 8 * p.nbr;
