@@ -215,6 +215,27 @@ def main() -> int:
             tL, _ = time_launches(torch, lstm, 1000, 50)
             extra[f"c3_b{batch}"]["lstm_step_us"] = tL * 1e6
             del G, mats
+        # ---- a GRU layer of the paper's size (Section 5: hidden 1024, both gate matrices 3072 x 1024, pruned 10x,
+        #      32 x 32 blocks): one step = two products + the cell, at batch 1, 8 and 32 (the paper quotes batch 32)
+        from paper_2108_11033_amd import tune
+        Hg = 1024
+        Wgi, _, mgi = tune.synthesize(3 * Hg, Hg, 1, 32, 32, 10.0, "f16", seed=1)
+        Wgh, _, mgh = tune.synthesize(3 * Hg, Hg, 1, 32, 32, 10.0, "f16", seed=2)
+        Agi = g.pack(Wgi, "f16", 32, 32, mgi.row_ptr, mgi.row_idx, mgi.col_ptr, mgi.col_idx)
+        Agh = g.pack(Wgh, "f16", 32, 32, mgh.row_ptr, mgh.row_idx, mgh.col_ptr, mgh.col_idx)
+        gru = {}
+        for batch in (1, 8, 32):
+            xg = dev_tensor(gen.normal_activations(Hg, batch, "f16", seed=9), "f16")
+            hb = torch.zeros((Hg, batch), dtype=torch.float16, device=dev)
+            h32 = torch.zeros((Hg, batch), dtype=torch.float32, device=dev)
+            gi_ = torch.empty((3 * Hg, batch), dtype=torch.float32, device=dev)
+            gh_ = torch.empty((3 * Hg, batch), dtype=torch.float32, device=dev)
+            tG, _ = time_launches(torch, lambda i: g.gru_step(Agi, Agh, xg, batch, hb, batch, batch, gi_, batch, gh_, batch,
+                                                              None, None, h32, batch, hb, batch, stream), 500, 50)
+            gru[f"b{batch}_step_us"] = tG * 1e6
+        gru["kernel_b32"] = g.spmm_kernel_name(Agi, xg, 32, 32)
+        extra["gru_1024"] = gru
+        del Agi, Agh
         # ---- c5: large non-uniform bf16 SpMM
         w5 = gen.c5_nonuniform()
         A5 = pack(w5)

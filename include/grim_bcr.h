@@ -225,6 +225,34 @@ grim_status grim_bcr_lstm_step(const grim_bcr_matrix *A, const void *xh_dev, int
                                void *h_dev, int64_t ldh, float *h32_dev, int64_t ldh32, void *hip_stream);
 
 /*
+ * GRU cell around the gate products (Section 5 evaluates a two-layer GRU; its layers are the
+ * matrix-vector products of Section 3.1).  Two BCR matrices of 3H rows each, W_i (3H x I) and
+ * W_h (3H x H), gate rows stacked reset, update, candidate; gi = W_i x and gh = W_h h come from
+ * grim_bcr_spmv / grim_bcr_spmm, grim_gru_cell is the elementwise rest (the standard GRU with the
+ * reset gate applied to the hidden-side candidate product; the paper does not restate the cell):
+ *     r = sigmoid(gi_r + bi_r + gh_r + bh_r)      z = sigmoid(gi_z + bi_z + gh_z + bh_z)
+ *     n = tanh(gi_n + bi_n + r * (gh_n + bh_n))   h <- (1 - z) * n + z * h
+ *   gi_dev, gh_dev   3H x batch fp32 (ldgi, ldgh >= batch)
+ *   bias_i_dev, bias_h_dev   3H fp32 each, or NULL
+ *   h32_dev   H x batch fp32 (ldh32): the state, read and overwritten
+ *   h_dev     optional copy of the new state in element type dt (ldh): what the next step's
+ *             hidden-side product reads.  May be NULL.
+ * grim_bcr_gru_step = the two products (x_dev: I x batch, hin_dev: H x batch, both of the matrices'
+ * element type; any batch >= 1: up to 8 columns run on the SpMV kernels, more on the SpMM kernels)
+ * into gi_dev and gh_dev, then grim_gru_cell writing hout_dev (may be hin_dev itself: the cell runs
+ * after both products).  Both only enqueue work on hip_stream.  Errors: NULL, SHAPE (rows not 3H on
+ * both, Ah->K != H, batch < 1, leading dimension too small), DTYPE (element types differ), DEVICE,
+ * UNSUPPORTED (as the products).
+ */
+grim_status grim_gru_cell(const float *gi_dev, int64_t ldgi, const float *gh_dev, int64_t ldgh,
+                          const float *bias_i_dev, const float *bias_h_dev, float *h32_dev, int64_t ldh32,
+                          void *h_dev, grim_dtype dt, int64_t ldh, int64_t H, int32_t batch, void *hip_stream);
+grim_status grim_bcr_gru_step(const grim_bcr_matrix *Ai, const grim_bcr_matrix *Ah, const void *x_dev, int64_t ldx,
+                              const void *hin_dev, int64_t ldhin, int32_t batch, float *gi_dev, int64_t ldgi,
+                              float *gh_dev, int64_t ldgh, const float *bias_i_dev, const float *bias_h_dev,
+                              float *h32_dev, int64_t ldh32, void *hout_dev, int64_t ldhout, void *hip_stream);
+
+/*
  * BCRC export (Section 4.3, "Compact Model Storage"): the paper's six-array, row-level form of the
  * same pruned matrix.  Rows of the whole matrix are reordered so that rows with the same set of
  * kept (global) columns are adjacent -- groups in order of the first original row that shows the

@@ -57,7 +57,7 @@ class BcrcView(ctypes.Structure):
 EXPORTS = ["grim_bcr_pack", "grim_bcr_unpack", "grim_bcr_arrays", "grim_bcr_spmm", "grim_bcr_spmm_tuned",
            "grim_bcr_spmv", "grim_bcr_group_create", "grim_bcr_spmv_batched", "grim_bcr_group_free",
            "grim_bcr_free", "grim_status_str", "grim_bcr_spmm_kernel_name",
-           "grim_bcr_export_bcrc", "grim_bcrc_arrays", "grim_bcrc_free", "grim_lstm_cell", "grim_bcr_lstm_step",
+           "grim_bcr_export_bcrc", "grim_bcrc_arrays", "grim_bcrc_free", "grim_lstm_cell", "grim_bcr_lstm_step", "grim_gru_cell", "grim_bcr_gru_step",
            "grim_bcr_conv2d"]
 
 
@@ -100,6 +100,8 @@ def load_library():
     lib.grim_bcr_conv2d.argtypes = [p, p, i32, i32, i32, i32, i32, p, i64, p]
     lib.grim_lstm_cell.argtypes = [p, i64, p, p, i64, p, i32, i64, p, i64, i64, i32, p]
     lib.grim_bcr_lstm_step.argtypes = [p, p, i32, i64, p, i64, p, p, i64, p, i64, p, i64, p]
+    lib.grim_gru_cell.argtypes = [p, i64, p, i64, p, p, p, i64, p, i32, i64, i64, i32, p]
+    lib.grim_bcr_gru_step.argtypes = [p, p, p, i64, p, i64, i32, p, i64, p, i64, p, p, p, i64, p, i64, p]
     lib.grim_bcr_spmm_kernel_name.argtypes = [p, p, i64, i64, i32, i32, i32]
     for name in EXPORTS:
         getattr(lib, name).restype = i32
@@ -275,6 +277,22 @@ def lstm_step(A: BcrMatrix, xh, batch: int, ldx: int, gates, ldg: int, bias, c, 
     """grim_bcr_lstm_step: gate product of [W_ih | W_hh] with [x; h], then the cell."""
     _check(A._lib.grim_bcr_lstm_step(A.handle, _addr(xh), batch, ldx, _addr(gates), ldg, _addr(bias), _addr(c), ldc,
                                      _addr(h), ldh, _addr(h32), ldh32, _stream(stream)), "grim_bcr_lstm_step")
+
+
+def gru_cell(gi, ldgi: int, gh, ldgh: int, bias_i, bias_h, h32, ldh32: int, h, dtype, ldh: int, H: int, batch: int,
+             stream=None):
+    """grim_gru_cell: enqueue the elementwise part of a GRU step (fp32 state updated in place, h written)."""
+    lib = load_library()
+    _check(lib.grim_gru_cell(_addr(gi), ldgi, _addr(gh), ldgh, _addr(bias_i), _addr(bias_h), _addr(h32), ldh32,
+                             _addr(h), _DT_CODE[dtype], ldh, H, batch, _stream(stream)), "grim_gru_cell")
+
+
+def gru_step(Ai: BcrMatrix, Ah: BcrMatrix, x, ldx: int, hin, ldhin: int, batch: int, gi, ldgi: int, gh, ldgh: int,
+             bias_i, bias_h, h32, ldh32: int, hout, ldhout: int, stream=None):
+    """grim_bcr_gru_step: the products W_i x and W_h h, then the cell."""
+    _check(Ai._lib.grim_bcr_gru_step(Ai.handle, Ah.handle, _addr(x), ldx, _addr(hin), ldhin, batch, _addr(gi), ldgi,
+                                     _addr(gh), ldgh, _addr(bias_i), _addr(bias_h), _addr(h32), ldh32, _addr(hout),
+                                     ldhout, _stream(stream)), "grim_bcr_gru_step")
 
 
 def export_bcrc(A: BcrMatrix) -> dict:

@@ -183,4 +183,7 @@ grim_status launch_spmv(const GemvDesc *table_dev_or_null, const GemvDesc &singl
 grim_status launch_lstm_cell(const float *gates, int64_t ldg, const float *bias, float *c, int64_t ldc, void *h,
                              int32_t dtype, int64_t ldh, float *h32, int64_t ldh32, int64_t H, int32_t batch,
                              hipStream_t stream);
+grim_status launch_gru_cell(const float *gi, int64_t ldgi, const float *gh, int64_t ldgh, const float *bias_i,
+                            const float *bias_h, float *h32, int64_t ldh32, void *h, int32_t dtype, int64_t ldh,
+                            int64_t H, int32_t batch, hipStream_t stream);
 }  // namespace grim

@@ -698,6 +698,34 @@ grim_status grim_bcr_lstm_step(const grim_bcr_matrix *A, const void *xh_dev, int
                           hip_stream);
 }
 
+grim_status grim_gru_cell(const float *gi_dev, int64_t ldgi, const float *gh_dev, int64_t ldgh, const float *bias_i_dev,
+                          const float *bias_h_dev, float *h32_dev, int64_t ldh32, void *h_dev, grim_dtype dt, int64_t ldh,
+                          int64_t H, int32_t batch, void *hip_stream) {
+    if (!gi_dev || !gh_dev || !h32_dev) return GRIM_ERR_NULL;
+    if (H < 1 || batch < 1 || ldgi < batch || ldgh < batch || ldh32 < batch || (h_dev && ldh < batch)) return GRIM_ERR_SHAPE;
+    if (H > (int64_t(1) << 40) / batch) return GRIM_ERR_SHAPE;
+    if (dt != GRIM_F32 && dt != GRIM_F16 && dt != GRIM_BF16) return GRIM_ERR_DTYPE;
+    return launch_gru_cell(gi_dev, ldgi, gh_dev, ldgh, bias_i_dev, bias_h_dev, h32_dev, ldh32, h_dev, dt, ldh, H, batch,
+                           static_cast<hipStream_t>(hip_stream));
+}
+
+grim_status grim_bcr_gru_step(const grim_bcr_matrix *Ai, const grim_bcr_matrix *Ah, const void *x_dev, int64_t ldx,
+                              const void *hin_dev, int64_t ldhin, int32_t batch, float *gi_dev, int64_t ldgi,
+                              float *gh_dev, int64_t ldgh, const float *bias_i_dev, const float *bias_h_dev,
+                              float *h32_dev, int64_t ldh32, void *hout_dev, int64_t ldhout, void *hip_stream) {
+    if (!Ai || !Ah || !x_dev || !hin_dev || !gi_dev || !gh_dev || !h32_dev) return GRIM_ERR_NULL;
+    if (Ai->M != Ah->M || Ai->M % 3 != 0 || Ah->K != Ai->M / 3) return GRIM_ERR_SHAPE;
+    if (Ai->dtype != Ah->dtype) return GRIM_ERR_DTYPE;
+    const int64_t H = Ai->M / 3;
+    if (batch < 1 || ldh32 < batch || (hout_dev && ldhout < batch)) return GRIM_ERR_SHAPE;
+    grim_status st = grim_bcr_spmm(Ai, x_dev, batch, ldx, gi_dev, ldgi, hip_stream);
+    if (st != GRIM_OK) return st;
+    st = grim_bcr_spmm(Ah, hin_dev, batch, ldhin, gh_dev, ldgh, hip_stream);
+    if (st != GRIM_OK) return st;
+    return grim_gru_cell(gi_dev, ldgi, gh_dev, ldgh, bias_i_dev, bias_h_dev, h32_dev, ldh32, hout_dev, (grim_dtype)Ai->dtype,
+                         ldhout, H, batch, hip_stream);
+}
+
 grim_status grim_bcr_group_create(const grim_bcr_matrix *const *mats, int32_t count, grim_bcr_group **out) {
     if (out) *out = nullptr;
     if (!mats || !out) return GRIM_ERR_NULL;

@@ -1,4 +1,6 @@
-// LSTM cell around the gate product (Section 3.1: the gate matrices of an RNN layer are one
+// Recurrent cells around the gate products.
+//
+// LSTM cell (Section 3.1: the gate matrices of an RNN layer are one
 // matrix-vector product per time step; Section 5 evaluates RNNs end to end).
 //
 // The BCR product y = [W_ih | W_hh] * [x; h] delivers the four gate pre-activations stacked as
@@ -53,6 +55,55 @@ __global__ void __launch_bounds__(256) lstm_cell_kernel(LstmParams p) {
         else if (p.dtype == GRIM_F16) static_cast<_Float16 *>(p.h)[r * p.ldh + b] = (_Float16)h;
         else static_cast<unsigned short *>(p.h)[r * p.ldh + b] = f32_to_bf16_rne(h);
     }
+}
+
+// GRU cell (Section 5 evaluates a two-layer GRU).  Two products feed it, gi = W_i x and gh = W_h h,
+// each with its gate rows stacked reset, update, candidate; the reset gate scales the hidden-side
+// candidate product, which is why the two cannot be one product of a stacked matrix:
+//     r = sigmoid(gi_r + bi_r + gh_r + bh_r)        z = sigmoid(gi_z + bi_z + gh_z + bh_z)
+//     n = tanh(gi_n + bi_n + r * (gh_n + bh_n))     h' = (1 - z) * n + z * h
+// The state h stays fp32 and is updated in place; h' is also written in the matrix's element type,
+// the form the next step's hidden-side product reads.
+struct GruParams {
+    const float *gi, *gh;
+    const float *bias_i, *bias_h;
+    float *h32;
+    void *h;
+    int64_t ldgi, ldgh, ldh32, ldh, H;
+    int32_t batch, dtype;
+};
+
+__global__ void __launch_bounds__(256) gru_cell_kernel(GruParams p) {
+    const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (e >= p.H * p.batch) return;
+    const int64_t j = e / p.batch;
+    const int b = (int)(e - j * p.batch);
+    float pi[3], ph[3];
+#pragma unroll
+    for (int k = 0; k < 3; ++k) {
+        pi[k] = p.gi[(k * p.H + j) * p.ldgi + b] + (p.bias_i ? p.bias_i[k * p.H + j] : 0.f);
+        ph[k] = p.gh[(k * p.H + j) * p.ldgh + b] + (p.bias_h ? p.bias_h[k * p.H + j] : 0.f);
+    }
+    const float r = sigmoidf_(pi[0] + ph[0]);
+    const float z = sigmoidf_(pi[1] + ph[1]);
+    const float n = tanhf(pi[2] + r * ph[2]);
+    const float h = (1.0f - z) * n + z * p.h32[j * p.ldh32 + b];
+    p.h32[j * p.ldh32 + b] = h;
+    if (p.h) {
+        if (p.dtype == GRIM_F32) static_cast<float *>(p.h)[j * p.ldh + b] = h;
+        else if (p.dtype == GRIM_F16) static_cast<_Float16 *>(p.h)[j * p.ldh + b] = (_Float16)h;
+        else static_cast<unsigned short *>(p.h)[j * p.ldh + b] = f32_to_bf16_rne(h);
+    }
+}
+
+grim_status launch_gru_cell(const float *gi, int64_t ldgi, const float *gh, int64_t ldgh, const float *bias_i,
+                            const float *bias_h, float *h32, int64_t ldh32, void *h, int32_t dtype, int64_t ldh,
+                            int64_t H, int32_t batch, hipStream_t stream) {
+    GruParams p{gi, gh, bias_i, bias_h, h32, h, ldgi, ldgh, ldh32, ldh, H, batch, dtype};
+    const int64_t nwg = (H * batch + 255) / 256;
+    if (nwg > 0x7fffffff) return GRIM_ERR_SHAPE;
+    hipLaunchKernelGGL(gru_cell_kernel, dim3((unsigned)nwg), dim3(256), 0, stream, p);
+    return hipGetLastError() == hipSuccess ? GRIM_OK : GRIM_ERR_DEVICE;
 }
 
 grim_status launch_lstm_cell(const float *gates, int64_t ldg, const float *bias, float *c, int64_t ldc, void *h,
