@@ -294,10 +294,22 @@ def main() -> int:
         tc, _ = time_launches(torch, lambda i: g.conv2d(A, Fs[i % sets], Cin, Hc, Wc, 3, 3, Ys[i % sets], wl.N, stream),
                               args.steps, args.warmup)
         cbytes = abytes - wl.K * wl.N * 2 + Cin * Hc * Wc * 2
+        # context: what forming the matrix costs with the library routine of the framework that owns the buffers
+        unfold = lambda i: torch.nn.functional.unfold(Fs[i % sets].view(1, Cin, Hc, Wc), 3, padding=1)
+        tu, _ = time_launches(torch, unfold, 100, 10)
         out["conv"] = {"workload": "c2's weights on a 256 x 56 x 56 fp16 feature map, 3x3, zero padding 1",
                        "us": tc * 1e6, "useful_tflops": flops / tc / 1e12, "algorithmic_mb": cbytes / 1e6,
                        "gbs": cbytes / tc / 1e9, "product_on_materialised_im2col_us": t_cold * 1e6,
-                       "im2col_matrix_mb": wl.K * wl.N * 2 / 1e6}
+                       "torch_unfold_us": tu * 1e6, "im2col_matrix_mb": wl.K * wl.N * 2 / 1e6}
+        # the same layer on a 224 x 224 map (N = 50176): the matrix would be 231 MB
+        Hb = 224
+        Fb = [dev_tensor(gen.normal_activations(Cin, Hb * Hb, wl.dtype, seed=78 + i, relu=True), wl.dtype) for i in range(2)]
+        Yb_ = [torch.empty((wl.M, Hb * Hb), dtype=torch.float32, device=dev) for _ in range(2)]
+        tcb, _ = time_launches(torch, lambda i: g.conv2d(A, Fb[i % 2], Cin, Hb, Hb, 3, 3, Yb_[i % 2], Hb * Hb, stream), 30, 3)
+        tub, _ = time_launches(torch, lambda i: torch.nn.functional.unfold(Fb[i % 2].view(1, Cin, Hb, Hb), 3, padding=1), 10, 2)
+        out["conv"]["at_224x224"] = {"us": tcb * 1e6, "useful_tflops": 2.0 * vd["nnz"] * Hb * Hb / tcb / 1e12,
+                                     "torch_unfold_us": tub * 1e6, "im2col_matrix_mb": wl.K * Hb * Hb * 2 / 1e6}
+        del Fb, Yb_
         del Fs
 
     if args.sweep:

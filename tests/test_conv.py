@@ -118,6 +118,29 @@ def test_conv_integer_data_is_exact_and_equals_the_im2col_product():
 
 
 @pytest.mark.gpu
+def test_conv_full_size_sampled():
+    """The configuration bench.py --conv times (c2's weights on a 256 x 56 x 56 map): sampled output rows against the
+    reference, every border position included, and the whole result against the product on the materialised matrix
+    (same kernel family, same summation order: bit for bit)."""
+    import torch
+    import paper_2108_11033_amd as g
+    from helpers import pack_workload, run_spmm, TOL
+    wl = gen.c2_vgg_conv(64)
+    dtype, Cin, H, W, M = wl.dtype, 256, 56, 56, wl.M
+    A = pack_workload(g, wl.W, dtype, wl.mask)
+    F = gen.normal_activations(Cin, H * W, dtype, seed=77, relu=True).reshape(Cin, H, W)
+    Y = _run(g, A, F, dtype, M, Cin, H, W, 3, 3)
+    Wm, F64 = _masked(wl.W, dtype, wl.mask), gen.storage_to_f64(F, dtype)
+    rows = np.array([0, 7, 8, 100, 129, 255])
+    Yref, S = conv_ref.conv_same(Wm[rows], F64, 3, 3), conv_ref.abs_scale(Wm[rows], F64, 3, 3)
+    assert (np.abs(Y[rows] - Yref) <= TOL[dtype] * np.maximum(S, 1e-30)).all()
+    assert np.abs(Y[rows] - Yref).max() <= TOL[dtype] * np.abs(Yref).max()
+    X = conv_ref.im2col(F, 3, 3)
+    Yx = run_spmm(g, A, X, dtype, M, H * W, kernel=3)
+    assert Yx.tobytes() == np.ascontiguousarray(Y.reshape(M, -1)).tobytes()
+
+
+@pytest.mark.gpu
 def test_conv_refusals():
     import torch
     import paper_2108_11033_amd as g
