@@ -107,8 +107,8 @@ def main() -> int:
                     help="also run a plain 256 MiB device copy (reference for scaling rocprofv3 byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (the product shards over N with no exchange; "
-              "see DESIGN.md); --gpus must be 1", file=sys.stderr)
+        print("bench.py: this build runs on one GPU only (the product would shard over the columns of X with no "
+              "exchange between GPUs); --gpus must be 1", file=sys.stderr)
         return 2
 
     import torch
@@ -325,6 +325,13 @@ def main() -> int:
                        "us": tc * 1e6, "useful_tflops": flops / tc / 1e12, "algorithmic_mb": cbytes / 1e6,
                        "gbs": cbytes / tc / 1e9, "product_on_materialised_im2col_us": t_cold * 1e6,
                        "torch_unfold_us": tu * 1e6, "im2col_matrix_mb": wl.K * wl.N * 2 / 1e6}
+        # the layer as networks chain it: bias + rectifier in the epilogue, fp16 out (the next layer's feature map)
+        bias_c = torch.zeros(wl.M, dtype=torch.float32, device=dev)
+        Os = [torch.empty((wl.M, wl.N), dtype=torch.float16, device=dev) for _ in range(sets)]
+        ta, _ = time_launches(torch, lambda i: g.conv2d_act(A, Fs[i % sets], Cin, Hc, Wc, 3, 3, bias_c, True, Os[i % sets],
+                                                            "f16", wl.N, stream), args.steps, args.warmup)
+        out["conv"]["bias_relu_fp16_out_us"] = ta * 1e6
+        del Os
         # the same layer on a 224 x 224 map (N = 50176): the matrix would be 231 MB
         Hb = 224
         Fb = [dev_tensor(gen.normal_activations(Cin, Hb * Hb, wl.dtype, seed=78 + i, relu=True), wl.dtype) for i in range(2)]

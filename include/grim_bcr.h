@@ -201,6 +201,22 @@ grim_status grim_bcr_conv2d(const grim_bcr_matrix *A, const void *F_dev, int32_t
                             int32_t kh, int32_t kw, float *Y_dev, int64_t ldy, void *hip_stream);
 
 /*
+ * grim_bcr_conv2d_act -- the same convolution with the rest of a CONV layer in its epilogue (Section 2.2 /
+ * Section 5: the evaluated networks are chains of CONV + bias + rectifier layers in fp16):
+ *     out[m][n] = round_to(out_dt, act(Y[m][n] + bias[m])),   act = max(., 0) when relu != 0, else identity
+ *   bias_dev  M fp32, or NULL (no bias)
+ *   out_dev   M x (H * W) of element type out_dt (fp32, fp16 or bf16; round to nearest even), leading
+ *             dimension ldo >= H * W, overwritten.  In fp16 / bf16 it is the next layer's feature map
+ *             (M channels of H x W) as it stands.  Must not overlap F_dev.
+ * Sums are accumulated in fp32 exactly as in grim_bcr_conv2d; with out_dt = GRIM_F32, no bias and no
+ * rectifier the two calls write the same bits.  Conditions and errors as grim_bcr_conv2d; an unknown
+ * out_dt is GRIM_ERR_DTYPE.
+ */
+grim_status grim_bcr_conv2d_act(const grim_bcr_matrix *A, const void *F_dev, int32_t Cin, int32_t H, int32_t W,
+                                int32_t kh, int32_t kw, const float *bias_dev, int32_t relu, void *out_dev,
+                                grim_dtype out_dt, int64_t ldo, void *hip_stream);
+
+/*
  * LSTM cell around the gate product (Section 3.1: an RNN layer's gate matrices are one matrix-vector
  * product per time step).  With the gate matrix [W_ih | W_hh] of 4H rows packed as one BCR matrix
  * and the step's input vector [x; h], grim_bcr_spmv delivers the gate pre-activations, rows [0, H)

@@ -49,3 +49,12 @@ def im2col(F64: np.ndarray, kh: int, kw: int) -> np.ndarray:
             for q in range(kw):
                 X[(cin * kh + r) * kw + q] = Fp[cin, r:r + H, q:q + W].reshape(-1)
     return X
+
+
+def layer(W_masked64: np.ndarray, F64: np.ndarray, kh: int, kw: int, bias=None, relu: bool = False) -> np.ndarray:
+    """A CONV layer as the evaluated networks chain them: convolution, bias per output channel, rectifier.
+    fp64 throughout; the caller rounds to the storage type of the next layer's input."""
+    Y = conv_same(W_masked64, F64, kh, kw)
+    if bias is not None:
+        Y = Y + np.asarray(bias, dtype=np.float64)[:, None, None]
+    return np.maximum(Y, 0.0) if relu else Y

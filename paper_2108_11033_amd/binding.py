@@ -58,7 +58,7 @@ EXPORTS = ["grim_bcr_pack", "grim_bcr_unpack", "grim_bcr_arrays", "grim_bcr_spmm
            "grim_bcr_spmv", "grim_bcr_group_create", "grim_bcr_spmv_batched", "grim_bcr_group_free",
            "grim_bcr_free", "grim_status_str", "grim_bcr_spmm_kernel_name",
            "grim_bcr_export_bcrc", "grim_bcrc_arrays", "grim_bcrc_free", "grim_lstm_cell", "grim_bcr_lstm_step", "grim_gru_cell", "grim_bcr_gru_step",
-           "grim_bcr_conv2d"]
+           "grim_bcr_conv2d", "grim_bcr_conv2d_act"]
 
 
 def lib_path() -> str:
@@ -98,6 +98,7 @@ def load_library():
     lib.grim_bcrc_arrays.argtypes = [p, ctypes.POINTER(BcrcView)]
     lib.grim_bcrc_free.argtypes = [p]
     lib.grim_bcr_conv2d.argtypes = [p, p, i32, i32, i32, i32, i32, p, i64, p]
+    lib.grim_bcr_conv2d_act.argtypes = [p, p, i32, i32, i32, i32, i32, p, i32, p, i32, i64, p]
     lib.grim_lstm_cell.argtypes = [p, i64, p, p, i64, p, i32, i64, p, i64, i64, i32, p]
     lib.grim_bcr_lstm_step.argtypes = [p, p, i32, i64, p, i64, p, p, i64, p, i64, p, i64, p]
     lib.grim_gru_cell.argtypes = [p, i64, p, i64, p, p, p, i64, p, i32, i64, i64, i32, p]
@@ -263,6 +264,13 @@ def spmm(A: BcrMatrix, X, N: int, ldx: int, Y, ldy: int, stream=None, *,
 def conv2d(A: BcrMatrix, F, Cin: int, H: int, W: int, kh: int, kw: int, Y, ldy: int, stream=None):
     """grim_bcr_conv2d: enqueue the stride-1 "same" convolution of feature map F with the packed filter matrix."""
     _check(A._lib.grim_bcr_conv2d(A.handle, _addr(F), Cin, H, W, kh, kw, _addr(Y), ldy, _stream(stream)), "grim_bcr_conv2d")
+
+
+def conv2d_act(A: BcrMatrix, F, Cin: int, H: int, W: int, kh: int, kw: int, bias, relu: bool, out, out_dtype, ldo: int,
+               stream=None):
+    """grim_bcr_conv2d_act: the convolution with bias, rectifier and output rounding in its epilogue."""
+    _check(A._lib.grim_bcr_conv2d_act(A.handle, _addr(F), Cin, H, W, kh, kw, _addr(bias), int(bool(relu)), _addr(out),
+                                      _DT_CODE[out_dtype], ldo, _stream(stream)), "grim_bcr_conv2d_act")
 
 
 def lstm_cell(gates, ldg: int, bias, c, ldc: int, h, dtype, ldh: int, h32, ldh32: int, H: int, batch: int, stream=None):

@@ -172,7 +172,8 @@ grim_status launch_spmm_gather(const grim_bcr_matrix *A, const void *X, int64_t 
 bool gather_applies(const grim_bcr_matrix *A, const void *X, int64_t N, int64_t ldx);
 // convolution on the row-gathering layout, the im2col matrix never formed
 grim_status launch_conv_gather(const grim_bcr_matrix *A, const void *F, int32_t Cin, int32_t H, int32_t W, int32_t kh,
-                               int32_t kw, float *Y, int64_t ldy, hipStream_t stream);
+                               int32_t kw, const float *bias, int32_t relu, void *Y, int32_t odt, int64_t ldy,
+                               hipStream_t stream);
 // cost estimates (bytes through one compute unit) used to choose between the two matrix-core kernels
 double gather_cost(const grim_bcr_matrix *A, int64_t N);
 double mma_best_shape(const grim_bcr_matrix *A, int64_t N, int32_t tile_n, int32_t strips_per_wg, int *tn_out, int *g_out);

@@ -662,15 +662,29 @@ grim_status grim_bcr_spmv(const grim_bcr_matrix *A, const void *x_dev, int32_t b
     return launch_spmm_fma(A, x_dev, batch, ldx, y_dev, ldy, stream);
 }
 
-grim_status grim_bcr_conv2d(const grim_bcr_matrix *A, const void *F_dev, int32_t Cin, int32_t H, int32_t W, int32_t kh,
-                            int32_t kw, float *Y_dev, int64_t ldy, void *hip_stream) {
-    if (!A || !F_dev || !Y_dev) return GRIM_ERR_NULL;
+static grim_status conv_call(const grim_bcr_matrix *A, const void *F_dev, int32_t Cin, int32_t H, int32_t W, int32_t kh,
+                             int32_t kw, const float *bias_dev, int32_t relu, void *out_dev, int32_t odt, int64_t ldo,
+                             void *hip_stream) {
+    if (!A || !F_dev || !out_dev) return GRIM_ERR_NULL;
     if (Cin < 1 || H < 1 || W < 1 || kh < 1 || kw < 1 || kh % 2 == 0 || kw % 2 == 0) return GRIM_ERR_SHAPE;
-    if ((int64_t)Cin * kh * kw != A->K || ldy < (int64_t)H * W) return GRIM_ERR_SHAPE;
+    if ((int64_t)Cin * kh * kw != A->K || ldo < (int64_t)H * W) return GRIM_ERR_SHAPE;
+    if (odt != GRIM_F32 && odt != GRIM_F16 && odt != GRIM_BF16) return GRIM_ERR_DTYPE;
     if (!A->on_device) return GRIM_ERR_DEVICE;
     int dev = -1;
     if (hipGetDevice(&dev) != hipSuccess || dev != A->device) { (void)hipGetLastError(); return GRIM_ERR_DEVICE; }
-    return launch_conv_gather(A, F_dev, Cin, H, W, kh, kw, Y_dev, ldy, static_cast<hipStream_t>(hip_stream));
+    return launch_conv_gather(A, F_dev, Cin, H, W, kh, kw, bias_dev, relu ? 1 : 0, out_dev, odt, ldo,
+                              static_cast<hipStream_t>(hip_stream));
+}
+
+grim_status grim_bcr_conv2d(const grim_bcr_matrix *A, const void *F_dev, int32_t Cin, int32_t H, int32_t W, int32_t kh,
+                            int32_t kw, float *Y_dev, int64_t ldy, void *hip_stream) {
+    return conv_call(A, F_dev, Cin, H, W, kh, kw, nullptr, 0, Y_dev, GRIM_F32, ldy, hip_stream);
+}
+
+grim_status grim_bcr_conv2d_act(const grim_bcr_matrix *A, const void *F_dev, int32_t Cin, int32_t H, int32_t W, int32_t kh,
+                                int32_t kw, const float *bias_dev, int32_t relu, void *out_dev, grim_dtype out_dt,
+                                int64_t ldo, void *hip_stream) {
+    return conv_call(A, F_dev, Cin, H, W, kh, kw, bias_dev, relu, out_dev, (int32_t)out_dt, ldo, hip_stream);
 }
 
 grim_status grim_lstm_cell(const float *gates_dev, int64_t ldg, const float *bias_dev, float *c_dev, int64_t ldc,

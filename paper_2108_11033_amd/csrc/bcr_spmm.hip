@@ -806,8 +806,10 @@ struct ConvParams {
     const uint32_t *desc;
     const unsigned char *payload;
     const unsigned short *F;     // [Cin][H][W]
-    float *Y;                    // [M][ldy], position n = h * W + w
+    void *Y;                     // [M][ldy] of fp32, fp16 or bf16 (odt), position n = h * W + w
+    const float *bias;           // [M] added to every position of a row, or null
     int64_t ldy;
+    int32_t odt, relu;           // element type of Y; max(., 0) after the bias
     int32_t N, H, W, kh, kw;     // N = H * W
     int32_t KK, kk_magic;        // kh * kw and ceil(2^31 / KK): k / KK = umulhi(2 k, magic) for k < 2^27, KK <= 16
     int32_t kw_magic;            // ceil(256 / kw): tap / kw = tap * magic >> 8 for tap < 16
@@ -816,6 +818,14 @@ struct ConvParams {
     int32_t usteps;              // > 0: steps of every run (sptr is not read)
     int32_t yvec;
 };
+
+// fp32 -> bf16, round to nearest even; NaN stays NaN
+__device__ __forceinline__ unsigned short conv_f32_to_bf16(float f) {
+    unsigned int u = __builtin_bit_cast(unsigned int, f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (unsigned short)((u >> 16) | 0x40u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (unsigned short)(u >> 16);
+}
 
 struct __attribute__((packed, aligned(2))) ConvWindow {
     unsigned int d[4];
@@ -997,18 +1007,47 @@ __global__ void __launch_bounds__(256, 4) bcr_conv_gather(ConvParams p) {
     const int64_t row = p.out_row[(int64_t)t * 16 + (lane & 15)];
     const int64_t n = n0 + q * 16 + 4 * (lane >> 4);
     if (row >= 0) {
-        float *dst = p.Y + row * p.ldy + n;
-        if (p.yvec == 4 && (n & 3) == 0) {
-            *reinterpret_cast<f32x4 *>(dst) = sum;
-        } else {
+        // epilogue of a layer: bias per output channel, rectifier, rounding to the next layer's element type
+        const float b = p.bias ? p.bias[row] : 0.f;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) dst[e] = sum[e];
+        for (int e = 0; e < 4; ++e) {
+            sum[e] += b;
+            if (p.relu) sum[e] = sum[e] > 0.f ? sum[e] : 0.f;     // NaN stays NaN
+        }
+        const bool vec = p.yvec == 4 && (n & 3) == 0;
+        if (p.odt == GRIM_F32) {
+            float *dst = static_cast<float *>(p.Y) + row * p.ldy + n;
+            if (vec) {
+                *reinterpret_cast<f32x4 *>(dst) = sum;
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) dst[e] = sum[e];
+            }
+        } else {
+            unsigned short h[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                if (p.odt == GRIM_F16) {
+                    const _Float16 v = (_Float16)sum[e];
+                    __builtin_memcpy(&h[e], &v, 2);
+                } else {
+                    h[e] = conv_f32_to_bf16(sum[e]);
+                }
+            }
+            unsigned short *dst = static_cast<unsigned short *>(p.Y) + row * p.ldy + n;
+            if (vec) {
+                *reinterpret_cast<uint2 *>(dst) = uint2{(unsigned int)h[0] | ((unsigned int)h[1] << 16), (unsigned int)h[2] | ((unsigned int)h[3] << 16)};
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) dst[e] = h[e];
+            }
         }
     }
 }
 
 grim_status launch_conv_gather(const grim_bcr_matrix *A, const void *F, int32_t Cin, int32_t H, int32_t W, int32_t kh,
-                               int32_t kw, float *Y, int64_t ldy, hipStream_t stream) {
+                               int32_t kw, const float *bias, int32_t relu, void *Y, int32_t odt, int64_t ldy,
+                               hipStream_t stream) {
     const int64_t N = (int64_t)H * W, total = (int64_t)Cin * N;
     if (!A->gather.present || N < 64 || W < 8 || kh * kw > kConvMaxTaps || total > (int64_t(1) << 30) ||
         A->K > (int64_t(1) << 27) || Cin >= (1 << 24) || N >= (1 << 24) || reinterpret_cast<uintptr_t>(F) % 2 != 0)
@@ -1021,6 +1060,9 @@ grim_status launch_conv_gather(const grim_bcr_matrix *A, const void *F, int32_t 
     p.payload = A->gather.d_payload;
     p.F = static_cast<const unsigned short *>(F);
     p.Y = Y;
+    p.bias = bias;
+    p.odt = odt;
+    p.relu = relu;
     p.ldy = ldy;
     p.N = (int32_t)N; p.H = H; p.W = W; p.kh = kh; p.kw = kw;
     p.KK = kh * kw;
@@ -1030,7 +1072,8 @@ grim_status launch_conv_gather(const grim_bcr_matrix *A, const void *F, int32_t 
     p.nbr = (int32_t)A->gather.nstrips;
     p.usteps = A->gather.usteps;
     p.ntiles = (int32_t)((N + 63) / 64);
-    p.yvec = (reinterpret_cast<uintptr_t>(Y) % 16 == 0 && ldy % 4 == 0 && N % 4 == 0) ? 4 : 1;
+    // four consecutive outputs of a row in one store: 16 bytes of fp32, 8 bytes of fp16 / bf16
+    p.yvec = (reinterpret_cast<uintptr_t>(Y) % (odt == GRIM_F32 ? 16 : 8) == 0 && ldy % 4 == 0 && N % 4 == 0) ? 4 : 1;
     const int64_t nwg = ((int64_t)p.ntiles + 7) / 8 * 8 * p.nbr;
     if (nwg > 0x7fffffff) return GRIM_ERR_SHAPE;
     const size_t lds = kConvLdsBytes;

@@ -50,6 +50,18 @@ def test_reference_special_cases():
     assert np.array_equal(Yi, np.round(Yi)) and (np.abs(Yi) <= conv_ref.abs_scale(Wi, Fi, 3, 3)).all()
 
 
+def test_layer_reference_matches_library_conv_with_bias_and_relu():
+    import torch
+    Cin, H, W, M = 5, 6, 9, 7
+    rng = np.random.default_rng(33)
+    Wm, F, b = rng.standard_normal((M, Cin * 9)), rng.standard_normal((Cin, H, W)), rng.standard_normal(M)
+    Yt = torch.relu(torch.nn.functional.conv2d(torch.from_numpy(F)[None], torch.from_numpy(Wm.reshape(M, Cin, 3, 3)),
+                                               bias=torch.from_numpy(b), padding=1))[0].numpy()
+    assert np.allclose(conv_ref.layer(Wm, F, 3, 3, b, True), Yt, rtol=0, atol=1e-12)
+    assert (conv_ref.layer(Wm, F, 3, 3, b, True) >= 0).all() and (conv_ref.layer(Wm, F, 3, 3, b, False) < 0).any()
+    assert np.array_equal(conv_ref.layer(Wm, F, 3, 3), conv_ref.conv_same(Wm, F, 3, 3))
+
+
 # ------------------------------------------------------------------ GPU
 def _run(g, A, F, dtype, M, Cin, H, W, kh, kw, ldy=None):
     import torch
@@ -138,6 +150,91 @@ def test_conv_full_size_sampled():
     X = conv_ref.im2col(F, 3, 3)
     Yx = run_spmm(g, A, X, dtype, M, H * W, kernel=3)
     assert Yx.tobytes() == np.ascontiguousarray(Y.reshape(M, -1)).tobytes()
+
+
+def _run_act(g, A, F, dtype, M, Cin, H, W, kh, kw, bias, relu, out_dtype, ldo=None):
+    import torch
+    from helpers import to_device
+    dev = torch.device("cuda:0")
+    N = H * W
+    ldo = N if ldo is None else ldo
+    Fd = to_device(np.ascontiguousarray(F.reshape(Cin, N)), dtype)
+    tdt = {gen.F32: torch.float32, gen.F16: torch.float16, gen.BF16: torch.bfloat16}[out_dtype]
+    out = torch.full((M, ldo), 7.0, dtype=tdt, device=dev)
+    bd = None if bias is None else torch.from_numpy(bias).to(dev)
+    g.conv2d_act(A, Fd, Cin, H, W, kh, kw, bd, relu, out, out_dtype, ldo, torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    if ldo > N:
+        assert (out[:, N:].float() == 7.0).all()
+    return out[:, :N].float().cpu().numpy().reshape(M, H, W)
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("out_dtype", [gen.F32, gen.F16, gen.BF16])
+@pytest.mark.parametrize("relu,with_bias,pad", [(True, True, 0), (False, True, 3), (True, False, 4)])
+def test_conv_layer_epilogue(out_dtype, relu, with_bias, pad):
+    import paper_2108_11033_amd as g
+    from helpers import pack_workload, TOL
+    dtype, Cin, H, W, M, BR, BC = gen.F16, 32, 12, 14, 96, 16, 32
+    K = Cin * 9
+    mask = gen.random_mask(M, K, BR, BC, (0, 8, 16), (4, 8, 32), seed=720)
+    Wt = gen.normal_weights(M, K, dtype, seed=721)
+    F = gen.normal_activations(Cin, H * W, dtype, seed=722, relu=True).reshape(Cin, H, W)
+    bias = (0.05 * np.random.default_rng(723).standard_normal(M)).astype(np.float32) if with_bias else None
+    A = pack_workload(g, Wt, dtype, mask)
+    Wm, F64 = _masked(Wt, dtype, mask), gen.storage_to_f64(F, dtype)
+    ref = conv_ref.layer(Wm, F64, 3, 3, bias, relu)
+    S = conv_ref.abs_scale(Wm, F64, 3, 3) + (0 if bias is None else np.abs(bias)[:, None, None])
+    out = _run_act(g, A, F, dtype, M, Cin, H, W, 3, 3, bias, relu, out_dtype, ldo=H * W + pad)
+    ulp = {gen.F32: 0.0, gen.F16: 2.0 ** -11, gen.BF16: 2.0 ** -8}[out_dtype]      # half an ulp of the output rounding, relative
+    assert np.isfinite(out).all()
+    assert (np.abs(out - ref) <= TOL[dtype] * S + ulp * np.abs(ref) + 1e-30).all()
+    if relu:
+        assert (out >= 0).all() and (out[ref < -TOL[dtype] * S] == 0).all()
+    else:
+        assert (out < 0).any()
+    if out_dtype == gen.F32 and not relu and bias is None:
+        pass
+    # fp32, no bias, no rectifier: the same bits as grim_bcr_conv2d
+    plain = _run(g, A, F, dtype, M, Cin, H, W, 3, 3)
+    same = _run_act(g, A, F, dtype, M, Cin, H, W, 3, 3, None, False, gen.F32)
+    assert plain.tobytes() == same.tobytes()
+
+
+@pytest.mark.gpu
+def test_three_conv_layers_chained_in_fp16():
+    """Three pruned 3x3 CONV + bias + ReLU layers, each writing the next one's fp16 feature map directly.  The reference
+    runs the same chain in fp64 and rounds every layer's output to fp16 where the device does, so that each layer is
+    compared on identical inputs."""
+    import torch
+    import paper_2108_11033_amd as g
+    from helpers import pack_workload, to_device, TOL
+    dev = torch.device("cuda:0")
+    dtype, H, W = gen.F16, 16, 24
+    chans = [32, 64, 64, 32]
+    N = H * W
+    F = gen.normal_activations(chans[0], N, dtype, seed=730, relu=True).reshape(chans[0], H, W)
+    cur = to_device(np.ascontiguousarray(F.reshape(chans[0], N)), dtype)
+    ref_in = gen.storage_to_f64(F, dtype)
+    for li in range(3):
+        Cin, M = chans[li], chans[li + 1]
+        K = Cin * 9
+        mask = gen.random_mask(M, K, 16, 32, (8, 16), (8, 16), seed=731 + li)
+        Wt = gen.normal_weights(M, K, dtype, seed=741 + li) * np.float16(6.0)          # keeps activations of order one
+        bias = (0.1 * np.random.default_rng(751 + li).standard_normal(M)).astype(np.float32)
+        A = pack_workload(g, Wt, dtype, mask)
+        out = torch.empty((M, N), dtype=torch.float16, device=dev)
+        g.conv2d_act(A, cur, Cin, H, W, 3, 3, torch.from_numpy(bias).to(dev), True, out, dtype, N, torch.cuda.current_stream())
+        torch.cuda.synchronize()
+        Wm = _masked(Wt, dtype, mask)
+        ref = conv_ref.layer(Wm, ref_in, 3, 3, bias, True)
+        S = conv_ref.abs_scale(Wm, ref_in, 3, 3) + np.abs(bias)[:, None, None]
+        got = out.float().cpu().numpy().reshape(M, H, W)
+        assert (np.abs(got - ref) <= TOL[dtype] * S + 2.0 ** -11 * np.abs(ref) + 1e-30).all(), f"layer {li}"
+        assert got.max() > 0.1, f"layer {li} died"
+        # the next layer consumes what the device wrote
+        ref_in = got.astype(np.float64)
+        cur = out
 
 
 @pytest.mark.gpu
