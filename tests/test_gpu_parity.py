@@ -252,6 +252,25 @@ def test_spmv_falls_back_when_blocks_exceed_masks(g):
     assert_close(run_spmv(g, A, x, dtype, M, 2), yref, S, dtype, "spmv 64x64 blocks")
 
 
+# ------------------------------------------------------------------ staged kernel: more tiles than compute units
+@pytest.mark.parametrize("dtype,BR", [(gen.F16, 16), (gen.BF16, 32)])
+@pytest.mark.parametrize("N,tile_n,strips", [(9004, 32, 4), (17000, 64, 4), (17001, 64, 8), (9004, 32, 8)])
+def test_staged_kernel_more_tiles_than_compute_units(g, dtype, BR, N, tile_n, strips):
+    """More workgroups than the GPU holds at once (256 compute units), so that workgroups start while others are
+    still running: odd chunk counts, one and two strip groups per tile, rows of X at every alignment, ragged ends,
+    every entry checked."""
+    M, K, BC = BR * (strips if strips == 4 else 2 * strips), 96 * 3, 32      # chunk of 96 rows -> 3 chunks per tile
+    mask = gen.random_mask(M, K, BR, BC, (0, BR // 4, BR // 2, BR), (0, 8, 11, 32), seed=320 + BR)
+    W = gen.normal_weights(M, K, dtype, seed=321)
+    X = gen.normal_activations(K, N, dtype, seed=322, relu=True)
+    A = pack_workload(g, W, dtype, mask, chunk_rows=96)
+    Yref, S = oracle_product(W, X, dtype, mask)
+    Y = run_spmm(g, A, X, dtype, M, N, kernel=2, tile_n=tile_n, strips_per_wg=strips)
+    assert_close(Y, Yref, S, dtype, f"staged {dtype} N={N} tile {tile_n} strips {strips}")
+    Y2 = run_spmm(g, A, X, dtype, M, N, kernel=2, tile_n=tile_n, strips_per_wg=strips)
+    assert Y2.tobytes() == Y.tobytes()
+
+
 # ------------------------------------------------------------------ row-gathering matrix-core kernel
 @pytest.mark.parametrize("dtype", [gen.F16, gen.BF16])
 @pytest.mark.parametrize("N,ldx_pad,ldy_pad", [(64, 0, 0), (200, 0, 0), (196, 0, 0), (328, 8, 4), (132, 4, 3)])
