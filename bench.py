@@ -258,6 +258,23 @@ def main() -> int:
                                                               None, None, h32, batch, hb, batch, stream), 500, 50)
             gru[f"b{batch}_step_us"] = tG * 1e6
         gru["kernel_b32"] = g.spmm_kernel_name(Agi, xg, 32, 32)
+        # the three GRU matrix sizes the paper counts register loads on (Section 5.3), pruned 10.7x: one product each
+        shapes = {}
+        for (Mg, Kg, BRg, BCg, krg, kcg) in ((152, 1024, 8, 32, 4, 6), (512, 1024, 32, 32, 8, 12), (1024, 1024, 32, 32, 8, 12)):
+            mk = gen.random_mask(Mg, Kg, BRg, BCg, krg, kcg, seed=40 + Mg)
+            Wg = gen.normal_weights(Mg, Kg, "f16", seed=41 + Mg)
+            Ag = g.pack(Wg, "f16", BRg, BCg, mk.row_ptr, mk.row_idx, mk.col_ptr, mk.col_idx)
+            rec = {}
+            for batch in (1, 32):
+                xg2 = dev_tensor(gen.normal_activations(Kg, batch, "f16", seed=9), "f16")
+                yg2 = torch.empty((Mg, batch), dtype=torch.float32, device=dev)
+                xa2, ya2, sh2 = int(xg2.data_ptr()), int(yg2.data_ptr()), int(stream.cuda_stream)
+                tg, _ = time_launches(torch, lambda i: g.spmm(Ag, xa2, batch, batch, ya2, batch, sh2), 500, 50)
+                rec[f"b{batch}_us"] = tg * 1e6
+                rec[f"b{batch}_kernel"] = g.spmm_kernel_name(Ag, xg2, batch, batch)
+            shapes[f"{Mg}x{Kg}"] = rec
+            del Ag
+        gru["paper_shapes"] = shapes
         extra["gru_1024"] = gru
         del Agi, Agh
         # ---- c5: large non-uniform bf16 SpMM

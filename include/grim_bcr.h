@@ -139,8 +139,8 @@ grim_status grim_bcr_spmm(const grim_bcr_matrix *A, const void *X_dev, int64_t N
  *   kernel         0 = choose, 1 = force the portable FMA kernel, 2 = force the staged matrix-core
  *                  kernel (fp16 / bf16, BR = 16 or 32; tile_n / strips_per_wg apply to it),
  *                  3 = force the row-gathering matrix-core kernel (fp16 / bf16, BR a divisor or a
- *                  multiple of 16 -- the paper's 4 x 16 blocks included --, N >= 64, N and ldx
- *                  multiples of 4, X 8-byte aligned; tile_n and strips_per_wg must be 0)
+ *                  multiple of 16 -- the paper's 4 x 16 blocks included --, N and ldx multiples of 4,
+ *                  X 8-byte aligned; tile_n and strips_per_wg must be 0)
  * Combinations that are not compiled, that the matrix or the operands do not qualify for, or whose
  * staging buffers do not fit the 160 KB of LDS for this matrix, return GRIM_ERR_UNSUPPORTED. */
 grim_status grim_bcr_spmm_tuned(const grim_bcr_matrix *A, const void *X_dev, int64_t N, int64_t ldx,

@@ -581,7 +581,8 @@ struct GatherParams {
 #define GATHER_STAMP(slot) do { } while (0)
 #endif
 
-template <bool BF16, bool WIDE>   // WIDE: rows of X are 16-byte aligned (else 8-byte: two loads per piece)
+// WIDE: rows of X are 16-byte aligned (else 8-byte: two loads per piece); NARROW: N < 64
+template <bool BF16, bool WIDE, bool NARROW>
 __global__ void __launch_bounds__(256, 4) bcr_spmm_gather(GatherParams p) {
     constexpr int NT = 4, TN = 64, PITCH = 128, CPR = 8;
     constexpr int SB = 4;                        // steps a wave has in flight
@@ -594,7 +595,8 @@ __global__ void __launch_bounds__(256, 4) bcr_spmm_gather(GatherParams p) {
     if (tile >= p.ntiles) return;
     GATHER_STAMP(0);
     int64_t n0 = (int64_t)tile * TN;
-    if (n0 + TN > p.N) n0 = p.N - TN;            // ragged last tile: overlap the neighbour (N >= 64, N % 4 == 0)
+    if (n0 + TN > p.N && p.N >= TN) n0 = p.N - TN;   // ragged last tile: overlap the neighbour (N % 4 == 0)
+    // N < 64: one tile that starts at column 0; its pieces past N are fetched from column 0 instead (never stored)
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -605,7 +607,9 @@ __global__ void __launch_bounds__(256, 4) bcr_spmm_gather(GatherParams p) {
 
     // fetch side: lane = (row slot rs, 16-byte piece c); its i-th load is k slot i * 8 + rs
     const int rs = lane >> 3, c = lane & 7;
-    const unsigned short *xcol = p.X + n0 + c * 8;
+    const bool in_a = !NARROW || c * 8 < p.N, in_b = !NARROW || c * 8 + 4 < p.N;
+    const unsigned short *xcol = p.X + n0 + (in_a ? c * 8 : 0);
+    const int boff = in_b ? 4 : 0;               // second half of a piece (8-byte aligned rows)
     int wr_off[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -667,7 +671,7 @@ __global__ void __launch_bounds__(256, 4) bcr_spmm_gather(GatherParams p) {
                     RX[u][i] = *reinterpret_cast<const u32x4 *>(src);
                 } else {
                     const uint2 a = *reinterpret_cast<const uint2 *>(src);
-                    const uint2 b = *reinterpret_cast<const uint2 *>(src + 4);
+                    const uint2 b = *reinterpret_cast<const uint2 *>(NARROW ? src + boff : src + 4);
                     RX[u][i] = u32x4{a.x, a.y, b.x, b.y};
                 }
             }
@@ -720,7 +724,7 @@ __global__ void __launch_bounds__(256, 4) bcr_spmm_gather(GatherParams p) {
     // D[n][m]: lane holds m = lane % 16, n = 4 * (lane / 16) + 0..3
     const int64_t row = orow;
     const int64_t n = n0 + q * 16 + 4 * (lane >> 4);
-    if (row >= 0) {
+    if (row >= 0 && n < p.N) {                   // n, N multiples of 4: all four columns or none
         float *dst = p.Y + row * p.ldy + n;
         if (p.yvec == 4) {
             *reinterpret_cast<f32x4 *>(dst) = sum;
@@ -733,7 +737,7 @@ __global__ void __launch_bounds__(256, 4) bcr_spmm_gather(GatherParams p) {
 }
 
 bool gather_applies(const grim_bcr_matrix *A, const void *X, int64_t N, int64_t ldx) {
-    return A->gather.present && N >= 64 && N % 4 == 0 && ldx % 4 == 0 && reinterpret_cast<uintptr_t>(X) % 8 == 0;
+    return A->gather.present && N >= 4 && N % 4 == 0 && ldx % 4 == 0 && reinterpret_cast<uintptr_t>(X) % 8 == 0;
 }
 
 // Bytes through one compute unit, the quantity both matrix-core kernels are bound by at these
@@ -772,13 +776,16 @@ grim_status launch_spmm_gather(const grim_bcr_matrix *A, const void *X, int64_t 
     const size_t lds = 4 * 8192;
     const bool wide = N % 8 == 0 && ldx % 8 == 0 && reinterpret_cast<uintptr_t>(X) % 16 == 0;
     const dim3 grid((unsigned)nwg), block(256);
+    const bool narrow = N < 64;
+#define GRIM_GATHER(BF, WD, NR) hipLaunchKernelGGL((bcr_spmm_gather<BF, WD, NR>), grid, block, lds, stream, p)
     if (A->dtype == GRIM_BF16) {
-        if (wide) hipLaunchKernelGGL((bcr_spmm_gather<true, true>), grid, block, lds, stream, p);
-        else hipLaunchKernelGGL((bcr_spmm_gather<true, false>), grid, block, lds, stream, p);
+        if (narrow) { if (wide) GRIM_GATHER(true, true, true); else GRIM_GATHER(true, false, true); }
+        else { if (wide) GRIM_GATHER(true, true, false); else GRIM_GATHER(true, false, false); }
     } else {
-        if (wide) hipLaunchKernelGGL((bcr_spmm_gather<false, true>), grid, block, lds, stream, p);
-        else hipLaunchKernelGGL((bcr_spmm_gather<false, false>), grid, block, lds, stream, p);
+        if (narrow) { if (wide) GRIM_GATHER(false, true, true); else GRIM_GATHER(false, false, true); }
+        else { if (wide) GRIM_GATHER(false, true, false); else GRIM_GATHER(false, false, false); }
     }
+#undef GRIM_GATHER
     return hipGetLastError() == hipSuccess ? GRIM_OK : GRIM_ERR_DEVICE;
 }
 

@@ -273,9 +273,11 @@ def test_staged_kernel_more_tiles_than_compute_units(g, dtype, BR, N, tile_n, st
 
 # ------------------------------------------------------------------ row-gathering matrix-core kernel
 @pytest.mark.parametrize("dtype", [gen.F16, gen.BF16])
-@pytest.mark.parametrize("N,ldx_pad,ldy_pad", [(64, 0, 0), (200, 0, 0), (196, 0, 0), (328, 8, 4), (132, 4, 3)])
+@pytest.mark.parametrize("N,ldx_pad,ldy_pad", [(64, 0, 0), (200, 0, 0), (196, 0, 0), (328, 8, 4), (132, 4, 3),
+                                               (4, 0, 0), (8, 0, 1), (12, 0, 0), (32, 0, 0), (36, 4, 0), (60, 0, 2)])
 def test_gather_kernel_shapes(g, dtype, N, ldx_pad, ldy_pad):
-    """kernel = 3 forced: tiles that overlap at the ragged end, rows of X aligned to 16 and to 8 bytes,
+    """kernel = 3 forced: tiles that overlap at the ragged end, fewer than 64 columns (one tile, the pieces past N
+    never fetched past the end of X nor stored), rows of X aligned to 16 and to 8 bytes,
     padded leading dimensions (Y with a stride that rules out 16-byte stores), non-uniform blocks with
     empty ones, strips with fewer steps than waves, an all-empty strip."""
     M, K, BR, BC = 16 * 9, 32 * 23, 16, 32
@@ -308,7 +310,7 @@ def test_gather_kernel_c2_and_refusals(g):
     Y = run_spmm(g, A, wl.X, wl.dtype, wl.M, wl.N, kernel=3)
     assert_close(Y, Yref, S, wl.dtype, "gather c2")
     from paper_2108_11033_amd.binding import GrimError
-    for N in (8, 63, 66, 201):                                   # too narrow / rows not 8-byte aligned
+    for N in (2, 63, 66, 201):                                   # rows not 8-byte aligned
         X = gen.normal_activations(wl.K, N, wl.dtype, seed=303)
         with pytest.raises(GrimError) as e:
             run_spmm(g, A, X, wl.dtype, wl.M, N, kernel=3)
