@@ -658,8 +658,8 @@ grim_status grim_bcr_spmv(const grim_bcr_matrix *A, const void *x_dev, int32_t b
         return launch_spmv(nullptr, d, 1, A->M, A->K, A->BR, A->BC, A->dtype, A->gemv.uniform_kr, A->gemv.uniform_kc,
                            A->gemv.vec, A->gemv.krmax, A->gemv.kcmax, x_dev, 0, batch, ldx, y_dev, 0, ldy, stream);
     }
-    if (A->BR > 64) return GRIM_ERR_UNSUPPORTED;
-    return launch_spmm_fma(A, x_dev, batch, ldx, y_dev, ldy, stream);
+    // blocks the SpMV kernels do not take (more than 32 rows or columns): whatever the SpMM entry point picks
+    return grim_bcr_spmm_tuned(A, x_dev, batch, ldx, y_dev, ldy, 0, 0, 0, hip_stream);
 }
 
 static grim_status conv_call(const grim_bcr_matrix *A, const void *F_dev, int32_t Cin, int32_t H, int32_t W, int32_t kh,

@@ -250,6 +250,12 @@ def test_spmv_falls_back_when_blocks_exceed_masks(g):
     A = pack_workload(g, W, dtype, mask)
     yref, S = oracle_product(W, x, dtype, mask)
     assert_close(run_spmv(g, A, x, dtype, M, 2), yref, S, dtype, "spmv 64x64 blocks")
+    # batches the row-gathering kernel takes (multiples of 4) go there, the rest to the vector-ALU kernel
+    for batch in (4, 8, 5):
+        xb = gen.normal_activations(K, batch, dtype, seed=153 + batch)
+        yref, S = oracle_product(W, xb, dtype, mask)
+        assert_close(run_spmv(g, A, xb, dtype, M, batch), yref, S, dtype, f"spmv 64x64 blocks, batch {batch}")
+        assert g.spmm_kernel_name(A, to_device(xb, dtype), batch, batch) == ("bcr_spmm_gather" if batch % 4 == 0 else "bcr_spmm_fma")
 
 
 # ------------------------------------------------------------------ staged kernel: more tiles than compute units
