@@ -107,8 +107,16 @@ __device__ __forceinline__ int nth_set_bit(unsigned int m, int j) {
 
 __host__ __device__ inline int gemv_xg_stride(int kcmax, int B) { return ((kcmax + 7) & ~7) * B; }
 
+typedef _Float16 gh2 __attribute__((ext_vector_type(2)));
+typedef __bf16 gb2 __attribute__((ext_vector_type(2)));
+
+// threads of a workgroup of bcr_spmv: from 2 right-hand sides on, twice as many lanes share the strip's blocks and
+// outputs (the phases are chains of dependent LDS round trips, so more waves per strip shorten them)
+__host__ __device__ constexpr int gemv_threads(int B) { return B >= 2 ? 512 : 256; }
+
 template <int DT, int B, int VEC>
-__global__ void __launch_bounds__(256, (B == 1 ? 6 : 1)) bcr_spmv(GemvParams p) {
+__global__ void __launch_bounds__(gemv_threads(B), (B == 1 ? 6 : 1)) bcr_spmv(GemvParams p) {
+    constexpr int NTH = gemv_threads(B);
     using T = typename GElem<DT>::type;
     struct __attribute__((aligned(sizeof(T) * VEC))) WVec { T v[VEC]; };
     struct __attribute__((aligned(sizeof(T) * VEC))) XVec { T v[VEC * B]; };
@@ -125,7 +133,7 @@ __global__ void __launch_bounds__(256, (B == 1 ? 6 : 1)) bcr_spmv(GemvParams p) 
     const int zero_slot = p.seg_blocks * p.krmax * B;                      // part[zero_slot] == 0
     float *red = part + ((zero_slot + 4) & ~3);                            // [nseg][BR * B]
     const int rb = p.BR * B;                                               // outputs of the strip
-    const int nseg = 256 / rb;                                             // BR <= 32 and B <= 8: rb <= 256
+    const int nseg = NTH / rb;                                             // BR <= 32 and B <= 8: rb <= 256
     T *xs = reinterpret_cast<T *>(red + ((nseg * rb + 3) & ~3));
 
     const int tid = threadIdx.x;
@@ -177,16 +185,16 @@ __global__ void __launch_bounds__(256, (B == 1 ? 6 : 1)) bcr_spmv(GemvParams p) 
         gu32x4 wreg[4], xreg[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            if (i * 256 < nvec) {                            // same for the whole workgroup
-                int v = tid + i * 256;
+            if (i * NTH < nvec) {                            // same for the whole workgroup
+                int v = tid + i * NTH;
                 v = v < nvec ? v : nvec - 1;                 // clamp: the duplicates are never stored
                 wreg[i] = *reinterpret_cast<const GRIM_GLOBAL gu32x4 *>(W + a0 + (size_t)v * 16);
             }
         }
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            if (i * 256 < nxv) {
-                int v = tid + i * 256;
+            if (i * NTH < nxv) {
+                int v = tid + i * NTH;
                 v = v < nxv ? v : nxv - 1;
                 xreg[i] = xsrc[v];
             }
@@ -197,20 +205,20 @@ __global__ void __launch_bounds__(256, (B == 1 ? 6 : 1)) bcr_spmv(GemvParams p) 
         if (tid <= nb) wof[tid] = wo - wstart;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const int v = tid + i * 256;
+            const int v = tid + i * NTH;
             if (v < nvec) *reinterpret_cast<gu32x4 *>(wl + (size_t)v * 16) = wreg[i];
         }
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const int v = tid + i * 256;
+            const int v = tid + i * NTH;
             if (v < nxv) reinterpret_cast<gu32x4 *>(xs)[v] = xreg[i];
         }
-        for (int v = tid + 1024; v < nvec; v += 256)
+        for (int v = tid + 4 * NTH; v < nvec; v += NTH)
             *reinterpret_cast<gu32x4 *>(wl + (size_t)v * 16) = *reinterpret_cast<const GRIM_GLOBAL gu32x4 *>(W + a0 + (size_t)v * 16);
-        for (int v = tid + 1024; v < nxv; v += 256) reinterpret_cast<gu32x4 *>(xs)[v] = xsrc[v];
+        for (int v = tid + 4 * NTH; v < nxv; v += NTH) reinterpret_cast<gu32x4 *>(xs)[v] = xsrc[v];
         if (c0 == 0 && !p.xvec16) {
             // x with a leading dimension or unaligned: element by element, layout [k][b]
-            for (int e = tid; e < p.K * B; e += 256) xs[e] = x[(int64_t)(e / B) * p.ldx + (e % B)];
+            for (int e = tid; e < p.K * B; e += NTH) xs[e] = x[(int64_t)(e / B) * p.ldx + (e % B)];
         }
         GEMV_STAMP(2);
         __syncthreads();
@@ -220,7 +228,7 @@ __global__ void __launch_bounds__(256, (B == 1 ? 6 : 1)) bcr_spmv(GemvParams p) 
         //         wave, whose LDS operations complete in order, so no workgroup barrier is needed
         //         before the rows read the gathered values.  Then lane -> compact row: dot product.
         const T *wbase = reinterpret_cast<const T *>(wl + (bstart - a0));
-        const int slots = 256 >> p.lpb_shift;
+        const int slots = NTH >> p.lpb_shift;
         const int li = tid & (lpb - 1);
         for (int s = tid >> p.lpb_shift; s < nb; s += slots) {
             const unsigned int cm = cmask[s];
@@ -323,8 +331,6 @@ __host__ __device__ constexpr int exact_region_vectors(int nv) {
     return 64 * nv + (exact_pad_period(nv) ? 64 / exact_pad_period(nv) : 0);
 }
 
-typedef _Float16 gh2 __attribute__((ext_vector_type(2)));
-typedef __bf16 gb2 __attribute__((ext_vector_type(2)));
 
 template <int DT, int KR, int KC>
 __global__ void __launch_bounds__(256) bcr_spmv_wave_exact(GemvParams p) {
@@ -891,7 +897,7 @@ static grim_status launch_vec(const GemvParams &p, int vec, dim3 grid, size_t ld
             }                                                                                                 \
             attr_done = true;                                                                                 \
         }                                                                                                     \
-        hipLaunchKernelGGL(kern, grid, dim3(256), lds, stream, p);                                            \
+        hipLaunchKernelGGL(kern, grid, dim3(gemv_threads(B)), lds, stream, p);                                \
         return hipGetLastError() == hipSuccess ? GRIM_OK : GRIM_ERR_DEVICE;                                   \
     }
     if (vec >= 8 && sizeof(typename GElem<DT>::type) == 2) GRIM_GEMV(8)
@@ -1013,7 +1019,7 @@ grim_status launch_spmv(const GemvDesc *table, const GemvDesc &single, int32_t c
         if (st != GRIM_ERR_UNSUPPORTED) return st;
     }
     const int rb = BR * batch;
-    const int nseg = 256 / rb;
+    const int nseg = gemv_threads(batch) / rb;
     const size_t lds = (size_t)p.wbytes + 16 + 2 * kSegMax * 4 + (kSegMax + 4) * 4 +
                        (((size_t)seg * gemv_xg_stride(kcmax, batch) * esz + 15) & ~size_t(15)) +
                        (size_t)((seg * krmax * batch + 4) & ~3) * 4 + (size_t)((nseg * rb + 3) & ~3) * 4 +
