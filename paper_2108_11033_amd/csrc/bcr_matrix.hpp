@@ -66,6 +66,7 @@ struct GatherLayout {
     int64_t xrows = 0;                    // k slots that name a row of X (not padding), over all strips
     int64_t nstrips = 0;                  // 16-row runs: ceil(M / 16)
     int32_t usteps = 0;                   // > 0: every run has this many steps (the kernels then skip the sptr look-up)
+    int32_t max_steps = 0;                // most steps any run has
     std::vector<int32_t> sptr;            // [nstrips + 1] first step of each run
     std::vector<int32_t> out_row;         // [nstrips * 16] original row of every stored row (-1 past M)
     std::vector<uint32_t> rows;           // [nsteps * 32]

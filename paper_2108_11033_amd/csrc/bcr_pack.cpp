@@ -228,6 +228,8 @@ void build_gather_layout(grim_bcr_matrix *A) {
     L.usteps = nss > 0 ? L.sptr[1] - L.sptr[0] : 0;
     for (int64_t u = 0; u < nss && L.usteps > 0; ++u)
         if (L.sptr[(size_t)u + 1] - L.sptr[(size_t)u] != L.usteps) L.usteps = 0;
+    L.max_steps = 0;
+    for (int64_t u = 0; u < nss; ++u) L.max_steps = std::max<int32_t>(L.max_steps, L.sptr[(size_t)u + 1] - L.sptr[(size_t)u]);
     L.present = true;
 }
 

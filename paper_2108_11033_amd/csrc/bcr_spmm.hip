@@ -581,8 +581,10 @@ struct GatherParams {
 #define GATHER_STAMP(slot) do { } while (0)
 #endif
 
-// WIDE: rows of X are 16-byte aligned (else 8-byte: two loads per piece); NARROW: N < 64
-template <bool BF16, bool WIDE, bool NARROW>
+// WIDE: rows of X are 16-byte aligned (else 8-byte: two loads per piece); NARROW: N < 64;
+// SOLO: strips of a few steps only (a 3 x 3 layer of 64 channels has 5, a dense first layer 1) -- every wave takes a
+// (tile, strip) of its own, four consecutive strips per workgroup: no split of K, no partial tiles, no barrier
+template <bool BF16, bool WIDE, bool NARROW, bool SOLO>
 __global__ void __launch_bounds__(256, 4) bcr_spmm_gather(GatherParams p) {
     constexpr int NT = 4, TN = 64, PITCH = 128, CPR = 8;
     constexpr int SB = 4;                        // steps a wave has in flight
@@ -590,9 +592,11 @@ __global__ void __launch_bounds__(256, 4) bcr_spmm_gather(GatherParams p) {
     // workgroup -> (tile, stored strip); all strips of a tile run on the same XCD
     const int id = blockIdx.x;
     const int xcd = id & 7, slot = id >> 3;
-    const int tile = (slot / p.nbr) * 8 + xcd;
-    const int t = slot % p.nbr;
-    if (tile >= p.ntiles) return;
+    const int wave0 = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int per_tile = SOLO ? (p.nbr + 3) / 4 : p.nbr;          // workgroups per tile
+    const int tile = (slot / per_tile) * 8 + xcd;
+    const int t = SOLO ? (slot % per_tile) * 4 + wave0 : slot % per_tile;
+    if (tile >= p.ntiles || t >= p.nbr) return;                      // (SOLO has no barrier a wave could be missed at)
     GATHER_STAMP(0);
     int64_t n0 = (int64_t)tile * TN;
     if (n0 + TN > p.N && p.N >= TN) n0 = p.N - TN;   // ragged last tile: overlap the neighbour (N % 4 == 0)
@@ -602,7 +606,8 @@ __global__ void __launch_bounds__(256, 4) bcr_spmm_gather(GatherParams p) {
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     // one dependent memory round trip less at the start when every run has the same number of steps
     const int g0 = p.usteps ? t * p.usteps : p.sptr[t], nst = p.usteps ? p.usteps : p.sptr[t + 1] - g0;
-    const int s_beg = g0 + (int)((int64_t)nst * wave / 4), s_end = g0 + (int)((int64_t)nst * (wave + 1) / 4);
+    const int s_beg = SOLO ? g0 : g0 + (int)((int64_t)nst * wave / 4);
+    const int s_end = SOLO ? g0 + nst : g0 + (int)((int64_t)nst * (wave + 1) / 4);
     char *buf = lds + wave * 8192;               // two step buffers of 32 rows x 128 bytes
 
     // fetch side: lane = (row slot rs, 16-byte piece c); its i-th load is k slot i * 8 + rs
@@ -706,6 +711,27 @@ __global__ void __launch_bounds__(256, 4) bcr_spmm_gather(GatherParams p) {
         }
     }
 
+    if constexpr (SOLO) {
+        // the wave owns the whole 16 x 64 tile: D[n][m], lane holds m = lane % 16, n = 4 * (lane / 16) + 0..3 of sub-tile q
+        const int64_t row = orow;
+        if (row >= 0) {
+#pragma unroll
+            for (int q = 0; q < NT; ++q) {
+                const int64_t n = n0 + q * 16 + 4 * (lane >> 4);
+                if (n < p.N) {
+                    float *dst = p.Y + row * p.ldy + n;
+                    if (p.yvec == 4) {
+                        *reinterpret_cast<f32x4 *>(dst) = acc[q];
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) dst[e] = acc[q][e];
+                    }
+                }
+            }
+        }
+        GATHER_STAMP(6);
+        return;
+    }
     // add the four waves' partial tiles in wave order; wave q finishes sub-tile q.  A wave parks
     // its partial tile in its own (now idle) step buffers.
     GATHER_STAMP(4);
@@ -746,10 +772,11 @@ bool gather_applies(const grim_bcr_matrix *A, const void *X, int64_t N, int64_t 
 double gather_cost(const grim_bcr_matrix *A, int64_t N) {
     const GatherLayout &L = A->gather;
     const double nbr = (double)L.nstrips;
-    const double per_wg = (double)L.xrows / nbr * 128.0 +
-                          ((double)L.nsteps * 160.0 + (double)L.payload.size()) / nbr + 30e3;
+    const double per_wg = (double)L.xrows / nbr * 128.0 + ((double)L.nsteps * 160.0 + (double)L.payload.size()) / nbr;
     const double nwg = (double)((N + 63) / 64) * nbr;
-    return (nwg > 256.0 ? nwg / 256.0 : 1.0) * per_wg;
+    // the bytes go through the compute units one after the other; the start-up of a workgroup overlaps with the
+    // three others a compute unit holds
+    return (nwg > 256.0 ? nwg / 256.0 : 1.0) * per_wg + (nwg > 1024.0 ? nwg / 1024.0 : 1.0) * 30e3;
 }
 
 grim_status launch_spmm_gather(const grim_bcr_matrix *A, const void *X, int64_t N, int64_t ldx, float *Y, int64_t ldy,
@@ -768,7 +795,11 @@ grim_status launch_spmm_gather(const grim_bcr_matrix *A, const void *X, int64_t 
     p.usteps = A->gather.usteps;
     p.ntiles = (int32_t)((N + 63) / 64);
     p.yvec = (reinterpret_cast<uintptr_t>(Y) % 16 == 0 && ldy % 4 == 0 && N % 4 == 0) ? 4 : 1;
-    const int64_t nwg = ((int64_t)p.ntiles + 7) / 8 * 8 * p.nbr;
+    // strips of at most 8 steps (two batches of a wave) with enough (tile, strip) pairs to fill the GPU: wave per pair
+    const bool narrow = N < 64;
+    const bool solo = !narrow && A->gather.max_steps <= 8 && (int64_t)p.ntiles * p.nbr >= 1024;
+    const int64_t per_tile = solo ? (p.nbr + 3) / 4 : p.nbr;
+    const int64_t nwg = ((int64_t)p.ntiles + 7) / 8 * 8 * per_tile;
     if (nwg > 0x7fffffff) return GRIM_ERR_SHAPE;
 #ifdef GRIM_DBG
     p.dbg = reinterpret_cast<long long *>(getenv("GRIM_DBG_PTR") ? strtoull(getenv("GRIM_DBG_PTR"), nullptr, 0) : 0ull);
@@ -776,14 +807,15 @@ grim_status launch_spmm_gather(const grim_bcr_matrix *A, const void *X, int64_t 
     const size_t lds = 4 * 8192;
     const bool wide = N % 8 == 0 && ldx % 8 == 0 && reinterpret_cast<uintptr_t>(X) % 16 == 0;
     const dim3 grid((unsigned)nwg), block(256);
-    const bool narrow = N < 64;
-#define GRIM_GATHER(BF, WD, NR) hipLaunchKernelGGL((bcr_spmm_gather<BF, WD, NR>), grid, block, lds, stream, p)
+#define GRIM_GATHER(BF, WD, NR, SO) hipLaunchKernelGGL((bcr_spmm_gather<BF, WD, NR, SO>), grid, block, lds, stream, p)
     if (A->dtype == GRIM_BF16) {
-        if (narrow) { if (wide) GRIM_GATHER(true, true, true); else GRIM_GATHER(true, false, true); }
-        else { if (wide) GRIM_GATHER(true, true, false); else GRIM_GATHER(true, false, false); }
+        if (narrow) { if (wide) GRIM_GATHER(true, true, true, false); else GRIM_GATHER(true, false, true, false); }
+        else if (solo) { if (wide) GRIM_GATHER(true, true, false, true); else GRIM_GATHER(true, false, false, true); }
+        else { if (wide) GRIM_GATHER(true, true, false, false); else GRIM_GATHER(true, false, false, false); }
     } else {
-        if (narrow) { if (wide) GRIM_GATHER(false, true, true); else GRIM_GATHER(false, false, true); }
-        else { if (wide) GRIM_GATHER(false, true, false); else GRIM_GATHER(false, false, false); }
+        if (narrow) { if (wide) GRIM_GATHER(false, true, true, false); else GRIM_GATHER(false, false, true, false); }
+        else if (solo) { if (wide) GRIM_GATHER(false, true, false, true); else GRIM_GATHER(false, false, false, true); }
+        else { if (wide) GRIM_GATHER(false, true, false, false); else GRIM_GATHER(false, false, false, false); }
     }
 #undef GRIM_GATHER
     return hipGetLastError() == hipSuccess ? GRIM_OK : GRIM_ERR_DEVICE;
@@ -1157,7 +1189,7 @@ static grim_status launch_mma_br(MmaParams &p, const grim_bcr_matrix *A, int til
 
 // Pick the launch shape by bytes through one compute unit: a workgroup streams its tile's rows of
 // X (64-byte row pieces of a 32-column tile cost about 1.8x per byte), the records of its strips,
-// and pays a fixed start-up; workgroups beyond 256 run in rounds.  Returns the cost (< 0: no
+// and pays a fixed start-up (130 KB worth: two barriers' worth of pipeline fill); workgroups beyond 256 run in rounds.  Returns the cost (< 0: no
 // compiled shape fits); tile_n / strips_per_wg != 0 pin that knob.
 double mma_best_shape(const grim_bcr_matrix *A, int64_t N, int32_t tile_n, int32_t strips_per_wg, int *tn_out, int *g_out) {
     if (!A->mma.present) return -1.0;
@@ -1172,7 +1204,7 @@ double mma_best_shape(const grim_bcr_matrix *A, int64_t N, int32_t tile_n, int32
             const int64_t nwg = ((N + t - 1) / t) * ((A->nbr + g - 1) / g);
             const double rounds = (double)((nwg + 255) / 256);
             const double bytes = (double)A->K * t * 2 * (t == 32 ? 1.8 : 1.0) +
-                                 rec_total * (double)(g < A->nbr ? g : A->nbr) / (double)A->nbr + 100e3;
+                                 rec_total * (double)(g < A->nbr ? g : A->nbr) / (double)A->nbr + 130e3;
             const double cost = rounds * bytes;
             if (best < 0 || cost < best) { best = cost; *tn_out = t; *g_out = g; }
         }

@@ -309,6 +309,31 @@ def test_gather_kernel_shapes(g, dtype, N, ldx_pad, ldy_pad):
     assert Y2.tobytes() == Y.tobytes()
 
 
+@pytest.mark.parametrize("dtype,N", [(gen.F16, 44820), (gen.BF16, 44808)])
+def test_gather_kernel_wave_per_strip(g, dtype, N):
+    """Strips of a few steps and thousands of (tile, strip) pairs (the first layers of a CNN at full resolution): every
+    wave then takes a pair of its own.  Six strips, so the second workgroup of a tile has two idle waves; one strip keeps
+    nothing; rows of X 8- and 16-byte aligned; a ragged last tile; every entry checked."""
+    M, K, BR, BC = 96, 96, 16, 32
+    mask = gen.random_mask(M, K, BR, BC, (0, 3, 8, 16), (0, 5, 8, 32), seed=330)
+    nbc = K // BC
+    keep_r, keep_c = [], []
+    for b in range((M // BR) * nbc):
+        r = mask.row_idx[mask.row_ptr[b]:mask.row_ptr[b + 1]]
+        c = mask.col_idx[mask.col_ptr[b]:mask.col_ptr[b + 1]]
+        if b // nbc == 4:
+            r, c = r[:0], c[:0]
+        keep_r.append(r); keep_c.append(c)
+    mask = gen.mask_from_sets(M, K, BR, BC, keep_r, keep_c)
+    W = gen.normal_weights(M, K, dtype, seed=331)
+    X = gen.normal_activations(K, N, dtype, seed=332, relu=True)
+    A = pack_workload(g, W, dtype, mask)
+    Yref, S = oracle_product(W, X, dtype, mask)
+    Y = run_spmm(g, A, X, dtype, M, N, kernel=3)
+    assert_close(Y, Yref, S, dtype, f"gather, wave per strip, {dtype} N={N}")
+    assert run_spmm(g, A, X, dtype, M, N, kernel=3).tobytes() == Y.tobytes()
+
+
 def test_gather_kernel_c2_and_refusals(g):
     wl = gen.c2_vgg_conv(3136)
     A = pack_workload(g, wl.W, wl.dtype, wl.mask)
