@@ -576,7 +576,7 @@ struct GatherParams {
 };
 
 #ifdef GRIM_DBG
-#define GATHER_STAMP(slot) do { if (p.dbg && (threadIdx.x & 63) == 0) p.dbg[((int64_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * 8 + (slot)] = (long long)__builtin_amdgcn_s_memtime(); } while (0)
+#define GATHER_STAMP(slot) do { if (p.dbg && (threadIdx.x & 63) == 0 && threadIdx.x < 256) p.dbg[((int64_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * 8 + (slot)] = (long long)__builtin_amdgcn_s_memtime(); } while (0)
 #else
 #define GATHER_STAMP(slot) do { } while (0)
 #endif
@@ -584,8 +584,10 @@ struct GatherParams {
 // WIDE: rows of X are 16-byte aligned (else 8-byte: two loads per piece); NARROW: N < 64;
 // SOLO: strips of a few steps only (a 3 x 3 layer of 64 channels has 5, a dense first layer 1) -- every wave takes a
 // (tile, strip) of its own, four consecutive strips per workgroup: no split of K, no partial tiles, no barrier
-template <bool BF16, bool WIDE, bool NARROW, bool SOLO>
-__global__ void __launch_bounds__(256, 4) bcr_spmm_gather(GatherParams p) {
+// EIGHT: eight waves split a strip's steps instead of four (few workgroups, long strips: the 14 x 14 layers)
+template <bool BF16, bool WIDE, bool NARROW, bool SOLO, bool EIGHT>
+__global__ void __launch_bounds__(EIGHT ? 512 : 256, EIGHT ? 2 : 4) bcr_spmm_gather(GatherParams p) {
+    constexpr int NWV = EIGHT ? 8 : 4;          // waves of the workgroup
     constexpr int NT = 4, TN = 64, PITCH = 128, CPR = 8;
     constexpr int SB = 4;                        // steps a wave has in flight
     extern __shared__ __attribute__((aligned(16))) char lds[];
@@ -606,8 +608,8 @@ __global__ void __launch_bounds__(256, 4) bcr_spmm_gather(GatherParams p) {
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     // one dependent memory round trip less at the start when every run has the same number of steps
     const int g0 = p.usteps ? t * p.usteps : p.sptr[t], nst = p.usteps ? p.usteps : p.sptr[t + 1] - g0;
-    const int s_beg = SOLO ? g0 : g0 + (int)((int64_t)nst * wave / 4);
-    const int s_end = SOLO ? g0 + nst : g0 + (int)((int64_t)nst * (wave + 1) / 4);
+    const int s_beg = SOLO ? g0 : g0 + (int)((int64_t)nst * wave / NWV);
+    const int s_end = SOLO ? g0 + nst : g0 + (int)((int64_t)nst * (wave + 1) / NWV);
     char *buf = lds + wave * 8192;               // two step buffers of 32 rows x 128 bytes
 
     // fetch side: lane = (row slot rs, 16-byte piece c); its i-th load is k slot i * 8 + rs
@@ -732,18 +734,19 @@ __global__ void __launch_bounds__(256, 4) bcr_spmm_gather(GatherParams p) {
         GATHER_STAMP(6);
         return;
     }
-    // add the four waves' partial tiles in wave order; wave q finishes sub-tile q.  A wave parks
-    // its partial tile in its own (now idle) step buffers.
+    // add the waves' partial tiles in wave order; wave q finishes sub-tile q.  A wave parks its
+    // partial tile in its own (now idle) step buffers.
     GATHER_STAMP(4);
     f32x4 *red = reinterpret_cast<f32x4 *>(lds);
 #pragma unroll
     for (int q = 0; q < NT; ++q) red[wave * 512 + q * 64 + lane] = acc[q];
     __syncthreads();
     GATHER_STAMP(5);
+    if (EIGHT && wave >= NT) return;             // the first four waves finish the four sub-tiles
     const int q = wave;
     f32x4 sum = red[q * 64 + lane];
 #pragma unroll
-    for (int w = 1; w < 4; ++w) {
+    for (int w = 1; w < NWV; ++w) {
         const f32x4 v = red[w * 512 + q * 64 + lane];
         sum[0] += v[0]; sum[1] += v[1]; sum[2] += v[2]; sum[3] += v[3];
     }
@@ -795,28 +798,28 @@ grim_status launch_spmm_gather(const grim_bcr_matrix *A, const void *X, int64_t 
     p.usteps = A->gather.usteps;
     p.ntiles = (int32_t)((N + 63) / 64);
     p.yvec = (reinterpret_cast<uintptr_t>(Y) % 16 == 0 && ldy % 4 == 0 && N % 4 == 0) ? 4 : 1;
-    // strips of at most 8 steps (two batches of a wave) with enough (tile, strip) pairs to fill the GPU: wave per pair
+    // strips of at most 8 steps (two batches of a wave) with enough (tile, strip) pairs to fill the GPU: wave per pair;
+    // long strips and fewer workgroups than compute units: eight waves per strip
     const bool narrow = N < 64;
     const bool solo = !narrow && A->gather.max_steps <= 8 && (int64_t)p.ntiles * p.nbr >= 1024;
+    const bool eight = !narrow && !solo && A->gather.max_steps >= 16 && (int64_t)p.ntiles * p.nbr <= 256;
     const int64_t per_tile = solo ? (p.nbr + 3) / 4 : p.nbr;
     const int64_t nwg = ((int64_t)p.ntiles + 7) / 8 * 8 * per_tile;
     if (nwg > 0x7fffffff) return GRIM_ERR_SHAPE;
 #ifdef GRIM_DBG
     p.dbg = reinterpret_cast<long long *>(getenv("GRIM_DBG_PTR") ? strtoull(getenv("GRIM_DBG_PTR"), nullptr, 0) : 0ull);
 #endif
-    const size_t lds = 4 * 8192;
+    const size_t lds = (eight ? 8 : 4) * 8192;
     const bool wide = N % 8 == 0 && ldx % 8 == 0 && reinterpret_cast<uintptr_t>(X) % 16 == 0;
-    const dim3 grid((unsigned)nwg), block(256);
-#define GRIM_GATHER(BF, WD, NR, SO) hipLaunchKernelGGL((bcr_spmm_gather<BF, WD, NR, SO>), grid, block, lds, stream, p)
-    if (A->dtype == GRIM_BF16) {
-        if (narrow) { if (wide) GRIM_GATHER(true, true, true, false); else GRIM_GATHER(true, false, true, false); }
-        else if (solo) { if (wide) GRIM_GATHER(true, true, false, true); else GRIM_GATHER(true, false, false, true); }
-        else { if (wide) GRIM_GATHER(true, true, false, false); else GRIM_GATHER(true, false, false, false); }
-    } else {
-        if (narrow) { if (wide) GRIM_GATHER(false, true, true, false); else GRIM_GATHER(false, false, true, false); }
-        else if (solo) { if (wide) GRIM_GATHER(false, true, false, true); else GRIM_GATHER(false, false, false, true); }
-        else { if (wide) GRIM_GATHER(false, true, false, false); else GRIM_GATHER(false, false, false, false); }
-    }
+    const dim3 grid((unsigned)nwg), block(eight ? 512 : 256);
+#define GRIM_GATHER(BF, WD, NR, SO, EI) hipLaunchKernelGGL((bcr_spmm_gather<BF, WD, NR, SO, EI>), grid, block, lds, stream, p)
+#define GRIM_GATHER_DT(BF)                                                                                         \
+    if (narrow) { if (wide) GRIM_GATHER(BF, true, true, false, false); else GRIM_GATHER(BF, false, true, false, false); }        \
+    else if (solo) { if (wide) GRIM_GATHER(BF, true, false, true, false); else GRIM_GATHER(BF, false, false, true, false); }     \
+    else if (eight) { if (wide) GRIM_GATHER(BF, true, false, false, true); else GRIM_GATHER(BF, false, false, false, true); }    \
+    else { if (wide) GRIM_GATHER(BF, true, false, false, false); else GRIM_GATHER(BF, false, false, false, false); }
+    if (A->dtype == GRIM_BF16) { GRIM_GATHER_DT(true) } else { GRIM_GATHER_DT(false) }
+#undef GRIM_GATHER_DT
 #undef GRIM_GATHER
     return hipGetLastError() == hipSuccess ? GRIM_OK : GRIM_ERR_DEVICE;
 }
