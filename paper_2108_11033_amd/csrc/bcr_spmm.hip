@@ -169,6 +169,9 @@ __device__ __forceinline__ f32x16 mfma32(i16x8 a, i16x8 b, f32x16 c) {
 // LDS transpose read: the 16 lanes of a block each name 8 bytes (4 values along n of one
 // staged row); lane i of the block receives value (i % 4) of the chunks named by lanes
 // i / 4, 4 + i / 4, 8 + i / 4 and 12 + i / 4 -- four rows at one column, the MFMA k order.
+__device__ __forceinline__ i16x4 lds_tr_read_at(unsigned int lds_byte_address) {
+    return __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) i16x4 *)(uintptr_t)lds_byte_address);
+}
 __device__ __forceinline__ i16x4 lds_tr_read(const char *lds_addr) {
     return __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) i16x4 *)(lds_addr));
 }
@@ -869,7 +872,7 @@ __device__ __forceinline__ unsigned short conv_f32_to_bf16(float f) {
     return (unsigned short)(u >> 16);
 }
 
-struct __attribute__((packed, aligned(2))) ConvWindow {
+struct __attribute__((packed, aligned(4))) ConvWindow {
     unsigned int d[4];
 };
 
@@ -930,6 +933,9 @@ __global__ void __launch_bounds__(256, 4) bcr_conv_gather(ConvParams p) {
     const int r0 = kgroup * 8 + qd, r1 = r0 + 4;
     const int sw0 = swizzle<CPR>(r0), sw1 = swizzle<CPR>(r1);
     const int x0 = r0 * PITCH + within, x1 = r1 * PITCH + within;
+    // the lane's two transpose reads of sub-tile 0
+    const unsigned int buf_lds = (unsigned int)(uintptr_t)(__attribute__((address_space(3))) char *)buf;
+    const unsigned int tr0 = x0 + ((cl ^ sw0) << 4), tr1 = x1 + ((cl ^ sw1) << 4);           // offsets in a step buffer
 
     f32x4 acc[NT];
 #pragma unroll
@@ -940,6 +946,7 @@ __global__ void __launch_bounds__(256, 4) bcr_conv_gather(ConvParams p) {
     const i16x8 *pay = reinterpret_cast<const i16x8 *>(p.payload);
     const char *Fb = reinterpret_cast<const char *>(p.F);
     const int HW = p.N, wstep = p.W - p.kw, nshift = nbase - (ph * p.W + pw), emax = p.total - 8;
+    const int nshift7 = nshift + (7 - c) * 8;    // the same for the last piece of the tile
     for (int s = s_beg; s < s_end; s += SB) {
         const int nb = s_end - s < SB ? s_end - s : SB;
         u32x4 hdr[SB];
@@ -955,13 +962,30 @@ __global__ void __launch_bounds__(256, 4) bcr_conv_gather(ConvParams p) {
         i16x8 PW[SB];
         // element index of the window of k slot `k` for this lane, and the tap it belongs to
         // (24-bit multiplies: Cin, H * W, W and the tap numbers are all below 2^24)
-        auto window = [&](unsigned int k, int &tap) {
+        auto window = [&](unsigned int k, int &tap, int shift) {
             const unsigned int cin = __umulhi(k << 1, (unsigned int)p.kk_magic);
             tap = (int)(k - __umul24(cin, (unsigned int)p.KK));
             const unsigned int r = __umul24((unsigned int)tap, (unsigned int)p.kw_magic) >> 8;   // tap / kw
             // r * W + (tap - r * kw), less the centre tap's offset
-            return (int)(__umul24(cin, (unsigned int)HW) + __umul24(r, (unsigned int)wstep)) + tap + nshift;
+            return (int)(__umul24(cin, (unsigned int)HW) + __umul24(r, (unsigned int)wstep)) + tap + shift;
         };
+        // A 16-byte load at an odd element (2 bytes off a dword) costs about three aligned ones in the
+        // vector L1, a load that is only dword-aligned next to nothing.  A window that starts at an
+        // odd element is therefore fetched one element early; when the step is written the lane
+        // shifts it by 16 bits and takes its last element from the next lane's first dword.  The
+        // last lane of a row piece has no such neighbour: the 32 boundary elements of a step (one
+        // per k slot) are fetched by lanes 0..31 with one extra 2-byte load per step and handed
+        // over by a lane permute.
+        unsigned int ext[SB];
+#pragma unroll
+        for (int u = 0; u < SB; ++u) {
+            const int st = s + (u < nb ? u : nb - 1);
+            const unsigned int kx = p.rows[(int64_t)st * 32 + (lane & 7) * 4 + ((lane >> 3) & 3)];   // k slot lane % 32
+            int tapx;
+            const int e7 = window(kx == 0xffffffffu ? 0u : kx, tapx, nshift7);
+            const bool need = lane < 32 && kx != 0xffffffffu && (e7 & 1) && e7 + 7 >= 0 && e7 + 7 < p.total;
+            ext[u] = need ? (unsigned int)p.F[e7 + 7] : 0u;
+        }
         bool edge_any = false;
 #pragma unroll
         for (int u = 0; u < SB; ++u) {
@@ -970,12 +994,13 @@ __global__ void __launch_bounds__(256, 4) bcr_conv_gather(ConvParams p) {
             for (int i = 0; i < 4; ++i) {
                 const bool is_pad = hdr[u][i] == 0xffffffffu;
                 int tap;
-                const int e0 = window(is_pad ? 0u : hdr[u][i], tap);
-                vsel[u] |= (unsigned int)(is_pad ? p.KK : tap) << (8 * i);
+                const int e0 = window(is_pad ? 0u : hdr[u][i], tap, nshift);
                 const bool edge = e0 < 0 || e0 > emax;
                 edge_any |= edge;
+                const int odd = e0 & 1;
+                vsel[u] |= ((unsigned int)(is_pad ? p.KK : tap) | (unsigned int)odd << 7) << (8 * i);
                 ConvWindow wv;
-                __builtin_memcpy(&wv, Fb + (unsigned int)(edge ? 0 : e0 * 2), 16);   // byte offset below 2^31
+                __builtin_memcpy(&wv, Fb + (unsigned int)(edge ? 0 : (e0 - odd) * 2), 16);   // byte offset below 2^31
                 RX[u][i] = u32x4{wv.d[0], wv.d[1], wv.d[2], wv.d[3]};
             }
         }
@@ -989,12 +1014,14 @@ __global__ void __launch_bounds__(256, 4) bcr_conv_gather(ConvParams p) {
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     int tap;
-                    const int e0 = window(h2[i] == 0xffffffffu ? 0u : h2[i], tap);
+                    const int e0 = window(h2[i] == 0xffffffffu ? 0u : h2[i], tap, nshift);
                     if (e0 < 0 || e0 > emax) {
+                        // the same eight elements the common path fetches (one early for an odd start), so that
+                        // the lane's neighbours find what they expect in its first dword
                         unsigned int d[4] = {0u, 0u, 0u, 0u};
 #pragma unroll
                         for (int j = 0; j < 8; ++j) {
-                            const int e = e0 + j;
+                            const int e = e0 - (e0 & 1) + j;
                             const unsigned int v = e >= 0 && e < p.total ? p.F[e] : 0u;
                             d[j >> 1] |= v << ((j & 1) * 16);
                         }
@@ -1016,16 +1043,31 @@ __global__ void __launch_bounds__(256, 4) bcr_conv_gather(ConvParams p) {
                 char *b = buf + (u & 1) * 4096;
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    const u32x4 vm = vtab[((vsel[u] >> (8 * i)) & 0xffu) * 8 + c];
-                    const u32x4 v = {RX[u][i][0] & vm[0], RX[u][i][1] & vm[1], RX[u][i][2] & vm[2], RX[u][i][3] & vm[3]};
+                    const unsigned int sel = (vsel[u] >> (8 * i)) & 0xffu;
+                    const u32x4 vm = vtab[(sel & 0x7fu) * 8 + c];
+                    const unsigned int sh = (sel >> 7) * 16u;             // 16: the window starts one element into the fetch
+                    // the dword after the lane's four: the next lane's first one, or the boundary element
+                    const unsigned int w0 = RX[u][i][0];
+                    const unsigned int nxt = (unsigned int)__builtin_amdgcn_update_dpp(0, (int)w0, 0x101 /* row_shl:1 */, 0xf, 0xf, true);
+                    const unsigned int bnd = (unsigned int)__shfl((int)ext[u], i * 8 + rs);
+                    const unsigned int w4 = c == 7 ? bnd : nxt;
+                    const u32x4 v = {__builtin_amdgcn_alignbit(RX[u][i][1], w0, sh) & vm[0],
+                                     __builtin_amdgcn_alignbit(RX[u][i][2], RX[u][i][1], sh) & vm[1],
+                                     __builtin_amdgcn_alignbit(RX[u][i][3], RX[u][i][2], sh) & vm[2],
+                                     __builtin_amdgcn_alignbit(w4, RX[u][i][3], sh) & vm[3]};
                     *reinterpret_cast<u32x4 *>(b + wr_off0 + i * 8 * PITCH) = v;
                 }
                 __builtin_amdgcn_wave_barrier();
+                // The 16-byte chunk of sub-tile q is (2 q + cl) ^ swizzle = (cl ^ swizzle) ^ 2 q: the eight
+                // read addresses are two bases with q << 5 XOR-ed in.  The empty asm keeps the compiler from
+                // holding all eight in registers across the loop (they would not fit and spill).
+                unsigned int a0 = tr0, a1 = tr1;
+                asm volatile("" : "+v"(a0), "+v"(a1));
+                const unsigned int sb = buf_lds + (u & 1) * 4096;
 #pragma unroll
                 for (int q = 0; q < NT; ++q) {
-                    const int cq = q * 2 + cl;
-                    const i16x4 lo = lds_tr_read(b + x0 + ((cq ^ sw0) << 4));
-                    const i16x4 hi = lds_tr_read(b + x1 + ((cq ^ sw1) << 4));
+                    const i16x4 lo = lds_tr_read_at(sb + (a0 ^ (unsigned int)(q << 5)));
+                    const i16x4 hi = lds_tr_read_at(sb + (a1 ^ (unsigned int)(q << 5)));
                     const i16x8 x = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
                     acc[q] = mfma16<BF16>(x, PW[u], acc[q]);
                 }
