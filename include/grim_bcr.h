@@ -194,7 +194,7 @@ void grim_bcr_group_free(grim_bcr_group *G);
  * The result equals grim_bcr_spmm on the materialised im2col matrix (bit for bit when every sum is
  * exact); only the feature map is read -- kh * kw times fewer bytes -- and only the rows a strip keeps.
  * Runs on the row-gathering matrix-core kernel: fp16 / bf16, block height a divisor or a multiple of
- * 16, 64 <= H * W < 2^24, W >= 8, kh * kw <= 16, Cin * H * W <= 2^30; otherwise GRIM_ERR_UNSUPPORTED.
+ * 16, 64 <= H * W < 2^24, W >= 8, kh * kw <= 16, Cin * H * W <= 2^26; otherwise GRIM_ERR_UNSUPPORTED.
  * Errors: NULL, SHAPE (even kernel, K != Cin * kh * kw, ldy < H * W, sizes < 1), DEVICE, UNSUPPORTED.
  */
 grim_status grim_bcr_conv2d(const grim_bcr_matrix *A, const void *F_dev, int32_t Cin, int32_t H, int32_t W,

@@ -922,9 +922,8 @@ __global__ void __launch_bounds__(256, 4) bcr_conv_gather(ConvParams p) {
     }
     __syncthreads();
 
-    // fetch side: lane = (row slot rs, piece c): positions nbase .. nbase + 7 of the tile
+    // fetch side: lane = (row slot rs, piece c): positions n0 + 8 c .. n0 + 8 c + 7 of the tile
     const int rs = lane >> 3, c = lane & 7;
-    const int nbase = n0 + c * 8;
     const int wr_off0 = rs * PITCH + ((c ^ swizzle<CPR>(rs)) << 4);     // the swizzle does not depend on i (row i * 8 + rs)
     // multiply side (as in the row-gathering kernel)
     const int i16 = lane & 15, kgroup = lane >> 4, qd = i16 >> 2, m_row = i16;
@@ -941,64 +940,69 @@ __global__ void __launch_bounds__(256, 4) bcr_conv_gather(ConvParams p) {
 #pragma unroll
     for (int q = 0; q < NT; ++q) acc[q] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    const u32x4 *rows4 = reinterpret_cast<const u32x4 *>(p.rows);
     const uint2 *desc2 = reinterpret_cast<const uint2 *>(p.desc);
     const i16x8 *pay = reinterpret_cast<const i16x8 *>(p.payload);
     const char *Fb = reinterpret_cast<const char *>(p.F);
-    const int HW = p.N, wstep = p.W - p.kw, nshift = nbase - (ph * p.W + pw), emax = p.total - 8;
-    const int nshift7 = nshift + (7 - c) * 8;    // the same for the last piece of the tile
+    const int HW = p.N, wstep = p.W - p.kw, emax = p.total - 8;
+    const int nshift0 = n0 - (ph * p.W + pw);    // window start relative to a channel, tile's first column, centre tap removed
+    const int cofs = c * 8 - (1 << 25);          // this lane's piece, and the bias of the packed form
     for (int s = s_beg; s < s_end; s += SB) {
         const int nb = s_end - s < SB ? s_end - s : SB;
-        u32x4 hdr[SB];
+        // Lane j takes k slot j % 32 of every step of the batch: it splits the slot's row number once into
+        // (window start for the tile's first column, tap) and the lanes that fetch the slot's eight row
+        // pieces pick that pair up with a lane permute -- one integer division per lane and step instead of
+        // four.  Packed as tap (or KK for padding) << 27 | window start + 2^25.
+        unsigned int pk[SB];
         uint2 dsc[SB];
 #pragma unroll
         for (int u = 0; u < SB; ++u) {
             const int st = s + (u < nb ? u : nb - 1);
-            hdr[u] = rows4[(int64_t)st * 8 + rs];
+            pk[u] = p.rows[(int64_t)st * 32 + (lane & 7) * 4 + ((lane >> 3) & 3)];
             dsc[u] = desc2[(int64_t)st * 4 + kgroup];
         }
         u32x4 RX[SB][4];
-        unsigned int vsel[SB];                   // per step, 8 bits per window: which validity mask goes with it (the tap; KK: padding)
+        unsigned int vsel[SB];                   // per step, 8 bits per window: validity mask (the tap; KK: padding) | odd start << 7
         i16x8 PW[SB];
-        // element index of the window of k slot `k` for this lane, and the tap it belongs to
-        // (24-bit multiplies: Cin, H * W, W and the tap numbers are all below 2^24)
-        auto window = [&](unsigned int k, int &tap, int shift) {
-            const unsigned int cin = __umulhi(k << 1, (unsigned int)p.kk_magic);
-            tap = (int)(k - __umul24(cin, (unsigned int)p.KK));
-            const unsigned int r = __umul24((unsigned int)tap, (unsigned int)p.kw_magic) >> 8;   // tap / kw
-            // r * W + (tap - r * kw), less the centre tap's offset
-            return (int)(__umul24(cin, (unsigned int)HW) + __umul24(r, (unsigned int)wstep)) + tap + shift;
-        };
-        // A 16-byte load at an odd element (2 bytes off a dword) costs about three aligned ones in the
-        // vector L1, a load that is only dword-aligned next to nothing.  A window that starts at an
-        // odd element is therefore fetched one element early; when the step is written the lane
-        // shifts it by 16 bits and takes its last element from the next lane's first dword.  The
-        // last lane of a row piece has no such neighbour: the 32 boundary elements of a step (one
-        // per k slot) are fetched by lanes 0..31 with one extra 2-byte load per step and handed
-        // over by a lane permute.
         unsigned int ext[SB];
 #pragma unroll
         for (int u = 0; u < SB; ++u) {
-            const int st = s + (u < nb ? u : nb - 1);
-            const unsigned int kx = p.rows[(int64_t)st * 32 + (lane & 7) * 4 + ((lane >> 3) & 3)];   // k slot lane % 32
-            int tapx;
-            const int e7 = window(kx == 0xffffffffu ? 0u : kx, tapx, nshift7);
-            const bool need = lane < 32 && kx != 0xffffffffu && (e7 & 1) && e7 + 7 >= 0 && e7 + 7 < p.total;
+            const bool is_pad = pk[u] == 0xffffffffu;
+            const unsigned int kk = is_pad ? 0u : pk[u];
+            // (24-bit multiplies: Cin, H * W, W and the tap numbers are all below 2^24)
+            const unsigned int cin = __umulhi(kk << 1, (unsigned int)p.kk_magic);
+            const int tap = (int)(kk - __umul24(cin, (unsigned int)p.KK));
+            const unsigned int r = __umul24((unsigned int)tap, (unsigned int)p.kw_magic) >> 8;   // tap / kw
+            // r * W + (tap - r * kw), less the centre tap's offset, for the tile's first column
+            const int eb = (int)(__umul24(cin, (unsigned int)HW) + __umul24(r, (unsigned int)wstep)) + tap + nshift0;
+            pk[u] = (unsigned int)(is_pad ? p.KK : tap) << 27 | (unsigned int)(eb + (1 << 25));
+            // A 16-byte load at an odd element (2 bytes off a dword) costs about three aligned ones in the
+            // vector L1, a load that is only dword-aligned next to nothing.  A window that starts at an odd
+            // element is therefore fetched one element early; when the step is written the lane shifts it
+            // by 16 bits and takes its last element from the next lane's first dword.  The last lane of a
+            // row piece has no such neighbour: lanes 0..31 fetch the boundary element of their k slot with
+            // one extra 2-byte load per step, handed over by a lane permute.
+            const int e7 = eb + 56;
+            const bool need = lane < 32 && !is_pad && (e7 & 1) && e7 + 7 >= 0 && e7 + 7 < p.total;
             ext[u] = need ? (unsigned int)p.F[e7 + 7] : 0u;
         }
+        // window start of piece (u, i) for this lane, and the selector of its validity mask
+        auto piece = [&](int u, int i, unsigned int &sel) {
+            const unsigned int v = (unsigned int)__shfl((int)pk[u], i * 8 + rs);
+            sel = v >> 27;
+            return (int)(v & 0x7ffffffu) + cofs;
+        };
         bool edge_any = false;
 #pragma unroll
         for (int u = 0; u < SB; ++u) {
             vsel[u] = 0u;
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                const bool is_pad = hdr[u][i] == 0xffffffffu;
-                int tap;
-                const int e0 = window(is_pad ? 0u : hdr[u][i], tap, nshift);
+                unsigned int sel;
+                const int e0 = piece(u, i, sel);
                 const bool edge = e0 < 0 || e0 > emax;
                 edge_any |= edge;
                 const int odd = e0 & 1;
-                vsel[u] |= ((unsigned int)(is_pad ? p.KK : tap) | (unsigned int)odd << 7) << (8 * i);
+                vsel[u] |= (sel | (unsigned int)odd << 7) << (8 * i);
                 ConvWindow wv;
                 __builtin_memcpy(&wv, Fb + (unsigned int)(edge ? 0 : (e0 - odd) * 2), 16);   // byte offset below 2^31
                 RX[u][i] = u32x4{wv.d[0], wv.d[1], wv.d[2], wv.d[3]};
@@ -1006,15 +1010,12 @@ __global__ void __launch_bounds__(256, 4) bcr_conv_gather(ConvParams p) {
         }
         if (__builtin_amdgcn_ballot_w64(edge_any)) {
             // Rare: only where the tile touches the first or last positions of the feature map.
-            // The row numbers are fetched again, so that the common path need not keep them.
 #pragma unroll
             for (int u = 0; u < SB; ++u) {
-                const int st = s + (u < nb ? u : nb - 1);
-                const u32x4 h2 = rows4[(int64_t)st * 8 + rs];
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    int tap;
-                    const int e0 = window(h2[i] == 0xffffffffu ? 0u : h2[i], tap, nshift);
+                    unsigned int sel;
+                    const int e0 = piece(u, i, sel);
                     if (e0 < 0 || e0 > emax) {
                         // the same eight elements the common path fetches (one early for an odd start), so that
                         // the lane's neighbours find what they expect in its first dword
@@ -1133,7 +1134,7 @@ grim_status launch_conv_gather(const grim_bcr_matrix *A, const void *F, int32_t 
                                int32_t kw, const float *bias, int32_t relu, void *Y, int32_t odt, int64_t ldy,
                                hipStream_t stream) {
     const int64_t N = (int64_t)H * W, total = (int64_t)Cin * N;
-    if (!A->gather.present || N < 64 || W < 8 || kh * kw > kConvMaxTaps || total > (int64_t(1) << 30) ||
+    if (!A->gather.present || N < 64 || W < 8 || kh * kw > kConvMaxTaps || total > (int64_t(1) << 26) || (int64_t)(kh / 2) * W + kw / 2 >= (1 << 24) ||
         A->K > (int64_t(1) << 27) || Cin >= (1 << 24) || N >= (1 << 24) || reinterpret_cast<uintptr_t>(F) % 2 != 0)
         return GRIM_ERR_UNSUPPORTED;
     ConvParams p;
