@@ -946,6 +946,8 @@ __global__ void __launch_bounds__(256, 4) bcr_conv_gather(ConvParams p) {
     const int HW = p.N, wstep = p.W - p.kw, emax = p.total - 8;
     const int nshift0 = n0 - (ph * p.W + pw);    // window start relative to a channel, tile's first column, centre tap removed
     const int cofs = c * 8 - (1 << 25);          // this lane's piece, and the bias of the packed form
+    // can a window of this tile start before the feature map or end behind it?  (only in the first / last channel)
+    const bool tile_edge = n0 < ph * p.W + pw || n0 + TN + ph * p.W + pw > HW;
     for (int s = s_beg; s < s_end; s += SB) {
         const int nb = s_end - s < SB ? s_end - s : SB;
         // Lane j takes k slot j % 32 of every step of the batch: it splits the slot's row number once into
@@ -964,73 +966,85 @@ __global__ void __launch_bounds__(256, 4) bcr_conv_gather(ConvParams p) {
         unsigned int vsel[SB];                   // per step, 8 bits per window: validity mask (the tap; KK: padding) | odd start << 7
         i16x8 PW[SB];
         unsigned int ext[SB];
-#pragma unroll
-        for (int u = 0; u < SB; ++u) {
-            const bool is_pad = pk[u] == 0xffffffffu;
-            const unsigned int kk = is_pad ? 0u : pk[u];
-            // (24-bit multiplies: Cin, H * W, W and the tap numbers are all below 2^24)
-            const unsigned int cin = __umulhi(kk << 1, (unsigned int)p.kk_magic);
-            const int tap = (int)(kk - __umul24(cin, (unsigned int)p.KK));
-            const unsigned int r = __umul24((unsigned int)tap, (unsigned int)p.kw_magic) >> 8;   // tap / kw
-            // r * W + (tap - r * kw), less the centre tap's offset, for the tile's first column
-            const int eb = (int)(__umul24(cin, (unsigned int)HW) + __umul24(r, (unsigned int)wstep)) + tap + nshift0;
-            pk[u] = (unsigned int)(is_pad ? p.KK : tap) << 27 | (unsigned int)(eb + (1 << 25));
-            // A 16-byte load at an odd element (2 bytes off a dword) costs about three aligned ones in the
-            // vector L1, a load that is only dword-aligned next to nothing.  A window that starts at an odd
-            // element is therefore fetched one element early; when the step is written the lane shifts it
-            // by 16 bits and takes its last element from the next lane's first dword.  The last lane of a
-            // row piece has no such neighbour: lanes 0..31 fetch the boundary element of their k slot with
-            // one extra 2-byte load per step, handed over by a lane permute.
-            const int e7 = eb + 56;
-            const bool need = lane < 32 && !is_pad && (e7 & 1) && e7 + 7 >= 0 && e7 + 7 < p.total;
-            ext[u] = need ? (unsigned int)p.F[e7 + 7] : 0u;
-        }
         // window start of piece (u, i) for this lane, and the selector of its validity mask
         auto piece = [&](int u, int i, unsigned int &sel) {
             const unsigned int v = (unsigned int)__shfl((int)pk[u], i * 8 + rs);
             sel = v >> 27;
             return (int)(v & 0x7ffffffu) + cofs;
         };
-        bool edge_any = false;
-#pragma unroll
-        for (int u = 0; u < SB; ++u) {
-            vsel[u] = 0u;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                unsigned int sel;
-                const int e0 = piece(u, i, sel);
-                const bool edge = e0 < 0 || e0 > emax;
-                edge_any |= edge;
-                const int odd = e0 & 1;
-                vsel[u] |= (sel | (unsigned int)odd << 7) << (8 * i);
-                ConvWindow wv;
-                __builtin_memcpy(&wv, Fb + (unsigned int)(edge ? 0 : (e0 - odd) * 2), 16);   // byte offset below 2^31
-                RX[u][i] = u32x4{wv.d[0], wv.d[1], wv.d[2], wv.d[3]};
-            }
-        }
-        if (__builtin_amdgcn_ballot_w64(edge_any)) {
-            // Rare: only where the tile touches the first or last positions of the feature map.
+        // SAFE: the tile touches the first or last positions of the feature map, where a window can reach
+        // outside it (first / last channel only); every other tile skips those checks altogether.
+        auto fetch = [&](auto safe_tag) {
+            constexpr bool SAFE = decltype(safe_tag)::value;
 #pragma unroll
             for (int u = 0; u < SB; ++u) {
+                const bool is_pad = pk[u] == 0xffffffffu;
+                const unsigned int kk = is_pad ? 0u : pk[u];
+                // (24-bit multiplies: Cin, H * W, W and the tap numbers are all below 2^24)
+                const unsigned int cin = __umulhi(kk << 1, (unsigned int)p.kk_magic);
+                const int tap = (int)(kk - __umul24(cin, (unsigned int)p.KK));
+                const unsigned int r = __umul24((unsigned int)tap, (unsigned int)p.kw_magic) >> 8;   // tap / kw
+                // r * W + (tap - r * kw), less the centre tap's offset, for the tile's first column
+                const int eb = (int)(__umul24(cin, (unsigned int)HW) + __umul24(r, (unsigned int)wstep)) + tap + nshift0;
+                pk[u] = (unsigned int)(is_pad ? p.KK : tap) << 27 | (unsigned int)(eb + (1 << 25));
+                // A 16-byte load at an odd element (2 bytes off a dword) costs about three aligned ones in the
+                // vector L1, a load that is only dword-aligned next to nothing.  A window that starts at an odd
+                // element is therefore fetched one element early; when the step is written the lane shifts it
+                // by 16 bits and takes its last element from the next lane's first dword.  The last lane of a
+                // row piece has no such neighbour: lanes 0..31 fetch the boundary element of their k slot with
+                // one extra 2-byte load per step, handed over by a lane permute.
+                const int e7 = eb + 56;
+                bool need = lane < 32 && !is_pad && (e7 & 1);
+                if constexpr (SAFE) need = need && e7 + 7 >= 0 && e7 + 7 < p.total;
+                ext[u] = need ? (unsigned int)p.F[e7 + 7] : 0u;
+            }
+            bool edge_any = false;
+#pragma unroll
+            for (int u = 0; u < SB; ++u) {
+                vsel[u] = 0u;
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     unsigned int sel;
                     const int e0 = piece(u, i, sel);
-                    if (e0 < 0 || e0 > emax) {
-                        // the same eight elements the common path fetches (one early for an odd start), so that
-                        // the lane's neighbours find what they expect in its first dword
-                        unsigned int d[4] = {0u, 0u, 0u, 0u};
+                    const int odd = e0 & 1;
+                    vsel[u] |= (sel | (unsigned int)odd << 7) << (8 * i);
+                    int ea = e0 - odd;
+                    if constexpr (SAFE) {
+                        const bool edge = e0 < 0 || e0 > emax;
+                        edge_any |= edge;
+                        ea = edge ? 0 : ea;
+                    }
+                    ConvWindow wv;
+                    __builtin_memcpy(&wv, Fb + (unsigned int)(ea * 2), 16);      // byte offset below 2^31
+                    RX[u][i] = u32x4{wv.d[0], wv.d[1], wv.d[2], wv.d[3]};
+                }
+            }
+            if constexpr (SAFE) {
+                if (__builtin_amdgcn_ballot_w64(edge_any)) {
 #pragma unroll
-                        for (int j = 0; j < 8; ++j) {
-                            const int e = e0 - (e0 & 1) + j;
-                            const unsigned int v = e >= 0 && e < p.total ? p.F[e] : 0u;
-                            d[j >> 1] |= v << ((j & 1) * 16);
+                    for (int u = 0; u < SB; ++u) {
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            unsigned int sel;
+                            const int e0 = piece(u, i, sel);
+                            if (e0 < 0 || e0 > emax) {
+                                // the same eight elements the common path fetches (one early for an odd start), so
+                                // that the lane's neighbours find what they expect in its first dword
+                                unsigned int d[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+                                for (int j = 0; j < 8; ++j) {
+                                    const int e = e0 - (e0 & 1) + j;
+                                    const unsigned int v = e >= 0 && e < p.total ? p.F[e] : 0u;
+                                    d[j >> 1] |= v << ((j & 1) * 16);
+                                }
+                                RX[u][i] = u32x4{d[0], d[1], d[2], d[3]};
+                            }
                         }
-                        RX[u][i] = u32x4{d[0], d[1], d[2], d[3]};
                     }
                 }
             }
-        }
+        };
+        if (tile_edge) fetch(std::true_type{}); else fetch(std::false_type{});
 #pragma unroll
         for (int u = 0; u < SB; ++u) {
             const bool kept = (dsc[u].x >> m_row) & 1u;
