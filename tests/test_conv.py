@@ -109,6 +109,33 @@ def test_conv_parity(dtype, Cin, H, W, kh, kw, BR, BC):
 
 
 @pytest.mark.gpu
+def test_conv_random_geometries():
+    """Seeded sweep over image sizes (widths of every parity and alignment, so that windows start at odd and even
+    elements, wrap to the next image row inside a piece, and reach outside the feature map in the first and last
+    tiles), kernel shapes and channel counts; integer data, so every result must equal the reference exactly."""
+    import paper_2108_11033_amd as g
+    from helpers import pack_workload
+    rng = np.random.default_rng(760)
+    dtype = gen.F16
+    for case in range(14):
+        kh, kw = [(3, 3), (1, 3), (3, 1), (5, 3), (1, 1), (3, 5)][case % 6]
+        W = int(rng.integers(8, 41))
+        H = int(rng.integers(max(2, (64 + W - 1) // W), 30))
+        BC = [8, 16, 32][case % 3]
+        Cin = BC * int(rng.integers(1, 5)) // np.gcd(BC, kh * kw) * 1
+        while (Cin * kh * kw) % BC:
+            Cin += 1
+        M, K = 32, Cin * kh * kw
+        mask = gen.random_mask(M, K, 16, BC, (0, 5, 16), tuple(sorted({1, BC // 2, BC})), seed=761 + case)
+        Wt = gen.small_int_values((M, K), dtype, seed=762 + case)
+        F = gen.small_int_values((Cin, H, W), dtype, seed=763 + case)
+        A = pack_workload(g, Wt, dtype, mask)
+        Yref = conv_ref.conv_same(_masked(Wt, dtype, mask), gen.storage_to_f64(F, dtype), kh, kw)
+        Y = _run(g, A, F, dtype, M, Cin, H, W, kh, kw)
+        assert np.array_equal(Y.astype(np.float64), Yref), (case, Cin, H, W, kh, kw, BC)
+
+
+@pytest.mark.gpu
 def test_conv_integer_data_is_exact_and_equals_the_im2col_product():
     """Small integers: every sum is exact, so the fused path, the library's own product on the materialised
     im2col matrix and the reference must agree bit for bit."""
