@@ -358,6 +358,25 @@ def main() -> int:
         out["conv"]["at_224x224"] = {"us": tcb * 1e6, "useful_tflops": 2.0 * vd["nnz"] * Hb * Hb / tcb / 1e12,
                                      "torch_unfold_us": tub * 1e6, "im2col_matrix_mb": wl.K * Hb * Hb * 2 / 1e6}
         del Fb, Yb_
+        # the 13 VGG-16 conv layers (c4's weights) as fused layers: convolution + bias + rectifier + fp16 output,
+        # each from a feature map of its input size (pooling between the stages is not part of this library)
+        stack = []
+        tot = 0.0
+        for li in range(13):
+            Mv, Kv, Nv = gen.VGG16_LAYERS[li]
+            Cv, Hv = Kv // 9, int(round(Nv ** 0.5))
+            w4 = gen.c4_vgg16_layer(li, N=64)
+            A4 = pack(w4)
+            Fv = [dev_tensor(gen.normal_activations(Cv, Nv, "f16", seed=90 + li + 20 * i, relu=True), "f16") for i in range(2)]
+            Ov = [torch.empty((Mv, Nv), dtype=torch.float16, device=dev) for _ in range(2)]
+            bv = torch.zeros(Mv, dtype=torch.float32, device=dev)
+            tv, _ = time_launches(torch, lambda i: g.conv2d_act(A4, Fv[i % 2], Cv, Hv, Hv, 3, 3, bv, True, Ov[i % 2], "f16", Nv, stream),
+                                  50, 5)
+            stack.append(tv * 1e6)
+            tot += tv
+            del A4, Fv, Ov
+        out["conv"]["vgg16_13_fused_layers_us"] = stack
+        out["conv"]["vgg16_13_fused_layers_total_us"] = tot * 1e6
         del Fs
 
     if args.sweep:

@@ -877,30 +877,37 @@ struct __attribute__((packed, aligned(4))) ConvWindow {
 };
 
 constexpr int kConvMaxTaps = 16;
-constexpr int kConvLdsBytes = 4 * 8192 + (kConvMaxTaps + 1) * 8 * 16;
+constexpr int kConvTableBytes = (kConvMaxTaps + 1) * 8 * 16;   // validity masks, behind the waves' step buffers
 
-template <bool BF16>
-__global__ void __launch_bounds__(256, 4) bcr_conv_gather(ConvParams p) {
+// SOLO, EIGHT: as in the row-gathering kernel -- a (tile, strip) pair per wave for strips of a few steps, eight
+// waves per strip for long strips with few workgroups
+template <bool BF16, bool SOLO, bool EIGHT>
+__global__ void __launch_bounds__(EIGHT ? 512 : 256, EIGHT ? 2 : 4) bcr_conv_gather(ConvParams p) {
     constexpr int NT = 4, TN = 64, PITCH = 128, CPR = 8;
     constexpr int SB = 3;                        // steps a wave has in flight
+    constexpr int NWV = EIGHT ? 8 : 4;           // waves of the workgroup
     extern __shared__ __attribute__((aligned(16))) char lds[];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int id = blockIdx.x;
     const int xcd = id & 7, slot = id >> 3;
-    const int tile = (slot / p.nbr) * 8 + xcd;
-    const int t = slot % p.nbr;
+    const int per_tile = SOLO ? (p.nbr + 3) / 4 : p.nbr;           // workgroups per tile
+    const int tile = (slot / per_tile) * 8 + xcd;
+    const int t_raw = SOLO ? (slot % per_tile) * 4 + wave : slot % per_tile;
     if (tile >= p.ntiles) return;
+    const bool active = t_raw < p.nbr;           // SOLO: the last workgroup of a tile may have idle waves
+    const int t = active ? t_raw : p.nbr - 1;
     int n0 = tile * TN;
     if (n0 + TN > p.N) n0 = p.N - TN;            // ragged last tile: overlap the neighbour (N >= 64)
 
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     // one dependent memory round trip less at the start when every run has the same number of steps
     const int g0 = p.usteps ? t * p.usteps : p.sptr[t], nst = p.usteps ? p.usteps : p.sptr[t + 1] - g0;
-    const int s_beg = g0 + (int)((int64_t)nst * wave / 4), s_end = g0 + (int)((int64_t)nst * (wave + 1) / 4);
+    const int s_beg = SOLO ? g0 : g0 + (int)((int64_t)nst * wave / NWV);
+    const int s_end = SOLO ? g0 + nst : g0 + (int)((int64_t)nst * (wave + 1) / NWV);
     char *buf = lds + wave * 8192;
     // per (tap, piece of the tile) the 16-byte validity mask of the piece's 8 positions; entry KK
     // is all zero (padding slots).
-    u32x4 *vtab = reinterpret_cast<u32x4 *>(lds + 4 * 8192);
+    u32x4 *vtab = reinterpret_cast<u32x4 *>(lds + NWV * 8192);
     const int ph = p.kh >> 1, pw = p.kw >> 1;
     if (tid < (p.KK + 1) * 8) {
         const int tap = tid >> 3, cc = tid & 7;
@@ -921,6 +928,7 @@ __global__ void __launch_bounds__(256, 4) bcr_conv_gather(ConvParams p) {
         vtab[tid] = u32x4{m[0], m[1], m[2], m[3]};
     }
     __syncthreads();
+    if (SOLO && !active) return;                 // (no barrier follows in that form)
 
     // fetch side: lane = (row slot rs, piece c): positions n0 + 8 c .. n0 + 8 c + 7 of the tile
     const int rs = lane >> 3, c = lane & 7;
@@ -1091,22 +1099,9 @@ __global__ void __launch_bounds__(256, 4) bcr_conv_gather(ConvParams p) {
         }
     }
 
-    // the waves' partial tiles go through their step buffers; the tables behind them stay intact
-    f32x4 *red = reinterpret_cast<f32x4 *>(lds);
-#pragma unroll
-    for (int q = 0; q < NT; ++q) red[wave * 512 + q * 64 + lane] = acc[q];
-    __syncthreads();
-    const int q = wave;
-    f32x4 sum = red[q * 64 + lane];
-#pragma unroll
-    for (int w = 1; w < 4; ++w) {
-        const f32x4 v = red[w * 512 + q * 64 + lane];
-        sum[0] += v[0]; sum[1] += v[1]; sum[2] += v[2]; sum[3] += v[3];
-    }
-    const int64_t row = p.out_row[(int64_t)t * 16 + (lane & 15)];
-    const int64_t n = n0 + q * 16 + 4 * (lane >> 4);
-    if (row >= 0) {
-        // epilogue of a layer: bias per output channel, rectifier, rounding to the next layer's element type
+    // epilogue of a layer for four consecutive positions n .. n + 3 of output channel `row`: bias, rectifier,
+    // rounding to the next layer's element type
+    auto finish = [&](int64_t row, int64_t n, f32x4 sum) {
         const float b = p.bias ? p.bias[row] : 0.f;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
@@ -1141,7 +1136,29 @@ __global__ void __launch_bounds__(256, 4) bcr_conv_gather(ConvParams p) {
                 for (int e = 0; e < 4; ++e) dst[e] = h[e];
             }
         }
+    };
+    const int64_t row = p.out_row[(int64_t)t * 16 + (lane & 15)];
+    if constexpr (SOLO) {
+        if (row >= 0) {
+#pragma unroll
+            for (int q = 0; q < NT; ++q) finish(row, n0 + q * 16 + 4 * (lane >> 4), acc[q]);
+        }
+        return;
     }
+    // the waves' partial tiles go through their step buffers; the tables behind them stay intact
+    f32x4 *red = reinterpret_cast<f32x4 *>(lds);
+#pragma unroll
+    for (int q = 0; q < NT; ++q) red[wave * 512 + q * 64 + lane] = acc[q];
+    __syncthreads();
+    if (EIGHT && wave >= NT) return;             // the first four waves finish the four sub-tiles
+    const int q = wave;
+    f32x4 sum = red[q * 64 + lane];
+#pragma unroll
+    for (int w = 1; w < NWV; ++w) {
+        const f32x4 v = red[w * 512 + q * 64 + lane];
+        sum[0] += v[0]; sum[1] += v[1]; sum[2] += v[2]; sum[3] += v[3];
+    }
+    if (row >= 0) finish(row, n0 + q * 16 + 4 * (lane >> 4), sum);
 }
 
 grim_status launch_conv_gather(const grim_bcr_matrix *A, const void *F, int32_t Cin, int32_t H, int32_t W, int32_t kh,
@@ -1173,11 +1190,18 @@ grim_status launch_conv_gather(const grim_bcr_matrix *A, const void *F, int32_t 
     p.ntiles = (int32_t)((N + 63) / 64);
     // four consecutive outputs of a row in one store: 16 bytes of fp32, 8 bytes of fp16 / bf16
     p.yvec = (reinterpret_cast<uintptr_t>(Y) % (odt == GRIM_F32 ? 16 : 8) == 0 && ldy % 4 == 0 && N % 4 == 0) ? 4 : 1;
-    const int64_t nwg = ((int64_t)p.ntiles + 7) / 8 * 8 * p.nbr;
+    // the same launch forms as the row-gathering kernel
+    const bool solo = A->gather.max_steps <= 8 && (int64_t)p.ntiles * p.nbr >= 1024;
+    const bool eight = !solo && A->gather.max_steps >= 16 && (int64_t)p.ntiles * p.nbr <= 256;
+    const int64_t per_tile = solo ? (p.nbr + 3) / 4 : p.nbr;
+    const int64_t nwg = ((int64_t)p.ntiles + 7) / 8 * 8 * per_tile;
     if (nwg > 0x7fffffff) return GRIM_ERR_SHAPE;
-    const size_t lds = kConvLdsBytes;
-    if (A->dtype == GRIM_BF16) hipLaunchKernelGGL(bcr_conv_gather<true>, dim3((unsigned)nwg), dim3(256), lds, stream, p);
-    else hipLaunchKernelGGL(bcr_conv_gather<false>, dim3((unsigned)nwg), dim3(256), lds, stream, p);
+    const size_t lds = (size_t)(eight ? 8 : 4) * 8192 + kConvTableBytes;
+    const dim3 grid((unsigned)nwg), block(eight ? 512 : 256);
+#define GRIM_CONV(BF, SO, EI) hipLaunchKernelGGL((bcr_conv_gather<BF, SO, EI>), grid, block, lds, stream, p)
+    if (A->dtype == GRIM_BF16) { if (solo) GRIM_CONV(true, true, false); else if (eight) GRIM_CONV(true, false, true); else GRIM_CONV(true, false, false); }
+    else { if (solo) GRIM_CONV(false, true, false); else if (eight) GRIM_CONV(false, false, true); else GRIM_CONV(false, false, false); }
+#undef GRIM_CONV
     return hipGetLastError() == hipSuccess ? GRIM_OK : GRIM_ERR_DEVICE;
 }
 

@@ -109,6 +109,31 @@ def test_conv_parity(dtype, Cin, H, W, kh, kw, BR, BC):
 
 
 @pytest.mark.gpu
+@pytest.mark.parametrize("Cin,H,W,M,BC,keep_c,form", [
+    (8, 96, 116, 96, 8, (2, 8), "a (tile, strip) pair per wave: strips of a few steps, thousands of pairs, idle waves in a tile's last workgroup"),
+    (64, 16, 24, 64, 32, (24, 32), "eight waves per strip: long strips, few workgroups"),
+])
+def test_conv_launch_forms(Cin, H, W, M, BC, keep_c, form):
+    """The two other launch forms of the convolution kernel (same arithmetic per step, different split of the work)."""
+    import paper_2108_11033_amd as g
+    from helpers import pack_workload, TOL
+    dtype, K = gen.F16, Cin * 9
+    mask = gen.random_mask(M, K, 16, BC, (0, 8, 16), keep_c, seed=770 + Cin)
+    Wt = gen.normal_weights(M, K, dtype, seed=771)
+    F = gen.normal_activations(Cin, H * W, dtype, seed=772, relu=True).reshape(Cin, H, W)
+    bias = (0.05 * np.random.default_rng(773).standard_normal(M)).astype(np.float32)
+    A = pack_workload(g, Wt, dtype, mask)
+    Wm, F64 = _masked(Wt, dtype, mask), gen.storage_to_f64(F, dtype)
+    ref = conv_ref.layer(Wm, F64, 3, 3, bias, True)
+    S = conv_ref.abs_scale(Wm, F64, 3, 3) + np.abs(bias)[:, None, None]
+    out = _run_act(g, A, F, dtype, M, Cin, H, W, 3, 3, bias, True, gen.F32)
+    assert (np.abs(out - ref) <= TOL[dtype] * S + 1e-30).all(), form
+    plain = _run(g, A, F, dtype, M, Cin, H, W, 3, 3)
+    Sp = conv_ref.abs_scale(Wm, F64, 3, 3)
+    assert (np.abs(plain - conv_ref.conv_same(Wm, F64, 3, 3)) <= TOL[dtype] * Sp + 1e-30).all(), form
+
+
+@pytest.mark.gpu
 def test_conv_random_geometries():
     """Seeded sweep over image sizes (widths of every parity and alignment, so that windows start at odd and even
     elements, wrap to the next image row inside a piece, and reach outside the feature map in the first and last
