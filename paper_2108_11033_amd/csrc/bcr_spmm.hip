@@ -905,6 +905,20 @@ __global__ void __launch_bounds__(EIGHT ? 512 : 256, EIGHT ? 2 : 4) bcr_conv_gat
     const int s_beg = SOLO ? g0 : g0 + (int)((int64_t)nst * wave / NWV);
     const int s_end = SOLO ? g0 + nst : g0 + (int)((int64_t)nst * (wave + 1) / NWV);
     char *buf = lds + wave * 8192;
+    // The first batch's row numbers and block descriptors are asked for before the validity table is built,
+    // so that their latency runs under it.
+    const int kgroup0 = lane >> 4;
+    const uint2 *desc2 = reinterpret_cast<const uint2 *>(p.desc);
+    unsigned int npk[SB];
+    uint2 ndsc[SB];
+#pragma unroll
+    for (int u = 0; u < SB; ++u) {
+        int st = s_beg + u;
+        st = st < s_end ? st : s_end - 1;
+        st = st < 0 ? 0 : st;                    // (a wave without steps: any valid step, never used)
+        npk[u] = p.rows[(int64_t)st * 32 + (lane & 7) * 4 + ((lane >> 3) & 3)];
+        ndsc[u] = desc2[(int64_t)st * 4 + kgroup0];
+    }
     // per (tap, piece of the tile) the 16-byte validity mask of the piece's 8 positions; entry KK
     // is all zero (padding slots).
     u32x4 *vtab = reinterpret_cast<u32x4 *>(lds + NWV * 8192);
@@ -948,7 +962,6 @@ __global__ void __launch_bounds__(EIGHT ? 512 : 256, EIGHT ? 2 : 4) bcr_conv_gat
 #pragma unroll
     for (int q = 0; q < NT; ++q) acc[q] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    const uint2 *desc2 = reinterpret_cast<const uint2 *>(p.desc);
     const i16x8 *pay = reinterpret_cast<const i16x8 *>(p.payload);
     const char *Fb = reinterpret_cast<const char *>(p.F);
     const int HW = p.N, wstep = p.W - p.kw, emax = p.total - 8;
@@ -966,9 +979,14 @@ __global__ void __launch_bounds__(EIGHT ? 512 : 256, EIGHT ? 2 : 4) bcr_conv_gat
         uint2 dsc[SB];
 #pragma unroll
         for (int u = 0; u < SB; ++u) {
-            const int st = s + (u < nb ? u : nb - 1);
-            pk[u] = p.rows[(int64_t)st * 32 + (lane & 7) * 4 + ((lane >> 3) & 3)];
-            dsc[u] = desc2[(int64_t)st * 4 + kgroup];
+            if (s == s_beg) {
+                pk[u] = npk[u];
+                dsc[u] = ndsc[u];
+            } else {
+                const int st = s + (u < nb ? u : nb - 1);
+                pk[u] = p.rows[(int64_t)st * 32 + (lane & 7) * 4 + ((lane >> 3) & 3)];
+                dsc[u] = desc2[(int64_t)st * 4 + kgroup];
+            }
         }
         u32x4 RX[SB][4];
         unsigned int vsel[SB];                   // per step, 8 bits per window: validity mask (the tap; KK: padding) | odd start << 7
