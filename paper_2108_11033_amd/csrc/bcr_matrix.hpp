@@ -178,7 +178,9 @@ grim_status launch_conv_gather(const grim_bcr_matrix *A, const void *F, int32_t 
 // cost estimates (bytes through one compute unit) used to choose between the two matrix-core kernels
 double gather_cost(const grim_bcr_matrix *A, int64_t N);
 double mma_best_shape(const grim_bcr_matrix *A, int64_t N, int32_t tile_n, int32_t strips_per_wg, int *tn_out, int *g_out);
-grim_status launch_spmv(const GemvDesc *table_dev_or_null, const GemvDesc &single, int32_t count,
+// matrices of one launch: a device table of `count` descriptors, or (no table) `single` alone, or
+// `single` and `*second` (count = 2)
+grim_status launch_spmv(const GemvDesc *table_dev_or_null, const GemvDesc &single, const GemvDesc *second, int32_t count,
                         int64_t M, int64_t K, int32_t BR, int32_t BC, int32_t dtype, int32_t ukr,
                         int32_t ukc, int32_t vec, int32_t krmax, int32_t kcmax, const void *x, int64_t x_stride, int32_t batch,
                         int64_t ldx, float *y, int64_t y_stride, int64_t ldy, hipStream_t stream);

@@ -619,7 +619,7 @@ grim_status grim_bcr_spmm_tuned(const grim_bcr_matrix *A, const void *X_dev, int
     switch (spmm_route(A, X_dev, N, ldx, tile_n, strips_per_wg, kernel)) {
         case ROUTE_SPMV: {
             GemvDesc d = desc_of(A);
-            return launch_spmv(nullptr, d, 1, A->M, A->K, A->BR, A->BC, A->dtype, A->gemv.uniform_kr, A->gemv.uniform_kc,
+            return launch_spmv(nullptr, d, nullptr, 1, A->M, A->K, A->BR, A->BC, A->dtype, A->gemv.uniform_kr, A->gemv.uniform_kc,
                                A->gemv.vec, A->gemv.krmax, A->gemv.kcmax, X_dev, 0, (int32_t)N, ldx, Y_dev, 0, ldy, stream);
         }
         case ROUTE_GATHER: return launch_spmm_gather(A, X_dev, N, ldx, Y_dev, ldy, stream);
@@ -657,7 +657,7 @@ grim_status grim_bcr_spmv(const grim_bcr_matrix *A, const void *x_dev, int32_t b
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     if (gemv_ok(A, batch)) {
         GemvDesc d = desc_of(A);
-        return launch_spmv(nullptr, d, 1, A->M, A->K, A->BR, A->BC, A->dtype, A->gemv.uniform_kr, A->gemv.uniform_kc,
+        return launch_spmv(nullptr, d, nullptr, 1, A->M, A->K, A->BR, A->BC, A->dtype, A->gemv.uniform_kr, A->gemv.uniform_kc,
                            A->gemv.vec, A->gemv.krmax, A->gemv.kcmax, x_dev, 0, batch, ldx, y_dev, 0, ldy, stream);
     }
     // blocks the SpMV kernels do not take (more than 32 rows or columns): whatever the SpMM entry point picks
@@ -734,9 +734,26 @@ grim_status grim_bcr_gru_step(const grim_bcr_matrix *Ai, const grim_bcr_matrix *
     if (Ai->dtype != Ah->dtype) return GRIM_ERR_DTYPE;
     const int64_t H = Ai->M / 3;
     if (batch < 1 || ldh32 < batch || (hout_dev && ldhout < batch)) return GRIM_ERR_SHAPE;
-    grim_status st = grim_bcr_spmm(Ai, x_dev, batch, ldx, gi_dev, ldgi, hip_stream);
+    grim_status st = check_call(Ai, x_dev, batch, ldx, gi_dev, ldgi);
+    if (st == GRIM_OK) st = check_call(Ah, hin_dev, batch, ldhin, gh_dev, ldgh);
     if (st != GRIM_OK) return st;
-    st = grim_bcr_spmm(Ah, hin_dev, batch, ldhin, gh_dev, ldgh, hip_stream);
+    // Both products in one launch when the two matrices have one shape and the SpMV kernels take
+    // them: the second operand / result is addressed as the first plus a stride (of either sign).
+    const int esz = dtype_size(Ai->dtype);
+    const ptrdiff_t xd = static_cast<const char *>(hin_dev) - static_cast<const char *>(x_dev);
+    const ptrdiff_t yd = reinterpret_cast<const char *>(gh_dev) - reinterpret_cast<const char *>(gi_dev);
+    if (batch <= 8 && Ai->K == Ah->K && Ai->BR == Ah->BR && Ai->BC == Ah->BC && gemv_ok(Ai, batch) && gemv_ok(Ah, batch) &&
+        ldx == ldhin && ldgi == ldgh && xd % esz == 0 && yd % 4 == 0) {
+        const GemvDesc di = desc_of(Ai), dh = desc_of(Ah);
+        const bool same = Ai->gemv.uniform_kr == Ah->gemv.uniform_kr && Ai->gemv.uniform_kc == Ah->gemv.uniform_kc;
+        st = launch_spmv(nullptr, di, &dh, 2, Ai->M, Ai->K, Ai->BR, Ai->BC, Ai->dtype, same ? Ai->gemv.uniform_kr : -1,
+                         same ? Ai->gemv.uniform_kc : -1, std::min(Ai->gemv.vec, Ah->gemv.vec),
+                         std::max(Ai->gemv.krmax, Ah->gemv.krmax), std::max(Ai->gemv.kcmax, Ah->gemv.kcmax), x_dev, xd / esz,
+                         batch, ldx, gi_dev, yd / 4, ldgi, static_cast<hipStream_t>(hip_stream));
+    } else {
+        st = grim_bcr_spmm(Ai, x_dev, batch, ldx, gi_dev, ldgi, hip_stream);
+        if (st == GRIM_OK) st = grim_bcr_spmm(Ah, hin_dev, batch, ldhin, gh_dev, ldgh, hip_stream);
+    }
     if (st != GRIM_OK) return st;
     return grim_gru_cell(gi_dev, ldgi, gh_dev, ldgh, bias_i_dev, bias_h_dev, h32_dev, ldh32, hout_dev, (grim_dtype)Ai->dtype,
                          ldhout, H, batch, hip_stream);
@@ -792,7 +809,7 @@ grim_status grim_bcr_spmv_batched(const grim_bcr_group *G, const void *x_dev, in
     int dev = -1;
     if (hipGetDevice(&dev) != hipSuccess || dev != G->device) return GRIM_ERR_DEVICE;
     GemvDesc none{nullptr, nullptr, nullptr, nullptr};
-    return launch_spmv(G->d_table, none, G->count, G->M, G->K, G->BR, G->BC, G->dtype, G->uniform_kr, G->uniform_kc, G->vec, G->krmax, G->kcmax,
+    return launch_spmv(G->d_table, none, nullptr, G->count, G->M, G->K, G->BR, G->BC, G->dtype, G->uniform_kr, G->uniform_kc, G->vec, G->krmax, G->kcmax,
                        x_dev, x_stride, batch, ldx, y_dev, y_stride, ldy, static_cast<hipStream_t>(hip_stream));
 }
 

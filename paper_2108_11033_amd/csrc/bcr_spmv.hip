@@ -27,7 +27,8 @@ namespace grim {
 
 struct GemvParams {
     const GemvDesc *table;   // device table (batched launch) or nullptr
-    GemvDesc single;
+    GemvDesc single;         // no table: matrix 0 ...
+    GemvDesc second;         // ... and matrix 1 of a two-matrix launch
     int32_t BR, BC, nbc, K;
     int32_t nbr_total;       // row strips of the matrix
     int32_t ukr, ukc;        // uniform kept counts or -1
@@ -139,7 +140,7 @@ __global__ void __launch_bounds__(gemv_threads(B), (B == 1 ? 6 : 1)) bcr_spmv(Ge
     const int tid = threadIdx.x;
     const int64_t t = blockIdx.x;            // stored strip
     const int64_t mi = blockIdx.y;           // matrix of the group
-    const GemvGlobal d = to_global(p.table ? p.table[mi] : p.single);
+    const GemvGlobal d = to_global(p.table ? p.table[mi] : mi ? p.second : p.single);
     const GRIM_GLOBAL char *W = d.weights;
     const GRIM_GLOBAL T *x = (const GRIM_GLOBAL T *)p.x + mi * p.x_stride;
     GRIM_GLOBAL float *y = (GRIM_GLOBAL float *)p.y + mi * p.y_stride;
@@ -348,7 +349,7 @@ __global__ void __launch_bounds__(256) bcr_spmv_wave_exact(GemvParams p) {
     float *part = reinterpret_cast<float *>(wl);                  // reuses the weights' space
 
     const int64_t mi = blockIdx.y;
-    const GemvGlobal d = to_global(p.table ? p.table[mi] : p.single);
+    const GemvGlobal d = to_global(p.table ? p.table[mi] : mi ? p.second : p.single);
     const GRIM_GLOBAL char *W = d.weights;
     const GRIM_GLOBAL T *x = (const GRIM_GLOBAL T *)p.x + mi * p.x_stride;
     GRIM_GLOBAL float *y = (GRIM_GLOBAL float *)p.y + mi * p.y_stride;
@@ -656,7 +657,7 @@ __global__ void __launch_bounds__(512) bcr_spmv_wave_exact_b(GemvParams p) {
     float *ybuf = reinterpret_cast<float *>(wl + p.wbytes - 8 * 32 * 4);   // [8][32], behind weights and table
 
     const int64_t mi = blockIdx.y;
-    const GemvGlobal d = to_global(p.table ? p.table[mi] : p.single);
+    const GemvGlobal d = to_global(p.table ? p.table[mi] : mi ? p.second : p.single);
     const GRIM_GLOBAL char *W = d.weights;
     const GRIM_GLOBAL T *x = (const GRIM_GLOBAL T *)p.x + mi * p.x_stride;
     GRIM_GLOBAL float *y = (GRIM_GLOBAL float *)p.y + mi * p.y_stride;
@@ -933,7 +934,7 @@ static int wave_strips_per_wave(int64_t count, int64_t nbr, int max_sps) {
     return sps;
 }
 
-grim_status launch_spmv(const GemvDesc *table, const GemvDesc &single, int32_t count, int64_t M, int64_t K, int32_t BR,
+grim_status launch_spmv(const GemvDesc *table, const GemvDesc &single, const GemvDesc *second, int32_t count, int64_t M, int64_t K, int32_t BR,
                         int32_t BC, int32_t dtype, int32_t ukr, int32_t ukc, int32_t vec, int32_t krmax, int32_t kcmax,
                         const void *x, int64_t x_stride, int32_t batch, int64_t ldx, float *y, int64_t y_stride, int64_t ldy,
                         hipStream_t stream) {
@@ -941,11 +942,13 @@ grim_status launch_spmv(const GemvDesc *table, const GemvDesc &single, int32_t c
     const int esz = dtype_size(dtype);
     const int64_t nbr = M / BR;
     if (nbr > 0x7fffffff || count > 65535) return GRIM_ERR_SHAPE;
+    if (!table && count != (second ? 2 : 1)) return GRIM_ERR_SHAPE;
     if (krmax < 1) krmax = 1;
     if (kcmax < 1) kcmax = 1;
     GemvParams p;
     p.table = table;
     p.single = single;
+    p.second = second ? *second : single;
     p.BR = BR; p.BC = BC; p.nbc = (int32_t)(K / BC); p.K = (int32_t)K;
     p.nbr_total = (int32_t)nbr;
     p.sps = 1;

@@ -138,6 +138,53 @@ def test_sequence_of_steps(batch):
 
 
 @pytest.mark.gpu
+@pytest.mark.parametrize("batch,uniform,x_first", [(1, True, True), (1, False, False), (4, True, False), (8, False, True),
+                                                   (3, True, True)])
+def test_sequence_equal_widths_one_launch(batch, uniform, x_first):
+    """Input width = hidden width and at most 8 columns: both gate products leave in one launch, the hidden-side
+    operands addressed as the input-side ones plus a stride.  Both signs of the stride (x before h and after it in
+    memory, likewise the two results), uniformly and unevenly pruned matrices (different kernels)."""
+    from helpers import pack_workload, TOL
+    torch, dev, g = _gpu()
+    dtype, H, T = gen.F16, 96, 5
+    M, BR, BC = 3 * H, 16, 32
+    kept = (8, 12) if uniform else ((4, 8, 16), (8, 12, 20))
+    mi = gen.random_mask(M, H, BR, BC, kept[0], kept[1], seed=620)
+    mh = gen.random_mask(M, H, BR, BC, kept[0], kept[1], seed=621)
+    Wi = gen.normal_weights(M, H, dtype, seed=622) * np.float16(6.0)
+    Wh = gen.normal_weights(M, H, dtype, seed=623) * np.float16(6.0)
+    xs = [gen.normal_activations(H, batch, dtype, seed=624 + t) for t in range(T)]
+    rng = np.random.default_rng(625)
+    bi, bh = (0.1 * rng.standard_normal(M)).astype(np.float32), (0.1 * rng.standard_normal(M)).astype(np.float32)
+    Ai, Ah = pack_workload(g, Wi, dtype, mi), pack_workload(g, Wh, dtype, mh)
+    Wim = orc.masked_dense(gen.storage_to_f64(Wi, dtype), BR, BC, mi.row_ptr, mi.row_idx, mi.col_ptr, mi.col_idx)
+    Whm = orc.masked_dense(gen.storage_to_f64(Wh, dtype), BR, BC, mh.row_ptr, mh.row_idx, mh.col_ptr, mh.col_idx)
+    xh = torch.zeros((2, H, batch), dtype=torch.float16, device=dev)       # x and the state in one allocation
+    gates = torch.full((2, M, batch), float("nan"), dtype=torch.float32, device=dev)
+    xbuf, hbuf = (xh[0], xh[1]) if x_first else (xh[1], xh[0])
+    gi, gh = (gates[0], gates[1]) if x_first else (gates[1], gates[0])
+    h32 = torch.zeros((H, batch), dtype=torch.float32, device=dev)
+    bid, bhd = torch.from_numpy(bi).to(dev), torch.from_numpy(bh).to(dev)
+    stream = torch.cuda.current_stream()
+    h_ref = np.zeros((H, batch))
+    for t in range(T):
+        xbuf.copy_(torch.from_numpy(xs[t]).to(dev))
+        g.gru_step(Ai, Ah, xbuf, batch, hbuf, batch, batch, gi, batch, gh, batch, bid, bhd, h32, batch, hbuf, batch, stream)
+        torch.cuda.synchronize()
+        hin = h_ref.astype(np.float16).astype(np.float64)
+        gi_ref, gh_ref, h_ref = gru_ref.step(Wim, Whm, gen.storage_to_f64(xs[t], dtype), hin, bi, bh, h_ref)
+        assert np.abs(h32.cpu().numpy() - h_ref).max() <= 2 * TOL[dtype], f"h at step {t}"
+        assert np.abs(hbuf.float().cpu().numpy() - h_ref).max() <= 2 * TOL[dtype] + 2.0 ** -10
+    # the two products of the last step, element by element, against separate products of the same operands
+    gi2 = torch.empty((M, batch), dtype=torch.float32, device=dev)
+    g.spmv(Ai, xbuf, batch, batch, gi2, batch, stream)
+    torch.cuda.synchronize()
+    assert torch.equal(gi, gi2)                                # same kernel, same order of additions
+    assert np.abs(gi.cpu().numpy() - gi_ref).max() <= 2 * TOL[dtype] * np.abs(gi_ref).max()
+    assert np.abs(h_ref).max() > 0.05
+
+
+@pytest.mark.gpu
 def test_step_refusals():
     from helpers import pack_workload
     from paper_2108_11033_amd import GrimError
