@@ -561,6 +561,44 @@ __global__ void __launch_bounds__((NW + NP) * 64) bcr_spmm_mma(MmaParams p) {
 // group of strips), but only kept rows are fetched, and every compute unit has work even when
 // the tiles are few.
 // ------------------------------------------------------------------------------------------
+// Workgroup id -> (tile of columns, unit of the tile's work) for the kernels whose workgroups of one
+// tile fetch the same rows: ids are dealt to the 8 XCDs round-robin, each XCD has its own L2, so a
+// tile's units go to one XCD.  With that alone the last ntiles % 8 tiles (all of them when there
+// are fewer than 8: one tile for N <= 64) would leave XCDs idle, so each of those tiles is cut into
+// 2^shift interleaved parts, enough for a multiple of 8, and the parts are dealt instead.
+struct XcdMap {
+    int32_t per_tile;         // units per tile
+    int32_t tail_slot0;       // first slot (id / 8) of the tail tiles
+    int32_t tail_tile0;       // first tail tile, a multiple of 8
+    int32_t shift;            // tail tiles are cut into 1 << shift parts ...
+    int32_t per_part;         // ... of this many units
+};
+static XcdMap xcd_map(int32_t ntiles, int64_t per_tile, int64_t *nwg) {
+    XcdMap m;
+    const int32_t full = ntiles / 8, r = ntiles % 8;
+    m.per_tile = (int32_t)per_tile;
+    m.tail_slot0 = (int32_t)(full * per_tile);
+    m.tail_tile0 = full * 8;
+    m.shift = r == 0 ? 0 : r % 4 == 0 ? 1 : r % 2 == 0 ? 2 : 3;
+    m.per_part = (int32_t)((per_tile + (1 << m.shift) - 1) >> m.shift);
+    *nwg = 8 * (full * per_tile + (int64_t)((r << m.shift) / 8) * m.per_part);
+    return m;
+}
+// false: the workgroup has no tile
+__device__ __forceinline__ bool xcd_map_at(const XcdMap &m, int id, int ntiles, int *tile, int *unit) {
+    const int xcd = id & 7, slot = id >> 3;
+    if (slot < m.tail_slot0) {
+        *tile = (slot / m.per_tile) * 8 + xcd;
+        *unit = slot % m.per_tile;
+        return true;
+    }
+    const int s2 = slot - m.tail_slot0;
+    const int part = (s2 / m.per_part) * 8 + xcd;
+    *tile = m.tail_tile0 + (part >> m.shift);
+    *unit = ((s2 % m.per_part) << m.shift) + (part & ((1 << m.shift) - 1));
+    return *tile < ntiles;
+}
+
 struct GatherParams {
     const int32_t *sptr;
     const int32_t *out_row;   // original row of stored row t * 16 + m, -1 past the matrix
@@ -573,6 +611,7 @@ struct GatherParams {
     int32_t nbr, ntiles;      // nbr: 16-row runs of the stored row order
     int32_t usteps;           // > 0: steps of every run (sptr is not read)
     int32_t yvec;
+    XcdMap map;
 #ifdef GRIM_DBG
     long long *dbg;
 #endif
@@ -594,14 +633,12 @@ __global__ void __launch_bounds__(EIGHT ? 512 : 256, EIGHT ? 2 : 4) bcr_spmm_gat
     constexpr int NT = 4, TN = 64, PITCH = 128, CPR = 8;
     constexpr int SB = 4;                        // steps a wave has in flight
     extern __shared__ __attribute__((aligned(16))) char lds[];
-    // workgroup -> (tile, stored strip); all strips of a tile run on the same XCD
-    const int id = blockIdx.x;
-    const int xcd = id & 7, slot = id >> 3;
+    // workgroup -> (tile, stored strip, or four of them for SOLO)
     const int wave0 = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int per_tile = SOLO ? (p.nbr + 3) / 4 : p.nbr;          // workgroups per tile
-    const int tile = (slot / per_tile) * 8 + xcd;
-    const int t = SOLO ? (slot % per_tile) * 4 + wave0 : slot % per_tile;
-    if (tile >= p.ntiles || t >= p.nbr) return;                      // (SOLO has no barrier a wave could be missed at)
+    int tile, unit;
+    if (!xcd_map_at(p.map, blockIdx.x, p.ntiles, &tile, &unit)) return;
+    const int t = SOLO ? unit * 4 + wave0 : unit;
+    if (t >= p.nbr) return;                                           // (SOLO has no barrier a wave could be missed at)
     GATHER_STAMP(0);
     int64_t n0 = (int64_t)tile * TN;
     if (n0 + TN > p.N && p.N >= TN) n0 = p.N - TN;   // ragged last tile: overlap the neighbour (N % 4 == 0)
@@ -807,7 +844,9 @@ grim_status launch_spmm_gather(const grim_bcr_matrix *A, const void *X, int64_t 
     const bool solo = !narrow && A->gather.max_steps <= 8 && (int64_t)p.ntiles * p.nbr >= 1024;
     const bool eight = !narrow && !solo && A->gather.max_steps >= 16 && (int64_t)p.ntiles * p.nbr <= 256;
     const int64_t per_tile = solo ? (p.nbr + 3) / 4 : p.nbr;
-    const int64_t nwg = ((int64_t)p.ntiles + 7) / 8 * 8 * per_tile;
+    if (((int64_t)p.ntiles + 7) / 8 * 8 * per_tile > 0x7fffffff) return GRIM_ERR_SHAPE;
+    int64_t nwg = 0;
+    p.map = xcd_map(p.ntiles, per_tile, &nwg);
     if (nwg > 0x7fffffff) return GRIM_ERR_SHAPE;
 #ifdef GRIM_DBG
     p.dbg = reinterpret_cast<long long *>(getenv("GRIM_DBG_PTR") ? strtoull(getenv("GRIM_DBG_PTR"), nullptr, 0) : 0ull);
@@ -862,6 +901,7 @@ struct ConvParams {
     int32_t nbr, ntiles;
     int32_t usteps;              // > 0: steps of every run (sptr is not read)
     int32_t yvec;
+    XcdMap map;
 };
 
 // fp32 -> bf16, round to nearest even; NaN stays NaN
@@ -889,12 +929,9 @@ __global__ void __launch_bounds__(EIGHT ? 512 : 256, EIGHT ? 2 : 4) bcr_conv_gat
     extern __shared__ __attribute__((aligned(16))) char lds[];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int id = blockIdx.x;
-    const int xcd = id & 7, slot = id >> 3;
-    const int per_tile = SOLO ? (p.nbr + 3) / 4 : p.nbr;           // workgroups per tile
-    const int tile = (slot / per_tile) * 8 + xcd;
-    const int t_raw = SOLO ? (slot % per_tile) * 4 + wave : slot % per_tile;
-    if (tile >= p.ntiles) return;
+    int tile, unit;
+    if (!xcd_map_at(p.map, blockIdx.x, p.ntiles, &tile, &unit)) return;
+    const int t_raw = SOLO ? unit * 4 + wave : unit;
     const bool active = t_raw < p.nbr;           // SOLO: the last workgroup of a tile may have idle waves
     const int t = active ? t_raw : p.nbr - 1;
     int n0 = tile * TN;
@@ -1212,7 +1249,9 @@ grim_status launch_conv_gather(const grim_bcr_matrix *A, const void *F, int32_t 
     const bool solo = A->gather.max_steps <= 8 && (int64_t)p.ntiles * p.nbr >= 1024;
     const bool eight = !solo && A->gather.max_steps >= 16 && (int64_t)p.ntiles * p.nbr <= 256;
     const int64_t per_tile = solo ? (p.nbr + 3) / 4 : p.nbr;
-    const int64_t nwg = ((int64_t)p.ntiles + 7) / 8 * 8 * per_tile;
+    if (((int64_t)p.ntiles + 7) / 8 * 8 * per_tile > 0x7fffffff) return GRIM_ERR_SHAPE;
+    int64_t nwg = 0;
+    p.map = xcd_map(p.ntiles, per_tile, &nwg);
     if (nwg > 0x7fffffff) return GRIM_ERR_SHAPE;
     const size_t lds = (size_t)(eight ? 8 : 4) * 8192 + kConvTableBytes;
     const dim3 grid((unsigned)nwg), block(eight ? 512 : 256);
