@@ -148,7 +148,7 @@ grim_status grim_bcr_spmm_tuned(const grim_bcr_matrix *A, const void *X_dev, int
                                 int32_t kernel, void *hip_stream);
 
 /* grim_bcr_spmm_kernel_name -- which kernel family the grim_bcr_spmm_tuned call with these arguments
- * would launch: "bcr_spmm_gather", "bcr_spmm_mma" (staged), "bcr_spmm_fma", "bcr_spmv" (N <= 8), or
+ * would launch: "bcr_spmm_gather", "bcr_spmm_mma" (staged), "bcr_spmm_fma", "bcr_spmv" (N <= 8, but see grim_bcr_spmv), or
  * "none" when the call would fail.  A static string; launches nothing.  For profiling and reports. */
 const char *grim_bcr_spmm_kernel_name(const grim_bcr_matrix *A, const void *X_dev, int64_t N, int64_t ldx,
                                       int32_t tile_n, int32_t strips_per_wg, int32_t kernel);
@@ -158,7 +158,10 @@ const char *grim_bcr_spmm_kernel_name(const grim_bcr_matrix *A, const void *X_de
  * gate matrices are matrix-vector products).  Same conventions as grim_bcr_spmm with
  * N = batch: x_dev is K x batch (ldx >= batch), y_dev is M x batch fp32 (ldy >= batch).
  * Reads the compact weights exactly once; the bytes moved are the stored weights plus
- * 8 bytes of row/column bit masks per block.
+ * 8 bytes of row/column bit masks per block.  One case runs on the matrix cores instead, as
+ * one padded tile of the row-gathering SpMM kernel, because that is quicker: batch = 8 of an
+ * fp16 / bf16 matrix that kernel takes, with ldx a multiple of 8 and x_dev 16-byte aligned
+ * (grim_bcr_spmm with N = 8 makes the same choice; grim_bcr_spmm_kernel_name reports it).
  * Errors: as grim_bcr_spmm; batch outside 1..8 is GRIM_ERR_SHAPE.
  */
 grim_status grim_bcr_spmv(const grim_bcr_matrix *A, const void *x_dev, int32_t batch, int64_t ldx,

@@ -57,6 +57,13 @@ def test_c3_lstm_gates_spmv(g, batch):
     # spmm with N <= 8 reaches the same kernel and the same bits
     y2 = run_spmm(g, A, wl.X, wl.dtype, wl.M, batch)
     assert y2.tobytes() == y.tobytes()
+    if batch == 8:
+        # 8 columns in 16-byte-aligned rows ran on the matrix-core kernel; the SpMV kernel takes the same
+        # product when the rows are not 16-byte aligned
+        X = to_device(wl.X, wl.dtype)
+        assert g.spmm_kernel_name(A, X, 8, 8) == "bcr_spmm_gather"
+        y3 = run_spmv(g, A, wl.X, wl.dtype, wl.M, batch, ldx=12, ldy=9)
+        assert_close(y3, yref, S, wl.dtype, "c3 batch=8 on the SpMV kernel")
 
 
 @pytest.mark.parametrize("layer", range(13))
@@ -226,7 +233,13 @@ def test_spmv_nonuniform_all_batches(g, dtype, batch):
     y = run_spmv(g, A, x, dtype, M, batch)
     assert_close(y, yref, S, dtype, f"spmv {dtype} b={batch}")
     y2 = run_spmv(g, A, x, dtype, M, batch, ldx=batch + 3, ldy=batch + 1)
-    assert y2.tobytes() == y.tobytes()
+    if batch == 8 and dtype != gen.F32:
+        # 8 columns in 16-byte-aligned rows went to the matrix-core kernel, padded rows go to the SpMV kernel:
+        # two orders of addition; the SpMV kernel's own bits must not depend on the padding
+        assert_close(y2, yref, S, dtype, f"spmv {dtype} b={batch}, padded rows")
+        assert run_spmv(g, A, x, dtype, M, batch, ldx=batch + 4, ldy=batch).tobytes() == y2.tobytes()
+    else:
+        assert y2.tobytes() == y.tobytes()
 
 
 @pytest.mark.parametrize("BR,BC", [(8, 16), (16, 8), (32, 24), (4, 32)])
@@ -394,7 +407,9 @@ def test_kernel_choice_follows_the_cost_model(g):
     assert g.spmm_kernel_name(A, X, 200, 200) == "bcr_spmm_gather"
     assert g.spmm_kernel_name(A, X, 200, 200, kernel=2) == "bcr_spmm_mma"
     assert g.spmm_kernel_name(A, X, 200, 200, tile_n=64) == "bcr_spmm_mma"
-    assert g.spmm_kernel_name(A, X, 8, 200) == "bcr_spmv"
+    assert g.spmm_kernel_name(A, X, 4, 200) == "bcr_spmv"
+    assert g.spmm_kernel_name(A, X, 8, 200) == "bcr_spmm_gather"      # 8 columns in 16-byte-aligned rows: one padded tile
+    assert g.spmm_kernel_name(A, X, 8, 204) == "bcr_spmv"             # rows 8-byte aligned only
     assert g.spmm_kernel_name(A, X, 199, 200) == "bcr_spmm_mma"       # rows not 8-byte aligned
     assert g.spmm_kernel_name(A, X, 200, 200, kernel=1) == "bcr_spmm_fma"
     assert g.spmm_kernel_name(A, X, 200, 100) == "none"               # ldx < N
@@ -524,7 +539,8 @@ def test_spmv_batched_matches_single_calls(g, batch):
     y = yd.cpu().numpy()
     for i in range(count):
         assert_close(y[i], refs[i][0], refs[i][1], dtype, f"batched {i}")
-        yi = run_spmv(g, mats[i], xs[i], dtype, M, batch)
+        # (a leading dimension that is no multiple of 8 keeps the single call on the SpMV kernels at batch 8)
+        yi = run_spmv(g, mats[i], xs[i], dtype, M, batch, ldx=batch + 4)
         assert yi.tobytes() == y[i].tobytes()
 
 
