@@ -322,6 +322,22 @@ def test_gather_kernel_shapes(g, dtype, N, ldx_pad, ldy_pad):
     assert Y2.tobytes() == Y.tobytes()
 
 
+def test_gather_kernel_every_tile_count_around_the_xcd_count(g):
+    """1 to 17 tiles: the tiles past the last multiple of 8 are cut into 2, 4 or 8 sets of strips (here 5 strips, so the
+    sets are uneven and some are empty) and dealt to the XCDs; every (tile, strip) must be computed exactly once."""
+    dtype = gen.F16
+    M, K, BR, BC = 80, 256, 16, 32
+    mask = gen.random_mask(M, K, BR, BC, (4, 8, 16), (4, 8, 12), seed=340)
+    W = gen.normal_weights(M, K, dtype, seed=341)
+    A = pack_workload(g, W, dtype, mask)
+    Xall = gen.normal_activations(K, 64 * 17, dtype, seed=342)
+    Yall, Sall = oracle_product(W, Xall, dtype, mask)
+    for tiles in range(1, 18):
+        N = 64 * tiles - (4 if tiles % 3 == 0 else 0)
+        Y = run_spmm(g, A, Xall[:, :N].copy(), dtype, M, N, kernel=3)
+        assert_close(Y, Yall[:, :N], Sall[:, :N], dtype, f"gather, {tiles} tiles")
+
+
 @pytest.mark.parametrize("dtype,N", [(gen.F16, 44820), (gen.BF16, 44808)])
 def test_gather_kernel_wave_per_strip(g, dtype, N):
     """Strips of a few steps and thousands of (tile, strip) pairs (the first layers of a CNN at full resolution): every
