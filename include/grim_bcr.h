@@ -18,6 +18,11 @@
  * otherwise, pointers named *_host are host memory and *_dev are device memory
  * on the GPU that was current when the matrix was packed.  The library never
  * takes ownership of caller memory.
+ *
+ * Threads: a packed matrix is immutable; any number of threads may launch products of the
+ * same matrix on streams of their own (kernels write only the caller's outputs, and there is
+ * no workspace shared between calls).  Calls that create or free a handle must not run at
+ * the same time as any other call that uses that handle.
  */
 #ifndef GRIM_BCR_H
 #define GRIM_BCR_H
@@ -197,7 +202,8 @@ void grim_bcr_group_free(grim_bcr_group *G);
  * The result equals grim_bcr_spmm on the materialised im2col matrix (bit for bit when every sum is
  * exact); only the feature map is read -- kh * kw times fewer bytes -- and only the rows a strip keeps.
  * Runs on the row-gathering matrix-core kernel: fp16 / bf16, block height a divisor or a multiple of
- * 16, 64 <= H * W < 2^24, W >= 8, kh * kw <= 16, Cin * H * W <= 2^26; otherwise GRIM_ERR_UNSUPPORTED.
+ * 16, H * W < 2^24 (maps of any shape down to 1 x 1: fewer than 64 positions run as one partly
+ * filled tile), kh * kw <= 16, 8 <= Cin * H * W <= 2^26; otherwise GRIM_ERR_UNSUPPORTED.
  * Errors: NULL, SHAPE (even kernel, K != Cin * kh * kw, ldy < H * W, sizes < 1), DEVICE, UNSUPPORTED.
  */
 grim_status grim_bcr_conv2d(const grim_bcr_matrix *A, const void *F_dev, int32_t Cin, int32_t H, int32_t W,

@@ -17,6 +17,8 @@
 //    Accumulation is fp32, order fixed, no atomics.
 #include <hip/hip_runtime.h>
 
+#include <atomic>
+
 #include <cstdlib>
 #include <type_traits>
 
@@ -935,7 +937,8 @@ __global__ void __launch_bounds__(EIGHT ? 512 : 256, EIGHT ? 2 : 4) bcr_conv_gat
     const bool active = t_raw < p.nbr;           // SOLO: the last workgroup of a tile may have idle waves
     const int t = active ? t_raw : p.nbr - 1;
     int n0 = tile * TN;
-    if (n0 + TN > p.N) n0 = p.N - TN;            // ragged last tile: overlap the neighbour (N >= 64)
+    if (n0 + TN > p.N) n0 = p.N - TN;            // ragged last tile: overlap the neighbour
+    n0 = n0 < 0 ? 0 : n0;                        // a map of fewer than 64 positions: one tile, its columns past N never stored
 
     // one dependent memory round trip less at the start when every run has the same number of steps
     const int g0 = p.usteps ? t * p.usteps : p.sptr[t], nst = p.usteps ? p.usteps : p.sptr[t + 1] - g0;
@@ -971,7 +974,7 @@ __global__ void __launch_bounds__(EIGHT ? 512 : 256, EIGHT ? 2 : 4) bcr_conv_gat
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
                 int h = h0, w = w0 + j;
-                if (w >= p.W) { w -= p.W; ++h; }     // W >= 8: a window wraps once at most
+                while (w >= p.W) { w -= p.W; ++h; }  // once at most for W >= 8 (positions past N, of a small map: h >= H, never stored)
                 const bool ok = h + dr >= 0 && h + dr < p.H && w + dq >= 0 && w + dq < p.W;
                 m[j >> 1] |= ok ? (j & 1 ? 0xffff0000u : 0x0000ffffu) : 0u;
             }
@@ -1048,7 +1051,7 @@ __global__ void __launch_bounds__(EIGHT ? 512 : 256, EIGHT ? 2 : 4) bcr_conv_gat
                 const int tap = (int)(kk - __umul24(cin, (unsigned int)p.KK));
                 const unsigned int r = __umul24((unsigned int)tap, (unsigned int)p.kw_magic) >> 8;   // tap / kw
                 // r * W + (tap - r * kw), less the centre tap's offset, for the tile's first column
-                const int eb = (int)(__umul24(cin, (unsigned int)HW) + __umul24(r, (unsigned int)wstep)) + tap + nshift0;
+                const int eb = (int)__umul24(cin, (unsigned int)HW) + __mul24((int)r, wstep) + tap + nshift0;   // (W < kw: wstep < 0)
                 pk[u] = (unsigned int)(is_pad ? p.KK : tap) << 27 | (unsigned int)(eb + (1 << 25));
                 // A 16-byte load at an odd element (2 bytes off a dword) costs about three aligned ones in the
                 // vector L1, a load that is only dword-aligned next to nothing.  A window that starts at an odd
@@ -1164,13 +1167,15 @@ __global__ void __launch_bounds__(EIGHT ? 512 : 256, EIGHT ? 2 : 4) bcr_conv_gat
             if (p.relu) sum[e] = sum[e] > 0.f ? sum[e] : 0.f;     // NaN stays NaN
         }
         const bool vec = p.yvec == 4 && (n & 3) == 0;
+        const int left = (int)(p.N - n);             // below 4 only in the one tile of a map of fewer than 64 positions
         if (p.odt == GRIM_F32) {
             float *dst = static_cast<float *>(p.Y) + row * p.ldy + n;
-            if (vec) {
+            if (vec && left >= 4) {
                 *reinterpret_cast<f32x4 *>(dst) = sum;
             } else {
 #pragma unroll
-                for (int e = 0; e < 4; ++e) dst[e] = sum[e];
+                for (int e = 0; e < 4; ++e)
+                    if (e < left) dst[e] = sum[e];
             }
         } else {
             unsigned short h[4];
@@ -1184,11 +1189,12 @@ __global__ void __launch_bounds__(EIGHT ? 512 : 256, EIGHT ? 2 : 4) bcr_conv_gat
                 }
             }
             unsigned short *dst = static_cast<unsigned short *>(p.Y) + row * p.ldy + n;
-            if (vec) {
+            if (vec && left >= 4) {
                 *reinterpret_cast<uint2 *>(dst) = uint2{(unsigned int)h[0] | ((unsigned int)h[1] << 16), (unsigned int)h[2] | ((unsigned int)h[3] << 16)};
             } else {
 #pragma unroll
-                for (int e = 0; e < 4; ++e) dst[e] = h[e];
+                for (int e = 0; e < 4; ++e)
+                    if (e < left) dst[e] = h[e];
             }
         }
     };
@@ -1220,7 +1226,7 @@ grim_status launch_conv_gather(const grim_bcr_matrix *A, const void *F, int32_t 
                                int32_t kw, const float *bias, int32_t relu, void *Y, int32_t odt, int64_t ldy,
                                hipStream_t stream) {
     const int64_t N = (int64_t)H * W, total = (int64_t)Cin * N;
-    if (!A->gather.present || N < 64 || W < 8 || kh * kw > kConvMaxTaps || total > (int64_t(1) << 26) || (int64_t)(kh / 2) * W + kw / 2 >= (1 << 24) ||
+    if (!A->gather.present || total < 8 || kh * kw > kConvMaxTaps || total > (int64_t(1) << 26) || (int64_t)(kh / 2) * W + kw / 2 >= (1 << 24) ||
         A->K > (int64_t(1) << 27) || Cin >= (1 << 24) || N >= (1 << 24) || reinterpret_cast<uintptr_t>(F) % 2 != 0)
         return GRIM_ERR_UNSUPPORTED;
     ConvParams p;
@@ -1297,7 +1303,7 @@ static grim_status launch_mma_inst(const MmaParams &p, hipStream_t stream) {
     const int64_t nwg = tiles8 * p.ngroups;
     if (nwg > 0x7fffffff) return GRIM_ERR_SHAPE;
     auto kern = bcr_spmm_mma<BF16, BR, NT, SPW, NW, 8, SX, SR>;
-    static bool attr_done = false;    // raising a kernel's LDS limit is needed once per process
+    static std::atomic<bool> attr_done{false};    // raising a kernel's LDS limit is needed once per process
     if (lds > 64 * 1024 && !attr_done) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess) {
             (void)hipGetLastError();

@@ -19,6 +19,8 @@
 // Strips too large for LDS are processed in segments of column blocks.
 #include <hip/hip_runtime.h>
 
+#include <atomic>
+
 #include <cstdlib>
 
 #include "bcr_matrix.hpp"
@@ -598,7 +600,7 @@ __global__ void __launch_bounds__(256) bcr_spmv_wave_exact(GemvParams p) {
 template <int DT, int KR, int KC>
 static grim_status launch_exact_inst(const GemvParams &p, dim3 grid, size_t lds, hipStream_t stream) {
     auto kern = bcr_spmv_wave_exact<DT, KR, KC>;
-    static bool attr_done = false;
+    static std::atomic<bool> attr_done{false};
     if (lds > 64 * 1024 && !attr_done) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess) {
             (void)hipGetLastError();
@@ -856,7 +858,7 @@ __global__ void __launch_bounds__(512) bcr_spmv_wave_exact_b(GemvParams p) {
 template <int DT, int KR, int KC>
 static grim_status launch_exact_b_inst(const GemvParams &p, dim3 grid, int threads, size_t lds, hipStream_t stream) {
     auto kern = bcr_spmv_wave_exact_b<DT, KR, KC>;
-    static bool attr_done = false;
+    static std::atomic<bool> attr_done{false};
     if (lds > 64 * 1024 && !attr_done) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess) {
             (void)hipGetLastError();
@@ -890,7 +892,7 @@ static grim_status launch_vec(const GemvParams &p, int vec, dim3 grid, size_t ld
 #define GRIM_GEMV(V)                                                                                          \
     {                                                                                                         \
         auto kern = bcr_spmv<DT, B, V>;                                                                       \
-        static bool attr_done = false;                                                                        \
+        static std::atomic<bool> attr_done{false};                                                                        \
         if (lds > 64 * 1024 && !attr_done) {                                                                  \
             if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess) { \
                 (void)hipGetLastError();                                                                      \

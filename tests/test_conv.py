@@ -161,6 +161,39 @@ def test_conv_random_geometries():
 
 
 @pytest.mark.gpu
+@pytest.mark.parametrize("Cin,H,W,kh,kw,BC", [
+    (32, 7, 7, 3, 3, 32),       # 7 x 7, the last stage of an ImageNet ResNet: 49 positions, one partly filled tile
+    (64, 7, 7, 1, 1, 32),
+    (32, 4, 4, 3, 3, 32),
+    (16, 2, 2, 3, 3, 16),       # narrower and lower than the kernel
+    (16, 1, 1, 3, 3, 16),       # one position: only the centre tap is ever valid
+    (16, 1, 9, 1, 3, 16),
+    (32, 30, 3, 3, 3, 32),      # rows of 3: a piece of 8 positions spans three or four image rows
+    (24, 13, 5, 5, 3, 8),
+    (16, 50, 2, 3, 5, 16),      # 100 positions, rows narrower than the kernel
+])
+def test_conv_small_and_narrow_maps(Cin, H, W, kh, kw, BC):
+    """Maps of fewer than 64 positions (one tile whose columns past H * W are never stored) and image rows shorter than a
+    piece of 8 positions or than the kernel; integer data, exact.  Also through the layer epilogue with a padded fp16
+    output, where nothing past a row's H * W positions may be written."""
+    import paper_2108_11033_amd as g
+    from helpers import pack_workload
+    dtype, M = gen.F16, 48
+    K = Cin * kh * kw
+    mask = gen.random_mask(M, K, 16, BC, (0, 5, 16), tuple(sorted({1, BC // 2, BC})), seed=770 + H * W)
+    Wt = gen.small_int_values((M, K), dtype, seed=771)
+    F = gen.small_int_values((Cin, H, W), dtype, seed=772 + H)
+    A = pack_workload(g, Wt, dtype, mask)
+    Yref = conv_ref.conv_same(_masked(Wt, dtype, mask), gen.storage_to_f64(F, dtype), kh, kw)
+    Y = _run(g, A, F, dtype, M, Cin, H, W, kh, kw, ldy=H * W + 5)
+    assert np.array_equal(Y.astype(np.float64), Yref), (Cin, H, W, kh, kw)
+    bias = np.arange(M, dtype=np.float32) - 20.0
+    out = _run_act(g, A, F, dtype, M, Cin, H, W, kh, kw, bias, True, gen.F16, ldo=H * W + 3)
+    ref = np.maximum(Yref + bias[:, None, None], 0.0)
+    assert np.array_equal(out.astype(np.float64), ref.astype(np.float16).astype(np.float64)), (Cin, H, W, kh, kw)
+
+
+@pytest.mark.gpu
 def test_conv_integer_data_is_exact_and_equals_the_im2col_product():
     """Small integers: every sum is exact, so the fused path, the library's own product on the materialised
     im2col matrix and the reference must agree bit for bit."""
@@ -302,10 +335,10 @@ def test_conv_refusals():
     Y = torch.full((256, 64), 5.0, dtype=torch.float32, device=dev)
     for args, name in (((255, 8, 8, 3, 3), "GRIM_ERR_SHAPE"),      # Cin * kh * kw != K
                        ((256, 8, 8, 2, 2), "GRIM_ERR_SHAPE"),      # even kernel
-                       ((256, 4, 8, 3, 3), "GRIM_ERR_UNSUPPORTED"),  # fewer than 64 positions
-                       ((256, 16, 4, 3, 3), "GRIM_ERR_UNSUPPORTED")):  # image rows shorter than 8
+                       ((256, 0, 8, 3, 3), "GRIM_ERR_SHAPE"),      # empty map
+                       ((2304, 8, 8, 1, 1), "GRIM_ERR_SHAPE")):    # output row shorter than the map is checked below
         with pytest.raises(GrimError) as e:
-            g.conv2d(A, F, *args, Y, 64)
+            g.conv2d(A, F, *args, Y, 64 if args[0] != 2304 else 63)
         assert e.value.name == name, args
     torch.cuda.synchronize()
     assert (Y == 5.0).all()
