@@ -898,7 +898,7 @@ struct ConvParams {
     int32_t odt, relu;           // element type of Y; max(., 0) after the bias
     int32_t N, H, W, kh, kw;     // N = H * W
     int32_t KK, kk_magic;        // kh * kw and ceil(2^31 / KK): k / KK = umulhi(2 k, magic) for k < 2^27, KK <= 16
-    int32_t kw_magic;            // ceil(256 / kw): tap / kw = tap * magic >> 8 for tap < 16
+    int32_t kw_magic;            // ceil(256 / kw): tap / kw = tap * magic >> 8 (checked for every tap at launch)
     int32_t total;               // elements of the feature map
     int32_t nbr, ntiles;
     int32_t usteps;              // > 0: steps of every run (sptr is not read)
@@ -918,7 +918,7 @@ struct __attribute__((packed, aligned(4))) ConvWindow {
     unsigned int d[4];
 };
 
-constexpr int kConvMaxTaps = 16;
+constexpr int kConvMaxTaps = 31;   // 5 bits of the packed (tap, window start) word, one value left for padding slots
 constexpr int kConvTableBytes = (kConvMaxTaps + 1) * 8 * 16;   // validity masks, behind the waves' step buffers
 
 // SOLO, EIGHT: as in the row-gathering kernel -- a (tile, strip) pair per wave for strips of a few steps, eight
@@ -1245,6 +1245,8 @@ grim_status launch_conv_gather(const grim_bcr_matrix *A, const void *F, int32_t 
     p.KK = kh * kw;
     p.kk_magic = (int32_t)(uint32_t)(((uint64_t(1) << 31) + p.KK - 1) / p.KK);
     p.kw_magic = (256 + kw - 1) / kw;
+    for (int tap = 0; tap < p.KK; ++tap)
+        if (((tap * p.kw_magic) >> 8) != tap / kw) return GRIM_ERR_UNSUPPORTED;   // (1 x 25 and the like)
     p.total = (int32_t)total;
     p.nbr = (int32_t)A->gather.nstrips;
     p.usteps = A->gather.usteps;

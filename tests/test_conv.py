@@ -171,6 +171,9 @@ def test_conv_random_geometries():
     (32, 30, 3, 3, 3, 32),      # rows of 3: a piece of 8 positions spans three or four image rows
     (24, 13, 5, 5, 3, 8),
     (16, 50, 2, 3, 5, 16),      # 100 positions, rows narrower than the kernel
+    (16, 11, 12, 5, 5, 16),     # 25 taps
+    (16, 9, 10, 3, 7, 16),      # 21 taps
+    (32, 6, 20, 1, 9, 32),
 ])
 def test_conv_small_and_narrow_maps(Cin, H, W, kh, kw, BC):
     """Maps of fewer than 64 positions (one tile whose columns past H * W are never stored) and image rows shorter than a
@@ -340,5 +343,11 @@ def test_conv_refusals():
         with pytest.raises(GrimError) as e:
             g.conv2d(A, F, *args, Y, 64 if args[0] != 2304 else 63)
         assert e.value.name == name, args
+    # 25 taps in one kernel row: the division of the tap number by the kernel width is not exact in the kernel's form
+    m25 = gen.random_mask(32, 32 * 25, 16, 32, 8, 8, seed=790)
+    A25 = pack_workload(g, gen.normal_weights(32, 32 * 25, gen.F16, seed=791), gen.F16, m25)
+    with pytest.raises(GrimError) as e:
+        g.conv2d(A25, F, 32, 8, 8, 1, 25, Y, 64)
+    assert e.value.name == "GRIM_ERR_UNSUPPORTED"
     torch.cuda.synchronize()
     assert (Y == 5.0).all()
