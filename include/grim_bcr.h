@@ -265,8 +265,9 @@ grim_status grim_bcr_lstm_step(const grim_bcr_matrix *A, const void *xh_dev, int
  *             hidden-side product reads.  May be NULL.
  * grim_bcr_gru_step = the two products (x_dev: I x batch, hin_dev: H x batch, both of the matrices'
  * element type; any batch >= 1: up to 8 columns run on the SpMV kernels, more on the SpMM kernels;
- * W_i and W_h of one shape and block size, equal leading dimensions and at most 8 columns: one
- * launch computes both products)
+ * with equal leading dimensions on both sides one launch computes both products -- on the SpMV
+ * kernels for W_i and W_h of one shape and block size, on the row-gathering SpMM kernel for 4 to 60
+ * columns in multiples of 4)
  * into gi_dev and gh_dev, then grim_gru_cell writing hout_dev (may be hin_dev itself: the cell runs
  * after both products).  Both only enqueue work on hip_stream.  Errors: NULL, SHAPE (rows not 3H on
  * both, Ah->K != H, batch < 1, leading dimension too small), DTYPE (element types differ), DEVICE,

@@ -168,8 +168,12 @@ grim_status launch_spmm_mma(const grim_bcr_matrix *A, const void *X, int64_t N, 
                             int64_t ldy, int32_t tile_n, int32_t strips_per_wg, hipStream_t stream);
 bool mma_supported(const grim_bcr_matrix *A);
 // row-gathering matrix-core kernel; GRIM_ERR_UNSUPPORTED when the matrix or the operands do not qualify
+// A2 / X2 / Y2: a second product of the same N, ldx and ldy in the same launch (gather_pair_applies)
 grim_status launch_spmm_gather(const grim_bcr_matrix *A, const void *X, int64_t N, int64_t ldx, float *Y,
-                               int64_t ldy, hipStream_t stream);
+                               int64_t ldy, hipStream_t stream, const grim_bcr_matrix *A2 = nullptr,
+                               const void *X2 = nullptr, float *Y2 = nullptr);
+bool gather_pair_applies(const grim_bcr_matrix *A, const void *X, const grim_bcr_matrix *A2, const void *X2, int64_t N,
+                         int64_t ldx);
 bool gather_applies(const grim_bcr_matrix *A, const void *X, int64_t N, int64_t ldx);
 // convolution on the row-gathering layout, the im2col matrix never formed
 grim_status launch_conv_gather(const grim_bcr_matrix *A, const void *F, int32_t Cin, int32_t H, int32_t W, int32_t kh,

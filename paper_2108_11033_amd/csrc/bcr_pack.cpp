@@ -750,14 +750,21 @@ grim_status grim_bcr_gru_step(const grim_bcr_matrix *Ai, const grim_bcr_matrix *
     const int esz = dtype_size(Ai->dtype);
     const ptrdiff_t xd = static_cast<const char *>(hin_dev) - static_cast<const char *>(x_dev);
     const ptrdiff_t yd = reinterpret_cast<const char *>(gh_dev) - reinterpret_cast<const char *>(gi_dev);
-    if (batch <= 8 && Ai->K == Ah->K && Ai->BR == Ah->BR && Ai->BC == Ah->BC && gemv_ok(Ai, batch) && gemv_ok(Ah, batch) &&
-        ldx == ldhin && ldgi == ldgh && xd % esz == 0 && yd % 4 == 0) {
+    // (8 columns in 16-byte-aligned rows are quicker on the matrix cores, as for a lone product)
+    const bool eight_on_matrix_cores = ldx == ldhin && ldgi == ldgh && skinny_on_matrix_cores(Ai, x_dev, batch, ldx) &&
+                                       skinny_on_matrix_cores(Ah, hin_dev, batch, ldx) &&
+                                       gather_pair_applies(Ai, x_dev, Ah, hin_dev, batch, ldx);
+    if (!eight_on_matrix_cores && batch <= 8 && Ai->K == Ah->K && Ai->BR == Ah->BR && Ai->BC == Ah->BC && gemv_ok(Ai, batch) &&
+        gemv_ok(Ah, batch) && ldx == ldhin && ldgi == ldgh && xd % esz == 0 && yd % 4 == 0) {
         const GemvDesc di = desc_of(Ai), dh = desc_of(Ah);
         const bool same = Ai->gemv.uniform_kr == Ah->gemv.uniform_kr && Ai->gemv.uniform_kc == Ah->gemv.uniform_kc;
         st = launch_spmv(nullptr, di, &dh, 2, Ai->M, Ai->K, Ai->BR, Ai->BC, Ai->dtype, same ? Ai->gemv.uniform_kr : -1,
                          same ? Ai->gemv.uniform_kc : -1, std::min(Ai->gemv.vec, Ah->gemv.vec),
                          std::max(Ai->gemv.krmax, Ah->gemv.krmax), std::max(Ai->gemv.kcmax, Ah->gemv.kcmax), x_dev, xd / esz,
                          batch, ldx, gi_dev, yd / 4, ldgi, static_cast<hipStream_t>(hip_stream));
+    } else if (ldx == ldhin && ldgi == ldgh && gather_pair_applies(Ai, x_dev, Ah, hin_dev, batch, ldx)) {
+        // 4 .. 60 columns on the matrix cores: one launch of the row-gathering kernel, grid.y = product
+        st = launch_spmm_gather(Ai, x_dev, batch, ldx, gi_dev, ldgi, static_cast<hipStream_t>(hip_stream), Ah, hin_dev, gh_dev);
     } else {
         st = grim_bcr_spmm(Ai, x_dev, batch, ldx, gi_dev, ldgi, hip_stream);
         if (st == GRIM_OK) st = grim_bcr_spmm(Ah, hin_dev, batch, ldhin, gh_dev, ldgh, hip_stream);

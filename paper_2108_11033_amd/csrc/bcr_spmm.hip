@@ -601,6 +601,18 @@ __device__ __forceinline__ bool xcd_map_at(const XcdMap &m, int id, int ntiles, 
     return *tile < ntiles;
 }
 
+// the second product of a two-product launch (N < 64 form only; grid.y = 2)
+struct GatherSecond {
+    const int32_t *sptr;
+    const int32_t *out_row;
+    const uint32_t *rows;
+    const uint32_t *desc;
+    const unsigned char *payload;
+    const unsigned short *X;
+    float *Y;
+    int32_t usteps;
+};
+
 struct GatherParams {
     const int32_t *sptr;
     const int32_t *out_row;   // original row of stored row t * 16 + m, -1 past the matrix
@@ -614,6 +626,7 @@ struct GatherParams {
     int32_t usteps;           // > 0: steps of every run (sptr is not read)
     int32_t yvec;
     XcdMap map;
+    GatherSecond second;
 #ifdef GRIM_DBG
     long long *dbg;
 #endif
@@ -641,6 +654,19 @@ __global__ void __launch_bounds__(EIGHT ? 512 : 256, EIGHT ? 2 : 4) bcr_spmm_gat
     if (!xcd_map_at(p.map, blockIdx.x, p.ntiles, &tile, &unit)) return;
     const int t = SOLO ? unit * 4 + wave0 : unit;
     if (t >= p.nbr) return;                                           // (SOLO has no barrier a wave could be missed at)
+    // the matrix and operands of this workgroup: grid.y = 1 selects the second product of a two-product launch
+    const int32_t *sptr = p.sptr, *out_row = p.out_row;
+    const uint32_t *rows = p.rows, *desc = p.desc;
+    const unsigned char *payload = p.payload;
+    const unsigned short *X = p.X;
+    float *Y = p.Y;
+    int usteps = p.usteps;
+    if constexpr (NARROW) {
+        if (blockIdx.y) {
+            sptr = p.second.sptr; out_row = p.second.out_row; rows = p.second.rows; desc = p.second.desc;
+            payload = p.second.payload; X = p.second.X; Y = p.second.Y; usteps = p.second.usteps;
+        }
+    }
     GATHER_STAMP(0);
     int64_t n0 = (int64_t)tile * TN;
     if (n0 + TN > p.N && p.N >= TN) n0 = p.N - TN;   // ragged last tile: overlap the neighbour (N % 4 == 0)
@@ -649,7 +675,7 @@ __global__ void __launch_bounds__(EIGHT ? 512 : 256, EIGHT ? 2 : 4) bcr_spmm_gat
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     // one dependent memory round trip less at the start when every run has the same number of steps
-    const int g0 = p.usteps ? t * p.usteps : p.sptr[t], nst = p.usteps ? p.usteps : p.sptr[t + 1] - g0;
+    const int g0 = usteps ? t * usteps : sptr[t], nst = usteps ? usteps : sptr[t + 1] - g0;
     const int s_beg = SOLO ? g0 : g0 + (int)((int64_t)nst * wave / NWV);
     const int s_end = SOLO ? g0 + nst : g0 + (int)((int64_t)nst * (wave + 1) / NWV);
     char *buf = lds + wave * 8192;               // two step buffers of 32 rows x 128 bytes
@@ -657,7 +683,7 @@ __global__ void __launch_bounds__(EIGHT ? 512 : 256, EIGHT ? 2 : 4) bcr_spmm_gat
     // fetch side: lane = (row slot rs, 16-byte piece c); its i-th load is k slot i * 8 + rs
     const int rs = lane >> 3, c = lane & 7;
     const bool in_a = !NARROW || c * 8 < p.N, in_b = !NARROW || c * 8 + 4 < p.N;
-    const unsigned short *xcol = p.X + n0 + (in_a ? c * 8 : 0);
+    const unsigned short *xcol = X + n0 + (in_a ? c * 8 : 0);
     const int boff = in_b ? 4 : 0;               // second half of a piece (8-byte aligned rows)
     int wr_off[4];
 #pragma unroll
@@ -677,11 +703,11 @@ __global__ void __launch_bounds__(EIGHT ? 512 : 256, EIGHT ? 2 : 4) bcr_spmm_gat
     f32x4 acc[NT];
 #pragma unroll
     for (int q = 0; q < NT; ++q) acc[q] = f32x4{0.f, 0.f, 0.f, 0.f};
-    const int orow = p.out_row[(int64_t)t * 16 + (lane & 15)];   // asked for now, needed at the very end
+    const int orow = out_row[(int64_t)t * 16 + (lane & 15)];     // asked for now, needed at the very end
 
-    const u32x4 *rows4 = reinterpret_cast<const u32x4 *>(p.rows);
-    const uint2 *desc2 = reinterpret_cast<const uint2 *>(p.desc);
-    const i16x8 *pay = reinterpret_cast<const i16x8 *>(p.payload);
+    const u32x4 *rows4 = reinterpret_cast<const u32x4 *>(rows);
+    const uint2 *desc2 = reinterpret_cast<const uint2 *>(desc);
+    const i16x8 *pay = reinterpret_cast<const i16x8 *>(payload);
     // Row numbers and descriptor of the first step of the next batch are asked for together with
     // the current batch's, so that a wave whose steps do not fit one batch (18 steps over 4 waves:
     // 4 + 1) starts the rows of X of the next batch without another dependent round trip.
@@ -763,7 +789,7 @@ __global__ void __launch_bounds__(EIGHT ? 512 : 256, EIGHT ? 2 : 4) bcr_spmm_gat
             for (int q = 0; q < NT; ++q) {
                 const int64_t n = n0 + q * 16 + 4 * (lane >> 4);
                 if (n < p.N) {
-                    float *dst = p.Y + row * p.ldy + n;
+                    float *dst = Y + row * p.ldy + n;
                     if (p.yvec == 4) {
                         *reinterpret_cast<f32x4 *>(dst) = acc[q];
                     } else {
@@ -796,7 +822,7 @@ __global__ void __launch_bounds__(EIGHT ? 512 : 256, EIGHT ? 2 : 4) bcr_spmm_gat
     const int64_t row = orow;
     const int64_t n = n0 + q * 16 + 4 * (lane >> 4);
     if (row >= 0 && n < p.N) {                   // n, N multiples of 4: all four columns or none
-        float *dst = p.Y + row * p.ldy + n;
+        float *dst = Y + row * p.ldy + n;
         if (p.yvec == 4) {
             *reinterpret_cast<f32x4 *>(dst) = sum;
         } else {
@@ -824,9 +850,18 @@ double gather_cost(const grim_bcr_matrix *A, int64_t N) {
     return (nwg > 256.0 ? nwg / 256.0 : 1.0) * per_wg + (nwg > 1024.0 ? nwg / 1024.0 : 1.0) * 30e3;
 }
 
+// Two products Y = A X and Y2 = A2 X2 of fewer than 64 columns in one launch (the two gate products of a GRU step):
+// same element type, number of 16-row runs, N and leading dimensions; K may differ.
+bool gather_pair_applies(const grim_bcr_matrix *A, const void *X, const grim_bcr_matrix *A2, const void *X2, int64_t N,
+                         int64_t ldx) {
+    return N < 64 && gather_applies(A, X, N, ldx) && gather_applies(A2, X2, N, ldx) && A->dtype == A2->dtype &&
+           A->gather.nstrips == A2->gather.nstrips;
+}
+
 grim_status launch_spmm_gather(const grim_bcr_matrix *A, const void *X, int64_t N, int64_t ldx, float *Y, int64_t ldy,
-                               hipStream_t stream) {
+                               hipStream_t stream, const grim_bcr_matrix *A2, const void *X2, float *Y2) {
     if (!gather_applies(A, X, N, ldx)) return GRIM_ERR_UNSUPPORTED;
+    if (A2 && !gather_pair_applies(A, X, A2, X2, N, ldx)) return GRIM_ERR_UNSUPPORTED;
     GatherParams p;
     p.sptr = A->gather.d_sptr;
     p.rows = A->gather.d_rows;
@@ -840,6 +875,12 @@ grim_status launch_spmm_gather(const grim_bcr_matrix *A, const void *X, int64_t 
     p.usteps = A->gather.usteps;
     p.ntiles = (int32_t)((N + 63) / 64);
     p.yvec = (reinterpret_cast<uintptr_t>(Y) % 16 == 0 && ldy % 4 == 0 && N % 4 == 0) ? 4 : 1;
+    p.second = GatherSecond{p.sptr, p.out_row, p.rows, p.desc, p.payload, p.X, p.Y, p.usteps};
+    if (A2) {
+        p.second = GatherSecond{A2->gather.d_sptr, A2->gather.d_out_row, A2->gather.d_rows, A2->gather.d_desc,
+                                A2->gather.d_payload, static_cast<const unsigned short *>(X2), Y2, A2->gather.usteps};
+        if (reinterpret_cast<uintptr_t>(Y2) % 16 != 0) p.yvec = 1;
+    }
     // strips of at most 8 steps (two batches of a wave) with enough (tile, strip) pairs to fill the GPU: wave per pair;
     // long strips and fewer workgroups than compute units: eight waves per strip
     const bool narrow = N < 64;
@@ -854,8 +895,9 @@ grim_status launch_spmm_gather(const grim_bcr_matrix *A, const void *X, int64_t 
     p.dbg = reinterpret_cast<long long *>(getenv("GRIM_DBG_PTR") ? strtoull(getenv("GRIM_DBG_PTR"), nullptr, 0) : 0ull);
 #endif
     const size_t lds = (eight ? 8 : 4) * 8192;
-    const bool wide = N % 8 == 0 && ldx % 8 == 0 && reinterpret_cast<uintptr_t>(X) % 16 == 0;
-    const dim3 grid((unsigned)nwg), block(eight ? 512 : 256);
+    const bool wide = N % 8 == 0 && ldx % 8 == 0 && reinterpret_cast<uintptr_t>(X) % 16 == 0 &&
+                      (!A2 || reinterpret_cast<uintptr_t>(X2) % 16 == 0);
+    const dim3 grid((unsigned)nwg, A2 ? 2u : 1u), block(eight ? 512 : 256);
 #define GRIM_GATHER(BF, WD, NR, SO, EI) hipLaunchKernelGGL((bcr_spmm_gather<BF, WD, NR, SO, EI>), grid, block, lds, stream, p)
 #define GRIM_GATHER_DT(BF)                                                                                         \
     if (narrow) { if (wide) GRIM_GATHER(BF, true, true, false, false); else GRIM_GATHER(BF, false, true, false, false); }        \
