@@ -99,11 +99,12 @@ def test_cell_kernel(dtype, batch, pad):
 
 
 @pytest.mark.gpu
-@pytest.mark.parametrize("batch", [1, 4, 32])
+@pytest.mark.parametrize("batch", [1, 4, 12, 32, 60, 64])
 def test_sequence_of_steps(batch):
     """T steps of a GRU layer whose two gate matrices are BCR-pruned; the cell writes the new state in fp16 into the
     buffer the next step's hidden-side product reads.  Batch 32 (the paper's GRU measurement) runs the products on the
-    SpMM kernels, 1 and 4 on the SpMV kernels."""
+    SpMM kernels -- 4 to 60 columns as one launch for both products (12: rows of X not 16-byte aligned), 64 as two --,
+    1 on the SpMV kernels."""
     from helpers import to_device, pack_workload, TOL
     torch, dev, g = _gpu()
     dtype, I, H, T = gen.F16, 64, 96, 6
