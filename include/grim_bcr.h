@@ -239,9 +239,10 @@ grim_status grim_bcr_conv2d_act(const grim_bcr_matrix *A, const void *F_dev, int
  *   h_dev       H x batch of element type dt (ldh), written; typically the h part of the next step's
  *               input vector.  May be NULL.
  *   h32_dev     optional fp32 copy of h (ldh32); NULL to skip
- * grim_bcr_lstm_step = grim_bcr_spmv(A, xh_dev, ...) into gates_dev, then grim_lstm_cell; A must have
- * 4H rows.  Both only enqueue work on hip_stream.  Errors: NULL, SHAPE (batch outside 1..8 for the
- * step, H < 1, leading dimension too small, A->M != 4H), DTYPE, DEVICE, UNSUPPORTED.
+ * grim_bcr_lstm_step = grim_bcr_spmv(A, xh_dev, ...) (more than 8 columns: grim_bcr_spmm) into
+ * gates_dev, then grim_lstm_cell; A must have 4H rows.  Both only enqueue work on hip_stream.
+ * Errors: NULL, SHAPE (batch < 1, H < 1, leading dimension too small, A->M != 4H), DTYPE, DEVICE,
+ * UNSUPPORTED.
  */
 grim_status grim_lstm_cell(const float *gates_dev, int64_t ldg, const float *bias_dev, float *c_dev, int64_t ldc,
                            void *h_dev, grim_dtype dt, int64_t ldh, float *h32_dev, int64_t ldh32,

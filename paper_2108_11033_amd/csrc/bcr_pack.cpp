@@ -715,8 +715,9 @@ grim_status grim_bcr_lstm_step(const grim_bcr_matrix *A, const void *xh_dev, int
     if (!A || !xh_dev || !gates_dev || !c_dev) return GRIM_ERR_NULL;
     if (A->M % 4 != 0) return GRIM_ERR_SHAPE;
     const int64_t H = A->M / 4;
-    if (batch < 1 || batch > 8 || ldc < batch || (h_dev && ldh < batch) || (h32_dev && ldh32 < batch)) return GRIM_ERR_SHAPE;
-    grim_status st = grim_bcr_spmv(A, xh_dev, batch, ldx, gates_dev, ldg, hip_stream);
+    if (batch < 1 || ldc < batch || (h_dev && ldh < batch) || (h32_dev && ldh32 < batch)) return GRIM_ERR_SHAPE;
+    grim_status st = batch <= 8 ? grim_bcr_spmv(A, xh_dev, batch, ldx, gates_dev, ldg, hip_stream)
+                                : grim_bcr_spmm(A, xh_dev, batch, ldx, gates_dev, ldg, hip_stream);
     if (st != GRIM_OK) return st;
     return grim_lstm_cell(gates_dev, ldg, bias_dev, c_dev, ldc, h_dev, (grim_dtype)A->dtype, ldh, h32_dev, ldh32, H, batch,
                           hip_stream);

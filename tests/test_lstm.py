@@ -92,7 +92,7 @@ def test_cell_kernel(dtype, batch, pad):
 
 
 @pytest.mark.gpu
-@pytest.mark.parametrize("batch", [1, 4])
+@pytest.mark.parametrize("batch", [1, 4, 8, 32])
 def test_sequence_of_steps(batch):
     """T steps of an LSTM layer whose gate matrix [W_ih | W_hh] is BCR-pruned: h is written by the cell straight into
     the lower part of the next step's input vector.  fp16 weights and activations, fp32 state."""
