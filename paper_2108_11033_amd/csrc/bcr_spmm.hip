@@ -833,6 +833,14 @@ __global__ void __launch_bounds__(EIGHT ? 512 : 256, EIGHT ? 2 : 4) bcr_spmm_gat
     GATHER_STAMP(6);
 }
 
+// Wave per (tile, strip) instead of four waves splitting a strip's steps: strips of at most 8 steps (two batches of a
+// wave) with enough pairs to fill the GPU, and longer strips once there are half as many pairs again (measured: 9 steps
+// x 1568 pairs 11.3 -> 10.4 us, 18 steps x 12544 pairs 144 -> 129 us; 18 steps x 784 pairs 11.1 -> 12.9 us)
+// (the convolution kernel, with more work per step: 9 x 1568 15.4 -> 16.3 us, 18 x 12544 138 -> 113 us; it asks for 4096)
+static bool gather_wave_per_strip(const grim_bcr_matrix *A, int64_t pairs, int64_t pairs_for_long_strips = 1536) {
+    return (A->gather.max_steps <= 8 && pairs >= 1024) || (A->gather.max_steps <= 40 && pairs >= pairs_for_long_strips);
+}
+
 bool gather_applies(const grim_bcr_matrix *A, const void *X, int64_t N, int64_t ldx) {
     return A->gather.present && N >= 4 && N % 4 == 0 && ldx % 4 == 0 && reinterpret_cast<uintptr_t>(X) % 8 == 0;
 }
@@ -884,7 +892,7 @@ grim_status launch_spmm_gather(const grim_bcr_matrix *A, const void *X, int64_t 
     // strips of at most 8 steps (two batches of a wave) with enough (tile, strip) pairs to fill the GPU: wave per pair;
     // long strips and fewer workgroups than compute units: eight waves per strip
     const bool narrow = N < 64;
-    const bool solo = !narrow && A->gather.max_steps <= 8 && (int64_t)p.ntiles * p.nbr >= 1024;
+    const bool solo = !narrow && gather_wave_per_strip(A, (int64_t)p.ntiles * p.nbr);
     const bool eight = !narrow && !solo && A->gather.max_steps >= 16 && (int64_t)p.ntiles * p.nbr <= 256;
     const int64_t per_tile = solo ? (p.nbr + 3) / 4 : p.nbr;
     if (((int64_t)p.ntiles + 7) / 8 * 8 * per_tile > 0x7fffffff) return GRIM_ERR_SHAPE;
@@ -1296,7 +1304,7 @@ grim_status launch_conv_gather(const grim_bcr_matrix *A, const void *F, int32_t 
     // four consecutive outputs of a row in one store: 16 bytes of fp32, 8 bytes of fp16 / bf16
     p.yvec = (reinterpret_cast<uintptr_t>(Y) % (odt == GRIM_F32 ? 16 : 8) == 0 && ldy % 4 == 0 && N % 4 == 0) ? 4 : 1;
     // the same launch forms as the row-gathering kernel
-    const bool solo = A->gather.max_steps <= 8 && (int64_t)p.ntiles * p.nbr >= 1024;
+    const bool solo = gather_wave_per_strip(A, (int64_t)p.ntiles * p.nbr, 4096);
     const bool eight = !solo && A->gather.max_steps >= 16 && (int64_t)p.ntiles * p.nbr <= 256;
     const int64_t per_tile = solo ? (p.nbr + 3) / 4 : p.nbr;
     if (((int64_t)p.ntiles + 7) / 8 * 8 * per_tile > 0x7fffffff) return GRIM_ERR_SHAPE;

@@ -197,6 +197,23 @@ def test_conv_small_and_narrow_maps(Cin, H, W, kh, kw, BC):
 
 
 @pytest.mark.gpu
+def test_conv_wave_per_strip_long_strips():
+    """Nine steps per strip and 4096 (tile, strip) pairs (a 256 x 256 map, 64 output channels): every wave takes a
+    pair of its own and runs three batches of steps.  Integer data, exact, every entry."""
+    import paper_2108_11033_amd as g
+    from helpers import pack_workload
+    dtype, Cin, H, W, M = gen.F16, 32, 256, 256, 64
+    K = Cin * 9
+    mask = gen.random_mask(M, K, 16, 32, (4, 8, 16), 32, seed=780)       # every column kept: 9 steps in every strip
+    Wt = gen.small_int_values((M, K), dtype, seed=781)
+    F = gen.small_int_values((Cin, H, W), dtype, seed=782)
+    A = pack_workload(g, Wt, dtype, mask)
+    Yref = conv_ref.conv_same(_masked(Wt, dtype, mask), gen.storage_to_f64(F, dtype), 3, 3)
+    Y = _run(g, A, F, dtype, M, Cin, H, W, 3, 3)
+    assert np.array_equal(Y.astype(np.float64), Yref)
+
+
+@pytest.mark.gpu
 def test_conv_integer_data_is_exact_and_equals_the_im2col_product():
     """Small integers: every sum is exact, so the fused path, the library's own product on the materialised
     im2col matrix and the reference must agree bit for bit."""

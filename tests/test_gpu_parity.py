@@ -363,6 +363,31 @@ def test_gather_kernel_wave_per_strip(g, dtype, N):
     assert run_spmm(g, A, X, dtype, M, N, kernel=3).tobytes() == Y.tobytes()
 
 
+def test_gather_kernel_wave_per_strip_long_strips(g):
+    """Strips of more than 8 steps take the wave-per-pair form from 1536 (tile, strip) pairs on: a wave then runs
+    several batches of steps on its own.  Non-uniform blocks (4 to 22 steps per strip), 3 strips (one idle wave per
+    workgroup), 520 tiles with a ragged last one; every entry checked."""
+    dtype, N = gen.F16, 64 * 520 - 12
+    M, K, BR, BC = 48, 32 * 22, 16, 32
+    mask = gen.random_mask(M, K, BR, BC, (3, 8, 16), (4, 16, 32), seed=350)
+    # strip 1 keeps every column of every block: 22 steps
+    nbc = K // BC
+    keep_r, keep_c = [], []
+    for b in range((M // BR) * nbc):
+        r = mask.row_idx[mask.row_ptr[b]:mask.row_ptr[b + 1]]
+        c = mask.col_idx[mask.col_ptr[b]:mask.col_ptr[b + 1]]
+        if b // nbc == 1:
+            c = np.arange(BC, dtype=c.dtype)
+        keep_r.append(r); keep_c.append(c)
+    mask = gen.mask_from_sets(M, K, BR, BC, keep_r, keep_c)
+    W = gen.normal_weights(M, K, dtype, seed=351)
+    X = gen.normal_activations(K, N, dtype, seed=352, relu=True)
+    A = pack_workload(g, W, dtype, mask)
+    Yref, S = oracle_product(W, X, dtype, mask)
+    Y = run_spmm(g, A, X, dtype, M, N, kernel=3)
+    assert_close(Y, Yref, S, dtype, "gather, wave per strip, long strips")
+
+
 def test_gather_kernel_c2_and_refusals(g):
     wl = gen.c2_vgg_conv(3136)
     A = pack_workload(g, wl.W, wl.dtype, wl.mask)
