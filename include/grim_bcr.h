@@ -132,6 +132,8 @@ grim_status grim_bcr_arrays(const grim_bcr_matrix *A, grim_bcr_view *v);
  *          it never synchronises and never allocates.
  * Accumulation is in fp32 in a fixed order (no atomics): results are bit-reproducible
  * from run to run.  N <= 8 is forwarded to the SpMV kernel when that path supports A.
+ * A large product may be enqueued as two kernels on disjoint column ranges (the columns that
+ * fill whole rounds of workgroups, then the rest).
  * Errors: NULL, SHAPE (N < 1, ld too small), DEVICE, UNSUPPORTED.  Y is untouched on error.
  */
 grim_status grim_bcr_spmm(const grim_bcr_matrix *A, const void *X_dev, int64_t N, int64_t ldx,

@@ -630,7 +630,20 @@ grim_status grim_bcr_spmm_tuned(const grim_bcr_matrix *A, const void *X_dev, int
                                A->gemv.vec, A->gemv.krmax, A->gemv.kcmax, X_dev, 0, (int32_t)N, ldx, Y_dev, 0, ldy, stream);
         }
         case ROUTE_GATHER: return launch_spmm_gather(A, X_dev, N, ldx, Y_dev, ldy, stream);
-        case ROUTE_MMA: return launch_spmm_mma(A, X_dev, N, ldx, Y_dev, ldy, tile_n, strips_per_wg, stream);
+        case ROUTE_MMA: {
+            if (kernel == 0 && tile_n == 0 && strips_per_wg == 0) {
+                // whole rounds of workgroups on the staged kernel, the few columns left over on whatever suits them
+                int tn = 0, g = 0;
+                const int64_t n_main = mma_whole_rounds(A, N, &tn, &g);
+                if (n_main < N) {
+                    st = launch_spmm_mma(A, X_dev, n_main, ldx, Y_dev, ldy, tn, g, stream);
+                    if (st != GRIM_OK) return st;
+                    const char *x_rest = static_cast<const char *>(X_dev) + n_main * dtype_size(A->dtype);
+                    return grim_bcr_spmm_tuned(A, x_rest, N - n_main, ldx, Y_dev + n_main, ldy, 0, 0, 0, hip_stream);
+                }
+            }
+            return launch_spmm_mma(A, X_dev, N, ldx, Y_dev, ldy, tile_n, strips_per_wg, stream);
+        }
         case ROUTE_FMA: return launch_spmm_fma(A, X_dev, N, ldx, Y_dev, ldy, stream);
         case ROUTE_NONE: break;
     }

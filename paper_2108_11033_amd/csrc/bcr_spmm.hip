@@ -1411,6 +1411,27 @@ double mma_best_shape(const grim_bcr_matrix *A, int64_t N, int32_t tile_n, int32
     return best;
 }
 
+// The staged kernel's workgroups are large (one or two fit a compute unit), so a launch runs in rounds of that many
+// workgroups and a few left over cost a whole round: 784 tiles on 256 compute units take 4 rounds for 3.06 rounds of
+// work.  When the last round would be at most a quarter full, returns the number of leading columns that fill whole
+// rounds (a multiple of the tile width) and the launch shape for them; the caller sends the remaining columns through
+// the kernel choice of their own.  Returns N when there is nothing to split off.
+int64_t mma_whole_rounds(const grim_bcr_matrix *A, int64_t N, int *tn_out, int *g_out) {
+    int tn = 0, g = 0;
+    if (mma_best_shape(A, N, 0, 0, &tn, &g) < 0) return N;
+    *tn_out = tn; *g_out = g;
+    const int64_t ntiles = (N + tn - 1) / tn, ngroups = (A->nbr + g - 1) / g;
+    const int64_t lds = 2 * (int64_t)mma_stage_bytes(A->mma.chunk_rows, tn * 2, amax_of(A, g)) + (int64_t)A->mma.nchunks * (g + 1) * 8;
+    const int threads = ((g == 4 ? 4 : 8) + 8) * 64;
+    int64_t per_cu = 160 * 1024 / lds;
+    if (per_cu > 2048 / threads) per_cu = 2048 / threads;
+    if (per_cu < 1) per_cu = 1;
+    const int64_t slots = 256 * per_cu, nwg = ntiles * ngroups;
+    const int64_t full = nwg / slots * slots, rest = nwg - full;
+    if (full == 0 || rest == 0 || rest > slots / 4 || full % ngroups != 0) return N;
+    return full / ngroups * tn;
+}
+
 grim_status launch_spmm_mma(const grim_bcr_matrix *A, const void *X, int64_t N, int64_t ldx, float *Y, int64_t ldy,
                             int32_t tile_n, int32_t strips_per_wg, hipStream_t stream) {
     if (!A->mma.present) return GRIM_ERR_UNSUPPORTED;

@@ -93,6 +93,30 @@ def test_c5_full_size_sampled(g):
     assert np.isfinite(Y).all()
 
 
+@pytest.mark.parametrize("ragged", [20, 21])
+def test_staged_kernel_whole_rounds_and_a_remainder(g, ragged):
+    """Free kernel choice at a size where the staged kernel's workgroups would leave a nearly empty last round: the
+    leading columns that fill whole rounds run on the staged kernel, the rest as a product of their own (the
+    row-gathering kernel when the remainder is a multiple of 4 columns, else the staged one again).  Sampled rows x the
+    columns around the cut, both ends and a random sample."""
+    torch, dev = torch_dev()
+    wl0 = gen.c2_vgg_conv(64)
+    A = pack_workload(g, wl0.W, wl0.dtype, wl0.mask)
+    probe = torch.empty(16, dtype=torch.float16, device=dev)              # only the address is looked at
+    tiles = next((t for t in (259, 515, 771) if g.spmm_kernel_name(A, probe, 64 * t - ragged, 64 * t - ragged) == "bcr_spmm_mma"), None)
+    assert tiles is not None, "the staged kernel is never chosen for this matrix"
+    N, cut = 64 * tiles - ragged, 64 * (tiles - 3)
+    X = gen.normal_activations(wl0.K, N, wl0.dtype, seed=95, relu=True)
+    Y = run_spmm(g, A, X, wl0.dtype, wl0.M, N)
+    rng = np.random.default_rng(96)
+    rows = np.sort(rng.choice(wl0.M, 40, replace=False))
+    cols = np.unique(np.concatenate([np.arange(0, 70), np.arange(cut - 70, cut + 70), np.arange(N - 70, N),
+                                     rng.choice(N, 200, replace=False)]))
+    Yref, S = oracle_product(wl0.W, X, wl0.dtype, wl0.mask, rows=rows, cols=cols)
+    assert_close(Y[np.ix_(rows, cols)], Yref, S, wl0.dtype, f"whole rounds + remainder, N={N}")
+    assert np.isfinite(Y).all()
+
+
 # ------------------------------------------------------------------ launch shapes and kernels
 @pytest.mark.parametrize("dtype,BR", [(gen.F16, 16), (gen.BF16, 16), (gen.F16, 32), (gen.BF16, 32)])
 @pytest.mark.parametrize("tile_n,strips", [(32, 4), (32, 16), (64, 4), (64, 8), (64, 16), (128, 4), (128, 8)])
