@@ -182,7 +182,7 @@ grim_status launch_conv_gather(const grim_bcr_matrix *A, const void *F, int32_t 
 // cost estimates (bytes through one compute unit) used to choose between the two matrix-core kernels
 double gather_cost(const grim_bcr_matrix *A, int64_t N);
 double mma_best_shape(const grim_bcr_matrix *A, int64_t N, int32_t tile_n, int32_t strips_per_wg, int *tn_out, int *g_out);
-int64_t mma_whole_rounds(const grim_bcr_matrix *A, int64_t N, int *tn_out, int *g_out);
+int64_t mma_whole_rounds(const grim_bcr_matrix *A, int64_t N, bool rest_may_gather, int *tn_out, int *g_out);
 // matrices of one launch: a device table of `count` descriptors, or (no table) `single` alone, or
 // `single` and `*second` (count = 2)
 grim_status launch_spmv(const GemvDesc *table_dev_or_null, const GemvDesc &single, const GemvDesc *second, int32_t count,

@@ -634,7 +634,9 @@ grim_status grim_bcr_spmm_tuned(const grim_bcr_matrix *A, const void *X_dev, int
             if (kernel == 0 && tile_n == 0 && strips_per_wg == 0) {
                 // whole rounds of workgroups on the staged kernel, the few columns left over on whatever suits them
                 int tn = 0, g = 0;
-                const int64_t n_main = mma_whole_rounds(A, N, &tn, &g);
+                // (whether the rest may take the row-gathering kernel hangs on N and the alignment of X alone: the cut
+                // is a multiple of 32 columns)
+                const int64_t n_main = mma_whole_rounds(A, N, gather_applies(A, X_dev, N, ldx), &tn, &g);
                 if (n_main < N) {
                     st = launch_spmm_mma(A, X_dev, n_main, ldx, Y_dev, ldy, tn, g, stream);
                     if (st != GRIM_OK) return st;

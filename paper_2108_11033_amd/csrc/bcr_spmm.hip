@@ -1413,12 +1413,14 @@ double mma_best_shape(const grim_bcr_matrix *A, int64_t N, int32_t tile_n, int32
 
 // The staged kernel's workgroups are large (one or two fit a compute unit), so a launch runs in rounds of that many
 // workgroups and a few left over cost a whole round: 784 tiles on 256 compute units take 4 rounds for 3.06 rounds of
-// work.  When the last round would be at most a quarter full, returns the number of leading columns that fill whole
-// rounds (a multiple of the tile width) and the launch shape for them; the caller sends the remaining columns through
-// the kernel choice of their own.  Returns N when there is nothing to split off.
-int64_t mma_whole_rounds(const grim_bcr_matrix *A, int64_t N, int *tn_out, int *g_out) {
+// work.  Returns the number of leading columns that fill whole rounds (a multiple of the tile width) and the launch
+// shape for them when, by the cost model that also picks the kernel, these plus the remaining columns as a product of
+// their own (on the row-gathering kernel if `rest_may_gather`, else staged again) come cheaper than one launch; the
+// caller sends the remaining columns through the kernel choice.  Returns N when there is nothing to gain.
+int64_t mma_whole_rounds(const grim_bcr_matrix *A, int64_t N, bool rest_may_gather, int *tn_out, int *g_out) {
     int tn = 0, g = 0;
-    if (mma_best_shape(A, N, 0, 0, &tn, &g) < 0) return N;
+    const double cost_all = mma_best_shape(A, N, 0, 0, &tn, &g);
+    if (cost_all < 0) return N;
     *tn_out = tn; *g_out = g;
     const int64_t ntiles = (N + tn - 1) / tn, ngroups = (A->nbr + g - 1) / g;
     const int64_t lds = 2 * (int64_t)mma_stage_bytes(A->mma.chunk_rows, tn * 2, amax_of(A, g)) + (int64_t)A->mma.nchunks * (g + 1) * 8;
@@ -1428,8 +1430,17 @@ int64_t mma_whole_rounds(const grim_bcr_matrix *A, int64_t N, int *tn_out, int *
     if (per_cu < 1) per_cu = 1;
     const int64_t slots = 256 * per_cu, nwg = ntiles * ngroups;
     const int64_t full = nwg / slots * slots, rest = nwg - full;
-    if (full == 0 || rest == 0 || rest > slots / 4 || full % ngroups != 0) return N;
-    return full / ngroups * tn;
+    if (full == 0 || rest == 0 || full % ngroups != 0) return N;
+    const int64_t n_main = full / ngroups * tn, n_rest = N - n_main;
+    int t2 = 0, g2 = 0;
+    const double cost_main = mma_best_shape(A, n_main, tn, g, &t2, &g2);
+    double cost_rest = mma_best_shape(A, n_rest, 0, 0, &t2, &g2);
+    if (rest_may_gather && A->gather.present) {
+        const double c = gather_cost(A, n_rest);
+        if (cost_rest < 0 || c < cost_rest) cost_rest = c;
+    }
+    if (cost_main < 0 || cost_rest < 0 || cost_main + cost_rest > 0.97 * cost_all) return N;
+    return n_main;
 }
 
 grim_status launch_spmm_mma(const grim_bcr_matrix *A, const void *X, int64_t N, int64_t ldx, float *Y, int64_t ldy,
