@@ -563,6 +563,11 @@ __global__ void __launch_bounds__((NW + NP) * 64) bcr_spmm_mma(MmaParams p) {
 // group of strips), but only kept rows are fetched, and every compute unit has work even when
 // the tiles are few.
 // ------------------------------------------------------------------------------------------
+// Waves that split a long strip's steps in the few-workgroups form (template flag EIGHT).  A 36-step strip of a 14 x 14
+// layer: 8 waves of the row-gathering kernel (4 steps per batch) 7.66 us, 12 waves 7.63, 16 waves 8.56; the convolution
+// kernel (3 steps per batch) 11.0 us with 8, 8.6 us with 12 -- every wave then needs one batch only --, 9.7 us with 16.
+constexpr int kGatherLongWaves = 8, kConvLongWaves = 12;
+
 // Workgroup id -> (tile of columns, unit of the tile's work) for the kernels whose workgroups of one
 // tile fetch the same rows: ids are dealt to the 8 XCDs round-robin, each XCD has its own L2, so a
 // tile's units go to one XCD.  With that alone the last ntiles % 8 tiles (all of them when there
@@ -643,8 +648,8 @@ struct GatherParams {
 // (tile, strip) of its own, four consecutive strips per workgroup: no split of K, no partial tiles, no barrier
 // EIGHT: eight waves split a strip's steps instead of four (few workgroups, long strips: the 14 x 14 layers)
 template <bool BF16, bool WIDE, bool NARROW, bool SOLO, bool EIGHT>
-__global__ void __launch_bounds__(EIGHT ? 512 : 256, EIGHT ? 2 : 4) bcr_spmm_gather(GatherParams p) {
-    constexpr int NWV = EIGHT ? 8 : 4;          // waves of the workgroup
+__global__ void __launch_bounds__(EIGHT ? kGatherLongWaves * 64 : 256, EIGHT ? 1024 / (kGatherLongWaves * 64) : 4) bcr_spmm_gather(GatherParams p) {
+    constexpr int NWV = EIGHT ? kGatherLongWaves : 4;          // waves of the workgroup
     constexpr int NT = 4, TN = 64, PITCH = 128, CPR = 8;
     constexpr int SB = 4;                        // steps a wave has in flight
     extern __shared__ __attribute__((aligned(16))) char lds[];
@@ -902,11 +907,24 @@ grim_status launch_spmm_gather(const grim_bcr_matrix *A, const void *X, int64_t 
 #ifdef GRIM_DBG
     p.dbg = reinterpret_cast<long long *>(getenv("GRIM_DBG_PTR") ? strtoull(getenv("GRIM_DBG_PTR"), nullptr, 0) : 0ull);
 #endif
-    const size_t lds = (eight ? 8 : 4) * 8192;
+    const size_t lds = (eight ? kGatherLongWaves : 4) * 8192;
     const bool wide = N % 8 == 0 && ldx % 8 == 0 && reinterpret_cast<uintptr_t>(X) % 16 == 0 &&
                       (!A2 || reinterpret_cast<uintptr_t>(X2) % 16 == 0);
-    const dim3 grid((unsigned)nwg, A2 ? 2u : 1u), block(eight ? 512 : 256);
-#define GRIM_GATHER(BF, WD, NR, SO, EI) hipLaunchKernelGGL((bcr_spmm_gather<BF, WD, NR, SO, EI>), grid, block, lds, stream, p)
+    const dim3 grid((unsigned)nwg, A2 ? 2u : 1u), block(eight ? kGatherLongWaves * 64 : 256);
+#define GRIM_GATHER(BF, WD, NR, SO, EI)                                                                              \
+    do {                                                                                                             \
+        auto kern = bcr_spmm_gather<BF, WD, NR, SO, EI>;                                                             \
+        static std::atomic<bool> attr_done{false};   /* raising a kernel's LDS limit is needed once per process */  \
+        if (lds > 64 * 1024 && !attr_done) {                                                                         \
+            if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, \
+                                    160 * 1024) != hipSuccess) {                                                     \
+                (void)hipGetLastError();                                                                             \
+                return GRIM_ERR_DEVICE;                                                                              \
+            }                                                                                                        \
+            attr_done = true;                                                                                        \
+        }                                                                                                            \
+        hipLaunchKernelGGL(kern, grid, block, lds, stream, p);                                                       \
+    } while (0)
 #define GRIM_GATHER_DT(BF)                                                                                         \
     if (narrow) { if (wide) GRIM_GATHER(BF, true, true, false, false); else GRIM_GATHER(BF, false, true, false, false); }        \
     else if (solo) { if (wide) GRIM_GATHER(BF, true, false, true, false); else GRIM_GATHER(BF, false, false, true, false); }     \
@@ -947,7 +965,7 @@ struct ConvParams {
     int64_t ldy;
     int32_t odt, relu;           // element type of Y; max(., 0) after the bias
     int32_t N, H, W, kh, kw;     // N = H * W
-    int32_t KK, kk_magic;        // kh * kw and ceil(2^31 / KK): k / KK = umulhi(2 k, magic) for k < 2^27, KK <= 16
+    int32_t KK, kk_magic;        // kh * kw and ceil(2^31 / KK): k / KK = umulhi(2 k, magic) while k * KK < 2^31 (checked at launch)
     int32_t kw_magic;            // ceil(256 / kw): tap / kw = tap * magic >> 8 (checked for every tap at launch)
     int32_t total;               // elements of the feature map
     int32_t nbr, ntiles;
@@ -974,10 +992,10 @@ constexpr int kConvTableBytes = (kConvMaxTaps + 1) * 8 * 16;   // validity masks
 // SOLO, EIGHT: as in the row-gathering kernel -- a (tile, strip) pair per wave for strips of a few steps, eight
 // waves per strip for long strips with few workgroups
 template <bool BF16, bool SOLO, bool EIGHT>
-__global__ void __launch_bounds__(EIGHT ? 512 : 256, EIGHT ? 2 : 4) bcr_conv_gather(ConvParams p) {
+__global__ void __launch_bounds__(EIGHT ? kConvLongWaves * 64 : 256, EIGHT ? 1024 / (kConvLongWaves * 64) : 4) bcr_conv_gather(ConvParams p) {
     constexpr int NT = 4, TN = 64, PITCH = 128, CPR = 8;
     constexpr int SB = 3;                        // steps a wave has in flight
-    constexpr int NWV = EIGHT ? 8 : 4;           // waves of the workgroup
+    constexpr int NWV = EIGHT ? kConvLongWaves : 4;   // waves of the workgroup
     extern __shared__ __attribute__((aligned(16))) char lds[];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -1277,7 +1295,7 @@ grim_status launch_conv_gather(const grim_bcr_matrix *A, const void *F, int32_t 
                                hipStream_t stream) {
     const int64_t N = (int64_t)H * W, total = (int64_t)Cin * N;
     if (!A->gather.present || total < 8 || kh * kw > kConvMaxTaps || total > (int64_t(1) << 26) || (int64_t)(kh / 2) * W + kw / 2 >= (1 << 24) ||
-        A->K > (int64_t(1) << 27) || Cin >= (1 << 24) || N >= (1 << 24) || reinterpret_cast<uintptr_t>(F) % 2 != 0)
+        A->K > (int64_t(1) << 27) || A->K * (int64_t)(kh * kw) > (int64_t(1) << 31) || Cin >= (1 << 24) || N >= (1 << 24) || reinterpret_cast<uintptr_t>(F) % 2 != 0)
         return GRIM_ERR_UNSUPPORTED;
     ConvParams p;
     p.sptr = A->gather.d_sptr;
@@ -1311,9 +1329,22 @@ grim_status launch_conv_gather(const grim_bcr_matrix *A, const void *F, int32_t 
     int64_t nwg = 0;
     p.map = xcd_map(p.ntiles, per_tile, &nwg);
     if (nwg > 0x7fffffff) return GRIM_ERR_SHAPE;
-    const size_t lds = (size_t)(eight ? 8 : 4) * 8192 + kConvTableBytes;
-    const dim3 grid((unsigned)nwg), block(eight ? 512 : 256);
-#define GRIM_CONV(BF, SO, EI) hipLaunchKernelGGL((bcr_conv_gather<BF, SO, EI>), grid, block, lds, stream, p)
+    const size_t lds = (size_t)(eight ? kConvLongWaves : 4) * 8192 + kConvTableBytes;
+    const dim3 grid((unsigned)nwg), block(eight ? kConvLongWaves * 64 : 256);
+#define GRIM_CONV(BF, SO, EI)                                                                                        \
+    do {                                                                                                             \
+        auto kern = bcr_conv_gather<BF, SO, EI>;                                                                     \
+        static std::atomic<bool> attr_done{false};                                                                   \
+        if (lds > 64 * 1024 && !attr_done) {                                                                         \
+            if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, \
+                                    160 * 1024) != hipSuccess) {                                                     \
+                (void)hipGetLastError();                                                                             \
+                return GRIM_ERR_DEVICE;                                                                              \
+            }                                                                                                        \
+            attr_done = true;                                                                                        \
+        }                                                                                                            \
+        hipLaunchKernelGGL(kern, grid, block, lds, stream, p);                                                       \
+    } while (0)
     if (A->dtype == GRIM_BF16) { if (solo) GRIM_CONV(true, true, false); else if (eight) GRIM_CONV(true, false, true); else GRIM_CONV(true, false, false); }
     else { if (solo) GRIM_CONV(false, true, false); else if (eight) GRIM_CONV(false, false, true); else GRIM_CONV(false, false, false); }
 #undef GRIM_CONV
