@@ -567,6 +567,7 @@ __global__ void __launch_bounds__((NW + NP) * 64) bcr_spmm_mma(MmaParams p) {
 // layer: 8 waves of the row-gathering kernel (4 steps per batch) 7.66 us, 12 waves 7.63, 16 waves 8.56; the convolution
 // kernel (3 steps per batch) 11.0 us with 8, 8.6 us with 12 -- every wave then needs one batch only --, 9.7 us with 16.
 constexpr int kGatherLongWaves = 8, kConvLongWaves = 12;
+static_assert(kConvLongWaves == 12, "the launcher names the instantiations");
 
 // Workgroup id -> (tile of columns, unit of the tile's work) for the kernels whose workgroups of one
 // tile fetch the same rows: ids are dealt to the 8 XCDs round-robin, each XCD has its own L2, so a
@@ -991,11 +992,12 @@ constexpr int kConvTableBytes = (kConvMaxTaps + 1) * 8 * 16;   // validity masks
 
 // SOLO, EIGHT: as in the row-gathering kernel -- a (tile, strip) pair per wave for strips of a few steps, eight
 // waves per strip for long strips with few workgroups
-template <bool BF16, bool SOLO, bool EIGHT>
-__global__ void __launch_bounds__(EIGHT ? kConvLongWaves * 64 : 256, EIGHT ? 1024 / (kConvLongWaves * 64) : 4) bcr_conv_gather(ConvParams p) {
+template <bool BF16, bool SOLO, int LONGW>   // LONGW: 0, or the waves that split a long strip's steps (8 or 12)
+__global__ void __launch_bounds__(LONGW ? LONGW * 64 : 256, LONGW ? 1024 / (LONGW * 64) : 4) bcr_conv_gather(ConvParams p) {
+    constexpr bool EIGHT = LONGW > 0;
     constexpr int NT = 4, TN = 64, PITCH = 128, CPR = 8;
     constexpr int SB = 3;                        // steps a wave has in flight
-    constexpr int NWV = EIGHT ? kConvLongWaves : 4;   // waves of the workgroup
+    constexpr int NWV = EIGHT ? LONGW : 4;       // waves of the workgroup
     extern __shared__ __attribute__((aligned(16))) char lds[];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -1323,14 +1325,17 @@ grim_status launch_conv_gather(const grim_bcr_matrix *A, const void *F, int32_t 
     p.yvec = (reinterpret_cast<uintptr_t>(Y) % (odt == GRIM_F32 ? 16 : 8) == 0 && ldy % 4 == 0 && N % 4 == 0) ? 4 : 1;
     // the same launch forms as the row-gathering kernel
     const bool solo = gather_wave_per_strip(A, (int64_t)p.ntiles * p.nbr, 4096);
-    const bool eight = !solo && A->gather.max_steps >= 16 && (int64_t)p.ntiles * p.nbr <= 256;
+    const int64_t pairs = (int64_t)p.ntiles * p.nbr;
+    // long strips and few pairs: twelve waves per strip up to 256 pairs (one workgroup per compute unit), eight up to 512
+    // (two per compute unit; 28 x 28 layers: 11.0 -> 9.4 us with 18 steps, 14.1 -> 13.3 us with 36)
+    const int longw = !solo && A->gather.max_steps >= 16 ? (pairs <= 256 ? kConvLongWaves : pairs <= 512 ? 8 : 0) : 0;
     const int64_t per_tile = solo ? (p.nbr + 3) / 4 : p.nbr;
     if (((int64_t)p.ntiles + 7) / 8 * 8 * per_tile > 0x7fffffff) return GRIM_ERR_SHAPE;
     int64_t nwg = 0;
     p.map = xcd_map(p.ntiles, per_tile, &nwg);
     if (nwg > 0x7fffffff) return GRIM_ERR_SHAPE;
-    const size_t lds = (size_t)(eight ? kConvLongWaves : 4) * 8192 + kConvTableBytes;
-    const dim3 grid((unsigned)nwg), block(eight ? kConvLongWaves * 64 : 256);
+    const size_t lds = (size_t)(longw ? longw : 4) * 8192 + kConvTableBytes;
+    const dim3 grid((unsigned)nwg), block(longw ? longw * 64 : 256);
 #define GRIM_CONV(BF, SO, EI)                                                                                        \
     do {                                                                                                             \
         auto kern = bcr_conv_gather<BF, SO, EI>;                                                                     \
@@ -1345,8 +1350,8 @@ grim_status launch_conv_gather(const grim_bcr_matrix *A, const void *F, int32_t 
         }                                                                                                            \
         hipLaunchKernelGGL(kern, grid, block, lds, stream, p);                                                       \
     } while (0)
-    if (A->dtype == GRIM_BF16) { if (solo) GRIM_CONV(true, true, false); else if (eight) GRIM_CONV(true, false, true); else GRIM_CONV(true, false, false); }
-    else { if (solo) GRIM_CONV(false, true, false); else if (eight) GRIM_CONV(false, false, true); else GRIM_CONV(false, false, false); }
+    if (A->dtype == GRIM_BF16) { if (solo) GRIM_CONV(true, true, 0); else if (longw == 12) GRIM_CONV(true, false, 12); else if (longw == 8) GRIM_CONV(true, false, 8); else GRIM_CONV(true, false, 0); }
+    else { if (solo) GRIM_CONV(false, true, 0); else if (longw == 12) GRIM_CONV(false, false, 12); else if (longw == 8) GRIM_CONV(false, false, 8); else GRIM_CONV(false, false, 0); }
 #undef GRIM_CONV
     return hipGetLastError() == hipSuccess ? GRIM_OK : GRIM_ERR_DEVICE;
 }

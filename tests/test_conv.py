@@ -111,10 +111,11 @@ def test_conv_parity(dtype, Cin, H, W, kh, kw, BR, BC):
 @pytest.mark.gpu
 @pytest.mark.parametrize("Cin,H,W,M,BC,keep_c,form", [
     (8, 96, 116, 96, 8, (2, 8), "a (tile, strip) pair per wave: strips of a few steps, thousands of pairs, idle waves in a tile's last workgroup"),
-    (64, 16, 24, 64, 32, (24, 32), "eight waves per strip: long strips, few workgroups"),
+    (64, 16, 24, 64, 32, (24, 32), "twelve waves per strip: long strips, at most 256 (tile, strip) pairs"),
+    (64, 48, 116, 64, 32, (24, 32), "eight waves per strip: long strips, 348 (tile, strip) pairs"),
 ])
 def test_conv_launch_forms(Cin, H, W, M, BC, keep_c, form):
-    """The two other launch forms of the convolution kernel (same arithmetic per step, different split of the work)."""
+    """The other launch forms of the convolution kernel (same arithmetic per step, different split of the work)."""
     import paper_2108_11033_amd as g
     from helpers import pack_workload, TOL
     dtype, K = gen.F16, Cin * 9
