@@ -205,8 +205,8 @@ void grim_bcr_group_free(grim_bcr_group *G);
  * exact); only the feature map is read -- kh * kw times fewer bytes -- and only the rows a strip keeps.
  * Runs on the row-gathering matrix-core kernel: fp16 / bf16, block height a divisor or a multiple of
  * 16, H * W < 2^24 (maps of any shape down to 1 x 1: fewer than 64 positions run as one partly
- * filled tile), kh * kw <= 31 (5 x 5,
- * 3 x 7; a few flat shapes such as 1 x 25 are refused), 8 <= Cin * H * W <= 2^26; otherwise GRIM_ERR_UNSUPPORTED.
+ * filled tile), kh * kw <= 31 (5 x 5, 3 x 7; a few flat shapes such as 1 x 25 are refused),
+ * 8 <= Cin * H * W <= 2^26; otherwise GRIM_ERR_UNSUPPORTED.
  * Errors: NULL, SHAPE (even kernel, K != Cin * kh * kw, ldy < H * W, sizes < 1), DEVICE, UNSUPPORTED.
  */
 grim_status grim_bcr_conv2d(const grim_bcr_matrix *A, const void *F_dev, int32_t Cin, int32_t H, int32_t W,
