@@ -114,11 +114,12 @@ def test_conv_parity(dtype, Cin, H, W, kh, kw, BR, BC):
     (64, 16, 24, 64, 32, (24, 32), "twelve waves per strip: long strips, at most 256 (tile, strip) pairs"),
     (64, 48, 116, 64, 32, (24, 32), "eight waves per strip: long strips, 348 (tile, strip) pairs"),
 ])
-def test_conv_launch_forms(Cin, H, W, M, BC, keep_c, form):
+@pytest.mark.parametrize("dtype", [gen.F16, gen.BF16])
+def test_conv_launch_forms(dtype, Cin, H, W, M, BC, keep_c, form):
     """The other launch forms of the convolution kernel (same arithmetic per step, different split of the work)."""
     import paper_2108_11033_amd as g
     from helpers import pack_workload, TOL
-    dtype, K = gen.F16, Cin * 9
+    K = Cin * 9
     mask = gen.random_mask(M, K, 16, BC, (0, 8, 16), keep_c, seed=770 + Cin)
     Wt = gen.normal_weights(M, K, dtype, seed=771)
     F = gen.normal_activations(Cin, H * W, dtype, seed=772, relu=True).reshape(Cin, H, W)
