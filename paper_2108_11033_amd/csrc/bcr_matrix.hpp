@@ -175,6 +175,8 @@ grim_status launch_spmm_gather(const grim_bcr_matrix *A, const void *X, int64_t 
 bool gather_pair_applies(const grim_bcr_matrix *A, const void *X, const grim_bcr_matrix *A2, const void *X2, int64_t N,
                          int64_t ldx);
 bool gather_applies(const grim_bcr_matrix *A, const void *X, int64_t N, int64_t ldx);
+// launch form of the row-gathering kernels: a (tile, strip) pair per wave instead of four waves per strip
+bool gather_wave_per_strip(const grim_bcr_matrix *A, int64_t pairs, int64_t pairs_for_long_strips);
 // convolution on the row-gathering layout, the im2col matrix never formed
 grim_status launch_conv_gather(const grim_bcr_matrix *A, const void *F, int32_t Cin, int32_t H, int32_t W, int32_t kh,
                                int32_t kw, const float *bias, int32_t relu, void *Y, int32_t odt, int64_t ldy,

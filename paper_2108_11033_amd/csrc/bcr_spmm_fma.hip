@@ -1,0 +1,88 @@
+// Portable SpMM kernel on the vector ALUs for Y = W_bcr * X (Section 3.1: CONV as GEMM on the im2col matrix).
+// Any element type, BR <= 64.  One wave owns one row strip x 64 columns of X and walks the strip's blocks in
+// ascending column-block order; every gathered X value is loaded once and reused by all kept rows of the block
+// (the load-redundancy elimination of Section 4.4, here a consequence of treating the block as a small dense
+// matrix).
+#include "spmm_common.hpp"
+
+namespace grim {
+
+struct FmaParams {
+    const int32_t *strip_order;
+    const int32_t *row_ptr;
+    const int32_t *col_ptr;
+    const uint16_t *col_idx;
+    const int64_t *blk_ptr;
+    const uint64_t *rowmask;
+    const void *weights;
+    const void *X;
+    float *Y;
+    int64_t N, ldx, ldy;
+    int32_t BR, BC;
+    int64_t nbc;
+};
+
+template <int DT, int BRCAP>
+__global__ void __launch_bounds__(64) bcr_spmm_fma(FmaParams p) {
+    using T = typename Elem<DT>::type;
+    const int64_t t = blockIdx.x;                        // stored strip
+    const int64_t n = (int64_t)blockIdx.y * 64 + threadIdx.x;
+    const bool live = n < p.N;
+    const T *X = static_cast<const T *>(p.X);
+    const T *W = static_cast<const T *>(p.weights);
+    float acc[BRCAP];
+#pragma unroll
+    for (int r = 0; r < BRCAP; ++r) acc[r] = 0.f;
+    for (int64_t c = 0; c < p.nbc; ++c) {
+        const int64_t b = t * p.nbc + c;
+        const uint64_t mask = p.rowmask[b];
+        const int32_t cp0 = p.col_ptr[b];
+        const int32_t kc = p.col_ptr[b + 1] - cp0;
+        if (mask == 0 || kc == 0) continue;
+        const T *wb = W + p.blk_ptr[b];
+        for (int32_t j = 0; j < kc; ++j) {
+            const int64_t k = c * p.BC + p.col_idx[cp0 + j];
+            const float xv = live ? to_f32<DT>(X[k * p.ldx + n]) : 0.f;
+            int32_t i = 0;
+#pragma unroll
+            for (int r = 0; r < BRCAP; ++r) {
+                if ((mask >> r) & 1) {                  // same for the whole wave
+                    acc[r] = __builtin_fmaf(to_f32<DT>(wb[(int64_t)i * kc + j]), xv, acc[r]);
+                    ++i;
+                }
+            }
+        }
+    }
+    if (live) {
+        const int64_t row0 = (int64_t)p.strip_order[t] * p.BR;
+#pragma unroll
+        for (int r = 0; r < BRCAP; ++r)
+            if (r < p.BR) p.Y[(row0 + r) * p.ldy + n] = acc[r];
+    }
+}
+
+template <int DT>
+static grim_status launch_fma_dt(const FmaParams &p, int32_t BR, int64_t nbr, hipStream_t stream) {
+    if ((p.N + 63) / 64 > 65535 || nbr > 0x7fffffff) return GRIM_ERR_SHAPE;
+    dim3 grid((unsigned)nbr, (unsigned)((p.N + 63) / 64));
+    if (BR <= 16) hipLaunchKernelGGL((bcr_spmm_fma<DT, 16>), grid, dim3(64), 0, stream, p);
+    else if (BR <= 32) hipLaunchKernelGGL((bcr_spmm_fma<DT, 32>), grid, dim3(64), 0, stream, p);
+    else hipLaunchKernelGGL((bcr_spmm_fma<DT, 64>), grid, dim3(64), 0, stream, p);
+    return hipGetLastError() == hipSuccess ? GRIM_OK : GRIM_ERR_DEVICE;
+}
+
+grim_status launch_spmm_fma(const grim_bcr_matrix *A, const void *X, int64_t N, int64_t ldx, float *Y, int64_t ldy,
+                            hipStream_t stream) {
+    if (A->BR > 64) return GRIM_ERR_UNSUPPORTED;
+    FmaParams p{A->dev.strip_order, A->dev.row_ptr, A->dev.col_ptr, A->dev.col_idx, A->dev.blk_ptr, A->dev.rowmask64,
+                A->dev.weights, X, Y, N, ldx, ldy, A->BR, A->BC, A->nbc};
+    switch (A->dtype) {
+        case GRIM_F32: return launch_fma_dt<GRIM_F32>(p, A->BR, A->nbr, stream);
+        case GRIM_F16: return launch_fma_dt<GRIM_F16>(p, A->BR, A->nbr, stream);
+        case GRIM_BF16: return launch_fma_dt<GRIM_BF16>(p, A->BR, A->nbr, stream);
+    }
+    return GRIM_ERR_DTYPE;
+}
+
+
+}  // namespace grim

@@ -44,16 +44,8 @@ struct GemvParams {
     int32_t xvec16;          // x is contiguous and 16-byte aligned: copy with 16-byte loads
     int32_t sps;             // wave kernel: consecutive strips per wave
     int32_t batch;           // right-hand sides (kernels that take it at run time)
-#ifdef GRIM_DBG
-    long long *dbg;
-#endif
 };
 
-#ifdef GRIM_DBG
-#define GEMV_STAMP(k) do { if (p.dbg && blockIdx.x == 1 && blockIdx.y == gridDim.y / 2 && (threadIdx.x & 63) == 0) p.dbg[(threadIdx.x >> 6) * 16 + (k)] = (long long)__builtin_amdgcn_s_memtime(); } while (0)
-#else
-#define GEMV_STAMP(k) do { } while (0)
-#endif
 
 template <int DT> struct GElem;
 template <> struct GElem<GRIM_F32> { using type = float; };
@@ -154,7 +146,6 @@ __global__ void __launch_bounds__(gemv_threads(B), (B == 1 ? 6 : 1)) bcr_spmv(Ge
     const bool reducer = sg < nseg;
     float yacc = 0.f;
     if (tid == 0) part[zero_slot] = 0.f;
-    GEMV_STAMP(0);
 
     for (int c0 = 0; c0 < p.nbc; c0 += p.seg_blocks) {
         const int nb = p.nbc - c0 < p.seg_blocks ? p.nbc - c0 : p.seg_blocks;
@@ -202,7 +193,6 @@ __global__ void __launch_bounds__(gemv_threads(B), (B == 1 ? 6 : 1)) bcr_spmv(Ge
                 xreg[i] = xsrc[v];
             }
         }
-        GEMV_STAMP(1);
         if (c0 > 0) __syncthreads();                          // previous segment fully consumed
         if (tid < nb) { rmask[tid] = m0; cmask[tid] = m1; }
         if (tid <= nb) wof[tid] = wo - wstart;
@@ -223,9 +213,7 @@ __global__ void __launch_bounds__(gemv_threads(B), (B == 1 ? 6 : 1)) bcr_spmv(Ge
             // x with a leading dimension or unaligned: element by element, layout [k][b]
             for (int e = tid; e < p.K * B; e += NTH) xs[e] = x[(int64_t)(e / B) * p.ldx + (e % B)];
         }
-        GEMV_STAMP(2);
         __syncthreads();
-        GEMV_STAMP(3);
         // ---- 2. lane group -> block.  The group first gathers the block's kept columns of x
         //         (lane li takes kept columns li, li + lpb, ...); group and block live in one
         //         wave, whose LDS operations complete in order, so no workgroup barrier is needed
@@ -267,9 +255,7 @@ __global__ void __launch_bounds__(gemv_threads(B), (B == 1 ? 6 : 1)) bcr_spmv(Ge
                 for (int b = 0; b < B; ++b) part[(s * p.krmax + i) * B + b] = acc[b];
             }
         }
-        GEMV_STAMP(4);
         __syncthreads();
-        GEMV_STAMP(5);
         // ---- 3. per output: add the partials of the blocks that keep its row, ascending ----
         if (reducer) {
             const int per = (nb + nseg - 1) / nseg;
@@ -290,7 +276,6 @@ __global__ void __launch_bounds__(gemv_threads(B), (B == 1 ? 6 : 1)) bcr_spmv(Ge
             }
         }
     }
-    GEMV_STAMP(6);
     // block ranges are combined in ascending order by the first range's threads
     if (nseg > 1) {
         if (reducer) red[sg * rb + o] = yacc;
@@ -305,7 +290,6 @@ __global__ void __launch_bounds__(gemv_threads(B), (B == 1 ? 6 : 1)) bcr_spmv(Ge
         const int64_t row = (int64_t)d.strip_order[t] * p.BR + r_out;
         y[row * p.ldy + b_out] = yacc;
     }
-    GEMV_STAMP(7);
 }
 
 constexpr int kPartStride = 66;                    // floats per strip row of the partial table (wave-per-strip kernels)
@@ -420,7 +404,6 @@ __global__ void __launch_bounds__(256) bcr_spmv_wave_exact(GemvParams p) {
     // x -> LDS, once per workgroup.  Its loads go out first and the first item's right behind
     // them, so that the weights are already on their way while x is parked.
     Item cur, nxt;
-    GEMV_STAMP(0);
     if (p.xvec16) {
         const int nxv = p.K * ESZ / 16;
         const GRIM_GLOBAL gu32x4 *xsrc = reinterpret_cast<const GRIM_GLOBAL gu32x4 *>(x);
@@ -444,10 +427,8 @@ __global__ void __launch_bounds__(256) bcr_spmv_wave_exact(GemvParams p) {
         for (int e = tid; e < p.K; e += 256) xs[e] = x[(int64_t)e * p.ldx];
     }
     __syncthreads();
-    GEMV_STAMP(1);
     if (!nitems) return;
     for (int it = 0; it < nitems; ++it) {
-        GEMV_STAMP(9);
         const unsigned int rm = cur.rm, cm = cur.cm;
         if (cur.nvec == 64 * NV) {
 #pragma unroll
@@ -465,7 +446,6 @@ __global__ void __launch_bounds__(256) bcr_spmv_wave_exact(GemvParams p) {
             }
         }
         __builtin_amdgcn_wave_barrier();
-        GEMV_STAMP(3);
         // Stores and loads complete in no fixed order relative to each other, so waiting for a
         // load means waiting for every store issued before that wait as well.  The kept sums are
         // therefore stored here, right after the wait for this item's weights and a whole item
@@ -494,7 +474,6 @@ __global__ void __launch_bounds__(256) bcr_spmv_wave_exact(GemvParams p) {
 #pragma unroll
             for (int j = 0; j < NV; ++j) w[j] = wb[j];
         }
-        GEMV_STAMP(4);
         float acc[KR];
         if constexpr (DT == GRIM_F32) {
 #pragma unroll
@@ -533,7 +512,6 @@ __global__ void __launch_bounds__(256) bcr_spmv_wave_exact(GemvParams p) {
             }
         }
         __builtin_amdgcn_wave_barrier();                          // every lane holds its block in registers
-        GEMV_STAMP(5);
         for (int z = lane; z < (p.BR * kPartStride + 3) / 4; z += 64)
             reinterpret_cast<gu32x4 *>(part)[z] = gu32x4{0u, 0u, 0u, 0u};
         __builtin_amdgcn_wave_barrier();
@@ -547,7 +525,6 @@ __global__ void __launch_bounds__(256) bcr_spmv_wave_exact(GemvParams p) {
             }
         }
         __builtin_amdgcn_wave_barrier();
-        GEMV_STAMP(6);
         // Row sums in a fixed order.  Up to 16 strip rows: lanes (row, quarter) add 16 blocks
         // each, then quarters pair up; more rows: lanes (row, half) add 32 blocks each.  Every
         // lane group ends up with the full sum.
@@ -580,7 +557,6 @@ __global__ void __launch_bounds__(256) bcr_spmv_wave_exact(GemvParams p) {
         }
         yacc += rs;                                               // the same value in every lane group
         __builtin_amdgcn_wave_barrier();                          // table consumed before the next item refills LDS
-        GEMV_STAMP(7);
         if (cur.c0 + p.seg_blocks >= p.nbc) {                     // last segment of a strip
 #pragma unroll
             for (int k = 0; k < kKeep; ++k)
@@ -594,7 +570,6 @@ __global__ void __launch_bounds__(256) bcr_spmv_wave_exact(GemvParams p) {
         cur = nxt;
     }
     store_kept();
-    GEMV_STAMP(8);
 }
 
 template <int DT, int KR, int KC>
@@ -620,13 +595,9 @@ static grim_status launch_exact(const GemvParams &p, int kr, int kc, dim3 grid, 
 #define GRIM_EXACT(R, C)                                                                   \
     if constexpr ((R) * (C) * ESZ % 16 == 0 && (R) * (C) * ESZ <= 384)                     \
         if (kr == (R) && kc == (C)) return launch_exact_inst<DT, R, C>(p, grid, lds, stream);
-#ifdef GRIM_FEW_SHAPES   /* development builds */
-    GRIM_EXACT(8, 12)
-#else
     GRIM_EXACT(4, 4) GRIM_EXACT(4, 8) GRIM_EXACT(4, 12) GRIM_EXACT(4, 16)
     GRIM_EXACT(8, 4) GRIM_EXACT(8, 8) GRIM_EXACT(8, 12) GRIM_EXACT(8, 16)
     GRIM_EXACT(16, 4) GRIM_EXACT(16, 8) GRIM_EXACT(16, 12)
-#endif
 #undef GRIM_EXACT
     return GRIM_ERR_UNSUPPORTED;
 }
@@ -876,13 +847,9 @@ static grim_status launch_exact_b(const GemvParams &p, int kr, int kc, dim3 grid
 #define GRIM_EXACT(R, C)                                                                   \
     if constexpr ((R) * (C) * ESZ % 16 == 0 && (R) * (C) * ESZ <= 384)                     \
         if (kr == (R) && kc == (C)) return launch_exact_b_inst<DT, R, C>(p, grid, threads, lds, stream);
-#ifdef GRIM_FEW_SHAPES   /* development builds */
-    GRIM_EXACT(8, 12)
-#else
     GRIM_EXACT(4, 4) GRIM_EXACT(4, 8) GRIM_EXACT(4, 12) GRIM_EXACT(4, 16)
     GRIM_EXACT(8, 4) GRIM_EXACT(8, 8) GRIM_EXACT(8, 12) GRIM_EXACT(8, 16)
     GRIM_EXACT(16, 4) GRIM_EXACT(16, 8) GRIM_EXACT(16, 12)
-#endif
 #undef GRIM_EXACT
     return GRIM_ERR_UNSUPPORTED;
 }
@@ -930,9 +897,6 @@ static grim_status launch_batch(const GemvParams &p, int batch, int vec, dim3 gr
 static int wave_strips_per_wave(int64_t count, int64_t nbr, int max_sps) {
     int sps = 1;
     while (sps < max_sps && count * ((nbr + 4 * sps * 2 - 1) / (4 * sps * 2)) >= 512) sps *= 2;
-#ifdef GRIM_DBG
-    if (const char *e = getenv("GRIM_SPS")) sps = atoi(e);
-#endif
     return sps;
 }
 
@@ -973,9 +937,6 @@ grim_status launch_spmv(const GemvDesc *table, const GemvDesc &single, const Gem
     const bool contiguous = ldx == batch && reinterpret_cast<uintptr_t>(x) % 16 == 0 &&
                             (K * batch * esz) % 16 == 0 && (count == 1 || (x_stride * esz) % 16 == 0);
     p.xvec16 = contiguous ? 1 : 0;
-#ifdef GRIM_DBG
-    p.dbg = reinterpret_cast<long long *>(getenv("GRIM_DBG_PTR") ? strtoull(getenv("GRIM_DBG_PTR"), nullptr, 0) : 0ull);
-#endif
     if (batch == 1 && (int64_t)K * esz <= 32 * 1024) {
         // uniformly pruned matrix: one wave per strip, one lane per block
         if (ukr > 0 && ukc > 0 && (ukr * ukc * esz) % 16 == 0 && ukr * ukc * esz <= 384) {
