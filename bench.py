@@ -1,14 +1,17 @@
 #!/usr/bin/env python3
 """Benchmark of the BCR sparse product on one MI355X.
 
-A step is one pass of the hot path -- one grim_bcr_spmm launch -- over one batch of
-synthetic input of the headline workload: the VGG-style 3x3 convolution as an im2col
-BCR SpMM (M=256, K=2304, N=3136, fp16 in / fp32 accumulate, 16x32 blocks keeping
-8/16 rows and 8/32 columns).  Inputs are resident in HBM before the timed region; the
-steps rotate over enough (X, Y) buffer sets that no step finds its operands in the
-256 MB last-level cache.  Prints ONE JSON line.
+A step is one pass of the hot path -- one grim_bcr_spmm call: weight + index load, activation
+gather, sub-block contraction, scatter-accumulate and store -- over one batch of synthetic input of
+the headline workload, the largest configured one: the non-uniform BCR SpMM c5 (M=512, K=4608,
+N=25088 = batch 8 at 56x56, bf16 in / fp32 accumulate, 32x32 blocks whose kept-row and kept-column
+fractions are drawn from {1/8, 1/4, 1/2}).  Inputs are resident in HBM before the timed region and
+the steps alternate between two (X, Y) buffer sets (565 MB, more than the 256 MB last-level cache).
+The same JSON line carries, under "configs", the other configured workloads (c1, c2, c3 at batch 1
+and 8 in the three call forms, the 13 layers of c4, c2's layer at N = 50176) with time, algorithmic
+GB/s, fraction of the HBM roof and the kernel that ran.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--extra]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--headline-only] [--extra] [--conv] [--sweep]
 """
 from __future__ import annotations
 
@@ -25,13 +28,22 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
-# HBM bytes per c2 launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (KiB per dispatch), each scaled by
-# what the same counter reads for a device copy of known size (x 2.0 fetched, x 1.0 written); per kernel family, from
-# profiles/bcr_spmm_gather_c2.md and profiles/bcr_spmm_mma_c2.md
-C2_TRAFFIC_BYTES = {
-    "bcr_spmm_gather": (7765.9 * 2.0 + 3136.0) * 1024,
-    "bcr_spmm_mma": (7834.0 * 2.0 + 3136.0) * 1024,
+# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (KiB per dispatch), each scaled by what
+# the same counter reads for a device copy of known size (x 2.0 fetched, x 1.0 written), keyed by (workload, kernel);
+# the profile under profiles/ that holds the two counter runs is named beside each entry.  A (workload, kernel) pair
+# that no committed profile covers reports null and says so.
+TRAFFIC_BYTES = {
+    ("c2", "bcr_spmm_gather"): ((7765.9 * 2.0 + 3136.0) * 1024, "profiles/bcr_spmm_gather_c2.md"),
+    ("c2", "bcr_spmm_mma"): ((7834.0 * 2.0 + 3136.0) * 1024, "profiles/bcr_spmm_mma_c2.md"),
 }
+
+
+def traffic_of(workload: str, kernel: str):
+    hit = TRAFFIC_BYTES.get((workload, kernel))
+    if hit is None:
+        return None, f"no committed rocprofv3 counter run covers kernel {kernel} on {workload}"
+    return hit[0], hit[1]
+
 METRIC = "BCR SpMM/SpMV useful TFLOP/s, HBM GB/s, % of roofline vs oracle"
 
 
@@ -90,13 +102,15 @@ def cpu_baseline(wl, reps: int = 3) -> dict:
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=400)
-    ap.add_argument("--warmup", type=int, default=40)
-    ap.add_argument("--sets", type=int, default=32, help="(X, Y) buffer sets the steps rotate over")
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--tile-n", type=int, default=0)
     ap.add_argument("--strips-per-wg", type=int, default=0)
     ap.add_argument("--kernel", type=int, default=0, help="0 choose, 2 staged matrix-core kernel, 3 row-gathering one")
-    ap.add_argument("--extra", action="store_true", help="also time the SpMV and large non-uniform workloads")
+    ap.add_argument("--headline-only", action="store_true", help="time the headline workload only (no \"configs\" object)")
+    ap.add_argument("--extra", action="store_true",
+                    help="also time the recurrent steps (LSTM on c3's matrix, a GRU layer of the paper's size), the GRU "
+                         "matrix sizes of the paper's register-load study and a HIP graph of 1000 SpMV calls")
     ap.add_argument("--conv", action="store_true",
                     help="also time c2's layer as a convolution on the feature map (no im2col matrix)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
@@ -133,43 +147,51 @@ def main() -> int:
             return torch.from_numpy(a.view(np.int16).copy()).to(dev).view(torch.bfloat16)
         return torch.from_numpy(np.ascontiguousarray(a)).to(dev)
 
-    # ---------------- headline: c2 ----------------
-    wl = gen.c2_vgg_conv()
-    A = pack(wl)
-    vd = view_dict(A)
-    X0 = dev_tensor(wl.X, wl.dtype)
-    sets = max(1, args.sets)
-    Xs = [X0] + [X0.clone() for _ in range(sets - 1)]
-    Ys = [torch.empty((wl.M, wl.N), dtype=torch.float32, device=dev) for _ in range(sets)]
+    def spmm_record(wl, sets, steps, warmup, tune=None, key=None):
+        """Time grim_bcr_spmm on a workload, rotating over `sets` (X, Y) buffer sets; returns (record, A, Xs, Ys)."""
+        tune = tune or {}
+        A = pack(wl)
+        vd = view_dict(A)
+        X0 = dev_tensor(wl.X, wl.dtype)
+        Xs = [X0] + [X0.clone() for _ in range(sets - 1)]
+        Ys = [torch.empty((wl.M, wl.N), dtype=torch.float32, device=dev) for _ in range(sets)]
+        t, wall = time_launches(torch, lambda i: g.spmm(A, Xs[i % sets], wl.N, wl.N, Ys[i % sets], wl.N, stream, **tune),
+                                steps, warmup)
+        esz = gen.storage_itemsize(wl.dtype)
+        ab = spmm_algorithmic_bytes(vd, wl.N, esz)
+        kernel = g.spmm_kernel_name(A, Xs[0], wl.N, wl.N, **tune)
+        traffic, src = traffic_of(key or wl.name, kernel)
+        rec = {"us": t * 1e6, "useful_tflops": wl.useful_flops() / t / 1e12, "algorithmic_mb": ab / 1e6,
+               "gbs": ab / t / 1e9, "frac_hbm": ab / t / 1e9 / HBM_PEAK_GBS, "kernel": kernel,
+               "M": wl.M, "K": wl.K, "N": wl.N, "nnz": vd["nnz"], "buffer_sets": sets,
+               "buffer_set_mb": (esz * wl.K * wl.N + 4 * wl.M * wl.N) / 1e6, "traffic": traffic, "traffic_source": src,
+               "wall_us": wall * 1e6}
+        return rec, A, Xs, Ys
+
+    # ---------------- headline: c5, the largest configured workload ----------------
+    wl = gen.c5_nonuniform()
     tune = dict(tile_n=args.tile_n, strips_per_wg=args.strips_per_wg, kernel=args.kernel)
-    kernel_name = g.spmm_kernel_name(A, Xs[0], wl.N, wl.N, **tune)
-
-    def step(i):
-        j = i % sets
-        g.spmm(A, Xs[j], wl.N, wl.N, Ys[j], wl.N, stream, **tune)
-
-    t_cold, wall_cold = time_launches(torch, step, args.steps, args.warmup)
-    t_warm, _ = time_launches(torch, lambda i: g.spmm(A, Xs[0], wl.N, wl.N, Ys[0], wl.N, stream, **tune),
-                              args.steps, args.warmup)
+    sets = 2
+    head, A, Xs, Ys = spmm_record(wl, sets, args.steps, args.warmup, tune)
+    t_cold = head["us"] * 1e-6
     flops = wl.useful_flops()
-    abytes = spmm_algorithmic_bytes(vd, wl.N, 2)
-    value = flops / t_cold / 1e12
-    achieved = abytes / t_cold / 1e9
+    abytes = head["algorithmic_mb"] * 1e6
     out = {
-        "metric": METRIC, "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": t_cold * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f16", "data": "synthetic",
-        "config": {"workload": "c2: VGG-style 3x3 conv as im2col BCR SpMM, M=256 K=2304 N=3136, fp16 in / fp32 acc, "
-                               "16x32 blocks keep 8/16 rows x 8/32 cols (density 1/8)",
-                   "buffer_sets": sets, "useful_gflop_per_step": flops / 1e9, "algorithmic_mb_per_step": abytes / 1e6},
-        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": C2_TRAFFIC_BYTES.get(kernel_name),
-                     "kernel": kernel_name, "launch_us": t_cold * 1e6},
-        "warm_cache": {"ms_per_step": t_warm * 1e3, "useful_tflops": flops / t_warm / 1e12,
-                       "algorithmic_gbs": abytes / t_warm / 1e9,
-                       "note": "same X/Y every step: operands stay in the 256 MB last-level cache"},
-        "wall_ms_per_step": wall_cold * 1e3,
+        "metric": METRIC, "value": head["useful_tflops"], "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": t_cold * 1e3, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "c5: large non-uniform BCR SpMM, M=512 K=4608 N=25088 (batch 8 at 56x56), bf16 in / fp32 "
+                               "acc, 32x32 blocks, per block kept-row and kept-col fractions drawn from {1/8,1/4,1/2}",
+                   "buffer_sets": sets, "useful_gflop_per_step": flops / 1e9, "algorithmic_mb_per_step": abytes / 1e6,
+                   "nnz": head["nnz"]},
+        "roofline": {"bound": "hbm", "achieved": head["gbs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": head["frac_hbm"], "traffic": head["traffic"], "traffic_source": head["traffic_source"],
+                     "kernel": head["kernel"], "launch_us": head["us"],
+                     "hbm_roof_useful_tflops": flops / (abytes / (HBM_PEAK_GBS * 1e9)) / 1e12,
+                     "frac_of_mfma_peak": head["useful_tflops"] / 2500.0},
+        "wall_ms_per_step": head["wall_us"] * 1e-3,
     }
+    del A, Xs, Ys
 
     if args.calibrate:
         src = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
@@ -180,9 +202,23 @@ def main() -> int:
         out["calibration_copy_bytes"] = 256 << 20
         del src, dst
 
-    if args.extra:
-        extra = {}
-        # ---- c3: LSTM gate SpMV, batch 1 and 8: (A) same W, (B) rotating copies, (C) one batched launch
+    c3_mats = {}
+    if not args.headline_only:
+        cfg = {}
+        # ---- c1: the small fp32 case (latency-bound: 0.17 MB)
+        r1, A1, X1, Y1 = spmm_record(gen.c1_single_fp32(), 1, 500, 50)
+        cfg["c1"] = r1
+        del A1, X1, Y1
+        # ---- c2: rotating over 32 buffer sets (565 MB) and with the same operands every step (last-level cache)
+        w2 = gen.c2_vgg_conv()
+        r2, A2, X2, Y2 = spmm_record(w2, 32, 400, 40)
+        tw, _ = time_launches(torch, lambda i: g.spmm(A2, X2[0], w2.N, w2.N, Y2[0], w2.N, stream), 400, 40)
+        r2["warm_cache_us"] = tw * 1e6
+        r2["warm_cache_gbs"] = r2["algorithmic_mb"] * 1e6 / tw / 1e9
+        cfg["c2"] = r2
+        del A2, X2, Y2
+        # ---- c3: LSTM gate SpMV, batch 1 and 8: (A) same W back to back, (B) rotating over 256 packed copies,
+        #      (C) the 256 products in one batched launch
         for batch in (1, 8):
             w3 = gen.c3_lstm_gates(batch)
             copies = 256
@@ -197,7 +233,57 @@ def main() -> int:
             sh = int(stream.cuda_stream)
             tA, _ = time_launches(torch, lambda i: g.spmv(mats[0], xa[0], batch, batch, ya[0], batch, sh), 1000, 50)
             tB, _ = time_launches(torch, lambda i: g.spmv(mats[i % copies], xa[i % copies], batch, batch, ya[i % copies], batch, sh), 1000, 50)
-            # the same 1000 independent calls recorded once into a HIP graph and replayed (no host work per call)
+            G = binding.group(mats)
+            tC, _ = time_launches(torch, lambda i: g.spmv_batched(G, xs, w3.K * batch, batch, batch, ys, w3.M * batch, batch, stream), 20, 3)
+            tC /= copies
+            cfg[f"c3_b{batch}"] = {
+                "algorithmic_mb": b3 / 1e6, "useful_mflop": w3.useful_flops() / 1e6, "calls_timed": 1000,
+                "A_same_W_us": tA * 1e6, "A_gbs": b3 / tA / 1e9,
+                "B_rotating_us": tB * 1e6, "B_gbs": b3 / tB / 1e9, "B_frac_hbm": b3 / tB / 1e9 / HBM_PEAK_GBS,
+                "C_batched_us_per_product": tC * 1e6, "C_gbs": b3 / tC / 1e9, "C_frac_hbm": b3 / tC / 1e9 / HBM_PEAK_GBS,
+                "C_products_per_launch": copies,
+                "kernel": g.spmm_kernel_name(mats[0], xa[0], batch, batch),
+            }
+            del G
+            c3_mats[batch] = (w3, mats, xs, ys, xa, ya)
+            if not args.extra:
+                c3_mats.pop(batch)
+                del mats, xs, ys
+        # ---- c2's layer at a large N (224 x 224 positions): the same weights, 16x the columns
+        rb, Ab, Xb, Yb = spmm_record(gen.c2_vgg_conv(50176), 2, 30, 3, key="c2_N50176")
+        cfg["c2_N50176"] = rb
+        del Ab, Xb, Yb
+        # ---- c4: the 13 VGG-16 conv layers
+        layers = []
+        tot_t = tot_b = tot_f = 0.0
+        for li in range(13):
+            w4 = gen.c4_vgg16_layer(li)
+            r4, A4, X4, Y4 = spmm_record(w4, 4, 100, 10, key=f"c4_L{li + 1}")
+            layers.append({"layer": li + 1, "M": w4.M, "K": w4.K, "N": w4.N, "us": r4["us"],
+                           "useful_tflops": r4["useful_tflops"], "gbs": r4["gbs"], "frac_hbm": r4["frac_hbm"],
+                           "kernel": r4["kernel"]})
+            tot_t += r4["us"] * 1e-6; tot_b += r4["algorithmic_mb"] * 1e6; tot_f += w4.useful_flops()
+            del X4, Y4, A4
+        cfg["c4"] = {"layers": layers, "total_us": tot_t * 1e6, "useful_tflops": tot_f / tot_t / 1e12,
+                     "algorithmic_mb": tot_b / 1e6, "gbs": tot_b / tot_t / 1e9, "frac_hbm": tot_b / tot_t / 1e9 / HBM_PEAK_GBS}
+        out["configs"] = cfg
+
+    if args.extra:
+        extra = {}
+        for batch in (1, 8):
+            if batch not in c3_mats:
+                w3 = gen.c3_lstm_gates(batch)
+                copies = 256
+                mats = [pack(w3) for _ in range(copies)]
+                xs = dev_tensor(np.stack([w3.X] * copies), w3.dtype)
+                ys = torch.empty((copies, w3.M, batch), dtype=torch.float32, device=dev)
+                xa = [int(xs[j].data_ptr()) for j in range(copies)]
+                ya = [int(ys[j].data_ptr()) for j in range(copies)]
+            else:
+                w3, mats, xs, ys, xa, ya = c3_mats.pop(batch)
+                copies = len(mats)
+            b3 = spmv_algorithmic_bytes(view_dict(mats[0]), batch, 2)
+            # the 1000 independent calls recorded once into a HIP graph and replayed (no host work per call)
             gstream = torch.cuda.Stream()
             graph = torch.cuda.CUDAGraph()
             with torch.cuda.stream(gstream):
@@ -216,17 +302,7 @@ def main() -> int:
                 torch.cuda.synchronize()
                 tD = min(tD, (time.perf_counter() - t0) / 1000)
             del graph
-            G = binding.group(mats)
-            tC, _ = time_launches(torch, lambda i: g.spmv_batched(G, xs, w3.K * batch, batch, batch, ys, w3.M * batch, batch, stream), 20, 3)
-            tC /= copies
-            extra[f"c3_b{batch}"] = {
-                "algorithmic_mb": b3 / 1e6, "useful_mflop": w3.useful_flops() / 1e6,
-                "A_same_W_us": tA * 1e6, "A_gbs": b3 / tA / 1e9,
-                "B_rotating_us": tB * 1e6, "B_gbs": b3 / tB / 1e9, "B_frac_hbm": b3 / tB / 1e9 / HBM_PEAK_GBS,
-                "C_batched_us_per_product": tC * 1e6, "C_gbs": b3 / tC / 1e9, "C_frac_hbm": b3 / tC / 1e9 / HBM_PEAK_GBS,
-                "C_products_per_launch": copies,
-                "D_graph_of_1000_calls_us_per_call": tD * 1e6, "D_gbs": b3 / tD / 1e9,
-            }
+            extra[f"c3_b{batch}"] = {"D_graph_of_1000_calls_us_per_call": tD * 1e6, "D_gbs": b3 / tD / 1e9}
             # the same matrix as an LSTM layer (hidden = input = 1024): one step = gate product + cell
             Hh = w3.M // 4
             xh = [dev_tensor(w3.X, w3.dtype).clone() for _ in range(2)]
@@ -238,13 +314,13 @@ def main() -> int:
                             batch, None, 0, stream)
             tL, _ = time_launches(torch, lstm, 1000, 50)
             extra[f"c3_b{batch}"]["lstm_step_us"] = tL * 1e6
-            del G, mats
-        # ---- a GRU layer of the paper's size (Section 5: hidden 1024, both gate matrices 3072 x 1024, pruned 10x,
-        #      32 x 32 blocks): one step = two products + the cell, at batch 1, 8 and 32 (the paper quotes batch 32)
-        from paper_2108_11033_amd import tune
+            del mats, xs, ys
+        # ---- a GRU layer of the paper's size (Section 6.1: hidden 1024, both gate matrices 3072 x 1024, pruned 10x,
+        #      32 x 32 blocks): one step = two products + the cell, at batch 1, 8 and 32 (Section 6.3 quotes batch 32)
+        from paper_2108_11033_amd import tune as tune_mod
         Hg = 1024
-        Wgi, _, mgi = tune.synthesize(3 * Hg, Hg, 1, 32, 32, 10.0, "f16", seed=1)
-        Wgh, _, mgh = tune.synthesize(3 * Hg, Hg, 1, 32, 32, 10.0, "f16", seed=2)
+        Wgi, _, mgi = tune_mod.synthesize(3 * Hg, Hg, 1, 32, 32, 10.0, "f16", seed=1)
+        Wgh, _, mgh = tune_mod.synthesize(3 * Hg, Hg, 1, 32, 32, 10.0, "f16", seed=2)
         Agi = g.pack(Wgi, "f16", 32, 32, mgi.row_ptr, mgi.row_idx, mgi.col_ptr, mgi.col_idx)
         Agh = g.pack(Wgh, "f16", 32, 32, mgh.row_ptr, mgh.row_idx, mgh.col_ptr, mgh.col_idx)
         gru = {}
@@ -258,7 +334,7 @@ def main() -> int:
                                                               None, None, h32, batch, hb, batch, stream), 500, 50)
             gru[f"b{batch}_step_us"] = tG * 1e6
         gru["kernel_b32"] = g.spmm_kernel_name(Agi, xg, 32, 32)
-        # the three GRU matrix sizes the paper counts register loads on (Section 5.3), pruned 10.7x: one product each
+        # the three GRU matrix sizes the paper counts register loads on (Section 6.4), pruned 10.7x: one product each
         shapes = {}
         for (Mg, Kg, BRg, BCg, krg, kcg) in ((152, 1024, 8, 32, 4, 6), (512, 1024, 32, 32, 8, 12), (1024, 1024, 32, 32, 8, 12)):
             mk = gen.random_mask(Mg, Kg, BRg, BCg, krg, kcg, seed=40 + Mg)
@@ -277,86 +353,43 @@ def main() -> int:
         gru["paper_shapes"] = shapes
         extra["gru_1024"] = gru
         del Agi, Agh
-        # ---- c5: large non-uniform bf16 SpMM
-        w5 = gen.c5_nonuniform()
-        A5 = pack(w5)
-        v5 = view_dict(A5)
-        X5 = dev_tensor(w5.X, w5.dtype)
-        X5b = X5.clone()
-        Y5 = [torch.empty((w5.M, w5.N), dtype=torch.float32, device=dev) for _ in range(2)]
-        XX = [X5, X5b]
-        t5, _ = time_launches(torch, lambda i: g.spmm(A5, XX[i % 2], w5.N, w5.N, Y5[i % 2], w5.N, stream), 50, 5)
-        b5 = spmm_algorithmic_bytes(v5, w5.N, 2)
-        extra["c5"] = {"us": t5 * 1e6, "useful_tflops": w5.useful_flops() / t5 / 1e12, "algorithmic_mb": b5 / 1e6,
-                       "gbs": b5 / t5 / 1e9, "frac_hbm": b5 / t5 / 1e9 / HBM_PEAK_GBS, "nnz": v5["nnz"],
-                       "mma_layout_mb": v5["dev_bytes_mma"] / 1e6}
-        extra["c5"]["kernel"] = g.spmm_kernel_name(A5, X5, w5.N, w5.N)
-        del X5, X5b, Y5, XX, A5
-        # ---- c2's layer at a large N (224 x 224 positions): the same weights, 16x the columns
-        wb = gen.c2_vgg_conv(50176)
-        Ab = pack(wb)
-        vb = view_dict(Ab)
-        Xb = [dev_tensor(wb.X, wb.dtype)]
-        Xb.append(Xb[0].clone())
-        Yb = [torch.empty((wb.M, wb.N), dtype=torch.float32, device=dev) for _ in range(2)]
-        tb, _ = time_launches(torch, lambda i: g.spmm(Ab, Xb[i % 2], wb.N, wb.N, Yb[i % 2], wb.N, stream), 30, 3)
-        bb = spmm_algorithmic_bytes(vb, wb.N, 2)
-        extra["c2_N50176"] = {"us": tb * 1e6, "useful_tflops": wb.useful_flops() / tb / 1e12, "algorithmic_mb": bb / 1e6,
-                              "gbs": bb / tb / 1e9, "frac_hbm": bb / tb / 1e9 / HBM_PEAK_GBS,
-                              "kernel": g.spmm_kernel_name(Ab, Xb[0], wb.N, wb.N)}
-        del Xb, Yb, Ab
-        # ---- c4: the 13 VGG-16 conv layers
-        layers = []
-        tot_t = tot_b = tot_f = 0.0
-        for li in range(13):
-            w4 = gen.c4_vgg16_layer(li)
-            A4 = pack(w4)
-            v4 = view_dict(A4)
-            nset = 4
-            X4 = [dev_tensor(w4.X, w4.dtype)]
-            X4 += [X4[0].clone() for _ in range(nset - 1)]
-            Y4 = [torch.empty((w4.M, w4.N), dtype=torch.float32, device=dev) for _ in range(nset)]
-            t4, _ = time_launches(torch, lambda i: g.spmm(A4, X4[i % nset], w4.N, w4.N, Y4[i % nset], w4.N, stream), 100, 10)
-            b4 = spmm_algorithmic_bytes(v4, w4.N, 2)
-            layers.append({"layer": li + 1, "M": w4.M, "K": w4.K, "N": w4.N, "us": t4 * 1e6,
-                           "useful_tflops": w4.useful_flops() / t4 / 1e12, "gbs": b4 / t4 / 1e9,
-                           "kernel": g.spmm_kernel_name(A4, X4[0], w4.N, w4.N)})
-            tot_t += t4; tot_b += b4; tot_f += w4.useful_flops()
-            del X4, Y4, A4
-        extra["c4"] = {"layers": layers, "total_us": tot_t * 1e6, "useful_tflops": tot_f / tot_t / 1e12,
-                       "gbs": tot_b / tot_t / 1e9, "frac_hbm": tot_b / tot_t / 1e9 / HBM_PEAK_GBS}
         out["extra"] = extra
 
     if args.conv:
         # c2's layer fed with the feature map it stands for: 256 channels of 56 x 56, 3 x 3 kernel, same padding
         Cin, Hc, Wc = 256, 56, 56
-        F0 = dev_tensor(gen.normal_activations(Cin, Hc * Wc, wl.dtype, seed=77, relu=True), wl.dtype)
-        Fs = [F0] + [F0.clone() for _ in range(sets - 1)]
-        tc, _ = time_launches(torch, lambda i: g.conv2d(A, Fs[i % sets], Cin, Hc, Wc, 3, 3, Ys[i % sets], wl.N, stream),
-                              args.steps, args.warmup)
-        cbytes = abytes - wl.K * wl.N * 2 + Cin * Hc * Wc * 2
+        wc = gen.c2_vgg_conv()
+        csets = 32
+        rc, Ac, Xc, Yc = spmm_record(wc, csets, 400, 40)
+        del Xc
+        vdc = view_dict(Ac)
+        F0 = dev_tensor(gen.normal_activations(Cin, Hc * Wc, wc.dtype, seed=77, relu=True), wc.dtype)
+        Fs = [F0] + [F0.clone() for _ in range(csets - 1)]
+        tc, _ = time_launches(torch, lambda i: g.conv2d(Ac, Fs[i % csets], Cin, Hc, Wc, 3, 3, Yc[i % csets], wc.N, stream),
+                              400, 40)
+        cbytes = rc["algorithmic_mb"] * 1e6 - wc.K * wc.N * 2 + Cin * Hc * Wc * 2
         # context: what forming the matrix costs with the library routine of the framework that owns the buffers
-        unfold = lambda i: torch.nn.functional.unfold(Fs[i % sets].view(1, Cin, Hc, Wc), 3, padding=1)
+        unfold = lambda i: torch.nn.functional.unfold(Fs[i % csets].view(1, Cin, Hc, Wc), 3, padding=1)
         tu, _ = time_launches(torch, unfold, 100, 10)
         out["conv"] = {"workload": "c2's weights on a 256 x 56 x 56 fp16 feature map, 3x3, zero padding 1",
-                       "us": tc * 1e6, "useful_tflops": flops / tc / 1e12, "algorithmic_mb": cbytes / 1e6,
-                       "gbs": cbytes / tc / 1e9, "product_on_materialised_im2col_us": t_cold * 1e6,
-                       "torch_unfold_us": tu * 1e6, "im2col_matrix_mb": wl.K * wl.N * 2 / 1e6}
+                       "us": tc * 1e6, "useful_tflops": wc.useful_flops() / tc / 1e12, "algorithmic_mb": cbytes / 1e6,
+                       "gbs": cbytes / tc / 1e9, "product_on_materialised_im2col_us": rc["us"],
+                       "torch_unfold_us": tu * 1e6, "im2col_matrix_mb": wc.K * wc.N * 2 / 1e6}
         # the layer as networks chain it: bias + rectifier in the epilogue, fp16 out (the next layer's feature map)
-        bias_c = torch.zeros(wl.M, dtype=torch.float32, device=dev)
-        Os = [torch.empty((wl.M, wl.N), dtype=torch.float16, device=dev) for _ in range(sets)]
-        ta, _ = time_launches(torch, lambda i: g.conv2d_act(A, Fs[i % sets], Cin, Hc, Wc, 3, 3, bias_c, True, Os[i % sets],
-                                                            "f16", wl.N, stream), args.steps, args.warmup)
+        bias_c = torch.zeros(wc.M, dtype=torch.float32, device=dev)
+        Os = [torch.empty((wc.M, wc.N), dtype=torch.float16, device=dev) for _ in range(csets)]
+        ta, _ = time_launches(torch, lambda i: g.conv2d_act(Ac, Fs[i % csets], Cin, Hc, Wc, 3, 3, bias_c, True, Os[i % csets],
+                                                            "f16", wc.N, stream), 400, 40)
         out["conv"]["bias_relu_fp16_out_us"] = ta * 1e6
         del Os
         # the same layer on a 224 x 224 map (N = 50176): the matrix would be 231 MB
         Hb = 224
-        Fb = [dev_tensor(gen.normal_activations(Cin, Hb * Hb, wl.dtype, seed=78 + i, relu=True), wl.dtype) for i in range(2)]
-        Yb_ = [torch.empty((wl.M, Hb * Hb), dtype=torch.float32, device=dev) for _ in range(2)]
-        tcb, _ = time_launches(torch, lambda i: g.conv2d(A, Fb[i % 2], Cin, Hb, Hb, 3, 3, Yb_[i % 2], Hb * Hb, stream), 30, 3)
+        Fb = [dev_tensor(gen.normal_activations(Cin, Hb * Hb, wc.dtype, seed=78 + i, relu=True), wc.dtype) for i in range(2)]
+        Yb_ = [torch.empty((wc.M, Hb * Hb), dtype=torch.float32, device=dev) for _ in range(2)]
+        tcb, _ = time_launches(torch, lambda i: g.conv2d(Ac, Fb[i % 2], Cin, Hb, Hb, 3, 3, Yb_[i % 2], Hb * Hb, stream), 30, 3)
         tub, _ = time_launches(torch, lambda i: torch.nn.functional.unfold(Fb[i % 2].view(1, Cin, Hb, Hb), 3, padding=1), 10, 2)
-        out["conv"]["at_224x224"] = {"us": tcb * 1e6, "useful_tflops": 2.0 * vd["nnz"] * Hb * Hb / tcb / 1e12,
-                                     "torch_unfold_us": tub * 1e6, "im2col_matrix_mb": wl.K * Hb * Hb * 2 / 1e6}
+        out["conv"]["at_224x224"] = {"us": tcb * 1e6, "useful_tflops": 2.0 * vdc["nnz"] * Hb * Hb / tcb / 1e12,
+                                     "torch_unfold_us": tub * 1e6, "im2col_matrix_mb": wc.K * Hb * Hb * 2 / 1e6}
         del Fb, Yb_
         # the 13 VGG-16 conv layers (c4's weights) as fused layers: convolution + bias + rectifier + fp16 output,
         # each from a feature map of its input size (pooling between the stages is not part of this library)
@@ -377,7 +410,7 @@ def main() -> int:
             del A4, Fv, Ov
         out["conv"]["vgg16_13_fused_layers_us"] = stack
         out["conv"]["vgg16_13_fused_layers_total_us"] = tot * 1e6
-        del Fs
+        del Fs, Ac, Yc
 
     if args.sweep:
         from paper_2108_11033_amd import tune

@@ -55,8 +55,9 @@ typedef enum { GRIM_F32 = 0, GRIM_F16 = 1, GRIM_BF16 = 2 } grim_dtype;
 typedef struct grim_bcr_options {
     int32_t no_reorder;  /* 0 (default): store row strips by decreasing work (Section 4.2);
                             1: keep the natural strip order */
-    int32_t host_only;   /* 1: build only the host arrays (pack / unpack / arrays work without
-                            a GPU; spmm / spmv then return GRIM_ERR_DEVICE) */
+    int32_t host_only;   /* 1: build only the canonical host arrays (pack / unpack / arrays work without
+                            a GPU; spmm / spmv then return GRIM_ERR_DEVICE); 2: also build the derived
+                            kernel layouts on the host (grim_bcr_unpack_layout), still without a GPU */
     int32_t chunk_rows;  /* rows of X staged per step by the matrix-core SpMM kernel;
                             0 = choose.  Rounded to a whole number of column blocks. */
     int32_t reserved[5];
@@ -117,6 +118,16 @@ grim_status grim_bcr_pack(const void *W_host, grim_dtype dt, int64_t M, int64_t 
  * dimension ldw >= K, element type of the matrix) to host memory; pruned positions
  * become +0.  Bit-exact with respect to the packed input. */
 grim_status grim_bcr_unpack(const grim_bcr_matrix *A, void *W_host_out, int64_t ldw);
+
+/* grim_bcr_unpack_layout -- decode one of the layouts the kernels read (all derived from the compact
+ * arrays of Section 4.3 when the matrix is packed) back into the masked dense M x K matrix, exactly as
+ * grim_bcr_unpack does from the canonical arrays: a host-side check that a kernel layout holds every kept
+ * weight at the row and column the kernel will use it for, and nothing else.
+ *   layout  1 = staged matrix-core SpMM (step records per chunk and strip), 2 = row-gathering matrix-core
+ *           SpMM / convolution (steps per 16-row run), 3 = SpMV (compact weights + row / column bit masks)
+ * Works on any matrix whose layouts were built (host_only 0 or 2).  Errors: NULL, SHAPE (ldw < K, unknown
+ * layout), UNSUPPORTED (the matrix has no such layout), INDEX (a layout entry points outside the matrix). */
+grim_status grim_bcr_unpack_layout(const grim_bcr_matrix *A, int32_t layout, void *W_host_out, int64_t ldw);
 
 /* grim_bcr_arrays -- fill *v with borrowed pointers to the canonical arrays. */
 grim_status grim_bcr_arrays(const grim_bcr_matrix *A, grim_bcr_view *v);

@@ -58,11 +58,12 @@ EXPORTS = ["grim_bcr_pack", "grim_bcr_unpack", "grim_bcr_arrays", "grim_bcr_spmm
            "grim_bcr_spmv", "grim_bcr_group_create", "grim_bcr_spmv_batched", "grim_bcr_group_free",
            "grim_bcr_free", "grim_status_str", "grim_bcr_spmm_kernel_name",
            "grim_bcr_export_bcrc", "grim_bcrc_arrays", "grim_bcrc_free", "grim_lstm_cell", "grim_bcr_lstm_step", "grim_gru_cell", "grim_bcr_gru_step",
-           "grim_bcr_conv2d", "grim_bcr_conv2d_act"]
+           "grim_bcr_conv2d", "grim_bcr_conv2d_act", "grim_bcr_unpack_layout"]
 
 
 def lib_path() -> str:
-    return os.path.join(_HERE, "libgrim_bcr.so")
+    """The in-tree library; GRIM_BCR_LIB names another build of it (the sanitizer build of the host code)."""
+    return os.environ.get("GRIM_BCR_LIB") or os.path.join(_HERE, "libgrim_bcr.so")
 
 
 def load_library():
@@ -85,6 +86,7 @@ def load_library():
     i64, i32, p = ctypes.c_int64, ctypes.c_int32, ctypes.c_void_p
     lib.grim_bcr_pack.argtypes = [p, i32, i64, i64, i64, i32, i32, p, p, p, p, p, ctypes.POINTER(p)]
     lib.grim_bcr_unpack.argtypes = [p, p, i64]
+    lib.grim_bcr_unpack_layout.argtypes = [p, i32, p, i64]
     lib.grim_bcr_arrays.argtypes = [p, ctypes.POINTER(View)]
     lib.grim_bcr_spmm.argtypes = [p, p, i64, i64, p, i64, p]
     lib.grim_bcr_spmm_tuned.argtypes = [p, p, i64, i64, p, i64, i32, i32, i32, p]
@@ -186,6 +188,13 @@ class BcrMatrix:
         v = self.view()
         out = np.empty((v.M, v.K), dtype=_DT_NUMPY[v.dtype])
         _check(self._lib.grim_bcr_unpack(self.handle, _np_ptr(out), v.K), "grim_bcr_unpack")
+        return out
+
+    def unpack_layout(self, layout: int) -> np.ndarray:
+        """The masked dense matrix decoded from a kernel layout (1 staged SpMM, 2 row-gathering SpMM, 3 SpMV)."""
+        v = self.view()
+        out = np.empty((v.M, v.K), dtype=_DT_NUMPY[v.dtype])
+        _check(self._lib.grim_bcr_unpack_layout(self.handle, layout, _np_ptr(out), v.K), "grim_bcr_unpack_layout")
         return out
 
     def free(self):

@@ -450,7 +450,7 @@ grim_status grim_bcr_pack(const void *W_host, grim_dtype dt, int64_t M, int64_t 
                 }
             }
         }
-        if (!(opt && opt->host_only)) {
+        if (!(opt && opt->host_only == 1)) {
             build_mma_layout(A, opt ? opt->chunk_rows : 0);
             build_gather_layout(A);
             build_gemv_layout(A);
@@ -489,6 +489,102 @@ grim_status grim_bcr_unpack(const grim_bcr_matrix *A, void *W_host_out, int64_t 
         }
     }
     return GRIM_OK;
+}
+
+grim_status grim_bcr_unpack_layout(const grim_bcr_matrix *A, int32_t layout, void *W_host_out, int64_t ldw) {
+    if (!A || !W_host_out) return GRIM_ERR_NULL;
+    if (ldw < A->K) return GRIM_ERR_SHAPE;
+    const int esz = dtype_size(A->dtype);
+    unsigned char *W = static_cast<unsigned char *>(W_host_out);
+    auto clear = [&]() { for (int64_t i = 0; i < A->M; ++i) std::memset(W + i * ldw * esz, 0, (size_t)A->K * esz); };
+    auto put = [&](int64_t r, int64_t k, const void *src) { std::memcpy(W + (r * ldw + k) * esz, src, esz); };
+    if (layout == 1) {
+        // staged matrix-core layout: regions of [steps x header][payload] per (chunk, stored strip)
+        const MmaLayout &L = A->mma;
+        if (!L.present) return GRIM_ERR_UNSUPPORTED;
+        clear();
+        const int32_t ng = L.ks / 8, hdr = L.ks * 2 + ng * 8;
+        for (int32_t ch = 0; ch < L.nchunks; ++ch) {
+            for (int64_t st = 0; st < A->nbr; ++st) {
+                const size_t e = (size_t)ch * (A->nbr + 1) + st;
+                const int32_t nst = L.cptr[e + 1] - L.cptr[e];
+                const unsigned char *region = L.recs.data() + (size_t)L.bptr[e] * 16;
+                for (int32_t s = 0; s < nst; ++s) {
+                    const unsigned char *h = region + (size_t)s * hdr;
+                    for (int32_t g = 0; g < ng; ++g) {
+                        const uint16_t *hs = reinterpret_cast<const uint16_t *>(h) + g * 8;
+                        const uint32_t *hd = reinterpret_cast<const uint32_t *>(h + L.ks * 2) + g * 2;
+                        const uint32_t rowmask = hd[0];
+                        const unsigned char *pw = region + (size_t)hd[1] * 16;
+                        int32_t i = 0;
+                        for (int32_t r = 0; r < A->BR; ++r) {
+                            if (!((rowmask >> r) & 1u)) continue;
+                            for (int32_t slot = 0; slot < 8; ++slot) {
+                                const uint16_t srow = slot < 4 ? hs[2 * slot] : hs[2 * (slot - 4) + 1];
+                                if (srow == (uint16_t)L.chunk_rows) continue;      // the zero row: padding
+                                put((int64_t)A->strip_order[st] * A->BR + r, (int64_t)ch * L.chunk_rows + srow,
+                                    pw + ((size_t)i * 8 + slot) * 2);
+                            }
+                            ++i;
+                        }
+                    }
+                }
+            }
+        }
+        return GRIM_OK;
+    }
+    if (layout == 2) {
+        // row-gathering layout: per 16-row run a list of steps of four groups of 8 k slots
+        const GatherLayout &L = A->gather;
+        if (!L.present) return GRIM_ERR_UNSUPPORTED;
+        clear();
+        for (int64_t u = 0; u < L.nstrips; ++u) {
+            for (int64_t s = L.sptr[(size_t)u]; s < L.sptr[(size_t)u + 1]; ++s) {
+                for (int32_t g = 0; g < 4; ++g) {
+                    const uint32_t rowmask = L.desc[(size_t)s * 8 + g * 2];
+                    const unsigned char *pw = L.payload.data() + (size_t)L.desc[(size_t)s * 8 + g * 2 + 1] * 16;
+                    int32_t i = 0;
+                    for (int32_t r = 0; r < 16; ++r) {
+                        if (!((rowmask >> r) & 1u)) continue;
+                        const int32_t orow = L.out_row[(size_t)u * 16 + r];
+                        for (int32_t j = 0; j < 8; ++j) {
+                            const uint32_t k = L.rows[(size_t)s * 32 + (size_t)j * 4 + g];
+                            if (k == 0xffffffffu) continue;
+                            if (orow < 0 || k >= (uint32_t)A->K) return GRIM_ERR_INDEX;
+                            put(orow, k, pw + ((size_t)i * 8 + j) * 2);
+                        }
+                        ++i;
+                    }
+                }
+            }
+        }
+        return GRIM_OK;
+    }
+    if (layout == 3) {
+        // SpMV layout: the compact weights with one row and one column bit mask per stored block
+        const GemvLayout &G = A->gemv;
+        if (!G.present) return GRIM_ERR_UNSUPPORTED;
+        clear();
+        for (int64_t t = 0; t < A->nb; ++t) {
+            const uint32_t rm = G.masks[2 * (size_t)t], cm = G.masks[2 * (size_t)t + 1];
+            const int32_t kc = __builtin_popcount(cm);
+            const int64_t p = t / A->nbc, c = t % A->nbc;
+            int32_t i = 0;
+            for (int32_t r = 0; r < A->BR; ++r) {
+                if (!((rm >> r) & 1u)) continue;
+                int32_t j = 0;
+                for (int32_t q = 0; q < A->BC; ++q) {
+                    if (!((cm >> q) & 1u)) continue;
+                    put((int64_t)A->strip_order[p] * A->BR + r, c * A->BC + q,
+                        A->weights.data() + ((size_t)G.woff[(size_t)t] + (size_t)i * kc + j) * esz);
+                    ++j;
+                }
+                ++i;
+            }
+        }
+        return GRIM_OK;
+    }
+    return GRIM_ERR_SHAPE;
 }
 
 grim_status grim_bcr_export_bcrc(const grim_bcr_matrix *A, grim_bcrc **out) {

@@ -259,6 +259,30 @@ def test_conv_full_size_sampled():
     assert Yx.tobytes() == np.ascontiguousarray(Y.reshape(M, -1)).tobytes()
 
 
+@pytest.mark.gpu
+@pytest.mark.parametrize("layer", [1, 3])
+def test_conv_vgg_layers_at_224_and_112_sampled(layer):
+    """VGG-16 layers 2 (64 channels at 224 x 224) and 4 (128 channels at 112 x 112) on the layers' own matrices, as fused
+    convolutions at full size: sampled output channels (every row strip touched) against the reference at every
+    position, borders included."""
+    import paper_2108_11033_amd as g
+    from helpers import pack_workload, TOL
+    M, K, N = gen.VGG16_LAYERS[layer]
+    Cin, H = K // 9, int(round(N ** 0.5))
+    wl = gen.c4_vgg16_layer(layer, N=64)
+    dtype = wl.dtype
+    A = pack_workload(g, wl.W, dtype, wl.mask)
+    F = gen.normal_activations(Cin, H * H, dtype, seed=300 + layer, relu=True).reshape(Cin, H, H)
+    Y = _run(g, A, F, dtype, M, Cin, H, H, 3, 3)
+    rng = np.random.default_rng(310 + layer)
+    rows = np.sort(np.concatenate([s * 16 + rng.choice(16, 2, replace=False) for s in range(M // 16)]))
+    Wm, F64 = _masked(wl.W, dtype, wl.mask), gen.storage_to_f64(F, dtype)
+    Yref, S = conv_ref.conv_same(Wm[rows], F64, 3, 3), conv_ref.abs_scale(Wm[rows], F64, 3, 3)
+    assert np.isfinite(Y).all()
+    assert (np.abs(Y[rows] - Yref) <= TOL[dtype] * np.maximum(S, 1e-30)).all()
+    assert np.abs(Y[rows] - Yref).max() <= TOL[dtype] * np.abs(Yref).max()
+
+
 def _run_act(g, A, F, dtype, M, Cin, H, W, kh, kw, bias, relu, out_dtype, ldo=None):
     import torch
     from helpers import to_device

@@ -78,19 +78,48 @@ def test_c5_nonuniform_bf16_small_n(g):
     _spmm_case(g, gen.c5_nonuniform(N=300), "c5 N=300")
 
 
-def test_c5_full_size_sampled(g):
-    # full configuration in the launch shape the benchmark times; the oracle computes a
-    # sample of rows (all strips touched) x a sample of columns (first, last and ragged tiles)
-    wl = gen.c5_nonuniform()
+def _full_size_sampled(g, wl, what, rows_per_strip=3, seed=55, **tune):
+    """A configuration at its full size, in the launch form grim_bcr_spmm picks for it (the one bench.py times): the
+    oracle computes a sample of rows -- a few in EVERY row strip -- times a sample of columns: the first and last 70
+    (first, last and ragged tiles), 40 on either side of every multiple of 4096 (where the launches that cut a product
+    into whole rounds of workgroups plus a remainder put their cut, and where rounds of workgroups meet) and 200 drawn
+    at random."""
     A = pack_workload(g, wl.W, wl.dtype, wl.mask)
-    Y = run_spmm(g, A, wl.X, wl.dtype, wl.M, wl.N)
-    rng = np.random.default_rng(55)
-    rows = np.sort(rng.choice(wl.M, 48, replace=False))
-    cols = np.unique(np.concatenate([np.arange(0, 70), np.arange(wl.N - 70, wl.N),
-                                     rng.choice(wl.N, 200, replace=False)]))
+    Y = run_spmm(g, A, wl.X, wl.dtype, wl.M, wl.N, **tune)
+    rng = np.random.default_rng(seed)
+    BR = wl.mask.BR
+    rows = np.sort(np.concatenate([s * BR + rng.choice(BR, min(BR, rows_per_strip), replace=False)
+                                   for s in range(wl.M // BR)]))
+    cuts = np.arange(4096, wl.N, 4096)
+    near = np.concatenate([np.arange(c - 40, c + 40) for c in cuts]) if len(cuts) else np.zeros(0, dtype=np.int64)
+    cols = np.unique(np.concatenate([np.arange(0, 70), np.arange(wl.N - 70, wl.N), near,
+                                     rng.choice(wl.N, 200, replace=False)]).astype(np.int64))
     Yref, S = oracle_product(wl.W, wl.X, wl.dtype, wl.mask, rows=rows, cols=cols)
-    assert_close(Y[np.ix_(rows, cols)], Yref, S, wl.dtype, "c5 full sampled")
+    assert_close(Y[np.ix_(rows, cols)], Yref, S, wl.dtype, what)
     assert np.isfinite(Y).all()
+    return A, Y
+
+
+def test_c5_full_size_sampled(g):
+    _full_size_sampled(g, gen.c5_nonuniform(), "c5 full size, sampled")
+
+
+@pytest.mark.parametrize("layer", range(7))
+def test_c4_large_layers_full_size_sampled(g, layer):
+    # layers 1-7 (N = 50176, 12544 and 3136) on the layers' own matrices, the dense 16 x 27 first layer included
+    wl = gen.c4_vgg16_layer(layer)
+    _full_size_sampled(g, wl, f"c4 L{layer + 1} full size N={wl.N}, sampled", seed=60 + layer)
+
+
+def test_c2_at_224x224_full_size_sampled(g):
+    # c2's layer at N = 50176, as bench.py times it
+    wl = gen.c2_vgg_conv(50176)
+    A, Y = _full_size_sampled(g, wl, "c2 at N=50176, sampled", seed=70)
+    # and the whole result against one forced launch of the row-gathering kernel (another summation order:
+    # closeness only)
+    Yg = run_spmm(g, A, wl.X, wl.dtype, wl.M, wl.N, kernel=3)
+    scale = np.abs(Yg).max()
+    assert np.abs(Y - Yg).max() <= 2 * 2e-3 * scale
 
 
 @pytest.mark.parametrize("ragged", [20, 21])
