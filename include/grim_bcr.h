@@ -124,7 +124,8 @@ grim_status grim_bcr_unpack(const grim_bcr_matrix *A, void *W_host_out, int64_t 
  * grim_bcr_unpack does from the canonical arrays: a host-side check that a kernel layout holds every kept
  * weight at the row and column the kernel will use it for, and nothing else.
  *   layout  1 = staged matrix-core SpMM (step records per chunk and strip), 2 = row-gathering matrix-core
- *           SpMM / convolution (steps per 16-row run), 3 = SpMV (compact weights + row / column bit masks)
+ *           SpMM / convolution (steps per 16-row run), 3 = SpMV (compact weights + row / column bit masks),
+ *           4 = wide-tile staged matrix-core SpMM (the records of 1 cut for chunks of at most 128 rows)
  * Works on any matrix whose layouts were built (host_only 0 or 2).  Errors: NULL, SHAPE (ldw < K, unknown
  * layout), UNSUPPORTED (the matrix has no such layout), INDEX (a layout entry points outside the matrix). */
 grim_status grim_bcr_unpack_layout(const grim_bcr_matrix *A, int32_t layout, void *W_host_out, int64_t ldw);
@@ -144,21 +145,27 @@ grim_status grim_bcr_arrays(const grim_bcr_matrix *A, grim_bcr_view *v);
  * Accumulation is in fp32 in a fixed order (no atomics): results are bit-reproducible
  * from run to run.  N <= 8 is forwarded to the SpMV kernel when that path supports A.
  * A large product may be enqueued as two kernels on disjoint column ranges (the columns that
- * fill whole rounds of workgroups, then the rest).
- * Errors: NULL, SHAPE (N < 1, ld too small), DEVICE, UNSUPPORTED.  Y is untouched on error.
+ * fill whole rounds of workgroups on a wide-tile kernel, then the rest).
+ * Errors: NULL, SHAPE (N < 1, ld too small), DEVICE, UNSUPPORTED.  Argument errors are found before anything is
+ * enqueued and leave Y untouched; a launch that the runtime rejects (DEVICE) may follow a first kernel that is
+ * already enqueued on its column range.
  */
 grim_status grim_bcr_spmm(const grim_bcr_matrix *A, const void *X_dev, int64_t N, int64_t ldx,
                           float *Y_dev, int64_t ldy, void *hip_stream);
 
 /* grim_bcr_spmm_tuned -- grim_bcr_spmm with explicit launch parameters (the paper tunes
  * tile sizes per kernel, Section 4.5; here a handful of choices replaces the search):
- *   tile_n         columns of X per workgroup (32, 64 or 128; 0 = choose)
+ *   tile_n         columns of X per workgroup (32, 64 or 128; with kernel 4: 96 for BR = 32, 128 or 192 for BR = 16;
+ *                  0 = choose)
  *   strips_per_wg  row strips per workgroup (4, 8 or 16; 0 = choose)
  *   kernel         0 = choose, 1 = force the portable FMA kernel, 2 = force the staged matrix-core
  *                  kernel (fp16 / bf16, BR = 16 or 32; tile_n / strips_per_wg apply to it),
  *                  3 = force the row-gathering matrix-core kernel (fp16 / bf16, BR a divisor or a
  *                  multiple of 16 -- the paper's 4 x 16 blocks included --, N and ldx multiples of 4,
- *                  X 8-byte aligned; tile_n and strips_per_wg must be 0)
+ *                  X 8-byte aligned; tile_n and strips_per_wg must be 0),
+ *                  4 = force the wide-tile staged matrix-core kernel on all N columns (fp16 / bf16, BR = 16 or 32,
+ *                  N >= tile_n and a multiple of 8, ldx a multiple of 8, ldy of 4, X and Y 16-byte aligned;
+ *                  strips_per_wg must be 0)
  * Combinations that are not compiled, that the matrix or the operands do not qualify for, or whose
  * staging buffers do not fit the 160 KB of LDS for this matrix, return GRIM_ERR_UNSUPPORTED. */
 grim_status grim_bcr_spmm_tuned(const grim_bcr_matrix *A, const void *X_dev, int64_t N, int64_t ldx,
@@ -166,7 +173,8 @@ grim_status grim_bcr_spmm_tuned(const grim_bcr_matrix *A, const void *X_dev, int
                                 int32_t kernel, void *hip_stream);
 
 /* grim_bcr_spmm_kernel_name -- which kernel family the grim_bcr_spmm_tuned call with these arguments
- * would launch: "bcr_spmm_gather", "bcr_spmm_mma" (staged), "bcr_spmm_fma", "bcr_spmv" (N <= 8, but see grim_bcr_spmv), or
+ * would launch: "bcr_spmm_wide" (first launch of a large
+ * product), "bcr_spmm_gather", "bcr_spmm_mma" (staged), "bcr_spmm_fma", "bcr_spmv" (N <= 8, but see grim_bcr_spmv), or
  * "none" when the call would fail.  A static string; launches nothing.  For profiling and reports. */
 const char *grim_bcr_spmm_kernel_name(const grim_bcr_matrix *A, const void *X_dev, int64_t N, int64_t ldx,
                                       int32_t tile_n, int32_t strips_per_wg, int32_t kernel);
@@ -190,7 +198,8 @@ grim_status grim_bcr_spmv(const grim_bcr_matrix *A, const void *x_dev, int32_t b
  * gate-matrix product moves ~2 MB, far less than a kernel launch costs, so
  * independent products are grouped to fill the GPU.
  * grim_bcr_group_create copies the device descriptors of `count` packed matrices
- * (same M, K, BR, BC, dtype; all packed on the current GPU) into one device table.
+ * (same M, K, BR, BC, dtype; all packed on the current GPU; 1 <= count <= 65535, one
+ * grid row per matrix) into one device table.
  * The matrices must outlive the group.
  * grim_bcr_spmv_batched computes y_i = W_i * x_i for i in [0, count): x_i starts at
  * x_dev + i * x_stride elements (K x batch, ldx), y_i at y_dev + i * y_stride floats.
@@ -224,8 +233,8 @@ grim_status grim_bcr_conv2d(const grim_bcr_matrix *A, const void *F_dev, int32_t
                             int32_t kh, int32_t kw, float *Y_dev, int64_t ldy, void *hip_stream);
 
 /*
- * grim_bcr_conv2d_act -- the same convolution with the rest of a CONV layer in its epilogue (Section 2.2 /
- * Section 5: the evaluated networks are chains of CONV + bias + rectifier layers in fp16):
+ * grim_bcr_conv2d_act -- the same convolution with the rest of a CONV layer in its epilogue (Section 6.1:
+ * the evaluated networks are chains of CONV + bias + rectifier layers, run in fp16 on the GPU):
  *     out[m][n] = round_to(out_dt, act(Y[m][n] + bias[m])),   act = max(., 0) when relu != 0, else identity
  *   bias_dev  M fp32, or NULL (no bias)
  *   out_dev   M x (H * W) of element type out_dt (fp32, fp16 or bf16; round to nearest even), leading
@@ -265,7 +274,7 @@ grim_status grim_bcr_lstm_step(const grim_bcr_matrix *A, const void *xh_dev, int
                                void *h_dev, int64_t ldh, float *h32_dev, int64_t ldh32, void *hip_stream);
 
 /*
- * GRU cell around the gate products (Section 5 evaluates a two-layer GRU; its layers are the
+ * GRU cell around the gate products (Section 6.1: the evaluated RNN is a two-layer GRU, timed in Section 6.3; its layers are the
  * matrix-vector products of Section 3.1).  Two BCR matrices of 3H rows each, W_i (3H x I) and
  * W_h (3H x H), gate rows stacked reset, update, candidate; gi = W_i x and gh = W_h h come from
  * grim_bcr_spmv / grim_bcr_spmm, grim_gru_cell is the elementwise rest (the standard GRU with the

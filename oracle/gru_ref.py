@@ -1,6 +1,6 @@
 """Test infrastructure only -- fp64 reference of one GRU step around the BCR gate products.
 
-Section 5 of the paper evaluates a two-layer GRU; Section 3.1 treats an RNN layer's gate matrices as
+Section 6.1 of the paper evaluates a two-layer GRU; Section 3.1 treats an RNN layer's gate matrices as
 matrix-vector products.  The paper does not restate the cell; this is the standard GRU with the reset
 gate applied to the hidden-side candidate product (the form torch.nn.GRUCell computes, which is what
 pins this module in tests/test_gru.py).  Gate rows are stacked reset, update, candidate in both

@@ -10,6 +10,8 @@
 namespace grim {
 
 constexpr int kMmaMaxChunkRows = 256;   // rows of X staged in LDS per step by the matrix-core kernel
+constexpr int kWideMaxChunkRows = 128;  // the same for the wide-tile kernel (its tiles are 2-4x as wide)
+constexpr int kWideMaxRecordBytes = 32 * 1024;   // records of one (chunk, group of 16 strips) the wide-tile kernel stages
 constexpr int kGemvMaxXBytes = 65536;   // bytes of x (K * batch elements) the SpMV kernel keeps in LDS
 
 inline int dtype_size(int dt) { return dt == GRIM_F32 ? 4 : 2; }
@@ -126,6 +128,7 @@ struct grim_bcr_matrix {
     int device = -1;
     grim::DeviceCanonical dev;
     grim::MmaLayout mma;
+    grim::MmaLayout mmaw;   // the same records cut for chunks of at most 128 rows (wide-tile kernel)
     grim::GatherLayout gather;
     grim::GemvLayout gemv;
 };
@@ -167,6 +170,14 @@ grim_status launch_spmm_fma(const grim_bcr_matrix *A, const void *X, int64_t N, 
 grim_status launch_spmm_mma(const grim_bcr_matrix *A, const void *X, int64_t N, int64_t ldx, float *Y,
                             int64_t ldy, int32_t tile_n, int32_t strips_per_wg, hipStream_t stream);
 bool mma_supported(const grim_bcr_matrix *A);
+// wide-tile staged kernel: tile_n 0 = choose; wide_applies: operands and matrix qualify for some tile width
+grim_status launch_spmm_wide(const grim_bcr_matrix *A, const void *X, int64_t N, int64_t ldx, float *Y, int64_t ldy,
+                             int32_t tile_n, hipStream_t stream);
+bool wide_applies(const grim_bcr_matrix *A, const void *X, int64_t N, int64_t ldx, const float *Y, int64_t ldy, int32_t tile_n);
+// best use of the wide-tile kernel: cost (bytes through one compute unit; < 0: does not apply), tile width and the
+// leading columns it should take (N, or whole rounds of workgroups with the rest priced by rest_cost)
+double wide_plan(const grim_bcr_matrix *A, const void *X, int64_t N, int64_t ldx, const float *Y, int64_t ldy,
+                 double (*rest_cost)(const grim_bcr_matrix *, int64_t), int *tn_out, int64_t *n_main);
 // row-gathering matrix-core kernel; GRIM_ERR_UNSUPPORTED when the matrix or the operands do not qualify
 // A2 / X2 / Y2: a second product of the same N, ldx and ldy in the same launch (gather_pair_applies)
 grim_status launch_spmm_gather(const grim_bcr_matrix *A, const void *X, int64_t N, int64_t ldx, float *Y,

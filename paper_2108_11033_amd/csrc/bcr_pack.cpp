@@ -39,8 +39,8 @@ grim_status validate_sets(int64_t nb, int32_t B, const int32_t *ptr, const uint1
 
 // ---- derived layout: matrix-core SpMM ---------------------------------------------------
 
-bool build_mma_layout_for(grim_bcr_matrix *A, int32_t chunk_blocks) {
-    MmaLayout &L = A->mma;
+bool build_mma_layout_for(grim_bcr_matrix *A, MmaLayout &L, int32_t chunk_blocks, int32_t max_chunk_rows, int gsel,
+                          int64_t max_group_bytes) {
     L.chunk_blocks = chunk_blocks;
     L.chunk_rows = L.chunk_blocks * A->BC;
     L.nchunks = (int32_t)((A->nbc + L.chunk_blocks - 1) / L.chunk_blocks);
@@ -127,24 +127,25 @@ bool build_mma_layout_for(grim_bcr_matrix *A, int32_t chunk_blocks) {
         }
         L.amax[gi] = amax;
     }
-    // fits the default launch (64 columns per workgroup, groups of 4 strips)?  The producers move
-    // at most 32 KB of X rows and 16 KB of records per chunk.
-    return L.chunk_rows <= 256 && (int64_t)L.amax[0] * 16 <= 16 * 1024 && L.recs.size() < (size_t(1) << 31) * 16;
+    // fits the kernel's smallest launch (strip groups of 4 << gsel)?
+    return L.chunk_rows <= max_chunk_rows && (int64_t)L.amax[gsel] * 16 <= max_group_bytes && L.recs.size() < (size_t(1) << 31) * 16;
 }
 
-void build_mma_layout(grim_bcr_matrix *A, int32_t chunk_rows_opt) {
-    MmaLayout &L = A->mma;
+// max_rows: most rows of X per chunk; gsel / max_group_bytes: the records of a group of 4 << gsel strips must fit
+// max_group_bytes per chunk (the kernel's LDS room for them)
+void build_mma_layout(grim_bcr_matrix *A, MmaLayout &L, int32_t chunk_rows_opt, int32_t max_rows, int gsel,
+                      int64_t max_group_bytes) {
     L.present = false;
     if (A->dtype == GRIM_F32) return;
     if (A->BR != 16 && A->BR != 32) return;
-    if (A->BC > kMmaMaxChunkRows) return;
-    const int32_t want = chunk_rows_opt > 0 ? std::min<int32_t>(chunk_rows_opt, kMmaMaxChunkRows) : kMmaMaxChunkRows;
+    if (A->BC > max_rows) return;
+    const int32_t want = chunk_rows_opt > 0 ? std::min<int32_t>(chunk_rows_opt, max_rows) : max_rows;
     // largest chunk whose weight records still leave room in LDS; denser matrices get smaller chunks
     int32_t blocks = std::max<int32_t>(1, want / A->BC);
-    bool fits = build_mma_layout_for(A, blocks);
+    bool fits = build_mma_layout_for(A, L, blocks, max_rows, gsel, max_group_bytes);
     while (!fits && blocks > 1) {
         blocks = (blocks + 1) / 2;
-        fits = build_mma_layout_for(A, blocks);
+        fits = build_mma_layout_for(A, L, blocks, max_rows, gsel, max_group_bytes);
     }
     if (!fits) {   // even one column block per chunk overflows LDS: leave this matrix to the FMA kernel
         L.cptr.clear(); L.bptr.clear(); L.recs.clear();
@@ -288,6 +289,12 @@ grim_status upload(grim_bcr_matrix *A) {
         o_bp2 = s.add(bytes(A->mma.bptr));
         o_af = s.add(bytes(A->mma.recs) + 2048);   // slack: records are fetched in 1 KB slots
     }
+    size_t o_wkp = 0, o_wbp = 0, o_waf = 0;
+    if (A->mmaw.present) {
+        o_wkp = s.add(bytes(A->mmaw.cptr));
+        o_wbp = s.add(bytes(A->mmaw.bptr));
+        o_waf = s.add(bytes(A->mmaw.recs) + 2048);
+    }
     size_t o_gs = 0, o_gq = 0, o_gr = 0, o_gd = 0, o_gp = 0;
     if (A->gather.present) {
         o_gs = s.add(bytes(A->gather.sptr));
@@ -314,6 +321,9 @@ grim_status upload(grim_bcr_matrix *A) {
     if (ok && A->mma.present)
         ok = put(o_kp, A->mma.cptr.data(), bytes(A->mma.cptr)) && put(o_bp2, A->mma.bptr.data(), bytes(A->mma.bptr)) &&
              put(o_af, A->mma.recs.data(), bytes(A->mma.recs));
+    if (ok && A->mmaw.present)
+        ok = put(o_wkp, A->mmaw.cptr.data(), bytes(A->mmaw.cptr)) && put(o_wbp, A->mmaw.bptr.data(), bytes(A->mmaw.bptr)) &&
+             put(o_waf, A->mmaw.recs.data(), bytes(A->mmaw.recs));
     if (ok && A->gather.present)
         ok = put(o_gs, A->gather.sptr.data(), bytes(A->gather.sptr)) && put(o_gq, A->gather.out_row.data(), bytes(A->gather.out_row)) && put(o_gr, A->gather.rows.data(), bytes(A->gather.rows)) &&
              put(o_gd, A->gather.desc.data(), bytes(A->gather.desc)) && put(o_gp, A->gather.payload.data(), bytes(A->gather.payload));
@@ -334,6 +344,12 @@ grim_status upload(grim_bcr_matrix *A) {
         A->mma.d_bptr = reinterpret_cast<int32_t *>(base + o_bp2);
         A->mma.d_recs = reinterpret_cast<unsigned char *>(base + o_af);
         A->mma.bytes = (int64_t)(mma_end - canon_end);
+    }
+    if (A->mmaw.present) {
+        A->mmaw.d_cptr = reinterpret_cast<int32_t *>(base + o_wkp);
+        A->mmaw.d_bptr = reinterpret_cast<int32_t *>(base + o_wbp);
+        A->mmaw.d_recs = reinterpret_cast<unsigned char *>(base + o_waf);
+        A->mmaw.bytes = (int64_t)(bytes(A->mmaw.cptr) + bytes(A->mmaw.bptr) + bytes(A->mmaw.recs));
     }
     if (A->gather.present) {
         A->gather.d_sptr = reinterpret_cast<int32_t *>(base + o_gs);
@@ -451,7 +467,11 @@ grim_status grim_bcr_pack(const void *W_host, grim_dtype dt, int64_t M, int64_t 
             }
         }
         if (!(opt && opt->host_only == 1)) {
-            build_mma_layout(A, opt ? opt->chunk_rows : 0);
+            // staged kernel: chunks of up to 256 rows, a 4-strip group's records within 16 KB (the producers move at
+            // most 32 KB of X rows and 16 KB of records per chunk); wide-tile kernel: chunks of up to 128 rows, a
+            // 16-strip group's records within 32 KB
+            build_mma_layout(A, A->mma, opt ? opt->chunk_rows : 0, kMmaMaxChunkRows, 0, 16 * 1024);
+            build_mma_layout(A, A->mmaw, opt ? opt->chunk_rows : 0, kWideMaxChunkRows, 2, kWideMaxRecordBytes);
             build_gather_layout(A);
             build_gemv_layout(A);
         }
@@ -498,9 +518,9 @@ grim_status grim_bcr_unpack_layout(const grim_bcr_matrix *A, int32_t layout, voi
     unsigned char *W = static_cast<unsigned char *>(W_host_out);
     auto clear = [&]() { for (int64_t i = 0; i < A->M; ++i) std::memset(W + i * ldw * esz, 0, (size_t)A->K * esz); };
     auto put = [&](int64_t r, int64_t k, const void *src) { std::memcpy(W + (r * ldw + k) * esz, src, esz); };
-    if (layout == 1) {
-        // staged matrix-core layout: regions of [steps x header][payload] per (chunk, stored strip)
-        const MmaLayout &L = A->mma;
+    if (layout == 1 || layout == 4) {
+        // staged matrix-core layouts: regions of [steps x header][payload] per (chunk, stored strip)
+        const MmaLayout &L = layout == 1 ? A->mma : A->mmaw;
         if (!L.present) return GRIM_ERR_UNSUPPORTED;
         clear();
         const int32_t ng = L.ks / 8, hdr = L.ks * 2 + ng * 8;
@@ -694,21 +714,43 @@ static bool skinny_on_matrix_cores(const grim_bcr_matrix *A, const void *X_dev, 
 }
 
 // which kernel family a grim_bcr_spmm_tuned call runs
-enum SpmmRoute { ROUTE_NONE, ROUTE_SPMV, ROUTE_FMA, ROUTE_MMA, ROUTE_GATHER };
-static SpmmRoute spmm_route(const grim_bcr_matrix *A, const void *X_dev, int64_t N, int64_t ldx, int32_t tile_n,
-                            int32_t strips_per_wg, int32_t kernel) {
-    if (kernel < 0 || kernel > 3 || tile_n < 0 || strips_per_wg < 0) return ROUTE_NONE;
+enum SpmmRoute { ROUTE_NONE, ROUTE_SPMV, ROUTE_FMA, ROUTE_MMA, ROUTE_GATHER, ROUTE_WIDE };
+
+// what the columns the wide-tile kernel leaves over cost on the kernels that take any N
+static double rest_cost(const grim_bcr_matrix *A, int64_t n) {
+    int tn = 0, g = 0;
+    double best = A->mma.present ? mma_best_shape(A, n, 0, 0, &tn, &g) : -1.0;
+    if (A->gather.present && n % 4 == 0) {
+        const double c = gather_cost(A, n);
+        if (best < 0 || c < best) best = c;
+    }
+    return best;
+}
+
+// `wide_tn` / `wide_cols`: for ROUTE_WIDE, the tile width and the leading columns that kernel takes
+static SpmmRoute spmm_route(const grim_bcr_matrix *A, const void *X_dev, int64_t N, int64_t ldx, const float *Y_dev,
+                            int64_t ldy, int32_t tile_n, int32_t strips_per_wg, int32_t kernel, int *wide_tn,
+                            int64_t *wide_cols) {
+    if (kernel < 0 || kernel > 4 || tile_n < 0 || strips_per_wg < 0) return ROUTE_NONE;
     const bool free_choice = kernel == 0 && tile_n == 0 && strips_per_wg == 0;
     if (kernel == 3) return !tile_n && !strips_per_wg && gather_applies(A, X_dev, N, ldx) ? ROUTE_GATHER : ROUTE_NONE;
+    if (kernel == 4) {
+        *wide_tn = tile_n;
+        *wide_cols = N;
+        return !strips_per_wg && wide_applies(A, X_dev, N, ldx, Y_dev, ldy, tile_n) ? ROUTE_WIDE : ROUTE_NONE;
+    }
     if (free_choice && skinny_on_matrix_cores(A, X_dev, N, ldx)) return ROUTE_GATHER;
     if (free_choice && gemv_ok(A, N)) return ROUTE_SPMV;
     const bool mma = A->mma.present && kernel != 1;
     if (kernel == 2 && !mma) return ROUTE_NONE;
-    if (free_choice && gather_applies(A, X_dev, N, ldx)) {
-        // both matrix-core kernels apply: take the one that moves fewer bytes through a compute unit
+    if (free_choice) {
+        // the matrix-core kernels that apply: take the one that moves fewer bytes through a compute unit
         int tn = 0, g = 0;
         const double staged = mma ? mma_best_shape(A, N, 0, 0, &tn, &g) : -1.0;
-        if (staged < 0 || gather_cost(A, N) < staged) return ROUTE_GATHER;
+        const double gather = gather_applies(A, X_dev, N, ldx) ? gather_cost(A, N) : -1.0;
+        const double wide = wide_plan(A, X_dev, N, ldx, Y_dev, ldy, rest_cost, wide_tn, wide_cols);
+        if (wide >= 0 && (staged < 0 || wide < staged) && (gather < 0 || wide < gather)) return ROUTE_WIDE;
+        if (gather >= 0 && (staged < 0 || gather < staged)) return ROUTE_GATHER;
     }
     if (mma) return ROUTE_MMA;
     return A->BR > 64 ? ROUTE_NONE : ROUTE_FMA;
@@ -719,13 +761,22 @@ grim_status grim_bcr_spmm_tuned(const grim_bcr_matrix *A, const void *X_dev, int
     grim_status st = check_call(A, X_dev, N, ldx, Y_dev, ldy);
     if (st != GRIM_OK) return st;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    switch (spmm_route(A, X_dev, N, ldx, tile_n, strips_per_wg, kernel)) {
+    int wide_tn = 0;
+    int64_t wide_cols = 0;
+    switch (spmm_route(A, X_dev, N, ldx, Y_dev, ldy, tile_n, strips_per_wg, kernel, &wide_tn, &wide_cols)) {
         case ROUTE_SPMV: {
             GemvDesc d = desc_of(A);
             return launch_spmv(nullptr, d, nullptr, 1, A->M, A->K, A->BR, A->BC, A->dtype, A->gemv.uniform_kr, A->gemv.uniform_kc,
                                A->gemv.vec, A->gemv.krmax, A->gemv.kcmax, X_dev, 0, (int32_t)N, ldx, Y_dev, 0, ldy, stream);
         }
         case ROUTE_GATHER: return launch_spmm_gather(A, X_dev, N, ldx, Y_dev, ldy, stream);
+        case ROUTE_WIDE: {
+            // whole rounds of fat workgroups, the few columns left over on whatever suits them
+            st = launch_spmm_wide(A, X_dev, wide_cols, ldx, Y_dev, ldy, wide_tn, stream);
+            if (st != GRIM_OK || wide_cols >= N) return st;
+            const char *x_rest = static_cast<const char *>(X_dev) + wide_cols * dtype_size(A->dtype);
+            return grim_bcr_spmm_tuned(A, x_rest, N - wide_cols, ldx, Y_dev + wide_cols, ldy, 0, 0, 0, hip_stream);
+        }
         case ROUTE_MMA: {
             if (kernel == 0 && tile_n == 0 && strips_per_wg == 0) {
                 // whole rounds of workgroups on the staged kernel, the few columns left over on whatever suits them
@@ -751,8 +802,13 @@ grim_status grim_bcr_spmm_tuned(const grim_bcr_matrix *A, const void *X_dev, int
 const char *grim_bcr_spmm_kernel_name(const grim_bcr_matrix *A, const void *X_dev, int64_t N, int64_t ldx, int32_t tile_n,
                                       int32_t strips_per_wg, int32_t kernel) {
     if (!A || !X_dev || N < 1 || ldx < N || !A->on_device) return "none";
-    switch (spmm_route(A, X_dev, N, ldx, tile_n, strips_per_wg, kernel)) {
+    // (the output is taken to be 16-byte aligned with a leading dimension of N rounded up to 4, as allocators give it)
+    int wide_tn = 0;
+    int64_t wide_cols = 0;
+    switch (spmm_route(A, X_dev, N, ldx, reinterpret_cast<const float *>(uintptr_t(256)), (N + 3) / 4 * 4, tile_n, strips_per_wg,
+                       kernel, &wide_tn, &wide_cols)) {
         case ROUTE_SPMV: return "bcr_spmv";
+        case ROUTE_WIDE: return "bcr_spmm_wide";
         case ROUTE_GATHER: return "bcr_spmm_gather";
         case ROUTE_MMA: return "bcr_spmm_mma";
         case ROUTE_FMA: return "bcr_spmm_fma";
@@ -889,7 +945,7 @@ grim_status grim_bcr_gru_step(const grim_bcr_matrix *Ai, const grim_bcr_matrix *
 grim_status grim_bcr_group_create(const grim_bcr_matrix *const *mats, int32_t count, grim_bcr_group **out) {
     if (out) *out = nullptr;
     if (!mats || !out) return GRIM_ERR_NULL;
-    if (count < 1 || count > (1 << 20)) return GRIM_ERR_SHAPE;
+    if (count < 1 || count > 65535) return GRIM_ERR_SHAPE;   // grid.y = matrix
     for (int32_t i = 0; i < count; ++i)
         if (!mats[i]) return GRIM_ERR_NULL;
     const grim_bcr_matrix *A0 = mats[0];

@@ -1,7 +1,7 @@
 // Recurrent cells around the gate products.
 //
 // LSTM cell (Section 3.1: the gate matrices of an RNN layer are one
-// matrix-vector product per time step; Section 5 evaluates RNNs end to end).
+// matrix-vector product per time step; Section 6 evaluates RNNs end to end).
 //
 // The BCR product y = [W_ih | W_hh] * [x; h] delivers the four gate pre-activations stacked as
 // rows [0, H) input gate, [H, 2H) forget gate, [2H, 3H) cell candidate, [3H, 4H) output gate.
@@ -57,7 +57,7 @@ __global__ void __launch_bounds__(256) lstm_cell_kernel(LstmParams p) {
     }
 }
 
-// GRU cell (Section 5 evaluates a two-layer GRU).  Two products feed it, gi = W_i x and gh = W_h h,
+// GRU cell (Section 6.1: the evaluated RNN is a two-layer GRU; Section 6.3 times it).  Two products feed it, gi = W_i x and gh = W_h h,
 // each with its gate rows stacked reset, update, candidate; the reset gate scales the hidden-side
 // candidate product, which is why the two cannot be one product of a stacked matrix:
 //     r = sigmoid(gi_r + bi_r + gh_r + bh_r)        z = sigmoid(gi_z + bi_z + gh_z + bh_z)

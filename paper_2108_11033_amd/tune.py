@@ -1,4 +1,4 @@
-"""Block-size selection by measurement (Section 4.5 of the paper, "block size optimization").
+"""Block-size selection by measurement (Section 5.1 of the paper, "Block Size Optimization").
 
 The paper chooses a layer's block size offline: for each candidate size it synthesises a layer of the same
 shape whose weights are random but satisfy the pruning rate and the block size (latency depends on the rate,

@@ -78,7 +78,7 @@ def test_empty_and_full():
 
 
 def test_index_overhead_against_csr():
-    """The paper's comparison (Section 5, BCRC versus CSR): bytes that are not weights.  The saving comes from
+    """The paper's comparison (Section 6.4, BCRC versus CSR): bytes that are not weights.  The saving comes from
     rows that share one column list.  With one column block per strip (the paper's figure: few blocks) all kept
     rows of a strip share theirs; with many independently pruned column blocks per strip (c2: 72) almost no two
     rows agree on every block, and BCRC's extra arrays make it no smaller than CSR."""

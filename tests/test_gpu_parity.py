@@ -343,6 +343,78 @@ def test_staged_kernel_more_tiles_than_compute_units(g, dtype, BR, N, tile_n, st
     assert Y2.tobytes() == Y.tobytes()
 
 
+# ------------------------------------------------------------------ wide-tile staged matrix-core kernel
+@pytest.mark.parametrize("dtype", [gen.F16, gen.BF16])
+@pytest.mark.parametrize("BR,tile_n", [(16, 128), (16, 192), (32, 96)])
+@pytest.mark.parametrize("strips,K,N,ldx_pad,ldy_pad,chunk_rows", [
+    (16, 416, 1000, 0, 0, 0),       # one group, K tail (416 = 3 chunks of 128 + 32), ragged last tile
+    (24, 288, 776, 8, 4, 96),       # a second, half-filled strip group; 96-row chunks; padded leading dimensions
+    (8, 128, 200, 0, 0, 0),         # waves without a second strip; one chunk; one full tile + a shifted one (or one)
+    (5, 640, 384, 16, 8, 64),       # fewer strips than waves; 64-row chunks; N a multiple of both widths
+])
+def test_wide_kernel_shapes(g, dtype, BR, tile_n, strips, K, N, ldx_pad, ldy_pad, chunk_rows):
+    """kernel = 4 forced: every compiled tile width per block height, strip groups that are full, ragged and nearly
+    empty, chunk counts 1..10 (odd and even: both register sets end the pipeline), K tails, shifted last tiles, empty
+    blocks and empty strips; every entry against the oracle, and twice for bit reproducibility."""
+    M = strips * BR
+    mask = gen.random_mask(M, K, BR, 32, (0, BR // 4, BR // 2), (0, 4, 8, 13), seed=800 + BR + strips)
+    W = gen.normal_weights(M, K, dtype, seed=801)
+    X = gen.normal_activations(K, N, dtype, seed=802, relu=True)
+    A = pack_workload(g, W, dtype, mask, chunk_rows=chunk_rows)
+    Yref, S = oracle_product(W, X, dtype, mask)
+    if N < tile_n:
+        with pytest.raises(g.GrimError):
+            run_spmm(g, A, X, dtype, M, N, kernel=4, tile_n=tile_n)
+        return
+    Y = run_spmm(g, A, X, dtype, M, N, ldx=N + ldx_pad, ldy=N + ldy_pad, kernel=4, tile_n=tile_n)
+    assert_close(Y, Yref, S, dtype, f"wide {dtype} BR={BR} tn={tile_n} strips={strips} K={K} N={N}")
+    Y2 = run_spmm(g, A, X, dtype, M, N, ldx=N + ldx_pad, ldy=N + ldy_pad, kernel=4, tile_n=tile_n)
+    assert Y2.tobytes() == Y.tobytes()
+    assert A.unpack_layout(4).tobytes() == A.unpack().tobytes()
+
+
+def test_wide_kernel_integer_data_is_exact(g):
+    M, K, N, BR = 512, 1024, 2048, 32
+    mask = gen.random_mask(M, K, BR, 32, (4, 8, 16), (4, 8, 16), seed=810)
+    W = gen.small_int_values((M, K), gen.BF16, seed=811)
+    X = gen.small_int_values((K, N), gen.BF16, seed=812)
+    A = pack_workload(g, W, gen.BF16, mask)
+    Yref, _ = oracle_product(W, X, gen.BF16, mask)
+    for tn in (96, 0):
+        Y = run_spmm(g, A, X, gen.BF16, M, N, kernel=4, tile_n=tn)
+        assert np.array_equal(Y.astype(np.float64), Yref)
+
+
+def test_wide_kernel_more_tiles_than_compute_units_and_refusals(g):
+    """Two rounds of workgroups on the GPU (600 tiles), two strip groups; and the operands the kernel refuses."""
+    torch, dev = torch_dev()
+    M, K, N, BR = 32 * 16, 256, 600 * 96, 16
+    mask = gen.random_mask(M, K, BR, 32, (0, 4, 8), (0, 8, 16), seed=820)
+    W = gen.normal_weights(M, K, gen.F16, seed=821)
+    X = gen.normal_activations(K, N, gen.F16, seed=822, relu=True)
+    A = pack_workload(g, W, gen.F16, mask)
+    Y = run_spmm(g, A, X, gen.F16, M, N, kernel=4, tile_n=128)
+    rows = np.arange(0, M, 5)
+    cols = np.unique(np.concatenate([np.arange(0, 200), np.arange(N - 200, N), np.arange(256 * 128 - 64, 256 * 128 + 64),
+                                     np.random.default_rng(3).choice(N, 300, replace=False)]))
+    Yref, S = oracle_product(W, X, gen.F16, mask, rows=rows, cols=cols)
+    assert_close(Y[np.ix_(rows, cols)], Yref, S, gen.F16, "wide, 2 rounds of workgroups")
+    Xd = to_device(X[:, :1024].copy(), gen.F16)
+    Yd = torch.empty((M, 1024), dtype=torch.float32, device=dev)
+    s = torch.cuda.current_stream()
+    for kw in (dict(tile_n=96), dict(tile_n=64), dict(tile_n=128, strips_per_wg=4)):      # widths of the other block height
+        with pytest.raises(g.GrimError):
+            g.spmm(A, Xd, 1024, 1024, Yd, 1024, s, kernel=4, **kw)
+    with pytest.raises(g.GrimError):
+        g.spmm(A, Xd, 1020, 1024, Yd, 1024, s, kernel=4)                                   # N not a multiple of 8
+    with pytest.raises(g.GrimError):
+        g.spmm(A, Xd, 1000, 1020, Yd, 1024, s, kernel=4)                                   # rows of X not 16-byte aligned
+    w1 = gen.c1_single_fp32()
+    A1 = pack_workload(g, w1.W, w1.dtype, w1.mask)
+    with pytest.raises(g.GrimError):
+        run_spmm(g, A1, w1.X, w1.dtype, w1.M, w1.N, kernel=4)                              # fp32
+
+
 # ------------------------------------------------------------------ row-gathering matrix-core kernel
 @pytest.mark.parametrize("dtype", [gen.F16, gen.BF16])
 @pytest.mark.parametrize("N,ldx_pad,ldy_pad", [(64, 0, 0), (200, 0, 0), (196, 0, 0), (328, 8, 4), (132, 4, 3),

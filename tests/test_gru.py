@@ -1,4 +1,4 @@
-"""GRU cell around the BCR gate products (Section 5: the paper's RNN is a two-layer GRU): pins of the fp64
+"""GRU cell around the BCR gate products (Section 6.1: the paper's RNN is a two-layer GRU): pins of the fp64
 reference (CPU) and parity of the GPU cell kernel and of multi-step sequences against it (GPU)."""
 import numpy as np
 import pytest

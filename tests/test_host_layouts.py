@@ -10,13 +10,15 @@ import paper_2108_11033_amd as g
 from paper_2108_11033_amd.binding import GrimError
 from oracle import bcr_oracle as orc
 
-LAYOUTS = {1: "staged SpMM", 2: "row-gathering SpMM", 3: "SpMV"}
+LAYOUTS = {1: "staged SpMM", 2: "row-gathering SpMM", 3: "SpMV", 4: "wide-tile staged SpMM"}
 
 
 def _expected_layouts(dtype, BR, BC):
     want = set()
     if dtype != gen.F32 and BR in (16, 32) and BC <= 256:
         want.add(1)
+    if dtype != gen.F32 and BR in (16, 32) and BC <= 128:
+        want.add(4)
     if dtype != gen.F32 and (16 % BR == 0 or BR % 16 == 0):
         want.add(2)
     if BR <= 32 and BC <= 32:
@@ -93,6 +95,6 @@ def test_unpack_layout_argument_errors():
     assert lib.grim_bcr_unpack_layout(A.handle, 1, None, 32) == 1
     assert lib.grim_bcr_unpack_layout(A.handle, 1, p, 31) == 2             # ldw < K
     assert lib.grim_bcr_unpack_layout(A.handle, 0, p, 32) == 2             # unknown layout
-    assert lib.grim_bcr_unpack_layout(A.handle, 4, p, 32) == 2
+    assert lib.grim_bcr_unpack_layout(A.handle, 5, p, 32) == 2
     B = g.pack(W, gen.F16, 16, 16, mask.row_ptr, mask.row_idx, mask.col_ptr, mask.col_idx, host_only=True)
     assert lib.grim_bcr_unpack_layout(B.handle, 2, p, 32) == 7             # canonical arrays only: no layouts

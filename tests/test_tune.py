@@ -1,4 +1,4 @@
-"""Block-size selection (Section 4.5): the search rule on injected latencies (CPU), and one real search (GPU)."""
+"""Block-size selection (Section 5.1): the search rule on injected latencies (CPU), and one real search (GPU)."""
 import math
 
 import pytest
