@@ -10,7 +10,9 @@
 namespace grim {
 
 constexpr int kMmaMaxChunkRows = 256;   // rows of X staged in LDS per step by the matrix-core kernel
-constexpr int kWideMaxChunkRows = 128;  // the same for the wide-tile kernel (its tiles are 2-4x as wide)
+// the same for the wide-tile kernel: 128 rows of its 128- and 192-column tiles (BR = 16), 192 rows of its 96-column
+// tiles (BR = 32) -- what two LDS stages hold
+constexpr int wide_max_chunk_rows(int BR) { return BR == 32 ? 192 : 128; }
 constexpr int kWideMaxRecordBytes = 32 * 1024;   // records of one (chunk, group of 16 strips) the wide-tile kernel stages
 constexpr int kGemvMaxXBytes = 65536;   // bytes of x (K * batch elements) the SpMV kernel keeps in LDS
 

@@ -468,10 +468,10 @@ grim_status grim_bcr_pack(const void *W_host, grim_dtype dt, int64_t M, int64_t 
         }
         if (!(opt && opt->host_only == 1)) {
             // staged kernel: chunks of up to 256 rows, a 4-strip group's records within 16 KB (the producers move at
-            // most 32 KB of X rows and 16 KB of records per chunk); wide-tile kernel: chunks of up to 128 rows, a
+            // most 32 KB of X rows and 16 KB of records per chunk); wide-tile kernel: chunks of up to 128 or 192 rows, a
             // 16-strip group's records within 32 KB
             build_mma_layout(A, A->mma, opt ? opt->chunk_rows : 0, kMmaMaxChunkRows, 0, 16 * 1024);
-            build_mma_layout(A, A->mmaw, opt ? opt->chunk_rows : 0, kWideMaxChunkRows, 2, kWideMaxRecordBytes);
+            build_mma_layout(A, A->mmaw, opt ? opt->chunk_rows : 0, wide_max_chunk_rows(A->BR), 2, kWideMaxRecordBytes);
             build_gather_layout(A);
             build_gemv_layout(A);
         }

@@ -7,15 +7,15 @@
 //     each, and four fetching waves -- twelve waves, three per SIMD, 168 registers each: room for 96
 //     accumulators and two sets of operand fragments in a multiplying wave, for two chunks of loads in flight
 //     in a fetching wave;
-//   * K is cut into chunks of at most 128 rows.  The fetching waves move the rows of the tile and the step
-//     records of the group's strips global -> registers -> LDS; a chunk's loads are issued two chunks before it is
-//     written to LDS and three before it is multiplied, so that HBM latency spans two chunk periods; LDS holds
-//     two stages, one barrier per chunk.  Fetching runs under the multiplies of the chunk before;
+//   * K is cut into chunks of at most 128 rows (192 for the 96-column tiles of BR = 32).  The fetching waves move the rows of the tile and the step
+//     records of the group's strips global -> registers -> LDS; a chunk's rows are asked for two chunks before they
+//     are written to LDS and three before they are multiplied, so that HBM latency spans two chunk periods; LDS
+//     holds two stages, one barrier per chunk.  Fetching runs under the multiplies of the chunk before;
 //   * a multiplying wave walks the steps of both of its strips in a chunk as one list with a software pipeline
 //     one step deep: the LDS transpose reads (the gather of the kept rows straight into MFMA operand layout)
 //     and the weight read of the next step are issued before the current step is multiplied.  Lanes of rows a
 //     block does not keep multiply zeros, so sums land at strip positions and the scatter needs no pass of its own.
-// Record format and step layout are those of the staged kernel (bcr_matrix.hpp), cut for 128-row chunks.
+// Record format and step layout are those of the staged kernel (bcr_matrix.hpp), cut for these shorter chunks.
 // Accumulation is fp32 in a fixed order, no atomics.
 #include <algorithm>
 
@@ -70,7 +70,7 @@ __global__ void __launch_bounds__(kWideThreads) bcr_spmm_wide(WideParams p) {
     constexpr int NB = NT / NTB;                 // items per step
     constexpr int KS = BR == 16 ? 32 : 16;       // k slots per step
     constexpr int HDR = KS * 2 + (KS / 8) * 8;   // header bytes per step
-    constexpr int SXU = (kWideMaxChunkRows * CPR + kWideFetchThreads - 1) / kWideFetchThreads;   // X units per fetching thread and chunk
+    constexpr int SXU = (wide_max_chunk_rows(BR) * CPR + kWideFetchThreads - 1) / kWideFetchThreads;   // X units per fetching thread and chunk
     constexpr int NW = kWideMulWaves;
     constexpr int SRU = wide_sru(TN);
     static_assert(NT % NTB == 0, "sub-tiles come in whole batches");
@@ -126,9 +126,9 @@ __global__ void __launch_bounds__(kWideThreads) bcr_spmm_wide(WideParams p) {
         // rows 0 .. K - 1 of the tile's columns: the last valid byte is the end of row K - 1's piece
         const __amdgpu_buffer_rsrc_t xres = __builtin_amdgcn_make_buffer_rsrc(
             const_cast<unsigned short *>(p.X + n0), 0, (int)(((int64_t)(p.K - 1) * p.ldx + TN) * 2), kBufferFlags);
-        u32x4 RX0[SXU], RX1[SXU], RR0[SRU], RR1[SRU];
-        auto load_chunk = [&](int chunk, u32x4 (&rx)[SXU], u32x4 (&rr)[SRU]) {
-            // (past the last chunk the last one is fetched again and never stored)
+        u32x4 RX0[SXU], RX1[SXU], RR[SRU];
+        // (past the last chunk the last one is fetched again and never stored)
+        auto load_records = [&](int chunk, u32x4 (&rr)[SRU]) {
             chunk = chunk < p.nchunks ? chunk : p.nchunks - 1;
             const Table bp = bptr + (int64_t)chunk * (p.nbr + 1);
             const int b0 = __builtin_amdgcn_readfirstlane(bp[t0]), units = __builtin_amdgcn_readfirstlane(bp[t1]) - b0;
@@ -137,40 +137,55 @@ __global__ void __launch_bounds__(kWideThreads) bcr_spmm_wide(WideParams p) {
 #pragma unroll
             for (int i = 0; i < SRU; ++i)
                 rr[i] = __builtin_amdgcn_raw_buffer_load_b128(rres, (i * kWideFetchThreads + ft) * 16, 0, 0);
+        };
+        auto load_rows = [&](int chunk, u32x4 (&rx)[SXU]) {
+            chunk = chunk < p.nchunks ? chunk : p.nchunks - 1;
             const int soff = __builtin_amdgcn_readfirstlane((int)((int64_t)chunk * p.chunk_rows * p.ldx * 2));
 #pragma unroll
             for (int i = 0; i < SXU; ++i) rx[i] = __builtin_amdgcn_raw_buffer_load_b128(xres, xoff[i], soff, 0);
         };
-        auto store_chunk = [&](int chunk, const u32x4 (&rx)[SXU], const u32x4 (&rr)[SRU]) {
-            char *sbase = lds + (chunk & 1) * stage_bytes;
+        auto store_records = [&](int chunk, const u32x4 (&rr)[SRU]) {
+            char *sbase = lds + (chunk & 1) * stage_bytes + xbytes;
             const Table bp = bptr + (int64_t)chunk * (p.nbr + 1);
             const int units = bp[t1] - bp[t0];
 #pragma unroll
             for (int i = 0; i < SRU; ++i) {
                 const int u = i * kWideFetchThreads + ft;
-                if (u < units) *reinterpret_cast<u32x4 *>(sbase + xbytes + u * 16) = rr[i];
+                if (u < units) *reinterpret_cast<u32x4 *>(sbase + u * 16) = rr[i];
             }
+        };
+        auto store_rows = [&](int chunk, const u32x4 (&rx)[SXU]) {
+            char *sbase = lds + (chunk & 1) * stage_bytes;
+            int fo = ft;
+            asm volatile("" : "+v"(fo));         // the unit addresses are recomputed here, not held in registers across the loop
 #pragma unroll
             for (int i = 0; i < SXU; ++i) {
-                const int u = i * kWideFetchThreads + ft;
+                const int u = i * kWideFetchThreads + fo;
                 const int row = u / CPR, c = u - row * CPR;
                 if (row < p.chunk_rows) *reinterpret_cast<u32x4 *>(sbase + row * PITCH + c * 16) = rx[i];
             }
         };
-        // chunk c is multiplied from stage c % 2 while chunk c + 1 is written to the other stage (it was read last
-        // in chunk c - 1) from one register set and chunk c + 2 is in flight into the other set
-        load_chunk(0, RX0, RR0);
-        load_chunk(1, RX1, RR1);
-        store_chunk(0, RX0, RR0);
-        load_chunk(2, RX0, RR0);
+        // Chunk c is multiplied from stage c % 2 while chunk c + 1 is written to the other stage (read last in chunk
+        // c - 1).  Rows of X come from HBM: two register sets, a chunk's rows are asked for two chunks before they are
+        // written.  Records come from L2: one set, asked for one chunk ahead, and always BEFORE the rows asked for in
+        // the same period, so that the wait for them (loads return in order) leaves those younger rows in flight.
+        load_rows(0, RX0);
+        load_records(0, RR);
+        store_rows(0, RX0);
+        store_records(0, RR);
+        load_records(1, RR);
+        load_rows(1, RX1);
+        load_rows(2, RX0);
         __syncthreads();
         for (int c = 0; c < p.nchunks; c += 2) {
-            if (c + 1 < p.nchunks) store_chunk(c + 1, RX1, RR1);
-            load_chunk(c + 3, RX1, RR1);
+            if (c + 1 < p.nchunks) { store_rows(c + 1, RX1); store_records(c + 1, RR); }
+            load_records(c + 2, RR);
+            load_rows(c + 3, RX1);
             __syncthreads();
             if (c + 1 >= p.nchunks) break;
-            if (c + 2 < p.nchunks) store_chunk(c + 2, RX0, RR0);
-            load_chunk(c + 4, RX0, RR0);
+            if (c + 2 < p.nchunks) { store_rows(c + 2, RX0); store_records(c + 2, RR); }
+            load_records(c + 3, RR);
+            load_rows(c + 4, RX0);
             __syncthreads();
         }
         return;
@@ -290,15 +305,15 @@ __global__ void __launch_bounds__(kWideThreads) bcr_spmm_wide(WideParams p) {
                 hn = load_hdr(hdr_of(v + 3));
                 issue(v + 2, hc, fb, fa);
                 __builtin_amdgcn_sched_barrier(0);
-                multiply(a1, 0, fb);
+                if (v + 1 < n) multiply(a1, 0, fb);       // (a pair may reach one step past the list)
                 __builtin_amdgcn_sched_barrier(0);
             };
             hc = load_hdr(hdr_of(0));
             hn = load_hdr(hdr_of(1));
             issue(0, hc, fb, fa);
-            // Steps go in pairs on every path (no single-step tail: a tail that updates the accumulators on one path
-            // only makes the compiler keep a second copy of them).  A pair that reaches past the last step multiplies
-            // zero weights in its second half: at most one such half per chunk.
+            // Steps go in pairs on every path (a separate single-step tail that updates the accumulators on one path
+            // only makes the compiler keep a second copy of them); a pair that reaches one step past the list skips
+            // its second multiply.
             int v = 0;
             for (; v + 1 < en.nA; v += 2) pair(v, acc[0], acc[0]);
             if (v < en.nA) {
@@ -380,7 +395,7 @@ bool wide_applies(const grim_bcr_matrix *A, const void *X, int64_t N, int64_t ld
     if (!A->mmaw.present || A->dtype == GRIM_F32) return false;
     if (reinterpret_cast<uintptr_t>(X) % 16 != 0 || ldx % 8 != 0 || N % 8 != 0) return false;      // 16-byte row pieces
     if (reinterpret_cast<uintptr_t>(Y) % 16 != 0 || ldy % 4 != 0) return false;                    // 16-byte stores
-    if (A->mmaw.chunk_rows > kWideMaxChunkRows) return false;
+    if (A->mmaw.chunk_rows > wide_max_chunk_rows(A->BR)) return false;
     if (A->K * ldx * 2 >= (int64_t(1) << 31)) return false;                                        // 32-bit buffer offsets
     for (int tn : {96, 128, 192}) {
         if (tile_n && tn != tile_n) continue;

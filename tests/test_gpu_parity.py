@@ -565,7 +565,7 @@ def test_gather_kernel_block_heights(g, dtype, BR, BC):
 
 def test_kernel_choice_follows_the_cost_model(g):
     """grim_bcr_spmm_kernel_name reports the route; few tiles per strip group -> row-gathering kernel, very
-    many tiles of a many-strip matrix -> staged kernel; fp32 -> FMA kernel; N <= 8 -> SpMV."""
+    many tiles of a many-strip matrix -> wide-tile staged kernel; fp32 -> FMA kernel; N <= 8 -> SpMV."""
     torch, dev = torch_dev()
     wl = gen.c2_vgg_conv(200)
     A = pack_workload(g, wl.W, wl.dtype, wl.mask)
@@ -580,7 +580,11 @@ def test_kernel_choice_follows_the_cost_model(g):
     assert g.spmm_kernel_name(A, X, 200, 200, kernel=1) == "bcr_spmm_fma"
     assert g.spmm_kernel_name(A, X, 200, 100) == "none"               # ldx < N
     big = torch.empty(16, dtype=torch.float16, device=dev)            # only the address is looked at
-    assert g.spmm_kernel_name(A, big, 50176, 50176) == "bcr_spmm_mma"
+    assert g.spmm_kernel_name(A, big, 50176, 50176) == "bcr_spmm_wide"     # a round of 192-column tiles (+ a remainder)
+    assert g.spmm_kernel_name(A, big, 50176, 50176, kernel=2) == "bcr_spmm_mma"
+    assert g.spmm_kernel_name(A, big, 50176, 50176, kernel=4, tile_n=128) == "bcr_spmm_wide"
+    assert g.spmm_kernel_name(A, big, 50176, 50176, kernel=4, tile_n=96) == "none"      # 96 columns: 32-row blocks only
+    assert g.spmm_kernel_name(A, big, 50180, 50180) != "bcr_spmm_wide"     # N not a multiple of 8
     w1 = gen.c1_single_fp32()
     A1 = pack_workload(g, w1.W, w1.dtype, w1.mask)
     assert g.spmm_kernel_name(A1, to_device(w1.X, w1.dtype), w1.N, w1.N) == "bcr_spmm_fma"
