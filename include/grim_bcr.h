@@ -263,9 +263,20 @@ grim_status grim_bcr_conv2d_act(const grim_bcr_matrix *A, const void *F_dev, int
  *   h32_dev     optional fp32 copy of h (ldh32); NULL to skip
  * grim_bcr_lstm_step = grim_bcr_spmv(A, xh_dev, ...) (more than 8 columns: grim_bcr_spmm) into
  * gates_dev, then grim_lstm_cell; A must have 4H rows.  Both only enqueue work on hip_stream.
+ * With one right-hand side, fp16 / bf16, every block of A keeping the same number of rows and of columns, H a
+ * multiple of BR, and h_dev outside the vector xh_dev (write the new h into the NEXT step's input vector), the
+ * step is ONE launch: each workgroup computes the four gate rows of BR hidden units and applies the cell before it
+ * stores anything (gates_dev still receives the pre-activations).  Otherwise two launches.
  * Errors: NULL, SHAPE (batch < 1, H < 1, leading dimension too small, A->M != 4H), DTYPE, DEVICE,
  * UNSUPPORTED.
  */
+/* grim_bcr_rnn_step_launches -- how many kernels a recurrent step enqueues (for reports and tests; launches nothing):
+ * grim_bcr_lstm_step of A (Ah = NULL) or grim_bcr_gru_step of (A, Ah) at this batch, for operands with the usual
+ * alignment and a new state that does not overlap the step's inputs.  1 = the gate product(s) with the cell in the
+ * epilogue; 2 = product(s) in one launch, then the cell; 3 = a launch per product, then the cell; 0 = the step would
+ * be refused. */
+int32_t grim_bcr_rnn_step_launches(const grim_bcr_matrix *A, const grim_bcr_matrix *Ah, int32_t batch);
+
 grim_status grim_lstm_cell(const float *gates_dev, int64_t ldg, const float *bias_dev, float *c_dev, int64_t ldc,
                            void *h_dev, grim_dtype dt, int64_t ldh, float *h32_dev, int64_t ldh32,
                            int64_t H, int32_t batch, void *hip_stream);
@@ -292,7 +303,9 @@ grim_status grim_bcr_lstm_step(const grim_bcr_matrix *A, const void *xh_dev, int
  * kernels for W_i and W_h of one shape and block size, on the row-gathering SpMM kernel for 4 to 60
  * columns in multiples of 4)
  * into gi_dev and gh_dev, then grim_gru_cell writing hout_dev (may be hin_dev itself: the cell runs
- * after both products).  Both only enqueue work on hip_stream.  Errors: NULL, SHAPE (rows not 3H on
+ * after both products).  With one right-hand side, fp16 / bf16 matrices of one shape, block size and kept counts,
+ * H a multiple of BR, and hout_dev overlapping neither x_dev nor hin_dev, the step is ONE launch (products with
+ * the cell in their epilogue; gi_dev / gh_dev still receive the products).  Both only enqueue work on hip_stream.  Errors: NULL, SHAPE (rows not 3H on
  * both, Ah->K != H, batch < 1, leading dimension too small), DTYPE (element types differ), DEVICE,
  * UNSUPPORTED (as the products).
  */

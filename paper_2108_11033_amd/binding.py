@@ -58,7 +58,7 @@ EXPORTS = ["grim_bcr_pack", "grim_bcr_unpack", "grim_bcr_arrays", "grim_bcr_spmm
            "grim_bcr_spmv", "grim_bcr_group_create", "grim_bcr_spmv_batched", "grim_bcr_group_free",
            "grim_bcr_free", "grim_status_str", "grim_bcr_spmm_kernel_name",
            "grim_bcr_export_bcrc", "grim_bcrc_arrays", "grim_bcrc_free", "grim_lstm_cell", "grim_bcr_lstm_step", "grim_gru_cell", "grim_bcr_gru_step",
-           "grim_bcr_conv2d", "grim_bcr_conv2d_act", "grim_bcr_unpack_layout"]
+           "grim_bcr_conv2d", "grim_bcr_conv2d_act", "grim_bcr_unpack_layout", "grim_bcr_rnn_step_launches"]
 
 
 def lib_path() -> str:
@@ -106,6 +106,7 @@ def load_library():
     lib.grim_gru_cell.argtypes = [p, i64, p, i64, p, p, p, i64, p, i32, i64, i64, i32, p]
     lib.grim_bcr_gru_step.argtypes = [p, p, p, i64, p, i64, i32, p, i64, p, i64, p, p, p, i64, p, i64, p]
     lib.grim_bcr_spmm_kernel_name.argtypes = [p, p, i64, i64, i32, i32, i32]
+    lib.grim_bcr_rnn_step_launches.argtypes = [p, p, i32]
     for name in EXPORTS:
         getattr(lib, name).restype = i32
     lib.grim_status_str.restype = ctypes.c_char_p
@@ -280,6 +281,11 @@ def conv2d_act(A: BcrMatrix, F, Cin: int, H: int, W: int, kh: int, kw: int, bias
     """grim_bcr_conv2d_act: the convolution with bias, rectifier and output rounding in its epilogue."""
     _check(A._lib.grim_bcr_conv2d_act(A.handle, _addr(F), Cin, H, W, kh, kw, _addr(bias), int(bool(relu)), _addr(out),
                                       _DT_CODE[out_dtype], ldo, _stream(stream)), "grim_bcr_conv2d_act")
+
+
+def rnn_step_launches(A: BcrMatrix, Ah: Optional[BcrMatrix], batch: int) -> int:
+    """grim_bcr_rnn_step_launches: kernels per LSTM step of A (Ah None) or GRU step of (A, Ah)."""
+    return int(A._lib.grim_bcr_rnn_step_launches(A.handle, Ah.handle if Ah is not None else None, batch))
 
 
 def lstm_cell(gates, ldg: int, bias, c, ldc: int, h, dtype, ldh: int, h32, ldh32: int, H: int, batch: int, stream=None):

@@ -38,13 +38,25 @@ def _run(cmd, verbose):
         print(err)
 
 
+def _stale(src: str, obj: str) -> bool:
+    """An object is reused only while it is newer than its source and than every header (the sources share struct
+    definitions: an object built against an older header would read a matrix at the wrong offsets)."""
+    if not os.path.exists(obj):
+        return True
+    t = os.path.getmtime(obj)
+    deps = [src] + [os.path.join(d, f) for d in (CSRC, os.path.join(ROOT, "include")) for f in os.listdir(d)
+                    if f.endswith((".h", ".hpp"))]
+    return any(os.path.getmtime(d) > t for d in deps)
+
+
 def build(verbose: bool = False, only=None) -> str:
-    """Compile every source (or only the named ones, reusing the other objects) and link the library."""
+    """Compile every source and link the library.  `only`: recompile the named sources plus whatever is out of date,
+    reusing the other objects (a development shortcut; build() in __graft_entry__ compiles everything)."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     os.makedirs(OBJ, exist_ok=True)
     sources = list(SOURCES)
     objs = {s: os.path.join(OBJ, os.path.splitext(s)[0] + ".o") for s in sources}
-    todo = [s for s in sources if only is None or s in only or not os.path.exists(objs[s])]
+    todo = [s for s in sources if only is None or s in only or _stale(os.path.join(CSRC, s), objs[s])]
     jobs = min(len(todo), int(os.environ.get("MAX_JOBS", "8"))) or 1
     with ThreadPoolExecutor(jobs) as pool:
         list(pool.map(lambda s: _run([hipcc] + _flags() + ["-c", os.path.join(CSRC, s), "-o", objs[s]], verbose), todo))

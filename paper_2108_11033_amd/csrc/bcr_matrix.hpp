@@ -100,6 +100,7 @@ struct GemvLayout {
 
 struct DeviceCanonical {
     int32_t *strip_order = nullptr;
+    int32_t *strip_pos = nullptr;    // inverse of strip_order: stored position of original strip s
     int32_t *row_ptr = nullptr;
     uint16_t *row_idx = nullptr;
     int32_t *col_ptr = nullptr;
@@ -155,6 +156,22 @@ struct GemvDesc {
     const int32_t *strip_order;
 };
 
+// Recurrent cell applied in the epilogue of the one-right-hand-side wave-per-strip kernel (Section 3.1: an RNN layer
+// is one matrix-vector product per time step; the gate nonlinearities and the state update are the elementwise rest).
+// A workgroup then owns BR hidden units: its waves take the strips that hold these units' gate rows -- LSTM: four
+// strips of [W_ih | W_hh] (input, forget, candidate, output gate); GRU: three strips (reset, update, candidate) of
+// each of W_i and W_h -- found through `strip_pos`, the stored position of every original strip.
+struct RnnCell {
+    const int32_t *strip_pos;    // first matrix: stored position of original strip s
+    const int32_t *strip_pos2;   // second matrix (GRU)
+    const float *bias, *bias2;   // LSTM: 4H (bias); GRU: 3H input side (bias), 3H hidden side (bias2); null = none
+    float *c;                    // LSTM: cell state, H fp32, stride ldc, updated in place; GRU: hidden state h32
+    void *h;                     // new hidden state in element type hdt, stride ldh (null: not written)
+    float *h32;                  // LSTM: optional fp32 copy of the new hidden state, stride ldh32
+    int64_t ldc, ldh, ldh32;
+    int32_t H, hdt;
+};
+
 struct grim_bcr_group {
     int32_t count = 0;
     int64_t M = 0, K = 0;
@@ -204,6 +221,10 @@ grim_status launch_spmv(const GemvDesc *table_dev_or_null, const GemvDesc &singl
                         int64_t M, int64_t K, int32_t BR, int32_t BC, int32_t dtype, int32_t ukr,
                         int32_t ukc, int32_t vec, int32_t krmax, int32_t kcmax, const void *x, int64_t x_stride, int32_t batch,
                         int64_t ldx, float *y, int64_t y_stride, int64_t ldy, hipStream_t stream);
+bool spmv_cell_applies(int kind, int64_t M, int64_t K, int32_t BR, int32_t BC, int32_t dtype, int32_t ukr, int32_t ukc, int64_t H);
+grim_status launch_spmv_cell(int kind, const GemvDesc &d1, const GemvDesc *d2, int64_t M, int64_t K, int32_t BR, int32_t BC,
+                             int32_t dtype, int32_t ukr, int32_t ukc, const void *x, int64_t x_stride, int64_t ldx, float *y,
+                             int64_t y_stride, int64_t ldy, const RnnCell &cell, hipStream_t stream);
 grim_status launch_lstm_cell(const float *gates, int64_t ldg, const float *bias, float *c, int64_t ldc, void *h,
                              int32_t dtype, int64_t ldh, float *h32, int64_t ldh32, int64_t H, int32_t batch,
                              hipStream_t stream);

@@ -274,7 +274,10 @@ grim_status upload(grim_bcr_matrix *A) {
     if (hipGetDevice(&A->device) != hipSuccess) return GRIM_ERR_DEVICE;
     Slab s;
     auto bytes = [](const auto &v) { return v.size() * sizeof(v[0]); };
+    std::vector<int32_t> strip_pos((size_t)A->nbr);
+    for (int64_t q = 0; q < A->nbr; ++q) strip_pos[(size_t)A->strip_order[q]] = (int32_t)q;
     size_t o_so = s.add(bytes(A->strip_order));
+    size_t o_sp = s.add(bytes(strip_pos));
     size_t o_rp = s.add(bytes(A->row_ptr));
     size_t o_ri = s.add(bytes(A->row_idx));
     size_t o_cp = s.add(bytes(A->col_ptr));
@@ -314,7 +317,7 @@ grim_status upload(grim_bcr_matrix *A) {
     auto put = [&](size_t off, const void *src, size_t n) -> bool {
         return n == 0 || hipMemcpy(base + off, src, n, hipMemcpyHostToDevice) == hipSuccess;
     };
-    bool ok = put(o_so, A->strip_order.data(), bytes(A->strip_order)) && put(o_rp, A->row_ptr.data(), bytes(A->row_ptr)) &&
+    bool ok = put(o_so, A->strip_order.data(), bytes(A->strip_order)) && put(o_sp, strip_pos.data(), bytes(strip_pos)) && put(o_rp, A->row_ptr.data(), bytes(A->row_ptr)) &&
               put(o_ri, A->row_idx.data(), bytes(A->row_idx)) && put(o_cp, A->col_ptr.data(), bytes(A->col_ptr)) &&
               put(o_ci, A->col_idx.data(), bytes(A->col_idx)) && put(o_bp, A->blk_ptr.data(), bytes(A->blk_ptr)) &&
               put(o_w, A->weights.data(), A->weights.size()) && put(o_rm, A->rowmask64.data(), bytes(A->rowmask64));
@@ -331,6 +334,7 @@ grim_status upload(grim_bcr_matrix *A) {
         ok = put(o_gm, A->gemv.masks.data(), bytes(A->gemv.masks)) && put(o_go, A->gemv.woff.data(), bytes(A->gemv.woff));
     if (!ok) { (void)hipGetLastError(); (void)hipFree(base); return GRIM_ERR_DEVICE; }
     A->dev.strip_order = reinterpret_cast<int32_t *>(base + o_so);
+    A->dev.strip_pos = reinterpret_cast<int32_t *>(base + o_sp);
     A->dev.row_ptr = reinterpret_cast<int32_t *>(base + o_rp);
     A->dev.row_idx = reinterpret_cast<uint16_t *>(base + o_ri);
     A->dev.col_ptr = reinterpret_cast<int32_t *>(base + o_cp);
@@ -380,6 +384,12 @@ grim_status check_call(const grim_bcr_matrix *A, const void *X, int64_t N, int64
 
 bool gemv_ok(const grim_bcr_matrix *A, int64_t N) {
     return A->gemv.present && N >= 1 && N <= 8 && A->K * N * dtype_size(A->dtype) <= kGemvMaxXBytes;
+}
+
+// do the byte ranges [a, a + na) and [b, b + nb) overlap?
+bool ranges_overlap(const void *a, int64_t na, const void *b, int64_t nb) {
+    const uintptr_t a0 = reinterpret_cast<uintptr_t>(a), b0 = reinterpret_cast<uintptr_t>(b);
+    return a0 < b0 + (uintptr_t)nb && b0 < a0 + (uintptr_t)na;
 }
 
 GemvDesc desc_of(const grim_bcr_matrix *A) {
@@ -883,11 +893,46 @@ grim_status grim_bcr_lstm_step(const grim_bcr_matrix *A, const void *xh_dev, int
     if (A->M % 4 != 0) return GRIM_ERR_SHAPE;
     const int64_t H = A->M / 4;
     if (batch < 1 || ldc < batch || (h_dev && ldh < batch) || (h32_dev && ldh32 < batch)) return GRIM_ERR_SHAPE;
+    if (batch == 1 && A->gemv.present) {
+        // One launch: the cell in the epilogue of the gate product.  Workgroups then write h while others may still
+        // read the input vector, so the new h must not land in the vector this step reads.
+        grim_status st0 = check_call(A, xh_dev, batch, ldx, gates_dev, ldg);
+        if (st0 != GRIM_OK) return st0;
+        const int esz = dtype_size(A->dtype);
+        const bool aliased = h_dev && ranges_overlap(xh_dev, ((A->K - 1) * ldx + 1) * esz, h_dev, ((H - 1) * ldh + 1) * esz);
+        if (!aliased) {
+            RnnCell cell{A->dev.strip_pos, nullptr, bias_dev, nullptr, c_dev, h_dev, h32_dev, ldc, ldh, ldh32, (int32_t)H, A->dtype};
+            st0 = launch_spmv_cell(1, desc_of(A), nullptr, A->M, A->K, A->BR, A->BC, A->dtype, A->gemv.uniform_kr,
+                                   A->gemv.uniform_kc, xh_dev, 0, ldx, gates_dev, 0, ldg, cell, static_cast<hipStream_t>(hip_stream));
+            if (st0 != GRIM_ERR_UNSUPPORTED) return st0;
+        }
+    }
     grim_status st = batch <= 8 ? grim_bcr_spmv(A, xh_dev, batch, ldx, gates_dev, ldg, hip_stream)
                                 : grim_bcr_spmm(A, xh_dev, batch, ldx, gates_dev, ldg, hip_stream);
     if (st != GRIM_OK) return st;
     return grim_lstm_cell(gates_dev, ldg, bias_dev, c_dev, ldc, h_dev, (grim_dtype)A->dtype, ldh, h32_dev, ldh32, H, batch,
                           hip_stream);
+}
+
+int32_t grim_bcr_rnn_step_launches(const grim_bcr_matrix *A, const grim_bcr_matrix *Ah, int32_t batch) {
+    if (!A || batch < 1 || !A->on_device) return 0;
+    if (!Ah) {
+        if (A->M % 4 != 0) return 0;
+        const bool fused = batch == 1 && A->gemv.present &&
+                           spmv_cell_applies(1, A->M, A->K, A->BR, A->BC, A->dtype, A->gemv.uniform_kr, A->gemv.uniform_kc, A->M / 4);
+        return fused ? 1 : 2;
+    }
+    if (A->M != Ah->M || A->M % 3 != 0 || Ah->K != A->M / 3 || A->dtype != Ah->dtype || !Ah->on_device) return 0;
+    const bool same = A->K == Ah->K && A->BR == Ah->BR && A->BC == Ah->BC && A->gemv.present && Ah->gemv.present;
+    const bool fused = batch == 1 && same && A->gemv.uniform_kr == Ah->gemv.uniform_kr && A->gemv.uniform_kc == Ah->gemv.uniform_kc &&
+                       spmv_cell_applies(2, A->M, A->K, A->BR, A->BC, A->dtype, A->gemv.uniform_kr, A->gemv.uniform_kc, A->M / 3);
+    if (fused) return 1;
+    // both products in one launch (SpMV kernels up to 8 columns when the matrices have one shape; the row-gathering
+    // kernel for 4 .. 60 columns in multiples of 4), then the cell; otherwise a launch per product
+    const bool one_spmv = batch <= 8 && same && A->K * batch * dtype_size(A->dtype) <= kGemvMaxXBytes;
+    const bool one_gather = batch < 64 && batch % 4 == 0 && A->gather.present && Ah->gather.present &&
+                            A->gather.nstrips == Ah->gather.nstrips;
+    return one_spmv || one_gather ? 2 : 3;
 }
 
 grim_status grim_gru_cell(const float *gi_dev, int64_t ldgi, const float *gh_dev, int64_t ldgh, const float *bias_i_dev,
@@ -919,6 +964,22 @@ grim_status grim_bcr_gru_step(const grim_bcr_matrix *Ai, const grim_bcr_matrix *
     const ptrdiff_t xd = static_cast<const char *>(hin_dev) - static_cast<const char *>(x_dev);
     const ptrdiff_t yd = reinterpret_cast<const char *>(gh_dev) - reinterpret_cast<const char *>(gi_dev);
     // (8 columns in 16-byte-aligned rows are quicker on the matrix cores, as for a lone product)
+    if (batch == 1 && Ai->K == Ah->K && Ai->BR == Ah->BR && Ai->BC == Ah->BC && Ai->gemv.present && Ah->gemv.present &&
+        Ai->gemv.uniform_kr == Ah->gemv.uniform_kr && Ai->gemv.uniform_kc == Ah->gemv.uniform_kc && ldx == ldhin && ldgi == ldgh &&
+        xd % esz == 0 && yd % 4 == 0) {
+        // One launch: both gate products with the cell in the epilogue.  The new state must not land in the vector
+        // the hidden-side product reads (workgroups write it while others may still read).
+        const bool aliased = hout_dev && (ranges_overlap(hin_dev, ((Ah->K - 1) * ldhin + 1) * esz, hout_dev, ((H - 1) * ldhout + 1) * esz) ||
+                                          ranges_overlap(x_dev, ((Ai->K - 1) * ldx + 1) * esz, hout_dev, ((H - 1) * ldhout + 1) * esz));
+        if (!aliased) {
+            const GemvDesc di = desc_of(Ai), dh = desc_of(Ah);
+            RnnCell cell{Ai->dev.strip_pos, Ah->dev.strip_pos, bias_i_dev, bias_h_dev, h32_dev, hout_dev, nullptr, ldh32, ldhout, 0,
+                         (int32_t)H, Ai->dtype};
+            st = launch_spmv_cell(2, di, &dh, Ai->M, Ai->K, Ai->BR, Ai->BC, Ai->dtype, Ai->gemv.uniform_kr, Ai->gemv.uniform_kc,
+                                  x_dev, xd / esz, ldx, gi_dev, yd / 4, ldgi, cell, static_cast<hipStream_t>(hip_stream));
+            if (st != GRIM_ERR_UNSUPPORTED) return st;
+        }
+    }
     const bool eight_on_matrix_cores = ldx == ldhin && ldgi == ldgh && skinny_on_matrix_cores(Ai, x_dev, batch, ldx) &&
                                        skinny_on_matrix_cores(Ah, hin_dev, batch, ldx) &&
                                        gather_pair_applies(Ai, x_dev, Ah, hin_dev, batch, ldx);

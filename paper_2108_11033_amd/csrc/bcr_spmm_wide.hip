@@ -359,7 +359,7 @@ __global__ void __launch_bounds__(kWideThreads) bcr_spmm_wide(WideParams p) {
         __syncthreads();
     }
 
-    // ---- write the strip tiles of Y (original row order) ----
+    // ---- write the strip tiles of Y (original row order); streaming stores: Y is written once and not read here ----
 #pragma unroll
     for (int s = 0; s < 2; ++s) {
         const int t = s == 0 ? tA : tB;
@@ -370,14 +370,14 @@ __global__ void __launch_bounds__(kWideThreads) bcr_spmm_wide(WideParams p) {
             if constexpr (BR == 16) {
                 // D[n][m]: lane holds m = lane % 16, n = 4 * (lane / 16) + 0..3 (16-byte aligned: checked at launch)
                 const int64_t n = n0 + q * 16 + 4 * (lane >> 4);
-                *reinterpret_cast<f32x4 *>(p.Y + (row0 + (lane & 15)) * p.ldy + n) = acc[s][q];
+                __builtin_nontemporal_store(acc[s][q], reinterpret_cast<f32x4 *>(p.Y + (row0 + (lane & 15)) * p.ldy + n));
             } else {
                 // D[m][n]: lane holds n = lane % 32, m = 8 * (e / 4) + 4 * (lane / 32) + e % 4
                 const int64_t n = n0 + q * 32 + (lane & 31);
 #pragma unroll
                 for (int e = 0; e < 16; ++e) {
                     const int m = 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
-                    p.Y[(row0 + m) * p.ldy + n] = acc[s][q][e];
+                    __builtin_nontemporal_store(acc[s][q][e], &p.Y[(row0 + m) * p.ldy + n]);
                 }
             }
         }

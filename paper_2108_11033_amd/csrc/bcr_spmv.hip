@@ -44,6 +44,7 @@ struct GemvParams {
     int32_t xvec16;          // x is contiguous and 16-byte aligned: copy with 16-byte loads
     int32_t sps;             // wave kernel: consecutive strips per wave
     int32_t batch;           // right-hand sides (kernels that take it at run time)
+    RnnCell cell;            // recurrent cell in the epilogue (wave-per-strip kernel, one right-hand side)
 };
 
 
@@ -319,31 +320,56 @@ __host__ __device__ constexpr int exact_region_vectors(int nv) {
 }
 
 
-template <int DT, int KR, int KC>
-__global__ void __launch_bounds__(256) bcr_spmv_wave_exact(GemvParams p) {
+__device__ __forceinline__ float rnn_sigmoid(float v) { return 1.0f / (1.0f + expf(-v)); }
+__device__ __forceinline__ unsigned short rnn_f32_to_bf16(float f) {
+    unsigned int u = __builtin_bit_cast(unsigned int, f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (unsigned short)((u >> 16) | 0x40u);   // NaN stays NaN
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (unsigned short)(u >> 16);
+}
+__device__ __forceinline__ void rnn_store_h(void *h, int hdt, int64_t at, float v) {
+    if (hdt == GRIM_F32) static_cast<float *>(h)[at] = v;
+    else if (hdt == GRIM_F16) static_cast<_Float16 *>(h)[at] = (_Float16)v;
+    else static_cast<unsigned short *>(h)[at] = rnn_f32_to_bf16(v);
+}
+
+// CELL: 0 = the product alone; 1 = LSTM step, 2 = GRU step (see RnnCell): the workgroup's waves take the strips of
+// one group of BR hidden units, and the cell is applied to their sums before anything is stored.
+constexpr int exact_waves(int cell) { return cell == 2 ? 6 : 4; }
+
+template <int DT, int KR, int KC, int CELL = 0>
+__global__ void __launch_bounds__(exact_waves(CELL) * 64) bcr_spmv_wave_exact(GemvParams p) {
     using T = typename GElem<DT>::type;
     constexpr int ESZ = (int)sizeof(T);
+    constexpr int NWV = exact_waves(CELL), NTHR = NWV * 64;
     constexpr int NV = KR * KC * ESZ / 16;       // 16-byte vectors per block
     constexpr int PB = exact_pad_period(NV);     // one vector of padding after every PB blocks (0: none)
     static_assert(KR * KC * ESZ % 16 == 0 && (ESZ == 4 || KC % 2 == 0) && KC <= 32 && KR <= 32, "block shape");
     extern __shared__ __attribute__((aligned(16))) char smem[];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int xbytes = (p.K * ESZ + 15) & ~15;
-    T *xs = reinterpret_cast<T *>(smem);
+    // GRU: both input vectors sit in LDS, the hidden-side one behind the input-side one
+    const int xbytes1 = (p.K * ESZ + 15) & ~15, xbytes = CELL == 2 ? 2 * xbytes1 : xbytes1;
+    const int64_t mi = CELL == 2 ? wave / 3 : blockIdx.y;         // GRU: waves 0-2 take W_i, waves 3-5 W_h
+    T *xs = reinterpret_cast<T *>(smem + (CELL == 2 ? (int)mi * xbytes1 : 0));
     char *wl = smem + xbytes + wave * p.wbytes;
     float *part = reinterpret_cast<float *>(wl);                  // reuses the weights' space
 
-    const int64_t mi = blockIdx.y;
     const GemvGlobal d = to_global(p.table ? p.table[mi] : mi ? p.second : p.single);
     const GRIM_GLOBAL char *W = d.weights;
-    const GRIM_GLOBAL T *x = (const GRIM_GLOBAL T *)p.x + mi * p.x_stride;
+    const GRIM_GLOBAL T *x = (const GRIM_GLOBAL T *)p.x + (CELL == 2 ? 0 : mi * p.x_stride);
     GRIM_GLOBAL float *y = (GRIM_GLOBAL float *)p.y + mi * p.y_stride;
 
-
     const int nsegs = (p.nbc + p.seg_blocks - 1) / p.seg_blocks;
-    const int64_t t0 = ((int64_t)blockIdx.x * 4 + wave) * p.sps;
-    const int nstrips = p.nbr_total - t0 < p.sps ? (int)(p.nbr_total - t0) : p.sps;   // <= 0: nothing to do
+    // the product alone: a wave walks sps consecutive stored strips; with a cell: the strip of gate `gate` that holds
+    // hidden units blockIdx.x * BR .., wherever the reorder has stored it
+    const int gate = CELL == 2 ? wave % 3 : wave;
+    int64_t t0 = ((int64_t)blockIdx.x * 4 + wave) * p.sps;
+    if constexpr (CELL != 0) {
+        const int32_t *pos = (CELL == 2 && mi) ? p.cell.strip_pos2 : p.cell.strip_pos;
+        t0 = pos[gate * (p.cell.H / p.BR) + blockIdx.x];
+    }
+    const int nstrips = CELL != 0 ? 1 : p.nbr_total - t0 < p.sps ? (int)(p.nbr_total - t0) : p.sps;   // <= 0: nothing to do
     const int nitems = nstrips > 0 ? nstrips * nsegs : 0;
 
     struct Item {
@@ -392,7 +418,7 @@ __global__ void __launch_bounds__(256) bcr_spmv_wave_exact(GemvParams p) {
     // as well (as equal-work strips are), and for launches of one round of workgroups all at the
     // end, where they no longer cut into the stream of weight reads.
     constexpr int kKeep = 4;
-    float yacc = 0.f, ykeep[kKeep];
+    float yacc = 0.f, ysum = 0.f, ykeep[kKeep];
     int rowkeep[kKeep], npend = 0;                                // npend: strips kept, not yet stored
     auto store_kept = [&]() {
 #pragma unroll
@@ -404,27 +430,35 @@ __global__ void __launch_bounds__(256) bcr_spmv_wave_exact(GemvParams p) {
     // x -> LDS, once per workgroup.  Its loads go out first and the first item's right behind
     // them, so that the weights are already on their way while x is parked.
     Item cur, nxt;
+    T *xs0 = reinterpret_cast<T *>(smem);                          // (the whole x area: one vector, or two for the GRU)
+    const int nvecs = CELL == 2 ? 2 : 1;
     if (p.xvec16) {
-        const int nxv = p.K * ESZ / 16;
+        const int nxv1 = p.K * ESZ / 16, nxv = nxv1 * nvecs;
         const GRIM_GLOBAL gu32x4 *xsrc = reinterpret_cast<const GRIM_GLOBAL gu32x4 *>(x);
+        const GRIM_GLOBAL gu32x4 *xsrc2 = reinterpret_cast<const GRIM_GLOBAL gu32x4 *>(x + p.x_stride);
+        auto src_of = [&](int v) { return v < nxv1 ? xsrc + v : xsrc2 + (v - nxv1); };
+        auto dst_of = [&](int v) { return reinterpret_cast<gu32x4 *>(reinterpret_cast<char *>(xs0) + (v < nxv1 ? 0 : xbytes1)) + (v < nxv1 ? v : v - nxv1); };
         gu32x4 xreg[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i)
-            if (i * 256 < nxv) {
-                int v = tid + i * 256;
+            if (i * NTHR < nxv) {
+                int v = tid + i * NTHR;
                 v = v < nxv ? v : nxv - 1;
-                xreg[i] = xsrc[v];
+                xreg[i] = *src_of(v);
             }
         if (nitems) fetch(0, cur);
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const int v = tid + i * 256;
-            if (v < nxv) reinterpret_cast<gu32x4 *>(xs)[v] = xreg[i];
+            const int v = tid + i * NTHR;
+            if (v < nxv) *dst_of(v) = xreg[i];
         }
-        for (int v = tid + 1024; v < nxv; v += 256) reinterpret_cast<gu32x4 *>(xs)[v] = xsrc[v];
+        for (int v = tid + 4 * NTHR; v < nxv; v += NTHR) *dst_of(v) = *src_of(v);
     } else {
         if (nitems) fetch(0, cur);
-        for (int e = tid; e < p.K; e += 256) xs[e] = x[(int64_t)e * p.ldx];
+        for (int e = tid; e < p.K; e += NTHR) xs0[e] = x[(int64_t)e * p.ldx];
+        if constexpr (CELL == 2)
+            for (int e = tid; e < p.K; e += NTHR)
+                reinterpret_cast<T *>(reinterpret_cast<char *>(xs0) + xbytes1)[e] = x[p.x_stride + (int64_t)e * p.ldx];
     }
     __syncthreads();
     if (!nitems) return;
@@ -564,12 +598,60 @@ __global__ void __launch_bounds__(256) bcr_spmv_wave_exact(GemvParams p) {
                     ykeep[k] = yacc;
                     rowkeep[k] = cur.srow;
                 }
+            if constexpr (CELL != 0) ysum = yacc;
             yacc = 0.f;
             ++npend;
         }
         cur = nxt;
     }
-    store_kept();
+    if constexpr (CELL == 0) {
+        store_kept();
+    } else {
+        // The waves' strips are the gate rows of hidden units u0 .. u0 + BR - 1.  Their sums meet in LDS (the x area
+        // is free once every wave has multiplied), then one thread per hidden unit applies the cell.  The gate
+        // pre-activations (without bias) are stored as the product alone would store them.
+        __syncthreads();
+        float *gl = reinterpret_cast<float *>(smem);              // [NWV][32]
+        if (grp == 0 && r_out < p.BR) gl[wave * 32 + r_out] = ysum;
+        __syncthreads();
+        if (tid < p.BR) {
+            const RnnCell &cl = p.cell;
+            const int64_t H = cl.H, j = (int64_t)blockIdx.x * p.BR + tid;
+            GRIM_GLOBAL float *y0 = (GRIM_GLOBAL float *)p.y;
+            if constexpr (CELL == 1) {
+                const float pi = gl[tid], pf = gl[32 + tid], pg = gl[64 + tid], po = gl[96 + tid];
+                y0[j * p.ldy] = pi; y0[(H + j) * p.ldy] = pf; y0[(2 * H + j) * p.ldy] = pg; y0[(3 * H + j) * p.ldy] = po;
+                const float bi = cl.bias ? cl.bias[j] : 0.f, bf = cl.bias ? cl.bias[H + j] : 0.f;
+                const float bg = cl.bias ? cl.bias[2 * H + j] : 0.f, bo = cl.bias ? cl.bias[3 * H + j] : 0.f;
+                const float gi = rnn_sigmoid(pi + bi);
+                const float gf = rnn_sigmoid(pf + bf);
+                const float gg = tanhf(pg + bg);
+                const float go = rnn_sigmoid(po + bo);
+                const float c = gf * cl.c[j * cl.ldc] + gi * gg;
+                const float h = go * tanhf(c);
+                cl.c[j * cl.ldc] = c;
+                if (cl.h32) cl.h32[j * cl.ldh32] = h;
+                if (cl.h) rnn_store_h(cl.h, cl.hdt, j * cl.ldh, h);
+            } else {
+                GRIM_GLOBAL float *y1 = y0 + p.y_stride;
+                float pi[3], ph[3];
+#pragma unroll
+                for (int k = 0; k < 3; ++k) {
+                    const float vi = gl[k * 32 + tid], vh = gl[(3 + k) * 32 + tid];
+                    y0[(k * H + j) * p.ldy] = vi;
+                    y1[(k * H + j) * p.ldy] = vh;
+                    pi[k] = vi + (cl.bias ? cl.bias[k * H + j] : 0.f);
+                    ph[k] = vh + (cl.bias2 ? cl.bias2[k * H + j] : 0.f);
+                }
+                const float r = rnn_sigmoid(pi[0] + ph[0]);
+                const float z = rnn_sigmoid(pi[1] + ph[1]);
+                const float n = tanhf(pi[2] + r * ph[2]);
+                const float h = (1.0f - z) * n + z * cl.c[j * cl.ldc];
+                cl.c[j * cl.ldc] = h;
+                if (cl.h) rnn_store_h(cl.h, cl.hdt, j * cl.ldh, h);
+            }
+        }
+    }
 }
 
 template <int DT, int KR, int KC>
@@ -585,6 +667,34 @@ static grim_status launch_exact_inst(const GemvParams &p, dim3 grid, size_t lds,
     }
     hipLaunchKernelGGL(kern, grid, dim3(256), lds, stream, p);
     return hipGetLastError() == hipSuccess ? GRIM_OK : GRIM_ERR_DEVICE;
+}
+
+template <int DT, int KR, int KC, int CELL>
+static grim_status launch_cell_inst(const GemvParams &p, dim3 grid, size_t lds, hipStream_t stream) {
+    auto kern = bcr_spmv_wave_exact<DT, KR, KC, CELL>;
+    static std::atomic<bool> attr_done{false};
+    if (lds > 64 * 1024 && !attr_done) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess) {
+            (void)hipGetLastError();
+            return GRIM_ERR_DEVICE;
+        }
+        attr_done = true;
+    }
+    hipLaunchKernelGGL(kern, grid, dim3(exact_waves(CELL) * 64), lds, stream, p);
+    return hipGetLastError() == hipSuccess ? GRIM_OK : GRIM_ERR_DEVICE;
+}
+
+// the recurrent-cell variants are compiled for the two-byte element types
+template <int DT, int CELL>
+static grim_status launch_cell(const GemvParams &p, int kr, int kc, dim3 grid, size_t lds, hipStream_t stream) {
+#define GRIM_CELL(R, C)                                                                    \
+    if constexpr ((R) * (C) * 2 % 16 == 0 && (R) * (C) * 2 <= 384)                         \
+        if (kr == (R) && kc == (C)) return launch_cell_inst<DT, R, C, CELL>(p, grid, lds, stream);
+    GRIM_CELL(4, 4) GRIM_CELL(4, 8) GRIM_CELL(4, 12) GRIM_CELL(4, 16)
+    GRIM_CELL(8, 4) GRIM_CELL(8, 8) GRIM_CELL(8, 12) GRIM_CELL(8, 16)
+    GRIM_CELL(16, 4) GRIM_CELL(16, 8) GRIM_CELL(16, 12)
+#undef GRIM_CELL
+    return GRIM_ERR_UNSUPPORTED;
 }
 
 // Compiled (kept rows, kept columns) pairs; a block must be a whole number of 16-byte vectors
@@ -998,6 +1108,61 @@ grim_status launch_spmv(const GemvDesc *table, const GemvDesc &single, const Gem
         case GRIM_BF16: return launch_batch<GRIM_BF16>(p, batch, vec, grid, lds, stream);
     }
     return GRIM_ERR_DTYPE;
+}
+
+bool spmv_cell_applies(int kind, int64_t M, int64_t K, int32_t BR, int32_t BC, int32_t dtype, int32_t ukr, int32_t ukc, int64_t H) {
+    const int gates = kind == 1 ? 4 : 3, esz = 2;
+    if (kind != 1 && kind != 2) return false;
+    if (BR > 32 || BC > 32 || dtype == GRIM_F32 || ukr <= 0 || ukc <= 0) return false;
+    if (H < 1 || H > 0x7fffffff || M != (int64_t)gates * H || H % BR != 0 || K % BC != 0) return false;
+    if ((ukr * ukc * esz) % 16 != 0 || ukr * ukc * esz > 384 || K * esz > 32 * 1024) return false;
+    const int nv = ukr * ukc * esz / 16;
+    int64_t wb = (int64_t)exact_region_vectors(nv) * 16;
+    const int64_t table = ((int64_t)BR * kPartStride * 4 + 15) & ~int64_t(15);
+    if (wb < table) wb = table;
+    const int64_t lds = (kind == 2 ? 2 : 1) * ((K * esz + 15) & ~int64_t(15)) + exact_waves(kind) * wb;
+    return lds <= 160 * 1024;
+}
+
+// One recurrent step in one launch: the gate product(s) with the cell in the epilogue (kind 1: LSTM, one matrix of 4H
+// rows; kind 2: GRU, two matrices of 3H rows with the same K, block size and kept counts).  One right-hand side,
+// fp16 / bf16, every block keeping the same kr x kc, H a multiple of BR.  GRIM_ERR_UNSUPPORTED when the matrices do not
+// qualify: the caller then runs the product(s) and the cell as separate launches.
+grim_status launch_spmv_cell(int kind, const GemvDesc &d1, const GemvDesc *d2, int64_t M, int64_t K, int32_t BR, int32_t BC,
+                             int32_t dtype, int32_t ukr, int32_t ukc, const void *x, int64_t x_stride, int64_t ldx, float *y,
+                             int64_t y_stride, int64_t ldy, const RnnCell &cell, hipStream_t stream) {
+    if ((kind == 2 && !d2) || !spmv_cell_applies(kind, M, K, BR, BC, dtype, ukr, ukc, cell.H)) return GRIM_ERR_UNSUPPORTED;
+    const int esz = 2;
+    const int64_t groups = cell.H / BR;
+    if (groups > 0x7fffffff) return GRIM_ERR_SHAPE;
+    GemvParams p;
+    p.table = nullptr;
+    p.single = d1;
+    p.second = d2 ? *d2 : d1;
+    p.BR = BR; p.BC = BC; p.nbc = (int32_t)(K / BC); p.K = (int32_t)K;
+    p.nbr_total = (int32_t)(M / BR);
+    p.sps = 1;
+    p.batch = 1;
+    p.ukr = ukr; p.ukc = ukc; p.krmax = ukr; p.kcmax = ukc; p.lpb_shift = 2;
+    p.seg_blocks = 64;
+    const int nv = ukr * ukc * esz / 16;
+    int64_t wb = (int64_t)exact_region_vectors(nv) * 16;
+    const int64_t table = ((int64_t)BR * kPartStride * 4 + 15) & ~int64_t(15);
+    if (wb < table) wb = table;
+    p.wbytes = (int32_t)wb;
+    p.x = x; p.y = y; p.x_stride = x_stride; p.y_stride = y_stride; p.ldx = ldx; p.ldy = ldy;
+    p.xvec16 = (ldx == 1 && reinterpret_cast<uintptr_t>(x) % 16 == 0 && (K * esz) % 16 == 0 &&
+                (kind == 1 || (x_stride * esz) % 16 == 0)) ? 1 : 0;
+    p.cell = cell;
+    const int nvecs = kind == 2 ? 2 : 1, nw = exact_waves(kind);
+    const size_t lds = nvecs * (((size_t)K * esz + 15) & ~size_t(15)) + nw * (size_t)wb;
+    if (lds > 160 * 1024) return GRIM_ERR_UNSUPPORTED;
+    const dim3 grid((unsigned)groups);
+    if (kind == 1)
+        return dtype == GRIM_F16 ? launch_cell<GRIM_F16, 1>(p, ukr, ukc, grid, lds, stream)
+                                 : launch_cell<GRIM_BF16, 1>(p, ukr, ukc, grid, lds, stream);
+    return dtype == GRIM_F16 ? launch_cell<GRIM_F16, 2>(p, ukr, ukc, grid, lds, stream)
+                             : launch_cell<GRIM_BF16, 2>(p, ukr, ukc, grid, lds, stream);
 }
 
 }  // namespace grim
