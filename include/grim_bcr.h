@@ -318,6 +318,45 @@ grim_status grim_bcr_gru_step(const grim_bcr_matrix *Ai, const grim_bcr_matrix *
                               float *h32_dev, int64_t ldh32, void *hout_dev, int64_t ldhout, void *hip_stream);
 
 /*
+ * A recurrent layer over a whole sequence in ONE launch (Section 3.1: one matrix-vector product per time step;
+ * Section 6.3 times the recurrent network step by step).  The weights are read once and stay in registers for all T
+ * steps; workgroups (one per BR hidden units, all resident at once) hand the new hidden state to each other through
+ * a small exchange buffer that belongs to the matrix (A, or Ah for the GRU), allocated by the first such call.
+ *   grim_bcr_lstm_sequence   A: the gate matrix [W_ih | W_hh], 4H x (I + H), as for grim_bcr_lstm_step
+ *   grim_bcr_gru_sequence    Ai: 3H x I, Ah: 3H x H, as for grim_bcr_gru_step
+ *   xs_dev     T x I inputs in the matrices' element type, row t at xs_dev + t * ldxs elements (ldxs >= I)
+ *   bias*_dev  as for the step calls, or NULL
+ *   h0_dev     H elements (element type of the matrices): the hidden state the first step's product reads
+ *   c_dev      LSTM: H fp32, cell state, read before the first step and overwritten with the last step's
+ *   h32_dev    GRU: H fp32, hidden state in fp32 (the z * h term reads it), read and overwritten likewise
+ *   hs_dev     T x H outputs h_1 .. h_T in the matrices' element type (ldhs >= H), overwritten; hs32_dev: the same in
+ *              fp32 (ldhs32 >= H), or NULL.  Step t + 1 reads h_t rounded to the element type, as a chain of step
+ *              calls does, and computes the same values as that chain.
+ *   status_dev one int32 on the device, overwritten: 0 = done, 1 = a workgroup gave up waiting for another
+ *              workgroup's state (the GPU was too busy to hold all workgroups at once for longer than the limit); the
+ *              outputs are then undefined.  The caller reads it after synchronising with hip_stream.
+ *   max_polls  limit of unsuccessful reads of an exchange word before a workgroup gives up; 0 = default (2^21,
+ *              seconds).  Every workgroup leaves the kernel either way.
+ * One right-hand side.  Requirements: fp16 / bf16, blocks of at most 32 x 32 all keeping the same (rows, columns)
+ * out of {4, 8, 16} x {4, 8, 12, 16} (not 16 x 16), at most 64 column blocks per matrix, H a multiple of BR,
+ * H <= 8192 and H / BR workgroups <= the GPU's compute units; otherwise GRIM_ERR_UNSUPPORTED (loop over the step
+ * call instead); grim_bcr_rnn_sequence_supported(A, Ah or NULL) tells in advance (1 / 0).
+ * Two sequence calls on the same matrix must not overlap in time (they share the exchange buffer): enqueue them
+ * on one stream.  Only enqueues work on hip_stream (two launches: clearing the exchange words, the sequence).
+ * Errors: NULL, SHAPE (T < 1, rows not 4H / 3H, leading dimension too small), DTYPE, DEVICE, ALLOC, UNSUPPORTED.
+ */
+int32_t grim_bcr_rnn_sequence_supported(const grim_bcr_matrix *A, const grim_bcr_matrix *Ah);
+grim_status grim_bcr_lstm_sequence(const grim_bcr_matrix *A, const void *xs_dev, int64_t ldxs, int32_t T,
+                                   const float *bias_dev, const void *h0_dev, float *c_dev, void *hs_dev, int64_t ldhs,
+                                   float *hs32_dev, int64_t ldhs32, int32_t *status_dev, uint32_t max_polls,
+                                   void *hip_stream);
+grim_status grim_bcr_gru_sequence(const grim_bcr_matrix *Ai, const grim_bcr_matrix *Ah, const void *xs_dev, int64_t ldxs,
+                                  int32_t T, const float *bias_i_dev, const float *bias_h_dev, const void *h0_dev,
+                                  float *h32_dev, void *hs_dev, int64_t ldhs, float *hs32_dev, int64_t ldhs32,
+                                  int32_t *status_dev, uint32_t max_polls, void *hip_stream);
+
+
+/*
  * BCRC export (Section 4.3, "Compact Model Storage"): the paper's six-array, row-level form of the
  * same pruned matrix.  Rows of the whole matrix are reordered so that rows with the same set of
  * kept (global) columns are adjacent -- groups in order of the first original row that shows the

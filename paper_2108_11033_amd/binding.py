@@ -58,7 +58,8 @@ EXPORTS = ["grim_bcr_pack", "grim_bcr_unpack", "grim_bcr_arrays", "grim_bcr_spmm
            "grim_bcr_spmv", "grim_bcr_group_create", "grim_bcr_spmv_batched", "grim_bcr_group_free",
            "grim_bcr_free", "grim_status_str", "grim_bcr_spmm_kernel_name",
            "grim_bcr_export_bcrc", "grim_bcrc_arrays", "grim_bcrc_free", "grim_lstm_cell", "grim_bcr_lstm_step", "grim_gru_cell", "grim_bcr_gru_step",
-           "grim_bcr_conv2d", "grim_bcr_conv2d_act", "grim_bcr_unpack_layout", "grim_bcr_rnn_step_launches"]
+           "grim_bcr_conv2d", "grim_bcr_conv2d_act", "grim_bcr_unpack_layout", "grim_bcr_rnn_step_launches",
+           "grim_bcr_rnn_sequence_supported", "grim_bcr_lstm_sequence", "grim_bcr_gru_sequence"]
 
 
 def lib_path() -> str:
@@ -107,6 +108,9 @@ def load_library():
     lib.grim_bcr_gru_step.argtypes = [p, p, p, i64, p, i64, i32, p, i64, p, i64, p, p, p, i64, p, i64, p]
     lib.grim_bcr_spmm_kernel_name.argtypes = [p, p, i64, i64, i32, i32, i32]
     lib.grim_bcr_rnn_step_launches.argtypes = [p, p, i32]
+    lib.grim_bcr_rnn_sequence_supported.argtypes = [p, p]
+    lib.grim_bcr_lstm_sequence.argtypes = [p, p, i64, i32, p, p, p, p, i64, p, i64, p, ctypes.c_uint32, p]
+    lib.grim_bcr_gru_sequence.argtypes = [p, p, p, i64, i32, p, p, p, p, p, i64, p, i64, p, ctypes.c_uint32, p]
     for name in EXPORTS:
         getattr(lib, name).restype = i32
     lib.grim_status_str.restype = ctypes.c_char_p
@@ -300,6 +304,27 @@ def lstm_step(A: BcrMatrix, xh, batch: int, ldx: int, gates, ldg: int, bias, c, 
     """grim_bcr_lstm_step: gate product of [W_ih | W_hh] with [x; h], then the cell."""
     _check(A._lib.grim_bcr_lstm_step(A.handle, _addr(xh), batch, ldx, _addr(gates), ldg, _addr(bias), _addr(c), ldc,
                                      _addr(h), ldh, _addr(h32), ldh32, _stream(stream)), "grim_bcr_lstm_step")
+
+
+def rnn_sequence_supported(A: BcrMatrix, Ah: Optional[BcrMatrix] = None) -> bool:
+    """grim_bcr_rnn_sequence_supported: can the whole-sequence kernel run this LSTM (Ah None) / GRU layer?"""
+    return bool(A._lib.grim_bcr_rnn_sequence_supported(A.handle, Ah.handle if Ah is not None else None))
+
+
+def lstm_sequence(A: BcrMatrix, xs, ldxs: int, T: int, bias, h0, c, hs, ldhs: int, hs32, ldhs32: int, status,
+                  max_polls: int = 0, stream=None):
+    """grim_bcr_lstm_sequence: T LSTM steps in one launch; `status` is a device int32 (0 done, 1 gave up)."""
+    _check(A._lib.grim_bcr_lstm_sequence(A.handle, _addr(xs), ldxs, T, _addr(bias), _addr(h0), _addr(c), _addr(hs), ldhs,
+                                         _addr(hs32), ldhs32, _addr(status), max_polls, _stream(stream)),
+           "grim_bcr_lstm_sequence")
+
+
+def gru_sequence(Ai: BcrMatrix, Ah: BcrMatrix, xs, ldxs: int, T: int, bias_i, bias_h, h0, h32, hs, ldhs: int, hs32,
+                 ldhs32: int, status, max_polls: int = 0, stream=None):
+    """grim_bcr_gru_sequence: T GRU steps in one launch; `status` is a device int32 (0 done, 1 gave up)."""
+    _check(Ai._lib.grim_bcr_gru_sequence(Ai.handle, Ah.handle, _addr(xs), ldxs, T, _addr(bias_i), _addr(bias_h), _addr(h0),
+                                         _addr(h32), _addr(hs), ldhs, _addr(hs32), ldhs32, _addr(status), max_polls,
+                                         _stream(stream)), "grim_bcr_gru_sequence")
 
 
 def gru_cell(gi, ldgi: int, gh, ldgh: int, bias_i, bias_h, h32, ldh32: int, h, dtype, ldh: int, H: int, batch: int,

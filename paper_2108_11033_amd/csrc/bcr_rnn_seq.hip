@@ -1,0 +1,398 @@
+// A recurrent layer over a whole sequence in ONE launch (Section 3.1: an RNN layer is one matrix-vector product per
+// time step; Section 6.3 times the GRU step by step, where every step pays a kernel launch and re-reads the weights).
+//
+// A workgroup owns BR hidden units for the whole sequence.  Its waves take the strips that hold these units' gate
+// rows (LSTM: 4 strips of [W_ih | W_hh]; GRU: 3 strips of W_i and 3 of W_h), and every lane keeps ONE compact block of
+// its strip in registers from the first step to the last: the weights are read from memory once per sequence, not
+// once per step.  Per step a workgroup
+//   1. parks x_t and h_{t-1} in LDS,
+//   2. multiplies (a lane: its block times the block's kept columns of the vector; row sums through a
+//      [strip row][block] table in a fixed order, exactly as the one-step kernel does),
+//   3. applies the cell to its BR units and publishes their new h.
+// Workgroups exchange h through a small buffer of 8-byte words (fp32 value, step tag), two slots used in turn:
+// a producer writes a word with one atomic store, consumers re-read a word until its tag is the step they need.
+// Value and tag travel together, so no fence and no separate counter is needed.  Slot t & 1 can be overwritten with
+// h_{t+2} only by a workgroup that has read all of h_{t+1}, which exists only when every workgroup has finished
+// reading h_t: two slots are enough.  Every wait is bounded: after `max_polls` unsuccessful reads a workgroup gives
+// up, marks its own words as poisoned (which ends every other workgroup's wait at once) and sets *status; all
+// workgroups then leave the kernel normally.
+#include <hip/hip_runtime.h>
+
+#include <atomic>
+#include <mutex>
+
+#include "bcr_matrix.hpp"
+#include "spmv_common.hpp"
+
+namespace grim {
+
+constexpr unsigned int kSeqPoison = 0xffffffffu;   // tag of a word whose producer has given up
+constexpr unsigned int kSeqDefaultPolls = 1u << 21;
+
+struct SeqParams {
+    GemvDesc d1, d2;               // LSTM: the gate matrix; GRU: W_i and W_h
+    const int32_t *pos1, *pos2;    // stored position of every original strip
+    int32_t BR, BC;
+    int32_t nbc1, nbc2;            // column blocks per strip (<= 64 each)
+    int32_t K1, K2;                // LSTM: K1 = I + H; GRU: K1 = I, K2 = H
+    int32_t I, H, T;
+    int32_t xvec16;                // rows of xs can be copied with 16-byte loads
+    const void *xs;                // T x I inputs
+    int64_t ldxs;
+    const void *h0;                // H elements: h before the first step
+    const float *bias, *bias2;     // LSTM: 4H; GRU: 3H input side, 3H hidden side; null = none
+    float *state;                  // LSTM: c, GRU: h in fp32; H values, read at the start, written at the end
+    void *hs;                      // T x H outputs in the matrices' element type
+    int64_t ldhs;
+    float *hs32;                   // optional fp32 copy of the outputs
+    int64_t ldhs32;
+    unsigned long long *exch;      // 2 x H words (fp32 value, tag); all tags zero at launch
+    int32_t *status;               // set to 1 by a workgroup that gives up
+    uint32_t max_polls;
+};
+
+template <int DT> __device__ __forceinline__ typename GElem<DT>::type seq_round(float v);
+template <> __device__ __forceinline__ _Float16 seq_round<GRIM_F16>(float v) { return (_Float16)v; }
+template <> __device__ __forceinline__ unsigned short seq_round<GRIM_BF16>(float v) { return rnn_f32_to_bf16(v); }
+
+template <int DT, int KR, int KC, int CELL>
+__global__ void __launch_bounds__(exact_waves(CELL) * 64) bcr_rnn_seq(SeqParams p) {
+    using T = typename GElem<DT>::type;
+    static_assert(sizeof(T) == 2, "two-byte element types");
+    constexpr int NWV = exact_waves(CELL), NTHR = NWV * 64;
+    constexpr int NV = KR * KC * 2 / 16;
+    static_assert(KR * KC * 2 % 16 == 0 && KC % 2 == 0 && KC <= 32 && KR <= 32, "block shape");
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int mi = CELL == 2 ? wave / 3 : 0;
+    const int gate = CELL == 2 ? wave % 3 : wave;
+    const int H = p.H;
+
+    // LDS: input vector(s) | a [strip row][block] table per wave | the waves' row sums
+    const int xbytes1 = (p.K1 * 2 + 15) & ~15;
+    const int xbytes = CELL == 2 ? xbytes1 + ((p.K2 * 2 + 15) & ~15) : xbytes1;
+    const int tbytes = (p.BR * kPartStride * 4 + 15) & ~15;
+    T *xin = reinterpret_cast<T *>(smem);                                     // x_t; LSTM: h follows at element I
+    T *hin = CELL == 2 ? reinterpret_cast<T *>(smem + xbytes1) : xin + p.I;
+    float *part = reinterpret_cast<float *>(smem + xbytes + wave * tbytes);
+    float *gl = reinterpret_cast<float *>(smem + xbytes + NWV * tbytes);      // [NWV][32]
+    __shared__ int flag_word;
+    volatile int *flag = &flag_word;
+
+    // this lane's block: weights into registers for the whole sequence
+    const GemvGlobal d = to_global(mi ? p.d2 : p.d1);
+    const int nbc = mi ? p.nbc2 : p.nbc1;
+    const int32_t *pos = mi ? p.pos2 : p.pos1;
+    const int64_t t0 = pos[gate * (H / p.BR) + (int)blockIdx.x];
+    const int blk_l = lane < nbc ? lane : nbc - 1;                            // idle lanes re-read the last block
+    const int64_t blk = t0 * nbc + blk_l;
+    gu32x4 w[NV];
+#pragma unroll
+    for (int j = 0; j < NV; ++j)
+        w[j] = *reinterpret_cast<const GRIM_GLOBAL gu32x4 *>(d.weights + (size_t)blk * (NV * 16) + j * 16);
+    unsigned int rm = 0, cm = KC == 32 ? 0xffffffffu : (1u << (KC & 31)) - 1u;   // idle lanes: any KC columns, no rows
+    if (lane < nbc) {
+        const gu32x2 mm = *reinterpret_cast<const GRIM_GLOBAL gu32x2 *>(d.masks + 2 * blk);
+        rm = mm.x;
+        cm = mm.y;
+    }
+    const T *xb = ((CELL == 2 && mi) ? hin : xin) + blk_l * p.BC;
+
+    // the cell's threads: one per hidden unit, state and biases in registers
+    const int64_t ju = (int64_t)blockIdx.x * p.BR + tid;
+    float st = 0.f, b[6] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    if (tid < p.BR) {
+        st = p.state[ju];
+#pragma unroll
+        for (int k = 0; k < (CELL == 1 ? 4 : 3); ++k) {
+            if (p.bias) b[k] = p.bias[k * (int64_t)H + ju];
+            if (CELL == 2 && p.bias2) b[3 + k] = p.bias2[k * (int64_t)H + ju];
+        }
+    }
+    if (tid == 0) *flag = 0;
+
+    const int ngrp = p.BR <= 16 ? 4 : 2;
+    const int r_out = p.BR <= 16 ? lane & 15 : lane & 31;
+    const int grp = p.BR <= 16 ? lane >> 4 : lane >> 5;
+    (void)ngrp;
+    const GRIM_GLOBAL T *h0 = (const GRIM_GLOBAL T *)p.h0;
+    const GRIM_GLOBAL T *xs0 = (const GRIM_GLOBAL T *)p.xs;
+    // 16-byte path: a row of xs is at most 256 vectors (K1 <= 64 blocks of 32), one per thread, fetched a step ahead
+    const int nxv = p.I / 8;
+    gu32x4 xr = gu32x4{0u, 0u, 0u, 0u};
+    if (p.xvec16) xr = reinterpret_cast<const GRIM_GLOBAL gu32x4 *>(xs0)[tid < nxv ? tid : 0];
+    // positions of the block's kept columns, and the [strip row][block] table zeroed once: a lane only ever
+    // writes the entries of its block's kept rows, all others stay zero
+    unsigned short coff[KC];
+    {
+        unsigned int m = cm;
+#pragma unroll
+        for (int j = 0; j < KC; ++j) {
+            coff[j] = (unsigned short)__builtin_ctz(m);                 // KC bits are set
+            m &= m - 1;
+        }
+    }
+    for (int z = lane; z < (p.BR * kPartStride + 3) / 4; z += 64)
+        reinterpret_cast<gu32x4 *>(part)[z] = gu32x4{0u, 0u, 0u, 0u};
+    bool gave_up = false;
+    __syncthreads();
+
+    for (int t = 0; t < p.T; ++t) {
+        // ---- 1. x_t and h_t (the state BEFORE this step: h0, or what step t - 1 published under tag t)
+        if (p.xvec16) {
+            // x_t was asked for a step ago; x_{t+1} is asked for now and travels while this step waits for h
+            if (tid < nxv) reinterpret_cast<gu32x4 *>(xin)[tid] = xr;
+            const int tn = t + 1 < p.T ? t + 1 : t;
+            xr = reinterpret_cast<const GRIM_GLOBAL gu32x4 *>(xs0 + (int64_t)tn * p.ldxs)[tid < nxv ? tid : 0];
+        } else {
+            const GRIM_GLOBAL T *xg = xs0 + (int64_t)t * p.ldxs;
+            for (int e = tid; e < p.I; e += NTHR) xin[e] = xg[e];
+        }
+        if (t == 0) {
+            for (int e = tid; e < H; e += NTHR) hin[e] = h0[e];
+        } else {
+            const unsigned long long *ex = p.exch + (size_t)(t & 1) * H;
+            for (int base = tid; base < H; base += 4 * NTHR) {
+                unsigned long long v[4] = {0ull, 0ull, 0ull, 0ull};
+                unsigned int polls = 0;
+                bool ok;
+                for (;;) {
+                    ok = true;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const int e = base + i * NTHR;
+                        if (e < H) {
+                            v[i] = __hip_atomic_load(ex + e, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                            const unsigned int tag = (unsigned int)(v[i] >> 32);
+                            if (tag != (unsigned int)t) ok = false;
+                            if (tag == kSeqPoison) polls = p.max_polls;
+                        }
+                    }
+                    if (ok || polls >= p.max_polls) break;
+                    ++polls;
+                    __builtin_amdgcn_s_sleep(1);
+                }
+                if (!ok) {
+                    *flag = 1;
+                    break;
+                }
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int e = base + i * NTHR;
+                    if (e < H) hin[e] = seq_round<DT>(__builtin_bit_cast(float, (unsigned int)v[i]));
+                }
+            }
+        }
+        __syncthreads();
+        if (*flag) {                                                  // the same value for every thread
+            gave_up = true;
+            break;
+        }
+
+        // ---- 2. the block's KC activations, the products, the strip's row sums
+        T xe[KC];
+#pragma unroll
+        for (int j = 0; j < KC; ++j) xe[j] = xb[coff[j]];
+        unsigned int xp[KC / 2];
+#pragma unroll
+        for (int h = 0; h < KC / 2; ++h) {
+            unsigned short lo, hi;
+            __builtin_memcpy(&lo, &xe[2 * h], 2);
+            __builtin_memcpy(&hi, &xe[2 * h + 1], 2);
+            xp[h] = (unsigned int)lo | ((unsigned int)hi << 16);
+        }
+        float acc[KR];
+#pragma unroll
+        for (int i = 0; i < KR; ++i) {
+            float a = 0.f;
+#pragma unroll
+            for (int h = 0; h < KC / 2; ++h) {
+                const int q = i * (KC / 2) + h;
+                const unsigned int wd = w[q >> 2][q & 3];
+                if constexpr (DT == GRIM_F16)
+                    a = __builtin_amdgcn_fdot2(__builtin_bit_cast(gh2, wd), __builtin_bit_cast(gh2, xp[h]), a, false);
+                else
+                    a = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(gb2, wd), __builtin_bit_cast(gb2, xp[h]), a, false);
+            }
+            acc[i] = a;
+        }
+        if (rm) {
+            unsigned int m = rm;
+#pragma unroll
+            for (int i = 0; i < KR; ++i) {
+                const int r = __builtin_ctz(m);                       // KR bits are set
+                m &= m - 1;
+                part[r * kPartStride + lane] = acc[i];
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
+        float rs;
+        if (p.BR <= 16) {
+            float s = 0.f;
+            if (r_out < p.BR) {
+                const float2 *src = reinterpret_cast<const float2 *>(part + r_out * kPartStride + grp * 16);
+#pragma unroll
+                for (int q = 0; q < 8; ++q) {
+                    const float2 v = src[q];
+                    s += v.x;
+                    s += v.y;
+                }
+            }
+            const float s2 = s + __shfl_xor(s, 16);
+            rs = s2 + __shfl_xor(s2, 32);
+        } else {
+            float s = 0.f;
+            if (r_out < p.BR) {
+                const float2 *src = reinterpret_cast<const float2 *>(part + r_out * kPartStride + grp * 32);
+#pragma unroll
+                for (int q = 0; q < 16; ++q) {
+                    const float2 v = src[q];
+                    s += v.x;
+                    s += v.y;
+                }
+            }
+            rs = s + __shfl_xor(s, 32);
+        }
+        if (grp == 0 && r_out < p.BR) gl[wave * 32 + r_out] = rs;
+        __syncthreads();
+
+        // ---- 3. the cell on this workgroup's BR units; publish h_{t+1} under tag t + 1
+        if (tid < p.BR) {
+            float h;
+            if constexpr (CELL == 1) {
+                h = lstm_cell_apply(gl[tid] + b[0], gl[32 + tid] + b[1], gl[64 + tid] + b[2], gl[96 + tid] + b[3], st);
+            } else {
+                h = gru_cell_apply(gl[tid] + b[0], gl[32 + tid] + b[1], gl[64 + tid] + b[2], gl[96 + tid] + b[3],
+                                   gl[128 + tid] + b[4], gl[160 + tid] + b[5], st);
+                st = h;
+            }
+            const unsigned long long word = (unsigned long long)__builtin_bit_cast(unsigned int, h) |
+                                            ((unsigned long long)(unsigned int)(t + 1) << 32);
+            __hip_atomic_store(p.exch + (size_t)((t + 1) & 1) * H + ju, word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            static_cast<T *>(p.hs)[(int64_t)t * p.ldhs + ju] = seq_round<DT>(h);
+            if (p.hs32) p.hs32[(int64_t)t * p.ldhs32 + ju] = h;
+        }
+    }
+
+    if (gave_up) {
+        if (tid < p.BR) {
+            const unsigned long long word = (unsigned long long)kSeqPoison << 32;
+            __hip_atomic_store(p.exch + ju, word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(p.exch + (size_t)H + ju, word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        if (tid == 0) __hip_atomic_store(p.status, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    }
+    if (tid < p.BR) p.state[ju] = st;
+}
+
+// zeroes the exchange words' tags and the status word (a kernel, not a memset: callers may capture the launch)
+__global__ void __launch_bounds__(256) rnn_seq_clear(unsigned long long *exch, int64_t words, int32_t *status) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < words) exch[i] = 0ull;
+    if (i == 0) *status = 0;
+}
+
+template <int DT, int KR, int KC, int CELL>
+static grim_status launch_seq_inst(const SeqParams &p, dim3 grid, size_t lds, hipStream_t stream) {
+    auto kern = bcr_rnn_seq<DT, KR, KC, CELL>;
+    static std::atomic<bool> attr_done{false};
+    if (lds > 64 * 1024 && !attr_done) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess) {
+            (void)hipGetLastError();
+            return GRIM_ERR_DEVICE;
+        }
+        attr_done = true;
+    }
+    hipLaunchKernelGGL(kern, grid, dim3(exact_waves(CELL) * 64), lds, stream, p);
+    return hipGetLastError() == hipSuccess ? GRIM_OK : GRIM_ERR_DEVICE;
+}
+
+template <int DT, int CELL>
+static grim_status launch_seq(const SeqParams &p, int kr, int kc, dim3 grid, size_t lds, hipStream_t stream) {
+#define GRIM_SEQ(R, C) \
+    if (kr == (R) && kc == (C)) return launch_seq_inst<DT, R, C, CELL>(p, grid, lds, stream);
+    GRIM_SEQ(4, 4) GRIM_SEQ(4, 8) GRIM_SEQ(4, 12) GRIM_SEQ(4, 16)
+    GRIM_SEQ(8, 4) GRIM_SEQ(8, 8) GRIM_SEQ(8, 12) GRIM_SEQ(8, 16)
+    GRIM_SEQ(16, 4) GRIM_SEQ(16, 8) GRIM_SEQ(16, 12)
+#undef GRIM_SEQ
+    return GRIM_ERR_UNSUPPORTED;
+}
+
+static bool seq_pair_compiled(int kr, int kc) {
+    return (kr == 4 || kr == 8 || kr == 16) && (kc == 4 || kc == 8 || kc == 12 || kc == 16) && !(kr == 16 && kc == 16);
+}
+
+static size_t seq_lds_bytes(int kind, int64_t K1, int64_t K2, int BR) {
+    const size_t x = ((size_t)K1 * 2 + 15) & ~size_t(15), h = kind == 2 ? (((size_t)K2 * 2 + 15) & ~size_t(15)) : 0;
+    const size_t table = ((size_t)BR * kPartStride * 4 + 15) & ~size_t(15);
+    return x + h + exact_waves(kind) * (table + 32 * 4);
+}
+
+static int compute_units() {
+    static std::atomic<int> cached{0};
+    int n = cached.load();
+    if (n > 0) return n;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1) {
+        (void)hipGetLastError();
+        return 0;
+    }
+    cached = n;
+    return n;
+}
+
+// kind 1: LSTM (K1 = I + H), kind 2: GRU (K1 = I, K2 = H).  The matrices qualify when they hold two-byte elements in
+// blocks of at most 32 x 32 that all keep one compiled (rows, columns) pair, a strip has at most 64 column blocks
+// (a lane keeps one block), H is a multiple of BR and one workgroup per BR hidden units fits the GPU at once.
+bool rnn_seq_applies(int kind, int32_t BR, int32_t BC, int32_t dtype, int32_t ukr, int32_t ukc, int64_t K1, int64_t K2,
+                     int64_t I, int64_t H) {
+    if (kind != 1 && kind != 2) return false;
+    if ((dtype != GRIM_F16 && dtype != GRIM_BF16) || BR < 1 || BR > 32 || BC < 1 || BC > 32) return false;
+    if (!seq_pair_compiled(ukr, ukc) || ukr > BR || ukc > BC) return false;
+    if (H < 1 || I < 1 || H % BR != 0 || H > kSeqMaxH) return false;
+    if (kind == 1 ? K1 != I + H : (K1 != I || K2 != H)) return false;
+    if (K1 % BC != 0 || K1 / BC > 64 || (kind == 2 && (K2 % BC != 0 || K2 / BC > 64))) return false;
+    if (seq_lds_bytes(kind, K1, K2, BR) > 160 * 1024) return false;
+    const int cus = compute_units();
+    return cus > 0 && H / BR <= cus;
+}
+
+grim_status launch_rnn_seq(int kind, const GemvDesc &d1, const GemvDesc *d2, const int32_t *pos1, const int32_t *pos2,
+                           int32_t BR, int32_t BC, int32_t dtype, int32_t ukr, int32_t ukc, int64_t K1, int64_t K2, int64_t I,
+                           int64_t H, int32_t T, const void *xs, int64_t ldxs, const void *h0, const float *bias,
+                           const float *bias2, float *state, void *hs, int64_t ldhs, float *hs32, int64_t ldhs32,
+                           void *exch, int32_t *status, uint32_t max_polls, hipStream_t stream) {
+    if ((kind == 2 && (!d2 || !pos2)) || !rnn_seq_applies(kind, BR, BC, dtype, ukr, ukc, K1, K2, I, H)) return GRIM_ERR_UNSUPPORTED;
+    if (T < 1 || ldxs < I || ldhs < H || (hs32 && ldhs32 < H)) return GRIM_ERR_SHAPE;
+    SeqParams p;
+    p.d1 = d1;
+    p.d2 = d2 ? *d2 : d1;
+    p.pos1 = pos1;
+    p.pos2 = pos2 ? pos2 : pos1;
+    p.BR = BR; p.BC = BC;
+    p.nbc1 = (int32_t)(K1 / BC);
+    p.nbc2 = kind == 2 ? (int32_t)(K2 / BC) : p.nbc1;
+    p.K1 = (int32_t)K1; p.K2 = (int32_t)K2;
+    p.I = (int32_t)I; p.H = (int32_t)H; p.T = T;
+    p.xvec16 = (I % 8 == 0 && I / 8 <= exact_waves(kind) * 64 && ldxs % 8 == 0 && reinterpret_cast<uintptr_t>(xs) % 16 == 0) ? 1 : 0;
+    p.xs = xs; p.ldxs = ldxs; p.h0 = h0;
+    p.bias = bias; p.bias2 = bias2;
+    p.state = state;
+    p.hs = hs; p.ldhs = ldhs; p.hs32 = hs32; p.ldhs32 = ldhs32;
+    p.exch = static_cast<unsigned long long *>(exch);
+    p.status = status;
+    p.max_polls = max_polls ? max_polls : kSeqDefaultPolls;
+    const int64_t words = 2 * H;
+    hipLaunchKernelGGL(rnn_seq_clear, dim3((unsigned)((words + 255) / 256)), dim3(256), 0, stream, p.exch, words, status);
+    if (hipGetLastError() != hipSuccess) return GRIM_ERR_DEVICE;
+    const dim3 grid((unsigned)(H / BR));
+    const size_t lds = seq_lds_bytes(kind, K1, K2, BR);
+    if (kind == 1)
+        return dtype == GRIM_F16 ? launch_seq<GRIM_F16, 1>(p, ukr, ukc, grid, lds, stream)
+                                 : launch_seq<GRIM_BF16, 1>(p, ukr, ukc, grid, lds, stream);
+    return dtype == GRIM_F16 ? launch_seq<GRIM_F16, 2>(p, ukr, ukc, grid, lds, stream)
+                             : launch_seq<GRIM_BF16, 2>(p, ukr, ukc, grid, lds, stream);
+}
+
+}  // namespace grim

@@ -24,87 +24,9 @@
 #include <cstdlib>
 
 #include "bcr_matrix.hpp"
+#include "spmv_common.hpp"
 
 namespace grim {
-
-struct GemvParams {
-    const GemvDesc *table;   // device table (batched launch) or nullptr
-    GemvDesc single;         // no table: matrix 0 ...
-    GemvDesc second;         // ... and matrix 1 of a two-matrix launch
-    int32_t BR, BC, nbc, K;
-    int32_t nbr_total;       // row strips of the matrix
-    int32_t ukr, ukc;        // uniform kept counts or -1
-    int32_t lpb_shift;       // log2(lanes per block), 2..5
-    int32_t seg_blocks;      // column blocks per LDS segment (<= kSegMax)
-    int32_t wbytes;          // LDS bytes reserved for a segment's weights
-    int32_t krmax, kcmax;    // most rows / columns any block keeps
-    const void *x;
-    float *y;
-    int64_t x_stride, y_stride, ldx, ldy;
-    int32_t xvec16;          // x is contiguous and 16-byte aligned: copy with 16-byte loads
-    int32_t sps;             // wave kernel: consecutive strips per wave
-    int32_t batch;           // right-hand sides (kernels that take it at run time)
-    RnnCell cell;            // recurrent cell in the epilogue (wave-per-strip kernel, one right-hand side)
-};
-
-
-template <int DT> struct GElem;
-template <> struct GElem<GRIM_F32> { using type = float; };
-template <> struct GElem<GRIM_F16> { using type = _Float16; };
-template <> struct GElem<GRIM_BF16> { using type = unsigned short; };
-
-template <int DT> __device__ __forceinline__ float g2f(typename GElem<DT>::type v);
-template <> __device__ __forceinline__ float g2f<GRIM_F32>(float v) { return v; }
-template <> __device__ __forceinline__ float g2f<GRIM_F16>(_Float16 v) { return (float)v; }
-template <> __device__ __forceinline__ float g2f<GRIM_BF16>(unsigned short v) {
-    return __builtin_bit_cast(float, (unsigned int)v << 16);
-}
-
-constexpr int kSegMax = 64;          // column blocks per segment at most
-constexpr int kWLoads = 8;           // 16-byte weight loads per thread per segment (256 threads: 32 KB)
-constexpr int kGemvWBytes = kWLoads * 256 * 16;
-
-typedef unsigned int gu32x4 __attribute__((ext_vector_type(4)));
-typedef unsigned int gu32x2 __attribute__((ext_vector_type(2)));
-
-// Pointers read out of a descriptor in memory carry no address space, and loads through them
-// would be generic ("flat") loads, which also tick the counter that LDS traffic is waited on.
-// Everything the descriptors point to is device global memory, so the kernels say so.
-#define GRIM_GLOBAL __attribute__((address_space(1)))
-struct GemvGlobal {
-    const GRIM_GLOBAL char *weights;
-    const GRIM_GLOBAL unsigned int *masks;
-    const GRIM_GLOBAL unsigned int *woff;
-    const GRIM_GLOBAL int *strip_order;
-};
-__device__ __forceinline__ GemvGlobal to_global(const GemvDesc &d) {
-    GemvGlobal g;
-    g.weights = (const GRIM_GLOBAL char *)d.weights;
-    g.masks = (const GRIM_GLOBAL unsigned int *)d.masks;
-    g.woff = (const GRIM_GLOBAL unsigned int *)d.woff;
-    g.strip_order = (const GRIM_GLOBAL int *)d.strip_order;
-    return g;
-}
-
-// position of the j-th (0-based) set bit of m; j < popcount(m)
-__device__ __forceinline__ int nth_set_bit(unsigned int m, int j) {
-    int pos = 0;
-    int c = __builtin_popcount(m & 0xffffu);
-    if (j >= c) { j -= c; m >>= 16; pos = 16; }
-    c = __builtin_popcount(m & 0xffu);
-    if (j >= c) { j -= c; m >>= 8; pos += 8; }
-    c = __builtin_popcount(m & 0xfu);
-    if (j >= c) { j -= c; m >>= 4; pos += 4; }
-    c = __builtin_popcount(m & 0x3u);
-    if (j >= c) { j -= c; m >>= 2; pos += 2; }
-    if (j >= (int)(m & 1u)) pos += 1;
-    return pos;
-}
-
-__host__ __device__ inline int gemv_xg_stride(int kcmax, int B) { return ((kcmax + 7) & ~7) * B; }
-
-typedef _Float16 gh2 __attribute__((ext_vector_type(2)));
-typedef __bf16 gb2 __attribute__((ext_vector_type(2)));
 
 // threads of a workgroup of bcr_spmv: from 2 right-hand sides on, twice as many lanes share the strip's blocks and
 // outputs (the phases are chains of dependent LDS round trips, so more waves per strip shorten them)
@@ -293,8 +215,6 @@ __global__ void __launch_bounds__(gemv_threads(B), (B == 1 ? 6 : 1)) bcr_spmv(Ge
     }
 }
 
-constexpr int kPartStride = 66;                    // floats per strip row of the partial table (wave-per-strip kernels)
-
 // ------------------------------------------------------------------------------------------
 // One right-hand side, every block keeping exactly KR rows and KC columns (a layer pruned at one
 // rate): the wave-per-strip scheme with every size known at compile time.
@@ -306,37 +226,6 @@ constexpr int kPartStride = 66;                    // floats per strip row of th
 //   - each lane scatters its rows' sums to a [strip row][block] table in LDS (zero where a block
 //     does not keep the row); lanes (strip row, group) then add each row's 64 entries in a fixed order.
 // ------------------------------------------------------------------------------------------
-// Lanes read their blocks with 16-byte loads at a common offset from bases NV vectors apart;
-// 16 such vectors span the LDS banks.  When NV shares a factor g with 16 the bases of 16
-// neighbouring lanes fall on only 16/g distinct bank groups, so one vector of padding goes
-// after every 16/g blocks, which shifts each run of 16/g lanes onto its own group.
-__host__ __device__ constexpr int exact_pad_period(int nv) {
-    int g = 1;
-    while (g < 16 && nv % (g * 2) == 0) g *= 2;
-    return g == 1 ? 0 : 16 / g;
-}
-__host__ __device__ constexpr int exact_region_vectors(int nv) {
-    return 64 * nv + (exact_pad_period(nv) ? 64 / exact_pad_period(nv) : 0);
-}
-
-
-__device__ __forceinline__ float rnn_sigmoid(float v) { return 1.0f / (1.0f + expf(-v)); }
-__device__ __forceinline__ unsigned short rnn_f32_to_bf16(float f) {
-    unsigned int u = __builtin_bit_cast(unsigned int, f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (unsigned short)((u >> 16) | 0x40u);   // NaN stays NaN
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return (unsigned short)(u >> 16);
-}
-__device__ __forceinline__ void rnn_store_h(void *h, int hdt, int64_t at, float v) {
-    if (hdt == GRIM_F32) static_cast<float *>(h)[at] = v;
-    else if (hdt == GRIM_F16) static_cast<_Float16 *>(h)[at] = (_Float16)v;
-    else static_cast<unsigned short *>(h)[at] = rnn_f32_to_bf16(v);
-}
-
-// CELL: 0 = the product alone; 1 = LSTM step, 2 = GRU step (see RnnCell): the workgroup's waves take the strips of
-// one group of BR hidden units, and the cell is applied to their sums before anything is stored.
-constexpr int exact_waves(int cell) { return cell == 2 ? 6 : 4; }
-
 template <int DT, int KR, int KC, int CELL = 0>
 __global__ void __launch_bounds__(exact_waves(CELL) * 64) bcr_spmv_wave_exact(GemvParams p) {
     using T = typename GElem<DT>::type;
@@ -623,12 +512,8 @@ __global__ void __launch_bounds__(exact_waves(CELL) * 64) bcr_spmv_wave_exact(Ge
                 y0[j * p.ldy] = pi; y0[(H + j) * p.ldy] = pf; y0[(2 * H + j) * p.ldy] = pg; y0[(3 * H + j) * p.ldy] = po;
                 const float bi = cl.bias ? cl.bias[j] : 0.f, bf = cl.bias ? cl.bias[H + j] : 0.f;
                 const float bg = cl.bias ? cl.bias[2 * H + j] : 0.f, bo = cl.bias ? cl.bias[3 * H + j] : 0.f;
-                const float gi = rnn_sigmoid(pi + bi);
-                const float gf = rnn_sigmoid(pf + bf);
-                const float gg = tanhf(pg + bg);
-                const float go = rnn_sigmoid(po + bo);
-                const float c = gf * cl.c[j * cl.ldc] + gi * gg;
-                const float h = go * tanhf(c);
+                float c = cl.c[j * cl.ldc];
+                const float h = lstm_cell_apply(pi + bi, pf + bf, pg + bg, po + bo, c);
                 cl.c[j * cl.ldc] = c;
                 if (cl.h32) cl.h32[j * cl.ldh32] = h;
                 if (cl.h) rnn_store_h(cl.h, cl.hdt, j * cl.ldh, h);
@@ -643,10 +528,7 @@ __global__ void __launch_bounds__(exact_waves(CELL) * 64) bcr_spmv_wave_exact(Ge
                     pi[k] = vi + (cl.bias ? cl.bias[k * H + j] : 0.f);
                     ph[k] = vh + (cl.bias2 ? cl.bias2[k * H + j] : 0.f);
                 }
-                const float r = rnn_sigmoid(pi[0] + ph[0]);
-                const float z = rnn_sigmoid(pi[1] + ph[1]);
-                const float n = tanhf(pi[2] + r * ph[2]);
-                const float h = (1.0f - z) * n + z * cl.c[j * cl.ldc];
+                const float h = gru_cell_apply(pi[0], pi[1], pi[2], ph[0], ph[1], ph[2], cl.c[j * cl.ldc]);
                 cl.c[j * cl.ldc] = h;
                 if (cl.h) rnn_store_h(cl.h, cl.hdt, j * cl.ldh, h);
             }
@@ -1116,6 +998,8 @@ bool spmv_cell_applies(int kind, int64_t M, int64_t K, int32_t BR, int32_t BC, i
     if (BR > 32 || BC > 32 || dtype == GRIM_F32 || ukr <= 0 || ukc <= 0) return false;
     if (H < 1 || H > 0x7fffffff || M != (int64_t)gates * H || H % BR != 0 || K % BC != 0) return false;
     if ((ukr * ukc * esz) % 16 != 0 || ukr * ukc * esz > 384 || K * esz > 32 * 1024) return false;
+    if (!((ukr == 4 || ukr == 8 || ukr == 16) && (ukc == 4 || ukc == 8 || ukc == 12 || ukc == 16)) || (ukr == 16 && ukc == 16))
+        return false;                                              // the pairs launch_cell is compiled for
     const int nv = ukr * ukc * esz / 16;
     int64_t wb = (int64_t)exact_region_vectors(nv) * 16;
     const int64_t table = ((int64_t)BR * kPartStride * 4 + 15) & ~int64_t(15);

@@ -13,6 +13,7 @@
 #include <hip/hip_runtime.h>
 
 #include "bcr_matrix.hpp"
+#include "rnn_cell.hpp"
 
 namespace grim {
 
@@ -26,15 +27,6 @@ struct LstmParams {
     int32_t batch, dtype;
 };
 
-__device__ __forceinline__ float sigmoidf_(float v) { return 1.0f / (1.0f + expf(-v)); }
-
-__device__ __forceinline__ unsigned short f32_to_bf16_rne(float f) {
-    unsigned int u = __builtin_bit_cast(unsigned int, f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (unsigned short)((u >> 16) | 0x40u);   // NaN stays NaN
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return (unsigned short)(u >> 16);
-}
-
 __global__ void __launch_bounds__(256) lstm_cell_kernel(LstmParams p) {
     const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (e >= p.H * p.batch) return;
@@ -42,19 +34,12 @@ __global__ void __launch_bounds__(256) lstm_cell_kernel(LstmParams p) {
     const int b = (int)(e - r * p.batch);
     const float bi = p.bias ? p.bias[r] : 0.f, bf = p.bias ? p.bias[p.H + r] : 0.f;
     const float bg = p.bias ? p.bias[2 * p.H + r] : 0.f, bo = p.bias ? p.bias[3 * p.H + r] : 0.f;
-    const float gi = sigmoidf_(p.gates[r * p.ldg + b] + bi);
-    const float gf = sigmoidf_(p.gates[(p.H + r) * p.ldg + b] + bf);
-    const float gg = tanhf(p.gates[(2 * p.H + r) * p.ldg + b] + bg);
-    const float go = sigmoidf_(p.gates[(3 * p.H + r) * p.ldg + b] + bo);
-    const float c = gf * p.c[r * p.ldc + b] + gi * gg;
-    const float h = go * tanhf(c);
+    float c = p.c[r * p.ldc + b];
+    const float h = lstm_cell_apply(p.gates[r * p.ldg + b] + bi, p.gates[(p.H + r) * p.ldg + b] + bf,
+                                    p.gates[(2 * p.H + r) * p.ldg + b] + bg, p.gates[(3 * p.H + r) * p.ldg + b] + bo, c);
     p.c[r * p.ldc + b] = c;
     if (p.h32) p.h32[r * p.ldh32 + b] = h;
-    if (p.h) {
-        if (p.dtype == GRIM_F32) static_cast<float *>(p.h)[r * p.ldh + b] = h;
-        else if (p.dtype == GRIM_F16) static_cast<_Float16 *>(p.h)[r * p.ldh + b] = (_Float16)h;
-        else static_cast<unsigned short *>(p.h)[r * p.ldh + b] = f32_to_bf16_rne(h);
-    }
+    if (p.h) rnn_store_h(p.h, p.dtype, r * p.ldh + b, h);
 }
 
 // GRU cell (Section 6.1: the evaluated RNN is a two-layer GRU; Section 6.3 times it).  Two products feed it, gi = W_i x and gh = W_h h,
@@ -84,16 +69,9 @@ __global__ void __launch_bounds__(256) gru_cell_kernel(GruParams p) {
         pi[k] = p.gi[(k * p.H + j) * p.ldgi + b] + (p.bias_i ? p.bias_i[k * p.H + j] : 0.f);
         ph[k] = p.gh[(k * p.H + j) * p.ldgh + b] + (p.bias_h ? p.bias_h[k * p.H + j] : 0.f);
     }
-    const float r = sigmoidf_(pi[0] + ph[0]);
-    const float z = sigmoidf_(pi[1] + ph[1]);
-    const float n = tanhf(pi[2] + r * ph[2]);
-    const float h = (1.0f - z) * n + z * p.h32[j * p.ldh32 + b];
+    const float h = gru_cell_apply(pi[0], pi[1], pi[2], ph[0], ph[1], ph[2], p.h32[j * p.ldh32 + b]);
     p.h32[j * p.ldh32 + b] = h;
-    if (p.h) {
-        if (p.dtype == GRIM_F32) static_cast<float *>(p.h)[j * p.ldh + b] = h;
-        else if (p.dtype == GRIM_F16) static_cast<_Float16 *>(p.h)[j * p.ldh + b] = (_Float16)h;
-        else static_cast<unsigned short *>(p.h)[j * p.ldh + b] = f32_to_bf16_rne(h);
-    }
+    if (p.h) rnn_store_h(p.h, p.dtype, j * p.ldh + b, h);
 }
 
 grim_status launch_gru_cell(const float *gi, int64_t ldgi, const float *gh, int64_t ldgh, const float *bias_i,
