@@ -355,6 +355,21 @@ grim_status grim_bcr_gru_sequence(const grim_bcr_matrix *Ai, const grim_bcr_matr
                                   float *h32_dev, void *hs_dev, int64_t ldhs, float *hs32_dev, int64_t ldhs32,
                                   int32_t *status_dev, uint32_t max_polls, void *hip_stream);
 
+/*
+ * grim_bcr_lstm_sequence_noalloc -- grim_bcr_lstm_sequence for callers that cannot allocate device memory (code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): same arguments, same kernels,
+ * same results, but the exchange words live in a static device array of the library (2 x 8192 words of 8 bytes
+ * = 128 KB per GPU, held until the process ends) instead of a buffer allocated with the matrix.  The call
+ * allocates and frees nothing, on the device or through any library.  H > 8192 is GRIM_ERR_UNSUPPORTED.  All such
+ * calls on one GPU share the array (whatever the matrix): calls that overlap in time on one GPU race -- enqueue them
+ * on one stream.  The words are cleared by a small kernel at the start of every call, so the call can be captured.
+ * Errors as grim_bcr_lstm_sequence (no ALLOC).
+ */
+grim_status grim_bcr_lstm_sequence_noalloc(const grim_bcr_matrix *A, const void *xs_dev, int64_t ldxs, int32_t T,
+                                           const float *bias_dev, const void *h0_dev, float *c_dev, void *hs_dev,
+                                           int64_t ldhs, float *hs32_dev, int64_t ldhs32, int32_t *status_dev,
+                                           uint32_t max_polls, void *hip_stream);
+
 
 /*
  * BCRC export (Section 4.3, "Compact Model Storage"): the paper's six-array, row-level form of the

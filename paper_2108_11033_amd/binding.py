@@ -59,7 +59,8 @@ EXPORTS = ["grim_bcr_pack", "grim_bcr_unpack", "grim_bcr_arrays", "grim_bcr_spmm
            "grim_bcr_free", "grim_status_str", "grim_bcr_spmm_kernel_name",
            "grim_bcr_export_bcrc", "grim_bcrc_arrays", "grim_bcrc_free", "grim_lstm_cell", "grim_bcr_lstm_step", "grim_gru_cell", "grim_bcr_gru_step",
            "grim_bcr_conv2d", "grim_bcr_conv2d_act", "grim_bcr_unpack_layout", "grim_bcr_rnn_step_launches",
-           "grim_bcr_rnn_sequence_supported", "grim_bcr_lstm_sequence", "grim_bcr_gru_sequence"]
+           "grim_bcr_rnn_sequence_supported", "grim_bcr_lstm_sequence", "grim_bcr_gru_sequence",
+           "grim_bcr_lstm_sequence_noalloc"]
 
 
 def lib_path() -> str:
@@ -110,6 +111,7 @@ def load_library():
     lib.grim_bcr_rnn_step_launches.argtypes = [p, p, i32]
     lib.grim_bcr_rnn_sequence_supported.argtypes = [p, p]
     lib.grim_bcr_lstm_sequence.argtypes = [p, p, i64, i32, p, p, p, p, i64, p, i64, p, ctypes.c_uint32, p]
+    lib.grim_bcr_lstm_sequence_noalloc.argtypes = [p, p, i64, i32, p, p, p, p, i64, p, i64, p, ctypes.c_uint32, p]
     lib.grim_bcr_gru_sequence.argtypes = [p, p, p, i64, i32, p, p, p, p, p, i64, p, i64, p, ctypes.c_uint32, p]
     for name in EXPORTS:
         getattr(lib, name).restype = i32
@@ -317,6 +319,14 @@ def lstm_sequence(A: BcrMatrix, xs, ldxs: int, T: int, bias, h0, c, hs, ldhs: in
     _check(A._lib.grim_bcr_lstm_sequence(A.handle, _addr(xs), ldxs, T, _addr(bias), _addr(h0), _addr(c), _addr(hs), ldhs,
                                          _addr(hs32), ldhs32, _addr(status), max_polls, _stream(stream)),
            "grim_bcr_lstm_sequence")
+
+
+def lstm_sequence_noalloc(A: BcrMatrix, xs, ldxs: int, T: int, bias, h0, c, hs, ldhs: int, hs32, ldhs32: int, status,
+                          max_polls: int = 0, stream=None):
+    """grim_bcr_lstm_sequence_noalloc: the same sequence with the exchange words in the library's static device array."""
+    _check(A._lib.grim_bcr_lstm_sequence_noalloc(A.handle, _addr(xs), ldxs, T, _addr(bias), _addr(h0), _addr(c), _addr(hs),
+                                                 ldhs, _addr(hs32), ldhs32, _addr(status), max_polls, _stream(stream)),
+           "grim_bcr_lstm_sequence_noalloc")
 
 
 def gru_sequence(Ai: BcrMatrix, Ah: BcrMatrix, xs, ldxs: int, T: int, bias_i, bias_h, h0, h32, hs, ldhs: int, hs32,

@@ -239,6 +239,8 @@ grim_status launch_rnn_seq(int kind, const GemvDesc &d1, const GemvDesc *d2, con
                            int64_t H, int32_t T, const void *xs, int64_t ldxs, const void *h0, const float *bias,
                            const float *bias2, float *state, void *hs, int64_t ldhs, float *hs32, int64_t ldhs32,
                            void *exch, int32_t *status, uint32_t max_polls, hipStream_t stream);
+// device address of this GPU's static exchange words (2 * kSeqMaxH of them); allocates nothing
+grim_status rnn_seq_static_exchange(void **out);
 grim_status launch_lstm_cell(const float *gates, int64_t ldg, const float *bias, float *c, int64_t ldc, void *h,
                              int32_t dtype, int64_t ldh, float *h32, int64_t ldh32, int64_t H, int32_t batch,
                              hipStream_t stream);

@@ -992,6 +992,25 @@ grim_status grim_bcr_lstm_sequence(const grim_bcr_matrix *A, const void *xs_dev,
                           hs32_dev, ldhs32, exch, status_dev, max_polls, static_cast<hipStream_t>(hip_stream));
 }
 
+grim_status grim_bcr_lstm_sequence_noalloc(const grim_bcr_matrix *A, const void *xs_dev, int64_t ldxs, int32_t T,
+                                           const float *bias_dev, const void *h0_dev, float *c_dev, void *hs_dev,
+                                           int64_t ldhs, float *hs32_dev, int64_t ldhs32, int32_t *status_dev,
+                                           uint32_t max_polls, void *hip_stream) {
+    grim_status st = seq_check(A, xs_dev, T, h0_dev, c_dev, hs_dev, status_dev);
+    if (st != GRIM_OK) return st;
+    if (A->M % 4 != 0 || A->K <= A->M / 4) return GRIM_ERR_SHAPE;
+    const int64_t H = A->M / 4, I = A->K - H;
+    if (ldxs < I || ldhs < H || (hs32_dev && ldhs32 < H)) return GRIM_ERR_SHAPE;
+    if (H > kSeqMaxH) return GRIM_ERR_UNSUPPORTED;                 // beyond the static exchange words
+    if (!grim_bcr_rnn_sequence_supported(A, nullptr)) return GRIM_ERR_UNSUPPORTED;
+    void *exch = nullptr;
+    st = rnn_seq_static_exchange(&exch);
+    if (st != GRIM_OK) return st;
+    return launch_rnn_seq(1, desc_of(A), nullptr, A->dev.strip_pos, nullptr, A->BR, A->BC, A->dtype, A->gemv.uniform_kr,
+                          A->gemv.uniform_kc, A->K, 0, I, H, T, xs_dev, ldxs, h0_dev, bias_dev, nullptr, c_dev, hs_dev, ldhs,
+                          hs32_dev, ldhs32, exch, status_dev, max_polls, static_cast<hipStream_t>(hip_stream));
+}
+
 grim_status grim_bcr_gru_sequence(const grim_bcr_matrix *Ai, const grim_bcr_matrix *Ah, const void *xs_dev, int64_t ldxs,
                                   int32_t T, const float *bias_i_dev, const float *bias_h_dev, const void *h0_dev,
                                   float *h32_dev, void *hs_dev, int64_t ldhs, float *hs32_dev, int64_t ldhs32,

@@ -395,4 +395,31 @@ grim_status launch_rnn_seq(int kind, const GemvDesc &d1, const GemvDesc *d2, con
                              : launch_seq<GRIM_BF16, 2>(p, ukr, ukc, grid, lds, stream);
 }
 
+// Exchange words for callers that must not allocate: one array per GPU, part of the loaded code object, shared by
+// every such call on that GPU (calls that overlap in time on one GPU race).  Its name is a host-side stand-in; the
+// device address is asked for once per device, with that device current, and only that address is handed to kernels.
+static __device__ __align__(256) unsigned long long scratch[2 * kSeqMaxH];
+
+grim_status rnn_seq_static_exchange(void **out) {
+    constexpr int kMaxDevices = 64;
+    static std::mutex lock;
+    static void *address[kMaxDevices] = {};
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+        (void)hipGetLastError();
+        return GRIM_ERR_DEVICE;
+    }
+    std::lock_guard<std::mutex> hold(lock);
+    if (!address[dev]) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) {
+            (void)hipGetLastError();
+            return GRIM_ERR_DEVICE;
+        }
+        address[dev] = ptr;
+    }
+    *out = address[dev];
+    return GRIM_OK;
+}
+
 }  // namespace grim
