@@ -1,6 +1,7 @@
 // Portable SpMM kernel on the vector ALUs for Y = W_bcr * X (Section 3.1: CONV as GEMM on the im2col matrix).
-// Any element type, BR <= 64.  One wave owns one row strip x 64 columns of X and walks the strip's blocks in
-// ascending column-block order; every gathered X value is loaded once and reused by all kept rows of the block
+// Any element type, BR <= 64.  A workgroup of four waves owns one row strip x 64 columns of X; each wave walks a
+// quarter of the strip's blocks in ascending column-block order and the four sums are added in a fixed order;
+// every gathered X value is loaded once and reused by all kept rows of the block
 // (the load-redundancy elimination of Section 4.4, here a consequence of treating the block as a small dense
 // matrix).
 #include "spmm_common.hpp"
@@ -22,42 +23,73 @@ struct FmaParams {
     int64_t nbc;
 };
 
+constexpr int kFmaWaves = 4;     // waves of a workgroup: they share a strip's column blocks
+constexpr int kFmaBatch = 8;     // gathered values of X in flight per lane
+
 template <int DT, int BRCAP>
-__global__ void __launch_bounds__(64) bcr_spmm_fma(FmaParams p) {
+__global__ void __launch_bounds__(kFmaWaves * 64) bcr_spmm_fma(FmaParams p) {
     using T = typename Elem<DT>::type;
+    __shared__ float part[(kFmaWaves - 1) * BRCAP * 64];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int64_t t = blockIdx.x;                        // stored strip
-    const int64_t n = (int64_t)blockIdx.y * 64 + threadIdx.x;
+    const int64_t n = (int64_t)blockIdx.y * 64 + lane;
     const bool live = n < p.N;
+    const int64_t nc = live ? n : p.N - 1;               // idle lanes re-read the last column
     const T *X = static_cast<const T *>(p.X);
     const T *W = static_cast<const T *>(p.weights);
     float acc[BRCAP];
 #pragma unroll
     for (int r = 0; r < BRCAP; ++r) acc[r] = 0.f;
-    for (int64_t c = 0; c < p.nbc; ++c) {
+    // wave w takes the column blocks w, w + 4, ... in ascending order; the waves' sums are added in a fixed order
+    // at the end.  Within a block the gathered values of X are fetched kFmaBatch at a time, all loads of a batch
+    // issued before the first is used.
+    for (int64_t c = wave; c < p.nbc; c += kFmaWaves) {
         const int64_t b = t * p.nbc + c;
         const uint64_t mask = p.rowmask[b];
         const int32_t cp0 = p.col_ptr[b];
         const int32_t kc = p.col_ptr[b + 1] - cp0;
         if (mask == 0 || kc == 0) continue;
         const T *wb = W + p.blk_ptr[b];
-        for (int32_t j = 0; j < kc; ++j) {
-            const int64_t k = c * p.BC + p.col_idx[cp0 + j];
-            const float xv = live ? to_f32<DT>(X[k * p.ldx + n]) : 0.f;
-            int32_t i = 0;
+        for (int32_t j0 = 0; j0 < kc; j0 += kFmaBatch) {
+            float xv[kFmaBatch];
 #pragma unroll
-            for (int r = 0; r < BRCAP; ++r) {
-                if ((mask >> r) & 1) {                  // same for the whole wave
-                    acc[r] = __builtin_fmaf(to_f32<DT>(wb[(int64_t)i * kc + j]), xv, acc[r]);
-                    ++i;
+            for (int u = 0; u < kFmaBatch; ++u) {
+                const int32_t j = j0 + u < kc ? j0 + u : kc - 1;
+                const int64_t k = c * p.BC + p.col_idx[cp0 + j];
+                xv[u] = to_f32<DT>(X[k * p.ldx + nc]);
+            }
+#pragma unroll
+            for (int u = 0; u < kFmaBatch; ++u) {
+                if (j0 + u < kc) {
+                    int32_t i = 0;
+#pragma unroll
+                    for (int r = 0; r < BRCAP; ++r) {
+                        if ((mask >> r) & 1) {          // same for the whole wave
+                            acc[r] = __builtin_fmaf(to_f32<DT>(wb[(int64_t)i * kc + j0 + u]), xv[u], acc[r]);
+                            ++i;
+                        }
+                    }
                 }
             }
         }
     }
-    if (live) {
+    if (wave > 0) {
+#pragma unroll
+        for (int r = 0; r < BRCAP; ++r) part[((wave - 1) * BRCAP + r) * 64 + lane] = acc[r];
+    }
+    __syncthreads();
+    if (wave == 0 && live) {
         const int64_t row0 = (int64_t)p.strip_order[t] * p.BR;
 #pragma unroll
-        for (int r = 0; r < BRCAP; ++r)
-            if (r < p.BR) p.Y[(row0 + r) * p.ldy + n] = acc[r];
+        for (int r = 0; r < BRCAP; ++r) {
+            if (r < p.BR) {
+                float s = acc[r];
+#pragma unroll
+                for (int w = 1; w < kFmaWaves; ++w) s += part[((w - 1) * BRCAP + r) * 64 + lane];
+                p.Y[(row0 + r) * p.ldy + n] = s;
+            }
+        }
     }
 }
 
@@ -65,9 +97,9 @@ template <int DT>
 static grim_status launch_fma_dt(const FmaParams &p, int32_t BR, int64_t nbr, hipStream_t stream) {
     if ((p.N + 63) / 64 > 65535 || nbr > 0x7fffffff) return GRIM_ERR_SHAPE;
     dim3 grid((unsigned)nbr, (unsigned)((p.N + 63) / 64));
-    if (BR <= 16) hipLaunchKernelGGL((bcr_spmm_fma<DT, 16>), grid, dim3(64), 0, stream, p);
-    else if (BR <= 32) hipLaunchKernelGGL((bcr_spmm_fma<DT, 32>), grid, dim3(64), 0, stream, p);
-    else hipLaunchKernelGGL((bcr_spmm_fma<DT, 64>), grid, dim3(64), 0, stream, p);
+    if (BR <= 16) hipLaunchKernelGGL((bcr_spmm_fma<DT, 16>), grid, dim3(kFmaWaves * 64), 0, stream, p);
+    else if (BR <= 32) hipLaunchKernelGGL((bcr_spmm_fma<DT, 32>), grid, dim3(kFmaWaves * 64), 0, stream, p);
+    else hipLaunchKernelGGL((bcr_spmm_fma<DT, 64>), grid, dim3(kFmaWaves * 64), 0, stream, p);
     return hipGetLastError() == hipSuccess ? GRIM_OK : GRIM_ERR_DEVICE;
 }
 
