@@ -249,6 +249,37 @@ grim_status grim_bcr_conv2d_act(const grim_bcr_matrix *A, const void *F_dev, int
                                 grim_dtype out_dt, int64_t ldo, void *hip_stream);
 
 /*
+ * Convolution plan: a packed filter matrix bound to one layer geometry (Section 3.1: CONV as the filter matrix times
+ * the im2col matrix; Section 4.5: rows of that matrix whose weights are pruned are skipped).  For every row of the
+ * im2col matrix the matrix keeps, the plan holds where in a feature map that row starts (input channel, kernel row
+ * and column folded into one offset) and which kernel tap it is, so that the kernel does not split row numbers while
+ * it runs; it also carries a stride and serves a batch of images in one launch.
+ *   grim_bcr_conv_plan_create   A: packed M x (Cin * kh * kw) on the current device (must outlive the plan);
+ *                               kh, kw odd, padding kh / 2, kw / 2; stride 1 or 2 in both directions; the output
+ *                               map is Ho x Wo = ceil(H / stride) x ceil(W / stride).  Allocates the plan's words
+ *                               (4 bytes per kept im2col row, padded) on the device.  Errors: NULL, SHAPE, DEVICE,
+ *                               ALLOC, UNSUPPORTED (as grim_bcr_conv2d).
+ *   grim_bcr_conv2d_plan        F_dev: batch images [Cin][H][W] of A's element type, image b at F_dev +
+ *                               b * f_image_stride elements; out_dev: batch outputs [M][ldo] (ldo >= Ho * Wo) of
+ *                               element type out_dt, image b at out_dev + b * out_image_stride elements, overwritten
+ *                               (entries n < Ho * Wo of each row); bias_dev (M fp32 or NULL), relu and the rounding as
+ *                               grim_bcr_conv2d_act.  With batch = 1 the image strides are ignored.  Sums in fp32 in
+ *                               the same order as grim_bcr_conv2d: with stride 1 the two write the same bits.  Stride 2
+ *                               computes on the input grid and stores the even positions (every second row is skipped
+ *                               when W is a multiple of 8).  Enqueues one launch on hip_stream, allocates nothing.
+ *                               Errors: NULL, SHAPE (batch < 1, ldo or an image stride too small), DTYPE, DEVICE,
+ *                               UNSUPPORTED.
+ *   grim_bcr_conv_plan_free     frees the plan (not the matrix).
+ */
+typedef struct grim_bcr_conv_plan grim_bcr_conv_plan;
+grim_status grim_bcr_conv_plan_create(const grim_bcr_matrix *A, int32_t Cin, int32_t H, int32_t W, int32_t kh, int32_t kw,
+                                      int32_t stride, grim_bcr_conv_plan **out);
+void grim_bcr_conv_plan_free(grim_bcr_conv_plan *plan);
+grim_status grim_bcr_conv2d_plan(const grim_bcr_conv_plan *plan, const void *F_dev, int32_t batch, int64_t f_image_stride,
+                                 const float *bias_dev, int32_t relu, void *out_dev, grim_dtype out_dt, int64_t ldo,
+                                 int64_t out_image_stride, void *hip_stream);
+
+/*
  * LSTM cell around the gate product (Section 3.1: an RNN layer's gate matrices are one matrix-vector
  * product per time step).  With the gate matrix [W_ih | W_hh] of 4H rows packed as one BCR matrix
  * and the step's input vector [x; h], grim_bcr_spmv delivers the gate pre-activations, rows [0, H)

@@ -32,6 +32,30 @@ def conv_same(Wm64: np.ndarray, F64: np.ndarray, kh: int, kw: int) -> np.ndarray
     return Y
 
 
+def conv2d(Wm64: np.ndarray, F64: np.ndarray, kh: int, kw: int, stride: int = 1) -> np.ndarray:
+    """A batch of images at a stride, padding kh // 2 and kw // 2 (the layers of the evaluated networks, Section 6.1):
+    Wm64: M x (Cin * kh * kw), F64: B x Cin x H x W  ->  B x M x Ho x Wo with Ho = ceil(H / stride), Wo = ceil(W / stride),
+
+        Y[b, m, ho, wo] = sum over (cin, r, q) of  Wm[m, cin, r, q] * F[b, cin, stride * ho + r - kh // 2, stride * wo + q - kw // 2]
+
+    Written out per image and per kernel tap on the strided view of the padded image."""
+    B, Cin, H, W = F64.shape
+    M = Wm64.shape[0]
+    Wr = Wm64.reshape(M, Cin, kh, kw)
+    ph, pw = kh // 2, kw // 2
+    Ho, Wo = -(-H // stride), -(-W // stride)
+    Y = np.zeros((B, M, Ho, Wo), dtype=np.float64)
+    for b in range(B):
+        Fp = np.zeros((Cin, H + 2 * ph, W + 2 * pw), dtype=np.float64)
+        Fp[:, ph:ph + H, pw:pw + W] = F64[b]
+        for r in range(kh):
+            for q in range(kw):
+                # padded coordinates of tap (r, q) at output (ho, wo): (stride * ho + r, stride * wo + q)
+                view = Fp[:, r:r + stride * (Ho - 1) + 1:stride, q:q + stride * (Wo - 1) + 1:stride]
+                Y[b] += np.einsum("mc,chw->mhw", Wr[:, :, r, q], view)
+    return Y
+
+
 def abs_scale(Wm64: np.ndarray, F64: np.ndarray, kh: int, kw: int) -> np.ndarray:
     """S[m, h, w] = sum of |terms|, the scale the error is measured against."""
     return conv_same(np.abs(Wm64), np.abs(F64), kh, kw)

@@ -60,7 +60,7 @@ EXPORTS = ["grim_bcr_pack", "grim_bcr_unpack", "grim_bcr_arrays", "grim_bcr_spmm
            "grim_bcr_export_bcrc", "grim_bcrc_arrays", "grim_bcrc_free", "grim_lstm_cell", "grim_bcr_lstm_step", "grim_gru_cell", "grim_bcr_gru_step",
            "grim_bcr_conv2d", "grim_bcr_conv2d_act", "grim_bcr_unpack_layout", "grim_bcr_rnn_step_launches",
            "grim_bcr_rnn_sequence_supported", "grim_bcr_lstm_sequence", "grim_bcr_gru_sequence",
-           "grim_bcr_lstm_sequence_noalloc"]
+           "grim_bcr_lstm_sequence_noalloc", "grim_bcr_conv_plan_create", "grim_bcr_conv_plan_free", "grim_bcr_conv2d_plan"]
 
 
 def lib_path() -> str:
@@ -111,6 +111,9 @@ def load_library():
     lib.grim_bcr_rnn_step_launches.argtypes = [p, p, i32]
     lib.grim_bcr_rnn_sequence_supported.argtypes = [p, p]
     lib.grim_bcr_lstm_sequence.argtypes = [p, p, i64, i32, p, p, p, p, i64, p, i64, p, ctypes.c_uint32, p]
+    lib.grim_bcr_conv_plan_create.argtypes = [p, i32, i32, i32, i32, i32, i32, ctypes.POINTER(p)]
+    lib.grim_bcr_conv_plan_free.argtypes = [p]
+    lib.grim_bcr_conv2d_plan.argtypes = [p, p, i32, i64, p, i32, p, i32, i64, i64, p]
     lib.grim_bcr_lstm_sequence_noalloc.argtypes = [p, p, i64, i32, p, p, p, p, i64, p, i64, p, ctypes.c_uint32, p]
     lib.grim_bcr_gru_sequence.argtypes = [p, p, p, i64, i32, p, p, p, p, p, i64, p, i64, p, ctypes.c_uint32, p]
     for name in EXPORTS:
@@ -120,6 +123,7 @@ def load_library():
     lib.grim_bcr_free.restype = None
     lib.grim_bcrc_free.restype = None
     lib.grim_bcr_group_free.restype = None
+    lib.grim_bcr_conv_plan_free.restype = None
     _lib = lib
     return lib
 
@@ -292,6 +296,34 @@ def conv2d_act(A: BcrMatrix, F, Cin: int, H: int, W: int, kh: int, kw: int, bias
 def rnn_step_launches(A: BcrMatrix, Ah: Optional[BcrMatrix], batch: int) -> int:
     """grim_bcr_rnn_step_launches: kernels per LSTM step of A (Ah None) or GRU step of (A, Ah)."""
     return int(A._lib.grim_bcr_rnn_step_launches(A.handle, Ah.handle if Ah is not None else None, batch))
+
+
+class ConvPlan:
+    """grim_bcr_conv_plan: a packed filter matrix bound to one layer geometry (and a stride); freed with the object.
+    Keeps the matrix alive."""
+
+    def __init__(self, A: "BcrMatrix", Cin: int, H: int, W: int, kh: int, kw: int, stride: int = 1):
+        self._lib = A._lib
+        self.A = A
+        self.geometry = (Cin, H, W, kh, kw, stride)
+        self.out_hw = ((H + stride - 1) // stride, (W + stride - 1) // stride)
+        h = ctypes.c_void_p()
+        _check(self._lib.grim_bcr_conv_plan_create(A.handle, Cin, H, W, kh, kw, stride, ctypes.byref(h)),
+               "grim_bcr_conv_plan_create")
+        self.handle = h
+
+    def __del__(self):
+        h, self.handle = getattr(self, "handle", None), None
+        if h:
+            self._lib.grim_bcr_conv_plan_free(h)
+
+
+def conv2d_plan(plan: ConvPlan, F, batch: int, f_image_stride: int, bias, relu: bool, out, out_dtype, ldo: int,
+                out_image_stride: int, stream=None):
+    """grim_bcr_conv2d_plan: the planned convolution layer on `batch` images."""
+    _check(plan._lib.grim_bcr_conv2d_plan(plan.handle, _addr(F), batch, f_image_stride, _addr(bias), 1 if relu else 0,
+                                          _addr(out), _DT_CODE[out_dtype], ldo, out_image_stride, _stream(stream)),
+           "grim_bcr_conv2d_plan")
 
 
 def lstm_cell(gates, ldg: int, bias, c, ldc: int, h, dtype, ldh: int, h32, ldh32: int, H: int, batch: int, stream=None):

@@ -37,6 +37,16 @@ struct ConvParams {
     int32_t nbr, ntiles;
     int32_t usteps;              // > 0: steps of every run (sptr is not read)
     int32_t yvec;
+    // a convolution plan: per k slot of `rows` the tap and the window start for output position 0, already split
+    // (tap << 27 | start + 2^25; tap = KK for padding slots); null: the kernel splits the row numbers itself
+    const uint32_t *plan;
+    int32_t batch, tiles_per_img;        // images; ntiles = batch * tiles_per_img
+    int64_t f_img_stride, y_img_stride;  // elements between images of F and of Y
+    // stride 1: the 64 positions of a tile are output positions.  stride 2: they are positions of the INPUT grid, of
+    // which only those with even row and column are stored (output (h / 2, w / 2)); hmul = 2: the tiles walk the even
+    // rows only (needs W % 8 == 0, so that a lane's 8 positions never straddle two rows), hmul = 1: all rows
+    int32_t stride, hmul, Wo;
+    int32_t Nv;                  // positions the tiles of one image walk: (rows walked) * W
     XcdMap map;
 };
 
@@ -68,11 +78,14 @@ __global__ void __launch_bounds__(LONGW ? LONGW * 64 : 256, LONGW ? 1024 / (LONG
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     int tile, unit;
     if (!xcd_map_at(p.map, blockIdx.x, p.ntiles, &tile, &unit)) return;
+    const int img = tile / p.tiles_per_img;
+    tile -= img * p.tiles_per_img;
+    const unsigned short *Fimg = p.F + (int64_t)img * p.f_img_stride;
     const int t_raw = SOLO ? unit * 4 + wave : unit;
     const bool active = t_raw < p.nbr;           // SOLO: the last workgroup of a tile may have idle waves
     const int t = active ? t_raw : p.nbr - 1;
     int n0 = tile * TN;
-    if (n0 + TN > p.N) n0 = p.N - TN;            // ragged last tile: overlap the neighbour
+    if (n0 + TN > p.Nv) n0 = p.Nv - TN;          // ragged last tile: overlap the neighbour
     n0 = n0 < 0 ? 0 : n0;                        // a map of fewer than 64 positions: one tile, its columns past N never stored
 
     // one dependent memory round trip less at the start when every run has the same number of steps
@@ -84,6 +97,7 @@ __global__ void __launch_bounds__(LONGW ? LONGW * 64 : 256, LONGW ? 1024 / (LONG
     // so that their latency runs under it.
     const int kgroup0 = lane >> 4;
     const uint2 *desc2 = reinterpret_cast<const uint2 *>(p.desc);
+    const uint32_t *slots = p.plan ? p.plan : p.rows;
     unsigned int npk[SB];
     uint2 ndsc[SB];
 #pragma unroll
@@ -91,7 +105,7 @@ __global__ void __launch_bounds__(LONGW ? LONGW * 64 : 256, LONGW ? 1024 / (LONG
         int st = s_beg + u;
         st = st < s_end ? st : s_end - 1;
         st = st < 0 ? 0 : st;                    // (a wave without steps: any valid step, never used)
-        npk[u] = p.rows[(int64_t)st * 32 + (lane & 7) * 4 + ((lane >> 3) & 3)];
+        npk[u] = slots[(int64_t)st * 32 + (lane & 7) * 4 + ((lane >> 3) & 3)];
         ndsc[u] = desc2[(int64_t)st * 4 + kgroup0];
     }
     // per (tap, piece of the tile) the 16-byte validity mask of the piece's 8 positions; entry KK
@@ -108,8 +122,8 @@ __global__ void __launch_bounds__(LONGW ? LONGW * 64 : 256, LONGW ? 1024 / (LONG
         if (tap < p.KK) {
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
-                int h = h0, w = w0 + j;
-                while (w >= p.W) { w -= p.W; ++h; }  // once at most for W >= 8 (positions past N, of a small map: h >= H, never stored)
+                int h = h0 * p.hmul, w = w0 + j;
+                while (w >= p.W) { w -= p.W; h += p.hmul; }  // once at most for W >= 8 (positions past the last, of a small map: h >= H, never stored)
                 const bool ok = h + dr >= 0 && h + dr < p.H && w + dq >= 0 && w + dq < p.W;
                 m[j >> 1] |= ok ? (j & 1 ? 0xffff0000u : 0x0000ffffu) : 0u;
             }
@@ -138,12 +152,22 @@ __global__ void __launch_bounds__(LONGW ? LONGW * 64 : 256, LONGW ? 1024 / (LONG
     for (int q = 0; q < NT; ++q) acc[q] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     const i16x8 *pay = reinterpret_cast<const i16x8 *>(p.payload);
-    const char *Fb = reinterpret_cast<const char *>(p.F);
+    const char *Fb = reinterpret_cast<const char *>(Fimg);
     const int HW = p.N, wstep = p.W - p.kw, emax = p.total - 8;
-    const int nshift0 = n0 - (ph * p.W + pw);    // window start relative to a channel, tile's first column, centre tap removed
-    const int cofs = c * 8 - (1 << 25);          // this lane's piece, and the bias of the packed form
+    const int centre = ph * p.W + pw;            // offset of the centre tap: window starts are relative to it
+    // element (inside a channel) of the first of the 8 positions of piece cc: the position itself, or with every
+    // second row skipped (2 * row * W + column)
+    auto pos_off = [&](int cc) {
+        const int nb = n0 + cc * 8;
+        return p.hmul == 1 ? nb : nb + (nb / p.W) * p.W;
+    };
+    const int cofs = pos_off(c) - (1 << 25);     // this lane's piece, and the bias of the packed form
+    const int off7 = pos_off(7);
+    // Windows that start at an odd element are fetched one element early and shifted (see below), which takes the
+    // next piece to continue this one in memory: true unless rows are skipped
+    const bool use_shift = p.hmul == 1;
     // can a window of this tile start before the feature map or end behind it?  (only in the first / last channel)
-    const bool tile_edge = n0 < ph * p.W + pw || n0 + TN + ph * p.W + pw > HW;
+    const bool tile_edge = pos_off(0) < centre || off7 + 8 + centre > HW;
     for (int s = s_beg; s < s_end; s += SB) {
         const int nb = s_end - s < SB ? s_end - s : SB;
         // Lane j takes k slot j % 32 of every step of the batch: it splits the slot's row number once into
@@ -159,7 +183,7 @@ __global__ void __launch_bounds__(LONGW ? LONGW * 64 : 256, LONGW ? 1024 / (LONG
                 dsc[u] = ndsc[u];
             } else {
                 const int st = s + (u < nb ? u : nb - 1);
-                pk[u] = p.rows[(int64_t)st * 32 + (lane & 7) * 4 + ((lane >> 3) & 3)];
+                pk[u] = slots[(int64_t)st * 32 + (lane & 7) * 4 + ((lane >> 3) & 3)];
                 dsc[u] = desc2[(int64_t)st * 4 + kgroup];
             }
         }
@@ -179,25 +203,32 @@ __global__ void __launch_bounds__(LONGW ? LONGW * 64 : 256, LONGW ? 1024 / (LONG
             constexpr bool SAFE = decltype(safe_tag)::value;
 #pragma unroll
             for (int u = 0; u < SB; ++u) {
-                const bool is_pad = pk[u] == 0xffffffffu;
-                const unsigned int kk = is_pad ? 0u : pk[u];
-                // (24-bit multiplies: Cin, H * W, W and the tap numbers are all below 2^24)
-                const unsigned int cin = __umulhi(kk << 1, (unsigned int)p.kk_magic);
-                const int tap = (int)(kk - __umul24(cin, (unsigned int)p.KK));
-                const unsigned int r = __umul24((unsigned int)tap, (unsigned int)p.kw_magic) >> 8;   // tap / kw
-                // r * W + (tap - r * kw), less the centre tap's offset, for the tile's first column
-                const int eb = (int)__umul24(cin, (unsigned int)HW) + __mul24((int)r, wstep) + tap + nshift0;   // (W < kw: wstep < 0)
-                pk[u] = (unsigned int)(is_pad ? p.KK : tap) << 27 | (unsigned int)(eb + (1 << 25));
+                bool is_pad;
+                int eb;                          // window start for position 0 of the image
+                if (p.plan) {                    // (uniform) already split when the plan was made
+                    is_pad = (int)(pk[u] >> 27) == p.KK;
+                    eb = (int)(pk[u] & 0x7ffffffu) - (1 << 25);
+                } else {
+                    is_pad = pk[u] == 0xffffffffu;
+                    const unsigned int kk = is_pad ? 0u : pk[u];
+                    // (24-bit multiplies: Cin, H * W, W and the tap numbers are all below 2^24)
+                    const unsigned int cin = __umulhi(kk << 1, (unsigned int)p.kk_magic);
+                    const int tap = (int)(kk - __umul24(cin, (unsigned int)p.KK));
+                    const unsigned int r = __umul24((unsigned int)tap, (unsigned int)p.kw_magic) >> 8;   // tap / kw
+                    // r * W + (tap - r * kw), less the centre tap's offset
+                    eb = (int)__umul24(cin, (unsigned int)HW) + __mul24((int)r, wstep) + tap - centre;   // (W < kw: wstep < 0)
+                    pk[u] = (unsigned int)(is_pad ? p.KK : tap) << 27 | (unsigned int)(eb + (1 << 25));
+                }
                 // A 16-byte load at an odd element (2 bytes off a dword) costs about three aligned ones in the
                 // vector L1, a load that is only dword-aligned next to nothing.  A window that starts at an odd
                 // element is therefore fetched one element early; when the step is written the lane shifts it
                 // by 16 bits and takes its last element from the next lane's first dword.  The last lane of a
                 // row piece has no such neighbour: lanes 0..31 fetch the boundary element of their k slot with
                 // one extra 2-byte load per step, handed over by a lane permute.
-                const int e7 = eb + 56;
-                bool need = lane < 32 && !is_pad && (e7 & 1);
+                const int e7 = eb + off7;
+                bool need = use_shift && lane < 32 && !is_pad && (e7 & 1);
                 if constexpr (SAFE) need = need && e7 + 7 >= 0 && e7 + 7 < p.total;
-                ext[u] = need ? (unsigned int)p.F[e7 + 7] : 0u;
+                ext[u] = need ? (unsigned int)Fimg[e7 + 7] : 0u;
             }
             bool edge_any = false;
 #pragma unroll
@@ -207,7 +238,7 @@ __global__ void __launch_bounds__(LONGW ? LONGW * 64 : 256, LONGW ? 1024 / (LONG
                 for (int i = 0; i < 4; ++i) {
                     unsigned int sel;
                     const int e0 = piece(u, i, sel);
-                    const int odd = e0 & 1;
+                    const int odd = use_shift ? e0 & 1 : 0;
                     vsel[u] |= (sel | (unsigned int)odd << 7) << (8 * i);
                     int ea = e0 - odd;
                     if constexpr (SAFE) {
@@ -234,8 +265,8 @@ __global__ void __launch_bounds__(LONGW ? LONGW * 64 : 256, LONGW ? 1024 / (LONG
                                 unsigned int d[4] = {0u, 0u, 0u, 0u};
 #pragma unroll
                                 for (int j = 0; j < 8; ++j) {
-                                    const int e = e0 - (e0 & 1) + j;
-                                    const unsigned int v = e >= 0 && e < p.total ? p.F[e] : 0u;
+                                    const int e = e0 - (use_shift ? e0 & 1 : 0) + j;
+                                    const unsigned int v = e >= 0 && e < p.total ? Fimg[e] : 0u;
                                     d[j >> 1] |= v << ((j & 1) * 16);
                                 }
                                 RX[u][i] = u32x4{d[0], d[1], d[2], d[3]};
@@ -294,6 +325,16 @@ __global__ void __launch_bounds__(LONGW ? LONGW * 64 : 256, LONGW ? 1024 / (LONG
 
     // epilogue of a layer for four consecutive positions n .. n + 3 of output channel `row`: bias, rectifier,
     // rounding to the next layer's element type
+    char *Yimg = static_cast<char *>(p.Y) + (int64_t)img * p.y_img_stride * (p.odt == GRIM_F32 ? 4 : 2);
+    auto store_one = [&](int64_t at, float v) {
+        if (p.odt == GRIM_F32) {
+            reinterpret_cast<float *>(Yimg)[at] = v;
+        } else if (p.odt == GRIM_F16) {
+            reinterpret_cast<_Float16 *>(Yimg)[at] = (_Float16)v;
+        } else {
+            reinterpret_cast<unsigned short *>(Yimg)[at] = conv_f32_to_bf16(v);
+        }
+    };
     auto finish = [&](int64_t row, int64_t n, f32x4 sum) {
         const float b = p.bias ? p.bias[row] : 0.f;
 #pragma unroll
@@ -301,10 +342,21 @@ __global__ void __launch_bounds__(LONGW ? LONGW * 64 : 256, LONGW ? 1024 / (LONG
             sum[e] += b;
             if (p.relu) sum[e] = sum[e] > 0.f ? sum[e] : 0.f;     // NaN stays NaN
         }
+        const int left = (int)(p.Nv - n);            // below 4 only in the one tile of a map of fewer than 64 positions
+        if (p.stride != 1) {
+            // positions of the input grid: the ones with even row and column are outputs
+            int hv = (int)(n / p.W), w = (int)(n - (int64_t)hv * p.W);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int h = hv * p.hmul;
+                if (e < left && !(h & 1) && !(w & 1)) store_one(row * p.ldy + (int64_t)(h >> 1) * p.Wo + (w >> 1), sum[e]);
+                if (++w == p.W) { w = 0; ++hv; }
+            }
+            return;
+        }
         const bool vec = p.yvec == 4 && (n & 3) == 0;
-        const int left = (int)(p.N - n);             // below 4 only in the one tile of a map of fewer than 64 positions
         if (p.odt == GRIM_F32) {
-            float *dst = static_cast<float *>(p.Y) + row * p.ldy + n;
+            float *dst = reinterpret_cast<float *>(Yimg) + row * p.ldy + n;
             if (vec && left >= 4) {
                 *reinterpret_cast<f32x4 *>(dst) = sum;
             } else {
@@ -323,7 +375,7 @@ __global__ void __launch_bounds__(LONGW ? LONGW * 64 : 256, LONGW ? 1024 / (LONG
                     h[e] = conv_f32_to_bf16(sum[e]);
                 }
             }
-            unsigned short *dst = static_cast<unsigned short *>(p.Y) + row * p.ldy + n;
+            unsigned short *dst = reinterpret_cast<unsigned short *>(Yimg) + row * p.ldy + n;
             if (vec && left >= 4) {
                 *reinterpret_cast<uint2 *>(dst) = uint2{(unsigned int)h[0] | ((unsigned int)h[1] << 16), (unsigned int)h[2] | ((unsigned int)h[3] << 16)};
             } else {
@@ -357,10 +409,22 @@ __global__ void __launch_bounds__(LONGW ? LONGW * 64 : 256, LONGW ? 1024 / (LONG
     if (row >= 0) finish(row, n0 + q * 16 + 4 * (lane >> 4), sum);
 }
 
+// The window-start word of one k slot (row `k` of the im2col matrix, 0xffffffff: padding) for a convolution plan.
+uint32_t conv_plan_word(uint32_t k, int32_t H, int32_t W, int32_t kh, int32_t kw) {
+    const int32_t KK = kh * kw;
+    if (k == 0xffffffffu) return (uint32_t)KK << 27 | (1u << 25);
+    const int64_t cin = k / KK;
+    const int32_t tap = (int32_t)(k % KK), r = tap / kw, q = tap % kw;
+    const int64_t eb = cin * H * W + (int64_t)r * W + q - ((int64_t)(kh / 2) * W + kw / 2);
+    return (uint32_t)tap << 27 | (uint32_t)(eb + (1 << 25));
+}
+
 grim_status launch_conv_gather(const grim_bcr_matrix *A, const void *F, int32_t Cin, int32_t H, int32_t W, int32_t kh,
                                int32_t kw, const float *bias, int32_t relu, void *Y, int32_t odt, int64_t ldy,
-                               hipStream_t stream) {
+                               hipStream_t stream, int32_t batch, int32_t stride, int64_t f_img_stride,
+                               int64_t y_img_stride, const uint32_t *plan) {
     const int64_t N = (int64_t)H * W, total = (int64_t)Cin * N;
+    if (batch < 1 || (stride != 1 && stride != 2)) return GRIM_ERR_UNSUPPORTED;
     if (!A->gather.present || total < 8 || kh * kw > kConvMaxTaps || total > (int64_t(1) << 26) || (int64_t)(kh / 2) * W + kw / 2 >= (1 << 24) ||
         A->K > (int64_t(1) << 27) || A->K * (int64_t)(kh * kw) > (int64_t(1) << 31) || Cin >= (1 << 24) || N >= (1 << 24) || reinterpret_cast<uintptr_t>(F) % 2 != 0)
         return GRIM_ERR_UNSUPPORTED;
@@ -385,9 +449,22 @@ grim_status launch_conv_gather(const grim_bcr_matrix *A, const void *F, int32_t 
     p.total = (int32_t)total;
     p.nbr = (int32_t)A->gather.nstrips;
     p.usteps = A->gather.usteps;
-    p.ntiles = (int32_t)((N + 63) / 64);
+    p.plan = plan;
+    p.batch = batch;
+    p.f_img_stride = f_img_stride;
+    p.y_img_stride = y_img_stride;
+    p.stride = stride;
+    p.hmul = stride == 2 && W % 8 == 0 ? 2 : 1;
+    p.Wo = (W + stride - 1) / stride;
+    const int64_t Nv = p.hmul == 2 ? (int64_t)((H + 1) / 2) * W : N;
+    p.Nv = (int32_t)Nv;
+    p.tiles_per_img = (int32_t)((Nv + 63) / 64);
+    if ((int64_t)p.tiles_per_img * batch > 0x7fffffff / 16) return GRIM_ERR_SHAPE;
+    p.ntiles = p.tiles_per_img * batch;
     // four consecutive outputs of a row in one store: 16 bytes of fp32, 8 bytes of fp16 / bf16
-    p.yvec = (reinterpret_cast<uintptr_t>(Y) % (odt == GRIM_F32 ? 16 : 8) == 0 && ldy % 4 == 0 && N % 4 == 0) ? 4 : 1;
+    const int esz_out = odt == GRIM_F32 ? 4 : 2;
+    p.yvec = (stride == 1 && reinterpret_cast<uintptr_t>(Y) % (odt == GRIM_F32 ? 16 : 8) == 0 && ldy % 4 == 0 && N % 4 == 0 &&
+              (batch == 1 || (y_img_stride * esz_out) % (odt == GRIM_F32 ? 16 : 8) == 0)) ? 4 : 1;
     // the same launch forms as the row-gathering kernel
     const bool solo = gather_wave_per_strip(A, (int64_t)p.ntiles * p.nbr, 4096);
     const int64_t pairs = (int64_t)p.ntiles * p.nbr;

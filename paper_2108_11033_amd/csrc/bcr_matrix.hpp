@@ -212,9 +212,13 @@ bool gather_applies(const grim_bcr_matrix *A, const void *X, int64_t N, int64_t 
 // launch form of the row-gathering kernels: a (tile, strip) pair per wave instead of four waves per strip
 bool gather_wave_per_strip(const grim_bcr_matrix *A, int64_t pairs, int64_t pairs_for_long_strips);
 // convolution on the row-gathering layout, the im2col matrix never formed
+// batch images f_img_stride / y_img_stride elements apart; stride 1 or 2 ("same" padding, output ceil(H / stride) x
+// ceil(W / stride)); plan: the k slots' window-start words (conv_plan_word) on the device, or null
 grim_status launch_conv_gather(const grim_bcr_matrix *A, const void *F, int32_t Cin, int32_t H, int32_t W, int32_t kh,
                                int32_t kw, const float *bias, int32_t relu, void *Y, int32_t odt, int64_t ldy,
-                               hipStream_t stream);
+                               hipStream_t stream, int32_t batch = 1, int32_t stride = 1, int64_t f_img_stride = 0,
+                               int64_t y_img_stride = 0, const uint32_t *plan = nullptr);
+uint32_t conv_plan_word(uint32_t k, int32_t H, int32_t W, int32_t kh, int32_t kw);
 // cost estimates (bytes through one compute unit) used to choose between the two matrix-core kernels
 double gather_cost(const grim_bcr_matrix *A, int64_t N);
 double mma_best_shape(const grim_bcr_matrix *A, int64_t N, int32_t tile_n, int32_t strips_per_wg, int *tn_out, int *g_out);

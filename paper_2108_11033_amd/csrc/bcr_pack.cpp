@@ -4,6 +4,7 @@
 #include <algorithm>
 #include <cstring>
 #include <map>
+#include <memory>
 #include <new>
 #include <numeric>
 
@@ -872,6 +873,64 @@ grim_status grim_bcr_conv2d_act(const grim_bcr_matrix *A, const void *F_dev, int
                                 int32_t kw, const float *bias_dev, int32_t relu, void *out_dev, grim_dtype out_dt,
                                 int64_t ldo, void *hip_stream) {
     return conv_call(A, F_dev, Cin, H, W, kh, kw, bias_dev, relu, out_dev, (int32_t)out_dt, ldo, hip_stream);
+}
+
+struct grim_bcr_conv_plan {
+    const grim_bcr_matrix *A = nullptr;
+    int32_t Cin = 0, H = 0, W = 0, kh = 0, kw = 0, stride = 1;
+    int device = -1;
+    uint32_t *d_words = nullptr;
+};
+
+grim_status grim_bcr_conv_plan_create(const grim_bcr_matrix *A, int32_t Cin, int32_t H, int32_t W, int32_t kh, int32_t kw,
+                                      int32_t stride, grim_bcr_conv_plan **out) {
+    if (!A || !out) return GRIM_ERR_NULL;
+    *out = nullptr;
+    if (Cin < 1 || H < 1 || W < 1 || kh < 1 || kw < 1 || kh % 2 == 0 || kw % 2 == 0) return GRIM_ERR_SHAPE;
+    if ((int64_t)Cin * kh * kw != A->K || (stride != 1 && stride != 2)) return GRIM_ERR_SHAPE;
+    if (!A->on_device) return GRIM_ERR_DEVICE;
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev != A->device) { (void)hipGetLastError(); return GRIM_ERR_DEVICE; }
+    if (!A->gather.present || kh * kw > 31 || (int64_t)Cin * H * W > (int64_t(1) << 26) || A->gather.rows.empty())
+        return GRIM_ERR_UNSUPPORTED;
+    std::vector<uint32_t> words(A->gather.rows.size());
+    for (size_t i = 0; i < words.size(); ++i) words[i] = conv_plan_word(A->gather.rows[i], H, W, kh, kw);
+    std::unique_ptr<grim_bcr_conv_plan> P(new (std::nothrow) grim_bcr_conv_plan);
+    if (!P) return GRIM_ERR_ALLOC;
+    P->A = A; P->Cin = Cin; P->H = H; P->W = W; P->kh = kh; P->kw = kw; P->stride = stride; P->device = dev;
+    void *ptr = nullptr;
+    if (hipMalloc(&ptr, words.size() * 4) != hipSuccess) { (void)hipGetLastError(); return GRIM_ERR_ALLOC; }
+    if (hipMemcpy(ptr, words.data(), words.size() * 4, hipMemcpyHostToDevice) != hipSuccess) {
+        (void)hipGetLastError();
+        (void)hipFree(ptr);
+        return GRIM_ERR_DEVICE;
+    }
+    P->d_words = static_cast<uint32_t *>(ptr);
+    *out = P.release();
+    return GRIM_OK;
+}
+
+void grim_bcr_conv_plan_free(grim_bcr_conv_plan *P) {
+    if (!P) return;
+    if (P->d_words) (void)hipFree(P->d_words);
+    delete P;
+}
+
+grim_status grim_bcr_conv2d_plan(const grim_bcr_conv_plan *P, const void *F_dev, int32_t batch, int64_t f_image_stride,
+                                 const float *bias_dev, int32_t relu, void *out_dev, grim_dtype out_dt, int64_t ldo,
+                                 int64_t out_image_stride, void *hip_stream) {
+    if (!P || !F_dev || !out_dev) return GRIM_ERR_NULL;
+    const int64_t Ho = (P->H + P->stride - 1) / P->stride, Wo = (P->W + P->stride - 1) / P->stride;
+    const int64_t M = P->A->M;
+    if (batch < 1 || ldo < Ho * Wo) return GRIM_ERR_SHAPE;
+    if (batch > 1 && (f_image_stride < (int64_t)P->Cin * P->H * P->W || out_image_stride < (M - 1) * ldo + Ho * Wo))
+        return GRIM_ERR_SHAPE;
+    if (out_dt != GRIM_F32 && out_dt != GRIM_F16 && out_dt != GRIM_BF16) return GRIM_ERR_DTYPE;
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev != P->device) { (void)hipGetLastError(); return GRIM_ERR_DEVICE; }
+    return launch_conv_gather(P->A, F_dev, P->Cin, P->H, P->W, P->kh, P->kw, bias_dev, relu ? 1 : 0, out_dev, (int32_t)out_dt,
+                              ldo, static_cast<hipStream_t>(hip_stream), batch, P->stride, f_image_stride, out_image_stride,
+                              P->d_words);
 }
 
 grim_status grim_lstm_cell(const float *gates_dev, int64_t ldg, const float *bias_dev, float *c_dev, int64_t ldc,

@@ -62,6 +62,39 @@ def test_layer_reference_matches_library_conv_with_bias_and_relu():
     assert np.array_equal(conv_ref.layer(Wm, F, 3, 3), conv_ref.conv_same(Wm, F, 3, 3))
 
 
+
+@pytest.mark.parametrize("kh,kw,stride,H,W", [(3, 3, 2, 8, 10), (3, 3, 2, 7, 9), (1, 1, 2, 5, 6), (5, 5, 2, 9, 9), (3, 3, 1, 6, 5)])
+def test_batched_strided_reference_equals_library_conv_and_plain_loops(kh, kw, stride, H, W):
+    import torch
+    B, Cin, M = 2, 3, 4
+    rng = np.random.default_rng(34)
+    Wm = rng.standard_normal((M, Cin * kh * kw))
+    Wm[rng.random(Wm.shape) < 0.5] = 0.0
+    F = rng.standard_normal((B, Cin, H, W))
+    Y = conv_ref.conv2d(Wm, F, kh, kw, stride)
+    Yt = torch.nn.functional.conv2d(torch.from_numpy(F), torch.from_numpy(Wm.reshape(M, Cin, kh, kw)), stride=stride,
+                                    padding=(kh // 2, kw // 2)).numpy()
+    assert Y.shape == Yt.shape == (B, M, -(-H // stride), -(-W // stride))
+    assert np.allclose(Y, Yt, rtol=0, atol=1e-12)
+    # the definition, term by term
+    Wr = Wm.reshape(M, Cin, kh, kw)
+    for b, m, ho, wo in [(0, 0, 0, 0), (1, 3, Y.shape[2] - 1, Y.shape[3] - 1), (1, 2, 1, 2), (0, 1, Y.shape[2] - 1, 0)]:
+        s = 0.0
+        for cin in range(Cin):
+            for r in range(kh):
+                for q in range(kw):
+                    h, w = stride * ho + r - kh // 2, stride * wo + q - kw // 2
+                    if 0 <= h < H and 0 <= w < W:
+                        s += Wr[m, cin, r, q] * F[b, cin, h, w]
+        assert abs(Y[b, m, ho, wo] - s) <= 1e-12
+    # stride 1, one image: the single-image reference
+    if stride == 1:
+        assert np.array_equal(Y[1], conv_ref.conv_same(Wm, F[1], kh, kw))
+    else:
+        # a strided convolution is the stride-1 result read at every stride-th position
+        assert np.allclose(Y[0], conv_ref.conv_same(Wm, F[0], kh, kw)[:, ::stride, ::stride], rtol=0, atol=1e-12)
+
+
 # ------------------------------------------------------------------ GPU
 def _run(g, A, F, dtype, M, Cin, H, W, kh, kw, ldy=None):
     import torch
@@ -366,6 +399,139 @@ def test_three_conv_layers_chained_in_fp16():
         # the next layer consumes what the device wrote
         ref_in = got.astype(np.float64)
         cur = out
+
+
+
+def _run_plan(g, A, F, dtype, M, kh, kw, stride, bias=None, relu=False, out_dtype=gen.F32, pad=0):
+    """F: B x Cin x H x W storage-typed.  Returns (B x M x Ho x Wo) in fp64 and the raw output tensor."""
+    import torch
+    from helpers import to_device
+    dev = torch.device("cuda:0")
+    B, Cin, H, W = F.shape
+    Ho, Wo = -(-H // stride), -(-W // stride)
+    plan = g.ConvPlan(A, Cin, H, W, kh, kw, stride)
+    assert plan.out_hw == (Ho, Wo)
+    fstride = Cin * H * W + pad
+    Fp = np.zeros((B, fstride), dtype=F.dtype); Fp[:, :Cin * H * W] = F.reshape(B, -1)
+    Fd = to_device(Fp, dtype)
+    ldo = Ho * Wo + pad
+    ostride = M * ldo + pad
+    tdt = {gen.F32: torch.float32, gen.F16: torch.float16, gen.BF16: torch.bfloat16}[out_dtype]
+    out = torch.full((B, ostride), 7.0, dtype=tdt, device=dev)
+    bd = None if bias is None else torch.from_numpy(bias).to(dev)
+    g.conv2d_plan(plan, Fd, B, fstride, bd, relu, out, out_dtype, ldo, ostride, torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    o = out.float().cpu().numpy().astype(np.float64)
+    body = o[:, :M * ldo].reshape(B, M, ldo)
+    if pad:
+        assert (body[:, :, Ho * Wo:] == 7.0).all() and (o[:, M * ldo:] == 7.0).all(), "wrote outside the outputs"
+    return body[:, :, :Ho * Wo].reshape(B, M, Ho, Wo)
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("dtype", [gen.F16, gen.BF16])
+@pytest.mark.parametrize("Cin,H,W,kh,kw,BR,BC,stride,B,pad", [
+    (16, 24, 24, 3, 3, 16, 16, 1, 3, 0),     # a batch at stride 1
+    (16, 12, 20, 3, 3, 4, 16, 1, 2, 3),      # odd image strides: the second image starts 2 bytes off a dword
+    (32, 32, 40, 3, 3, 16, 32, 2, 2, 0),     # stride 2, W a multiple of 8: every second row skipped
+    (8, 15, 13, 3, 3, 16, 8, 2, 2, 1),       # stride 2, odd sizes: all rows walked, odd outputs dropped
+    (32, 7, 7, 1, 1, 16, 32, 2, 3, 0),       # 1 x 1 at stride 2 (a down-sampling shortcut), fewer than 64 positions
+    (4, 56, 56, 5, 5, 16, 20, 2, 1, 0),
+    (24, 9, 16, 3, 1, 16, 24, 2, 2, 5),
+])
+def test_conv_plan_batch_and_stride(dtype, Cin, H, W, kh, kw, BR, BC, stride, B, pad):
+    import paper_2108_11033_amd as g
+    from helpers import pack_workload, TOL
+    M, K = 96, Cin * kh * kw
+    mask = gen.random_mask(M, K, BR, BC, tuple(sorted({0, 1, BR // 2, BR})), tuple(sorted({1, BC // 4 + 1, BC})), seed=740 + Cin)
+    Wt = gen.normal_weights(M, K, dtype, seed=741)
+    F = gen.normal_activations(Cin, B * H * W, dtype, seed=742, relu=True).reshape(Cin, B, H, W).transpose(1, 0, 2, 3).copy()
+    A = pack_workload(g, Wt, dtype, mask)
+    Wm, F64 = _masked(Wt, dtype, mask), gen.storage_to_f64(F, dtype)
+    Yref = conv_ref.conv2d(Wm, F64, kh, kw, stride)
+    S = conv_ref.conv2d(np.abs(Wm), np.abs(F64), kh, kw, stride)
+    Y = _run_plan(g, A, F, dtype, M, kh, kw, stride, pad=pad)
+    assert np.isfinite(Y).all()
+    assert (Y[S == 0] == 0).all()
+    pos = S > 0
+    assert (np.abs(Y - Yref)[pos] / S[pos]).max() <= TOL[dtype]
+    assert np.abs(Y - Yref).max() <= TOL[dtype] * np.abs(Yref).max()
+    if stride == 1:
+        # the planned convolution adds the same terms in the same order as the unplanned one, image by image
+        for b in range(B):
+            Yb = _run(g, A, F[b], dtype, M, Cin, H, W, kh, kw)
+            assert np.array_equal(Yb, Y[b].astype(np.float32))
+
+
+@pytest.mark.gpu
+def test_conv_plan_layer_epilogue_and_refusals():
+    import torch
+    import paper_2108_11033_amd as g
+    from helpers import pack_workload, TOL
+    dtype, Cin, H, W, M, stride, B = gen.F16, 16, 16, 16, 48, 2, 2
+    K = Cin * 9
+    mask = gen.random_mask(M, K, 16, 16, (4, 8), (4, 8), seed=760)
+    Wt = gen.normal_weights(M, K, dtype, seed=761)
+    F = gen.normal_activations(Cin, B * H * W, dtype, seed=762).reshape(Cin, B, H, W).transpose(1, 0, 2, 3).copy()
+    bias = np.random.default_rng(763).standard_normal(M).astype(np.float32) * 0.05
+    A = pack_workload(g, Wt, dtype, mask)
+    Wm, F64 = _masked(Wt, dtype, mask), gen.storage_to_f64(F, dtype)
+    ref = np.maximum(conv_ref.conv2d(Wm, F64, 3, 3, stride) + bias.astype(np.float64)[None, :, None, None], 0.0)
+    for out_dtype, slack in [(gen.F32, 0.0), (gen.F16, 2.0 ** -11), (gen.BF16, 2.0 ** -8)]:
+        Y = _run_plan(g, A, F, dtype, M, 3, 3, stride, bias=bias, relu=True, out_dtype=out_dtype, pad=2)
+        assert (Y >= 0).all()
+        assert np.abs(Y - ref).max() <= (TOL[dtype] + slack) * max(1.0, np.abs(ref).max())
+    with pytest.raises(g.GrimError) as e:
+        g.ConvPlan(A, Cin, H, W, 3, 3, 3)                      # stride 3
+    assert "SHAPE" in str(e.value)
+    with pytest.raises(g.GrimError) as e:
+        g.ConvPlan(A, Cin + 1, H, W, 3, 3, 1)                  # K does not match
+    assert "SHAPE" in str(e.value)
+    plan = g.ConvPlan(A, Cin, H, W, 3, 3, 2)
+    dev = torch.device("cuda:0")
+    Fd = torch.zeros((B, Cin * H * W), dtype=torch.float16, device=dev)
+    out = torch.zeros((B, M * 64), dtype=torch.float32, device=dev)
+    with pytest.raises(g.GrimError) as e:
+        g.conv2d_plan(plan, Fd, B, Cin * H * W, None, False, out, gen.F32, 63, M * 64)       # ldo < Ho * Wo
+    assert "SHAPE" in str(e.value)
+    with pytest.raises(g.GrimError) as e:
+        g.conv2d_plan(plan, Fd, B, Cin * H * W - 1, None, False, out, gen.F32, 64, M * 64)   # images overlap
+    assert "SHAPE" in str(e.value)
+    torch.cuda.synchronize()
+
+
+@pytest.mark.gpu
+def test_conv_plan_on_the_large_nonuniform_workload_as_a_batch_of_images():
+    """The largest SpMM workload is a 3 x 3 convolution of 512 channels on a batch of 8 images of 56 x 56
+    (K = 4608, N = 8 * 3136): as a planned convolution on the feature maps, compared with the reference on sampled
+    output channels, and with the product on the materialised im2col matrix of one image."""
+    import torch
+    import paper_2108_11033_amd as g
+    from helpers import pack_workload, to_device, TOL
+    wl = gen.c5_nonuniform()
+    dtype, M, Cin, H, W, B = wl.dtype, wl.M, 512, 56, 56, 8
+    assert wl.K == Cin * 9 and wl.N == B * H * W
+    A = pack_workload(g, wl.W, dtype, wl.mask)
+    F = gen.normal_activations(Cin, B * H * W, dtype, seed=770, relu=True).reshape(Cin, B, H, W).transpose(1, 0, 2, 3).copy()
+    Y = _run_plan(g, A, F, dtype, M, 3, 3, 1)
+    Wm, F64 = _masked(wl.W, dtype, wl.mask), gen.storage_to_f64(F, dtype)
+    rows = np.array([0, 1, 31, 32, 255, 300, 511])
+    for b in (0, 3, 7):
+        ref = conv_ref.conv_same(Wm[rows], F64[b], 3, 3)
+        S = conv_ref.abs_scale(Wm[rows], F64[b], 3, 3)
+        got = Y[b][rows]
+        pos = S > 0
+        assert (np.abs(got - ref)[pos] / S[pos]).max() <= TOL[dtype]
+        assert (got[~pos] == 0).all()
+    # image 5 through the SpMM entry point on its im2col matrix: the same sums up to the order of additions
+    X = gen.round_to_storage(conv_ref.im2col(F64[5], 3, 3).astype(np.float32), dtype)
+    dev = torch.device("cuda:0")
+    Xd = to_device(X, dtype)
+    Yd = torch.empty((M, H * W), dtype=torch.float32, device=dev)
+    g.spmm(A, Xd, H * W, H * W, Yd, H * W, torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    Ym = Yd.cpu().numpy().astype(np.float64).reshape(M, H, W)
+    assert np.abs(Ym - Y[5]).max() <= TOL[dtype] * np.abs(Ym).max()
 
 
 @pytest.mark.gpu
