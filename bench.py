@@ -384,6 +384,34 @@ def main() -> int:
                                                             "f16", wc.N, stream), 400, 40)
         out["conv"]["bias_relu_fp16_out_us"] = ta * 1e6
         del Os
+        # the same layer through a convolution plan (window starts and taps split when the plan is made)
+        plan_c = g.ConvPlan(Ac, Cin, Hc, Wc, 3, 3, 1)
+        tp, _ = time_launches(torch, lambda i: g.conv2d_plan(plan_c, Fs[i % csets], 1, 0, None, False, Yc[i % csets], "f32",
+                                                             wc.N, 0, stream), 400, 40)
+        out["conv"]["planned_us"] = tp * 1e6
+        # at stride 2 (28 x 28 outputs)
+        plan_s2 = g.ConvPlan(Ac, Cin, Hc, Wc, 3, 3, 2)
+        Ys2 = [torch.empty((wc.M, 28 * 28), dtype=torch.float32, device=dev) for _ in range(csets)]
+        ts2, _ = time_launches(torch, lambda i: g.conv2d_plan(plan_s2, Fs[i % csets], 1, 0, None, False, Ys2[i % csets], "f32",
+                                                              28 * 28, 0, stream), 400, 40)
+        out["conv"]["planned_stride2_us"] = ts2 * 1e6
+        del Ys2, plan_c, plan_s2
+        # the largest SpMM workload as what it stands for: a 3 x 3 convolution of 512 channels on a batch of 8 images of
+        # 56 x 56 (the im2col matrix would be 231 MB; the feature maps are 25.7 MB)
+        w5 = gen.c5_nonuniform()
+        A5 = pack(w5)
+        B5, C5, H5 = 8, 512, 56
+        plan5 = g.ConvPlan(A5, C5, H5, H5, 3, 3, 1)
+        F5 = [dev_tensor(gen.normal_activations(C5, B5 * H5 * H5, w5.dtype, seed=79 + i, relu=True), w5.dtype) for i in range(4)]
+        Y5 = [torch.empty((B5, w5.M, H5 * H5), dtype=torch.float32, device=dev) for _ in range(4)]
+        t5, _ = time_launches(torch, lambda i: g.conv2d_plan(plan5, F5[i % 4], B5, C5 * H5 * H5, None, False, Y5[i % 4], "f32",
+                                                             H5 * H5, w5.M * H5 * H5, stream), 50, 5)
+        v5 = view_dict(A5)
+        b5 = C5 * H5 * H5 * B5 * 2 + w5.M * w5.N * 4 + v5["nnz"] * 2
+        out["conv"]["c5_as_batch_of_8_images"] = {"us": t5 * 1e6, "useful_tflops": 2.0 * v5["nnz"] * w5.N / t5 / 1e12,
+                                                   "algorithmic_mb": b5 / 1e6, "gbs": b5 / t5 / 1e9,
+                                                   "frac_hbm": b5 / t5 / 1e9 / HBM_PEAK_GBS}
+        del F5, Y5, plan5, A5
         # the same layer on a 224 x 224 map (N = 50176): the matrix would be 231 MB
         Hb = 224
         Fb = [dev_tensor(gen.normal_activations(Cin, Hb * Hb, wc.dtype, seed=78 + i, relu=True), wc.dtype) for i in range(2)]
