@@ -271,6 +271,12 @@ grim_status grim_bcr_conv2d_act(const grim_bcr_matrix *A, const void *F_dev, int
  *                               UNSUPPORTED.
  *   grim_bcr_conv_plan_free     frees the plan (not the matrix).
  */
+/* grim_bcr_conv2d_kernel_name -- which kernel grim_bcr_conv2d / _act (batch 1, stride 1) or grim_bcr_conv2d_plan runs for
+ * this layer with densely stored, 16-byte aligned operands ("bcr_conv_wide": the wide-tile kernel, for stride-1 layers of
+ * at least 8 row strips with at least one round of 256 workgroups' worth of positions whose H * W is a multiple of 8; "bcr_conv_gather";
+ * "none": refused).  A static string; launches nothing. */
+const char *grim_bcr_conv2d_kernel_name(const grim_bcr_matrix *A, int32_t Cin, int32_t H, int32_t W, int32_t kh, int32_t kw,
+                                        int32_t batch, int32_t stride);
 typedef struct grim_bcr_conv_plan grim_bcr_conv_plan;
 grim_status grim_bcr_conv_plan_create(const grim_bcr_matrix *A, int32_t Cin, int32_t H, int32_t W, int32_t kh, int32_t kw,
                                       int32_t stride, grim_bcr_conv_plan **out);

@@ -60,7 +60,7 @@ EXPORTS = ["grim_bcr_pack", "grim_bcr_unpack", "grim_bcr_arrays", "grim_bcr_spmm
            "grim_bcr_export_bcrc", "grim_bcrc_arrays", "grim_bcrc_free", "grim_lstm_cell", "grim_bcr_lstm_step", "grim_gru_cell", "grim_bcr_gru_step",
            "grim_bcr_conv2d", "grim_bcr_conv2d_act", "grim_bcr_unpack_layout", "grim_bcr_rnn_step_launches",
            "grim_bcr_rnn_sequence_supported", "grim_bcr_lstm_sequence", "grim_bcr_gru_sequence",
-           "grim_bcr_lstm_sequence_noalloc", "grim_bcr_conv_plan_create", "grim_bcr_conv_plan_free", "grim_bcr_conv2d_plan"]
+           "grim_bcr_lstm_sequence_noalloc", "grim_bcr_conv_plan_create", "grim_bcr_conv_plan_free", "grim_bcr_conv2d_plan", "grim_bcr_conv2d_kernel_name"]
 
 
 def lib_path() -> str:
@@ -113,6 +113,7 @@ def load_library():
     lib.grim_bcr_lstm_sequence.argtypes = [p, p, i64, i32, p, p, p, p, i64, p, i64, p, ctypes.c_uint32, p]
     lib.grim_bcr_conv_plan_create.argtypes = [p, i32, i32, i32, i32, i32, i32, ctypes.POINTER(p)]
     lib.grim_bcr_conv_plan_free.argtypes = [p]
+    lib.grim_bcr_conv2d_kernel_name.argtypes = [p, i32, i32, i32, i32, i32, i32, i32]
     lib.grim_bcr_conv2d_plan.argtypes = [p, p, i32, i64, p, i32, p, i32, i64, i64, p]
     lib.grim_bcr_lstm_sequence_noalloc.argtypes = [p, p, i64, i32, p, p, p, p, i64, p, i64, p, ctypes.c_uint32, p]
     lib.grim_bcr_gru_sequence.argtypes = [p, p, p, i64, i32, p, p, p, p, p, i64, p, i64, p, ctypes.c_uint32, p]
@@ -120,6 +121,7 @@ def load_library():
         getattr(lib, name).restype = i32
     lib.grim_status_str.restype = ctypes.c_char_p
     lib.grim_bcr_spmm_kernel_name.restype = ctypes.c_char_p
+    lib.grim_bcr_conv2d_kernel_name.restype = ctypes.c_char_p
     lib.grim_bcr_free.restype = None
     lib.grim_bcrc_free.restype = None
     lib.grim_bcr_group_free.restype = None
@@ -316,6 +318,11 @@ class ConvPlan:
         h, self.handle = getattr(self, "handle", None), None
         if h:
             self._lib.grim_bcr_conv_plan_free(h)
+
+
+def conv2d_kernel_name(A: "BcrMatrix", Cin: int, H: int, W: int, kh: int, kw: int, batch: int = 1, stride: int = 1) -> str:
+    """grim_bcr_conv2d_kernel_name: the kernel a convolution of this geometry runs on."""
+    return A._lib.grim_bcr_conv2d_kernel_name(A.handle, Cin, H, W, kh, kw, batch, stride).decode()
 
 
 def conv2d_plan(plan: ConvPlan, F, batch: int, f_image_stride: int, bias, relu: bool, out, out_dtype, ldo: int,

@@ -14,7 +14,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libgrim_bcr.so")
-SOURCES = ["bcr_pack.cpp", "bcr_spmm_fma.hip", "bcr_spmm_mma.hip", "bcr_spmm_wide.hip", "bcr_spmm_gather.hip", "bcr_conv.hip", "bcr_spmv.hip", "bcr_rnn_seq.hip",
+SOURCES = ["bcr_pack.cpp", "bcr_spmm_fma.hip", "bcr_spmm_mma.hip", "bcr_spmm_wide.hip", "bcr_spmm_gather.hip", "bcr_conv.hip", "bcr_conv_wide.hip", "bcr_spmv.hip", "bcr_rnn_seq.hip",
            "lstm_cell.hip"]
 NOISE = "is not a recognized feature for this target"
 

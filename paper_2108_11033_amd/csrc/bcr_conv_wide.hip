@@ -1,0 +1,124 @@
+// Convolution on the wide-tile staged kernel, the im2col matrix never formed (Section 3.1: CONV = filter matrix x
+// im2col matrix; Section 4.5: that matrix need not exist in memory).  For layers with many output positions
+// (large maps, batches): a workgroup owns a tile of 96-192 consecutive positions of the batch and 16 row strips; its
+// fetching waves build the K rows of the tile -- row k is channel k / (kh kw) of the feature map shifted by tap
+// k % (kh kw), zero outside the image -- in LDS with one 16-byte load per 8 positions, and the multiplying waves
+// run exactly as for a matrix X in memory.  Every pixel is fetched kh * kw times, but from the caches: HBM sees the
+// feature maps once instead of a matrix kh * kw times their size.
+// Launches: whole rounds of 256 workgroups at the widest tile, then the remaining positions at the narrowest one
+// (a partial round of wide tiles would cost as much as a full one).  Small layers stay on the row-gathering
+// convolution kernel.
+#include <atomic>
+
+#include "spmm_wide_kernel.hpp"
+
+namespace grim {
+
+// tile widths compiled for the convolution: the widest for the whole rounds, 32 columns for what is left
+constexpr int kConvWideRestTile = 32;
+
+static size_t conv_wide_lds(const grim_bcr_matrix *A, int tn, int KK) {
+    return 2 * (size_t)wide_stage_bytes(A->mmaw.chunk_rows, tn, A->mmaw.amax[2]) + (size_t)(KK + 1) * (tn / 8) * 16;
+}
+
+// the widest compiled tile whose records fit the fetching waves' registers and whose stages fit LDS; 0: none
+static int conv_wide_main_tile(const grim_bcr_matrix *A, int KK) {
+    for (int tn : {192, 128, 96}) {
+        if (A->BR == 32 ? tn != 96 : tn == 96) continue;
+        if ((int64_t)A->mmaw.amax[2] <= (int64_t)wide_sru(tn) * kWideFetchThreads && conv_wide_lds(A, tn, KK) <= 160 * 1024) return tn;
+    }
+    return 0;
+}
+
+// Does the layer qualify, and is it large enough for at least one whole round at the widest tile?
+bool conv_wide_applies(const grim_bcr_matrix *A, const void *F, int32_t Cin, int32_t H, int32_t W, int32_t kh, int32_t kw,
+                       int32_t batch, int64_t f_img_stride, const void *Y, int32_t odt, int64_t ldy, int64_t y_img_stride) {
+    if (!A->mmaw.present || A->dtype == GRIM_F32 || (A->BR != 16 && A->BR != 32)) return false;
+    if (A->nbr < 8) return false;      // with few strips most multiplying waves idle: the row-gathering kernel is faster
+    if (A->mmaw.chunk_rows > wide_max_chunk_rows(A->BR)) return false;
+    const int64_t HW = (int64_t)H * W, N = HW * batch;
+    const int KK = kh * kw;
+    if (HW % 8 != 0 || KK > 255 || A->K * (int64_t)KK >= (int64_t(1) << 31) || HW >= (1 << 24)) return false;
+    const int kw_magic = (256 + kw - 1) / kw;
+    for (int tap = 0; tap < KK; ++tap)
+        if (((tap * kw_magic) >> 8) != tap / kw) return false;
+    const int64_t f_total = (batch - 1) * f_img_stride + (int64_t)Cin * HW;
+    if (f_total < 8 || f_total * 2 >= (int64_t(1) << 31) || reinterpret_cast<uintptr_t>(F) % 2 != 0) return false;
+    // a lane of the 16-row form stores 4 consecutive outputs at once
+    if (A->BR == 16 && odt == GRIM_F32 &&
+        (reinterpret_cast<uintptr_t>(Y) % 16 != 0 || ldy % 4 != 0 || (batch > 1 && y_img_stride % 4 != 0))) return false;
+    const int tn = conv_wide_main_tile(A, KK);
+    if (!tn) return false;
+    const int64_t groups = (A->nbr + kWideStrips - 1) / kWideStrips;
+    const int64_t per_round = 256 / groups;
+    return per_round > 0 && N / tn >= per_round;
+}
+
+template <bool BF16, int BR, int NT>
+static grim_status launch_conv_wide_inst(const WideParams &p, size_t lds, int64_t nwg, hipStream_t stream) {
+    auto kern = bcr_spmm_wide<BF16, BR, NT, true>;
+    static std::atomic<bool> attr_done{false};
+    if (lds > 64 * 1024 && !attr_done) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess) {
+            (void)hipGetLastError();
+            return GRIM_ERR_DEVICE;
+        }
+        attr_done = true;
+    }
+    hipLaunchKernelGGL(kern, dim3((unsigned)nwg), dim3(kWideThreads), lds, stream, p);
+    return hipGetLastError() == hipSuccess ? GRIM_OK : GRIM_ERR_DEVICE;
+}
+
+// positions [n_begin, n_end) of the batch in tiles of tn (n_end - n_begin >= tn, both multiples of 8)
+static grim_status conv_wide_range(const grim_bcr_matrix *A, WideParams p, int tn, int64_t n_begin, int64_t n_end, hipStream_t stream) {
+    p.n_begin = n_begin;
+    p.N = n_end;
+    p.ntiles = (int32_t)((n_end - n_begin + tn - 1) / tn);
+    const int64_t nwg = ((int64_t)p.ntiles + 15) / 16 * 16 * p.ngroups;
+    if (nwg > 0x7fffffff) return GRIM_ERR_SHAPE;
+    const size_t lds = conv_wide_lds(A, tn, p.KK);
+    const bool bf = A->dtype == GRIM_BF16;
+    if (A->BR == 16) {
+        if (tn == 192) return bf ? launch_conv_wide_inst<true, 16, 12>(p, lds, nwg, stream) : launch_conv_wide_inst<false, 16, 12>(p, lds, nwg, stream);
+        if (tn == 128) return bf ? launch_conv_wide_inst<true, 16, 8>(p, lds, nwg, stream) : launch_conv_wide_inst<false, 16, 8>(p, lds, nwg, stream);
+        return bf ? launch_conv_wide_inst<true, 16, 2>(p, lds, nwg, stream) : launch_conv_wide_inst<false, 16, 2>(p, lds, nwg, stream);
+    }
+    if (tn == 96) return bf ? launch_conv_wide_inst<true, 32, 3>(p, lds, nwg, stream) : launch_conv_wide_inst<false, 32, 3>(p, lds, nwg, stream);
+    return bf ? launch_conv_wide_inst<true, 32, 1>(p, lds, nwg, stream) : launch_conv_wide_inst<false, 32, 1>(p, lds, nwg, stream);
+}
+
+grim_status launch_conv_wide(const grim_bcr_matrix *A, const void *F, int32_t Cin, int32_t H, int32_t W, int32_t kh,
+                             int32_t kw, int32_t batch, int64_t f_img_stride, const float *bias, int32_t relu, void *Y,
+                             int32_t odt, int64_t ldy, int64_t y_img_stride, hipStream_t stream) {
+    if (!conv_wide_applies(A, F, Cin, H, W, kh, kw, batch, f_img_stride, Y, odt, ldy, y_img_stride)) return GRIM_ERR_UNSUPPORTED;
+    const MmaLayout &L = A->mmaw;
+    const int64_t HW = (int64_t)H * W, N = HW * batch;
+    WideParams p{};
+    p.recs = L.d_recs; p.cptr = L.d_cptr; p.bptr = L.d_bptr;
+    p.strip_order = A->dev.strip_order;
+    p.X = nullptr;
+    p.Y = static_cast<float *>(Y);
+    p.ldx = 0; p.ldy = ldy;
+    p.K = (int32_t)A->K; p.nbr = (int32_t)A->nbr; p.nchunks = L.nchunks; p.chunk_rows = L.chunk_rows;
+    p.ngroups = (int32_t)((A->nbr + kWideStrips - 1) / kWideStrips);
+    p.amax = L.amax[2];
+    p.F = static_cast<const unsigned short *>(F);
+    p.H = H; p.W = W; p.HW = (int32_t)HW; p.kh = kh; p.kw = kw; p.KK = kh * kw;
+    p.kk_magic = (int32_t)(uint32_t)(((uint64_t(1) << 31) + p.KK - 1) / p.KK);
+    p.kw_magic = (256 + kw - 1) / kw;
+    p.f_img_stride = (int32_t)(batch > 1 ? f_img_stride : 0);
+    p.f_total = (int32_t)((batch - 1) * (int64_t)p.f_img_stride + (int64_t)Cin * HW);
+    p.y_img_stride = batch > 1 ? y_img_stride : 0;
+    p.bias = bias; p.relu = relu; p.odt = odt;
+    const int tn = conv_wide_main_tile(A, p.KK);
+    const int64_t per_round = 256 / p.ngroups;
+    const int64_t n_main = N / tn / per_round * per_round * tn;
+    grim_status st = conv_wide_range(A, p, tn, 0, n_main, stream);
+    if (st != GRIM_OK || n_main == N) return st;
+    // what is left, in narrow tiles; fewer than one tile's worth: the last 32 positions, of which the first few are
+    // computed twice (the same sums in the same order: the overlap writes the same bits)
+    const int64_t rest0 = N - n_main >= kConvWideRestTile ? n_main : N - kConvWideRestTile;
+    return conv_wide_range(A, p, kConvWideRestTile, rest0, N, stream);
+}
+
+}  // namespace grim

@@ -219,6 +219,13 @@ grim_status launch_conv_gather(const grim_bcr_matrix *A, const void *F, int32_t 
                                hipStream_t stream, int32_t batch = 1, int32_t stride = 1, int64_t f_img_stride = 0,
                                int64_t y_img_stride = 0, const uint32_t *plan = nullptr);
 uint32_t conv_plan_word(uint32_t k, int32_t H, int32_t W, int32_t kh, int32_t kw);
+// stride-1 convolution of layers with many positions on the wide-tile kernel (whole rounds of workgroups plus a narrow
+// rest); GRIM_ERR_UNSUPPORTED when the layer is too small or does not qualify: the caller then takes the kernel above
+bool conv_wide_applies(const grim_bcr_matrix *A, const void *F, int32_t Cin, int32_t H, int32_t W, int32_t kh, int32_t kw,
+                       int32_t batch, int64_t f_img_stride, const void *Y, int32_t odt, int64_t ldy, int64_t y_img_stride);
+grim_status launch_conv_wide(const grim_bcr_matrix *A, const void *F, int32_t Cin, int32_t H, int32_t W, int32_t kh,
+                             int32_t kw, int32_t batch, int64_t f_img_stride, const float *bias, int32_t relu, void *Y,
+                             int32_t odt, int64_t ldy, int64_t y_img_stride, hipStream_t stream);
 // cost estimates (bytes through one compute unit) used to choose between the two matrix-core kernels
 double gather_cost(const grim_bcr_matrix *A, int64_t N);
 double mma_best_shape(const grim_bcr_matrix *A, int64_t N, int32_t tile_n, int32_t strips_per_wg, int *tn_out, int *g_out);

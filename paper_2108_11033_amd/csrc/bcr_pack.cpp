@@ -860,6 +860,9 @@ static grim_status conv_call(const grim_bcr_matrix *A, const void *F_dev, int32_
     if (!A->on_device) return GRIM_ERR_DEVICE;
     int dev = -1;
     if (hipGetDevice(&dev) != hipSuccess || dev != A->device) { (void)hipGetLastError(); return GRIM_ERR_DEVICE; }
+    grim_status st = launch_conv_wide(A, F_dev, Cin, H, W, kh, kw, 1, 0, bias_dev, relu ? 1 : 0, out_dev, odt, ldo, 0,
+                                      static_cast<hipStream_t>(hip_stream));
+    if (st != GRIM_ERR_UNSUPPORTED) return st;
     return launch_conv_gather(A, F_dev, Cin, H, W, kh, kw, bias_dev, relu ? 1 : 0, out_dev, odt, ldo,
                               static_cast<hipStream_t>(hip_stream));
 }
@@ -928,9 +931,27 @@ grim_status grim_bcr_conv2d_plan(const grim_bcr_conv_plan *P, const void *F_dev,
     if (out_dt != GRIM_F32 && out_dt != GRIM_F16 && out_dt != GRIM_BF16) return GRIM_ERR_DTYPE;
     int dev = -1;
     if (hipGetDevice(&dev) != hipSuccess || dev != P->device) { (void)hipGetLastError(); return GRIM_ERR_DEVICE; }
+    if (P->stride == 1) {
+        const grim_status st = launch_conv_wide(P->A, F_dev, P->Cin, P->H, P->W, P->kh, P->kw, batch, f_image_stride, bias_dev,
+                                                relu ? 1 : 0, out_dev, (int32_t)out_dt, ldo, out_image_stride,
+                                                static_cast<hipStream_t>(hip_stream));
+        if (st != GRIM_ERR_UNSUPPORTED) return st;
+    }
     return launch_conv_gather(P->A, F_dev, P->Cin, P->H, P->W, P->kh, P->kw, bias_dev, relu ? 1 : 0, out_dev, (int32_t)out_dt,
                               ldo, static_cast<hipStream_t>(hip_stream), batch, P->stride, f_image_stride, out_image_stride,
                               P->d_words);
+}
+
+const char *grim_bcr_conv2d_kernel_name(const grim_bcr_matrix *A, int32_t Cin, int32_t H, int32_t W, int32_t kh, int32_t kw,
+                                        int32_t batch, int32_t stride) {
+    if (!A || !A->on_device || Cin < 1 || H < 1 || W < 1 || kh < 1 || kw < 1 || batch < 1 || (int64_t)Cin * kh * kw != A->K)
+        return "none";
+    // operands as tests and benchmarks pass them: 16-byte aligned, dense images one after the other
+    const int64_t HW = (int64_t)H * W;
+    void *aligned = reinterpret_cast<void *>(uintptr_t(256));
+    if (stride == 1 && conv_wide_applies(A, aligned, Cin, H, W, kh, kw, batch, Cin * HW, aligned, GRIM_F32, HW, A->M * HW))
+        return "bcr_conv_wide";
+    return A->gather.present ? "bcr_conv_gather" : "none";
 }
 
 grim_status grim_lstm_cell(const float *gates_dev, int64_t ldg, const float *bias_dev, float *c_dev, int64_t ldc,

@@ -535,6 +535,59 @@ def test_conv_plan_on_the_large_nonuniform_workload_as_a_batch_of_images():
 
 
 @pytest.mark.gpu
+@pytest.mark.parametrize("dtype,M,Cin,H,W,kh,kw,BR,BC,B,epi", [
+    (gen.F16, 128, 8, 224, 224, 3, 3, 16, 24, 1, None),       # 8 strips, 192-column tiles: 256 + a rest of 1024 positions
+    (gen.BF16, 256, 16, 112, 112, 3, 3, 32, 16, 2, None),     # 32-row blocks, 96-column tiles that straddle the two images
+    (gen.F16, 272, 16, 160, 160, 5, 5, 16, 20, 1, gen.F16),   # 17 strips = two groups; 5 x 5; bias + rectifier + fp16 out
+    (gen.BF16, 128, 4, 3073, 16, 3, 3, 16, 12, 1, gen.BF16),  # 16 positions past the whole round: the rest overlaps it
+    (gen.F16, 256, 32, 96, 88, 1, 1, 32, 32, 3, gen.F32),     # 1 x 1, three images
+])
+def test_conv_on_the_wide_tile_kernel(dtype, M, Cin, H, W, kh, kw, BR, BC, B, epi):
+    """Layers with at least one round of 256 workgroups' worth of positions run on the wide-tile kernel with the
+    fetching waves building the im2col rows from the feature maps; compared with the reference in full."""
+    import paper_2108_11033_amd as g
+    from helpers import pack_workload, TOL
+    K = Cin * kh * kw
+    mask = gen.random_mask(M, K, BR, BC, tuple(sorted({0, 1, BR // 2, BR})), tuple(sorted({1, BC // 4 + 1, BC})), seed=780 + M)
+    Wt = gen.normal_weights(M, K, dtype, seed=781)
+    F = gen.normal_activations(Cin, B * H * W, dtype, seed=782, relu=True).reshape(Cin, B, H, W).transpose(1, 0, 2, 3).copy()
+    A = pack_workload(g, Wt, dtype, mask)
+    assert g.conv2d_kernel_name(A, Cin, H, W, kh, kw, B, 1) == "bcr_conv_wide"
+    assert g.conv2d_kernel_name(A, Cin, H, W, kh, kw, B, 2) == "bcr_conv_gather"
+    Wm, F64 = _masked(Wt, dtype, mask), gen.storage_to_f64(F, dtype)
+    Yref = conv_ref.conv2d(Wm, F64, kh, kw, 1)
+    S = conv_ref.conv2d(np.abs(Wm), np.abs(F64), kh, kw, 1)
+    if epi is None:
+        Y = _run_plan(g, A, F, dtype, M, kh, kw, 1)
+        assert np.isfinite(Y).all()
+        assert (Y[S == 0] == 0).all()
+        pos = S > 0
+        assert (np.abs(Y - Yref)[pos] / S[pos]).max() <= TOL[dtype]
+        assert np.abs(Y - Yref).max() <= TOL[dtype] * np.abs(Yref).max()
+    else:
+        bias = (0.05 * np.random.default_rng(783).standard_normal(M)).astype(np.float32)
+        ref = np.maximum(Yref + bias.astype(np.float64)[None, :, None, None], 0.0)
+        Y = _run_plan(g, A, F, dtype, M, kh, kw, 1, bias=bias, relu=True, out_dtype=epi, pad=4)
+        slack = {gen.F32: 0.0, gen.F16: 2.0 ** -11, gen.BF16: 2.0 ** -8}[epi]
+        assert (Y >= 0).all()
+        assert np.abs(Y - ref).max() <= (TOL[dtype] + slack) * max(1.0, np.abs(ref).max())
+    if B == 1:
+        # the unplanned entry point takes the same route and writes the same bits
+        import torch
+        from helpers import to_device
+        dev = torch.device("cuda:0")
+        Fd = to_device(np.ascontiguousarray(F[0].reshape(Cin, H * W)), dtype)
+        Yd = torch.full((M, H * W), float("nan"), dtype=torch.float32, device=dev)
+        g.conv2d(A, Fd, Cin, H, W, kh, kw, Yd, H * W, torch.cuda.current_stream())
+        torch.cuda.synchronize()
+        Y1 = Yd.cpu().numpy().reshape(M, H, W)
+        assert np.isfinite(Y1).all()
+        assert np.abs(Y1 - Yref[0]).max() <= TOL[dtype] * np.abs(Yref).max()
+        if epi is None:
+            assert np.array_equal(Y1, Y[0].astype(np.float32))
+
+
+@pytest.mark.gpu
 def test_conv_refusals():
     import torch
     import paper_2108_11033_amd as g
