@@ -316,13 +316,29 @@ def main() -> int:
                             batch, None, 0, stream)
             tL, _ = time_launches(torch, lstm, 1000, 50)
             extra[f"c3_b{batch}"]["lstm_step_us"] = tL * 1e6
+            extra[f"c3_b{batch}"]["lstm_step_launches"] = g.rnn_step_launches(mats[0], None, batch)
+            if batch == 1 and g.rnn_sequence_supported(mats[0]):
+                # T steps in one launch (weights stay in registers, h passes between workgroups through tagged words)
+                Ih = w3.K - Hh
+                status = torch.zeros((1,), dtype=torch.int32, device=dev)
+                for T in (16, 256):
+                    xs_t = dev_tensor(gen.normal_activations(Ih, T, w3.dtype, seed=11), w3.dtype).t().contiguous()
+                    h0 = torch.zeros((Hh,), dtype=xs_t.dtype, device=dev)
+                    cs = torch.zeros((Hh,), dtype=torch.float32, device=dev)
+                    hs = torch.empty((T, Hh), dtype=xs_t.dtype, device=dev)
+                    tS, _ = time_launches(torch, lambda i: g.lstm_sequence(mats[0], xs_t, Ih, T, None, h0, cs, hs, Hh, None, 0,
+                                                                           status, 0, stream), 10, 2)
+                    torch.cuda.synchronize()
+                    assert int(status.item()) == 0
+                    extra[f"c3_b{batch}"][f"lstm_sequence_T{T}_us_per_step"] = tS * 1e6 / T
             del mats, xs, ys
-        # ---- a GRU layer of the paper's size (Section 6.1: hidden 1024, both gate matrices 3072 x 1024, pruned 10x,
-        #      32 x 32 blocks): one step = two products + the cell, at batch 1, 8 and 32 (Section 6.3 quotes batch 32)
+        # ---- a GRU layer of the paper's size (Section 6.1: hidden 1024, both gate matrices 3072 x 1024, 32 x 32 blocks
+        #      keeping 8 rows x 12 columns = pruned 10.7x, the rate of Section 6.4): one step = two products + the cell,
+        #      at batch 1, 8 and 32 (Section 6.3 quotes batch 32)
         from paper_2108_11033_amd import tune as tune_mod
         Hg = 1024
-        Wgi, _, mgi = tune_mod.synthesize(3 * Hg, Hg, 1, 32, 32, 10.0, "f16", seed=1)
-        Wgh, _, mgh = tune_mod.synthesize(3 * Hg, Hg, 1, 32, 32, 10.0, "f16", seed=2)
+        Wgi, _, mgi = tune_mod.synthesize(3 * Hg, Hg, 1, 32, 32, 1024 / 96, "f16", seed=1, row_frac=0.25)
+        Wgh, _, mgh = tune_mod.synthesize(3 * Hg, Hg, 1, 32, 32, 1024 / 96, "f16", seed=2, row_frac=0.25)
         Agi = g.pack(Wgi, "f16", 32, 32, mgi.row_ptr, mgi.row_idx, mgi.col_ptr, mgi.col_idx)
         Agh = g.pack(Wgh, "f16", 32, 32, mgh.row_ptr, mgh.row_idx, mgh.col_ptr, mgh.col_idx)
         gru = {}
@@ -335,6 +351,27 @@ def main() -> int:
             tG, _ = time_launches(torch, lambda i: g.gru_step(Agi, Agh, xg, batch, hb, batch, batch, gi_, batch, gh_, batch,
                                                               None, None, h32, batch, hb, batch, stream), 500, 50)
             gru[f"b{batch}_step_us"] = tG * 1e6
+            gru[f"b{batch}_step_launches"] = g.rnn_step_launches(Agi, Agh, batch)
+            if batch == 1:
+                # new state into a second buffer: the step is then one launch (the cell in the products' epilogue)
+                hb2 = torch.zeros((Hg, batch), dtype=torch.float16, device=dev)
+                hbs = [hb, hb2]
+                tG1, _ = time_launches(torch, lambda i: g.gru_step(Agi, Agh, xg, batch, hbs[i % 2], batch, batch, gi_, batch, gh_,
+                                                                   batch, None, None, h32, batch, hbs[(i + 1) % 2], batch, stream),
+                                       500, 50)
+                gru["b1_step_two_buffers_us"] = tG1 * 1e6
+        if g.rnn_sequence_supported(Agi, Agh):
+            status = torch.zeros((1,), dtype=torch.int32, device=dev)
+            for T in (16, 256):
+                xs_t = dev_tensor(gen.normal_activations(Hg, T, "f16", seed=12), "f16").t().contiguous()
+                h0 = torch.zeros((Hg,), dtype=torch.float16, device=dev)
+                hst = torch.zeros((Hg,), dtype=torch.float32, device=dev)
+                hs = torch.empty((T, Hg), dtype=torch.float16, device=dev)
+                tS, _ = time_launches(torch, lambda i: g.gru_sequence(Agi, Agh, xs_t, Hg, T, None, None, h0, hst, hs, Hg, None, 0,
+                                                                      status, 0, stream), 10, 2)
+                torch.cuda.synchronize()
+                assert int(status.item()) == 0
+                gru[f"sequence_T{T}_us_per_step"] = tS * 1e6 / T
         gru["kernel_b32"] = g.spmm_kernel_name(Agi, xg, 32, 32)
         # the three GRU matrix sizes the paper counts register loads on (Section 6.4), pruned 10.7x: one product each
         shapes = {}

@@ -316,6 +316,20 @@ __global__ void __launch_bounds__(exact_waves(CELL) * 64) bcr_spmv_wave_exact(Ge
         }
         npend = 0;
     };
+    // the cell's operands (previous state, biases) are asked for first: their latency runs under the whole product
+    float cell_st = 0.f, cell_b[6] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    if constexpr (CELL != 0) {
+        if (tid < p.BR) {
+            const RnnCell &cl = p.cell;
+            const int64_t H = cl.H, j = (int64_t)blockIdx.x * p.BR + tid;
+            cell_st = cl.c[j * cl.ldc];
+#pragma unroll
+            for (int k = 0; k < (CELL == 1 ? 4 : 3); ++k) {
+                if (cl.bias) cell_b[k] = cl.bias[k * H + j];
+                if (CELL == 2 && cl.bias2) cell_b[3 + k] = cl.bias2[k * H + j];
+            }
+        }
+    }
     // x -> LDS, once per workgroup.  Its loads go out first and the first item's right behind
     // them, so that the weights are already on their way while x is parked.
     Item cur, nxt;
@@ -510,10 +524,8 @@ __global__ void __launch_bounds__(exact_waves(CELL) * 64) bcr_spmv_wave_exact(Ge
             if constexpr (CELL == 1) {
                 const float pi = gl[tid], pf = gl[32 + tid], pg = gl[64 + tid], po = gl[96 + tid];
                 y0[j * p.ldy] = pi; y0[(H + j) * p.ldy] = pf; y0[(2 * H + j) * p.ldy] = pg; y0[(3 * H + j) * p.ldy] = po;
-                const float bi = cl.bias ? cl.bias[j] : 0.f, bf = cl.bias ? cl.bias[H + j] : 0.f;
-                const float bg = cl.bias ? cl.bias[2 * H + j] : 0.f, bo = cl.bias ? cl.bias[3 * H + j] : 0.f;
-                float c = cl.c[j * cl.ldc];
-                const float h = lstm_cell_apply(pi + bi, pf + bf, pg + bg, po + bo, c);
+                float c = cell_st;
+                const float h = lstm_cell_apply(pi + cell_b[0], pf + cell_b[1], pg + cell_b[2], po + cell_b[3], c);
                 cl.c[j * cl.ldc] = c;
                 if (cl.h32) cl.h32[j * cl.ldh32] = h;
                 if (cl.h) rnn_store_h(cl.h, cl.hdt, j * cl.ldh, h);
@@ -525,10 +537,10 @@ __global__ void __launch_bounds__(exact_waves(CELL) * 64) bcr_spmv_wave_exact(Ge
                     const float vi = gl[k * 32 + tid], vh = gl[(3 + k) * 32 + tid];
                     y0[(k * H + j) * p.ldy] = vi;
                     y1[(k * H + j) * p.ldy] = vh;
-                    pi[k] = vi + (cl.bias ? cl.bias[k * H + j] : 0.f);
-                    ph[k] = vh + (cl.bias2 ? cl.bias2[k * H + j] : 0.f);
+                    pi[k] = vi + cell_b[k];
+                    ph[k] = vh + cell_b[3 + k];
                 }
-                const float h = gru_cell_apply(pi[0], pi[1], pi[2], ph[0], ph[1], ph[2], cl.c[j * cl.ldc]);
+                const float h = gru_cell_apply(pi[0], pi[1], pi[2], ph[0], ph[1], ph[2], cell_st);
                 cl.c[j * cl.ldc] = h;
                 if (cl.h) rnn_store_h(cl.h, cl.hdt, j * cl.ldh, h);
             }
