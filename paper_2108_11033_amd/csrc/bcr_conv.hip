@@ -67,9 +67,13 @@ constexpr int kConvTableBytes = (kConvMaxTaps + 1) * 8 * 16;   // validity masks
 
 // SOLO, EIGHT: as in the row-gathering kernel -- a (tile, strip) pair per wave for strips of a few steps, eight
 // waves per strip for long strips with few workgroups
-template <bool BF16, bool SOLO, int LONGW>   // LONGW: 0, or the waves that split a long strip's steps (8 or 12)
+// MODE: 0 = row numbers split in the kernel, stride 1; 1 = a plan's words, stride 1; 2 = a plan's words, stride 2.
+// Compile-time, so that the plain form carries none of the others' state in registers.
+template <bool BF16, bool SOLO, int LONGW, int MODE>   // LONGW: 0, or the waves that split a long strip's steps (8 or 12)
 __global__ void __launch_bounds__(LONGW ? LONGW * 64 : 256, LONGW ? 1024 / (LONGW * 64) : 4) bcr_conv_gather(ConvParams p) {
     constexpr bool EIGHT = LONGW > 0;
+    constexpr bool PLAN = MODE != 0, S2 = MODE == 2;
+    const int hmul = S2 ? p.hmul : 1;
     constexpr int NT = 4, TN = 64, PITCH = 128, CPR = 8;
     constexpr int SB = 3;                        // steps a wave has in flight
     constexpr int NWV = EIGHT ? LONGW : 4;       // waves of the workgroup
@@ -78,8 +82,10 @@ __global__ void __launch_bounds__(LONGW ? LONGW * 64 : 256, LONGW ? 1024 / (LONG
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     int tile, unit;
     if (!xcd_map_at(p.map, blockIdx.x, p.ntiles, &tile, &unit)) return;
-    const int img = tile / p.tiles_per_img;
-    tile -= img * p.tiles_per_img;
+    // (a division by a run-time value is done on the vector ALU even for uniform operands; without the
+    // readfirstlane everything derived from the image and tile numbers would live in vector registers)
+    const int img = __builtin_amdgcn_readfirstlane(tile / p.tiles_per_img);
+    tile = __builtin_amdgcn_readfirstlane(tile - img * p.tiles_per_img);
     const unsigned short *Fimg = p.F + (int64_t)img * p.f_img_stride;
     const int t_raw = SOLO ? unit * 4 + wave : unit;
     const bool active = t_raw < p.nbr;           // SOLO: the last workgroup of a tile may have idle waves
@@ -97,7 +103,7 @@ __global__ void __launch_bounds__(LONGW ? LONGW * 64 : 256, LONGW ? 1024 / (LONG
     // so that their latency runs under it.
     const int kgroup0 = lane >> 4;
     const uint2 *desc2 = reinterpret_cast<const uint2 *>(p.desc);
-    const uint32_t *slots = p.plan ? p.plan : p.rows;
+    const uint32_t *slots = PLAN ? p.plan : p.rows;
     unsigned int npk[SB];
     uint2 ndsc[SB];
 #pragma unroll
@@ -122,8 +128,8 @@ __global__ void __launch_bounds__(LONGW ? LONGW * 64 : 256, LONGW ? 1024 / (LONG
         if (tap < p.KK) {
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
-                int h = h0 * p.hmul, w = w0 + j;
-                while (w >= p.W) { w -= p.W; h += p.hmul; }  // once at most for W >= 8 (positions past the last, of a small map: h >= H, never stored)
+                int h = h0 * hmul, w = w0 + j;
+                while (w >= p.W) { w -= p.W; h += hmul; }  // once at most for W >= 8 (positions past the last, of a small map: h >= H, never stored)
                 const bool ok = h + dr >= 0 && h + dr < p.H && w + dq >= 0 && w + dq < p.W;
                 m[j >> 1] |= ok ? (j & 1 ? 0xffff0000u : 0x0000ffffu) : 0u;
             }
@@ -159,15 +165,18 @@ __global__ void __launch_bounds__(LONGW ? LONGW * 64 : 256, LONGW ? 1024 / (LONG
     // second row skipped (2 * row * W + column)
     auto pos_off = [&](int cc) {
         const int nb = n0 + cc * 8;
-        return p.hmul == 1 ? nb : nb + (nb / p.W) * p.W;
+        return hmul == 1 ? nb : nb + (nb / p.W) * p.W;
     };
-    const int cofs = pos_off(c) - (1 << 25);     // this lane's piece, and the bias of the packed form
-    const int off7 = pos_off(7);
+    // Stride 1: the tile's first position goes into the (uniform) window start of a k slot and a lane adds only its
+    // piece's 8 c -- this split, not the sum formed per lane, is what keeps the fetch loop within its registers.
+    const int tile_pos = S2 ? pos_off(0) : n0;
+    const int cofs = (S2 ? pos_off(c) - tile_pos : c * 8) - (1 << 25);     // this lane's piece, and the bias of the packed form
+    const int off7 = S2 ? pos_off(7) - tile_pos : 56;                       // piece 7 relative to tile_pos
     // Windows that start at an odd element are fetched one element early and shifted (see below), which takes the
     // next piece to continue this one in memory: true unless rows are skipped
-    const bool use_shift = p.hmul == 1;
+    const bool use_shift = hmul == 1;
     // can a window of this tile start before the feature map or end behind it?  (only in the first / last channel)
-    const bool tile_edge = pos_off(0) < centre || off7 + 8 + centre > HW;
+    const bool tile_edge = pos_off(0) < centre || pos_off(7) + 8 + centre > HW;
     for (int s = s_beg; s < s_end; s += SB) {
         const int nb = s_end - s < SB ? s_end - s : SB;
         // Lane j takes k slot j % 32 of every step of the batch: it splits the slot's row number once into
@@ -204,10 +213,11 @@ __global__ void __launch_bounds__(LONGW ? LONGW * 64 : 256, LONGW ? 1024 / (LONG
 #pragma unroll
             for (int u = 0; u < SB; ++u) {
                 bool is_pad;
-                int eb;                          // window start for position 0 of the image
-                if (p.plan) {                    // (uniform) already split when the plan was made
+                int eb;                          // window start for the tile's first position (stride 2: for position 0)
+                if constexpr (PLAN) {            // already split when the plan was made
                     is_pad = (int)(pk[u] >> 27) == p.KK;
-                    eb = (int)(pk[u] & 0x7ffffffu) - (1 << 25);
+                    eb = (int)(pk[u] & 0x7ffffffu) - (1 << 25) + tile_pos;
+                    pk[u] = (pk[u] & 0xf8000000u) | (unsigned int)(eb + (1 << 25));
                 } else {
                     is_pad = pk[u] == 0xffffffffu;
                     const unsigned int kk = is_pad ? 0u : pk[u];
@@ -216,7 +226,7 @@ __global__ void __launch_bounds__(LONGW ? LONGW * 64 : 256, LONGW ? 1024 / (LONG
                     const int tap = (int)(kk - __umul24(cin, (unsigned int)p.KK));
                     const unsigned int r = __umul24((unsigned int)tap, (unsigned int)p.kw_magic) >> 8;   // tap / kw
                     // r * W + (tap - r * kw), less the centre tap's offset
-                    eb = (int)__umul24(cin, (unsigned int)HW) + __mul24((int)r, wstep) + tap - centre;   // (W < kw: wstep < 0)
+                    eb = (int)__umul24(cin, (unsigned int)HW) + __mul24((int)r, wstep) + tap - centre + tile_pos;   // (W < kw: wstep < 0)
                     pk[u] = (unsigned int)(is_pad ? p.KK : tap) << 27 | (unsigned int)(eb + (1 << 25));
                 }
                 // A 16-byte load at an odd element (2 bytes off a dword) costs about three aligned ones in the
@@ -343,12 +353,12 @@ __global__ void __launch_bounds__(LONGW ? LONGW * 64 : 256, LONGW ? 1024 / (LONG
             if (p.relu) sum[e] = sum[e] > 0.f ? sum[e] : 0.f;     // NaN stays NaN
         }
         const int left = (int)(p.Nv - n);            // below 4 only in the one tile of a map of fewer than 64 positions
-        if (p.stride != 1) {
+        if constexpr (S2) {
             // positions of the input grid: the ones with even row and column are outputs
             int hv = (int)(n / p.W), w = (int)(n - (int64_t)hv * p.W);
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                const int h = hv * p.hmul;
+                const int h = hv * hmul;
                 if (e < left && !(h & 1) && !(w & 1)) store_one(row * p.ldy + (int64_t)(h >> 1) * p.Wo + (w >> 1), sum[e]);
                 if (++w == p.W) { w = 0; ++hv; }
             }
@@ -478,9 +488,11 @@ grim_status launch_conv_gather(const grim_bcr_matrix *A, const void *F, int32_t 
     if (nwg > 0x7fffffff) return GRIM_ERR_SHAPE;
     const size_t lds = (size_t)(longw ? longw : 4) * 8192 + kConvTableBytes;
     const dim3 grid((unsigned)nwg), block(longw ? longw * 64 : 256);
-#define GRIM_CONV(BF, SO, EI)                                                                                        \
+    const int mode = stride == 2 ? 2 : plan ? 1 : 0;
+    if (stride == 2 && !plan) return GRIM_ERR_UNSUPPORTED;
+#define GRIM_CONV_M(BF, SO, EI, MO)                                                                                  \
     do {                                                                                                             \
-        auto kern = bcr_conv_gather<BF, SO, EI>;                                                                     \
+        auto kern = bcr_conv_gather<BF, SO, EI, MO>;                                                                 \
         static std::atomic<bool> attr_done{false};                                                                   \
         if (lds > 64 * 1024 && !attr_done) {                                                                         \
             if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, \
@@ -492,9 +504,14 @@ grim_status launch_conv_gather(const grim_bcr_matrix *A, const void *F, int32_t 
         }                                                                                                            \
         hipLaunchKernelGGL(kern, grid, block, lds, stream, p);                                                       \
     } while (0)
+#define GRIM_CONV(BF, SO, EI)                                                                                        \
+    do {                                                                                                             \
+        if (mode == 0) GRIM_CONV_M(BF, SO, EI, 0); else if (mode == 1) GRIM_CONV_M(BF, SO, EI, 1); else GRIM_CONV_M(BF, SO, EI, 2); \
+    } while (0)
     if (A->dtype == GRIM_BF16) { if (solo) GRIM_CONV(true, true, 0); else if (longw == 12) GRIM_CONV(true, false, 12); else if (longw == 8) GRIM_CONV(true, false, 8); else GRIM_CONV(true, false, 0); }
     else { if (solo) GRIM_CONV(false, true, 0); else if (longw == 12) GRIM_CONV(false, false, 12); else if (longw == 8) GRIM_CONV(false, false, 8); else GRIM_CONV(false, false, 0); }
 #undef GRIM_CONV
+#undef GRIM_CONV_M
     return hipGetLastError() == hipSuccess ? GRIM_OK : GRIM_ERR_DEVICE;
 }
 
