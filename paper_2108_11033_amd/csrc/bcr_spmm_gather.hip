@@ -43,6 +43,8 @@ struct GatherParams {
     int32_t nbr, ntiles;      // nbr: 16-row runs of the stored row order
     int32_t usteps;           // > 0: steps of every run (sptr is not read)
     int32_t yvec;
+    int32_t K;                // rows of X
+    int32_t touch;            // start the tile's rows of X on their way from HBM when the workgroup starts
     XcdMap map;
     GatherSecond second;
 };
@@ -83,6 +85,22 @@ __global__ void __launch_bounds__(EIGHT ? kGatherLongWaves * 64 : 256, EIGHT ? 1
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    // A wave learns which rows of X it needs only after a first round trip (row numbers), and fetches them in one or
+    // two batches: with X in HBM that is up to three dependent trips to memory.  The strips of a tile run at the same
+    // time on one XCD and together keep nearly every row of the tile (16 strips keeping a quarter each leave 1 % out),
+    // so each workgroup starts its share of ALL the tile's rows on their way into that XCD's L2 right now -- one byte
+    // from the first and the last 128-byte line of every row piece, values never used -- and the fetches proper find
+    // them there or on their way.
+    if constexpr (!NARROW) {
+        if (p.touch) {
+            const int units = p.map.per_tile;                          // workgroups of this tile
+            const int per = (p.K + units - 1) / units;
+            const int r_end = (unit + 1) * per < p.K ? (unit + 1) * per : p.K;
+            const char *base = reinterpret_cast<const char *>(X + n0) + (tid & 1) * 127;
+            for (int r = unit * per + (tid >> 1); r < r_end; r += NWV * 32)
+                (void)*reinterpret_cast<const volatile unsigned char *>(base + (int64_t)r * p.ldx * 2);
+        }
+    }
     // one dependent memory round trip less at the start when every run has the same number of steps
     const int g0 = usteps ? t * usteps : sptr[t], nst = usteps ? usteps : sptr[t + 1] - g0;
     const int s_beg = SOLO ? g0 : g0 + (int)((int64_t)nst * wave / NWV);
@@ -282,6 +300,7 @@ grim_status launch_spmm_gather(const grim_bcr_matrix *A, const void *X, int64_t 
     p.Y = Y;
     p.N = N; p.ldx = ldx; p.ldy = ldy;
     p.nbr = (int32_t)A->gather.nstrips;
+    p.K = (int32_t)A->K;
     p.usteps = A->gather.usteps;
     p.ntiles = (int32_t)((N + 63) / 64);
     p.yvec = (reinterpret_cast<uintptr_t>(Y) % 16 == 0 && ldy % 4 == 0 && N % 4 == 0) ? 4 : 1;
@@ -294,6 +313,10 @@ grim_status launch_spmm_gather(const grim_bcr_matrix *A, const void *X, int64_t 
     // strips of at most 8 steps (two batches of a wave) with enough (tile, strip) pairs to fill the GPU: wave per pair;
     // long strips and fewer workgroups than compute units: eight waves per strip
     const bool narrow = N < 64;
+    // Long strips only: a wave then runs ten and more dependent batches, and having the rows in L2 shortens each (the
+    // last 512 columns of a 4608-row product: 10 -> 7.7 us); with 18-step strips the extra requests cost more than they
+    // save (12.0 -> 12.4 us on a 2304-row product, five-step strips 15.5 -> 24 us).
+    p.touch = !narrow && A->gather.max_steps >= 40 ? 1 : 0;
     const bool solo = !narrow && gather_wave_per_strip(A, (int64_t)p.ntiles * p.nbr, 1536);
     const bool eight = !narrow && !solo && A->gather.max_steps >= 16 && (int64_t)p.ntiles * p.nbr <= 256;
     const int64_t per_tile = solo ? (p.nbr + 3) / 4 : p.nbr;
