@@ -46,7 +46,8 @@ struct ConvParams {
     // which only those with even row and column are stored (output (h / 2, w / 2)); hmul = 2: the tiles walk the even
     // rows only (needs W % 8 == 0, so that a lane's 8 positions never straddle two rows), hmul = 1: all rows
     int32_t stride, hmul, Wo;
-    int32_t Nv;                  // positions the tiles of one image walk: (rows walked) * W
+    int32_t Nv;                  // positions the tiles of one image walk: (rows walked) * W (or the end of a range)
+    int32_t img0, pos_begin;     // first image of the launch; first position the tiles walk (a range of one image)
     XcdMap map;
 };
 
@@ -84,13 +85,14 @@ __global__ void __launch_bounds__(LONGW ? LONGW * 64 : 256, LONGW ? 1024 / (LONG
     if (!xcd_map_at(p.map, blockIdx.x, p.ntiles, &tile, &unit)) return;
     // (a division by a run-time value is done on the vector ALU even for uniform operands; without the
     // readfirstlane everything derived from the image and tile numbers would live in vector registers)
-    const int img = __builtin_amdgcn_readfirstlane(tile / p.tiles_per_img);
-    tile = __builtin_amdgcn_readfirstlane(tile - img * p.tiles_per_img);
+    const int img_l = __builtin_amdgcn_readfirstlane(tile / p.tiles_per_img);
+    tile = __builtin_amdgcn_readfirstlane(tile - img_l * p.tiles_per_img);
+    const int img = img_l + p.img0;
     const unsigned short *Fimg = p.F + (int64_t)img * p.f_img_stride;
     const int t_raw = SOLO ? unit * 4 + wave : unit;
     const bool active = t_raw < p.nbr;           // SOLO: the last workgroup of a tile may have idle waves
     const int t = active ? t_raw : p.nbr - 1;
-    int n0 = tile * TN;
+    int n0 = p.pos_begin + tile * TN;
     if (n0 + TN > p.Nv) n0 = p.Nv - TN;          // ragged last tile: overlap the neighbour
     n0 = n0 < 0 ? 0 : n0;                        // a map of fewer than 64 positions: one tile, its columns past N never stored
 
@@ -432,7 +434,7 @@ uint32_t conv_plan_word(uint32_t k, int32_t H, int32_t W, int32_t kh, int32_t kw
 grim_status launch_conv_gather(const grim_bcr_matrix *A, const void *F, int32_t Cin, int32_t H, int32_t W, int32_t kh,
                                int32_t kw, const float *bias, int32_t relu, void *Y, int32_t odt, int64_t ldy,
                                hipStream_t stream, int32_t batch, int32_t stride, int64_t f_img_stride,
-                               int64_t y_img_stride, const uint32_t *plan) {
+                               int64_t y_img_stride, const uint32_t *plan, int32_t img0, int64_t pos_begin, int64_t pos_end) {
     const int64_t N = (int64_t)H * W, total = (int64_t)Cin * N;
     if (batch < 1 || (stride != 1 && stride != 2)) return GRIM_ERR_UNSUPPORTED;
     if (!A->gather.present || total < 8 || kh * kw > kConvMaxTaps || total > (int64_t(1) << 26) || (int64_t)(kh / 2) * W + kw / 2 >= (1 << 24) ||
@@ -466,9 +468,17 @@ grim_status launch_conv_gather(const grim_bcr_matrix *A, const void *F, int32_t 
     p.stride = stride;
     p.hmul = stride == 2 && W % 8 == 0 ? 2 : 1;
     p.Wo = (W + stride - 1) / stride;
-    const int64_t Nv = p.hmul == 2 ? (int64_t)((H + 1) / 2) * W : N;
+    int64_t Nv = p.hmul == 2 ? (int64_t)((H + 1) / 2) * W : N;
+    p.img0 = img0;
+    p.pos_begin = 0;
+    if (pos_end > 0) {
+        // a range of positions of one image (stride 1): at least one tile's worth, so that the ragged last tile stays inside it
+        if (stride != 1 || batch != 1 || pos_begin < 0 || pos_end > N || pos_end - pos_begin < 64) return GRIM_ERR_UNSUPPORTED;
+        p.pos_begin = (int32_t)pos_begin;
+        Nv = pos_end;
+    }
     p.Nv = (int32_t)Nv;
-    p.tiles_per_img = (int32_t)((Nv + 63) / 64);
+    p.tiles_per_img = (int32_t)((Nv - p.pos_begin + 63) / 64);
     if ((int64_t)p.tiles_per_img * batch > 0x7fffffff / 16) return GRIM_ERR_SHAPE;
     p.ntiles = p.tiles_per_img * batch;
     // four consecutive outputs of a row in one store: 16 bytes of fp32, 8 bytes of fp16 / bf16

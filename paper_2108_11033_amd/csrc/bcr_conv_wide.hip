@@ -115,8 +115,19 @@ grim_status launch_conv_wide(const grim_bcr_matrix *A, const void *F, int32_t Ci
     const int64_t n_main = N / tn / per_round * per_round * tn;
     grim_status st = conv_wide_range(A, p, tn, 0, n_main, stream);
     if (st != GRIM_OK || n_main == N) return st;
-    // what is left, in narrow tiles; fewer than one tile's worth: the last 32 positions, of which the first few are
-    // computed twice (the same sums in the same order: the overlap writes the same bits)
+    // What is left.  A narrow tile of this kernel walks all K for its 16 strips in one chain of chunk periods whatever
+    // its width (16 workgroups: 50 us for the last 512 positions of a 4608-row layer), so a rest of at least 64 positions
+    // inside one image goes to the row-gathering convolution, whose workgroups split the strips and K (256 workgroups
+    // for the same positions).  Otherwise narrow tiles; fewer than one tile's worth: the last 32 positions, of which the
+    // first few are computed twice (the same sums in the same order: the overlap writes the same bits).
+    const int64_t img_r = n_main / HW;
+    if (N - n_main >= 64 && (N - 1) / HW == img_r && A->gather.present) {
+        const char *Fi = static_cast<const char *>(F) + img_r * (int64_t)p.f_img_stride * 2;
+        char *Yi = static_cast<char *>(Y) + img_r * p.y_img_stride * (odt == GRIM_F32 ? 4 : 2);
+        st = launch_conv_gather(A, Fi, Cin, H, W, kh, kw, bias, relu, Yi, odt, ldy, stream, 1, 1, 0, 0, nullptr, 0,
+                                n_main - img_r * HW, N - img_r * HW);
+        if (st != GRIM_ERR_UNSUPPORTED) return st;
+    }
     const int64_t rest0 = N - n_main >= kConvWideRestTile ? n_main : N - kConvWideRestTile;
     return conv_wide_range(A, p, kConvWideRestTile, rest0, N, stream);
 }

@@ -217,7 +217,8 @@ bool gather_wave_per_strip(const grim_bcr_matrix *A, int64_t pairs, int64_t pair
 grim_status launch_conv_gather(const grim_bcr_matrix *A, const void *F, int32_t Cin, int32_t H, int32_t W, int32_t kh,
                                int32_t kw, const float *bias, int32_t relu, void *Y, int32_t odt, int64_t ldy,
                                hipStream_t stream, int32_t batch = 1, int32_t stride = 1, int64_t f_img_stride = 0,
-                               int64_t y_img_stride = 0, const uint32_t *plan = nullptr);
+                               int64_t y_img_stride = 0, const uint32_t *plan = nullptr, int32_t img0 = 0,
+                               int64_t pos_begin = 0, int64_t pos_end = 0);   // pos_end > 0: positions [pos_begin, pos_end) of image img0 only
 uint32_t conv_plan_word(uint32_t k, int32_t H, int32_t W, int32_t kh, int32_t kw);
 // stride-1 convolution of layers with many positions on the wide-tile kernel (whole rounds of workgroups plus a narrow
 // rest); GRIM_ERR_UNSUPPORTED when the layer is too small or does not qualify: the caller then takes the kernel above

@@ -15,7 +15,7 @@ grim_status launch_spmm_gather(const grim_bcr_matrix *, const void *, int64_t, i
 bool gather_pair_applies(const grim_bcr_matrix *, const void *, const grim_bcr_matrix *, const void *, int64_t, int64_t) { return false; }
 bool gather_applies(const grim_bcr_matrix *, const void *, int64_t, int64_t) { return false; }
 bool gather_wave_per_strip(const grim_bcr_matrix *, int64_t, int64_t) { return false; }
-grim_status launch_conv_gather(const grim_bcr_matrix *, const void *, int32_t, int32_t, int32_t, int32_t, int32_t, const float *, int32_t, void *, int32_t, int64_t, hipStream_t, int32_t, int32_t, int64_t, int64_t, const uint32_t *) { return GRIM_ERR_DEVICE; }
+grim_status launch_conv_gather(const grim_bcr_matrix *, const void *, int32_t, int32_t, int32_t, int32_t, int32_t, const float *, int32_t, void *, int32_t, int64_t, hipStream_t, int32_t, int32_t, int64_t, int64_t, const uint32_t *, int32_t, int64_t, int64_t) { return GRIM_ERR_DEVICE; }
 uint32_t conv_plan_word(uint32_t, int32_t, int32_t, int32_t, int32_t) { return 0; }
 bool conv_wide_applies(const grim_bcr_matrix *, const void *, int32_t, int32_t, int32_t, int32_t, int32_t, int32_t, int64_t, const void *, int32_t, int64_t, int64_t) { return false; }
 grim_status launch_conv_wide(const grim_bcr_matrix *, const void *, int32_t, int32_t, int32_t, int32_t, int32_t, int32_t, int64_t, const float *, int32_t, void *, int32_t, int64_t, int64_t, hipStream_t) { return GRIM_ERR_UNSUPPORTED; }
