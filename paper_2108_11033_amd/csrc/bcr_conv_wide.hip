@@ -18,7 +18,9 @@ namespace grim {
 constexpr int kConvWideRestTile = 32;
 
 static size_t conv_wide_lds(const grim_bcr_matrix *A, int tn, int KK) {
-    return 2 * (size_t)wide_stage_bytes(A->mmaw.chunk_rows, tn, A->mmaw.amax[2]) + (size_t)(KK + 1) * (tn / 8) * 16;
+    // two stages, the (tap, piece) mask table, four per-chunk row tables
+    return 2 * (size_t)wide_stage_bytes(A->mmaw.chunk_rows, tn, A->mmaw.amax[2]) + (size_t)(KK + 1) * (tn / 8) * 16 +
+           4 * (size_t)wide_max_chunk_rows(A->BR) * 8;
 }
 
 // the widest compiled tile whose records fit the fetching waves' registers and whose stages fit LDS; 0: none

@@ -171,7 +171,6 @@ __global__ void __launch_bounds__(kWideThreads) bcr_spmm_wide(WideParams p) {
                 vtab[e] = u32x4{m[0], m[1], m[2], m[3]};
             }
         }
-        if constexpr (CONV) __syncthreads();     // the table is complete before the first chunk is stored
         // (channel-and-tap offset, tap) of row k of the never-formed matrix; rows past K: tap KK (masked to zero)
         auto conv_row = [&](int k, int &tap) {
             const bool past = k >= p.K;
@@ -182,6 +181,22 @@ __global__ void __launch_bounds__(kWideThreads) bcr_spmm_wide(WideParams p) {
             tap = past ? p.KK : t_;
             return (int)cin * p.HW + r * p.W + (t_ - r * p.kw) - centre;
         };
+        // That split is made once per row and chunk, not once per 16-byte unit: a ring of four per-chunk tables in LDS
+        // (behind the mask table) holds it for the chunks whose rows are being asked for or written; one thread per row
+        // fills the table of chunk c + 4 during the period of chunk c, a barrier before anyone reads it.
+        constexpr int RTP = wide_max_chunk_rows(BR);
+        int2 *rowtab = reinterpret_cast<int2 *>(lds + 2 * stage_bytes + (CONV ? (p.KK + 1) * CPR * 16 : 0));
+        auto fill_rows = [&](int chunk) {
+            if (ft < RTP) {
+                int tap;
+                const int eb = conv_row(chunk * p.chunk_rows + ft, tap);
+                rowtab[(chunk & 3) * RTP + ft] = int2{eb, tap};
+            }
+        };
+        if constexpr (CONV) {
+            for (int ch = 0; ch < 4; ++ch) fill_rows(ch);
+            __syncthreads();                     // both tables are complete before the first chunk is asked for
+        }
         // rows 0 .. K - 1 of the tile's columns: the last valid byte is the end of row K - 1's piece
         const __amdgpu_buffer_rsrc_t xres = __builtin_amdgcn_make_buffer_rsrc(
             const_cast<unsigned short *>(CONV ? p.F : p.X + n0), 0, CONV ? 16 : (int)(((int64_t)(p.K - 1) * p.ldx + TN) * 2), kBufferFlags);
@@ -208,21 +223,22 @@ __global__ void __launch_bounds__(kWideThreads) bcr_spmm_wide(WideParams p) {
                 rr[i] = __builtin_amdgcn_raw_buffer_load_b128(rres, (i * kWideFetchThreads + ft) * 16, 0, 0);
         };
         auto load_rows = [&](int chunk, u32x4 (&rx)[SXU]) {
+            const int chunk_u = chunk;           // (CONV: rows past the last chunk are past K: any address, never stored)
             chunk = chunk < p.nchunks ? chunk : p.nchunks - 1;
             if constexpr (CONV) {
                 // the unit's 8 pixels: one 16-byte load at a 2-byte alignment, always issued, at an address clamped
                 // into the batch (a window that starts before it or ends behind it is shifted into place when stored)
-                const int k0 = chunk * p.chunk_rows;
+                // (the rows' table entries are read together, so that their LDS round trips overlap)
+                int eb[SXU];
+#pragma unroll
+                for (int i = 0; i < SXU; ++i) eb[i] = rowtab[(chunk_u & 3) * RTP + (i * kWideFetchThreads + ft) / CPR].x;
 #pragma unroll
                 for (int i = 0; i < SXU; ++i) {
-                    const int u = i * kWideFetchThreads + ft;
-                    int tap;
-                    int e = xoff[i % XP] + conv_row(k0 + u / CPR, tap);
+                    int e = xoff[i % XP] + eb[i];
                     e = e < 0 ? 0 : e > p.f_total - 8 ? p.f_total - 8 : e;
                     WideWindow wv;
                     __builtin_memcpy(&wv, reinterpret_cast<const char *>(p.F) + (unsigned int)(e * 2), 16);
                     rx[i] = u32x4{wv.d[0], wv.d[1], wv.d[2], wv.d[3]};
-                    __builtin_amdgcn_sched_barrier(0);       // one unit's address arithmetic at a time: few live registers
                 }
             } else {
                 const int soff = __builtin_amdgcn_readfirstlane((int)((int64_t)chunk * p.chunk_rows * p.ldx * 2));
@@ -243,27 +259,53 @@ __global__ void __launch_bounds__(kWideThreads) bcr_spmm_wide(WideParams p) {
             char *sbase = lds + (chunk & 1) * stage_bytes;
             int fo = ft;
             asm volatile("" : "+v"(fo));         // the unit addresses are recomputed here, not held in registers across the loop
+            if constexpr (CONV) {
+                // three units at a time: their table entries, then their masks, are read together (two dependent LDS
+                // round trips per group instead of per unit)
+                constexpr int G = 3;
 #pragma unroll
-            for (int i = 0; i < SXU; ++i) {
-                const int u = i * kWideFetchThreads + fo;
-                const int row = u / CPR, c = u - row * CPR;
-                u32x4 v = rx[i];
-                if constexpr (CONV) {
-                    int tap;
-                    const int e = xoff[i % XP] + conv_row(chunk * p.chunk_rows + row, tap);
-                    const int ec = e < 0 ? 0 : e > p.f_total - 8 ? p.f_total - 8 : e;
-                    const int d = e - ec;        // the pixels wanted start d elements behind (before: d < 0) the ones loaded
-                    if (__builtin_amdgcn_ballot_w64(d != 0) != 0 && d != 0) {      // (rare: the first and last pixels of the batch)
-                        unsigned __int128 x = (unsigned __int128)v[0] | (unsigned __int128)v[1] << 32 |
-                                              (unsigned __int128)v[2] << 64 | (unsigned __int128)v[3] << 96;
-                        x = d >= 8 || d <= -8 ? (unsigned __int128)0 : d > 0 ? x >> (16 * d) : x << (16 * -d);
-                        v = u32x4{(unsigned int)x, (unsigned int)(x >> 32), (unsigned int)(x >> 64), (unsigned int)(x >> 96)};
+                for (int g = 0; g < SXU; g += G) {
+                    int2 ri[G];
+                    u32x4 vm[G];
+#pragma unroll
+                    for (int j = 0; j < G; ++j) {
+                        const int i = g + j < SXU ? g + j : SXU - 1;
+                        ri[j] = rowtab[(chunk & 3) * RTP + (i * kWideFetchThreads + fo) / CPR];
                     }
-                    const u32x4 vm = vtab[tap * CPR + c];
-                    v = u32x4{v[0] & vm[0], v[1] & vm[1], v[2] & vm[2], v[3] & vm[3]};
+#pragma unroll
+                    for (int j = 0; j < G; ++j) {
+                        const int i = g + j < SXU ? g + j : SXU - 1;
+                        const int u = i * kWideFetchThreads + fo;
+                        vm[j] = vtab[ri[j].y * CPR + (u - u / CPR * CPR)];
+                    }
+#pragma unroll
+                    for (int j = 0; j < G; ++j) {
+                        if (g + j < SXU) {
+                            const int i = g + j;
+                            const int u = i * kWideFetchThreads + fo;
+                            const int row = u / CPR, c = u - row * CPR;
+                            u32x4 v = rx[i];
+                            const int e = xoff[i % XP] + ri[j].x;
+                            const int ec = e < 0 ? 0 : e > p.f_total - 8 ? p.f_total - 8 : e;
+                            const int d = e - ec;    // the pixels wanted start d elements behind (before: d < 0) the ones loaded
+                            if (__builtin_amdgcn_ballot_w64(d != 0) != 0 && d != 0) {      // (rare: the first and last pixels of the batch)
+                                unsigned __int128 x = (unsigned __int128)v[0] | (unsigned __int128)v[1] << 32 |
+                                                      (unsigned __int128)v[2] << 64 | (unsigned __int128)v[3] << 96;
+                                x = d >= 8 || d <= -8 ? (unsigned __int128)0 : d > 0 ? x >> (16 * d) : x << (16 * -d);
+                                v = u32x4{(unsigned int)x, (unsigned int)(x >> 32), (unsigned int)(x >> 64), (unsigned int)(x >> 96)};
+                            }
+                            v = u32x4{v[0] & vm[j][0], v[1] & vm[j][1], v[2] & vm[j][2], v[3] & vm[j][3]};
+                            if (row < p.chunk_rows) *reinterpret_cast<u32x4 *>(sbase + row * PITCH + c * 16) = v;
+                        }
+                    }
                 }
-                if (row < p.chunk_rows) *reinterpret_cast<u32x4 *>(sbase + row * PITCH + c * 16) = v;
-                if constexpr (CONV) __builtin_amdgcn_sched_barrier(0);
+            } else {
+#pragma unroll
+                for (int i = 0; i < SXU; ++i) {
+                    const int u = i * kWideFetchThreads + fo;
+                    const int row = u / CPR, c = u - row * CPR;
+                    if (row < p.chunk_rows) *reinterpret_cast<u32x4 *>(sbase + row * PITCH + c * 16) = rx[i];
+                }
             }
         };
         // Chunk c is multiplied from stage c % 2 while chunk c + 1 is written to the other stage (read last in chunk
@@ -282,6 +324,7 @@ __global__ void __launch_bounds__(kWideThreads) bcr_spmm_wide(WideParams p) {
         __syncthreads();
         for (int c = 0; c < p.nchunks; c += 2) {
             rnxt = rec_range(c + 2);
+            if constexpr (CONV) fill_rows(c + 4);
             if (c + 1 < p.nchunks) { store_rows(c + 1, RX1); store_records(c + 1, rcur, RR); }
             load_records(rnxt, RR);
             rcur = rnxt;
@@ -289,6 +332,7 @@ __global__ void __launch_bounds__(kWideThreads) bcr_spmm_wide(WideParams p) {
             __syncthreads();
             if (c + 1 >= p.nchunks) break;
             rnxt = rec_range(c + 3);
+            if constexpr (CONV) fill_rows(c + 5);
             if (c + 2 < p.nchunks) { store_rows(c + 2, RX0); store_records(c + 2, rcur, RR); }
             load_records(rnxt, RR);
             rcur = rnxt;
