@@ -5,9 +5,9 @@
 // k % (kh kw), zero outside the image -- in LDS with one 16-byte load per 8 positions, and the multiplying waves
 // run exactly as for a matrix X in memory.  Every pixel is fetched kh * kw times, but from the caches: HBM sees the
 // feature maps once instead of a matrix kh * kw times their size.
-// Launches: whole rounds of 256 workgroups at the widest tile, then the remaining positions at the narrowest one
-// (a partial round of wide tiles would cost as much as a full one).  Small layers stay on the row-gathering
-// convolution kernel.
+// Launches: whole rounds of 256 workgroups at the widest tile; the remaining positions go to the row-gathering
+// convolution on a position range, or to 32-column tiles of this kernel when that does not apply (a partial round of
+// wide tiles would cost as much as a full one).  Small layers stay on the row-gathering convolution kernel.
 #include <atomic>
 
 #include "spmm_wide_kernel.hpp"
