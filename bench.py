@@ -331,6 +331,20 @@ def main() -> int:
                     torch.cuda.synchronize()
                     assert int(status.item()) == 0
                     extra[f"c3_b{batch}"][f"lstm_sequence_T{T}_us_per_step"] = tS * 1e6 / T
+                # 2, 4, 8 sequences side by side in the same launch
+                T = 256
+                for nb in (2, 4, 8):
+                    if not g.rnn_sequence_supported(mats[0], None, nb):
+                        continue
+                    xs_b = dev_tensor(gen.normal_activations(Ih, T * nb, w3.dtype, seed=13), w3.dtype).t().contiguous()
+                    h0 = torch.zeros((nb, Hh), dtype=xs_b.dtype, device=dev)
+                    cs = torch.zeros((nb, Hh), dtype=torch.float32, device=dev)
+                    hs = torch.empty((T * nb, Hh), dtype=xs_b.dtype, device=dev)
+                    tS, _ = time_launches(torch, lambda i: g.lstm_sequence_batch(mats[0], xs_b, Ih, T, nb, None, h0, cs, hs, Hh,
+                                                                                 None, 0, status, 0, stream), 10, 2)
+                    torch.cuda.synchronize()
+                    assert int(status.item()) == 0
+                    extra[f"c3_b{batch}"][f"lstm_sequence_batch{nb}_T{T}_us_per_step"] = tS * 1e6 / T
             del mats, xs, ys
         # ---- a GRU layer of the paper's size (Section 6.1: hidden 1024, both gate matrices 3072 x 1024, 32 x 32 blocks
         #      keeping 8 rows x 12 columns = pruned 10.7x, the rate of Section 6.4): one step = two products + the cell,
@@ -371,6 +385,19 @@ def main() -> int:
                 torch.cuda.synchronize()
                 assert int(status.item()) == 0
                 gru[f"sequence_T{T}_us_per_step"] = tS * 1e6 / T
+            T = 256
+            for nb in (2, 4, 8):
+                if not g.rnn_sequence_supported(Agi, Agh, nb):
+                    continue
+                xs_b = dev_tensor(gen.normal_activations(Hg, T * nb, "f16", seed=14), "f16").t().contiguous()
+                h0 = torch.zeros((nb, Hg), dtype=torch.float16, device=dev)
+                hst = torch.zeros((nb, Hg), dtype=torch.float32, device=dev)
+                hs = torch.empty((T * nb, Hg), dtype=torch.float16, device=dev)
+                tS, _ = time_launches(torch, lambda i: g.gru_sequence_batch(Agi, Agh, xs_b, Hg, T, nb, None, None, h0, hst, hs, Hg,
+                                                                            None, 0, status, 0, stream), 10, 2)
+                torch.cuda.synchronize()
+                assert int(status.item()) == 0
+                gru[f"sequence_batch{nb}_T{T}_us_per_step"] = tS * 1e6 / T
         gru["kernel_b32"] = g.spmm_kernel_name(Agi, xg, 32, 32)
         # the three GRU matrix sizes the paper counts register loads on (Section 6.4), pruned 10.7x: one product each
         shapes = {}

@@ -374,15 +374,25 @@ grim_status grim_bcr_gru_step(const grim_bcr_matrix *Ai, const grim_bcr_matrix *
  *              outputs are then undefined.  The caller reads it after synchronising with hip_stream.
  *   max_polls  limit of unsuccessful reads of an exchange word before a workgroup gives up; 0 = default (2^21,
  *              seconds).  Every workgroup leaves the kernel either way.
- * One right-hand side.  Requirements: fp16 / bf16, blocks of at most 32 x 32 all keeping the same (rows, columns)
+ * The *_batch forms run `batch` independent sequences (1 .. 8) in the same launch, spread over further sets of
+ * H / BR workgroups while the GPU has compute units for them and several per workgroup beyond that:
+ * row t * batch + b of xs_dev / hs_dev / hs32_dev belongs to step t of sequence b; h0_dev is batch x H elements,
+ * c_dev / h32_dev batch x H fp32, sequence b at offset b * H.  Every sequence gets the bits a call of its own
+ * with batch 1 would give.  More than 8, or a workgroup's vectors not fitting its local memory
+ * (sequences per workgroup x (I + H) x 2 bytes plus tables within 160 KB): GRIM_ERR_UNSUPPORTED;
+ * grim_bcr_rnn_sequence_batch_supported tells in advance.  The calls without _batch are batch = 1.
+ * The exchange buffer holds 2 x 8 x H words of 8 bytes.
+ * Requirements: fp16 / bf16, blocks of at most 32 x 32 all keeping the same (rows, columns)
  * out of {4, 8, 16} x {4, 8, 12, 16} (not 16 x 16), at most 64 column blocks per matrix, H a multiple of BR,
  * H <= 8192 and H / BR workgroups <= the GPU's compute units; otherwise GRIM_ERR_UNSUPPORTED (loop over the step
  * call instead); grim_bcr_rnn_sequence_supported(A, Ah or NULL) tells in advance (1 / 0).
  * Two sequence calls on the same matrix must not overlap in time (they share the exchange buffer): enqueue them
  * on one stream.  Only enqueues work on hip_stream (two launches: clearing the exchange words, the sequence).
- * Errors: NULL, SHAPE (T < 1, rows not 4H / 3H, leading dimension too small), DTYPE, DEVICE, ALLOC, UNSUPPORTED.
+ * Errors: NULL, SHAPE (T < 1, batch < 1, rows not 4H / 3H, leading dimension too small), DTYPE, DEVICE, ALLOC,
+ * UNSUPPORTED.
  */
 int32_t grim_bcr_rnn_sequence_supported(const grim_bcr_matrix *A, const grim_bcr_matrix *Ah);
+int32_t grim_bcr_rnn_sequence_batch_supported(const grim_bcr_matrix *A, const grim_bcr_matrix *Ah, int32_t batch);
 grim_status grim_bcr_lstm_sequence(const grim_bcr_matrix *A, const void *xs_dev, int64_t ldxs, int32_t T,
                                    const float *bias_dev, const void *h0_dev, float *c_dev, void *hs_dev, int64_t ldhs,
                                    float *hs32_dev, int64_t ldhs32, int32_t *status_dev, uint32_t max_polls,
@@ -391,6 +401,14 @@ grim_status grim_bcr_gru_sequence(const grim_bcr_matrix *Ai, const grim_bcr_matr
                                   int32_t T, const float *bias_i_dev, const float *bias_h_dev, const void *h0_dev,
                                   float *h32_dev, void *hs_dev, int64_t ldhs, float *hs32_dev, int64_t ldhs32,
                                   int32_t *status_dev, uint32_t max_polls, void *hip_stream);
+grim_status grim_bcr_lstm_sequence_batch(const grim_bcr_matrix *A, const void *xs_dev, int64_t ldxs, int32_t T, int32_t batch,
+                                         const float *bias_dev, const void *h0_dev, float *c_dev, void *hs_dev, int64_t ldhs,
+                                         float *hs32_dev, int64_t ldhs32, int32_t *status_dev, uint32_t max_polls,
+                                         void *hip_stream);
+grim_status grim_bcr_gru_sequence_batch(const grim_bcr_matrix *Ai, const grim_bcr_matrix *Ah, const void *xs_dev, int64_t ldxs,
+                                        int32_t T, int32_t batch, const float *bias_i_dev, const float *bias_h_dev,
+                                        const void *h0_dev, float *h32_dev, void *hs_dev, int64_t ldhs, float *hs32_dev,
+                                        int64_t ldhs32, int32_t *status_dev, uint32_t max_polls, void *hip_stream);
 
 /*
  * grim_bcr_lstm_sequence_noalloc -- grim_bcr_lstm_sequence for callers that cannot allocate device memory (code

@@ -60,7 +60,8 @@ EXPORTS = ["grim_bcr_pack", "grim_bcr_unpack", "grim_bcr_arrays", "grim_bcr_spmm
            "grim_bcr_export_bcrc", "grim_bcrc_arrays", "grim_bcrc_free", "grim_lstm_cell", "grim_bcr_lstm_step", "grim_gru_cell", "grim_bcr_gru_step",
            "grim_bcr_conv2d", "grim_bcr_conv2d_act", "grim_bcr_unpack_layout", "grim_bcr_rnn_step_launches",
            "grim_bcr_rnn_sequence_supported", "grim_bcr_lstm_sequence", "grim_bcr_gru_sequence",
-           "grim_bcr_lstm_sequence_noalloc", "grim_bcr_conv_plan_create", "grim_bcr_conv_plan_free", "grim_bcr_conv2d_plan", "grim_bcr_conv2d_kernel_name"]
+           "grim_bcr_lstm_sequence_noalloc", "grim_bcr_rnn_sequence_batch_supported", "grim_bcr_lstm_sequence_batch",
+           "grim_bcr_gru_sequence_batch", "grim_bcr_conv_plan_create", "grim_bcr_conv_plan_free", "grim_bcr_conv2d_plan", "grim_bcr_conv2d_kernel_name"]
 
 
 def lib_path() -> str:
@@ -117,6 +118,9 @@ def load_library():
     lib.grim_bcr_conv2d_plan.argtypes = [p, p, i32, i64, p, i32, p, i32, i64, i64, p]
     lib.grim_bcr_lstm_sequence_noalloc.argtypes = [p, p, i64, i32, p, p, p, p, i64, p, i64, p, ctypes.c_uint32, p]
     lib.grim_bcr_gru_sequence.argtypes = [p, p, p, i64, i32, p, p, p, p, p, i64, p, i64, p, ctypes.c_uint32, p]
+    lib.grim_bcr_rnn_sequence_batch_supported.argtypes = [p, p, i32]
+    lib.grim_bcr_lstm_sequence_batch.argtypes = [p, p, i64, i32, i32, p, p, p, p, i64, p, i64, p, ctypes.c_uint32, p]
+    lib.grim_bcr_gru_sequence_batch.argtypes = [p, p, p, i64, i32, i32, p, p, p, p, p, i64, p, i64, p, ctypes.c_uint32, p]
     for name in EXPORTS:
         getattr(lib, name).restype = i32
     lib.grim_status_str.restype = ctypes.c_char_p
@@ -347,9 +351,26 @@ def lstm_step(A: BcrMatrix, xh, batch: int, ldx: int, gates, ldg: int, bias, c, 
                                      _addr(h), ldh, _addr(h32), ldh32, _stream(stream)), "grim_bcr_lstm_step")
 
 
-def rnn_sequence_supported(A: BcrMatrix, Ah: Optional[BcrMatrix] = None) -> bool:
-    """grim_bcr_rnn_sequence_supported: can the whole-sequence kernel run this LSTM (Ah None) / GRU layer?"""
-    return bool(A._lib.grim_bcr_rnn_sequence_supported(A.handle, Ah.handle if Ah is not None else None))
+def rnn_sequence_supported(A: BcrMatrix, Ah: Optional[BcrMatrix] = None, batch: int = 1) -> bool:
+    """grim_bcr_rnn_sequence_batch_supported: can the whole-sequence kernel run this LSTM (Ah None) / GRU layer
+    on `batch` sequences side by side?"""
+    return bool(A._lib.grim_bcr_rnn_sequence_batch_supported(A.handle, Ah.handle if Ah is not None else None, batch))
+
+
+def lstm_sequence_batch(A: BcrMatrix, xs, ldxs: int, T: int, batch: int, bias, h0, c, hs, ldhs: int, hs32, ldhs32: int,
+                        status, max_polls: int = 0, stream=None):
+    """grim_bcr_lstm_sequence_batch: T LSTM steps of `batch` sequences in one launch (row t * batch + b)."""
+    _check(A._lib.grim_bcr_lstm_sequence_batch(A.handle, _addr(xs), ldxs, T, batch, _addr(bias), _addr(h0), _addr(c),
+                                               _addr(hs), ldhs, _addr(hs32), ldhs32, _addr(status), max_polls,
+                                               _stream(stream)), "grim_bcr_lstm_sequence_batch")
+
+
+def gru_sequence_batch(Ai: BcrMatrix, Ah: BcrMatrix, xs, ldxs: int, T: int, batch: int, bias_i, bias_h, h0, h32, hs,
+                       ldhs: int, hs32, ldhs32: int, status, max_polls: int = 0, stream=None):
+    """grim_bcr_gru_sequence_batch: T GRU steps of `batch` sequences in one launch (row t * batch + b)."""
+    _check(Ai._lib.grim_bcr_gru_sequence_batch(Ai.handle, Ah.handle, _addr(xs), ldxs, T, batch, _addr(bias_i), _addr(bias_h),
+                                               _addr(h0), _addr(h32), _addr(hs), ldhs, _addr(hs32), ldhs32, _addr(status),
+                                               max_polls, _stream(stream)), "grim_bcr_gru_sequence_batch")
 
 
 def lstm_sequence(A: BcrMatrix, xs, ldxs: int, T: int, bias, h0, c, hs, ldhs: int, hs32, ldhs32: int, status,

@@ -241,14 +241,15 @@ bool spmv_cell_applies(int kind, int64_t M, int64_t K, int32_t BR, int32_t BC, i
 grim_status launch_spmv_cell(int kind, const GemvDesc &d1, const GemvDesc *d2, int64_t M, int64_t K, int32_t BR, int32_t BC,
                              int32_t dtype, int32_t ukr, int32_t ukc, const void *x, int64_t x_stride, int64_t ldx, float *y,
                              int64_t y_stride, int64_t ldy, const RnnCell &cell, hipStream_t stream);
-// a recurrent layer over a whole sequence in one launch (kind 1: LSTM, K1 = I + H; kind 2: GRU, K1 = I, K2 = H);
-// exch: 2 * H words of 8 bytes; hidden sizes up to kSeqMaxH
+// a recurrent layer over a whole sequence in one launch (kind 1: LSTM, K1 = I + H; kind 2: GRU, K1 = I, K2 = H), `batch`
+// sequences side by side (1 .. kSeqMaxBatch); exch: at most 2 * batch * H words of 8 bytes; hidden sizes up to kSeqMaxH
 constexpr int64_t kSeqMaxH = 8192;
+constexpr int32_t kSeqMaxBatch = 8;
 bool rnn_seq_applies(int kind, int32_t BR, int32_t BC, int32_t dtype, int32_t ukr, int32_t ukc, int64_t K1, int64_t K2,
-                     int64_t I, int64_t H);
+                     int64_t I, int64_t H, int32_t batch);
 grim_status launch_rnn_seq(int kind, const GemvDesc &d1, const GemvDesc *d2, const int32_t *pos1, const int32_t *pos2,
                            int32_t BR, int32_t BC, int32_t dtype, int32_t ukr, int32_t ukc, int64_t K1, int64_t K2, int64_t I,
-                           int64_t H, int32_t T, const void *xs, int64_t ldxs, const void *h0, const float *bias,
+                           int64_t H, int32_t T, int32_t batch, const void *xs, int64_t ldxs, const void *h0, const float *bias,
                            const float *bias2, float *state, void *hs, int64_t ldhs, float *hs32, int64_t ldhs32,
                            void *exch, int32_t *status, uint32_t max_polls, hipStream_t stream);
 // device address of this GPU's static exchange words (2 * kSeqMaxH of them); allocates nothing

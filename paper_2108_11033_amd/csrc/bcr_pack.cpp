@@ -1020,7 +1020,8 @@ static grim_status seq_exchange_of(const grim_bcr_matrix *A, int64_t H, void **o
     std::lock_guard<std::mutex> hold(A->seq_lock);
     if (!A->seq_exch) {
         void *ptr = nullptr;
-        if (hipMalloc(&ptr, (size_t)(2 * H) * 8) != hipSuccess) {
+        // two slots of at most one word per hidden unit and sequence, for the largest batch
+        if (hipMalloc(&ptr, (size_t)(2 * H) * kSeqMaxBatch * 8) != hipSuccess) {
             (void)hipGetLastError();
             return GRIM_ERR_ALLOC;
         }
@@ -1030,10 +1031,10 @@ static grim_status seq_exchange_of(const grim_bcr_matrix *A, int64_t H, void **o
     return GRIM_OK;
 }
 
-static grim_status seq_check(const grim_bcr_matrix *A, const void *xs, int32_t T, const void *h0, const float *state,
-                             const void *hs, const int32_t *status) {
+static grim_status seq_check(const grim_bcr_matrix *A, const void *xs, int32_t T, int32_t batch, const void *h0,
+                             const float *state, const void *hs, const int32_t *status) {
     if (!A || !xs || !h0 || !state || !hs || !status) return GRIM_ERR_NULL;
-    if (T < 1) return GRIM_ERR_SHAPE;
+    if (T < 1 || batch < 1) return GRIM_ERR_SHAPE;
     if (!A->on_device) return GRIM_ERR_DEVICE;
     int dev = -1;
     if (hipGetDevice(&dev) != hipSuccess || dev != A->device) return GRIM_ERR_DEVICE;
@@ -1041,42 +1042,54 @@ static grim_status seq_check(const grim_bcr_matrix *A, const void *xs, int32_t T
 }
 
 int32_t grim_bcr_rnn_sequence_supported(const grim_bcr_matrix *A, const grim_bcr_matrix *Ah) {
+    return grim_bcr_rnn_sequence_batch_supported(A, Ah, 1);
+}
+
+int32_t grim_bcr_rnn_sequence_batch_supported(const grim_bcr_matrix *A, const grim_bcr_matrix *Ah, int32_t batch) {
     if (!A || !A->on_device || !A->gemv.present) return 0;
     if (!Ah) {
         if (A->M % 4 != 0 || A->K <= A->M / 4) return 0;
         const int64_t H = A->M / 4;
-        return rnn_seq_applies(1, A->BR, A->BC, A->dtype, A->gemv.uniform_kr, A->gemv.uniform_kc, A->K, 0, A->K - H, H) ? 1 : 0;
+        return rnn_seq_applies(1, A->BR, A->BC, A->dtype, A->gemv.uniform_kr, A->gemv.uniform_kc, A->K, 0, A->K - H, H, batch) ? 1 : 0;
     }
     if (!Ah->on_device || !Ah->gemv.present || A->M != Ah->M || A->M % 3 != 0 || Ah->K != A->M / 3) return 0;
     if (A->dtype != Ah->dtype || A->BR != Ah->BR || A->BC != Ah->BC || A->gemv.uniform_kr != Ah->gemv.uniform_kr ||
         A->gemv.uniform_kc != Ah->gemv.uniform_kc)
         return 0;
-    return rnn_seq_applies(2, A->BR, A->BC, A->dtype, A->gemv.uniform_kr, A->gemv.uniform_kc, A->K, Ah->K, A->K, Ah->K) ? 1 : 0;
+    return rnn_seq_applies(2, A->BR, A->BC, A->dtype, A->gemv.uniform_kr, A->gemv.uniform_kc, A->K, Ah->K, A->K, Ah->K, batch) ? 1 : 0;
 }
 
 grim_status grim_bcr_lstm_sequence(const grim_bcr_matrix *A, const void *xs_dev, int64_t ldxs, int32_t T,
                                    const float *bias_dev, const void *h0_dev, float *c_dev, void *hs_dev, int64_t ldhs,
                                    float *hs32_dev, int64_t ldhs32, int32_t *status_dev, uint32_t max_polls,
                                    void *hip_stream) {
-    grim_status st = seq_check(A, xs_dev, T, h0_dev, c_dev, hs_dev, status_dev);
+    return grim_bcr_lstm_sequence_batch(A, xs_dev, ldxs, T, 1, bias_dev, h0_dev, c_dev, hs_dev, ldhs, hs32_dev, ldhs32,
+                                        status_dev, max_polls, hip_stream);
+}
+
+grim_status grim_bcr_lstm_sequence_batch(const grim_bcr_matrix *A, const void *xs_dev, int64_t ldxs, int32_t T, int32_t batch,
+                                         const float *bias_dev, const void *h0_dev, float *c_dev, void *hs_dev, int64_t ldhs,
+                                         float *hs32_dev, int64_t ldhs32, int32_t *status_dev, uint32_t max_polls,
+                                         void *hip_stream) {
+    grim_status st = seq_check(A, xs_dev, T, batch, h0_dev, c_dev, hs_dev, status_dev);
     if (st != GRIM_OK) return st;
     if (A->M % 4 != 0 || A->K <= A->M / 4) return GRIM_ERR_SHAPE;
     const int64_t H = A->M / 4, I = A->K - H;
     if (ldxs < I || ldhs < H || (hs32_dev && ldhs32 < H)) return GRIM_ERR_SHAPE;
-    if (!grim_bcr_rnn_sequence_supported(A, nullptr)) return GRIM_ERR_UNSUPPORTED;
+    if (!grim_bcr_rnn_sequence_batch_supported(A, nullptr, batch)) return GRIM_ERR_UNSUPPORTED;
     void *exch = nullptr;
     st = seq_exchange_of(A, H, &exch);
     if (st != GRIM_OK) return st;
     return launch_rnn_seq(1, desc_of(A), nullptr, A->dev.strip_pos, nullptr, A->BR, A->BC, A->dtype, A->gemv.uniform_kr,
-                          A->gemv.uniform_kc, A->K, 0, I, H, T, xs_dev, ldxs, h0_dev, bias_dev, nullptr, c_dev, hs_dev, ldhs,
-                          hs32_dev, ldhs32, exch, status_dev, max_polls, static_cast<hipStream_t>(hip_stream));
+                          A->gemv.uniform_kc, A->K, 0, I, H, T, batch, xs_dev, ldxs, h0_dev, bias_dev, nullptr, c_dev, hs_dev,
+                          ldhs, hs32_dev, ldhs32, exch, status_dev, max_polls, static_cast<hipStream_t>(hip_stream));
 }
 
 grim_status grim_bcr_lstm_sequence_noalloc(const grim_bcr_matrix *A, const void *xs_dev, int64_t ldxs, int32_t T,
                                            const float *bias_dev, const void *h0_dev, float *c_dev, void *hs_dev,
                                            int64_t ldhs, float *hs32_dev, int64_t ldhs32, int32_t *status_dev,
                                            uint32_t max_polls, void *hip_stream) {
-    grim_status st = seq_check(A, xs_dev, T, h0_dev, c_dev, hs_dev, status_dev);
+    grim_status st = seq_check(A, xs_dev, T, 1, h0_dev, c_dev, hs_dev, status_dev);
     if (st != GRIM_OK) return st;
     if (A->M % 4 != 0 || A->K <= A->M / 4) return GRIM_ERR_SHAPE;
     const int64_t H = A->M / 4, I = A->K - H;
@@ -1087,7 +1100,7 @@ grim_status grim_bcr_lstm_sequence_noalloc(const grim_bcr_matrix *A, const void 
     st = rnn_seq_static_exchange(&exch);
     if (st != GRIM_OK) return st;
     return launch_rnn_seq(1, desc_of(A), nullptr, A->dev.strip_pos, nullptr, A->BR, A->BC, A->dtype, A->gemv.uniform_kr,
-                          A->gemv.uniform_kc, A->K, 0, I, H, T, xs_dev, ldxs, h0_dev, bias_dev, nullptr, c_dev, hs_dev, ldhs,
+                          A->gemv.uniform_kc, A->K, 0, I, H, T, 1, xs_dev, ldxs, h0_dev, bias_dev, nullptr, c_dev, hs_dev, ldhs,
                           hs32_dev, ldhs32, exch, status_dev, max_polls, static_cast<hipStream_t>(hip_stream));
 }
 
@@ -1095,7 +1108,15 @@ grim_status grim_bcr_gru_sequence(const grim_bcr_matrix *Ai, const grim_bcr_matr
                                   int32_t T, const float *bias_i_dev, const float *bias_h_dev, const void *h0_dev,
                                   float *h32_dev, void *hs_dev, int64_t ldhs, float *hs32_dev, int64_t ldhs32,
                                   int32_t *status_dev, uint32_t max_polls, void *hip_stream) {
-    grim_status st = seq_check(Ai, xs_dev, T, h0_dev, h32_dev, hs_dev, status_dev);
+    return grim_bcr_gru_sequence_batch(Ai, Ah, xs_dev, ldxs, T, 1, bias_i_dev, bias_h_dev, h0_dev, h32_dev, hs_dev, ldhs,
+                                       hs32_dev, ldhs32, status_dev, max_polls, hip_stream);
+}
+
+grim_status grim_bcr_gru_sequence_batch(const grim_bcr_matrix *Ai, const grim_bcr_matrix *Ah, const void *xs_dev, int64_t ldxs,
+                                        int32_t T, int32_t batch, const float *bias_i_dev, const float *bias_h_dev,
+                                        const void *h0_dev, float *h32_dev, void *hs_dev, int64_t ldhs, float *hs32_dev,
+                                        int64_t ldhs32, int32_t *status_dev, uint32_t max_polls, void *hip_stream) {
+    grim_status st = seq_check(Ai, xs_dev, T, batch, h0_dev, h32_dev, hs_dev, status_dev);
     if (st != GRIM_OK) return st;
     if (!Ah) return GRIM_ERR_NULL;
     if (Ai->M != Ah->M || Ai->M % 3 != 0 || Ah->K != Ai->M / 3) return GRIM_ERR_SHAPE;
@@ -1103,13 +1124,13 @@ grim_status grim_bcr_gru_sequence(const grim_bcr_matrix *Ai, const grim_bcr_matr
     if (!Ah->on_device || Ah->device != Ai->device) return GRIM_ERR_DEVICE;
     const int64_t H = Ah->K, I = Ai->K;
     if (ldxs < I || ldhs < H || (hs32_dev && ldhs32 < H)) return GRIM_ERR_SHAPE;
-    if (!grim_bcr_rnn_sequence_supported(Ai, Ah)) return GRIM_ERR_UNSUPPORTED;
+    if (!grim_bcr_rnn_sequence_batch_supported(Ai, Ah, batch)) return GRIM_ERR_UNSUPPORTED;
     void *exch = nullptr;
     st = seq_exchange_of(Ah, H, &exch);
     if (st != GRIM_OK) return st;
     const GemvDesc dh = desc_of(Ah);
     return launch_rnn_seq(2, desc_of(Ai), &dh, Ai->dev.strip_pos, Ah->dev.strip_pos, Ai->BR, Ai->BC, Ai->dtype,
-                          Ai->gemv.uniform_kr, Ai->gemv.uniform_kc, I, H, I, H, T, xs_dev, ldxs, h0_dev, bias_i_dev, bias_h_dev,
+                          Ai->gemv.uniform_kr, Ai->gemv.uniform_kc, I, H, I, H, T, batch, xs_dev, ldxs, h0_dev, bias_i_dev, bias_h_dev,
                           h32_dev, hs_dev, ldhs, hs32_dev, ldhs32, exch, status_dev, max_polls,
                           static_cast<hipStream_t>(hip_stream));
 }

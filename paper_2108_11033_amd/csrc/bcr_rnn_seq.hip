@@ -1,6 +1,10 @@
 // A recurrent layer over a whole sequence in ONE launch (Section 3.1: an RNN layer is one matrix-vector product per
 // time step; Section 6.3 times the GRU step by step, where every step pays a kernel launch and re-reads the weights).
 //
+// Up to 8 independent sequences run side by side (a batch).  A recurrent layer of 1024 hidden units occupies 32 of the
+// 256 compute units, so the sequences are first spread over further sets of workgroups (grid.y: each set holds its
+// own copy of the weights in registers and exchanges h only within itself, at the pace of a single sequence); when the
+// compute units are used up a workgroup carries several sequences in turn on one set of weights.
 // A workgroup owns BR hidden units for the whole sequence.  Its waves take the strips that hold these units' gate
 // rows (LSTM: 4 strips of [W_ih | W_hh]; GRU: 3 strips of W_i and 3 of W_h), and every lane keeps ONE compact block of
 // its strip in registers from the first step to the last: the weights are read from memory once per sequence, not
@@ -9,15 +13,17 @@
 //   2. multiplies (a lane: its block times the block's kept columns of the vector; row sums through a
 //      [strip row][block] table in a fixed order, exactly as the one-step kernel does),
 //   3. applies the cell to its BR units and publishes their new h.
-// Workgroups exchange h through a small buffer of 8-byte words (fp32 value, step tag), two slots used in turn:
+// Workgroups exchange h through a small buffer of 8-byte words (the new h of one hidden unit for two sequences of the
+// batch, already rounded to the element type the next product reads; step tag), two slots used in turn:
 // a producer writes a word with one atomic store, consumers re-read a word until its tag is the step they need.
-// Value and tag travel together, so no fence and no separate counter is needed.  Slot t & 1 can be overwritten with
+// Values and tag travel together, so no fence and no separate counter is needed.  Slot t & 1 can be overwritten with
 // h_{t+2} only by a workgroup that has read all of h_{t+1}, which exists only when every workgroup has finished
 // reading h_t: two slots are enough.  Every wait is bounded: after `max_polls` unsuccessful reads a workgroup gives
 // up, marks its own words as poisoned (which ends every other workgroup's wait at once) and sets *status; all
 // workgroups then leave the kernel normally.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <atomic>
 #include <mutex>
 
@@ -28,6 +34,7 @@ namespace grim {
 
 constexpr unsigned int kSeqPoison = 0xffffffffu;   // tag of a word whose producer has given up
 constexpr unsigned int kSeqDefaultPolls = 1u << 21;
+constexpr size_t kSeqMaxLds = 160 * 1024 - 256;    // dynamic part: the kernel also has a few static bytes
 
 struct SeqParams {
     GemvDesc d1, d2;               // LSTM: the gate matrix; GRU: W_i and W_h
@@ -36,26 +43,35 @@ struct SeqParams {
     int32_t nbc1, nbc2;            // column blocks per strip (<= 64 each)
     int32_t K1, K2;                // LSTM: K1 = I + H; GRU: K1 = I, K2 = H
     int32_t I, H, T;
+    int32_t B;                     // sequences side by side (1 .. 8), dealt to grid.y sets of workgroups
+    int32_t SPB, NQ;               // sequences per workgroup; pairs of them = exchange words per hidden unit
     int32_t xvec16;                // rows of xs can be copied with 16-byte loads
-    const void *xs;                // T x I inputs
+    const void *xs;                // T x B rows of I inputs, row t * B + b
     int64_t ldxs;
-    const void *h0;                // H elements: h before the first step
+    const void *h0;                // B x H elements: h before the first step
     const float *bias, *bias2;     // LSTM: 4H; GRU: 3H input side, 3H hidden side; null = none
-    float *state;                  // LSTM: c, GRU: h in fp32; H values, read at the start, written at the end
-    void *hs;                      // T x H outputs in the matrices' element type
+    float *state;                  // LSTM: c, GRU: h in fp32; B x H values, read at the start, written at the end
+    void *hs;                      // T x B rows of H outputs in the matrices' element type
     int64_t ldhs;
     float *hs32;                   // optional fp32 copy of the outputs
     int64_t ldhs32;
-    unsigned long long *exch;      // 2 x H words (fp32 value, tag); all tags zero at launch
+    unsigned long long *exch;      // grid.y x 2 x NQ x H words (two 16-bit values, tag); all tags zero at launch
     int32_t *status;               // set to 1 by a workgroup that gives up
     uint32_t max_polls;
 };
 
-template <int DT> __device__ __forceinline__ typename GElem<DT>::type seq_round(float v);
-template <> __device__ __forceinline__ _Float16 seq_round<GRIM_F16>(float v) { return (_Float16)v; }
+// the bits of v rounded to the element type (nearest even)
+template <int DT> __device__ __forceinline__ unsigned short seq_round(float v);
+template <> __device__ __forceinline__ unsigned short seq_round<GRIM_F16>(float v) {
+    const _Float16 h = (_Float16)v;
+    return __builtin_bit_cast(unsigned short, h);
+}
 template <> __device__ __forceinline__ unsigned short seq_round<GRIM_BF16>(float v) { return rnn_f32_to_bf16(v); }
 
-template <int DT, int KR, int KC, int CELL>
+constexpr int kSeqXVec = 4;   // 16-byte pieces of a step's inputs a thread fetches ahead
+
+// MULTI: a workgroup carries more than one sequence
+template <int DT, int KR, int KC, int CELL, bool MULTI>
 __global__ void __launch_bounds__(exact_waves(CELL) * 64) bcr_rnn_seq(SeqParams p) {
     using T = typename GElem<DT>::type;
     static_assert(sizeof(T) == 2, "two-byte element types");
@@ -68,15 +84,22 @@ __global__ void __launch_bounds__(exact_waves(CELL) * 64) bcr_rnn_seq(SeqParams 
     const int mi = CELL == 2 ? wave / 3 : 0;
     const int gate = CELL == 2 ? wave % 3 : wave;
     const int H = p.H;
+    // this workgroup's sequences: b0 .. b0 + B - 1 of the p.B
+    const int set = blockIdx.y, b0 = set * p.SPB;
+    const int B = MULTI ? (p.SPB < p.B - b0 ? p.SPB : p.B - b0) : 1;
+    const int NQ = MULTI ? p.NQ : 1;
+    unsigned long long *const exch = p.exch + (size_t)set * 2 * NQ * H;
 
-    // LDS: input vector(s) | a [strip row][block] table per wave | the waves' row sums
-    const int xbytes1 = (p.K1 * 2 + 15) & ~15;
-    const int xbytes = CELL == 2 ? xbytes1 + ((p.K2 * 2 + 15) & ~15) : xbytes1;
+    // LDS: the B input vectors (x; LSTM: h follows at element I; GRU: the B vectors h after all x) | a
+    // [strip row][block] table per wave | the waves' row sums per sequence
+    const int xbytes1 = (B * p.K1 * 2 + 15) & ~15;
+    const int xbytes = CELL == 2 ? xbytes1 + ((B * p.K2 * 2 + 15) & ~15) : xbytes1;
     const int tbytes = (p.BR * kPartStride * 4 + 15) & ~15;
-    T *xin = reinterpret_cast<T *>(smem);                                     // x_t; LSTM: h follows at element I
-    T *hin = CELL == 2 ? reinterpret_cast<T *>(smem + xbytes1) : xin + p.I;
+    T *xin = reinterpret_cast<T *>(smem);
+    unsigned short *hin = reinterpret_cast<unsigned short *>(CELL == 2 ? smem + xbytes1 : smem + p.I * 2);
+    const int hld = CELL == 2 ? p.K2 : p.K1;                                  // elements from one sequence's h to the next's
     float *part = reinterpret_cast<float *>(smem + xbytes + wave * tbytes);
-    float *gl = reinterpret_cast<float *>(smem + xbytes + NWV * tbytes);      // [NWV][32]
+    float *gl = reinterpret_cast<float *>(smem + xbytes + NWV * tbytes);      // [B][NWV][32]
     __shared__ int flag_word;
     volatile int *flag = &flag_word;
 
@@ -97,13 +120,18 @@ __global__ void __launch_bounds__(exact_waves(CELL) * 64) bcr_rnn_seq(SeqParams 
         rm = mm.x;
         cm = mm.y;
     }
-    const T *xb = ((CELL == 2 && mi) ? hin : xin) + blk_l * p.BC;
+    const T *xb = ((CELL == 2 && mi) ? reinterpret_cast<const T *>(hin) : xin) + blk_l * p.BC;
+    const int xld = (CELL == 2 && mi) ? p.K2 : p.K1;                          // elements from one sequence's vector to the next's
 
-    // the cell's threads: one per hidden unit, state and biases in registers
-    const int64_t ju = (int64_t)blockIdx.x * p.BR + tid;
-    float st = 0.f, b[6] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    if (tid < p.BR) {
-        st = p.state[ju];
+    // the cell's threads: one per (hidden unit, pair of sequences), states and biases in registers
+    const int cq = MULTI ? tid / p.BR : 0, cu = tid - cq * p.BR;
+    const bool cell_thread = MULTI ? cq < NQ : tid < p.BR;
+    const int64_t ju = (int64_t)blockIdx.x * p.BR + cu;
+    float st[2] = {0.f, 0.f}, b[6] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    if (cell_thread) {
+#pragma unroll
+        for (int k = 0; k < 2; ++k)
+            if (2 * cq + k < B) st[k] = p.state[(int64_t)(b0 + 2 * cq + k) * H + ju];
 #pragma unroll
         for (int k = 0; k < (CELL == 1 ? 4 : 3); ++k) {
             if (p.bias) b[k] = p.bias[k * (int64_t)H + ju];
@@ -116,12 +144,23 @@ __global__ void __launch_bounds__(exact_waves(CELL) * 64) bcr_rnn_seq(SeqParams 
     const int r_out = p.BR <= 16 ? lane & 15 : lane & 31;
     const int grp = p.BR <= 16 ? lane >> 4 : lane >> 5;
     (void)ngrp;
-    const GRIM_GLOBAL T *h0 = (const GRIM_GLOBAL T *)p.h0;
-    const GRIM_GLOBAL T *xs0 = (const GRIM_GLOBAL T *)p.xs;
-    // 16-byte path: a row of xs is at most 256 vectors (K1 <= 64 blocks of 32), one per thread, fetched a step ahead
-    const int nxv = p.I / 8;
-    gu32x4 xr = gu32x4{0u, 0u, 0u, 0u};
-    if (p.xvec16) xr = reinterpret_cast<const GRIM_GLOBAL gu32x4 *>(xs0)[tid < nxv ? tid : 0];
+    const GRIM_GLOBAL unsigned short *h0 = (const GRIM_GLOBAL unsigned short *)p.h0 + (int64_t)b0 * H;
+    const GRIM_GLOBAL T *xs0 = (const GRIM_GLOBAL T *)p.xs + (int64_t)b0 * p.ldxs;
+    // 16-byte path: the B rows of a step are at most XV pieces per thread, fetched a step ahead
+    constexpr int XV = MULTI ? kSeqXVec : 1;
+    const int nxv1 = p.I / 8, nxv = B * nxv1;
+    gu32x4 xr[XV];
+    int64_t xsrc[XV];                  // piece -> element offset inside the step's rows of xs
+    int xdst[XV];                      // piece -> element offset in LDS
+#pragma unroll
+    for (int k = 0; k < XV; ++k) {
+        const int v = tid + k * NTHR < nxv ? tid + k * NTHR : 0;
+        const int vb = v / nxv1, vi = v - vb * nxv1;
+        xsrc[k] = vb * p.ldxs + vi * 8;
+        xdst[k] = vb * p.K1 + vi * 8;
+        xr[k] = gu32x4{0u, 0u, 0u, 0u};
+        if (p.xvec16 && k * NTHR < nxv) xr[k] = *reinterpret_cast<const GRIM_GLOBAL gu32x4 *>(xs0 + xsrc[k]);
+    }
     // positions of the block's kept columns, and the [strip row][block] table zeroed once: a lane only ever
     // writes the entries of its block's kept rows, all others stay zero
     unsigned short coff[KC];
@@ -142,45 +181,73 @@ __global__ void __launch_bounds__(exact_waves(CELL) * 64) bcr_rnn_seq(SeqParams 
         // ---- 1. x_t and h_t (the state BEFORE this step: h0, or what step t - 1 published under tag t)
         if (p.xvec16) {
             // x_t was asked for a step ago; x_{t+1} is asked for now and travels while this step waits for h
-            if (tid < nxv) reinterpret_cast<gu32x4 *>(xin)[tid] = xr;
             const int tn = t + 1 < p.T ? t + 1 : t;
-            xr = reinterpret_cast<const GRIM_GLOBAL gu32x4 *>(xs0 + (int64_t)tn * p.ldxs)[tid < nxv ? tid : 0];
+            const GRIM_GLOBAL T *xg = xs0 + (int64_t)tn * p.B * p.ldxs;
+#pragma unroll
+            for (int k = 0; k < XV; ++k)
+                if (k * NTHR < nxv) {                                 // the same for all threads
+                    if (tid + k * NTHR < nxv) *reinterpret_cast<gu32x4 *>(xin + xdst[k]) = xr[k];
+                    xr[k] = *reinterpret_cast<const GRIM_GLOBAL gu32x4 *>(xg + xsrc[k]);
+                }
         } else {
-            const GRIM_GLOBAL T *xg = xs0 + (int64_t)t * p.ldxs;
-            for (int e = tid; e < p.I; e += NTHR) xin[e] = xg[e];
+            for (int bb = 0; bb < B; ++bb) {
+                const GRIM_GLOBAL T *xg = xs0 + ((int64_t)t * p.B + bb) * p.ldxs;
+                for (int e = tid; e < p.I; e += NTHR) xin[bb * p.K1 + e] = xg[e];
+            }
         }
         if (t == 0) {
-            for (int e = tid; e < H; e += NTHR) hin[e] = h0[e];
+            for (int bb = 0; bb < B; ++bb)
+                for (int e = tid; e < H; e += NTHR) hin[bb * hld + e] = h0[(int64_t)bb * H + e];
         } else {
-            const unsigned long long *ex = p.exch + (size_t)(t & 1) * H;
-            for (int base = tid; base < H; base += 4 * NTHR) {
-                unsigned long long v[4] = {0ull, 0ull, 0ull, 0ull};
-                unsigned int polls = 0;
-                bool ok;
-                for (;;) {
-                    ok = true;
+            // words of two pairs of sequences per round: up to 8 reads in flight
+            const unsigned long long *ex = exch + (size_t)(t & 1) * NQ * H;
+            bool bad = false;
+            for (int q0 = 0; q0 < NQ && !bad; q0 += 2) {
+                for (int base = tid; base < H && !bad; base += 4 * NTHR) {
+                    unsigned long long v[8] = {0ull, 0ull, 0ull, 0ull, 0ull, 0ull, 0ull, 0ull};
+                    unsigned int polls = 0;
+                    bool ok;
+                    for (;;) {
+                        ok = true;
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        const int e = base + i * NTHR;
-                        if (e < H) {
-                            v[i] = __hip_atomic_load(ex + e, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                            const unsigned int tag = (unsigned int)(v[i] >> 32);
-                            if (tag != (unsigned int)t) ok = false;
-                            if (tag == kSeqPoison) polls = p.max_polls;
+                        for (int j = 0; j < 2; ++j) {
+                            if (q0 + j < NQ) {
+#pragma unroll
+                                for (int i = 0; i < 4; ++i) {
+                                    const int e = base + i * NTHR;
+                                    if (e < H) {
+                                        v[j * 4 + i] = __hip_atomic_load(ex + (size_t)(q0 + j) * H + e, __ATOMIC_RELAXED,
+                                                                         __HIP_MEMORY_SCOPE_AGENT);
+                                        const unsigned int tag = (unsigned int)(v[j * 4 + i] >> 32);
+                                        if (tag != (unsigned int)t) ok = false;
+                                        if (tag == kSeqPoison) polls = p.max_polls;
+                                    }
+                                }
+                            }
+                        }
+                        if (ok || polls >= p.max_polls) break;
+                        ++polls;
+                        __builtin_amdgcn_s_sleep(1);
+                    }
+                    if (!ok) {
+                        *flag = 1;
+                        bad = true;
+                        break;
+                    }
+#pragma unroll
+                    for (int j = 0; j < 2; ++j) {
+                        if (q0 + j < NQ) {
+#pragma unroll
+                            for (int i = 0; i < 4; ++i) {
+                                const int e = base + i * NTHR;
+                                if (e < H) {
+                                    const unsigned int pair = (unsigned int)v[j * 4 + i];
+                                    hin[(2 * (q0 + j)) * hld + e] = (unsigned short)(pair & 0xffffu);
+                                    if (2 * (q0 + j) + 1 < B) hin[(2 * (q0 + j) + 1) * hld + e] = (unsigned short)(pair >> 16);
+                                }
+                            }
                         }
                     }
-                    if (ok || polls >= p.max_polls) break;
-                    ++polls;
-                    __builtin_amdgcn_s_sleep(1);
-                }
-                if (!ok) {
-                    *flag = 1;
-                    break;
-                }
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const int e = base + i * NTHR;
-                    if (e < H) hin[e] = seq_round<DT>(__builtin_bit_cast(float, (unsigned int)v[i]));
                 }
             }
         }
@@ -190,100 +257,117 @@ __global__ void __launch_bounds__(exact_waves(CELL) * 64) bcr_rnn_seq(SeqParams 
             break;
         }
 
-        // ---- 2. the block's KC activations, the products, the strip's row sums
-        T xe[KC];
+        // ---- 2. per sequence: the block's KC activations, the products, the strip's row sums.  One table per wave
+        // serves the sequences in turn: a wave's LDS accesses are carried out in order.
+        for (int bb = 0; bb < B; ++bb) {
+            const T *xbb = xb + bb * xld;
+            T xe[KC];
 #pragma unroll
-        for (int j = 0; j < KC; ++j) xe[j] = xb[coff[j]];
-        unsigned int xp[KC / 2];
-#pragma unroll
-        for (int h = 0; h < KC / 2; ++h) {
-            unsigned short lo, hi;
-            __builtin_memcpy(&lo, &xe[2 * h], 2);
-            __builtin_memcpy(&hi, &xe[2 * h + 1], 2);
-            xp[h] = (unsigned int)lo | ((unsigned int)hi << 16);
-        }
-        float acc[KR];
-#pragma unroll
-        for (int i = 0; i < KR; ++i) {
-            float a = 0.f;
+            for (int j = 0; j < KC; ++j) xe[j] = xbb[coff[j]];
+            unsigned int xp[KC / 2];
 #pragma unroll
             for (int h = 0; h < KC / 2; ++h) {
-                const int q = i * (KC / 2) + h;
-                const unsigned int wd = w[q >> 2][q & 3];
-                if constexpr (DT == GRIM_F16)
-                    a = __builtin_amdgcn_fdot2(__builtin_bit_cast(gh2, wd), __builtin_bit_cast(gh2, xp[h]), a, false);
-                else
-                    a = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(gb2, wd), __builtin_bit_cast(gb2, xp[h]), a, false);
+                unsigned short lo, hi;
+                __builtin_memcpy(&lo, &xe[2 * h], 2);
+                __builtin_memcpy(&hi, &xe[2 * h + 1], 2);
+                xp[h] = (unsigned int)lo | ((unsigned int)hi << 16);
             }
-            acc[i] = a;
-        }
-        if (rm) {
-            unsigned int m = rm;
+            float acc[KR];
 #pragma unroll
             for (int i = 0; i < KR; ++i) {
-                const int r = __builtin_ctz(m);                       // KR bits are set
-                m &= m - 1;
-                part[r * kPartStride + lane] = acc[i];
-            }
-        }
-        __builtin_amdgcn_wave_barrier();
-        float rs;
-        if (p.BR <= 16) {
-            float s = 0.f;
-            if (r_out < p.BR) {
-                const float2 *src = reinterpret_cast<const float2 *>(part + r_out * kPartStride + grp * 16);
+                float a = 0.f;
 #pragma unroll
-                for (int q = 0; q < 8; ++q) {
-                    const float2 v = src[q];
-                    s += v.x;
-                    s += v.y;
+                for (int h = 0; h < KC / 2; ++h) {
+                    const int q = i * (KC / 2) + h;
+                    const unsigned int wd = w[q >> 2][q & 3];
+                    if constexpr (DT == GRIM_F16)
+                        a = __builtin_amdgcn_fdot2(__builtin_bit_cast(gh2, wd), __builtin_bit_cast(gh2, xp[h]), a, false);
+                    else
+                        a = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(gb2, wd), __builtin_bit_cast(gb2, xp[h]), a, false);
+                }
+                acc[i] = a;
+            }
+            if (rm) {
+                unsigned int m = rm;
+#pragma unroll
+                for (int i = 0; i < KR; ++i) {
+                    const int r = __builtin_ctz(m);                       // KR bits are set
+                    m &= m - 1;
+                    part[r * kPartStride + lane] = acc[i];
                 }
             }
-            const float s2 = s + __shfl_xor(s, 16);
-            rs = s2 + __shfl_xor(s2, 32);
-        } else {
-            float s = 0.f;
-            if (r_out < p.BR) {
-                const float2 *src = reinterpret_cast<const float2 *>(part + r_out * kPartStride + grp * 32);
+            __builtin_amdgcn_wave_barrier();
+            float rs;
+            if (p.BR <= 16) {
+                float s = 0.f;
+                if (r_out < p.BR) {
+                    const float2 *src = reinterpret_cast<const float2 *>(part + r_out * kPartStride + grp * 16);
 #pragma unroll
-                for (int q = 0; q < 16; ++q) {
-                    const float2 v = src[q];
-                    s += v.x;
-                    s += v.y;
+                    for (int q = 0; q < 8; ++q) {
+                        const float2 v = src[q];
+                        s += v.x;
+                        s += v.y;
+                    }
                 }
+                const float s2 = s + __shfl_xor(s, 16);
+                rs = s2 + __shfl_xor(s2, 32);
+            } else {
+                float s = 0.f;
+                if (r_out < p.BR) {
+                    const float2 *src = reinterpret_cast<const float2 *>(part + r_out * kPartStride + grp * 32);
+#pragma unroll
+                    for (int q = 0; q < 16; ++q) {
+                        const float2 v = src[q];
+                        s += v.x;
+                        s += v.y;
+                    }
+                }
+                rs = s + __shfl_xor(s, 32);
             }
-            rs = s + __shfl_xor(s, 32);
+            if (grp == 0 && r_out < p.BR) gl[(bb * NWV + wave) * 32 + r_out] = rs;
+            __builtin_amdgcn_wave_barrier();
         }
-        if (grp == 0 && r_out < p.BR) gl[wave * 32 + r_out] = rs;
         __syncthreads();
 
-        // ---- 3. the cell on this workgroup's BR units; publish h_{t+1} under tag t + 1
-        if (tid < p.BR) {
-            float h;
-            if constexpr (CELL == 1) {
-                h = lstm_cell_apply(gl[tid] + b[0], gl[32 + tid] + b[1], gl[64 + tid] + b[2], gl[96 + tid] + b[3], st);
-            } else {
-                h = gru_cell_apply(gl[tid] + b[0], gl[32 + tid] + b[1], gl[64 + tid] + b[2], gl[96 + tid] + b[3],
-                                   gl[128 + tid] + b[4], gl[160 + tid] + b[5], st);
-                st = h;
+        // ---- 3. the cell on this workgroup's BR units, two sequences per thread; publish h_{t+1} under tag t + 1
+        if (cell_thread) {
+            unsigned int pair = 0;
+#pragma unroll
+            for (int k = 0; k < 2; ++k) {
+                const int bb = 2 * cq + k;
+                if (bb < B) {
+                    const float *g = gl + bb * NWV * 32 + cu;
+                    float h;
+                    if constexpr (CELL == 1) {
+                        h = lstm_cell_apply(g[0] + b[0], g[32] + b[1], g[64] + b[2], g[96] + b[3], st[k]);
+                    } else {
+                        h = gru_cell_apply(g[0] + b[0], g[32] + b[1], g[64] + b[2], g[96] + b[3], g[128] + b[4], g[160] + b[5], st[k]);
+                        st[k] = h;
+                    }
+                    const unsigned short hr = seq_round<DT>(h);
+                    pair |= (unsigned int)hr << (16 * k);
+                    static_cast<unsigned short *>(p.hs)[((int64_t)t * p.B + b0 + bb) * p.ldhs + ju] = hr;
+                    if (p.hs32) p.hs32[((int64_t)t * p.B + b0 + bb) * p.ldhs32 + ju] = h;
+                }
             }
-            const unsigned long long word = (unsigned long long)__builtin_bit_cast(unsigned int, h) |
-                                            ((unsigned long long)(unsigned int)(t + 1) << 32);
-            __hip_atomic_store(p.exch + (size_t)((t + 1) & 1) * H + ju, word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            static_cast<T *>(p.hs)[(int64_t)t * p.ldhs + ju] = seq_round<DT>(h);
-            if (p.hs32) p.hs32[(int64_t)t * p.ldhs32 + ju] = h;
+            const unsigned long long word = (unsigned long long)pair | ((unsigned long long)(unsigned int)(t + 1) << 32);
+            __hip_atomic_store(exch + ((size_t)((t + 1) & 1) * NQ + cq) * H + ju, word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     }
 
     if (gave_up) {
-        if (tid < p.BR) {
+        if (cell_thread) {
             const unsigned long long word = (unsigned long long)kSeqPoison << 32;
-            __hip_atomic_store(p.exch + ju, word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __hip_atomic_store(p.exch + (size_t)H + ju, word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(exch + (size_t)cq * H + ju, word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(exch + ((size_t)NQ + cq) * H + ju, word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
         if (tid == 0) __hip_atomic_store(p.status, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
     }
-    if (tid < p.BR) p.state[ju] = st;
+    if (cell_thread) {
+#pragma unroll
+        for (int k = 0; k < 2; ++k)
+            if (2 * cq + k < B) p.state[(int64_t)(b0 + 2 * cq + k) * H + ju] = st[k];
+    }
 }
 
 // zeroes the exchange words' tags and the status word (a kernel, not a memset: callers may capture the launch)
@@ -293,12 +377,12 @@ __global__ void __launch_bounds__(256) rnn_seq_clear(unsigned long long *exch, i
     if (i == 0) *status = 0;
 }
 
-template <int DT, int KR, int KC, int CELL>
+template <int DT, int KR, int KC, int CELL, bool MULTI>
 static grim_status launch_seq_inst(const SeqParams &p, dim3 grid, size_t lds, hipStream_t stream) {
-    auto kern = bcr_rnn_seq<DT, KR, KC, CELL>;
+    auto kern = bcr_rnn_seq<DT, KR, KC, CELL, MULTI>;
     static std::atomic<bool> attr_done{false};
     if (lds > 64 * 1024 && !attr_done) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)kSeqMaxLds) != hipSuccess) {
             (void)hipGetLastError();
             return GRIM_ERR_DEVICE;
         }
@@ -310,8 +394,10 @@ static grim_status launch_seq_inst(const SeqParams &p, dim3 grid, size_t lds, hi
 
 template <int DT, int CELL>
 static grim_status launch_seq(const SeqParams &p, int kr, int kc, dim3 grid, size_t lds, hipStream_t stream) {
-#define GRIM_SEQ(R, C) \
-    if (kr == (R) && kc == (C)) return launch_seq_inst<DT, R, C, CELL>(p, grid, lds, stream);
+#define GRIM_SEQ(R, C)                                                                                   \
+    if (kr == (R) && kc == (C))                                                                          \
+        return p.SPB > 1 ? launch_seq_inst<DT, R, C, CELL, true>(p, grid, lds, stream)                   \
+                         : launch_seq_inst<DT, R, C, CELL, false>(p, grid, lds, stream);
     GRIM_SEQ(4, 4) GRIM_SEQ(4, 8) GRIM_SEQ(4, 12) GRIM_SEQ(4, 16)
     GRIM_SEQ(8, 4) GRIM_SEQ(8, 8) GRIM_SEQ(8, 12) GRIM_SEQ(8, 16)
     GRIM_SEQ(16, 4) GRIM_SEQ(16, 8) GRIM_SEQ(16, 12)
@@ -323,10 +409,10 @@ static bool seq_pair_compiled(int kr, int kc) {
     return (kr == 4 || kr == 8 || kr == 16) && (kc == 4 || kc == 8 || kc == 12 || kc == 16) && !(kr == 16 && kc == 16);
 }
 
-static size_t seq_lds_bytes(int kind, int64_t K1, int64_t K2, int BR) {
-    const size_t x = ((size_t)K1 * 2 + 15) & ~size_t(15), h = kind == 2 ? (((size_t)K2 * 2 + 15) & ~size_t(15)) : 0;
+static size_t seq_lds_bytes(int kind, int64_t K1, int64_t K2, int BR, int batch) {
+    const size_t x = ((size_t)batch * K1 * 2 + 15) & ~size_t(15), h = kind == 2 ? (((size_t)batch * K2 * 2 + 15) & ~size_t(15)) : 0;
     const size_t table = ((size_t)BR * kPartStride * 4 + 15) & ~size_t(15);
-    return x + h + exact_waves(kind) * (table + 32 * 4);
+    return x + h + exact_waves(kind) * (table + (size_t)batch * 32 * 4);
 }
 
 static int compute_units() {
@@ -342,29 +428,44 @@ static int compute_units() {
     return n;
 }
 
+// `batch` sequences on H / BR workgroups per set: as many sets as the compute units hold (at most one per sequence),
+// then several sequences per workgroup
+static void seq_split(int64_t H, int BR, int batch, int cus, int *sets, int *per_wg) {
+    const int64_t wgs = H / BR;
+    int g = (int)std::min<int64_t>(batch, std::max<int64_t>(1, cus / wgs));
+    const int spb = (batch + g - 1) / g;
+    *per_wg = spb;
+    *sets = (batch + spb - 1) / spb;
+}
+
 // kind 1: LSTM (K1 = I + H), kind 2: GRU (K1 = I, K2 = H).  The matrices qualify when they hold two-byte elements in
 // blocks of at most 32 x 32 that all keep one compiled (rows, columns) pair, a strip has at most 64 column blocks
-// (a lane keeps one block), H is a multiple of BR and one workgroup per BR hidden units fits the GPU at once.
+// (a lane keeps one block), H is a multiple of BR and one workgroup per BR hidden units fits the GPU at once; 1 .. 8
+// sequences side by side whose vectors fit LDS.
 bool rnn_seq_applies(int kind, int32_t BR, int32_t BC, int32_t dtype, int32_t ukr, int32_t ukc, int64_t K1, int64_t K2,
-                     int64_t I, int64_t H) {
+                     int64_t I, int64_t H, int32_t batch) {
     if (kind != 1 && kind != 2) return false;
+    if (batch < 1 || batch > kSeqMaxBatch) return false;
     if ((dtype != GRIM_F16 && dtype != GRIM_BF16) || BR < 1 || BR > 32 || BC < 1 || BC > 32) return false;
     if (!seq_pair_compiled(ukr, ukc) || ukr > BR || ukc > BC) return false;
     if (H < 1 || I < 1 || H % BR != 0 || H > kSeqMaxH) return false;
     if (kind == 1 ? K1 != I + H : (K1 != I || K2 != H)) return false;
     if (K1 % BC != 0 || K1 / BC > 64 || (kind == 2 && (K2 % BC != 0 || K2 / BC > 64))) return false;
-    if (seq_lds_bytes(kind, K1, K2, BR) > 160 * 1024) return false;
     const int cus = compute_units();
-    return cus > 0 && H / BR <= cus;
+    if (cus < 1 || H / BR > cus) return false;
+    int sets, per_wg;
+    seq_split(H, BR, batch, cus, &sets, &per_wg);
+    return seq_lds_bytes(kind, K1, K2, BR, per_wg) <= kSeqMaxLds;
 }
 
 grim_status launch_rnn_seq(int kind, const GemvDesc &d1, const GemvDesc *d2, const int32_t *pos1, const int32_t *pos2,
                            int32_t BR, int32_t BC, int32_t dtype, int32_t ukr, int32_t ukc, int64_t K1, int64_t K2, int64_t I,
-                           int64_t H, int32_t T, const void *xs, int64_t ldxs, const void *h0, const float *bias,
+                           int64_t H, int32_t T, int32_t batch, const void *xs, int64_t ldxs, const void *h0, const float *bias,
                            const float *bias2, float *state, void *hs, int64_t ldhs, float *hs32, int64_t ldhs32,
                            void *exch, int32_t *status, uint32_t max_polls, hipStream_t stream) {
-    if ((kind == 2 && (!d2 || !pos2)) || !rnn_seq_applies(kind, BR, BC, dtype, ukr, ukc, K1, K2, I, H)) return GRIM_ERR_UNSUPPORTED;
+    if ((kind == 2 && (!d2 || !pos2)) || !rnn_seq_applies(kind, BR, BC, dtype, ukr, ukc, K1, K2, I, H, batch)) return GRIM_ERR_UNSUPPORTED;
     if (T < 1 || ldxs < I || ldhs < H || (hs32 && ldhs32 < H)) return GRIM_ERR_SHAPE;
+    if ((int64_t)T * batch > 0x7fffffff) return GRIM_ERR_SHAPE;
     SeqParams p;
     p.d1 = d1;
     p.d2 = d2 ? *d2 : d1;
@@ -375,7 +476,12 @@ grim_status launch_rnn_seq(int kind, const GemvDesc &d1, const GemvDesc *d2, con
     p.nbc2 = kind == 2 ? (int32_t)(K2 / BC) : p.nbc1;
     p.K1 = (int32_t)K1; p.K2 = (int32_t)K2;
     p.I = (int32_t)I; p.H = (int32_t)H; p.T = T;
-    p.xvec16 = (I % 8 == 0 && I / 8 <= exact_waves(kind) * 64 && ldxs % 8 == 0 && reinterpret_cast<uintptr_t>(xs) % 16 == 0) ? 1 : 0;
+    int sets = 1, per_wg = 1;
+    seq_split(H, BR, batch, compute_units(), &sets, &per_wg);
+    p.B = batch; p.SPB = per_wg; p.NQ = (per_wg + 1) / 2;
+    // pieces a thread fetches ahead: one when a workgroup carries one sequence, up to kSeqXVec otherwise
+    p.xvec16 = (I % 8 == 0 && K1 % 8 == 0 && per_wg * (I / 8) <= (per_wg > 1 ? kSeqXVec : 1) * exact_waves(kind) * 64 &&
+                ldxs % 8 == 0 && reinterpret_cast<uintptr_t>(xs) % 16 == 0) ? 1 : 0;
     p.xs = xs; p.ldxs = ldxs; p.h0 = h0;
     p.bias = bias; p.bias2 = bias2;
     p.state = state;
@@ -383,11 +489,11 @@ grim_status launch_rnn_seq(int kind, const GemvDesc &d1, const GemvDesc *d2, con
     p.exch = static_cast<unsigned long long *>(exch);
     p.status = status;
     p.max_polls = max_polls ? max_polls : kSeqDefaultPolls;
-    const int64_t words = 2 * H;
+    const int64_t words = (int64_t)sets * 2 * p.NQ * H;                // at most 2 * kSeqMaxBatch * H
     hipLaunchKernelGGL(rnn_seq_clear, dim3((unsigned)((words + 255) / 256)), dim3(256), 0, stream, p.exch, words, status);
     if (hipGetLastError() != hipSuccess) return GRIM_ERR_DEVICE;
-    const dim3 grid((unsigned)(H / BR));
-    const size_t lds = seq_lds_bytes(kind, K1, K2, BR);
+    const dim3 grid((unsigned)(H / BR), (unsigned)sets);
+    const size_t lds = seq_lds_bytes(kind, K1, K2, BR, per_wg);
     if (kind == 1)
         return dtype == GRIM_F16 ? launch_seq<GRIM_F16, 1>(p, ukr, ukc, grid, lds, stream)
                                  : launch_seq<GRIM_BF16, 1>(p, ukr, ukc, grid, lds, stream);

@@ -263,3 +263,149 @@ def test_sequence_refusals():
         g.lstm_sequence(A3, xs, I, 3, None, h0, c, hs, H, None, 0, status)
     assert "UNSUPPORTED" in str(e.value)
     torch.cuda.synchronize()
+
+
+# ---- several sequences side by side (batch): every sequence gets the bits of a call of its own
+
+def _run_lstm_batch(torch, dev, g, A, xs, dtype, bias, h0, c0, pad=0, max_polls=0):
+    """xs [T, B, I], h0 [B, H] storage bits, c0 [B, H]: returns status, hs [T, B, H], hs32 [T, B, H], c [B, H]."""
+    from helpers import to_device
+    T, B, I = xs.shape
+    H = h0.shape[1]
+    ldxs, ldhs = I + pad, H + pad
+    xp = np.zeros((T * B, ldxs), dtype=xs.dtype); xp[:, :I] = xs.reshape(T * B, I)
+    xd = to_device(xp, dtype)
+    hd = to_device(np.ascontiguousarray(h0), dtype)
+    c = torch.from_numpy(np.ascontiguousarray(c0, dtype=np.float32)).to(dev)
+    hs = torch.full((T * B, ldhs), 7.0, dtype=_tdt(torch, dtype), device=dev)
+    hs32 = torch.full((T * B, ldhs), float("nan"), dtype=torch.float32, device=dev)
+    status = torch.full((1,), -1, dtype=torch.int32, device=dev)
+    bd = None if bias is None else torch.from_numpy(bias).to(dev)
+    g.lstm_sequence_batch(A, xd, ldxs, T, B, bd, hd, c, hs, ldhs, hs32, ldhs, status, max_polls, torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    if pad:
+        assert (hs[:, H:].float() == 7.0).all() and torch.isnan(hs32[:, H:]).all(), "wrote outside the H outputs of a row"
+    return (int(status.item()), hs[:, :H].float().cpu().numpy().reshape(T, B, H), hs32[:, :H].cpu().numpy().reshape(T, B, H),
+            c.cpu().numpy())
+
+
+@pytest.mark.parametrize("dtype", [gen.F16, gen.BF16])
+@pytest.mark.parametrize("H,I,BR,BC,kr,kc,T,B,pad", [
+    (96, 64, 32, 32, 8, 12, 9, 2, 0),        # one pair of sequences
+    (128, 72, 16, 8, 4, 4, 7, 3, 3),         # an odd batch (the second pair is half empty), unaligned rows of xs
+    (256, 64, 8, 16, 4, 8, 6, 5, 8),         # strips of 8 rows: 3 cell threads per hidden unit
+    (1024, 1024, 32, 32, 8, 12, 5, 8, 0),    # the LSTM workload's gate matrix, full batch: two rounds of exchange reads
+    (512, 1536, 32, 32, 8, 12, 4, 8, 0),     # 16 workgroups per sequence
+    # more workgroups per sequence than an eighth of the GPU: workgroups carry several sequences in turn
+    (1024, 64, 8, 32, 4, 8, 4, 5, 0),        # 128 workgroups: two sets, of 3 and 2 sequences
+    (2016, 32, 8, 32, 4, 8, 3, 3, 8),        # 252 workgroups: one set carries all three
+    (1024, 1024, 8, 32, 4, 8, 3, 8, 3),      # four sequences per workgroup, inputs copied element by element
+])
+def test_lstm_sequence_batch_equals_sequences_of_their_own(dtype, H, I, BR, BC, kr, kc, T, B, pad):
+    from helpers import TOL
+    torch, dev, g = _gpu()
+    scale = 6.0 if H < 512 else 2.0
+    A, Wm = _lstm_case(g, dtype, H, I, BR, BC, kr, kc, seed=1700 + H, scale=scale)
+    assert g.rnn_sequence_supported(A, None, B)
+    rng = np.random.default_rng(1701 + B)
+    xs = np.stack([_inputs(T, I, dtype, 1710 + b) for b in range(B)], axis=1)           # [T, B, I]
+    bias = (0.2 * rng.standard_normal(4 * H)).astype(np.float32)
+    h0 = np.stack([gen.round_to_storage((0.5 * rng.standard_normal(H)).astype(np.float32), dtype) for _ in range(B)])
+    c0 = rng.standard_normal((B, H)).astype(np.float32)
+    status, hs, hs32, c = _run_lstm_batch(torch, dev, g, A, xs, dtype, bias, h0, c0, pad=pad)
+    assert status == 0
+    for b in range(B):
+        s1, hs1, hs32_1, c1 = _run_lstm(torch, dev, g, A, np.ascontiguousarray(xs[:, b]), dtype, bias, h0[b], c0[b])
+        assert s1 == 0
+        assert np.array_equal(hs32[:, b], hs32_1), f"sequence {b}: fp32 outputs"
+        assert np.array_equal(hs[:, b], hs1), f"sequence {b}: outputs"
+        assert np.array_equal(c[b], c1), f"sequence {b}: cell state"
+    # and one of them against the fp64 reference, so the pair of calls cannot be wrong together
+    b = B - 1
+    hs_ref, c_ref = _lstm_reference(Wm, np.ascontiguousarray(xs[:, b]), dtype, bias, h0[b], c0[b])
+    for t in range(T):
+        assert np.abs(hs32[t, b] - hs_ref[t]).max() <= TOL[dtype] * (1 + t), f"h32 at step {t}"
+    assert np.abs(hs_ref[-1]).max() > 0.05
+    # sequences differ from each other
+    assert not np.array_equal(hs32[:, 0], hs32[:, 1])
+
+
+@pytest.mark.parametrize("dtype", [gen.F16, gen.BF16])
+@pytest.mark.parametrize("H,I,BR,BC,kr,kc,T,B", [
+    (128, 96, 16, 32, 8, 8, 8, 4),
+    (1024, 1024, 32, 32, 8, 12, 5, 8),       # the paper's hidden size (Section 6.1)
+    (512, 160, 32, 16, 4, 16, 6, 7),
+    (1024, 96, 8, 32, 4, 8, 5, 4),           # 128 workgroups per sequence: two sets of two sequences
+    (1024, 96, 8, 32, 4, 8, 4, 7),           # sets of 4 and 3
+])
+def test_gru_sequence_batch_equals_sequences_of_their_own(dtype, H, I, BR, BC, kr, kc, T, B):
+    from helpers import TOL, to_device
+    torch, dev, g = _gpu()
+    Ai, Ah, Wim, Whm = _gru_case(g, dtype, H, I, BR, BC, kr, kc, seed=1800 + H, scale=5.0 if H < 512 else 2.0)
+    assert g.rnn_sequence_supported(Ai, Ah, B)
+    rng = np.random.default_rng(1801 + B)
+    xs = np.stack([_inputs(T, I, dtype, 1810 + b) for b in range(B)], axis=1)
+    bi = (0.2 * rng.standard_normal(3 * H)).astype(np.float32)
+    bh = (0.2 * rng.standard_normal(3 * H)).astype(np.float32)
+    h32_0 = (0.5 * rng.standard_normal((B, H))).astype(np.float32)
+    h0 = np.stack([gen.round_to_storage(h32_0[b], dtype) for b in range(B)])
+    xd = to_device(np.ascontiguousarray(xs.reshape(T * B, I)), dtype)
+    hd = to_device(np.ascontiguousarray(h0), dtype)
+    h32 = torch.from_numpy(h32_0.copy()).to(dev)
+    hs = torch.full((T * B, H), 7.0, dtype=_tdt(torch, dtype), device=dev)
+    hs32 = torch.full((T * B, H), float("nan"), dtype=torch.float32, device=dev)
+    status = torch.full((1,), -1, dtype=torch.int32, device=dev)
+    g.gru_sequence_batch(Ai, Ah, xd, I, T, B, torch.from_numpy(bi).to(dev), torch.from_numpy(bh).to(dev), hd, h32, hs, H, hs32, H,
+                         status, 0, torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    assert int(status.item()) == 0
+    hsn = hs.float().cpu().numpy().reshape(T, B, H)
+    hs32n = hs32.cpu().numpy().reshape(T, B, H)
+    for b in range(B):
+        s1, hs1, hs32_1, last1 = _run_gru(torch, dev, g, Ai, Ah, np.ascontiguousarray(xs[:, b]), dtype, bi, bh, h0[b], h32_0[b])
+        assert s1 == 0
+        assert np.array_equal(hs32n[:, b], hs32_1), f"sequence {b}: fp32 outputs"
+        assert np.array_equal(hsn[:, b], hs1), f"sequence {b}: outputs"
+        assert np.array_equal(h32[b].cpu().numpy(), last1), f"sequence {b}: final state"
+    b = 0
+    h = h32_0[b].astype(np.float64).reshape(-1, 1)
+    for t in range(T):
+        x64 = gen.storage_to_f64(xs[t, b], dtype).reshape(-1, 1)
+        hin = _round(h, dtype) if t else gen.storage_to_f64(h0[b], dtype).reshape(-1, 1)
+        h = gru_ref.step(Wim, Whm, x64, hin, bi, bh, h)[-1]
+        assert np.abs(hs32n[t, b] - h[:, 0]).max() <= TOL[dtype] * (1 + t), f"h32 at step {t}"
+    assert not np.array_equal(hs32n[:, 0], hs32n[:, 1])
+
+
+def test_sequence_batch_limits_and_a_tiny_wait_limit():
+    torch, dev, g = _gpu()
+    dtype, H, I = gen.F16, 256, 64
+    A, _ = _lstm_case(g, dtype, H, I, 32, 32, 8, 12, seed=1900)
+    assert g.rnn_sequence_supported(A, None, 8) and not g.rnn_sequence_supported(A, None, 9)
+    assert not g.rnn_sequence_supported(A, None, 0)
+    rng = np.random.default_rng(1901)
+    B, T = 8, 150
+    xs = np.stack([_inputs(T, I, dtype, 1910 + b) for b in range(B)], axis=1)
+    h0 = np.stack([gen.round_to_storage((0.5 * rng.standard_normal(H)).astype(np.float32), dtype) for _ in range(B)])
+    c0 = rng.standard_normal((B, H)).astype(np.float32)
+    ok = _run_lstm_batch(torch, dev, g, A, xs, dtype, None, h0, c0)
+    assert ok[0] == 0
+    # one re-read allowed: the call completes with the same bits or gives up cleanly, and the next call is right again
+    status, _, hs32, _ = _run_lstm_batch(torch, dev, g, A, xs, dtype, None, h0, c0, max_polls=1)
+    assert status in (0, 1)
+    if status == 0:
+        assert np.array_equal(hs32, ok[2])
+    again = _run_lstm_batch(torch, dev, g, A, xs[:5], dtype, None, h0, c0)
+    assert again[0] == 0 and np.array_equal(again[2], ok[2][:5])
+    xd = torch.zeros((9 * 3, I), dtype=torch.float16, device=dev)
+    hd = torch.zeros((9, H), dtype=torch.float16, device=dev)
+    c = torch.zeros((9, H), dtype=torch.float32, device=dev)
+    hs = torch.zeros((9 * 3, H), dtype=torch.float16, device=dev)
+    st = torch.zeros((1,), dtype=torch.int32, device=dev)
+    with pytest.raises(g.GrimError) as e:
+        g.lstm_sequence_batch(A, xd, I, 3, 9, None, hd, c, hs, H, None, 0, st)
+    assert "UNSUPPORTED" in str(e.value)
+    with pytest.raises(g.GrimError) as e:
+        g.lstm_sequence_batch(A, xd, I, 3, 0, None, hd, c, hs, H, None, 0, st)
+    assert "SHAPE" in str(e.value)
+    torch.cuda.synchronize()
