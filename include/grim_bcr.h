@@ -300,10 +300,11 @@ grim_status grim_bcr_conv2d_plan(const grim_bcr_conv_plan *plan, const void *F_d
  *   h32_dev     optional fp32 copy of h (ldh32); NULL to skip
  * grim_bcr_lstm_step = grim_bcr_spmv(A, xh_dev, ...) (more than 8 columns: grim_bcr_spmm) into
  * gates_dev, then grim_lstm_cell; A must have 4H rows.  Both only enqueue work on hip_stream.
- * With one right-hand side, fp16 / bf16, every block of A keeping the same number of rows and of columns, H a
- * multiple of BR, and h_dev outside the vector xh_dev (write the new h into the NEXT step's input vector), the
- * step is ONE launch: each workgroup computes the four gate rows of BR hidden units and applies the cell before it
- * stores anything (gates_dev still receives the pre-activations).  Otherwise two launches.
+ * With fp16 / bf16, every block of A keeping the same number of rows and of columns, H a multiple of BR, h_dev
+ * outside the vectors xh_dev (write the new h into the NEXT step's input vectors) and batch x H / BR workgroups no
+ * more than the GPU's compute units (batch <= 8 for H = 1024 in 32-row strips), the step is ONE launch: each
+ * workgroup computes the four gate rows of BR hidden units for one column and applies the cell before it stores
+ * anything (gates_dev still receives the pre-activations).  Otherwise two launches.
  * Errors: NULL, SHAPE (batch < 1, H < 1, leading dimension too small, A->M != 4H), DTYPE, DEVICE,
  * UNSUPPORTED.
  */
@@ -340,9 +341,10 @@ grim_status grim_bcr_lstm_step(const grim_bcr_matrix *A, const void *xh_dev, int
  * kernels for W_i and W_h of one shape and block size, on the row-gathering SpMM kernel for 4 to 60
  * columns in multiples of 4)
  * into gi_dev and gh_dev, then grim_gru_cell writing hout_dev (may be hin_dev itself: the cell runs
- * after both products).  With one right-hand side, fp16 / bf16 matrices of one shape, block size and kept counts,
- * H a multiple of BR, and hout_dev overlapping neither x_dev nor hin_dev, the step is ONE launch (products with
- * the cell in their epilogue; gi_dev / gh_dev still receive the products).  Both only enqueue work on hip_stream.  Errors: NULL, SHAPE (rows not 3H on
+ * after both products).  With fp16 / bf16 matrices of one shape, block size and kept counts, H a multiple of BR,
+ * hout_dev overlapping neither x_dev nor hin_dev, and batch x H / BR workgroups no more than the GPU's compute
+ * units, the step is ONE launch (products with the cell in their epilogue, a set of workgroups per column;
+ * gi_dev / gh_dev still receive the products).  Both only enqueue work on hip_stream.  Errors: NULL, SHAPE (rows not 3H on
  * both, Ah->K != H, batch < 1, leading dimension too small), DTYPE (element types differ), DEVICE,
  * UNSUPPORTED (as the products).
  */

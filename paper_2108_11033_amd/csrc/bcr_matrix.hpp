@@ -238,9 +238,12 @@ grim_status launch_spmv(const GemvDesc *table_dev_or_null, const GemvDesc &singl
                         int32_t ukc, int32_t vec, int32_t krmax, int32_t kcmax, const void *x, int64_t x_stride, int32_t batch,
                         int64_t ldx, float *y, int64_t y_stride, int64_t ldy, hipStream_t stream);
 bool spmv_cell_applies(int kind, int64_t M, int64_t K, int32_t BR, int32_t BC, int32_t dtype, int32_t ukr, int32_t ukc, int64_t H);
+// a recurrent step in one launch: the product(s) with the cell in the epilogue, one set of workgroups per column of x
+constexpr int32_t kCellMaxBatch = 32;
+bool spmv_cell_batch_ok(int64_t H, int32_t BR, int32_t batch);   // all sets of workgroups in one round on this GPU?
 grim_status launch_spmv_cell(int kind, const GemvDesc &d1, const GemvDesc *d2, int64_t M, int64_t K, int32_t BR, int32_t BC,
-                             int32_t dtype, int32_t ukr, int32_t ukc, const void *x, int64_t x_stride, int64_t ldx, float *y,
-                             int64_t y_stride, int64_t ldy, const RnnCell &cell, hipStream_t stream);
+                             int32_t dtype, int32_t ukr, int32_t ukc, const void *x, int64_t x_stride, int32_t batch, int64_t ldx,
+                             float *y, int64_t y_stride, int64_t ldy, const RnnCell &cell, hipStream_t stream);
 // a recurrent layer over a whole sequence in one launch (kind 1: LSTM, K1 = I + H; kind 2: GRU, K1 = I, K2 = H), `batch`
 // sequences side by side (1 .. kSeqMaxBatch); exch: at most 2 * batch * H words of 8 bytes; hidden sizes up to kSeqMaxH
 constexpr int64_t kSeqMaxH = 8192;

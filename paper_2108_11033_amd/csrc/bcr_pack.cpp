@@ -973,17 +973,17 @@ grim_status grim_bcr_lstm_step(const grim_bcr_matrix *A, const void *xh_dev, int
     if (A->M % 4 != 0) return GRIM_ERR_SHAPE;
     const int64_t H = A->M / 4;
     if (batch < 1 || ldc < batch || (h_dev && ldh < batch) || (h32_dev && ldh32 < batch)) return GRIM_ERR_SHAPE;
-    if (batch == 1 && A->gemv.present) {
-        // One launch: the cell in the epilogue of the gate product.  Workgroups then write h while others may still
-        // read the input vector, so the new h must not land in the vector this step reads.
+    if (A->gemv.present && spmv_cell_batch_ok(H, A->BR, batch)) {
+        // One launch: the cell in the epilogue of the gate product, a set of workgroups per column of xh.  Workgroups
+        // then write h while others may still read the input vectors, so the new h must not land in what this step reads.
         grim_status st0 = check_call(A, xh_dev, batch, ldx, gates_dev, ldg);
         if (st0 != GRIM_OK) return st0;
         const int esz = dtype_size(A->dtype);
-        const bool aliased = h_dev && ranges_overlap(xh_dev, ((A->K - 1) * ldx + 1) * esz, h_dev, ((H - 1) * ldh + 1) * esz);
+        const bool aliased = h_dev && ranges_overlap(xh_dev, ((A->K - 1) * ldx + batch) * esz, h_dev, ((H - 1) * ldh + batch) * esz);
         if (!aliased) {
             RnnCell cell{A->dev.strip_pos, nullptr, bias_dev, nullptr, c_dev, h_dev, h32_dev, ldc, ldh, ldh32, (int32_t)H, A->dtype};
             st0 = launch_spmv_cell(1, desc_of(A), nullptr, A->M, A->K, A->BR, A->BC, A->dtype, A->gemv.uniform_kr,
-                                   A->gemv.uniform_kc, xh_dev, 0, ldx, gates_dev, 0, ldg, cell, static_cast<hipStream_t>(hip_stream));
+                                   A->gemv.uniform_kc, xh_dev, 0, batch, ldx, gates_dev, 0, ldg, cell, static_cast<hipStream_t>(hip_stream));
             if (st0 != GRIM_ERR_UNSUPPORTED) return st0;
         }
     }
@@ -998,13 +998,13 @@ int32_t grim_bcr_rnn_step_launches(const grim_bcr_matrix *A, const grim_bcr_matr
     if (!A || batch < 1 || !A->on_device) return 0;
     if (!Ah) {
         if (A->M % 4 != 0) return 0;
-        const bool fused = batch == 1 && A->gemv.present &&
+        const bool fused = A->gemv.present && spmv_cell_batch_ok(A->M / 4, A->BR, batch) &&
                            spmv_cell_applies(1, A->M, A->K, A->BR, A->BC, A->dtype, A->gemv.uniform_kr, A->gemv.uniform_kc, A->M / 4);
         return fused ? 1 : 2;
     }
     if (A->M != Ah->M || A->M % 3 != 0 || Ah->K != A->M / 3 || A->dtype != Ah->dtype || !Ah->on_device) return 0;
     const bool same = A->K == Ah->K && A->BR == Ah->BR && A->BC == Ah->BC && A->gemv.present && Ah->gemv.present;
-    const bool fused = batch == 1 && same && A->gemv.uniform_kr == Ah->gemv.uniform_kr && A->gemv.uniform_kc == Ah->gemv.uniform_kc &&
+    const bool fused = spmv_cell_batch_ok(A->M / 3, A->BR, batch) && same && A->gemv.uniform_kr == Ah->gemv.uniform_kr && A->gemv.uniform_kc == Ah->gemv.uniform_kc &&
                        spmv_cell_applies(2, A->M, A->K, A->BR, A->BC, A->dtype, A->gemv.uniform_kr, A->gemv.uniform_kc, A->M / 3);
     if (fused) return 1;
     // both products in one launch (SpMV kernels up to 8 columns when the matrices have one shape; the row-gathering
@@ -1164,19 +1164,19 @@ grim_status grim_bcr_gru_step(const grim_bcr_matrix *Ai, const grim_bcr_matrix *
     const ptrdiff_t xd = static_cast<const char *>(hin_dev) - static_cast<const char *>(x_dev);
     const ptrdiff_t yd = reinterpret_cast<const char *>(gh_dev) - reinterpret_cast<const char *>(gi_dev);
     // (8 columns in 16-byte-aligned rows are quicker on the matrix cores, as for a lone product)
-    if (batch == 1 && Ai->K == Ah->K && Ai->BR == Ah->BR && Ai->BC == Ah->BC && Ai->gemv.present && Ah->gemv.present &&
+    if (spmv_cell_batch_ok(H, Ai->BR, batch) && Ai->K == Ah->K && Ai->BR == Ah->BR && Ai->BC == Ah->BC && Ai->gemv.present && Ah->gemv.present &&
         Ai->gemv.uniform_kr == Ah->gemv.uniform_kr && Ai->gemv.uniform_kc == Ah->gemv.uniform_kc && ldx == ldhin && ldgi == ldgh &&
         xd % esz == 0 && yd % 4 == 0) {
         // One launch: both gate products with the cell in the epilogue.  The new state must not land in the vector
         // the hidden-side product reads (workgroups write it while others may still read).
-        const bool aliased = hout_dev && (ranges_overlap(hin_dev, ((Ah->K - 1) * ldhin + 1) * esz, hout_dev, ((H - 1) * ldhout + 1) * esz) ||
-                                          ranges_overlap(x_dev, ((Ai->K - 1) * ldx + 1) * esz, hout_dev, ((H - 1) * ldhout + 1) * esz));
+        const bool aliased = hout_dev && (ranges_overlap(hin_dev, ((Ah->K - 1) * ldhin + batch) * esz, hout_dev, ((H - 1) * ldhout + batch) * esz) ||
+                                          ranges_overlap(x_dev, ((Ai->K - 1) * ldx + batch) * esz, hout_dev, ((H - 1) * ldhout + batch) * esz));
         if (!aliased) {
             const GemvDesc di = desc_of(Ai), dh = desc_of(Ah);
             RnnCell cell{Ai->dev.strip_pos, Ah->dev.strip_pos, bias_i_dev, bias_h_dev, h32_dev, hout_dev, nullptr, ldh32, ldhout, 0,
                          (int32_t)H, Ai->dtype};
             st = launch_spmv_cell(2, di, &dh, Ai->M, Ai->K, Ai->BR, Ai->BC, Ai->dtype, Ai->gemv.uniform_kr, Ai->gemv.uniform_kc,
-                                  x_dev, xd / esz, ldx, gi_dev, yd / 4, ldgi, cell, static_cast<hipStream_t>(hip_stream));
+                                  x_dev, xd / esz, batch, ldx, gi_dev, yd / 4, ldgi, cell, static_cast<hipStream_t>(hip_stream));
             if (st != GRIM_ERR_UNSUPPORTED) return st;
         }
     }

@@ -46,7 +46,7 @@ def test_lstm_step_in_one_launch(dtype, H, I, BR, BC, kr, kc, ld):
     W = gen.normal_weights(M, K, dtype, seed=901)
     W = gen.round_to_storage(gen.storage_to_f64(W, dtype).astype(np.float32) * 6.0, dtype)
     A = pack_workload(g, W, dtype, mask)
-    assert g.rnn_step_launches(A, None, 1) == 1 and g.rnn_step_launches(A, None, 2) == 2
+    assert g.rnn_step_launches(A, None, 1) == 1 and g.rnn_step_launches(A, None, 8) == 1 and g.rnn_step_launches(A, None, 64) == 2
     rng = np.random.default_rng(902)
     xh = gen.normal_activations(K, 1, dtype, seed=903)
     bias = (0.2 * rng.standard_normal(M)).astype(np.float32)
@@ -101,7 +101,7 @@ def test_gru_step_in_one_launch(dtype, H, BR, kr, kc, x_first):
     Wi = gen.round_to_storage(gen.storage_to_f64(gen.normal_weights(M, H, dtype, seed=912), dtype).astype(np.float32) * scale, dtype)
     Wh = gen.round_to_storage(gen.storage_to_f64(gen.normal_weights(M, H, dtype, seed=913), dtype).astype(np.float32) * scale, dtype)
     Ai, Ah = pack_workload(g, Wi, dtype, mi), pack_workload(g, Wh, dtype, mh)
-    assert g.rnn_step_launches(Ai, Ah, 1) == 1 and g.rnn_step_launches(Ai, Ah, 4) == 2
+    assert g.rnn_step_launches(Ai, Ah, 1) == 1 and g.rnn_step_launches(Ai, Ah, 4) == 1 and g.rnn_step_launches(Ai, Ah, 64) >= 2
     rng = np.random.default_rng(914)
     x = gen.normal_activations(H, 1, dtype, seed=915)
     h0 = (0.5 * rng.standard_normal((H, 1))).astype(np.float32)
@@ -191,3 +191,105 @@ def test_sequences_through_the_fused_steps():
         assert np.abs(h32.cpu().numpy() - h_ref).max() <= 2 * TOL[dtype], f"h at step {t}"
         assert np.abs(hb[(t + 1) % 2].float().cpu().numpy() - h_ref).max() <= 2 * TOL[dtype] + 2.0 ** -10
     assert np.abs(h_ref).max() > 0.05
+
+
+@pytest.mark.parametrize("dtype", [gen.F16, gen.BF16])
+@pytest.mark.parametrize("H,I,BR,kr,kc,B,ld", [(128, 64, 32, 8, 12, 3, 3), (256, 256, 16, 8, 8, 8, 8), (1024, 1024, 32, 8, 12, 32, 40)])
+def test_lstm_step_of_several_columns_in_one_launch(dtype, H, I, BR, kr, kc, B, ld):
+    """A set of workgroups per column while the sets fit the GPU at once: every column gets the bits the one-column step
+    gives; with more columns the step is the product and the cell kernel.  Either way nothing lands outside the B
+    columns and the values agree with the fp64 reference."""
+    from helpers import to_device, pack_workload, TOL
+    torch, dev, g = _gpu()
+    M, K = 4 * H, I + H
+    mask = gen.random_mask(M, K, BR, 32, kr, kc, seed=950 + H)
+    W = gen.normal_weights(M, K, dtype, seed=951)
+    W = gen.round_to_storage(gen.storage_to_f64(W, dtype).astype(np.float32) * (6.0 if H < 512 else 2.0), dtype)
+    A = pack_workload(g, W, dtype, mask)
+    # one launch while all sets of workgroups fit the compute units at once (H / BR workgroups per column)
+    fused = g.rnn_step_launches(A, None, B) == 1
+    assert fused == (B <= 8)
+    rng = np.random.default_rng(952)
+    xh = gen.normal_activations(K, B, dtype, seed=953)
+    bias = (0.2 * rng.standard_normal(M)).astype(np.float32)
+    c0 = rng.standard_normal((H, B)).astype(np.float32)
+    stream = torch.cuda.current_stream()
+    tdt = _tdt(torch, dtype)
+    bd = torch.from_numpy(bias).to(dev)
+    x = torch.zeros((K, ld), dtype=tdt, device=dev); x[:, :B] = to_device(xh, dtype)
+    gates = torch.full((M, ld), float("nan"), dtype=torch.float32, device=dev)
+    c = torch.full((H, ld), 7.0, dtype=torch.float32, device=dev); c[:, :B] = torch.from_numpy(c0).to(dev)
+    h = torch.full((H, ld), 7.0, dtype=tdt, device=dev)
+    h32 = torch.full((H, ld), 7.0, dtype=torch.float32, device=dev)
+    g.lstm_step(A, x, B, ld, gates, ld, bd, c, ld, h, ld, h32, ld, stream)
+    torch.cuda.synchronize()
+    if ld > B:
+        assert torch.isnan(gates[:, B:]).all()
+        for tns in (c, h.float(), h32):
+            assert (tns[:, B:] == 7.0).all()
+    Wm = _masked(W, dtype, mask)
+    for b in sorted({0, 1, B // 2, B - 1}):
+        x1 = x[:, b:b + 1].contiguous()
+        g1 = torch.empty((M, 1), dtype=torch.float32, device=dev)
+        c1 = torch.from_numpy(c0[:, b:b + 1].copy()).to(dev)
+        h1 = torch.empty((H, 1), dtype=tdt, device=dev)
+        h321 = torch.empty((H, 1), dtype=torch.float32, device=dev)
+        g.lstm_step(A, x1, 1, 1, g1, 1, bd, c1, 1, h1, 1, h321, 1, stream)
+        torch.cuda.synchronize()
+        if fused:
+            assert torch.equal(gates[:, b], g1[:, 0]) and torch.equal(c[:, b], c1[:, 0]), f"column {b}"
+            assert torch.equal(h32[:, b], h321[:, 0]) and torch.equal(h[:, b], h1[:, 0]), f"column {b}"
+        _, c_ref, h_ref = lstm_ref.step(Wm, gen.storage_to_f64(xh[:, b:b + 1], dtype), bias, c0[:, b:b + 1].astype(np.float64))
+        assert np.abs(c[:, b:b + 1].cpu().numpy() - c_ref).max() <= TOL[dtype] * max(1.0, np.abs(c_ref).max())
+        assert np.abs(h32[:, b:b + 1].cpu().numpy() - h_ref).max() <= TOL[dtype]
+    assert not torch.equal(h32[:, 0], h32[:, 1])
+
+
+@pytest.mark.parametrize("dtype", [gen.F16, gen.BF16])
+@pytest.mark.parametrize("H,BR,kr,kc,B,ld", [(128, 32, 8, 12, 5, 8), (1024, 32, 8, 12, 8, 8), (1024, 32, 8, 12, 32, 32)])
+def test_gru_step_of_several_columns_in_one_launch(dtype, H, BR, kr, kc, B, ld):
+    from helpers import to_device, pack_workload, TOL
+    torch, dev, g = _gpu()
+    M, BC = 3 * H, 32
+    mi = gen.random_mask(M, H, BR, BC, kr, kc, seed=960)
+    mh = gen.random_mask(M, H, BR, BC, kr, kc, seed=961)
+    scale = 6.0 if H < 512 else 2.0
+    Wi = gen.round_to_storage(gen.storage_to_f64(gen.normal_weights(M, H, dtype, seed=962), dtype).astype(np.float32) * scale, dtype)
+    Wh = gen.round_to_storage(gen.storage_to_f64(gen.normal_weights(M, H, dtype, seed=963), dtype).astype(np.float32) * scale, dtype)
+    Ai, Ah = pack_workload(g, Wi, dtype, mi), pack_workload(g, Wh, dtype, mh)
+    fused = g.rnn_step_launches(Ai, Ah, B) == 1
+    assert fused == (B <= 8)
+    rng = np.random.default_rng(964)
+    xv = gen.normal_activations(H, B, dtype, seed=965)
+    h0 = (0.5 * rng.standard_normal((H, B))).astype(np.float32)
+    bi, bh = (0.1 * rng.standard_normal(M)).astype(np.float32), (0.1 * rng.standard_normal(M)).astype(np.float32)
+    bid, bhd = torch.from_numpy(bi).to(dev), torch.from_numpy(bh).to(dev)
+    stream = torch.cuda.current_stream()
+    tdt = _tdt(torch, dtype)
+    xh = torch.zeros((2, H, ld), dtype=tdt, device=dev)                    # x and the state in one allocation
+    xh[0, :, :B] = to_device(xv, dtype)
+    xh[1, :, :B] = torch.from_numpy(h0).to(dev).to(tdt)
+    gates = torch.full((2, M, ld), float("nan"), dtype=torch.float32, device=dev)
+    h32 = torch.full((H, ld), 7.0, dtype=torch.float32, device=dev); h32[:, :B] = torch.from_numpy(h0).to(dev)
+    hout = torch.full((H, ld), 7.0, dtype=tdt, device=dev)
+    g.gru_step(Ai, Ah, xh[0], ld, xh[1], ld, B, gates[0], ld, gates[1], ld, bid, bhd, h32, ld, hout, ld, stream)
+    torch.cuda.synchronize()
+    Wim, Whm = _masked(Wi, dtype, mi), _masked(Wh, dtype, mh)
+    hin_bits = xh[1, :, :B].float().cpu().numpy().astype(np.float64)
+    for b in sorted({0, 1, B // 2, B - 1}):
+        x1 = torch.zeros((2, H, 1), dtype=tdt, device=dev)
+        x1[0, :, 0] = xh[0, :, b]; x1[1, :, 0] = xh[1, :, b]
+        g1 = torch.empty((2, M, 1), dtype=torch.float32, device=dev)
+        h321 = torch.from_numpy(h0[:, b:b + 1].copy()).to(dev)
+        ho1 = torch.empty((H, 1), dtype=tdt, device=dev)
+        g.gru_step(Ai, Ah, x1[0], 1, x1[1], 1, 1, g1[0], 1, g1[1], 1, bid, bhd, h321, 1, ho1, 1, stream)
+        torch.cuda.synchronize()
+        if fused:
+            assert torch.equal(gates[0, :, b], g1[0, :, 0]) and torch.equal(gates[1, :, b], g1[1, :, 0]), f"column {b}"
+            assert torch.equal(h32[:, b], h321[:, 0]) and torch.equal(hout[:, b], ho1[:, 0]), f"column {b}"
+        _, _, h_ref = gru_ref.step(Wim, Whm, gen.storage_to_f64(xv[:, b:b + 1], dtype), hin_bits[:, b:b + 1], bi, bh,
+                                   h0[:, b:b + 1].astype(np.float64))
+        assert np.abs(h32[:, b:b + 1].cpu().numpy() - h_ref).max() <= 2 * TOL[dtype]
+    if ld > B:
+        assert (h32[:, B:] == 7.0).all() and (hout[:, B:].float() == 7.0).all()
+        assert torch.isnan(gates[:, :, B:]).all()
