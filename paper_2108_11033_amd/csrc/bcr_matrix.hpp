@@ -241,6 +241,8 @@ bool spmv_cell_applies(int kind, int64_t M, int64_t K, int32_t BR, int32_t BC, i
 // a recurrent step in one launch: the product(s) with the cell in the epilogue, one set of workgroups per column of x
 constexpr int32_t kCellMaxBatch = 32;
 bool spmv_cell_batch_ok(int64_t H, int32_t BR, int32_t batch);   // all sets of workgroups in one round on this GPU?
+bool spmv_exact_applies(int32_t dtype, int32_t ukr, int32_t ukc, int64_t K);
+bool spmv_column_sets_ok(int64_t count, int64_t nbr, int32_t batch);   // columns as sets of workgroups of the one-column kernel
 grim_status launch_spmv_cell(int kind, const GemvDesc &d1, const GemvDesc *d2, int64_t M, int64_t K, int32_t BR, int32_t BC,
                              int32_t dtype, int32_t ukr, int32_t ukc, const void *x, int64_t x_stride, int32_t batch, int64_t ldx,
                              float *y, int64_t y_stride, int64_t ldy, const RnnCell &cell, hipStream_t stream);

@@ -720,8 +720,18 @@ grim_status grim_bcr_arrays(const grim_bcr_matrix *A, grim_bcr_view *v) {
 
 // Eight right-hand sides in 16-byte-aligned rows: one (padded) tile of the row-gathering matrix-core
 // kernel beats the vector-ALU SpMV kernel (4096 x 2048 at 10.7x: 8.0 -> 5.6 us; at 4 it does not)
-static bool skinny_on_matrix_cores(const grim_bcr_matrix *A, const void *X_dev, int64_t N, int64_t ldx) {
-    return N == 8 && ldx % 8 == 0 && reinterpret_cast<uintptr_t>(X_dev) % 16 == 0 && gather_applies(A, X_dev, N, ldx);
+// a few columns of a uniformly pruned matrix: the one-column SpMV kernel on a set of workgroups per column, while all
+// sets fit the GPU in one round
+// (`count`: products of this shape in the launch -- 2 for the two sides of a GRU step)
+static bool columns_as_sets(const grim_bcr_matrix *A, int64_t N, int count) {
+    return N > 1 && N <= 8 && gemv_ok(A, N) && A->BR <= 32 && A->BC <= 32 &&
+           spmv_exact_applies(A->dtype, A->gemv.uniform_kr, A->gemv.uniform_kc, A->K) &&
+           spmv_column_sets_ok(count, A->nbr, (int32_t)N);
+}
+
+static bool skinny_on_matrix_cores(const grim_bcr_matrix *A, const void *X_dev, int64_t N, int64_t ldx, int count = 1) {
+    return N == 8 && !columns_as_sets(A, N, count) && ldx % 8 == 0 && reinterpret_cast<uintptr_t>(X_dev) % 16 == 0 &&
+           gather_applies(A, X_dev, N, ldx);
 }
 
 // which kernel family a grim_bcr_spmm_tuned call runs
@@ -1180,8 +1190,8 @@ grim_status grim_bcr_gru_step(const grim_bcr_matrix *Ai, const grim_bcr_matrix *
             if (st != GRIM_ERR_UNSUPPORTED) return st;
         }
     }
-    const bool eight_on_matrix_cores = ldx == ldhin && ldgi == ldgh && skinny_on_matrix_cores(Ai, x_dev, batch, ldx) &&
-                                       skinny_on_matrix_cores(Ah, hin_dev, batch, ldx) &&
+    const bool eight_on_matrix_cores = ldx == ldhin && ldgi == ldgh && skinny_on_matrix_cores(Ai, x_dev, batch, ldx, 2) &&
+                                       skinny_on_matrix_cores(Ah, hin_dev, batch, ldx, 2) &&
                                        gather_pair_applies(Ai, x_dev, Ah, hin_dev, batch, ldx);
     if (!eight_on_matrix_cores && batch <= 8 && Ai->K == Ah->K && Ai->BR == Ah->BR && Ai->BC == Ah->BC && gemv_ok(Ai, batch) &&
         gemv_ok(Ah, batch) && ldx == ldhin && ldgi == ldgh && xd % esz == 0 && yd % 4 == 0) {

@@ -239,9 +239,9 @@ __global__ void __launch_bounds__(exact_waves(CELL) * 64) bcr_spmv_wave_exact(Ge
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     // GRU: both input vectors sit in LDS, the hidden-side one behind the input-side one
     const int xbytes1 = (p.K * ESZ + 15) & ~15, xbytes = CELL == 2 ? 2 * xbytes1 : xbytes1;
-    // with a cell, grid.y counts the right-hand sides: a set of workgroups per column of x, each column on its own
-    // compute units (a layer of 1024 hidden units in 32-row strips is 32 workgroups)
-    const int bq = CELL != 0 ? blockIdx.y : 0;
+    // Several right-hand sides: a set of workgroups per column of x (grid.z; with a cell grid.y), each column on its
+    // own compute units -- a matrix of 128 strips is 32 workgroups
+    const int bq = CELL != 0 ? blockIdx.y : blockIdx.z;
     const int64_t mi = CELL == 2 ? wave / 3 : CELL == 1 ? 0 : blockIdx.y;   // GRU: waves 0-2 take W_i, waves 3-5 W_h
     T *xs = reinterpret_cast<T *>(smem + (CELL == 2 ? (int)mi * xbytes1 : 0));
     char *wl = smem + xbytes + wave * p.wbytes;
@@ -957,7 +957,9 @@ grim_status launch_spmv(const GemvDesc *table, const GemvDesc &single, const Gem
     const bool contiguous = ldx == batch && reinterpret_cast<uintptr_t>(x) % 16 == 0 &&
                             (K * batch * esz) % 16 == 0 && (count == 1 || (x_stride * esz) % 16 == 0);
     p.xvec16 = contiguous ? 1 : 0;
-    if (batch == 1 && (int64_t)K * esz <= 32 * 1024) {
+    // several columns as sets of workgroups of the one-column kernel, while all sets run in one round
+    const bool column_sets = batch > 1 && spmv_column_sets_ok(count, nbr, batch);
+    if ((batch == 1 || column_sets) && (int64_t)K * esz <= 32 * 1024) {
         // uniformly pruned matrix: one wave per strip, one lane per block
         if (ukr > 0 && ukc > 0 && (ukr * ukc * esz) % 16 == 0 && ukr * ukc * esz <= 384) {
             const int nv = ukr * ukc * esz / 16;
@@ -968,8 +970,9 @@ grim_status launch_spmv(const GemvDesc *table, const GemvDesc &single, const Gem
             if (wb < table) wb = table;
             q.wbytes = (int32_t)wb;
             const size_t wlds = (((size_t)K * esz + 15) & ~size_t(15)) + 4 * (size_t)wb;
-            q.sps = wave_strips_per_wave(count, nbr, 8);
-            dim3 wgrid((unsigned)((nbr + 4 * q.sps - 1) / (4 * q.sps)), (unsigned)count);
+            q.sps = batch == 1 ? wave_strips_per_wave(count, nbr, 8) : 1;
+            if (batch > 1) q.xvec16 = 0;                        // a column of x is strided
+            dim3 wgrid((unsigned)((nbr + 4 * q.sps - 1) / (4 * q.sps)), (unsigned)count, (unsigned)batch);
             grim_status st = GRIM_ERR_UNSUPPORTED;
             if (wlds <= 160 * 1024) {
                 switch (dtype) {
@@ -1040,23 +1043,39 @@ bool spmv_cell_applies(int kind, int64_t M, int64_t K, int32_t BR, int32_t BC, i
 // rows; kind 2: GRU, two matrices of 3H rows with the same K, block size and kept counts).  One right-hand side,
 // fp16 / bf16, every block keeping the same kr x kc, H a multiple of BR.  GRIM_ERR_UNSUPPORTED when the matrices do not
 // qualify: the caller then runs the product(s) and the cell as separate launches.
+static int spmv_compute_units() {
+    static std::atomic<int> cached{0};
+    int n = cached.load();
+    if (n > 0) return n;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1) {
+        (void)hipGetLastError();
+        return 0;
+    }
+    cached = n;
+    return n;
+}
+
+// the (kept rows, kept columns) pairs the one-column wave-per-strip kernel is compiled for
+bool spmv_exact_applies(int32_t dtype, int32_t ukr, int32_t ukc, int64_t K) {
+    const int esz = dtype_size(dtype);
+    if (!((ukr == 4 || ukr == 8 || ukr == 16) && (ukc == 4 || ukc == 8 || ukc == 12 || ukc == 16))) return false;
+    return (ukr * ukc * esz) % 16 == 0 && ukr * ukc * esz <= 384 && K * esz <= 32 * 1024;
+}
+
+// `count` products of nbr strips each on `batch` columns as sets of workgroups of the one-column kernel (four strips per
+// workgroup): do all sets fit the GPU in one round?
+bool spmv_column_sets_ok(int64_t count, int64_t nbr, int32_t batch) {
+    return batch >= 1 && batch <= 8 && count * ((nbr + 3) / 4) * batch <= spmv_compute_units();
+}
+
 // A set of H / BR workgroups per column of x pays while all sets run at once, one workgroup per compute unit (a GRU
 // layer of 1024 hidden units: 6.0 us with 1 column, 6.9 us with 8; with 32 columns, four rounds of workgroups, 22.9 us
 // against 8.4 us for the products on the matrix cores followed by the cell kernel).
 bool spmv_cell_batch_ok(int64_t H, int32_t BR, int32_t batch) {
     if (batch < 1 || batch > kCellMaxBatch || BR < 1) return false;
     if (batch == 1) return true;
-    static std::atomic<int> cached{0};
-    int n = cached.load();
-    if (n <= 0) {
-        int dev = 0;
-        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1) {
-            (void)hipGetLastError();
-            return false;
-        }
-        cached = n;
-    }
-    return H / BR * batch <= n;
+    return H / BR * batch <= spmv_compute_units();
 }
 
 grim_status launch_spmv_cell(int kind, const GemvDesc &d1, const GemvDesc *d2, int64_t M, int64_t K, int32_t BR, int32_t BC,

@@ -27,6 +27,8 @@ bool spmv_cell_applies(int, int64_t, int64_t, int32_t, int32_t, int32_t, int32_t
 grim_status launch_spmv_cell(int, const GemvDesc &, const GemvDesc *, int64_t, int64_t, int32_t, int32_t, int32_t, int32_t, int32_t, const void *, int64_t, int32_t, int64_t, float *, int64_t, int64_t, const RnnCell &, hipStream_t) { return GRIM_ERR_DEVICE; }
 grim_status rnn_seq_static_exchange(void **) { return GRIM_ERR_DEVICE; }
 bool spmv_cell_batch_ok(int64_t, int32_t, int32_t) { return false; }
+bool spmv_exact_applies(int32_t, int32_t, int32_t, int64_t) { return false; }
+bool spmv_column_sets_ok(int64_t, int64_t, int32_t) { return false; }
 bool rnn_seq_applies(int, int32_t, int32_t, int32_t, int32_t, int32_t, int64_t, int64_t, int64_t, int64_t, int32_t) { return false; }
 grim_status launch_rnn_seq(int, const GemvDesc &, const GemvDesc *, const int32_t *, const int32_t *, int32_t, int32_t, int32_t, int32_t, int32_t, int64_t, int64_t, int64_t, int64_t, int32_t, int32_t, const void *, int64_t, const void *, const float *, const float *, float *, void *, int64_t, float *, int64_t, void *, int32_t *, uint32_t, hipStream_t) { return GRIM_ERR_DEVICE; }
 grim_status launch_lstm_cell(const float *, int64_t, const float *, float *, int64_t, void *, int32_t, int64_t, float *, int64_t, int64_t, int32_t, hipStream_t) { return GRIM_ERR_DEVICE; }

@@ -58,12 +58,18 @@ def test_c3_lstm_gates_spmv(g, batch):
     y2 = run_spmm(g, A, wl.X, wl.dtype, wl.M, batch)
     assert y2.tobytes() == y.tobytes()
     if batch == 8:
-        # 8 columns in 16-byte-aligned rows ran on the matrix-core kernel; the SpMV kernel takes the same
-        # product when the rows are not 16-byte aligned
+        # 8 columns of this matrix run as 8 sets of workgroups of the one-column kernel (32 workgroups each: all 256 at
+        # once); every column then has the bits the one-column call gives, whatever the leading dimensions
         X = to_device(wl.X, wl.dtype)
-        assert g.spmm_kernel_name(A, X, 8, 8) == "bcr_spmm_gather"
+        assert g.spmm_kernel_name(A, X, 8, 8) == "bcr_spmv"
         y3 = run_spmv(g, A, wl.X, wl.dtype, wl.M, batch, ldx=12, ldy=9)
-        assert_close(y3, yref, S, wl.dtype, "c3 batch=8 on the SpMV kernel")
+        assert y3.tobytes() == y.tobytes()
+        for b in (0, 5, 7):
+            y1 = run_spmv(g, A, np.ascontiguousarray(wl.X[:, b:b + 1]), wl.dtype, wl.M, 1)
+            assert y1[:, 0].tobytes() == np.ascontiguousarray(y[:, b]).tobytes(), f"column {b}"
+        # the same product forced onto the matrix-core kernel (what larger or non-uniform matrices take at 8 columns)
+        y4 = run_spmm(g, A, wl.X, wl.dtype, wl.M, batch, kernel=3)
+        assert_close(y4, yref, S, wl.dtype, "c3 batch=8 on the row-gathering kernel")
 
 
 @pytest.mark.parametrize("layer", range(13))
@@ -574,7 +580,7 @@ def test_kernel_choice_follows_the_cost_model(g):
     assert g.spmm_kernel_name(A, X, 200, 200, kernel=2) == "bcr_spmm_mma"
     assert g.spmm_kernel_name(A, X, 200, 200, tile_n=64) == "bcr_spmm_mma"
     assert g.spmm_kernel_name(A, X, 4, 200) == "bcr_spmv"
-    assert g.spmm_kernel_name(A, X, 8, 200) == "bcr_spmm_gather"      # 8 columns in 16-byte-aligned rows: one padded tile
+    assert g.spmm_kernel_name(A, X, 8, 200) == "bcr_spmv"             # uniform blocks: a set of workgroups per column
     assert g.spmm_kernel_name(A, X, 8, 204) == "bcr_spmv"             # rows 8-byte aligned only
     assert g.spmm_kernel_name(A, X, 199, 200) == "bcr_spmm_mma"       # rows not 8-byte aligned
     assert g.spmm_kernel_name(A, X, 200, 200, kernel=1) == "bcr_spmm_fma"
