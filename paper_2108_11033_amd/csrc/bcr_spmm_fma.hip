@@ -1,6 +1,6 @@
 // Portable SpMM kernel on the vector ALUs for Y = W_bcr * X (Section 3.1: CONV as GEMM on the im2col matrix).
-// Any element type, BR <= 64.  A workgroup of four waves owns one row strip x 64 columns of X; each wave walks a
-// quarter of the strip's blocks in ascending column-block order and the four sums are added in a fixed order;
+// Any element type, BR <= 64.  A workgroup of 4 to 16 waves owns one row strip x 64 columns of X; each wave walks its
+// share of the strip's blocks in ascending column-block order and the waves' sums are added in a fixed order;
 // every gathered X value is loaded once and reused by all kept rows of the block
 // (the load-redundancy elimination of Section 4.4, here a consequence of treating the block as a small dense
 // matrix).
@@ -23,12 +23,16 @@ struct FmaParams {
     int64_t nbc;
 };
 
-constexpr int kFmaWaves = 4;     // waves of a workgroup: they share a strip's column blocks
+// Waves of a workgroup: they share a strip's column blocks.  A block costs a wave three dependent fetches (block
+// header, column indices, values of X), so the more waves the shorter the chain: as many as the partial sums leave
+// room for in 64 KB of LDS (256 x 256 in 16 x 16 blocks, 64 columns: 57 us with one wave per strip, 18 us with 4).
+constexpr int fma_waves(int brcap) { return brcap <= 16 ? 16 : brcap <= 32 ? 8 : 4; }
 constexpr int kFmaBatch = 8;     // gathered values of X in flight per lane
 
 template <int DT, int BRCAP>
-__global__ void __launch_bounds__(kFmaWaves * 64) bcr_spmm_fma(FmaParams p) {
+__global__ void __launch_bounds__(fma_waves(BRCAP) * 64) bcr_spmm_fma(FmaParams p) {
     using T = typename Elem<DT>::type;
+    constexpr int kFmaWaves = fma_waves(BRCAP);
     __shared__ float part[(kFmaWaves - 1) * BRCAP * 64];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -41,7 +45,7 @@ __global__ void __launch_bounds__(kFmaWaves * 64) bcr_spmm_fma(FmaParams p) {
     float acc[BRCAP];
 #pragma unroll
     for (int r = 0; r < BRCAP; ++r) acc[r] = 0.f;
-    // wave w takes the column blocks w, w + 4, ... in ascending order; the waves' sums are added in a fixed order
+    // wave w takes the column blocks w, w + waves, ... in ascending order; the waves' sums are added in a fixed order
     // at the end.  Within a block the gathered values of X are fetched kFmaBatch at a time, all loads of a batch
     // issued before the first is used.
     for (int64_t c = wave; c < p.nbc; c += kFmaWaves) {
@@ -97,9 +101,9 @@ template <int DT>
 static grim_status launch_fma_dt(const FmaParams &p, int32_t BR, int64_t nbr, hipStream_t stream) {
     if ((p.N + 63) / 64 > 65535 || nbr > 0x7fffffff) return GRIM_ERR_SHAPE;
     dim3 grid((unsigned)nbr, (unsigned)((p.N + 63) / 64));
-    if (BR <= 16) hipLaunchKernelGGL((bcr_spmm_fma<DT, 16>), grid, dim3(kFmaWaves * 64), 0, stream, p);
-    else if (BR <= 32) hipLaunchKernelGGL((bcr_spmm_fma<DT, 32>), grid, dim3(kFmaWaves * 64), 0, stream, p);
-    else hipLaunchKernelGGL((bcr_spmm_fma<DT, 64>), grid, dim3(kFmaWaves * 64), 0, stream, p);
+    if (BR <= 16) hipLaunchKernelGGL((bcr_spmm_fma<DT, 16>), grid, dim3(fma_waves(16) * 64), 0, stream, p);
+    else if (BR <= 32) hipLaunchKernelGGL((bcr_spmm_fma<DT, 32>), grid, dim3(fma_waves(32) * 64), 0, stream, p);
+    else hipLaunchKernelGGL((bcr_spmm_fma<DT, 64>), grid, dim3(fma_waves(64) * 64), 0, stream, p);
     return hipGetLastError() == hipSuccess ? GRIM_OK : GRIM_ERR_DEVICE;
 }
 
