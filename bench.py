@@ -331,9 +331,9 @@ def main() -> int:
                     torch.cuda.synchronize()
                     assert int(status.item()) == 0
                     extra[f"c3_b{batch}"][f"lstm_sequence_T{T}_us_per_step"] = tS * 1e6 / T
-                # 2, 4, 8 sequences side by side in the same launch
+                # 2 .. 32 sequences side by side in the same launch (up to 8 as sets of workgroups, then several per workgroup)
                 T = 256
-                for nb in (2, 4, 8):
+                for nb in (2, 4, 8, 16, 32):
                     if not g.rnn_sequence_supported(mats[0], None, nb):
                         continue
                     xs_b = dev_tensor(gen.normal_activations(Ih, T * nb, w3.dtype, seed=13), w3.dtype).t().contiguous()
@@ -386,7 +386,7 @@ def main() -> int:
                 assert int(status.item()) == 0
                 gru[f"sequence_T{T}_us_per_step"] = tS * 1e6 / T
             T = 256
-            for nb in (2, 4, 8):
+            for nb in (2, 4, 8, 16, 32):
                 if not g.rnn_sequence_supported(Agi, Agh, nb):
                     continue
                 xs_b = dev_tensor(gen.normal_activations(Hg, T * nb, "f16", seed=14), "f16").t().contiguous()

@@ -376,14 +376,14 @@ grim_status grim_bcr_gru_step(const grim_bcr_matrix *Ai, const grim_bcr_matrix *
  *              outputs are then undefined.  The caller reads it after synchronising with hip_stream.
  *   max_polls  limit of unsuccessful reads of an exchange word before a workgroup gives up; 0 = default (2^21,
  *              seconds).  Every workgroup leaves the kernel either way.
- * The *_batch forms run `batch` independent sequences (1 .. 8) in the same launch, spread over further sets of
+ * The *_batch forms run `batch` independent sequences (1 .. 32) in the same launch, spread over further sets of
  * H / BR workgroups while the GPU has compute units for them and several per workgroup beyond that:
  * row t * batch + b of xs_dev / hs_dev / hs32_dev belongs to step t of sequence b; h0_dev is batch x H elements,
  * c_dev / h32_dev batch x H fp32, sequence b at offset b * H.  Every sequence gets the bits a call of its own
- * with batch 1 would give.  More than 8, or a workgroup's vectors not fitting its local memory
+ * with batch 1 would give.  More than 32, or a workgroup's vectors not fitting its local memory
  * (sequences per workgroup x (I + H) x 2 bytes plus tables within 160 KB): GRIM_ERR_UNSUPPORTED;
  * grim_bcr_rnn_sequence_batch_supported tells in advance.  The calls without _batch are batch = 1.
- * The exchange buffer holds 2 x 8 x H words of 8 bytes.
+ * The exchange buffer holds 2 x 32 x H words of 8 bytes.
  * Requirements: fp16 / bf16, blocks of at most 32 x 32 all keeping the same (rows, columns)
  * out of {4, 8, 16} x {4, 8, 12, 16} (not 16 x 16), at most 64 column blocks per matrix, H a multiple of BR,
  * H <= 8192 and H / BR workgroups <= the GPU's compute units; otherwise GRIM_ERR_UNSUPPORTED (loop over the step

@@ -249,7 +249,7 @@ grim_status launch_spmv_cell(int kind, const GemvDesc &d1, const GemvDesc *d2, i
 // a recurrent layer over a whole sequence in one launch (kind 1: LSTM, K1 = I + H; kind 2: GRU, K1 = I, K2 = H), `batch`
 // sequences side by side (1 .. kSeqMaxBatch); exch: at most 2 * batch * H words of 8 bytes; hidden sizes up to kSeqMaxH
 constexpr int64_t kSeqMaxH = 8192;
-constexpr int32_t kSeqMaxBatch = 8;
+constexpr int32_t kSeqMaxBatch = 32;
 bool rnn_seq_applies(int kind, int32_t BR, int32_t BC, int32_t dtype, int32_t ukr, int32_t ukc, int64_t K1, int64_t K2,
                      int64_t I, int64_t H, int32_t batch);
 grim_status launch_rnn_seq(int kind, const GemvDesc &d1, const GemvDesc *d2, const int32_t *pos1, const int32_t *pos2,

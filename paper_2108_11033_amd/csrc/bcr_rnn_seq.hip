@@ -1,7 +1,7 @@
 // A recurrent layer over a whole sequence in ONE launch (Section 3.1: an RNN layer is one matrix-vector product per
 // time step; Section 6.3 times the GRU step by step, where every step pays a kernel launch and re-reads the weights).
 //
-// Up to 8 independent sequences run side by side (a batch).  A recurrent layer of 1024 hidden units occupies 32 of the
+// Up to 32 independent sequences run side by side (a batch).  A recurrent layer of 1024 hidden units occupies 32 of the
 // 256 compute units, so the sequences are first spread over further sets of workgroups (grid.y: each set holds its
 // own copy of the weights in registers and exchanges h only within itself, at the pace of a single sequence); when the
 // compute units are used up a workgroup carries several sequences in turn on one set of weights.
@@ -43,7 +43,7 @@ struct SeqParams {
     int32_t nbc1, nbc2;            // column blocks per strip (<= 64 each)
     int32_t K1, K2;                // LSTM: K1 = I + H; GRU: K1 = I, K2 = H
     int32_t I, H, T;
-    int32_t B;                     // sequences side by side (1 .. 8), dealt to grid.y sets of workgroups
+    int32_t B;                     // sequences side by side (1 .. 32), dealt to grid.y sets of workgroups
     int32_t SPB, NQ;               // sequences per workgroup; pairs of them = exchange words per hidden unit
     int32_t xvec16;                // rows of xs can be copied with 16-byte loads
     const void *xs;                // T x B rows of I inputs, row t * B + b
@@ -258,8 +258,11 @@ __global__ void __launch_bounds__(exact_waves(CELL) * 64) bcr_rnn_seq(SeqParams 
         }
 
         // ---- 2. per sequence: the block's KC activations, the products, the strip's row sums.  One table per wave
-        // serves the sequences in turn: a wave's LDS accesses are carried out in order.
-        for (int bb = 0; bb < B; ++bb) {
+        // serves the sequences in turn: a wave's LDS accesses are carried out in order, so the table of the next
+        // sequence can be written while the sums of this one are still on their way.  Blocks small enough for the
+        // registers take two sequences per pass: the two chains of gather -> products -> table -> sums overlap.
+        constexpr int NS = MULTI && KR * KC <= 96 ? 2 : 1;
+        auto products = [&](int bb, float (&acc)[KR]) {
             const T *xbb = xb + bb * xld;
             T xe[KC];
 #pragma unroll
@@ -272,7 +275,6 @@ __global__ void __launch_bounds__(exact_waves(CELL) * 64) bcr_rnn_seq(SeqParams 
                 __builtin_memcpy(&hi, &xe[2 * h + 1], 2);
                 xp[h] = (unsigned int)lo | ((unsigned int)hi << 16);
             }
-            float acc[KR];
 #pragma unroll
             for (int i = 0; i < KR; ++i) {
                 float a = 0.f;
@@ -287,6 +289,10 @@ __global__ void __launch_bounds__(exact_waves(CELL) * 64) bcr_rnn_seq(SeqParams 
                 }
                 acc[i] = a;
             }
+        };
+        // the lane's sums into the table, then the table entries this lane adds up (16 blocks per quarter of the wave
+        // up to 16 strip rows, 32 per half above)
+        auto through_table = [&](const float (&acc)[KR], float2 (&v)[16]) {
             if (rm) {
                 unsigned int m = rm;
 #pragma unroll
@@ -297,35 +303,52 @@ __global__ void __launch_bounds__(exact_waves(CELL) * 64) bcr_rnn_seq(SeqParams 
                 }
             }
             __builtin_amdgcn_wave_barrier();
-            float rs;
-            if (p.BR <= 16) {
-                float s = 0.f;
-                if (r_out < p.BR) {
+#pragma unroll
+            for (int q = 0; q < 16; ++q) v[q] = float2{0.f, 0.f};
+            if (r_out < p.BR) {
+                if (p.BR <= 16) {
                     const float2 *src = reinterpret_cast<const float2 *>(part + r_out * kPartStride + grp * 16);
 #pragma unroll
-                    for (int q = 0; q < 8; ++q) {
-                        const float2 v = src[q];
-                        s += v.x;
-                        s += v.y;
-                    }
-                }
-                const float s2 = s + __shfl_xor(s, 16);
-                rs = s2 + __shfl_xor(s2, 32);
-            } else {
-                float s = 0.f;
-                if (r_out < p.BR) {
+                    for (int q = 0; q < 8; ++q) v[q] = src[q];
+                } else {
                     const float2 *src = reinterpret_cast<const float2 *>(part + r_out * kPartStride + grp * 32);
 #pragma unroll
-                    for (int q = 0; q < 16; ++q) {
-                        const float2 v = src[q];
-                        s += v.x;
-                        s += v.y;
-                    }
+                    for (int q = 0; q < 16; ++q) v[q] = src[q];
                 }
-                rs = s + __shfl_xor(s, 32);
             }
-            if (grp == 0 && r_out < p.BR) gl[(bb * NWV + wave) * 32 + r_out] = rs;
             __builtin_amdgcn_wave_barrier();
+        };
+        // the row's sum in the fixed order of the one-step kernel (adding the zeros of the unused half changes nothing)
+        auto row_sum = [&](const float2 (&v)[16]) {
+            float s = 0.f;
+            if (p.BR <= 16) {
+#pragma unroll
+                for (int q = 0; q < 8; ++q) {
+                    s += v[q].x;
+                    s += v[q].y;
+                }
+                const float s2 = s + __shfl_xor(s, 16);
+                return s2 + __shfl_xor(s2, 32);
+            }
+#pragma unroll
+            for (int q = 0; q < 16; ++q) {
+                s += v[q].x;
+                s += v[q].y;
+            }
+            return s + __shfl_xor(s, 32);
+        };
+        for (int bs = 0; bs < B; bs += NS) {
+            float acc[NS][KR];
+            float2 v[NS][16];
+#pragma unroll
+            for (int s = 0; s < NS; ++s) products(bs + s < B ? bs + s : B - 1, acc[s]);      // (an odd last pass repeats a sequence)
+#pragma unroll
+            for (int s = 0; s < NS; ++s) through_table(acc[s], v[s]);
+#pragma unroll
+            for (int s = 0; s < NS; ++s) {
+                const float rs = row_sum(v[s]);
+                if (bs + s < B && grp == 0 && r_out < p.BR) gl[((bs + s) * NWV + wave) * 32 + r_out] = rs;
+            }
         }
         __syncthreads();
 
@@ -440,7 +463,7 @@ static void seq_split(int64_t H, int BR, int batch, int cus, int *sets, int *per
 
 // kind 1: LSTM (K1 = I + H), kind 2: GRU (K1 = I, K2 = H).  The matrices qualify when they hold two-byte elements in
 // blocks of at most 32 x 32 that all keep one compiled (rows, columns) pair, a strip has at most 64 column blocks
-// (a lane keeps one block), H is a multiple of BR and one workgroup per BR hidden units fits the GPU at once; 1 .. 8
+// (a lane keeps one block), H is a multiple of BR and one workgroup per BR hidden units fits the GPU at once; 1 .. 32
 // sequences side by side whose vectors fit LDS.
 bool rnn_seq_applies(int kind, int32_t BR, int32_t BC, int32_t dtype, int32_t ukr, int32_t ukc, int64_t K1, int64_t K2,
                      int64_t I, int64_t H, int32_t batch) {
@@ -455,6 +478,8 @@ bool rnn_seq_applies(int kind, int32_t BR, int32_t BC, int32_t dtype, int32_t uk
     if (cus < 1 || H / BR > cus) return false;
     int sets, per_wg;
     seq_split(H, BR, batch, cus, &sets, &per_wg);
+    // a cell thread per hidden unit and pair of the workgroup's sequences
+    if ((int64_t)BR * ((per_wg + 1) / 2) > exact_waves(kind) * 64) return false;
     return seq_lds_bytes(kind, K1, K2, BR, per_wg) <= kSeqMaxLds;
 }
 

@@ -300,6 +300,8 @@ def _run_lstm_batch(torch, dev, g, A, xs, dtype, bias, h0, c0, pad=0, max_polls=
     (1024, 64, 8, 32, 4, 8, 4, 5, 0),        # 128 workgroups: two sets, of 3 and 2 sequences
     (2016, 32, 8, 32, 4, 8, 3, 3, 8),        # 252 workgroups: one set carries all three
     (1024, 1024, 8, 32, 4, 8, 3, 8, 3),      # four sequences per workgroup, inputs copied element by element
+    (1024, 1024, 32, 32, 8, 12, 3, 32, 0),   # the LSTM workload at the batch of Section 6.3: 8 sets, four sequences each
+    (1024, 256, 32, 32, 8, 12, 4, 20, 0),    # 7 sets: six of three sequences (two per pass, then one), one of two
 ])
 def test_lstm_sequence_batch_equals_sequences_of_their_own(dtype, H, I, BR, BC, kr, kc, T, B, pad):
     from helpers import TOL
@@ -337,6 +339,7 @@ def test_lstm_sequence_batch_equals_sequences_of_their_own(dtype, H, I, BR, BC, 
     (512, 160, 32, 16, 4, 16, 6, 7),
     (1024, 96, 8, 32, 4, 8, 5, 4),           # 128 workgroups per sequence: two sets of two sequences
     (1024, 96, 8, 32, 4, 8, 4, 7),           # sets of 4 and 3
+    (1024, 1024, 32, 32, 8, 12, 3, 32),      # Section 6.3's batch: 8 sets of four sequences
 ])
 def test_gru_sequence_batch_equals_sequences_of_their_own(dtype, H, I, BR, BC, kr, kc, T, B):
     from helpers import TOL, to_device
@@ -381,7 +384,7 @@ def test_sequence_batch_limits_and_a_tiny_wait_limit():
     torch, dev, g = _gpu()
     dtype, H, I = gen.F16, 256, 64
     A, _ = _lstm_case(g, dtype, H, I, 32, 32, 8, 12, seed=1900)
-    assert g.rnn_sequence_supported(A, None, 8) and not g.rnn_sequence_supported(A, None, 9)
+    assert g.rnn_sequence_supported(A, None, 8) and g.rnn_sequence_supported(A, None, 32) and not g.rnn_sequence_supported(A, None, 33)
     assert not g.rnn_sequence_supported(A, None, 0)
     rng = np.random.default_rng(1901)
     B, T = 8, 150
@@ -397,13 +400,13 @@ def test_sequence_batch_limits_and_a_tiny_wait_limit():
         assert np.array_equal(hs32, ok[2])
     again = _run_lstm_batch(torch, dev, g, A, xs[:5], dtype, None, h0, c0)
     assert again[0] == 0 and np.array_equal(again[2], ok[2][:5])
-    xd = torch.zeros((9 * 3, I), dtype=torch.float16, device=dev)
-    hd = torch.zeros((9, H), dtype=torch.float16, device=dev)
-    c = torch.zeros((9, H), dtype=torch.float32, device=dev)
-    hs = torch.zeros((9 * 3, H), dtype=torch.float16, device=dev)
+    xd = torch.zeros((33 * 3, I), dtype=torch.float16, device=dev)
+    hd = torch.zeros((33, H), dtype=torch.float16, device=dev)
+    c = torch.zeros((33, H), dtype=torch.float32, device=dev)
+    hs = torch.zeros((33 * 3, H), dtype=torch.float16, device=dev)
     st = torch.zeros((1,), dtype=torch.int32, device=dev)
     with pytest.raises(g.GrimError) as e:
-        g.lstm_sequence_batch(A, xd, I, 3, 9, None, hd, c, hs, H, None, 0, st)
+        g.lstm_sequence_batch(A, xd, I, 3, 33, None, hd, c, hs, H, None, 0, st)
     assert "UNSUPPORTED" in str(e.value)
     with pytest.raises(g.GrimError) as e:
         g.lstm_sequence_batch(A, xd, I, 3, 0, None, hd, c, hs, H, None, 0, st)
