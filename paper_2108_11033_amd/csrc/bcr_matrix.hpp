@@ -196,6 +196,10 @@ bool mma_supported(const grim_bcr_matrix *A);
 // wide-tile staged kernel: tile_n 0 = choose; wide_applies: operands and matrix qualify for some tile width
 grim_status launch_spmm_wide(const grim_bcr_matrix *A, const void *X, int64_t N, int64_t ldx, float *Y, int64_t ldy,
                              int32_t tile_n, hipStream_t stream);
+// the same with the columns from wide_cols on computed by row-gathering workgroups in the same launch; UNSUPPORTED
+// (nothing enqueued) when those columns do not take the form of that kernel the launch is built for
+grim_status launch_spmm_wide_with_rest(const grim_bcr_matrix *A, const void *X, int64_t N, int64_t ldx, float *Y, int64_t ldy,
+                                       int32_t tile_n, int64_t wide_cols, hipStream_t stream);
 bool wide_applies(const grim_bcr_matrix *A, const void *X, int64_t N, int64_t ldx, const float *Y, int64_t ldy, int32_t tile_n);
 // best use of the wide-tile kernel: cost (bytes through one compute unit; < 0: does not apply), tile width and the
 // leading columns it should take (N, or whole rounds of workgroups with the rest priced by rest_cost)

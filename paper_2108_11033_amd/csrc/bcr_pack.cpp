@@ -792,10 +792,19 @@ grim_status grim_bcr_spmm_tuned(const grim_bcr_matrix *A, const void *X_dev, int
         }
         case ROUTE_GATHER: return launch_spmm_gather(A, X_dev, N, ldx, Y_dev, ldy, stream);
         case ROUTE_WIDE: {
-            // whole rounds of fat workgroups, the few columns left over on whatever suits them
+            // whole rounds of fat workgroups, the few columns left over on whatever suits them: in the same launch when
+            // that is the row-gathering kernel in the form the combined kernel carries, else in a launch of their own
+            const char *x_rest = static_cast<const char *>(X_dev) + wide_cols * dtype_size(A->dtype);
+            if (wide_cols < N) {
+                int tn2 = 0;
+                int64_t cols2 = 0;
+                if (spmm_route(A, x_rest, N - wide_cols, ldx, Y_dev + wide_cols, ldy, 0, 0, 0, &tn2, &cols2) == ROUTE_GATHER) {
+                    st = launch_spmm_wide_with_rest(A, X_dev, N, ldx, Y_dev, ldy, wide_tn, wide_cols, stream);
+                    if (st != GRIM_ERR_UNSUPPORTED) return st;
+                }
+            }
             st = launch_spmm_wide(A, X_dev, wide_cols, ldx, Y_dev, ldy, wide_tn, stream);
             if (st != GRIM_OK || wide_cols >= N) return st;
-            const char *x_rest = static_cast<const char *>(X_dev) + wide_cols * dtype_size(A->dtype);
             return grim_bcr_spmm_tuned(A, x_rest, N - wide_cols, ldx, Y_dev + wide_cols, ldy, 0, 0, 0, hip_stream);
         }
         case ROUTE_MMA: {

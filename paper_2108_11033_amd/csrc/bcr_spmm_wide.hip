@@ -18,6 +18,7 @@
 // Record format and step layout are those of the staged kernel (bcr_matrix.hpp), cut for these shorter chunks.
 // Accumulation is fp32 in a fixed order, no atomics.
 #include "spmm_wide_kernel.hpp"
+#include "spmm_gather_kernel.hpp"
 
 namespace grim {
 
@@ -96,8 +97,96 @@ static grim_status launch_wide_inst(const WideParams &p, size_t lds, int64_t nwg
     return hipGetLastError() == hipSuccess ? GRIM_OK : GRIM_ERR_DEVICE;
 }
 
+// The wide-tile workgroups and, behind them in the same launch, the row-gathering workgroups of the columns they leave
+// over (eight-wave form, 16-byte-aligned rows).  A launch of its own for those few columns costs a dispatch and runs
+// its short chains of dependent fetches on an otherwise idle GPU; here they start on whichever compute unit finishes
+// its wide workgroup first, while the others are still busy.  (A workgroup of this kernel has twelve waves: the last
+// four have no part in a row-gathering workgroup and wait at its one barrier.)
+template <bool BF16, int BR, int NT>
+__global__ void __launch_bounds__(kWideThreads) bcr_spmm_wide_rest(WideParams wp, GatherParams gp, int wide_wgs) {
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+    if ((int)blockIdx.x < wide_wgs) {
+        wide_body<BF16, BR, NT, false>(wp, lds, blockIdx.x);
+        return;
+    }
+    // (a workgroup number past the last (tile, strip) leaves as a whole: no wave may wait at a barrier others skip)
+    const int vblock = (int)blockIdx.x - wide_wgs;
+    int tile, unit;
+    if (!xcd_map_at(gp.map, vblock, gp.ntiles, &tile, &unit) || unit >= gp.nbr) return;
+    if (threadIdx.x >= kGatherLongWaves * 64) {
+        __syncthreads();
+        return;
+    }
+    gather_body<BF16, true, false, false, true>(gp, lds, vblock, 0);
+}
+
+template <bool BF16, int BR, int NT>
+static grim_status launch_wide_rest_inst(const WideParams &wp, const GatherParams &gp, size_t lds, int64_t wide_wgs, int64_t rest_wgs,
+                                         hipStream_t stream) {
+    auto kern = bcr_spmm_wide_rest<BF16, BR, NT>;
+    static std::atomic<bool> attr_done{false};
+    if (lds > 64 * 1024 && !attr_done) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess) {
+            (void)hipGetLastError();
+            return GRIM_ERR_DEVICE;
+        }
+        attr_done = true;
+    }
+    hipLaunchKernelGGL(kern, dim3((unsigned)(wide_wgs + rest_wgs)), dim3(kWideThreads), lds, stream, wp, gp, (int)wide_wgs);
+    return hipGetLastError() == hipSuccess ? GRIM_OK : GRIM_ERR_DEVICE;
+}
+
+static grim_status wide_setup(const grim_bcr_matrix *A, const void *X, int64_t N, int64_t ldx, float *Y, int64_t ldy, int32_t tile_n,
+                              WideParams *out, int *tn_out, int64_t *nwg_out);
+
 grim_status launch_spmm_wide(const grim_bcr_matrix *A, const void *X, int64_t N, int64_t ldx, float *Y, int64_t ldy,
                              int32_t tile_n, hipStream_t stream) {
+    WideParams p;
+    int tn = 0;
+    int64_t nwg = 0;
+    const grim_status st = wide_setup(A, X, N, ldx, Y, ldy, tile_n, &p, &tn, &nwg);
+    if (st != GRIM_OK) return st;
+    const size_t lds = (size_t)wide_lds_bytes(A, tn);
+    const bool bf = A->dtype == GRIM_BF16;
+    if (A->BR == 16) {
+        if (tn == 128) return bf ? launch_wide_inst<true, 16, 8>(p, lds, nwg, stream) : launch_wide_inst<false, 16, 8>(p, lds, nwg, stream);
+        return bf ? launch_wide_inst<true, 16, 12>(p, lds, nwg, stream) : launch_wide_inst<false, 16, 12>(p, lds, nwg, stream);
+    }
+    return bf ? launch_wide_inst<true, 32, 3>(p, lds, nwg, stream) : launch_wide_inst<false, 32, 3>(p, lds, nwg, stream);
+}
+
+// Columns [0, wide_cols) on the wide-tile workgroups and [wide_cols, N) on row-gathering workgroups, one launch.
+// GRIM_ERR_UNSUPPORTED (nothing enqueued) when the rest does not take the kernel form this launch is built for.
+grim_status launch_spmm_wide_with_rest(const grim_bcr_matrix *A, const void *X, int64_t N, int64_t ldx, float *Y, int64_t ldy,
+                                       int32_t tile_n, int64_t wide_cols, hipStream_t stream) {
+    if (wide_cols <= 0 || wide_cols >= N) return GRIM_ERR_UNSUPPORTED;
+    WideParams wp;
+    int tn = 0;
+    int64_t wide_wgs = 0;
+    grim_status st = wide_setup(A, X, wide_cols, ldx, Y, ldy, tile_n, &wp, &tn, &wide_wgs);
+    if (st != GRIM_OK) return st;
+    GatherParams gp;
+    GatherForm form;
+    const char *x_rest = static_cast<const char *>(X) + wide_cols * dtype_size(A->dtype);
+    st = gather_setup(A, x_rest, N - wide_cols, ldx, Y + wide_cols, ldy, nullptr, nullptr, nullptr, &gp, &form);
+    if (st != GRIM_OK) return st;
+    if (!form.wide || form.narrow || form.solo || !form.eight) return GRIM_ERR_UNSUPPORTED;
+    if (wide_wgs + form.nwg > 0x7fffffff) return GRIM_ERR_SHAPE;
+    const size_t lds = std::max<size_t>((size_t)wide_lds_bytes(A, tn), (size_t)kGatherLongWaves * 8192);
+    const bool bf = A->dtype == GRIM_BF16;
+    if (A->BR == 16) {
+        if (tn == 128)
+            return bf ? launch_wide_rest_inst<true, 16, 8>(wp, gp, lds, wide_wgs, form.nwg, stream)
+                      : launch_wide_rest_inst<false, 16, 8>(wp, gp, lds, wide_wgs, form.nwg, stream);
+        return bf ? launch_wide_rest_inst<true, 16, 12>(wp, gp, lds, wide_wgs, form.nwg, stream)
+                  : launch_wide_rest_inst<false, 16, 12>(wp, gp, lds, wide_wgs, form.nwg, stream);
+    }
+    return bf ? launch_wide_rest_inst<true, 32, 3>(wp, gp, lds, wide_wgs, form.nwg, stream)
+              : launch_wide_rest_inst<false, 32, 3>(wp, gp, lds, wide_wgs, form.nwg, stream);
+}
+
+static grim_status wide_setup(const grim_bcr_matrix *A, const void *X, int64_t N, int64_t ldx, float *Y, int64_t ldy, int32_t tile_n,
+                              WideParams *out, int *tn_out, int64_t *nwg_out) {
     int tn = tile_n;
     if (!tn) {
         // the widest tile that leaves at least 256 workgroups, else the narrowest
@@ -122,13 +211,10 @@ grim_status launch_spmm_wide(const grim_bcr_matrix *A, const void *X, int64_t N,
     p.amax = L.amax[2];
     const int64_t nwg = ((int64_t)p.ntiles + 15) / 16 * 16 * p.ngroups;      // tiles are dealt to the XCDs in pairs
     if (nwg > 0x7fffffff) return GRIM_ERR_SHAPE;
-    const size_t lds = (size_t)wide_lds_bytes(A, tn);
-    const bool bf = A->dtype == GRIM_BF16;
-    if (A->BR == 16) {
-        if (tn == 128) return bf ? launch_wide_inst<true, 16, 8>(p, lds, nwg, stream) : launch_wide_inst<false, 16, 8>(p, lds, nwg, stream);
-        return bf ? launch_wide_inst<true, 16, 12>(p, lds, nwg, stream) : launch_wide_inst<false, 16, 12>(p, lds, nwg, stream);
-    }
-    return bf ? launch_wide_inst<true, 32, 3>(p, lds, nwg, stream) : launch_wide_inst<false, 32, 3>(p, lds, nwg, stream);
+    *out = p;
+    *tn_out = tn;
+    *nwg_out = nwg;
+    return GRIM_OK;
 }
 
 }  // namespace grim

@@ -72,8 +72,9 @@ constexpr unsigned int kBufferFlags = 0x00020000u;
 
 // BR = 16: v_mfma_f32_16x16x32, product taken as (X^T tile) x (W^T fragment): a lane ends with 4 consecutive
 //          columns of one output row.  BR = 32: v_mfma_f32_32x32x16, weights first: a lane holds one column, 16 rows.
-template <bool BF16, int BR, int NT, bool CONV = false>
-__global__ void __launch_bounds__(kWideThreads) bcr_spmm_wide(WideParams p) {
+// (the body as a function of the workgroup's number, so that a kernel can run other workgroups next to these)
+template <bool BF16, int BR, int NT, bool CONV>
+__device__ __forceinline__ void wide_body(const WideParams &p, char *lds, int block_x) {
     constexpr int NSUB = BR == 16 ? 16 : 32;
     constexpr int TN = NT * NSUB;
     constexpr int PITCH = TN * 2 + kWidePad;     // LDS row pitch in bytes
@@ -88,14 +89,13 @@ __global__ void __launch_bounds__(kWideThreads) bcr_spmm_wide(WideParams p) {
     static_assert(NT % NTB == 0, "sub-tiles come in whole batches");
     using Acc = typename std::conditional<BR == 16, f32x4, f32x16>::type;
 
-    extern __shared__ __attribute__((aligned(16))) char lds[];
     const int xbytes = (p.chunk_rows + 1) * PITCH;            // X rows + zero row
     const int stage_bytes = xbytes + p.amax * 16;
 
     // workgroup -> (tile, strip group).  Workgroup ids are dealt to the 8 XCDs round-robin and each XCD has its own L2:
     // all groups of a tile run on the same XCD, and so do tiles 2 k and 2 k + 1 -- a 96-column tile is one and a half
     // 128-byte lines wide, so these two share a line of every row, which the pair then takes from HBM once.
-    const int id = blockIdx.x;
+    const int id = block_x;
     const int xcd = id & 7, slot = id >> 3;
     const int tslot = slot / p.ngroups;
     const int tile = (tslot >> 1) * 16 + xcd * 2 + (tslot & 1);
@@ -574,6 +574,12 @@ __global__ void __launch_bounds__(kWideThreads) bcr_spmm_wide(WideParams p) {
             }
         }
     }
+}
+
+template <bool BF16, int BR, int NT, bool CONV = false>
+__global__ void __launch_bounds__(kWideThreads) bcr_spmm_wide(WideParams p) {
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+    wide_body<BF16, BR, NT, CONV>(p, lds, blockIdx.x);
 }
 
 }  // namespace grim

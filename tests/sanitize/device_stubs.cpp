@@ -9,6 +9,7 @@ grim_status launch_spmm_fma(const grim_bcr_matrix *, const void *, int64_t, int6
 grim_status launch_spmm_mma(const grim_bcr_matrix *, const void *, int64_t, int64_t, float *, int64_t, int32_t, int32_t, hipStream_t) { return GRIM_ERR_DEVICE; }
 bool mma_supported(const grim_bcr_matrix *) { return false; }
 grim_status launch_spmm_wide(const grim_bcr_matrix *, const void *, int64_t, int64_t, float *, int64_t, int32_t, hipStream_t) { return GRIM_ERR_DEVICE; }
+grim_status launch_spmm_wide_with_rest(const grim_bcr_matrix *, const void *, int64_t, int64_t, float *, int64_t, int32_t, int64_t, hipStream_t) { return GRIM_ERR_DEVICE; }
 bool wide_applies(const grim_bcr_matrix *, const void *, int64_t, int64_t, const float *, int64_t, int32_t) { return false; }
 double wide_plan(const grim_bcr_matrix *, const void *, int64_t, int64_t, const float *, int64_t, double (*)(const grim_bcr_matrix *, int64_t), int *, int64_t *) { return -1.0; }
 grim_status launch_spmm_gather(const grim_bcr_matrix *, const void *, int64_t, int64_t, float *, int64_t, hipStream_t, const grim_bcr_matrix *, const void *, float *) { return GRIM_ERR_DEVICE; }
