@@ -100,8 +100,8 @@ static grim_status launch_wide_inst(const WideParams &p, size_t lds, int64_t nwg
 // The wide-tile workgroups and, behind them in the same launch, the row-gathering workgroups of the columns they leave
 // over (eight-wave form, 16-byte-aligned rows).  A launch of its own for those few columns costs a dispatch and runs
 // its short chains of dependent fetches on an otherwise idle GPU; here they start on whichever compute unit finishes
-// its wide workgroup first, while the others are still busy.  (A workgroup of this kernel has twelve waves: the last
-// four have no part in a row-gathering workgroup and wait at its one barrier.)
+// its wide workgroup first, while the others are still busy.  All twelve waves of a workgroup split the strip's steps
+// (the kernel of its own uses eight): at 40-odd steps per strip a wave then has one batch of loads, not two.
 template <bool BF16, int BR, int NT>
 __global__ void __launch_bounds__(kWideThreads) bcr_spmm_wide_rest(WideParams wp, GatherParams gp, int wide_wgs) {
     extern __shared__ __attribute__((aligned(16))) char lds[];
@@ -113,11 +113,7 @@ __global__ void __launch_bounds__(kWideThreads) bcr_spmm_wide_rest(WideParams wp
     const int vblock = (int)blockIdx.x - wide_wgs;
     int tile, unit;
     if (!xcd_map_at(gp.map, vblock, gp.ntiles, &tile, &unit) || unit >= gp.nbr) return;
-    if (threadIdx.x >= kGatherLongWaves * 64) {
-        __syncthreads();
-        return;
-    }
-    gather_body<BF16, true, false, false, true>(gp, lds, vblock, 0);
+    gather_body<BF16, true, false, false, true, kWideMulWaves + kWideFetchWaves>(gp, lds, vblock, 0);
 }
 
 template <bool BF16, int BR, int NT>
@@ -172,7 +168,7 @@ grim_status launch_spmm_wide_with_rest(const grim_bcr_matrix *A, const void *X, 
     if (st != GRIM_OK) return st;
     if (!form.wide || form.narrow || form.solo || !form.eight) return GRIM_ERR_UNSUPPORTED;
     if (wide_wgs + form.nwg > 0x7fffffff) return GRIM_ERR_SHAPE;
-    const size_t lds = std::max<size_t>((size_t)wide_lds_bytes(A, tn), (size_t)kGatherLongWaves * 8192);
+    const size_t lds = std::max<size_t>((size_t)wide_lds_bytes(A, tn), (size_t)(kWideMulWaves + kWideFetchWaves) * 8192);
     const bool bf = A->dtype == GRIM_BF16;
     if (A->BR == 16) {
         if (tn == 128)

@@ -67,9 +67,11 @@ grim_status gather_setup(const grim_bcr_matrix *A, const void *X, int64_t N, int
 // The body of the kernel as a function of the workgroup's number (block_x; block_y: second product of a pair), so that
 // another kernel can run such workgroups next to its own (the wide-tile kernel does, for the columns it leaves over).
 // Its first NWV waves must call it together; `lds` = NWV * 8 KB of workgroup memory.
-template <bool BF16, bool WIDE, bool NARROW, bool SOLO, bool EIGHT>
+// LONGW: the waves that split a strip in the EIGHT form (eight in the kernel of its own; a caller with more waves to
+// spare may pass more: fewer steps per wave, fewer dependent batches).
+template <bool BF16, bool WIDE, bool NARROW, bool SOLO, bool EIGHT, int LONGW = kGatherLongWaves>
 __device__ __forceinline__ void gather_body(const GatherParams &p, char *lds, int block_x, int block_y) {
-    constexpr int NWV = EIGHT ? kGatherLongWaves : 4;          // waves of the workgroup
+    constexpr int NWV = EIGHT ? LONGW : 4;                     // waves of the workgroup
     constexpr int NT = 4, TN = 64, PITCH = 128, CPR = 8;
     constexpr int SB = 4;                        // steps a wave has in flight
     // workgroup -> (tile, stored strip, or four of them for SOLO)
