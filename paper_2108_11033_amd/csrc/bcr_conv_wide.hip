@@ -8,9 +8,11 @@
 // Launches: whole rounds of 256 workgroups at the widest tile; the remaining positions go to the row-gathering
 // convolution on a position range, or to 32-column tiles of this kernel when that does not apply (a partial round of
 // wide tiles would cost as much as a full one).  Small layers stay on the row-gathering convolution kernel.
+#include <algorithm>
 #include <atomic>
 
 #include "spmm_wide_kernel.hpp"
+#include "conv_gather_kernel.hpp"
 
 namespace grim {
 
@@ -71,13 +73,57 @@ static grim_status launch_conv_wide_inst(const WideParams &p, size_t lds, int64_
     return hipGetLastError() == hipSuccess ? GRIM_OK : GRIM_ERR_DEVICE;
 }
 
-// positions [n_begin, n_end) of the batch in tiles of tn (n_end - n_begin >= tn, both multiples of 8)
-static grim_status conv_wide_range(const grim_bcr_matrix *A, WideParams p, int tn, int64_t n_begin, int64_t n_end, hipStream_t stream) {
+// The wide-tile workgroups and, behind them in the same launch, the workgroups of the row-gathering convolution (its
+// twelve-wave form, row numbers split in the kernel) for the positions left over: they start on whichever compute unit
+// is done with its wide workgroup instead of behind a dispatch of their own.
+template <bool BF16, int BR, int NT>
+__global__ void __launch_bounds__(kWideThreads) bcr_conv_wide_rest(WideParams wp, ConvParams cp, int wide_wgs) {
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+    if ((int)blockIdx.x < wide_wgs) {
+        wide_body<BF16, BR, NT, true>(wp, lds, blockIdx.x);
+        return;
+    }
+    conv_gather_body<BF16, false, kConvLongWaves, 0>(cp, lds, (int)blockIdx.x - wide_wgs);
+}
+static_assert(kConvLongWaves * 64 == kWideThreads, "the two bodies share the workgroup's twelve waves");
+
+template <bool BF16, int BR, int NT>
+static grim_status launch_conv_wide_rest_inst(const WideParams &wp, const ConvParams &cp, size_t lds, int64_t wide_wgs, int64_t rest_wgs,
+                                              hipStream_t stream) {
+    auto kern = bcr_conv_wide_rest<BF16, BR, NT>;
+    static std::atomic<bool> attr_done{false};
+    if (lds > 64 * 1024 && !attr_done) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess) {
+            (void)hipGetLastError();
+            return GRIM_ERR_DEVICE;
+        }
+        attr_done = true;
+    }
+    hipLaunchKernelGGL(kern, dim3((unsigned)(wide_wgs + rest_wgs)), dim3(kWideThreads), lds, stream, wp, cp, (int)wide_wgs);
+    return hipGetLastError() == hipSuccess ? GRIM_OK : GRIM_ERR_DEVICE;
+}
+
+// positions [n_begin, n_end) of the batch in tiles of tn (n_end - n_begin >= tn, both multiples of 8); with `rest`, its
+// workgroups (`rest_wgs` of them, `rest_lds` bytes of workgroup memory) behind the wide ones in the same launch
+static grim_status conv_wide_range(const grim_bcr_matrix *A, WideParams p, int tn, int64_t n_begin, int64_t n_end, hipStream_t stream,
+                                   const ConvParams *rest = nullptr, int64_t rest_wgs = 0, size_t rest_lds = 0) {
     p.n_begin = n_begin;
     p.N = n_end;
     p.ntiles = (int32_t)((n_end - n_begin + tn - 1) / tn);
     const int64_t nwg = ((int64_t)p.ntiles + 15) / 16 * 16 * p.ngroups;
-    if (nwg > 0x7fffffff) return GRIM_ERR_SHAPE;
+    if (nwg + rest_wgs > 0x7fffffff) return GRIM_ERR_SHAPE;
+    if (rest) {
+        const size_t lds2 = std::max(conv_wide_lds(A, tn, p.KK), rest_lds);
+        if (lds2 > 160 * 1024) return GRIM_ERR_UNSUPPORTED;
+        const bool bf2 = A->dtype == GRIM_BF16;
+        if (A->BR == 16) {
+            if (tn == 192) return bf2 ? launch_conv_wide_rest_inst<true, 16, 12>(p, *rest, lds2, nwg, rest_wgs, stream) : launch_conv_wide_rest_inst<false, 16, 12>(p, *rest, lds2, nwg, rest_wgs, stream);
+            if (tn == 128) return bf2 ? launch_conv_wide_rest_inst<true, 16, 8>(p, *rest, lds2, nwg, rest_wgs, stream) : launch_conv_wide_rest_inst<false, 16, 8>(p, *rest, lds2, nwg, rest_wgs, stream);
+            return GRIM_ERR_UNSUPPORTED;
+        }
+        if (tn == 96) return bf2 ? launch_conv_wide_rest_inst<true, 32, 3>(p, *rest, lds2, nwg, rest_wgs, stream) : launch_conv_wide_rest_inst<false, 32, 3>(p, *rest, lds2, nwg, rest_wgs, stream);
+        return GRIM_ERR_UNSUPPORTED;
+    }
     const size_t lds = conv_wide_lds(A, tn, p.KK);
     const bool bf = A->dtype == GRIM_BF16;
     if (A->BR == 16) {
@@ -115,8 +161,8 @@ grim_status launch_conv_wide(const grim_bcr_matrix *A, const void *F, int32_t Ci
     const int tn = conv_wide_main_tile(A, p.KK);
     const int64_t per_round = 256 / p.ngroups;
     const int64_t n_main = N / tn / per_round * per_round * tn;
-    grim_status st = conv_wide_range(A, p, tn, 0, n_main, stream);
-    if (st != GRIM_OK || n_main == N) return st;
+    grim_status st;
+    if (n_main == N) return conv_wide_range(A, p, tn, 0, n_main, stream);
     // What is left.  A narrow tile of this kernel walks all K for its 16 strips in one chain of chunk periods whatever
     // its width (16 workgroups: 50 us for the last 512 positions of a 4608-row layer), so a rest of at least 64 positions
     // inside one image goes to the row-gathering convolution, whose workgroups split the strips and K (256 workgroups
@@ -126,9 +172,23 @@ grim_status launch_conv_wide(const grim_bcr_matrix *A, const void *F, int32_t Ci
     if (N - n_main >= 64 && (N - 1) / HW == img_r && A->gather.present) {
         const char *Fi = static_cast<const char *>(F) + img_r * (int64_t)p.f_img_stride * 2;
         char *Yi = static_cast<char *>(Y) + img_r * p.y_img_stride * (odt == GRIM_F32 ? 4 : 2);
+        // in the same launch when the rest takes the form of that kernel the combined kernel carries
+        ConvParams cp;
+        ConvForm form;
+        st = conv_gather_setup(A, Fi, Cin, H, W, kh, kw, bias, relu, Yi, odt, ldy, 1, 1, 0, 0, nullptr, 0, n_main - img_r * HW,
+                               N - img_r * HW, &cp, &form);
+        if (st == GRIM_OK && !form.solo && form.longw == kConvLongWaves && form.mode == 0) {
+            st = conv_wide_range(A, p, tn, 0, n_main, stream, &cp, form.nwg, form.lds);
+            if (st != GRIM_ERR_UNSUPPORTED) return st;
+        }
+        st = conv_wide_range(A, p, tn, 0, n_main, stream);
+        if (st != GRIM_OK) return st;
         st = launch_conv_gather(A, Fi, Cin, H, W, kh, kw, bias, relu, Yi, odt, ldy, stream, 1, 1, 0, 0, nullptr, 0,
                                 n_main - img_r * HW, N - img_r * HW);
         if (st != GRIM_ERR_UNSUPPORTED) return st;
+    } else {
+        st = conv_wide_range(A, p, tn, 0, n_main, stream);
+        if (st != GRIM_OK) return st;
     }
     const int64_t rest0 = N - n_main >= kConvWideRestTile ? n_main : N - kConvWideRestTile;
     return conv_wide_range(A, p, kConvWideRestTile, rest0, N, stream);
