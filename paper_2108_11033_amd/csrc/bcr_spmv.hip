@@ -226,7 +226,8 @@ __global__ void __launch_bounds__(gemv_threads(B), (B == 1 ? 6 : 1)) bcr_spmv(Ge
 //   - each lane scatters its rows' sums to a [strip row][block] table in LDS (zero where a block
 //     does not keep the row); lanes (strip row, group) then add each row's 64 entries in a fixed order.
 // ------------------------------------------------------------------------------------------
-template <int DT, int KR, int KC, int CELL = 0>
+// KEEP: finished strips a lane group holds back before it stores them (see below)
+template <int DT, int KR, int KC, int CELL = 0, int KEEP = 4>
 __global__ void __launch_bounds__(exact_waves(CELL) * 64) bcr_spmv_wave_exact(GemvParams p) {
     using T = typename GElem<DT>::type;
     constexpr int ESZ = (int)sizeof(T);
@@ -308,8 +309,13 @@ __global__ void __launch_bounds__(exact_waves(CELL) * 64) bcr_spmv_wave_exact(Ge
     // since the last store -- and go out kKeep * ngrp strips at a time, or when the wave is done:
     // few, large stores, whole cache lines when the strips are neighbours in the original order
     // as well (as equal-work strips are), and for launches of one round of workgroups all at the
-    // end, where they no longer cut into the stream of weight reads.
-    constexpr int kKeep = 4;
+    // end, where they no longer cut into the stream of weight reads: 16 KB of y scattered into 1.7 MB
+    // of reads per product cost 5 % of the time (the same stores into one cache-resident 16 KB cost
+    // nothing: it is the DRAM turning round for them).  A large batched launch therefore runs as ONE round of
+    // workgroups whose waves walk 16 strips and hold all of them back (KEEP = 8): 0.70 -> 0.745 of
+    // HBM peak on 256 products of 4096 x 2048.  Small launches keep 4: the longer run of predicated stores costs a
+    // lone product 0.2 us.
+    constexpr int kKeep = KEEP;
     float yacc = 0.f, ysum = 0.f, ykeep[kKeep];
     int rowkeep[kKeep], npend = 0;                                // npend: strips kept, not yet stored
     auto store_kept = [&]() {
@@ -564,9 +570,9 @@ __global__ void __launch_bounds__(exact_waves(CELL) * 64) bcr_spmv_wave_exact(Ge
     }
 }
 
-template <int DT, int KR, int KC>
+template <int DT, int KR, int KC, int KEEP>
 static grim_status launch_exact_inst(const GemvParams &p, dim3 grid, size_t lds, hipStream_t stream) {
-    auto kern = bcr_spmv_wave_exact<DT, KR, KC>;
+    auto kern = bcr_spmv_wave_exact<DT, KR, KC, 0, KEEP>;
     static std::atomic<bool> attr_done{false};
     if (lds > 64 * 1024 && !attr_done) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess) {
@@ -614,7 +620,9 @@ static grim_status launch_exact(const GemvParams &p, int kr, int kc, dim3 grid, 
     constexpr int ESZ = (int)sizeof(typename GElem<DT>::type);
 #define GRIM_EXACT(R, C)                                                                   \
     if constexpr ((R) * (C) * ESZ % 16 == 0 && (R) * (C) * ESZ <= 384)                     \
-        if (kr == (R) && kc == (C)) return launch_exact_inst<DT, R, C>(p, grid, lds, stream);
+        if (kr == (R) && kc == (C))                                                        \
+            return p.sps > 8 ? launch_exact_inst<DT, R, C, 8>(p, grid, lds, stream)        \
+                             : launch_exact_inst<DT, R, C, 4>(p, grid, lds, stream);
     GRIM_EXACT(4, 4) GRIM_EXACT(4, 8) GRIM_EXACT(4, 12) GRIM_EXACT(4, 16)
     GRIM_EXACT(8, 4) GRIM_EXACT(8, 8) GRIM_EXACT(8, 12) GRIM_EXACT(8, 16)
     GRIM_EXACT(16, 4) GRIM_EXACT(16, 8) GRIM_EXACT(16, 12)
@@ -913,7 +921,8 @@ static grim_status launch_batch(const GemvParams &p, int batch, int vec, dim3 gr
 }
 
 // Strips a wave of the wave-per-strip kernels walks: 1 when the launch is small, up to max_sps
-// while at least 512 workgroups (two per compute unit) remain.
+// while at least 512 workgroups (two per compute unit) remain -- a large launch then is one round of
+// long-lived workgroups.
 static int wave_strips_per_wave(int64_t count, int64_t nbr, int max_sps) {
     int sps = 1;
     while (sps < max_sps && count * ((nbr + 4 * sps * 2 - 1) / (4 * sps * 2)) >= 512) sps *= 2;
@@ -970,7 +979,7 @@ grim_status launch_spmv(const GemvDesc *table, const GemvDesc &single, const Gem
             if (wb < table) wb = table;
             q.wbytes = (int32_t)wb;
             const size_t wlds = (((size_t)K * esz + 15) & ~size_t(15)) + 4 * (size_t)wb;
-            q.sps = batch == 1 ? wave_strips_per_wave(count, nbr, 8) : 1;
+            q.sps = batch == 1 ? wave_strips_per_wave(count, nbr, 16) : 1;
             if (batch > 1) q.xvec16 = 0;                        // a column of x is strided
             dim3 wgrid((unsigned)((nbr + 4 * q.sps - 1) / (4 * q.sps)), (unsigned)count, (unsigned)batch);
             grim_status st = GRIM_ERR_UNSUPPORTED;
