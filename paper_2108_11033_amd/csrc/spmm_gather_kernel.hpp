@@ -1,5 +1,7 @@
 // Kernel of bcr_spmm_gather.hip as a header: the wide-tile kernel's launcher builds a kernel that runs both.
 #pragma once
+#include <type_traits>
+
 #include "spmm_common.hpp"
 
 namespace grim {
@@ -158,7 +160,40 @@ __device__ __forceinline__ void gather_body(const GatherParams &p, char *lds, in
         nhdr = rows4[(int64_t)s_beg * 8 + rs];
         ndsc = desc2[(int64_t)s_beg * 4 + kgroup];
     }
-    for (int s = s_beg; s < s_end; s += SB) {
+    // The rows of X of a step (pad: bit i set = the lane's i-th k slot is padding and multiplies zeros; kept instead of
+    // the row numbers) and its weights, asked for into a register set
+    struct StepRows { u32x4 rx[4]; unsigned int pad; };
+    auto ask_rows = [&](StepRows &r, const u32x4 &h) {
+        r.pad = 0u;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            r.pad |= h[i] == 0xffffffffu ? 1u << i : 0u;
+            const unsigned int row = h[i] == 0xffffffffu ? 0u : h[i];
+            const unsigned short *src = xcol + (int64_t)row * p.ldx;
+            if constexpr (WIDE) {
+                r.rx[i] = *reinterpret_cast<const u32x4 *>(src);
+            } else {
+                const uint2 a = *reinterpret_cast<const uint2 *>(src);
+                const uint2 b = *reinterpret_cast<const uint2 *>(NARROW ? src + boff : src + 4);
+                r.rx[i] = u32x4{a.x, a.y, b.x, b.y};
+            }
+        }
+    };
+    auto ask_weights = [&](const uint2 &d) {
+        const bool kept = (d.x >> m_row) & 1u;
+        const unsigned int idx = d.y + (kept ? __builtin_popcount(d.x & below) : 0);
+        const i16x8 wv = pay[idx];               // a block's first kept row if this lane's is not kept (zeroed below)
+        return kept ? wv : i16x8{0, 0, 0, 0, 0, 0, 0, 0};
+    };
+    // A batch: SB steps in flight.  The rows of the first step of the NEXT batch are asked for as soon as this batch's
+    // first step has left its registers -- its row numbers came with this batch's -- so that a wave with one step more
+    // than a batch holds (18 steps over 4 waves: 4 + 1) does not pay a whole further round trip for it: the request
+    // travels while the rest of this batch arrives (FIRST: the batch that finds nothing asked for yet).  (With the
+    // request made unconditional in a copy of the batch for "another batch follows", so that every wait counts exactly
+    // the younger loads, the compiler needs 158 registers for what takes 128 here: not done.)
+    StepRows early;
+    auto batch = [&](int s, auto first_tag) {
+        constexpr bool FIRST = decltype(first_tag)::value;
         const int nb = s_end - s < SB ? s_end - s : SB;
         u32x4 hdr[SB];
         uint2 dsc[SB];
@@ -175,26 +210,13 @@ __device__ __forceinline__ void gather_body(const GatherParams &p, char *lds, in
             nhdr = rows4[(int64_t)st * 8 + rs];
             ndsc = desc2[(int64_t)st * 4 + kgroup];
         }
-        u32x4 RX[SB][4];
+        StepRows R[SB];
         i16x8 PW[SB];
+        if constexpr (!FIRST) R[0] = early;      // asked for during the batch before
 #pragma unroll
         for (int u = 0; u < SB; ++u) {
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const unsigned int row = hdr[u][i] == 0xffffffffu ? 0u : hdr[u][i];
-                const unsigned short *src = xcol + (int64_t)row * p.ldx;
-                if constexpr (WIDE) {
-                    RX[u][i] = *reinterpret_cast<const u32x4 *>(src);
-                } else {
-                    const uint2 a = *reinterpret_cast<const uint2 *>(src);
-                    const uint2 b = *reinterpret_cast<const uint2 *>(NARROW ? src + boff : src + 4);
-                    RX[u][i] = u32x4{a.x, a.y, b.x, b.y};
-                }
-            }
-            const bool kept = (dsc[u].x >> m_row) & 1u;
-            const unsigned int idx = dsc[u].y + (kept ? __builtin_popcount(dsc[u].x & below) : 0);
-            const i16x8 wv = pay[idx];           // a block's first kept row if this lane's is not kept (zeroed below)
-            PW[u] = kept ? wv : i16x8{0, 0, 0, 0, 0, 0, 0, 0};
+            if (FIRST || u > 0) ask_rows(R[u], hdr[u]);
+            PW[u] = ask_weights(dsc[u]);
         }
 #pragma unroll
         for (int u = 0; u < SB; ++u) {
@@ -202,10 +224,11 @@ __device__ __forceinline__ void gather_body(const GatherParams &p, char *lds, in
                 char *b = buf + (u & 1) * 4096;
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    const u32x4 v = hdr[u][i] == 0xffffffffu ? u32x4{0u, 0u, 0u, 0u} : RX[u][i];
+                    const u32x4 v = (R[u].pad >> i) & 1u ? u32x4{0u, 0u, 0u, 0u} : R[u].rx[i];
                     *reinterpret_cast<u32x4 *>(b + wr_off[i]) = v;
                 }
                 __builtin_amdgcn_wave_barrier();
+                if (u == 0 && s + SB < s_end) ask_rows(early, nhdr);   // set 0's rows are out of their registers
 #pragma unroll
                 for (int q = 0; q < NT; ++q) {
                     const int cq = q * 2 + cl;
@@ -217,7 +240,9 @@ __device__ __forceinline__ void gather_body(const GatherParams &p, char *lds, in
                 __builtin_amdgcn_wave_barrier();
             }
         }
-    }
+    };
+    if (s_beg < s_end) batch(s_beg, std::true_type{});
+    for (int s = s_beg + SB; s < s_end; s += SB) batch(s, std::false_type{});
 
     if constexpr (SOLO) {
         // the wave owns the whole 16 x 64 tile: D[n][m], lane holds m = lane % 16, n = 4 * (lane / 16) + 0..3 of sub-tile q
