@@ -200,7 +200,7 @@ __device__ __forceinline__ void wide_body(const WideParams &p, char *lds, int bl
         // rows 0 .. K - 1 of the tile's columns: the last valid byte is the end of row K - 1's piece
         const __amdgpu_buffer_rsrc_t xres = __builtin_amdgcn_make_buffer_rsrc(
             const_cast<unsigned short *>(CONV ? p.F : p.X + n0), 0, CONV ? 16 : (int)(((int64_t)(p.K - 1) * p.ldx + TN) * 2), kBufferFlags);
-        u32x4 RX0[SXU], RX1[SXU], RR[SRU];
+        u32x4 RX0[SXU], RX1[SXU];
         // (past the last chunk the last one is fetched again and never stored)
         // where the records of the group's strips in a chunk start and how many 16-byte units they are: two table
         // reads through the scalar cache, asked for at the top of a chunk period and used at its end, so that their
@@ -214,14 +214,26 @@ __device__ __forceinline__ void wide_body(const WideParams &p, char *lds, int bl
             r.units = __builtin_amdgcn_readfirstlane(bp[t1]) - r.b0;
             return r;
         };
-        auto load_records = [&](const RecRange &r, u32x4 (&rr)[SRU]) {
-            const int b0 = r.b0, units = r.units;
-            const __amdgpu_buffer_rsrc_t rres = __builtin_amdgcn_make_buffer_rsrc(
-                const_cast<unsigned char *>(p.recs) + (int64_t)b0 * 16, 0, units * 16, kBufferFlags);
+        // A chunk's records go from global memory straight into the stage's record area (no registers, no LDS store
+        // instructions): a wave's load puts lane l's 16 bytes at the wave's base + 16 l; lanes past the range's end are
+        // masked off and write nothing.  The stage must be free when the load is ISSUED (see the loop below).
+        const int fwave = __builtin_amdgcn_readfirstlane(ft >> 6);
+        auto direct_records = [&](int chunk, const RecRange &r) {
+            char *sbase = lds + (chunk & 1) * stage_bytes + xbytes;
+            const unsigned char *src = p.recs + (int64_t)r.b0 * 16;
 #pragma unroll
-            for (int i = 0; i < SRU; ++i)
-                rr[i] = __builtin_amdgcn_raw_buffer_load_b128(rres, (i * kWideFetchThreads + ft) * 16, 0, 0);
+            for (int i = 0; i < SRU; ++i) {
+                if (i * kWideFetchThreads < r.units) {
+                    const int u = i * kWideFetchThreads + ft;
+                    if (u < r.units)
+                        __builtin_amdgcn_global_load_lds(
+                            (const __attribute__((address_space(1))) void *)(src + (int64_t)u * 16),
+                            (__attribute__((address_space(3))) void *)(sbase + (i * kWideFetchThreads + fwave * 64) * 16), 16, 0, 0);
+                }
+            }
         };
+        // every load of this wave so far has arrived (the direct ones: is in LDS)
+        auto loads_landed = [&]() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); };
         auto load_rows = [&](int chunk, u32x4 (&rx)[SXU]) {
             const int chunk_u = chunk;           // (CONV: rows past the last chunk are past K: any address, never stored)
             chunk = chunk < p.nchunks ? chunk : p.nchunks - 1;
@@ -244,15 +256,6 @@ __device__ __forceinline__ void wide_body(const WideParams &p, char *lds, int bl
                 const int soff = __builtin_amdgcn_readfirstlane((int)((int64_t)chunk * p.chunk_rows * p.ldx * 2));
 #pragma unroll
                 for (int i = 0; i < SXU; ++i) rx[i] = __builtin_amdgcn_raw_buffer_load_b128(xres, xoff[i], soff, 0);
-            }
-        };
-        auto store_records = [&](int chunk, const RecRange &r, const u32x4 (&rr)[SRU]) {
-            char *sbase = lds + (chunk & 1) * stage_bytes + xbytes;
-            const int units = r.units;
-#pragma unroll
-            for (int i = 0; i < SRU; ++i) {
-                const int u = i * kWideFetchThreads + ft;
-                if (u < units) *reinterpret_cast<u32x4 *>(sbase + u * 16) = rr[i];
             }
         };
         auto store_rows = [&](int chunk, const u32x4 (&rx)[SXU]) {
@@ -309,15 +312,16 @@ __device__ __forceinline__ void wide_body(const WideParams &p, char *lds, int bl
             }
         };
         // Chunk c is multiplied from stage c % 2 while chunk c + 1 is written to the other stage (read last in chunk
-        // c - 1).  Rows of X come from HBM: two register sets, a chunk's rows are asked for two chunks before they are
-        // written.  Records come from L2: one set, asked for one chunk ahead, and always BEFORE the rows asked for in
-        // the same period, so that the wait for them (loads return in order) leaves those younger rows in flight.
-        RecRange rcur = rec_range(0), rnxt = rec_range(1);     // rcur: the range of the records in flight
+        // c - 1, so free from the barrier that ends period c - 1).  Rows of X come from HBM: two register sets, a chunk's
+        // rows are asked for two chunks before they are written.  Records come from L2 and go straight into the stage:
+        // asked for at the top of the period that fills the stage, before the rows are written, and waited for (with
+        // everything older, i.e. the rows asked for in the period before) ahead of the period's new row requests,
+        // which therefore stay in flight across the barrier.
+        RecRange rcur = rec_range(0), rnxt = rec_range(1);     // rcur: the range of the next chunk to be filled
+        direct_records(0, rcur);
         load_rows(0, RX0);
-        load_records(rcur, RR);
         store_rows(0, RX0);
-        store_records(0, rcur, RR);
-        load_records(rnxt, RR);
+        loads_landed();
         rcur = rnxt;
         load_rows(1, RX1);
         load_rows(2, RX0);
@@ -325,16 +329,16 @@ __device__ __forceinline__ void wide_body(const WideParams &p, char *lds, int bl
         for (int c = 0; c < p.nchunks; c += 2) {
             rnxt = rec_range(c + 2);
             if constexpr (CONV) fill_rows(c + 4);
-            if (c + 1 < p.nchunks) { store_rows(c + 1, RX1); store_records(c + 1, rcur, RR); }
-            load_records(rnxt, RR);
+            if (c + 1 < p.nchunks) { direct_records(c + 1, rcur); store_rows(c + 1, RX1); }
+            loads_landed();
             rcur = rnxt;
             load_rows(c + 3, RX1);
             __syncthreads();
             if (c + 1 >= p.nchunks) break;
             rnxt = rec_range(c + 3);
             if constexpr (CONV) fill_rows(c + 5);
-            if (c + 2 < p.nchunks) { store_rows(c + 2, RX0); store_records(c + 2, rcur, RR); }
-            load_records(rnxt, RR);
+            if (c + 2 < p.nchunks) { direct_records(c + 2, rcur); store_rows(c + 2, RX0); }
+            loads_landed();
             rcur = rnxt;
             load_rows(c + 4, RX0);
             __syncthreads();
