@@ -22,7 +22,7 @@ NOISE = "is not a recognized feature for this target"
 def _flags():
     return ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-x", "hip",
             "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-            "-Wno-unused-command-line-argument",
+            "-Wno-unused-command-line-argument", "-Wno-inline-asm",
             "-I", os.path.join(ROOT, "include"), "-I", CSRC]
 
 

@@ -215,25 +215,30 @@ __device__ __forceinline__ void wide_body(const WideParams &p, char *lds, int bl
             return r;
         };
         // A chunk's records go from global memory straight into the stage's record area (no registers, no LDS store
-        // instructions): a wave's load puts lane l's 16 bytes at the wave's base + 16 l; lanes past the range's end are
-        // masked off and write nothing.  The stage must be free when the load is ISSUED (see the loop below).
+        // instructions): a wave's load puts lane l's 16 bytes at the wave's base (in M0) + 16 l; lanes past the range's
+        // end are masked off and write nothing.  The stage must be free when the load is ISSUED (see the loop below).
+        // Written as assembly so that the compiler's own wait insertion does not see these loads: it would otherwise
+        // drain every load of the wave before the next LDS store and before every barrier, which ends the rows'
+        // two-chunk prefetch.  The waits it computes for the rows stay valid -- loads it does not know of only make a
+        // wait for an older load stricter -- and the wait for the records themselves is explicit (landed_but_rows).
         const int fwave = __builtin_amdgcn_readfirstlane(ft >> 6);
         auto direct_records = [&](int chunk, const RecRange &r) {
-            char *sbase = lds + (chunk & 1) * stage_bytes + xbytes;
+            const int sbase = (int)(uintptr_t)(__attribute__((address_space(3))) char *)lds + (chunk & 1) * stage_bytes + xbytes;
             const unsigned char *src = p.recs + (int64_t)r.b0 * 16;
 #pragma unroll
             for (int i = 0; i < SRU; ++i) {
                 if (i * kWideFetchThreads < r.units) {
                     const int u = i * kWideFetchThreads + ft;
                     if (u < r.units)
-                        __builtin_amdgcn_global_load_lds(
-                            (const __attribute__((address_space(1))) void *)(src + (int64_t)u * 16),
-                            (__attribute__((address_space(3))) void *)(sbase + (i * kWideFetchThreads + fwave * 64) * 16), 16, 0, 0);
+                        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+                                     :: "s"(sbase + (i * kWideFetchThreads + fwave * 64) * 16), "v"(src + (int64_t)u * 16)
+                                     : "memory", "m0");
                 }
             }
         };
-        // every load of this wave so far has arrived (the direct ones: is in LDS)
-        auto loads_landed = [&]() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); };
+        // every load of this wave has arrived (the direct ones: is in LDS) except the youngest SXU: loads return in
+        // order, and a chunk's rows are at least SXU load instructions, always issued
+        auto landed_but_rows = [&]() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(SXU) : "memory"); };
         auto load_rows = [&](int chunk, u32x4 (&rx)[SXU]) {
             const int chunk_u = chunk;           // (CONV: rows past the last chunk are past K: any address, never stored)
             chunk = chunk < p.nchunks ? chunk : p.nchunks - 1;
@@ -258,10 +263,21 @@ __device__ __forceinline__ void wide_body(const WideParams &p, char *lds, int bl
                 for (int i = 0; i < SXU; ++i) rx[i] = __builtin_amdgcn_raw_buffer_load_b128(xres, xoff[i], soff, 0);
             }
         };
+        // SpMM: where in a stage the thread's units go, held in registers (a store is then one instruction); a unit of
+        // a row past the chunk's last goes into the 32 padding bytes of row 0, which nobody reads -- no branch
+        int saddr[CONV ? 1 : SXU];
+        if constexpr (!CONV) {
+#pragma unroll
+            for (int i = 0; i < SXU; ++i) {
+                const int u = i * kWideFetchThreads + ft;
+                const int row = u / CPR, c = u - row * CPR;
+                saddr[i] = row < p.chunk_rows ? row * PITCH + c * 16 : TN * 2 + (u & 1) * 16;
+            }
+        }
         auto store_rows = [&](int chunk, const u32x4 (&rx)[SXU]) {
             char *sbase = lds + (chunk & 1) * stage_bytes;
             int fo = ft;
-            asm volatile("" : "+v"(fo));         // the unit addresses are recomputed here, not held in registers across the loop
+            if constexpr (CONV) asm volatile("" : "+v"(fo));   // the unit addresses are recomputed here, not held in registers across the loop
             if constexpr (CONV) {
                 // three units at a time: their table entries, then their masks, are read together (two dependent LDS
                 // round trips per group instead of per unit)
@@ -304,11 +320,7 @@ __device__ __forceinline__ void wide_body(const WideParams &p, char *lds, int bl
                 }
             } else {
 #pragma unroll
-                for (int i = 0; i < SXU; ++i) {
-                    const int u = i * kWideFetchThreads + fo;
-                    const int row = u / CPR, c = u - row * CPR;
-                    if (row < p.chunk_rows) *reinterpret_cast<u32x4 *>(sbase + row * PITCH + c * 16) = rx[i];
-                }
+                for (int i = 0; i < SXU; ++i) *reinterpret_cast<u32x4 *>(sbase + saddr[i]) = rx[i];
             }
         };
         // Chunk c is multiplied from stage c % 2 while chunk c + 1 is written to the other stage (read last in chunk
@@ -318,29 +330,31 @@ __device__ __forceinline__ void wide_body(const WideParams &p, char *lds, int bl
         // everything older, i.e. the rows asked for in the period before) ahead of the period's new row requests,
         // which therefore stay in flight across the barrier.
         RecRange rcur = rec_range(0), rnxt = rec_range(1);     // rcur: the range of the next chunk to be filled
-        direct_records(0, rcur);
         load_rows(0, RX0);
-        store_rows(0, RX0);
-        loads_landed();
-        rcur = rnxt;
+        direct_records(0, rcur);
         load_rows(1, RX1);
+        store_rows(0, RX0);
+        rcur = rnxt;
         load_rows(2, RX0);
+        landed_but_rows();
         __syncthreads();
         for (int c = 0; c < p.nchunks; c += 2) {
             rnxt = rec_range(c + 2);
             if constexpr (CONV) fill_rows(c + 4);
             if (c + 1 < p.nchunks) { direct_records(c + 1, rcur); store_rows(c + 1, RX1); }
-            loads_landed();
             rcur = rnxt;
             load_rows(c + 3, RX1);
+            landed_but_rows();
             __syncthreads();
-            if (c + 1 >= p.nchunks) break;
+            // (no way out of the loop here: with one, the waits the compiler computes for the first half assume that the
+            // second half's loads may not have been issued, and drain the rows asked for one period earlier; an odd
+            // number of chunks ends with one idle period, for which the multiplying waves have a barrier of their own)
             rnxt = rec_range(c + 3);
             if constexpr (CONV) fill_rows(c + 5);
             if (c + 2 < p.nchunks) { direct_records(c + 2, rcur); store_rows(c + 2, RX0); }
-            loads_landed();
             rcur = rnxt;
             load_rows(c + 4, RX0);
+            landed_but_rows();
             __syncthreads();
         }
         return;
@@ -514,6 +528,7 @@ __device__ __forceinline__ void wide_body(const WideParams &p, char *lds, int bl
         en = en1;
         __syncthreads();
     }
+    if (p.nchunks & 1) __syncthreads();          // (the fetching waves' periods come in pairs)
 
     // ---- write the strip tiles of Y (original row order); streaming stores: Y is written once and not read here ----
     // CONV: the layer's epilogue (bias, rectifier, rounding to the next layer's element type); column n is position
