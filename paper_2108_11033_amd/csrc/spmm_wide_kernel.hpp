@@ -125,9 +125,9 @@ __device__ __forceinline__ void wide_body(const WideParams &p, char *lds, int bl
             *reinterpret_cast<unsigned int *>(lds + st * stage_bytes + p.chunk_rows * PITCH + w * 4) = 0u;
         }
         // The thread's i-th unit of a chunk is unit i * 256 + ft = (row of the chunk, 16-byte piece of the row).
-        // All loads are buffer loads, always issued: a row past the end of K or a record unit past the end of the
-        // group's records is out of the buffer's range and reads zeros without a fetch -- no conditional load
-        // anywhere, so a wait for an older set of loads never has to assume that the younger set is missing.
+        // The loads of the rows are buffer loads, always issued: a row past the end of K is out of the buffer's range
+        // and reads zeros without a fetch -- no conditional load among them, so a wait for an older set of rows never
+        // has to assume that the younger set is missing.
         // SpMM: byte offset of the unit inside the tile's columns of X.  CONV: element of F at which the unit's 8
         // positions start (image and position of the piece), to which a row of the matrix adds its channel and tap.
         // (CONV: a thread's units i, i + XP, i + 2 XP, ... are the same piece of different rows, so XP offsets do)
