@@ -640,18 +640,23 @@ static grim_status launch_exact(const GemvParams &p, int kr, int kc, dim3 grid, 
 // is not issued just before a wait for loads), coalesced when y is contiguous.
 // x sits in LDS as [k][right-hand side], shared by the workgroup's waves.
 // ------------------------------------------------------------------------------------------
-template <int DT, int KR, int KC>
+// B8 (eight right-hand sides of 2-byte elements): a row of x is 16 bytes, so a lane takes all eight values of a kept
+// column with ONE 16-byte LDS read instead of eight 2-byte ones, and every column block's rows are followed by 16 bytes
+// of padding in LDS: the lanes of such a read (one per block) then start 4 banks apart instead of all in the same bank
+// (rows of 32 blocks x 16 bytes are 512 bytes apart: 2-byte reads at that stride take 64 turns).
+template <int DT, int KR, int KC, bool B8 = false>
 __global__ void __launch_bounds__(512) bcr_spmv_wave_exact_b(GemvParams p) {
     using T = typename GElem<DT>::type;
     constexpr int ESZ = (int)sizeof(T);
+    static_assert(!B8 || ESZ == 2, "eight 2-byte elements are one 16-byte row");
     constexpr int NV = KR * KC * ESZ / 16;       // 16-byte vectors per block
     constexpr int PB = exact_pad_period(NV);     // one vector of padding after every PB blocks (0: none)
     static_assert(KR * KC * ESZ % 16 == 0 && (ESZ == 4 || KC % 2 == 0) && KC <= 32 && KR <= 32, "block shape");
     extern __shared__ __attribute__((aligned(16))) char smem[];
     const int tid = threadIdx.x, lane = tid & 63, nthreads = blockDim.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int B = p.batch;
-    const int xbytes = (p.K * B * ESZ + 15) & ~15;
+    const int B = B8 ? 8 : p.batch;
+    const int xbytes = ((p.K * B + (B8 ? p.nbc * 8 : 0)) * ESZ + 15) & ~15;
     T *xs = reinterpret_cast<T *>(smem);
     char *wl = smem + xbytes + wave * p.wbytes;
     float *part = reinterpret_cast<float *>(wl);                  // reuses the weights' space
@@ -717,17 +722,18 @@ __global__ void __launch_bounds__(512) bcr_spmv_wave_exact_b(GemvParams p) {
             xreg[i] = xsrc[v];
         }
         if (nitems) fetch(0, cur);
+        // (B8: 16-byte unit v is row v of x; one unit of padding behind every block's BC rows)
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int v = tid + i * nthreads;
-            if (v < nxv) reinterpret_cast<gu32x4 *>(xs)[v] = xreg[i];
+            if (v < nxv) reinterpret_cast<gu32x4 *>(xs)[B8 ? v + v / p.BC : v] = xreg[i];
         }
-        for (int v = tid + 4 * nthreads; v < nxv; v += nthreads) reinterpret_cast<gu32x4 *>(xs)[v] = xsrc[v];
+        for (int v = tid + 4 * nthreads; v < nxv; v += nthreads) reinterpret_cast<gu32x4 *>(xs)[B8 ? v + v / p.BC : v] = xsrc[v];
     } else {
         if (nitems) fetch(0, cur);
         for (int e = tid; e < p.K * B; e += nthreads) {
             const int k = e / B;
-            xs[e] = x[(int64_t)k * p.ldx + (e - k * B)];
+            xs[B8 ? e + k / p.BC * 8 : e] = x[(int64_t)k * p.ldx + (e - k * B)];
         }
     }
     __syncthreads();
@@ -754,7 +760,7 @@ __global__ void __launch_bounds__(512) bcr_spmv_wave_exact_b(GemvParams p) {
             for (int j = 0; j < KC; ++j) {
                 const int col = __builtin_ctz(m);                 // KC bits are set
                 m &= m - 1;
-                xo[j] = (xblk * p.BC + col) * B;
+                xo[j] = (xblk * p.BC + col) * B + (B8 ? xblk * 8 : 0);
             }
         }
         gu32x4 w[NV];
@@ -763,10 +769,23 @@ __global__ void __launch_bounds__(512) bcr_spmv_wave_exact_b(GemvParams p) {
 #pragma unroll
             for (int j = 0; j < NV; ++j) w[j] = wb[j];
         }
-        for (int b = 0; b < B; ++b) {
-            T xe[KC];
+        // The [strip row][block] table takes the place of the parked weights.  It is cleared once per strip: every
+        // right-hand side writes the same entries (the rows its block keeps), so the next one overwrites them.
+        __builtin_amdgcn_wave_barrier();                          // every lane holds its block in registers
+        for (int z = lane; z < (p.BR * kPartStride + 3) / 4; z += 64)
+            reinterpret_cast<gu32x4 *>(part)[z] = gu32x4{0u, 0u, 0u, 0u};
+        __builtin_amdgcn_wave_barrier();
+        gu32x4 xv[B8 ? KC : 1];                                   // B8: the eight values of every kept column
+        if constexpr (B8) {
 #pragma unroll
-            for (int j = 0; j < KC; ++j) xe[j] = xs[xo[j] + b];
+            for (int j = 0; j < KC; ++j) xv[j] = *reinterpret_cast<const gu32x4 *>(xs + xo[j]);
+        }
+        auto column = [&](int b, bool odd, int q) {               // right-hand side b = 2 q + odd (B8: q and odd constants)
+            T xe[KC];
+            if constexpr (!B8) {
+#pragma unroll
+                for (int j = 0; j < KC; ++j) xe[j] = xs[xo[j] + b];
+            }
             float acc[KR];
             if constexpr (DT == GRIM_F32) {
 #pragma unroll
@@ -784,18 +803,23 @@ __global__ void __launch_bounds__(512) bcr_spmv_wave_exact_b(GemvParams p) {
                 unsigned int xp[KC / 2];
 #pragma unroll
                 for (int h = 0; h < KC / 2; ++h) {
-                    unsigned short lo, hi;
-                    __builtin_memcpy(&lo, &xe[2 * h], 2);
-                    __builtin_memcpy(&hi, &xe[2 * h + 1], 2);
-                    xp[h] = (unsigned int)lo | ((unsigned int)hi << 16);
+                    if constexpr (B8) {
+                        // halves b of two kept columns' dwords q, side by side (low: column 2 h, high: column 2 h + 1)
+                        xp[h] = __builtin_amdgcn_perm(xv[2 * h + 1][q], xv[2 * h][q], odd ? 0x07060302u : 0x05040100u);
+                    } else {
+                        unsigned short lo, hi;
+                        __builtin_memcpy(&lo, &xe[2 * h], 2);
+                        __builtin_memcpy(&hi, &xe[2 * h + 1], 2);
+                        xp[h] = (unsigned int)lo | ((unsigned int)hi << 16);
+                    }
                 }
 #pragma unroll
                 for (int i = 0; i < KR; ++i) {
                     float a = 0.f;
 #pragma unroll
                     for (int h = 0; h < KC / 2; ++h) {
-                        const int q = i * (KC / 2) + h;
-                        const unsigned int wd = w[q >> 2][q & 3];
+                        const int qq = i * (KC / 2) + h;
+                        const unsigned int wd = w[qq >> 2][qq & 3];
                         if constexpr (DT == GRIM_F16)
                             a = __builtin_amdgcn_fdot2(__builtin_bit_cast(gh2, wd), __builtin_bit_cast(gh2, xp[h]), a, false);
                         else
@@ -804,10 +828,6 @@ __global__ void __launch_bounds__(512) bcr_spmv_wave_exact_b(GemvParams p) {
                     acc[i] = a;
                 }
             }
-            __builtin_amdgcn_wave_barrier();                      // every lane holds its block in registers
-            for (int z = lane; z < (p.BR * kPartStride + 3) / 4; z += 64)
-                reinterpret_cast<gu32x4 *>(part)[z] = gu32x4{0u, 0u, 0u, 0u};
-            __builtin_amdgcn_wave_barrier();
             if (rm) {
                 unsigned int m = rm;
 #pragma unroll
@@ -846,7 +866,16 @@ __global__ void __launch_bounds__(512) bcr_spmv_wave_exact_b(GemvParams p) {
                 rs = s + __shfl_xor(s, 32);
             }
             if (grp == 0 && r_out < p.BR) ybuf[b * 32 + r_out] = rs;
-            __builtin_amdgcn_wave_barrier();                      // table consumed before it is zeroed again
+            __builtin_amdgcn_wave_barrier();                      // table consumed before the next right-hand side writes it
+        };
+        if constexpr (B8) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                column(2 * q, false, q);
+                column(2 * q + 1, true, q);
+            }
+        } else {
+            for (int b = 0; b < B; ++b) column(b, false, 0);
         }
         pend_row = cur.srow;
         cur = nxt;
@@ -854,9 +883,13 @@ __global__ void __launch_bounds__(512) bcr_spmv_wave_exact_b(GemvParams p) {
     flush();
 }
 
-template <int DT, int KR, int KC>
+// kept elements per block up to which the eight-column form (all of x's values of a block in registers) fits the
+// register file without spills
+constexpr int kExactB8MaxBlock = 96;
+
+template <int DT, int KR, int KC, bool B8>
 static grim_status launch_exact_b_inst(const GemvParams &p, dim3 grid, int threads, size_t lds, hipStream_t stream) {
-    auto kern = bcr_spmv_wave_exact_b<DT, KR, KC>;
+    auto kern = bcr_spmv_wave_exact_b<DT, KR, KC, B8>;
     static std::atomic<bool> attr_done{false};
     if (lds > 64 * 1024 && !attr_done) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess) {
@@ -874,7 +907,11 @@ static grim_status launch_exact_b(const GemvParams &p, int kr, int kc, dim3 grid
     constexpr int ESZ = (int)sizeof(typename GElem<DT>::type);
 #define GRIM_EXACT(R, C)                                                                   \
     if constexpr ((R) * (C) * ESZ % 16 == 0 && (R) * (C) * ESZ <= 384)                     \
-        if (kr == (R) && kc == (C)) return launch_exact_b_inst<DT, R, C>(p, grid, threads, lds, stream);
+        if (kr == (R) && kc == (C)) {                                                      \
+            if constexpr ((R) * (C) <= kExactB8MaxBlock)                                       \
+                if (p.batch == 8) return launch_exact_b_inst<DT, R, C, true>(p, grid, threads, lds, stream); \
+            return launch_exact_b_inst<DT, R, C, false>(p, grid, threads, lds, stream);        \
+        }
     GRIM_EXACT(4, 4) GRIM_EXACT(4, 8) GRIM_EXACT(4, 12) GRIM_EXACT(4, 16)
     GRIM_EXACT(8, 4) GRIM_EXACT(8, 8) GRIM_EXACT(8, 12) GRIM_EXACT(8, 16)
     GRIM_EXACT(16, 4) GRIM_EXACT(16, 8) GRIM_EXACT(16, 12)
@@ -1005,7 +1042,9 @@ grim_status launch_spmv(const GemvDesc *table, const GemvDesc &single, const Gem
         if (wb < table) wb = table;
         wb += 8 * 32 * 4;                                       // the wave's result tile
         q.wbytes = (int32_t)wb;
-        const size_t wlds = (((size_t)K * batch * esz + 15) & ~size_t(15)) + nw * (size_t)wb;
+        // (eight right-hand sides: 16 bytes of padding behind every column block's rows of x)
+        const bool b8 = batch == 8 && ukr * ukc <= kExactB8MaxBlock;
+        const size_t wlds = ((((size_t)K * batch + (b8 ? (size_t)(K / BC) * 8 : 0)) * esz + 15) & ~size_t(15)) + nw * (size_t)wb;
         int sps = 1;
         while (sps < 4 && (int64_t)count * ((nbr + nw * sps * 2 - 1) / (nw * sps * 2)) >= 512) sps *= 2;
         q.sps = sps;
