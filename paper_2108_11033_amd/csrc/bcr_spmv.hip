@@ -239,7 +239,8 @@ __global__ void __launch_bounds__(exact_waves(CELL) * 64) bcr_spmv_wave_exact(Ge
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     // GRU: both input vectors sit in LDS, the hidden-side one behind the input-side one
-    const int xbytes1 = (p.K * ESZ + 15) & ~15, xbytes = CELL == 2 ? 2 * xbytes1 : xbytes1;
+    const int xsk = exact_x_skew(p.BC, ESZ);     // elements of padding behind every block's part of x (0 or 4 bytes)
+    const int xbytes1 = ((p.K + p.nbc * xsk) * ESZ + 15) & ~15, xbytes = CELL == 2 ? 2 * xbytes1 : xbytes1;
     // Several right-hand sides: a set of workgroups per column of x (grid.z; with a cell grid.y), each column on its
     // own compute units -- a matrix of 128 strips is 32 workgroups
     const int bq = CELL != 0 ? blockIdx.y : blockIdx.z;
@@ -349,7 +350,17 @@ __global__ void __launch_bounds__(exact_waves(CELL) * 64) bcr_spmv_wave_exact(Ge
         const GRIM_GLOBAL gu32x4 *xsrc = reinterpret_cast<const GRIM_GLOBAL gu32x4 *>(x);
         const GRIM_GLOBAL gu32x4 *xsrc2 = reinterpret_cast<const GRIM_GLOBAL gu32x4 *>(x + p.x_stride);
         auto src_of = [&](int v) { return v < nxv1 ? xsrc + v : xsrc2 + (v - nxv1); };
-        auto dst_of = [&](int v) { return reinterpret_cast<gu32x4 *>(reinterpret_cast<char *>(xs0) + (v < nxv1 ? 0 : xbytes1)) + (v < nxv1 ? v : v - nxv1); };
+        // unit u of a vector goes 4 bytes further for every block before its own: four 4-byte stores
+        const int upb = p.BC * ESZ / 16;                           // 16-byte units per block (padded layout only)
+        auto put = [&](int v, const gu32x4 &val) {
+            const int u = v < nxv1 ? v : v - nxv1;
+            unsigned int *dst = reinterpret_cast<unsigned int *>(reinterpret_cast<char *>(xs0) + (v < nxv1 ? 0 : xbytes1)) +
+                                u * 4 + (xsk ? u / upb : 0);
+            dst[0] = val[0];
+            dst[1] = val[1];
+            dst[2] = val[2];
+            dst[3] = val[3];
+        };
         gu32x4 xreg[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i)
@@ -362,14 +373,18 @@ __global__ void __launch_bounds__(exact_waves(CELL) * 64) bcr_spmv_wave_exact(Ge
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int v = tid + i * NTHR;
-            if (v < nxv) *dst_of(v) = xreg[i];
+            if (v < nxv) put(v, xreg[i]);
         }
-        for (int v = tid + 4 * NTHR; v < nxv; v += NTHR) *dst_of(v) = *src_of(v);
+        for (int v = tid + 4 * NTHR; v < nxv; v += NTHR) {
+            const gu32x4 val = *src_of(v);
+            put(v, val);
+        }
     } else {
         if (nitems) fetch(0, cur);
         // strided vector(s), element by element: eight loads per thread in flight, then their stores
         const int nel = p.K * nvecs;
         T *xs1 = reinterpret_cast<T *>(reinterpret_cast<char *>(xs0) + xbytes1);
+        const int bc_shift = (p.BC & (p.BC - 1)) == 0 ? __builtin_ctz(p.BC) : -1;   // (a power of two: no division per element)
         for (int e0 = tid; e0 < nel; e0 += 8 * NTHR) {
             T v[8];
 #pragma unroll
@@ -381,7 +396,10 @@ __global__ void __launch_bounds__(exact_waves(CELL) * 64) bcr_spmv_wave_exact(Ge
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
                 const int e = e0 + i * NTHR;
-                if (e < nel) (e < p.K ? xs0 + e : xs1 + (e - p.K))[0] = v[i];
+                if (e < nel) {
+                    const int k = e < p.K ? e : e - p.K;
+                    (e < p.K ? xs0 : xs1)[k + (xsk ? (bc_shift >= 0 ? k >> bc_shift : k / p.BC) * xsk : 0)] = v[i];
+                }
             }
         }
     }
@@ -418,7 +436,7 @@ __global__ void __launch_bounds__(exact_waves(CELL) * 64) bcr_spmv_wave_exact(Ge
         {
             int xblk = cur.c0 + lane;
             xblk = xblk < p.nbc ? xblk : p.nbc - 1;
-            const T *xb = xs + xblk * p.BC;
+            const T *xb = xs + xblk * (p.BC + xsk);
             unsigned int m = cm;
 #pragma unroll
             for (int j = 0; j < KC; ++j) {
@@ -1015,7 +1033,7 @@ grim_status launch_spmv(const GemvDesc *table, const GemvDesc &single, const Gem
             const int64_t table = ((int64_t)BR * kPartStride * 4 + 15) & ~int64_t(15);
             if (wb < table) wb = table;
             q.wbytes = (int32_t)wb;
-            const size_t wlds = (((size_t)K * esz + 15) & ~size_t(15)) + 4 * (size_t)wb;
+            const size_t wlds = ((((size_t)K + (size_t)(K / BC) * exact_x_skew(BC, esz)) * esz + 15) & ~size_t(15)) + 4 * (size_t)wb;
             q.sps = batch == 1 ? wave_strips_per_wave(count, nbr, 16) : 1;
             if (batch > 1) q.xvec16 = 0;                        // a column of x is strided
             dim3 wgrid((unsigned)((nbr + 4 * q.sps - 1) / (4 * q.sps)), (unsigned)count, (unsigned)batch);
@@ -1083,7 +1101,7 @@ bool spmv_cell_applies(int kind, int64_t M, int64_t K, int32_t BR, int32_t BC, i
     int64_t wb = (int64_t)exact_region_vectors(nv) * 16;
     const int64_t table = ((int64_t)BR * kPartStride * 4 + 15) & ~int64_t(15);
     if (wb < table) wb = table;
-    const int64_t lds = (kind == 2 ? 2 : 1) * ((K * esz + 15) & ~int64_t(15)) + exact_waves(kind) * wb;
+    const int64_t lds = (kind == 2 ? 2 : 1) * (((K + K / BC * exact_x_skew(BC, esz)) * esz + 15) & ~int64_t(15)) + exact_waves(kind) * wb;
     return lds <= 160 * 1024;
 }
 
@@ -1154,7 +1172,7 @@ grim_status launch_spmv_cell(int kind, const GemvDesc &d1, const GemvDesc *d2, i
                 (kind == 1 || (x_stride * esz) % 16 == 0)) ? 1 : 0;
     p.cell = cell;
     const int nvecs = kind == 2 ? 2 : 1, nw = exact_waves(kind);
-    const size_t lds = nvecs * (((size_t)K * esz + 15) & ~size_t(15)) + nw * (size_t)wb;
+    const size_t lds = nvecs * ((((size_t)K + (size_t)(K / BC) * exact_x_skew(BC, esz)) * esz + 15) & ~size_t(15)) + nw * (size_t)wb;
     if (lds > 160 * 1024) return GRIM_ERR_UNSUPPORTED;
     const dim3 grid((unsigned)groups, (unsigned)batch);
     if (kind == 1)

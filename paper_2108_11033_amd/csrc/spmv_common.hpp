@@ -90,6 +90,13 @@ typedef __bf16 gb2 __attribute__((ext_vector_type(2)));
 
 constexpr int kPartStride = 66;                    // floats per strip row of the partial table (wave-per-strip kernels)
 
+// Wave-per-strip kernels, one right-hand side: lane l gathers the kept activations of column block l from the LDS copy of
+// x.  Blocks of BC elements are a multiple of 16 bytes apart (32 fp16: 64 bytes), so the lanes of such a 2-byte read fall
+// on every fourth, eighth or sixteenth bank only and take turns.  With 4 bytes of padding behind every block's part of
+// x the blocks are an odd number of banks apart.  (Blocks whose size is no multiple of 16 bytes keep the plain layout:
+// a 16-byte unit of the copy may not straddle two blocks.)  Elements of padding per block:
+__host__ __device__ inline int exact_x_skew(int BC, int esz) { return (BC * esz) % 16 == 0 ? 4 / esz : 0; }
+
 // Lanes read their blocks with 16-byte loads at a common offset from bases NV vectors apart;
 // 16 such vectors span the LDS banks.  When NV shares a factor g with 16 the bases of 16
 // neighbouring lanes fall on only 16/g distinct bank groups, so one vector of padding goes
