@@ -24,8 +24,8 @@ struct FmaParams {
 };
 
 // Waves of a workgroup: they share a strip's column blocks.  A block costs a wave three dependent fetches (block
-// header, column indices, values of X), so the more waves the shorter the chain: as many as the partial sums leave
-// room for in 64 KB of LDS (256 x 256 in 16 x 16 blocks, 64 columns: 57 us with one wave per strip, 18 us with 4).
+// header, column indices, values of X), so the more waves the shorter the chain: as many as their sums leave room
+// for in 64 KB of LDS (256 x 256 in 16 x 16 blocks, 64 columns: 57 us with one wave per strip, 18 us with 4).
 constexpr int fma_waves(int brcap) { return brcap <= 16 ? 16 : brcap <= 32 ? 8 : 4; }
 constexpr int kFmaBatch = 8;     // gathered values of X in flight per lane
 
@@ -33,7 +33,7 @@ template <int DT, int BRCAP>
 __global__ void __launch_bounds__(fma_waves(BRCAP) * 64) bcr_spmm_fma(FmaParams p) {
     using T = typename Elem<DT>::type;
     constexpr int kFmaWaves = fma_waves(BRCAP);
-    __shared__ float part[(kFmaWaves - 1) * BRCAP * 64];
+    __shared__ float part[kFmaWaves * BRCAP * 64];       // [wave][strip row][column]: 64 KB
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int64_t t = blockIdx.x;                        // stored strip
@@ -42,12 +42,14 @@ __global__ void __launch_bounds__(fma_waves(BRCAP) * 64) bcr_spmm_fma(FmaParams 
     const int64_t nc = live ? n : p.N - 1;               // idle lanes re-read the last column
     const T *X = static_cast<const T *>(p.X);
     const T *W = static_cast<const T *>(p.weights);
-    float acc[BRCAP];
+    float *mine = part + (wave * BRCAP) * 64 + lane;     // this lane's column of the wave's sums, one entry per strip row
 #pragma unroll
-    for (int r = 0; r < BRCAP; ++r) acc[r] = 0.f;
-    // wave w takes the column blocks w, w + waves, ... in ascending order; the waves' sums are added in a fixed order
-    // at the end.  Within a block the gathered values of X are fetched kFmaBatch at a time, all loads of a batch
-    // issued before the first is used.
+    for (int r = 0; r < BRCAP; ++r) mine[r * 64] = 0.f;
+    // Wave w takes the column blocks w, w + waves, ... in ascending order.  A block's sums are formed per KEPT row
+    // (rank i = 0 .. kept - 1), in groups of four ranks without a test of the row mask inside (a test per row and
+    // column made the loop a chain of 128 branches); rank i is then added to the entry of the row it stands for.
+    // Within a block the gathered values of X are fetched kFmaBatch at a time, all loads of a batch issued before the
+    // first is used.
     for (int64_t c = wave; c < p.nbc; c += kFmaWaves) {
         const int64_t b = t * p.nbc + c;
         const uint64_t mask = p.rowmask[b];
@@ -55,6 +57,28 @@ __global__ void __launch_bounds__(fma_waves(BRCAP) * 64) bcr_spmm_fma(FmaParams 
         const int32_t kc = p.col_ptr[b + 1] - cp0;
         if (mask == 0 || kc == 0) continue;
         const T *wb = W + p.blk_ptr[b];
+        const int32_t nk = __builtin_popcountll(mask);
+        // A block of at most 256 kept weights is fetched once, element e by lane e % 64 (four loads, all in flight with
+        // the block's column indices), and a weight is then read out of its lane's register.
+        const int32_t nel = nk * kc;
+        const bool in_lanes = BRCAP <= 16 && nel <= 4 * 64;
+        float wl[4] = {0.f, 0.f, 0.f, 0.f};
+        if (in_lanes) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int32_t e = q * 64 + lane < nel ? q * 64 + lane : nel - 1;
+                wl[q] = to_f32<DT>(wb[e]);
+            }
+        }
+        auto weight = [&](int32_t e) {                  // e: the same for the whole wave
+            if (!in_lanes) return to_f32<DT>(wb[e]);
+            const int32_t q = e >> 6;
+            const float v = q == 0 ? wl[0] : q == 1 ? wl[1] : q == 2 ? wl[2] : wl[3];
+            return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), e & 63));
+        };
+        float acc[BRCAP];
+#pragma unroll
+        for (int i = 0; i < BRCAP; ++i) acc[i] = 0.f;
         for (int32_t j0 = 0; j0 < kc; j0 += kFmaBatch) {
             float xv[kFmaBatch];
 #pragma unroll
@@ -66,34 +90,37 @@ __global__ void __launch_bounds__(fma_waves(BRCAP) * 64) bcr_spmm_fma(FmaParams 
 #pragma unroll
             for (int u = 0; u < kFmaBatch; ++u) {
                 if (j0 + u < kc) {
-                    int32_t i = 0;
 #pragma unroll
-                    for (int r = 0; r < BRCAP; ++r) {
-                        if ((mask >> r) & 1) {          // same for the whole wave
-                            acc[r] = __builtin_fmaf(to_f32<DT>(wb[(int64_t)i * kc + j0 + u]), xv[u], acc[r]);
-                            ++i;
+                    for (int i4 = 0; i4 < BRCAP; i4 += 4) {
+                        if (i4 < nk) {                  // (ranks past the last kept row re-use its weights; never stored)
+#pragma unroll
+                            for (int i = i4; i < i4 + 4; ++i) {
+                                const int32_t ic = i < nk ? i : nk - 1;
+                                acc[i] = __builtin_fmaf(weight(ic * kc + j0 + u), xv[u], acc[i]);
+                            }
                         }
                     }
                 }
             }
         }
-    }
-    if (wave > 0) {
+        uint64_t m = mask;
 #pragma unroll
-        for (int r = 0; r < BRCAP; ++r) part[((wave - 1) * BRCAP + r) * 64 + lane] = acc[r];
-    }
-    __syncthreads();
-    if (wave == 0 && live) {
-        const int64_t row0 = (int64_t)p.strip_order[t] * p.BR;
-#pragma unroll
-        for (int r = 0; r < BRCAP; ++r) {
-            if (r < p.BR) {
-                float s = acc[r];
-#pragma unroll
-                for (int w = 1; w < kFmaWaves; ++w) s += part[((w - 1) * BRCAP + r) * 64 + lane];
-                p.Y[(row0 + r) * p.ldy + n] = s;
+        for (int i = 0; i < BRCAP; ++i) {
+            if (i < nk) {                               // same for the whole wave
+                const int r = __builtin_ctzll(m);
+                m &= m - 1;
+                mine[r * 64] += acc[i];
             }
         }
+    }
+    __syncthreads();
+    // the strip's rows are dealt to the waves; a row's sums are added in wave order
+    const int64_t row0 = (int64_t)p.strip_order[t] * p.BR;
+    for (int r = wave; r < p.BR; r += kFmaWaves) {
+        float s = part[r * 64 + lane];
+#pragma unroll
+        for (int w = 1; w < kFmaWaves; ++w) s += part[(w * BRCAP + r) * 64 + lane];
+        if (live) p.Y[(row0 + r) * p.ldy + n] = s;
     }
 }
 
