@@ -70,39 +70,49 @@ __global__ void __launch_bounds__(fma_waves(BRCAP) * 64) bcr_spmm_fma(FmaParams 
                 wl[q] = to_f32<DT>(wb[e]);
             }
         }
-        auto weight = [&](int32_t e) {                  // e: the same for the whole wave
-            if (!in_lanes) return to_f32<DT>(wb[e]);
-            const int32_t q = e >> 6;
-            const float v = q == 0 ? wl[0] : q == 1 ? wl[1] : q == 2 ? wl[2] : wl[3];
-            return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), e & 63));
+        // MODE 0: weights from memory, 1: out of the lanes of wl[0] (at most 64 of them), 2: out of wl[0..3]
+        auto weight = [&](auto mode, int32_t e) {       // e: the same for the whole wave
+            constexpr int MODE = decltype(mode)::value;
+            if constexpr (MODE == 0) {
+                return to_f32<DT>(wb[e]);
+            } else {
+                const int32_t q = e >> 6;
+                const float v = MODE == 1 ? wl[0] : q == 0 ? wl[0] : q == 1 ? wl[1] : q == 2 ? wl[2] : wl[3];
+                return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), e & 63));
+            }
         };
         float acc[BRCAP];
 #pragma unroll
         for (int i = 0; i < BRCAP; ++i) acc[i] = 0.f;
-        for (int32_t j0 = 0; j0 < kc; j0 += kFmaBatch) {
-            float xv[kFmaBatch];
+        auto columns = [&](auto mode) {
+            for (int32_t j0 = 0; j0 < kc; j0 += kFmaBatch) {
+                float xv[kFmaBatch];
 #pragma unroll
-            for (int u = 0; u < kFmaBatch; ++u) {
-                const int32_t j = j0 + u < kc ? j0 + u : kc - 1;
-                const int64_t k = c * p.BC + p.col_idx[cp0 + j];
-                xv[u] = to_f32<DT>(X[k * p.ldx + nc]);
-            }
+                for (int u = 0; u < kFmaBatch; ++u) {
+                    const int32_t j = j0 + u < kc ? j0 + u : kc - 1;
+                    const int64_t k = c * p.BC + p.col_idx[cp0 + j];
+                    xv[u] = to_f32<DT>(X[k * p.ldx + nc]);
+                }
 #pragma unroll
-            for (int u = 0; u < kFmaBatch; ++u) {
-                if (j0 + u < kc) {
+                for (int u = 0; u < kFmaBatch; ++u) {
+                    if (j0 + u < kc) {
 #pragma unroll
-                    for (int i4 = 0; i4 < BRCAP; i4 += 4) {
-                        if (i4 < nk) {                  // (ranks past the last kept row re-use its weights; never stored)
+                        for (int i4 = 0; i4 < BRCAP; i4 += 4) {
+                            if (i4 < nk) {              // (ranks past the last kept row re-use its weights; never stored)
 #pragma unroll
-                            for (int i = i4; i < i4 + 4; ++i) {
-                                const int32_t ic = i < nk ? i : nk - 1;
-                                acc[i] = __builtin_fmaf(weight(ic * kc + j0 + u), xv[u], acc[i]);
+                                for (int i = i4; i < i4 + 4; ++i) {
+                                    const int32_t ic = i < nk ? i : nk - 1;
+                                    acc[i] = __builtin_fmaf(weight(mode, ic * kc + j0 + u), xv[u], acc[i]);
+                                }
                             }
                         }
                     }
                 }
             }
-        }
+        };
+        if (!in_lanes) columns(std::integral_constant<int, 0>{});
+        else if (nel <= 64) columns(std::integral_constant<int, 1>{});
+        else columns(std::integral_constant<int, 2>{});
         uint64_t m = mask;
 #pragma unroll
         for (int i = 0; i < BRCAP; ++i) {
