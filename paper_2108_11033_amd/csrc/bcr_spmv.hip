@@ -258,12 +258,15 @@ __global__ void __launch_bounds__(exact_waves(CELL) * 64) bcr_spmv_wave_exact(Ge
     // the product alone: a wave walks sps consecutive stored strips; with a cell: the strip of gate `gate` that holds
     // hidden units blockIdx.x * BR .., wherever the reorder has stored it
     const int gate = CELL == 2 ? wave % 3 : wave;
-    int64_t t0 = ((int64_t)blockIdx.x * 4 + wave) * p.sps;
+    // (a small launch leaves strips to one or two waves of a workgroup and takes more workgroups: a wave's 12 KB of
+    // weights then arrive through a compute unit of their own; the other waves only help to copy x)
+    const int wpg = CELL != 0 ? NWV : p.wpg;
+    int64_t t0 = ((int64_t)blockIdx.x * wpg + wave) * p.sps;
     if constexpr (CELL != 0) {
         const int32_t *pos = (CELL == 2 && mi) ? p.cell.strip_pos2 : p.cell.strip_pos;
         t0 = pos[gate * (p.cell.H / p.BR) + blockIdx.x];
     }
-    const int nstrips = CELL != 0 ? 1 : p.nbr_total - t0 < p.sps ? (int)(p.nbr_total - t0) : p.sps;   // <= 0: nothing to do
+    const int nstrips = CELL != 0 ? 1 : wave >= wpg ? 0 : p.nbr_total - t0 < p.sps ? (int)(p.nbr_total - t0) : p.sps;   // <= 0: nothing to do
     const int nitems = nstrips > 0 ? nstrips * nsegs : 0;
 
     struct Item {
@@ -978,6 +981,8 @@ static grim_status launch_batch(const GemvParams &p, int batch, int vec, dim3 gr
 // Strips a wave of the wave-per-strip kernels walks: 1 when the launch is small, up to max_sps
 // while at least 512 workgroups (two per compute unit) remain -- a large launch then is one round of
 // long-lived workgroups.
+static int spmv_compute_units();
+
 static int wave_strips_per_wave(int64_t count, int64_t nbr, int max_sps) {
     int sps = 1;
     while (sps < max_sps && count * ((nbr + 4 * sps * 2 - 1) / (4 * sps * 2)) >= 512) sps *= 2;
@@ -1002,6 +1007,7 @@ grim_status launch_spmv(const GemvDesc *table, const GemvDesc &single, const Gem
     p.BR = BR; p.BC = BC; p.nbc = (int32_t)(K / BC); p.K = (int32_t)K;
     p.nbr_total = (int32_t)nbr;
     p.sps = 1;
+    p.wpg = 4;
     p.batch = batch;
     p.ukr = ukr; p.ukc = ukc;
     p.krmax = krmax;
@@ -1036,7 +1042,10 @@ grim_status launch_spmv(const GemvDesc *table, const GemvDesc &single, const Gem
             const size_t wlds = ((((size_t)K + (size_t)(K / BC) * exact_x_skew(BC, esz)) * esz + 15) & ~size_t(15)) + 4 * (size_t)wb;
             q.sps = batch == 1 ? wave_strips_per_wave(count, nbr, 16) : 1;
             if (batch > 1) q.xvec16 = 0;                        // a column of x is strided
-            dim3 wgrid((unsigned)((nbr + 4 * q.sps - 1) / (4 * q.sps)), (unsigned)count, (unsigned)batch);
+            // while a workgroup per strip (or per two) still leaves every workgroup a compute unit of its own, take it
+            const int64_t cus = spmv_compute_units(), strips = (int64_t)count * nbr * batch;
+            q.wpg = q.sps == 1 && strips <= cus ? 1 : q.sps == 1 && strips <= 2 * cus ? 2 : 4;
+            dim3 wgrid((unsigned)((nbr + q.wpg * q.sps - 1) / (q.wpg * q.sps)), (unsigned)count, (unsigned)batch);
             grim_status st = GRIM_ERR_UNSUPPORTED;
             if (wlds <= 160 * 1024) {
                 switch (dtype) {
@@ -1159,6 +1168,7 @@ grim_status launch_spmv_cell(int kind, const GemvDesc &d1, const GemvDesc *d2, i
     p.BR = BR; p.BC = BC; p.nbc = (int32_t)(K / BC); p.K = (int32_t)K;
     p.nbr_total = (int32_t)(M / BR);
     p.sps = 1;
+    p.wpg = 4;
     p.batch = 1;
     p.ukr = ukr; p.ukc = ukc; p.krmax = ukr; p.kcmax = ukc; p.lpb_shift = 2;
     p.seg_blocks = 64;

@@ -24,6 +24,7 @@ struct GemvParams {
     int64_t x_stride, y_stride, ldx, ldy;
     int32_t xvec16;          // x is contiguous and 16-byte aligned: copy with 16-byte loads
     int32_t sps;             // wave kernel: consecutive strips per wave
+    int32_t wpg;             // one-column wave kernel without a cell: waves of a workgroup that take strips (1, 2 or 4)
     int32_t batch;           // right-hand sides (kernels that take it at run time)
     RnnCell cell;            // recurrent cell in the epilogue (wave-per-strip kernel, one right-hand side)
 };
