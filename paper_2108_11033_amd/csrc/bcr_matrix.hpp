@@ -122,6 +122,7 @@ struct grim_bcr_matrix {
     int64_t nbr = 0, nbc = 0, nb = 0, nnz = 0;
     // canonical host arrays (stored order)
     std::vector<int32_t> strip_order;
+    bool order_identity = false;     // stored strip p is original strip p (equal work everywhere: the stable sort moved nothing)
     std::vector<int32_t> row_ptr, col_ptr;
     std::vector<uint16_t> row_idx, col_idx;
     std::vector<int64_t> blk_ptr;
@@ -166,7 +167,7 @@ struct GemvDesc {
 // strips of [W_ih | W_hh] (input, forget, candidate, output gate); GRU: three strips (reset, update, candidate) of
 // each of W_i and W_h -- found through `strip_pos`, the stored position of every original strip.
 struct RnnCell {
-    const int32_t *strip_pos;    // first matrix: stored position of original strip s
+    const int32_t *strip_pos;    // first matrix: stored position of original strip s; nullptr: strip s is stored at s
     const int32_t *strip_pos2;   // second matrix (GRU)
     const float *bias, *bias2;   // LSTM: 4H (bias); GRU: 3H input side (bias), 3H hidden side (bias2); null = none
     float *c;                    // LSTM: cell state, H fp32, stride ldc, updated in place; GRU: hidden state h32

@@ -277,6 +277,8 @@ grim_status upload(grim_bcr_matrix *A) {
     auto bytes = [](const auto &v) { return v.size() * sizeof(v[0]); };
     std::vector<int32_t> strip_pos((size_t)A->nbr);
     for (int64_t q = 0; q < A->nbr; ++q) strip_pos[(size_t)A->strip_order[q]] = (int32_t)q;
+    A->order_identity = true;
+    for (int64_t q = 0; q < A->nbr; ++q) A->order_identity = A->order_identity && A->strip_order[q] == q;
     size_t o_so = s.add(bytes(A->strip_order));
     size_t o_sp = s.add(bytes(strip_pos));
     size_t o_rp = s.add(bytes(A->row_ptr));
@@ -1000,7 +1002,9 @@ grim_status grim_bcr_lstm_step(const grim_bcr_matrix *A, const void *xh_dev, int
         const int esz = dtype_size(A->dtype);
         const bool aliased = h_dev && ranges_overlap(xh_dev, ((A->K - 1) * ldx + batch) * esz, h_dev, ((H - 1) * ldh + batch) * esz);
         if (!aliased) {
-            RnnCell cell{A->dev.strip_pos, nullptr, bias_dev, nullptr, c_dev, h_dev, h32_dev, ldc, ldh, ldh32, (int32_t)H, A->dtype};
+            // (a matrix stored in its original strip order spares the step kernel the look-up its weight fetch waits for)
+            RnnCell cell{A->order_identity ? nullptr : A->dev.strip_pos, nullptr, bias_dev, nullptr, c_dev, h_dev, h32_dev, ldc, ldh, ldh32,
+                         (int32_t)H, A->dtype};
             st0 = launch_spmv_cell(1, desc_of(A), nullptr, A->M, A->K, A->BR, A->BC, A->dtype, A->gemv.uniform_kr,
                                    A->gemv.uniform_kc, xh_dev, 0, batch, ldx, gates_dev, 0, ldg, cell, static_cast<hipStream_t>(hip_stream));
             if (st0 != GRIM_ERR_UNSUPPORTED) return st0;
@@ -1192,7 +1196,7 @@ grim_status grim_bcr_gru_step(const grim_bcr_matrix *Ai, const grim_bcr_matrix *
                                           ranges_overlap(x_dev, ((Ai->K - 1) * ldx + batch) * esz, hout_dev, ((H - 1) * ldhout + batch) * esz));
         if (!aliased) {
             const GemvDesc di = desc_of(Ai), dh = desc_of(Ah);
-            RnnCell cell{Ai->dev.strip_pos, Ah->dev.strip_pos, bias_i_dev, bias_h_dev, h32_dev, hout_dev, nullptr, ldh32, ldhout, 0,
+            RnnCell cell{Ai->order_identity ? nullptr : Ai->dev.strip_pos, Ah->order_identity ? nullptr : Ah->dev.strip_pos, bias_i_dev, bias_h_dev, h32_dev, hout_dev, nullptr, ldh32, ldhout, 0,
                          (int32_t)H, Ai->dtype};
             st = launch_spmv_cell(2, di, &dh, Ai->M, Ai->K, Ai->BR, Ai->BC, Ai->dtype, Ai->gemv.uniform_kr, Ai->gemv.uniform_kc,
                                   x_dev, xd / esz, batch, ldx, gi_dev, yd / 4, ldgi, cell, static_cast<hipStream_t>(hip_stream));

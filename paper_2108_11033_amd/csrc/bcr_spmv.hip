@@ -264,7 +264,8 @@ __global__ void __launch_bounds__(exact_waves(CELL) * 64) bcr_spmv_wave_exact(Ge
     int64_t t0 = ((int64_t)blockIdx.x * wpg + wave) * p.sps;
     if constexpr (CELL != 0) {
         const int32_t *pos = (CELL == 2 && mi) ? p.cell.strip_pos2 : p.cell.strip_pos;
-        t0 = pos[gate * (p.cell.H / p.BR) + blockIdx.x];
+        const int s = gate * (p.cell.H / p.BR) + (int)blockIdx.x;
+        t0 = pos ? pos[s] : s;                                    // (no table: stored in the original order)
     }
     const int nstrips = CELL != 0 ? 1 : wave >= wpg ? 0 : p.nbr_total - t0 < p.sps ? (int)(p.nbr_total - t0) : p.sps;   // <= 0: nothing to do
     const int nitems = nstrips > 0 ? nstrips * nsegs : 0;
@@ -282,6 +283,9 @@ __global__ void __launch_bounds__(exact_waves(CELL) * 64) bcr_spmv_wave_exact(Ge
         const int nb = p.nbc - I.c0 < p.seg_blocks ? p.nbc - I.c0 : p.seg_blocks;
         const int64_t blk0 = t * p.nbc + I.c0;
         I.nvec = nb * NV;
+        // the masks first and without a branch: loads return in order, and x can be gathered as soon as the column
+        // mask is here, while the weights are still on their way
+        const gu32x2 mm = *reinterpret_cast<const GRIM_GLOBAL gu32x2 *>(d.masks + 2 * (blk0 + (lane < nb ? lane : nb - 1)));
         const GRIM_GLOBAL char *src = W + (size_t)blk0 * (NV * 16);
         if (nb == 64) {
 #pragma unroll
@@ -295,13 +299,8 @@ __global__ void __launch_bounds__(exact_waves(CELL) * 64) bcr_spmv_wave_exact(Ge
                 wreg[i] = *reinterpret_cast<const GRIM_GLOBAL gu32x4 *>(src + (unsigned int)(v * 16));
             }
         }
-        I.rm = 0;
-        I.cm = KC == 32 ? 0xffffffffu : (1u << (KC & 31)) - 1u;   // idle lanes: any KC columns, no rows
-        if (lane < nb) {
-            const gu32x2 mm = *reinterpret_cast<const GRIM_GLOBAL gu32x2 *>(d.masks + 2 * (blk0 + lane));
-            I.rm = mm.x;
-            I.cm = mm.y;
-        }
+        I.rm = lane < nb ? mm.x : 0u;
+        I.cm = lane < nb ? mm.y : KC == 32 ? 0xffffffffu : (1u << (KC & 31)) - 1u;   // idle lanes: any KC columns, no rows
         I.srow = sg == nsegs - 1 ? d.strip_order[t] : 0;
     };
 
@@ -410,6 +409,20 @@ __global__ void __launch_bounds__(exact_waves(CELL) * 64) bcr_spmv_wave_exact(Ge
     if (!nitems) return;
     for (int it = 0; it < nitems; ++it) {
         const unsigned int rm = cur.rm, cm = cur.cm;
+        // this block's KC activations: they need the column mask only, which arrives ahead of the weights
+        T xe[KC];
+        {
+            int xblk = cur.c0 + lane;
+            xblk = xblk < p.nbc ? xblk : p.nbc - 1;
+            const T *xb = xs + xblk * (p.BC + xsk);
+            unsigned int m = cm;
+#pragma unroll
+            for (int j = 0; j < KC; ++j) {
+                const int col = __builtin_ctz(m);                 // KC bits are set
+                m &= m - 1;
+                xe[j] = xb[col];
+            }
+        }
         if (cur.nvec == 64 * NV) {
 #pragma unroll
             for (int i = 0; i < NV; ++i) {
@@ -434,20 +447,6 @@ __global__ void __launch_bounds__(exact_waves(CELL) * 64) bcr_spmv_wave_exact(Ge
         nxt = cur;
         if (it + 1 < nitems) fetch(it + 1, nxt);
 
-        // this block's KC activations
-        T xe[KC];
-        {
-            int xblk = cur.c0 + lane;
-            xblk = xblk < p.nbc ? xblk : p.nbc - 1;
-            const T *xb = xs + xblk * (p.BC + xsk);
-            unsigned int m = cm;
-#pragma unroll
-            for (int j = 0; j < KC; ++j) {
-                const int col = __builtin_ctz(m);                 // KC bits are set
-                m &= m - 1;
-                xe[j] = xb[col];
-            }
-        }
         gu32x4 w[NV];
         {
             const gu32x4 *wb = reinterpret_cast<const gu32x4 *>(wl) + lane * NV + (PB ? lane / PB : 0);
