@@ -69,6 +69,8 @@ template <> __device__ __forceinline__ unsigned short seq_round<GRIM_F16>(float 
 template <> __device__ __forceinline__ unsigned short seq_round<GRIM_BF16>(float v) { return rnn_f32_to_bf16(v); }
 
 constexpr int kSeqXVec = 4;   // 16-byte pieces of a step's inputs a thread fetches ahead
+constexpr int kSeqPolls = 3;    // reads of an exchange word a waiting workgroup sends out at once ...
+constexpr int kSeqPollGap = 5;  // ... this many times 64 cycles apart
 
 // MULTI: a workgroup carries more than one sequence
 template <int DT, int KR, int KC, int CELL, bool MULTI>
@@ -199,35 +201,76 @@ __global__ void __launch_bounds__(exact_waves(CELL) * 64) bcr_rnn_seq(SeqParams 
             for (int bb = 0; bb < B; ++bb)
                 for (int e = tid; e < H; e += NTHR) hin[bb * hld + e] = h0[(int64_t)bb * H + e];
         } else {
-            // words of two pairs of sequences per round: up to 8 reads in flight
+            // Words of two pairs of sequences per round.  A read of an exchange word takes a round trip through the
+            // fabric (1.2 us), and the words of step t become visible a little after this workgroup has published
+            // its own: read once at a time, the first read comes back too early and the second costs a whole further
+            // round trip.  So the first NP reads of every word go out together, a fraction of a round trip apart
+            // (loads return in order; every read is issued whether its element exists or not, so that the wait for
+            // the oldest leaves the younger ones in flight).
             const unsigned long long *ex = exch + (size_t)(t & 1) * NQ * H;
+            constexpr int NJ = MULTI ? 2 : 1;
+            constexpr int NP = MULTI ? 2 : kSeqPolls;               // (several sequences: twice the words per read, fewer registers left)
             bool bad = false;
-            for (int q0 = 0; q0 < NQ && !bad; q0 += 2) {
+            for (int q0 = 0; q0 < NQ && !bad; q0 += NJ) {
                 for (int base = tid; base < H && !bad; base += 4 * NTHR) {
-                    unsigned long long v[8] = {0ull, 0ull, 0ull, 0ull, 0ull, 0ull, 0ull, 0ull};
-                    unsigned int polls = 0;
-                    bool ok;
-                    for (;;) {
-                        ok = true;
+                    unsigned long long v[NJ * 4], w[NP][NJ * 4];
+                    auto ask = [&](unsigned long long (&r)[NJ * 4]) {
 #pragma unroll
-                        for (int j = 0; j < 2; ++j) {
-                            if (q0 + j < NQ) {
+                        for (int j = 0; j < NJ; ++j) {
+                            const int q = q0 + j < NQ ? q0 + j : NQ - 1;
 #pragma unroll
-                                for (int i = 0; i < 4; ++i) {
-                                    const int e = base + i * NTHR;
-                                    if (e < H) {
-                                        v[j * 4 + i] = __hip_atomic_load(ex + (size_t)(q0 + j) * H + e, __ATOMIC_RELAXED,
-                                                                         __HIP_MEMORY_SCOPE_AGENT);
-                                        const unsigned int tag = (unsigned int)(v[j * 4 + i] >> 32);
-                                        if (tag != (unsigned int)t) ok = false;
-                                        if (tag == kSeqPoison) polls = p.max_polls;
-                                    }
-                                }
+                            for (int i = 0; i < 4; ++i) {
+                                const int e = base + i * NTHR < H ? base + i * NTHR : H - 1;
+                                r[j * 4 + i] = __hip_atomic_load(ex + (size_t)q * H + e, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                             }
                         }
-                        if (ok || polls >= p.max_polls) break;
-                        ++polls;
+                    };
+                    // 1: all tags are t, 0: not yet, -1: a workgroup has given up
+                    auto seen = [&](const unsigned long long (&r)[NJ * 4]) {
+                        int ok = 1;
+#pragma unroll
+                        for (int k = 0; k < NJ * 4; ++k) {
+                            const unsigned int tag = (unsigned int)(r[k] >> 32);
+                            if (tag != (unsigned int)t) ok = ok < 0 ? ok : 0;
+                            if (tag == kSeqPoison) ok = -1;
+                        }
+                        return ok;
+                    };
+                    // NP reads of every word go out at once, a fraction of a round trip apart, and are examined in turn
+                    // (straight-line code, so that the wait for an older read leaves the younger ones in flight); a
+                    // wave moves on as a whole, each lane with the first complete set of words it has seen (a slot is
+                    // written again two steps later at the earliest, so a later read cannot show anything else).
+#pragma unroll
+                    for (int d = 0; d < NP; ++d) {
+                        ask(w[d]);
+                        if (d + 1 < NP) __builtin_amdgcn_s_sleep(kSeqPollGap);
+                    }
+                    unsigned int polls = 0;
+                    bool ok = false, dead = false, waiting = true;
+#pragma unroll
+                    for (int d = 0; d < NP; ++d) {
+                        if (waiting) {                              // (the same for the whole wave)
+                            const int st_ = seen(w[d]);
+                            if (st_ > 0 && !ok) {
+#pragma unroll
+                                for (int k = 0; k < NJ * 4; ++k) v[k] = w[d][k];
+                                ok = true;
+                            }
+                            dead = dead || st_ < 0 || (!ok && ++polls >= p.max_polls);
+                            waiting = __builtin_amdgcn_ballot_w64(!ok && !dead) != 0;
+                        }
+                    }
+                    // not there yet: one read at a time from here on
+                    while (!ok && !dead) {
                         __builtin_amdgcn_s_sleep(1);
+                        ask(w[0]);
+                        const int st_ = seen(w[0]);
+                        if (st_ > 0) {
+#pragma unroll
+                            for (int k = 0; k < NJ * 4; ++k) v[k] = w[0][k];
+                            ok = true;
+                        }
+                        dead = st_ < 0 || (!ok && ++polls >= p.max_polls);
                     }
                     if (!ok) {
                         *flag = 1;
@@ -235,7 +278,7 @@ __global__ void __launch_bounds__(exact_waves(CELL) * 64) bcr_rnn_seq(SeqParams 
                         break;
                     }
 #pragma unroll
-                    for (int j = 0; j < 2; ++j) {
+                    for (int j = 0; j < NJ; ++j) {
                         if (q0 + j < NQ) {
 #pragma unroll
                             for (int i = 0; i < 4; ++i) {
