@@ -69,8 +69,8 @@ template <> __device__ __forceinline__ unsigned short seq_round<GRIM_F16>(float 
 template <> __device__ __forceinline__ unsigned short seq_round<GRIM_BF16>(float v) { return rnn_f32_to_bf16(v); }
 
 constexpr int kSeqXVec = 4;   // 16-byte pieces of a step's inputs a thread fetches ahead
-constexpr int kSeqPolls = 3;    // reads of an exchange word a waiting workgroup sends out at once ...
-constexpr int kSeqPollGap = 5;  // ... this many times 64 cycles apart
+constexpr int kSeqPolls = 2;    // reads of an exchange word a waiting workgroup sends out at once ...
+constexpr int kSeqPollGap = 8;  // ... this many times 64 cycles apart (2 x 8, 3 x 5 .. 12, 4 x 4 measured: LSTM alike, the GRU best with two)
 
 // MULTI: a workgroup carries more than one sequence
 template <int DT, int KR, int KC, int CELL, bool MULTI>
